@@ -1,0 +1,423 @@
+"""Sequential CPU model of a symmetric heap and the OpenSHMEM operations built on it.
+
+TEST INFRASTRUCTURE ONLY.  This module is the correctness oracle for the GPU
+library.  It is imported by the tests, by the smoke check and by the benchmark's
+CPU-baseline leg, and by nothing else; it shares no code with the GPU path and
+never calls it.  It is deliberately plain and slow.
+
+What is modelled, and the passage each part follows
+---------------------------------------------------
+* PGAS state (paper section "OpenSHMEM Memory and Execution Model"): ``npes``
+  processing elements numbered ``0 .. npes-1``; every PE owns one symmetric heap
+  of the same size with the same layout, so one byte offset names "the same
+  object" on every PE while the stored values may differ from PE to PE.
+* Address rule (paper section "Remote Memory Access", the scalar-put example):
+  the remote location of a symmetric object is the local address minus the
+  local heap base plus the remote heap base.  With one flat array per PE that
+  is simply "same offset, other array"; ``translate`` writes the rule out with
+  explicit base addresses so that the tests can pin it.
+* Work-group put/get (paper section "Proposed Device APIs"): the threads of a
+  group share one copy, each taking a piece of it.  The result is the byte
+  copy itself; which thread moved which byte is not observable.  ``wg_put``
+  and ``wg_get`` walk the message slice by slice only so that the slicing rule
+  used for several work-groups per message can be checked to cover the message
+  exactly once.
+* Signalling, ordering, atomics: the paper only says these follow OpenSHMEM 1.5,
+  so the 1.5 rules are used: ``put_signal`` updates a 64-bit unsigned signal
+  word on the target *after* the payload; ``signal_wait_until`` compares
+  unsigned; ``quiet``/``fence`` change no state in a model where every operation
+  completes at once; atomics are indivisible 64-bit read-modify-writes.
+* Push collect (paper section "Collective Operations", sync-and-broadcast
+  paragraph) and the duplicated reduction (same section, reduction paragraph):
+  ``fcollect`` concatenates every PE's block in PE order into every PE's
+  destination; ``reduce_sum_f32`` folds the PEs' vectors element-wise in PE
+  order 0, 1, ..., npes-1 in binary32 and every PE receives the same result.
+* The pipelined ring (a benchmark configuration, not a paper algorithm): chunks
+  travel with put-with-signal (ADD 1) to the next PE, the receiver waits for
+  chunk k by ``signal >= k+1`` and adds the bf16 payload, widened exactly to
+  binary32, into a binary32 accumulator in chunk order.
+
+Semantics of time: operations are applied one after another in the order the
+caller issues them and each takes full effect before the next starts.  A
+``signal_wait_until`` whose condition is false at that point cannot be satisfied
+by a sequential schedule, so it raises instead of blocking.
+
+Readings taken where the paper is silent are listed in the repository's design
+notes; the ones that matter here: overlapping source and destination on one PE
+is an error; signal and atomic targets must be 8-byte aligned; ``put_signal``
+with zero bytes still updates the signal; a PE may target itself.
+
+Parity status: every function here is pinned by the CPU tests (brute force on
+tiny heaps against an independent byte-at-a-time model, closed forms, library
+routines and hand-worked fixtures) except the allocator's *placement*, which is
+free by design (only invariants are checked) -- "parity unpinned" for offsets.
+"""
+from __future__ import annotations
+
+import numpy as np
+
+U64_MASK = (1 << 64) - 1
+
+SIGNAL_SET = 0
+SIGNAL_ADD = 1
+
+CMP_EQ, CMP_NE, CMP_GT, CMP_GE, CMP_LT, CMP_LE = range(6)
+
+_CMP = {
+    CMP_EQ: lambda a, b: a == b,
+    CMP_NE: lambda a, b: a != b,
+    CMP_GT: lambda a, b: a > b,
+    CMP_GE: lambda a, b: a >= b,
+    CMP_LT: lambda a, b: a < b,
+    CMP_LE: lambda a, b: a <= b,
+}
+
+
+class OracleError(Exception):
+    """An operation the OpenSHMEM rules do not define, or an illegal schedule."""
+
+
+def _to_i64(x: int) -> int:
+    """Two's-complement wrap of a Python int into the int64 range."""
+    x &= U64_MASK
+    return x - (1 << 64) if x >> 63 else x
+
+
+class ShmemOracle:
+    """``npes`` byte-array heaps plus the OpenSHMEM operations acting on them."""
+
+    DEFAULT_ALIGN = 256
+
+    def __init__(self, npes: int, heap_bytes: int):
+        if npes < 1 or heap_bytes < 1:
+            raise OracleError("need npes >= 1 and heap_bytes >= 1")
+        self.npes = int(npes)
+        self.heap_bytes = int(heap_bytes)
+        self.heap = [np.zeros(self.heap_bytes, dtype=np.uint8) for _ in range(self.npes)]
+        # allocator state: sorted list of (offset, size) of live blocks
+        self._live: list[tuple[int, int]] = []
+        self.log: list[tuple] = []  # ordering operations, in issue order
+
+    # ------------------------------------------------------------------ checks
+    def _pe(self, pe: int) -> int:
+        if not (0 <= pe < self.npes):
+            raise OracleError(f"PE {pe} outside 0..{self.npes - 1}")
+        return pe
+
+    def _range(self, off: int, n: int) -> None:
+        if off < 0 or n < 0 or off + n > self.heap_bytes:
+            raise OracleError(f"[{off}, {off}+{n}) leaves the heap of {self.heap_bytes} bytes")
+
+    def _word(self, off: int) -> None:
+        self._range(off, 8)
+        if off % 8:
+            raise OracleError("64-bit signal/atomic target must be 8-byte aligned")
+
+    # --------------------------------------------------------------- allocator
+    def malloc(self, nbytes: int, align: int = 0) -> int:
+        """Lowest-address first fit.  One offset, valid on every PE."""
+        align = align or self.DEFAULT_ALIGN
+        if align & (align - 1):
+            raise OracleError("alignment must be a power of two")
+        if nbytes == 0:
+            return U64_MASK
+        cur = 0
+        for o, s in self._live:
+            start = -(-cur // align) * align
+            if start + nbytes <= o:
+                break
+            cur = o + s
+        start = -(-cur // align) * align
+        if start + nbytes > self.heap_bytes:
+            raise OracleError("symmetric heap exhausted")
+        self._live.append((start, nbytes))
+        self._live.sort()
+        return start
+
+    def calloc(self, nbytes: int, align: int = 0) -> int:
+        off = self.malloc(nbytes, align)
+        if nbytes:
+            for p in range(self.npes):
+                self.heap[p][off:off + nbytes] = 0
+        return off
+
+    def free(self, off: int) -> None:
+        if off == U64_MASK:
+            return
+        for i, (o, _) in enumerate(self._live):
+            if o == off:
+                del self._live[i]
+                return
+        raise OracleError(f"free of offset {off} that is not a live block")
+
+    # ---------------------------------------------------------------- staging
+    def write(self, pe: int, off: int, data) -> None:
+        buf = np.frombuffer(np.ascontiguousarray(data).tobytes(), dtype=np.uint8)
+        self._pe(pe)
+        self._range(off, buf.size)
+        self.heap[pe][off:off + buf.size] = buf
+
+    def read(self, pe: int, off: int, n: int, dtype=np.uint8) -> np.ndarray:
+        self._pe(pe)
+        self._range(off, n)
+        return self.heap[pe][off:off + n].copy().view(dtype)
+
+    # ------------------------------------------------------ address translation
+    @staticmethod
+    def translate(local_addr: int, local_heap_base: int, remote_heap_base: int) -> int:
+        """Remote address of a symmetric object: local - local base + remote base."""
+        return local_addr - local_heap_base + remote_heap_base
+
+    # --------------------------------------------------------------------- RMA
+    def putmem(self, me: int, dst: int, src: int, n: int, pe: int) -> None:
+        """Bytes [src, src+n) of PE ``me`` become bytes [dst, dst+n) of PE ``pe``."""
+        self._pe(me), self._pe(pe)
+        self._range(src, n), self._range(dst, n)
+        if me == pe and n and src < dst + n and dst < src + n:
+            raise OracleError("overlapping source and destination on one PE")
+        self.heap[pe][dst:dst + n] = self.heap[me][src:src + n].copy()
+
+    def getmem(self, me: int, dst: int, src: int, n: int, pe: int) -> None:
+        """Bytes [src, src+n) of PE ``pe`` become bytes [dst, dst+n) of PE ``me``."""
+        self._pe(me), self._pe(pe)
+        self._range(src, n), self._range(dst, n)
+        if me == pe and n and src < dst + n and dst < src + n:
+            raise OracleError("overlapping source and destination on one PE")
+        self.heap[me][dst:dst + n] = self.heap[pe][src:src + n].copy()
+
+    @staticmethod
+    def wg_slices(n: int, n_wg: int) -> list[tuple[int, int]]:
+        """How ``n_wg`` work-groups share one message of ``n`` bytes.
+
+        Every group takes one contiguous slice whose length is n / n_wg rounded
+        up to a whole number of 16-byte units; late groups may get a short or an
+        empty slice.  Returns ``(begin, end)`` per group.
+        """
+        if n_wg < 1:
+            raise OracleError("need at least one work-group")
+        per = -(-n // n_wg)
+        per = -(-per // 16) * 16
+        out = []
+        for g in range(n_wg):
+            lo = min(n, g * per)
+            hi = min(n, lo + per)
+            out.append((lo, hi))
+        return out
+
+    def wg_put(self, me: int, dst: int, src: int, n: int, pe: int, n_wg: int = 1) -> None:
+        """Work-group put: each group copies its slice; together they copy the message."""
+        self._pe(me), self._pe(pe)
+        self._range(src, n), self._range(dst, n)
+        if me == pe and n and src < dst + n and dst < src + n:
+            raise OracleError("overlapping source and destination on one PE")
+        for lo, hi in self.wg_slices(n, n_wg):
+            self.heap[pe][dst + lo:dst + hi] = self.heap[me][src + lo:src + hi].copy()
+
+    def wg_get(self, me: int, dst: int, src: int, n: int, pe: int, n_wg: int = 1) -> None:
+        self._pe(me), self._pe(pe)
+        self._range(src, n), self._range(dst, n)
+        if me == pe and n and src < dst + n and dst < src + n:
+            raise OracleError("overlapping source and destination on one PE")
+        for lo, hi in self.wg_slices(n, n_wg):
+            self.heap[me][dst + lo:dst + hi] = self.heap[pe][src + lo:src + hi].copy()
+
+    # ----------------------------------------------------------------- signals
+    def _load_u64(self, pe: int, off: int) -> int:
+        return int.from_bytes(self.heap[pe][off:off + 8].tobytes(), "little")
+
+    def _store_u64(self, pe: int, off: int, v: int) -> None:
+        self.heap[pe][off:off + 8] = np.frombuffer((v & U64_MASK).to_bytes(8, "little"), dtype=np.uint8)
+
+    def put_signal(self, me: int, dst: int, src: int, n: int, sig: int, value: int, op: int, pe: int,
+                   n_wg: int = 1) -> None:
+        """Payload first, then the signal word on the target PE (SET or ADD mod 2^64)."""
+        self._pe(pe)
+        self._word(sig)
+        if op not in (SIGNAL_SET, SIGNAL_ADD):
+            raise OracleError("signal operation must be SET or ADD")
+        self.wg_put(me, dst, src, n, pe, n_wg)
+        if op == SIGNAL_SET:
+            self._store_u64(pe, sig, value)
+        else:
+            self._store_u64(pe, sig, self._load_u64(pe, sig) + value)
+
+    def signal_fetch(self, me: int, sig: int) -> int:
+        self._pe(me)
+        self._word(sig)
+        return self._load_u64(me, sig)
+
+    def signal_wait_until(self, me: int, sig: int, cmp: int, value: int) -> int:
+        """Unsigned comparison of the local signal word; returns the satisfying value."""
+        self._pe(me)
+        self._word(sig)
+        if cmp not in _CMP:
+            raise OracleError("unknown comparison")
+        cur = self._load_u64(me, sig)
+        if not _CMP[cmp](cur, value & U64_MASK):
+            raise OracleError(
+                f"wait on PE {me} (signal={cur}, cmp={cmp}, value={value}) can never be satisfied "
+                "in this sequential order")
+        return cur
+
+    # ---------------------------------------------------------------- ordering
+    def quiet(self, me: int) -> None:
+        self._pe(me)
+        self.log.append(("quiet", me))
+
+    def fence(self, me: int) -> None:
+        self._pe(me)
+        self.log.append(("fence", me))
+
+    def barrier_all(self) -> None:
+        self.log.append(("barrier_all",))
+
+    # ----------------------------------------------------------------- atomics
+    def _load_i64(self, pe: int, off: int) -> int:
+        return _to_i64(self._load_u64(pe, off))
+
+    def atomic_fetch(self, me: int, off: int, pe: int) -> int:
+        self._pe(me), self._pe(pe), self._word(off)
+        return self._load_i64(pe, off)
+
+    def atomic_set(self, me: int, off: int, value: int, pe: int) -> None:
+        self._pe(me), self._pe(pe), self._word(off)
+        self._store_u64(pe, off, value)
+
+    def atomic_swap(self, me: int, off: int, value: int, pe: int) -> int:
+        self._pe(me), self._pe(pe), self._word(off)
+        old = self._load_i64(pe, off)
+        self._store_u64(pe, off, value)
+        return old
+
+    def atomic_fetch_add(self, me: int, off: int, value: int, pe: int) -> int:
+        self._pe(me), self._pe(pe), self._word(off)
+        old = self._load_i64(pe, off)
+        self._store_u64(pe, off, old + value)
+        return old
+
+    def atomic_add(self, me: int, off: int, value: int, pe: int) -> None:
+        self.atomic_fetch_add(me, off, value, pe)
+
+    def atomic_fetch_inc(self, me: int, off: int, pe: int) -> int:
+        return self.atomic_fetch_add(me, off, 1, pe)
+
+    def atomic_inc(self, me: int, off: int, pe: int) -> None:
+        self.atomic_fetch_add(me, off, 1, pe)
+
+    def atomic_compare_swap(self, me: int, off: int, cond: int, value: int, pe: int) -> int:
+        self._pe(me), self._pe(pe), self._word(off)
+        old = self._load_i64(pe, off)
+        if old == _to_i64(cond):
+            self._store_u64(pe, off, value)
+        return old
+
+    # -------------------------------------------------------------- collectives
+    def fcollect(self, dst: int, src: int, n: int) -> None:
+        """Every PE's block of ``n`` bytes, in PE order, lands in every PE's destination."""
+        self._range(src, n)
+        self._range(dst, n * self.npes)
+        blocks = [self.heap[p][src:src + n].copy() for p in range(self.npes)]
+        for q in range(self.npes):
+            for p in range(self.npes):
+                self.heap[q][dst + p * n:dst + (p + 1) * n] = blocks[p]
+
+    def reduce_sum_f32(self, dst: int, src: int, nelems: int) -> dict:
+        """Element-wise binary32 sum over PEs in the order 0, 1, ..., npes-1.
+
+        Every PE's destination receives the same vector.  Also returns the
+        binary64 sum and the sum of magnitudes, for error-bound checks.
+        """
+        nb = 4 * nelems
+        self._range(src, nb)
+        self._range(dst, nb)
+        if src % 4 or dst % 4:
+            raise OracleError("float32 vectors must be 4-byte aligned")
+        vecs = [self.heap[p][src:src + nb].copy().view(np.float32) for p in range(self.npes)]
+        r = vecs[0].copy()
+        for p in range(1, self.npes):
+            r = (r + vecs[p]).astype(np.float32)
+        r64 = np.zeros(nelems, dtype=np.float64)
+        mag = np.zeros(nelems, dtype=np.float64)
+        for v in vecs:
+            r64 += v.astype(np.float64)
+            mag += np.abs(v.astype(np.float64))
+        out = r.view(np.uint8)
+        for q in range(self.npes):
+            self.heap[q][dst:dst + nb] = out
+        return {"f32": r, "f64": r64, "abs": mag}
+
+    # ----------------------------------------------------- benchmark composites
+    @staticmethod
+    def bf16_bits_to_f32(bits: np.ndarray) -> np.ndarray:
+        """bf16 is the top half of binary32: widening is a 16-bit left shift, exact."""
+        return (bits.astype(np.uint32) << np.uint32(16)).view(np.float32)
+
+    def ring_pipeline(self, src: int, slot: int, sig: int, acc: int, chunk_bytes: int, n_chunks: int,
+                      n_wg_prod: int = 1) -> None:
+        """Pipelined ring: PE p sends chunk k to slot k of PE (p+1) mod npes with
+        put-with-signal (ADD 1); the receiver waits ``signal >= k+1`` and adds the
+        bf16 chunk, widened to binary32, into its binary32 accumulator, k ascending.
+        The accumulator is zeroed first; the signal word must start at zero.
+        """
+        if chunk_bytes % 2:
+            raise OracleError("a chunk holds whole bf16 values")
+        nel = chunk_bytes // 2
+        self._range(src, chunk_bytes * n_chunks)
+        self._range(slot, chunk_bytes * n_chunks)
+        self._range(acc, 4 * nel)
+        # one legal sequential schedule: all sends of chunk k, then all consumes of chunk k
+        accs = [np.zeros(nel, dtype=np.float32) for _ in range(self.npes)]
+        for k in range(n_chunks):
+            for p in range(self.npes):
+                self.put_signal(p, slot + k * chunk_bytes, src + k * chunk_bytes, chunk_bytes,
+                                sig, 1, SIGNAL_ADD, (p + 1) % self.npes, n_wg_prod)
+            for p in range(self.npes):
+                self.signal_wait_until(p, sig, CMP_GE, k + 1)
+                bits = self.heap[p][slot + k * chunk_bytes:slot + (k + 1) * chunk_bytes].copy().view(np.uint16)
+                accs[p] = (accs[p] + self.bf16_bits_to_f32(bits)).astype(np.float32)
+        for p in range(self.npes):
+            self.heap[p][acc:acc + 4 * nel] = accs[p].view(np.uint8)
+
+    def amo_storm_loop(self, ctr: int, n_ctr: int, targets: np.ndarray) -> np.ndarray:
+        """One fetch-add(+1) per entry of ``targets`` in row-major order, one at a time.
+
+        ``targets`` has shape [n_items, ops_per_item]; entry t selects counter
+        ``t % n_ctr`` of PE ``t // n_ctr``.  Work-item g is issued by PE
+        ``g * npes // n_items``.  Returns the fetched values, same shape.  Pure
+        Python loop: for small cases only.
+        """
+        n_items = targets.shape[0]
+        out = np.zeros(targets.shape, dtype=np.int64)
+        for g in range(n_items):
+            me = g * self.npes // n_items
+            for j in range(targets.shape[1]):
+                t = int(targets[g, j])
+                out[g, j] = self.atomic_fetch_add(me, ctr + 8 * (t % n_ctr), 1, t // n_ctr)
+        return out
+
+    def amo_storm(self, ctr: int, n_ctr: int, targets: np.ndarray) -> np.ndarray:
+        """Same result as ``amo_storm_loop`` computed with array operations.
+
+        In row-major issue order the value fetched by an operation is the counter's
+        initial value plus the number of earlier operations on the same counter;
+        the final counter is the initial value plus the total count.
+        """
+        flat = targets.reshape(-1).astype(np.int64)
+        if flat.size and (flat.min() < 0 or flat.max() >= self.npes * n_ctr):
+            raise OracleError("target outside the counter set")
+        self._range(ctr, 8 * n_ctr)
+        if ctr % 8:
+            raise OracleError("counters must be 8-byte aligned")
+        order = np.argsort(flat, kind="stable")
+        sorted_t = flat[order]
+        first = np.searchsorted(sorted_t, sorted_t, side="left")
+        rank_sorted = np.arange(flat.size, dtype=np.int64) - first
+        rank = np.empty(flat.size, dtype=np.int64)
+        rank[order] = rank_sorted
+        counts = np.bincount(flat, minlength=self.npes * n_ctr).astype(np.int64)
+        init = np.concatenate([self.heap[p][ctr:ctr + 8 * n_ctr].copy().view(np.int64) for p in range(self.npes)])
+        fetched = (init[flat] + rank).reshape(targets.shape)
+        final = init + counts
+        for p in range(self.npes):
+            self.heap[p][ctr:ctr + 8 * n_ctr] = final[p * n_ctr:(p + 1) * n_ctr].view(np.uint8)
+        return fetched

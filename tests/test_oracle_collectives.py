@@ -1,0 +1,172 @@
+"""Pins for the oracle's collectives, the ring composite and the input generators (CPU only)."""
+import math
+import os
+
+import numpy as np
+import pytest
+import torch
+
+from oracle.shmem_oracle import CMP_GE, SIGNAL_ADD, OracleError, ShmemOracle
+from paper_2409_20476_amd import synth
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+
+
+def _fill(o, seed):
+    rng = np.random.default_rng(seed)
+    for p in range(o.npes):
+        o.heap[p][:] = rng.integers(0, 256, o.heap_bytes, dtype=np.uint8)
+
+
+@pytest.mark.parametrize("npes,n", [(1, 7), (2, 16), (3, 33), (8, 100)])
+def test_fcollect_is_concatenate_on_every_pe(npes, n):
+    o = ShmemOracle(npes, 2048)
+    _fill(o, n)
+    before = [h.copy() for h in o.heap]
+    want = np.concatenate([before[p][40:40 + n] for p in range(npes)])     # library routine
+    o.fcollect(1024, 40, n)
+    for q in range(npes):
+        assert (o.heap[q][1024:1024 + n * npes] == want).all()
+        rest = np.ones(2048, bool)
+        rest[1024:1024 + n * npes] = False
+        assert (o.heap[q][rest] == before[q][rest]).all()                  # nothing else touched
+
+
+def test_fcollect_equals_gets_by_every_pe():
+    """Built a second way, from the already pinned getmem: PE q fetches block p from PE p."""
+    a, b = ShmemOracle(4, 1024), ShmemOracle(4, 1024)
+    _fill(a, 1), _fill(b, 1)
+    a.fcollect(512, 8, 50)
+    for q in range(4):
+        for p in range(4):
+            b.getmem(q, 512 + 50 * p, 8, 50, p)
+    assert all((x == y).all() for x, y in zip(a.heap, b.heap))
+
+
+def test_reduce_golden_order_example():
+    rows = [[float(x) for x in l.split()] for l in open(os.path.join(GOLDEN, "reduce_order_example.txt"))
+            if not l.startswith("#")]
+    o = ShmemOracle(3, 256)
+    for p in range(3):
+        o.write(p, 0, np.array(rows[p], dtype=np.float32))
+    o.reduce_sum_f32(128, 0, 4)
+    for q in range(3):
+        assert o.read(q, 128, 16, np.float32).tolist() == rows[3]
+
+
+def test_reduce_special_cases_and_bounds():
+    rng = np.random.default_rng(11)
+    # one PE: identity
+    o = ShmemOracle(1, 4096)
+    x = rng.standard_normal(100).astype(np.float32)
+    o.write(0, 0, x)
+    o.reduce_sum_f32(2048, 0, 100)
+    assert (o.read(0, 2048, 400, np.float32) == x).all()
+    # small integers: every partial sum is exact, so the result equals the integer sum
+    o = ShmemOracle(8, 8192)
+    ints = rng.integers(-1000, 1000, size=(8, 500))
+    for p in range(8):
+        o.write(p, 0, ints[p].astype(np.float32))
+    o.reduce_sum_f32(4096, 0, 500)
+    for q in range(8):
+        assert (o.read(q, 4096, 2000, np.float32).astype(np.int64) == ints.sum(0)).all()
+    # N(0,1): within (npes-1) roundings of the exact sum, |err| <= 7 * 2^-24 * sum|x|
+    vals = rng.standard_normal((8, 500)).astype(np.float32)
+    for p in range(8):
+        o.write(p, 0, vals[p])
+    r = o.reduce_sum_f32(4096, 0, 500)
+    got = o.read(3, 4096, 2000, np.float32)
+    for i in range(500):
+        exact = math.fsum(float(v) for v in vals[:, i])
+        mag = math.fsum(abs(float(v)) for v in vals[:, i])
+        assert abs(float(got[i]) - exact) <= 7 * 2.0 ** -24 * mag
+        assert abs(r["f64"][i] - exact) <= 1e-12 * max(mag, 1.0)
+        assert abs(r["abs"][i] - mag) <= 1e-12 * max(mag, 1.0)
+    with pytest.raises(OracleError):
+        o.reduce_sum_f32(4098, 0, 4)
+
+
+def test_bf16_widening_and_rounding_match_torch():
+    rng = np.random.default_rng(2)
+    bits = rng.integers(0, 65536, 5000, dtype=np.uint16)
+    bits = bits[((bits >> 7) & 0xFF) != 0xFF]                 # finite values only
+    want = torch.from_numpy(bits.view(np.int16).copy()).view(torch.bfloat16).to(torch.float32).numpy()
+    got = ShmemOracle.bf16_bits_to_f32(bits)
+    assert (got.view(np.uint32) == want.view(np.uint32)).all()
+    x = (rng.random(20000, dtype=np.float32) * 2 - 1).astype(np.float32)
+    x[:4] = [0.0, 1.0, -1.0, 1.00390625]                      # last one is a tie: rounds to even
+    want_bits = torch.from_numpy(x).to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16)
+    assert (synth.f32_to_bf16_bits(x) == want_bits).all()
+
+
+def test_ring_slots_signal_and_accumulator():
+    npes, n_chunks, nel = 4, 6, 40
+    cb = 2 * nel
+    o = ShmemOracle(npes, 4096)
+    src, slot, sig, acc = 0, 1024, 2048, 2304
+    chunks = [synth.c3_chunks(p, n_chunks, nel) for p in range(npes)]
+    for p in range(npes):
+        o.write(p, src, chunks[p])
+    o.ring_pipeline(src, slot, sig, acc, cb, n_chunks, n_wg_prod=3)
+    for p in range(npes):
+        prev = (p - 1) % npes
+        assert (o.read(p, slot, cb * n_chunks, np.uint16).reshape(n_chunks, nel) == chunks[prev]).all()
+        assert o.signal_fetch(p, sig) == n_chunks
+        got = o.read(p, acc, 4 * nel, np.float32)
+        # second construction: torch widening, explicit left-to-right binary32 adds
+        t = torch.zeros(nel, dtype=torch.float32)
+        for k in range(n_chunks):
+            t = t + torch.from_numpy(chunks[prev][k].view(np.int16).copy()).view(torch.bfloat16).float()
+        assert (got == t.numpy()).all()
+        for i in range(nel):
+            vals = [float(ShmemOracle.bf16_bits_to_f32(chunks[prev][k, i:i + 1])[0]) for k in range(n_chunks)]
+            assert abs(float(got[i]) - math.fsum(vals)) <= (n_chunks - 1) * 2.0 ** -24 * math.fsum(map(abs, vals))
+
+
+def test_ring_equal_chunks_give_exact_multiple_and_order_is_chunk_order():
+    o = ShmemOracle(2, 4096)
+    x = np.array([0.5, -0.75, 1.0, 0.0078125], dtype=np.float32)
+    bits = synth.f32_to_bf16_bits(x)
+    for p in range(2):
+        o.write(p, 0, np.tile(bits, (64, 1)))
+    o.ring_pipeline(0, 1024, 2048, 2056 + 8, 8, 64)
+    assert (o.read(0, 2064, 16, np.float32) == 64 * x).all()
+    # order: 256, then 64 values of 2^-17... use bf16-exact values where order matters in binary32
+    o = ShmemOracle(1, 4096)
+    seq = np.array([[16777216.0], [1.0], [1.0], [-16777216.0]], dtype=np.float32)
+    o.write(0, 0, synth.f32_to_bf16_bits(seq.reshape(-1)).reshape(4, 1))
+    o.ring_pipeline(0, 64, 128, 256, 2, 4)
+    # ((0 + 2^24) + 1) -> 2^24 (tie to even), + 1 -> 2^24, - 2^24 -> 0; any other order gives 1 or 2
+    assert o.read(0, 256, 4, np.float32)[0] == 0.0
+
+
+def test_ring_equals_composition_of_pinned_ops():
+    npes, n_chunks, nel = 3, 5, 24
+    a, b = ShmemOracle(npes, 2048), ShmemOracle(npes, 2048)
+    for p in range(npes):
+        c = synth.c3_chunks(p, n_chunks, nel)
+        a.write(p, 0, c), b.write(p, 0, c)
+    a.ring_pipeline(0, 512, 1024, 1280, 2 * nel, n_chunks)
+    accs = np.zeros((npes, nel), dtype=np.float32)
+    for p in range(npes):               # a different legal order: PE by PE instead of chunk by chunk
+        for k in range(n_chunks):
+            b.put_signal(p, 512 + k * 2 * nel, k * 2 * nel, 2 * nel, 1024, 1, SIGNAL_ADD, (p + 1) % npes)
+    for p in range(npes):
+        for k in range(n_chunks):
+            b.signal_wait_until(p, 1024, CMP_GE, k + 1)
+            accs[p] += ShmemOracle.bf16_bits_to_f32(b.read(p, 512 + k * 2 * nel, 2 * nel, np.uint16))
+        b.write(p, 1280, accs[p])
+    assert all((x == y).all() for x, y in zip(a.heap, b.heap))
+
+
+def test_synth_is_seeded_and_in_range():
+    assert (synth.c1_payload() == synth.c1_payload()).all()
+    v = synth.c1_payload()
+    assert v.dtype == np.int32 and v.min() >= 0 and v.size == 4096
+    assert synth.c2_source(3, 8).size == 8 and (synth.c2_source(3, 64)[:8] == synth.c2_source(3, 8)).all()
+    assert not (synth.c2_source(3, 64) == synth.c2_source(4, 64)).all()
+    t = synth.c4_targets(128, 8, 16, 1024)
+    assert t.dtype == np.uint16 and t.shape == (128, 8) and t.max() < 16384
+    c = ShmemOracle.bf16_bits_to_f32(synth.c3_chunks(0, 2, 1000))
+    assert c.min() >= -1.0 and c.max() <= 1.0
+    assert synth.c5_fcollect_source(1, 10).dtype == np.int32 and synth.c5_reduce_source(1, 10).dtype == np.float32
