@@ -1,0 +1,208 @@
+/*
+ * shm355 -- device-initiated, work-group-collaborative OpenSHMEM data movement on one MI355X.
+ *
+ * C ABI of libshm355.so.  Plain pointers and sizes only; no C++ or framework types.
+ *
+ * Model (paper section "OpenSHMEM Memory and Execution Model"): `npes` processing
+ * elements, numbered 0..npes-1, each owning a symmetric heap with identical layout.
+ * Here the PEs are logical: PE p's heap is the p-th equal partition of one device
+ * allocation, and PE p's work is enqueued on its own HIP stream.  A symmetric
+ * address crosses this ABI as a byte offset into the heap and is valid for every
+ * PE; the device address is  base[pe] + offset  (paper section "Remote Memory
+ * Access": remote = local - local heap base + remote heap base).
+ *
+ * Because PEs are logical, every call that OpenSHMEM would make "as" a PE names
+ * that PE explicitly (`me`).
+ *
+ * Pointers: `void *heap_base`, `dev_*` arguments are DEVICE pointers; `host`
+ * buffers of shm_write/shm_read and all out-parameters (`*out`, `*off`, `*bytes`)
+ * are HOST pointers.  Streams are hipStream_t values passed as void*.
+ *
+ * Errors: every int function returns SHM_OK (0) or a negative code; nothing throws
+ * or aborts.  shm_last_error() gives a thread-local text for the last failure.
+ *
+ * Completion: shm_launch_* and shm_putmem/shm_getmem are asynchronous on the
+ * stream of the calling PE (team launches: on the team stream, PE 0's).  They are
+ * complete, and their effects visible to every PE and to shm_read, after
+ * shm_quiet(me) (that PE's work) or shm_barrier_all (everyone's).  A bounded device
+ * wait that expired is reported by the next shm_quiet/shm_barrier_all as
+ * SHM_ETIMEOUT.
+ */
+#ifndef SHM355_H
+#define SHM355_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define SHM_MAX_PES        32          /* most logical PEs in one context */
+#define SHM_WG_SIZE        256         /* threads per work-group of every launch */
+#define SHM_INTERNAL_BYTES 65536       /* tail of each partition kept for the library (arrival counters) */
+#define SHM_NULL_OFF       UINT64_MAX  /* offset returned by a zero-byte allocation */
+
+enum { SHM_OK = 0, SHM_EINVAL = -1, SHM_EPE = -2, SHM_ERANGE = -3, SHM_ENOMEM = -4,
+       SHM_EHIP = -5, SHM_ETIMEOUT = -6, SHM_ENODEV = -7 };
+
+enum { SHM_PATH_AUTO = 0, SHM_PATH_LDST = 1, SHM_PATH_SDMA = 2 };
+enum { SHM_SIGNAL_SET = 0, SHM_SIGNAL_ADD = 1 };
+enum { SHM_CMP_EQ = 0, SHM_CMP_NE = 1, SHM_CMP_GT = 2, SHM_CMP_GE = 3, SHM_CMP_LT = 4, SHM_CMP_LE = 5 };
+enum { SHM_INIT_DEFAULT = 0, SHM_INIT_NO_DEVICE = 1 };
+enum { SHM_AMO_FETCH = 0, SHM_AMO_SET = 1, SHM_AMO_SWAP = 2, SHM_AMO_COMPARE_SWAP = 3,
+       SHM_AMO_FETCH_ADD = 4, SHM_AMO_ADD = 5, SHM_AMO_FETCH_INC = 6, SHM_AMO_INC = 7 };
+enum { SHM_STORM_FETCH_ADD = 0, SHM_STORM_ADD = 1, SHM_STORM_CSWAP_LOOP = 2, SHM_STORM_PLAIN_STORE = 3 };
+enum { SHM_REDUCE_DUPLICATE = 0, SHM_REDUCE_SPLIT = 1 };
+
+typedef struct shm_ctx shm_ctx;
+
+/* ---- set-up (host only; paper section "Proposed Device APIs": initialisation, finalisation and
+ *      memory management are host-only) ------------------------------------------------------- */
+
+/* Create a context of `npes` PEs (1..SHM_MAX_PES) with `heap_bytes` per PE (multiple of 4096,
+ * larger than SHM_INTERNAL_BYTES).  heap_base: device pointer to npes*heap_bytes bytes, 256-byte
+ * aligned, borrowed (caller frees after shm_finalize); NULL = the library allocates and owns it.
+ * streams: npes hipStream_t values, borrowed; NULL = the library creates non-blocking streams.
+ * The internal tail of every partition is zeroed.  *out receives the context. */
+int shm_init(int npes, size_t heap_bytes, void *heap_base, void *const *streams, shm_ctx **out);
+
+/* As shm_init with flags.  SHM_INIT_NO_DEVICE builds a context that makes no HIP call at all
+ * (heap_base may be any non-NULL value, streams are ignored): allocation, argument checking and
+ * the cutover policy work; everything that would touch the device returns SHM_ENODEV after its
+ * arguments have been validated. */
+int shm_init_ex(int npes, size_t heap_bytes, void *heap_base, void *const *streams, unsigned flags, shm_ctx **out);
+
+/* Waits for all streams, releases what the library owns.  The context is invalid afterwards. */
+int shm_finalize(shm_ctx *ctx);
+
+int         shm_n_pes(const shm_ctx *ctx);           /* npes, or SHM_EINVAL */
+size_t      shm_heap_bytes(const shm_ctx *ctx);      /* bytes a caller can allocate per PE (partition minus internal tail) */
+const char *shm_last_error(void);                    /* text of this thread's last error; never NULL */
+
+/* Symmetric allocation (collective by construction: one offset for all PEs).  align: power of
+ * two, 0 = 256.  bytes == 0 succeeds with *off = SHM_NULL_OFF.  SHM_ENOMEM when no gap fits.
+ * shm_calloc also zeroes the block on every PE (synchronous).  shm_free(SHM_NULL_OFF) is a no-op;
+ * an offset that is not a live block is SHM_EINVAL. */
+int shm_malloc(shm_ctx *ctx, size_t bytes, size_t align, uint64_t *off);
+int shm_calloc(shm_ctx *ctx, size_t bytes, size_t align, uint64_t *off);
+int shm_free(shm_ctx *ctx, uint64_t off);
+
+/* Device address of symmetric offset `off` on PE `pe` (paper section "Remote Memory Access",
+ * address rule); NULL on a bad PE or an offset outside the partition. */
+void *shm_ptr(const shm_ctx *ctx, uint64_t off, int pe);
+
+/* Test staging, not OpenSHMEM: synchronous copies between a host buffer and PE `pe`'s heap. */
+int shm_write(shm_ctx *ctx, int pe, uint64_t off, const void *host, size_t n);
+int shm_read(shm_ctx *ctx, int pe, uint64_t off, void *host, size_t n);
+
+/* ---- host-initiated RMA and ordering (paper section "Architectural Overview": host-initiated
+ *      routines mirror the device ones; section "Xe-Link Capabilities": copy engines for large and
+ *      non-blocking transfers) ----------------------------------------------------------------- */
+
+/* PE `me` copies n bytes from its offset src_off to offset dst_off of PE `pe` (put), or from PE
+ * `pe`'s src_off to its own dst_off (get), with the copy engine path (hipMemcpyAsync on me's
+ * stream).  Overlapping ranges on one PE are SHM_EINVAL. */
+int shm_putmem(shm_ctx *ctx, int me, uint64_t dst_off, uint64_t src_off, size_t n, int pe);
+int shm_getmem(shm_ctx *ctx, int me, uint64_t dst_off, uint64_t src_off, size_t n, int pe);
+
+/* quiet: all of PE me's outstanding operations are complete and visible (host wait on its stream).
+ * fence: orders me's earlier operations before its later ones per target; streams are in-order, so
+ * this only validates.  barrier_all: quiet for every PE.  All three report an expired device wait. */
+int shm_quiet(shm_ctx *ctx, int me);
+int shm_fence(shm_ctx *ctx, int me);
+int shm_barrier_all(shm_ctx *ctx);
+
+/* ---- policy (paper section "Performance Evaluation": the cutover between stores from kernel
+ *      threads and the copy engine depends on message size and on the number of active work-items) */
+
+/* With SHM_PATH_AUTO a transfer of n bytes by n_wg work-groups uses the copy engine iff
+ * n >= cutover(class of n_wg); classes are n_wg <= 1, <= 4, <= 64, > 64.  SIZE_MAX = never. */
+int shm_set_cutover(shm_ctx *ctx, int n_wg, size_t bytes);
+int shm_get_cutover(const shm_ctx *ctx, int n_wg, size_t *bytes);
+/* Which path AUTO would take: writes SHM_PATH_LDST or SHM_PATH_SDMA to *path. */
+int shm_choose_path(const shm_ctx *ctx, size_t n, int n_wg, int *path);
+
+/* Upper bound for every device-side wait, in microseconds (default 2 000 000; must be > 0). */
+int shm_set_wait_timeout_us(shm_ctx *ctx, uint64_t us);
+/* Team launches run on PE 0's stream.  With team sync on (default) they first wait for all PE
+ * streams and all PE streams then wait for them; off = the caller orders streams itself. */
+int shm_set_team_sync(shm_ctx *ctx, int on);
+
+/* ---- kernel-launch entry points that exercise the device API ---------------------------------- */
+
+/* Work-group put/get (paper section "Proposed Device APIs", the work_group extensions; section
+ * "Remote Memory Access": multi-threaded vectorised copy).  n_wg work-groups of SHM_WG_SIZE
+ * threads share the message: group g takes bytes [g*s, min(n,(g+1)*s)) with s = ceil(n/n_wg)
+ * rounded up to 16.  path: LDST = kernel on me's stream, SDMA = hipMemcpyAsync on me's stream,
+ * AUTO = by cutover.  Any byte alignment; n may be 0. */
+int shm_launch_wg_put(shm_ctx *ctx, int me, int pe, uint64_t dst_off, uint64_t src_off, size_t n, int n_wg, int path);
+int shm_launch_wg_get(shm_ctx *ctx, int me, int pe, uint64_t dst_off, uint64_t src_off, size_t n, int n_wg, int path);
+
+/* Team form: every PE p does the same put/get towards PE (p + pe_shift) mod npes, each with n_wg
+ * work-groups, as ONE grid of npes*n_wg groups on the team stream (LDST) or as npes engine copies
+ * on the PEs' own streams (SDMA). */
+int shm_launch_wg_put_all(shm_ctx *ctx, int pe_shift, uint64_t dst_off, uint64_t src_off, size_t n, int n_wg, int path);
+int shm_launch_wg_get_all(shm_ctx *ctx, int pe_shift, uint64_t dst_off, uint64_t src_off, size_t n, int n_wg, int path);
+
+/* Put with signal (OpenSHMEM 1.5 semantics, which the paper's feature list adopts): after all n
+ * bytes are visible on PE `pe`, its 64-bit word at sig_off (8-byte aligned) is set to sig_val
+ * (SET) or increased by it modulo 2^64 (ADD), exactly once however many groups shared the copy.
+ * n == 0 still signals.  Always the kernel path. */
+int shm_launch_wg_put_signal(shm_ctx *ctx, int me, int pe, uint64_t dst_off, uint64_t src_off, size_t n,
+                             uint64_t sig_off, uint64_t sig_val, int sig_op, int n_wg);
+
+/* One work-group of PE `me` waits until  cmp(word at sig_off on me, val)  holds (unsigned), with
+ * acquire semantics, and stores the satisfying value to *dev_out (device pointer, may be NULL).
+ * The wait is bounded by the wait timeout. */
+int shm_launch_signal_wait_until(shm_ctx *ctx, int me, uint64_t sig_off, int cmp, uint64_t val, uint64_t *dev_out);
+
+/* One work-item of PE `me` performs one 64-bit atomic `op` (SHM_AMO_*) on offset `off` (8-byte
+ * aligned) of PE `pe` (paper section "Xe-Link Capabilities": atomics from GPU threads; section
+ * "Proposed Device APIs": AMOs are scalar).  *dev_out (device pointer or NULL) receives the
+ * fetched value for the fetching ops. */
+int shm_launch_amo(shm_ctx *ctx, int me, int pe, uint64_t off, int op, int64_t operand, int64_t cond, int64_t *dev_out);
+
+/* Benchmark configuration 1.  PE 0, one work-group: work-group put of n bytes from data_off to
+ * data_off on PE 1; quiet; zero-byte put-with-signal SET 1 on flag_off.  PE 1, one work-group on
+ * its own stream: wait flag == 1, then work-group get of PE 0's n bytes at data_off into its
+ * back_off.  Needs npes >= 2. */
+int shm_launch_pingflag(shm_ctx *ctx, uint64_t data_off, uint64_t back_off, size_t n, uint64_t flag_off);
+
+/* Benchmark configuration 3, one grid on the team stream.  For every PE p and chunk k <
+ * n_chunks: n_wg_prod producer groups put chunk k (chunk_bytes at src_off + k*chunk_bytes) into
+ * slot k (slot_off + k*chunk_bytes) of PE (p+1) mod npes with a put-with-signal ADD 1 on sig_off;
+ * n_wg_cons consumer groups of every PE wait for signal >= k+1 and add chunk k, read as bf16 and
+ * widened exactly, into a float32 accumulator kept in registers, in chunk order; at the end the
+ * accumulator is stored at acc_off (chunk_bytes/2 floats).  chunk_bytes must be a multiple of 16
+ * and all offsets 16-byte aligned; the signal word must be zero on entry; the grid must fit on the
+ * GPU at once (else SHM_EINVAL). */
+int shm_launch_ring_pipeline(shm_ctx *ctx, uint64_t src_off, uint64_t slot_off, uint64_t sig_off, uint64_t acc_off,
+                             size_t chunk_bytes, int n_chunks, int n_wg_prod, int n_wg_cons);
+
+/* Benchmark configuration 4, one grid on the team stream.  Work-item g < n_items performs
+ * ops_per_item atomics; its j-th target is dev_targets[g*ops_per_item + j] = pe*n_ctr + index,
+ * i.e. the int64 counter at ctr_off + 8*index on that PE.  kind: FETCH_ADD(+1) | ADD(+1, no
+ * return) | CSWAP_LOOP (increment built from compare-swap) | PLAIN_STORE (not atomic; a timing
+ * ceiling only).  dev_fetched (or NULL): [n_items*ops_per_item] fetched values.  dev_checksum (or
+ * NULL): one uint64 per work-group, the sum of what its items fetched. */
+int shm_launch_amo_storm(shm_ctx *ctx, uint64_t ctr_off, int n_ctr, const uint16_t *dev_targets, uint64_t n_items,
+                         int ops_per_item, int kind, int64_t *dev_fetched, uint64_t *dev_checksum);
+
+/* Benchmark configuration 5a: fcollect (paper section "Collective Operations": push, inner loop
+ * over destinations).  Every PE q receives at dst_off + p*bytes_per_pe the block at src_off of
+ * every PE p.  LDST: one grid, each source vector loaded once and stored to all PEs.  SDMA:
+ * npes*npes engine copies.  AUTO uses the cutover of n_wg on bytes_per_pe. */
+int shm_launch_fcollect(shm_ctx *ctx, uint64_t dst_off, uint64_t src_off, size_t bytes_per_pe, int n_wg, int path);
+
+/* Benchmark configuration 5b: float32 sum over PEs, operand order PE 0, 1, ..., npes-1 for every
+ * element, so all PEs get bit-identical results.  DUPLICATE: every PE computes every element from
+ * one local and npes-1 remote loads (paper section "Collective Operations", reduction paragraph).
+ * SPLIT: PE q reduces the q-th share of the addresses and pushes it to all PEs (same section, the
+ * remark on very large reductions).  Offsets 4-byte aligned (16 for the vector path). */
+int shm_launch_reduce_sum_f32(shm_ctx *ctx, uint64_t dst_off, uint64_t src_off, size_t nelems, int n_wg, int algo);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SHM355_H */

@@ -1,0 +1,714 @@
+// C ABI of libshm355.so: context, symmetric heap, host-initiated operations, the cutover policy
+// and the kernel-launch entry points.  Declarations and contracts are in include/shm355.h.
+#include "shm355.h"
+
+#include <hip/hip_runtime.h>
+
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <new>
+#include <string>
+
+#include "shm_heap.hpp"
+#include "shm_kernels.hpp"
+
+namespace {
+
+constexpr uint32_t ARRIVE_SLOTS = 4096;                       // 8-byte arrival counters per PE
+static_assert(ARRIVE_SLOTS * 8 <= SHM_INTERNAL_BYTES, "arrival counters must fit the internal tail");
+static_assert(SHM_WG_SIZE == SHMK_WG, "one work-group size everywhere");
+constexpr int MAX_N_WG = 1 << 20;
+
+thread_local std::string g_err = "";
+
+int fail(int code, const char *fmt, ...)
+{
+    char buf[512];
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(buf, sizeof buf, fmt, ap);
+    va_end(ap);
+    g_err = buf;
+    return code;
+}
+
+}  // namespace
+
+struct shm_ctx {
+    int npes = 0;
+    size_t part_bytes = 0;        // partition stride = heap bytes per PE including the internal tail
+    size_t user_bytes = 0;        // what callers may allocate and address
+    char *base = nullptr;
+    bool own_heap = false, own_streams = false, no_device = false;
+    hipStream_t stream[SHM_MAX_PES] = {};
+    hipEvent_t event[SHM_MAX_PES] = {};
+    uint64_t *status_host = nullptr;
+    uint64_t *status_dev = nullptr;
+    uint64_t wait_us = 2000000;
+    uint64_t ticks_per_us = 100;
+    size_t cutover[4] = {SIZE_MAX, SIZE_MAX, SIZE_MAX, SIZE_MAX};
+    bool team_sync = true;
+    int num_cu = 0;
+    uint32_t next_slot[SHM_MAX_PES] = {};
+    shm_heap_allocator alloc;
+};
+
+namespace {
+
+#define HIP_TRY(expr)                                                                            \
+    do {                                                                                         \
+        hipError_t e_ = (expr);                                                                  \
+        if (e_ != hipSuccess) return fail(SHM_EHIP, "%s: %s", #expr, hipGetErrorString(e_));     \
+    } while (0)
+
+shm_dev_ctx dev_view(const shm_ctx *c)
+{
+    shm_dev_ctx d;
+    memset(&d, 0, sizeof d);
+    for (int p = 0; p < c->npes; ++p) d.base[p] = c->base + static_cast<size_t>(p) * c->part_bytes;
+    d.status = c->status_dev;
+    d.wait_ticks = c->wait_us * c->ticks_per_us;
+    d.npes = c->npes;
+    return d;
+}
+
+int check_ctx(const shm_ctx *c) { return c ? SHM_OK : fail(SHM_EINVAL, "null context"); }
+
+int check_pe(const shm_ctx *c, int pe, const char *what)
+{
+    if (pe < 0 || pe >= c->npes) return fail(SHM_EPE, "%s %d outside 0..%d", what, pe, c->npes - 1);
+    return SHM_OK;
+}
+
+int check_range(const shm_ctx *c, uint64_t off, size_t n, const char *what)
+{
+    if (off > c->user_bytes || n > c->user_bytes - off)
+        return fail(SHM_ERANGE, "%s [%llu, +%zu) leaves the %zu-byte heap", what, (unsigned long long)off, n, c->user_bytes);
+    return SHM_OK;
+}
+
+int check_word(const shm_ctx *c, uint64_t off, const char *what)
+{
+    if (int r = check_range(c, off, 8, what)) return r;
+    if (off & 7) return fail(SHM_EINVAL, "%s offset %llu is not 8-byte aligned", what, (unsigned long long)off);
+    return SHM_OK;
+}
+
+int check_n_wg(int n_wg)
+{
+    if (n_wg < 1 || n_wg > MAX_N_WG) return fail(SHM_EINVAL, "n_wg %d outside 1..%d", n_wg, MAX_N_WG);
+    return SHM_OK;
+}
+
+bool overlaps(uint64_t a, uint64_t b, size_t n) { return n && a < b + n && b < a + n; }
+
+int wg_class(int n_wg) { return n_wg <= 1 ? 0 : n_wg <= 4 ? 1 : n_wg <= 64 ? 2 : 3; }
+
+int resolve_path(const shm_ctx *c, int path, size_t n, int n_wg, int *out)
+{
+    if (path == SHM_PATH_AUTO)
+        *out = (n >= c->cutover[wg_class(n_wg)]) ? SHM_PATH_SDMA : SHM_PATH_LDST;
+    else if (path == SHM_PATH_LDST || path == SHM_PATH_SDMA)
+        *out = path;
+    else
+        return fail(SHM_EINVAL, "unknown path %d", path);
+    return SHM_OK;
+}
+
+int launched(const char *what)
+{
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return fail(SHM_EHIP, "launch of %s: %s", what, hipGetErrorString(e));
+    return SHM_OK;
+}
+
+int no_device(const char *what) { return fail(SHM_ENODEV, "%s needs a device; context was built with SHM_INIT_NO_DEVICE", what); }
+
+int take_status(shm_ctx *c)
+{
+    if (c->status_host && *c->status_host) {
+        *c->status_host = 0;
+        return fail(SHM_ETIMEOUT, "a device-side wait expired after %llu us", (unsigned long long)c->wait_us);
+    }
+    return SHM_OK;
+}
+
+// All PE streams -> team stream (PE 0's).
+int team_join(shm_ctx *c)
+{
+    for (int p = 1; p < c->npes; ++p) {
+        HIP_TRY(hipEventRecord(c->event[p], c->stream[p]));
+        HIP_TRY(hipStreamWaitEvent(c->stream[0], c->event[p], 0));
+    }
+    return SHM_OK;
+}
+
+// Team stream -> all PE streams.
+int team_fork(shm_ctx *c)
+{
+    HIP_TRY(hipEventRecord(c->event[0], c->stream[0]));
+    for (int p = 1; p < c->npes; ++p) HIP_TRY(hipStreamWaitEvent(c->stream[p], c->event[0], 0));
+    return SHM_OK;
+}
+
+uint32_t take_slots(shm_ctx *c, int pe, uint32_t count)
+{
+    if (c->next_slot[pe] + count > ARRIVE_SLOTS) c->next_slot[pe] = 0;
+    const uint32_t s = c->next_slot[pe];
+    c->next_slot[pe] += count;
+    return s;
+}
+
+int rma_args(const shm_ctx *c, int me, int pe, uint64_t dst_off, uint64_t src_off, size_t n)
+{
+    if (int r = check_pe(c, me, "calling PE")) return r;
+    if (int r = check_pe(c, pe, "target PE")) return r;
+    if (int r = check_range(c, dst_off, n, "destination")) return r;
+    if (int r = check_range(c, src_off, n, "source")) return r;
+    if (me == pe && overlaps(dst_off, src_off, n)) return fail(SHM_EINVAL, "source and destination overlap on PE %d", me);
+    return SHM_OK;
+}
+
+int engine_copy(shm_ctx *c, int on_pe, int dst_pe, uint64_t dst_off, int src_pe, uint64_t src_off, size_t n)
+{
+    if (n == 0) return SHM_OK;
+    HIP_TRY(hipMemcpyAsync(shm_ptr(c, dst_off, dst_pe), shm_ptr(c, src_off, src_pe), n, hipMemcpyDeviceToDevice, c->stream[on_pe]));
+    return SHM_OK;
+}
+
+int wg_rma(shm_ctx *c, int me, int pe, uint64_t dst_off, uint64_t src_off, size_t n, int n_wg, int path, int is_get)
+{
+    if (int r = check_ctx(c)) return r;
+    if (int r = rma_args(c, me, pe, dst_off, src_off, n)) return r;
+    if (int r = check_n_wg(n_wg)) return r;
+    int use;
+    if (int r = resolve_path(c, path, n, n_wg, &use)) return r;
+    if (c->no_device) return no_device(is_get ? "shm_launch_wg_get" : "shm_launch_wg_put");
+    if (use == SHM_PATH_SDMA)
+        return is_get ? engine_copy(c, me, me, dst_off, pe, src_off, n) : engine_copy(c, me, pe, dst_off, me, src_off, n);
+    const int shift = (pe - me + c->npes) % c->npes;
+    hipLaunchKernelGGL(shmk_wg_rma, dim3(n_wg, 1), dim3(SHMK_WG), 0, c->stream[me], dev_view(c), dst_off, src_off, n, me, shift,
+                       is_get);
+    return launched("work-group put/get");
+}
+
+int wg_rma_all(shm_ctx *c, int pe_shift, uint64_t dst_off, uint64_t src_off, size_t n, int n_wg, int path, int is_get)
+{
+    if (int r = check_ctx(c)) return r;
+    if (pe_shift < 0 || pe_shift >= c->npes) return fail(SHM_EPE, "pe_shift %d outside 0..%d", pe_shift, c->npes - 1);
+    if (int r = rma_args(c, 0, pe_shift, dst_off, src_off, n)) return r;   // shift 0 = every PE targets itself
+    if (int r = check_n_wg(n_wg)) return r;
+    int use;
+    if (int r = resolve_path(c, path, n, n_wg, &use)) return r;
+    if (c->no_device) return no_device("team put/get");
+    if (use == SHM_PATH_SDMA) {
+        if (c->team_sync) {
+            if (int r = team_join(c)) return r;
+            if (int r = team_fork(c)) return r;
+        }
+        for (int p = 0; p < c->npes; ++p) {
+            const int t = (p + pe_shift) % c->npes;
+            if (int r = is_get ? engine_copy(c, p, p, dst_off, t, src_off, n) : engine_copy(c, p, t, dst_off, p, src_off, n)) return r;
+        }
+        if (c->team_sync) {
+            if (int r = team_join(c)) return r;
+            if (int r = team_fork(c)) return r;
+        }
+        return SHM_OK;
+    }
+    if (c->team_sync)
+        if (int r = team_join(c)) return r;
+    hipLaunchKernelGGL(shmk_wg_rma, dim3(n_wg, c->npes), dim3(SHMK_WG), 0, c->stream[0], dev_view(c), dst_off, src_off, n, 0,
+                       pe_shift, is_get);
+    if (int r = launched("team put/get")) return r;
+    if (c->team_sync)
+        if (int r = team_fork(c)) return r;
+    return SHM_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char *shm_last_error(void) { return g_err.c_str(); }
+
+int shm_init(int npes, size_t heap_bytes, void *heap_base, void *const *streams, shm_ctx **out)
+{
+    return shm_init_ex(npes, heap_bytes, heap_base, streams, SHM_INIT_DEFAULT, out);
+}
+
+int shm_init_ex(int npes, size_t heap_bytes, void *heap_base, void *const *streams, unsigned flags, shm_ctx **out)
+{
+    if (!out) return fail(SHM_EINVAL, "null out pointer");
+    *out = nullptr;
+    if (npes < 1 || npes > SHM_MAX_PES) return fail(SHM_EPE, "npes %d outside 1..%d", npes, SHM_MAX_PES);
+    if (heap_bytes <= SHM_INTERNAL_BYTES || heap_bytes % 4096)
+        return fail(SHM_EINVAL, "heap_bytes must be a multiple of 4096 larger than %d", SHM_INTERNAL_BYTES);
+    if (heap_bytes > SIZE_MAX / SHM_MAX_PES) return fail(SHM_EINVAL, "heap_bytes too large");
+    if (flags & ~static_cast<unsigned>(SHM_INIT_NO_DEVICE)) return fail(SHM_EINVAL, "unknown flags 0x%x", flags);
+    if (reinterpret_cast<uintptr_t>(heap_base) & 255) return fail(SHM_EINVAL, "heap_base must be 256-byte aligned");
+    shm_ctx *c = new (std::nothrow) shm_ctx;
+    if (!c) return fail(SHM_ENOMEM, "out of host memory");
+    c->npes = npes;
+    c->part_bytes = heap_bytes;
+    c->user_bytes = heap_bytes - SHM_INTERNAL_BYTES;
+    c->alloc.reset(c->user_bytes);
+    c->no_device = (flags & SHM_INIT_NO_DEVICE) != 0;
+    if (c->no_device) {
+        if (!heap_base) {
+            delete c;
+            return fail(SHM_EINVAL, "SHM_INIT_NO_DEVICE needs a non-null heap_base placeholder");
+        }
+        c->base = static_cast<char *>(heap_base);
+        *out = c;
+        return SHM_OK;
+    }
+    auto bail = [&](int code) {
+        shm_finalize(c);
+        return code;
+    };
+#define INIT_TRY(expr)                                                                                   \
+    do {                                                                                                 \
+        hipError_t e_ = (expr);                                                                          \
+        if (e_ != hipSuccess) return bail(fail(SHM_EHIP, "%s: %s", #expr, hipGetErrorString(e_)));       \
+    } while (0)
+    int dev = 0, rate_khz = 0;
+    INIT_TRY(hipGetDevice(&dev));
+    INIT_TRY(hipDeviceGetAttribute(&c->num_cu, hipDeviceAttributeMultiprocessorCount, dev));
+    if (hipDeviceGetAttribute(&rate_khz, hipDeviceAttributeWallClockRate, dev) == hipSuccess && rate_khz >= 1000)
+        c->ticks_per_us = static_cast<uint64_t>(rate_khz) / 1000;
+    if (heap_base) {
+        c->base = static_cast<char *>(heap_base);
+    } else {
+        void *p = nullptr;
+        hipError_t e = hipMalloc(&p, heap_bytes * npes);
+        if (e != hipSuccess) return bail(fail(SHM_ENOMEM, "hipMalloc of %zu bytes: %s", heap_bytes * npes, hipGetErrorString(e)));
+        c->base = static_cast<char *>(p);
+        c->own_heap = true;
+    }
+    if (streams) {
+        for (int p = 0; p < npes; ++p) c->stream[p] = static_cast<hipStream_t>(streams[p]);
+    } else {
+        c->own_streams = true;
+        for (int p = 0; p < npes; ++p) INIT_TRY(hipStreamCreateWithFlags(&c->stream[p], hipStreamNonBlocking));
+    }
+    for (int p = 0; p < npes; ++p) INIT_TRY(hipEventCreateWithFlags(&c->event[p], hipEventDisableTiming));
+    void *st = nullptr;
+    INIT_TRY(hipHostMalloc(&st, 64, hipHostMallocMapped));
+    c->status_host = static_cast<uint64_t *>(st);
+    *c->status_host = 0;
+    void *st_dev = nullptr;
+    INIT_TRY(hipHostGetDevicePointer(&st_dev, st, 0));
+    c->status_dev = static_cast<uint64_t *>(st_dev);
+    for (int p = 0; p < npes; ++p)
+        INIT_TRY(hipMemset(c->base + static_cast<size_t>(p) * heap_bytes + c->user_bytes, 0, SHM_INTERNAL_BYTES));
+    INIT_TRY(hipDeviceSynchronize());
+#undef INIT_TRY
+    *out = c;
+    return SHM_OK;
+}
+
+int shm_finalize(shm_ctx *c)
+{
+    if (int r = check_ctx(c)) return r;
+    if (!c->no_device) {
+        for (int p = 0; p < c->npes; ++p)
+            if (c->stream[p] || !c->own_streams) (void)hipStreamSynchronize(c->stream[p]);
+        for (int p = 0; p < c->npes; ++p) {
+            if (c->event[p]) (void)hipEventDestroy(c->event[p]);
+            if (c->own_streams && c->stream[p]) (void)hipStreamDestroy(c->stream[p]);
+        }
+        if (c->status_host) (void)hipHostFree(c->status_host);
+        if (c->own_heap && c->base) (void)hipFree(c->base);
+    }
+    delete c;
+    return SHM_OK;
+}
+
+int shm_n_pes(const shm_ctx *c) { return c ? c->npes : fail(SHM_EINVAL, "null context"); }
+
+size_t shm_heap_bytes(const shm_ctx *c) { return c ? c->user_bytes : 0; }
+
+int shm_malloc(shm_ctx *c, size_t bytes, size_t align, uint64_t *off)
+{
+    if (int r = check_ctx(c)) return r;
+    if (!off) return fail(SHM_EINVAL, "null offset pointer");
+    if (align == 0) align = 256;
+    if (align & (align - 1)) return fail(SHM_EINVAL, "alignment %zu is not a power of two", align);
+    if (bytes == 0) {
+        *off = SHM_NULL_OFF;
+        return SHM_OK;
+    }
+    const uint64_t o = c->alloc.allocate(bytes, align);
+    if (o == shm_heap_allocator::NPOS) return fail(SHM_ENOMEM, "no free extent of %zu bytes (align %zu) in the symmetric heap", bytes, align);
+    *off = o;
+    return SHM_OK;
+}
+
+int shm_calloc(shm_ctx *c, size_t bytes, size_t align, uint64_t *off)
+{
+    if (int r = shm_malloc(c, bytes, align, off)) return r;
+    if (bytes == 0 || c->no_device) return SHM_OK;
+    for (int p = 0; p < c->npes; ++p) HIP_TRY(hipMemsetAsync(shm_ptr(c, *off, p), 0, bytes, c->stream[p]));
+    for (int p = 0; p < c->npes; ++p) HIP_TRY(hipStreamSynchronize(c->stream[p]));
+    return SHM_OK;
+}
+
+int shm_free(shm_ctx *c, uint64_t off)
+{
+    if (int r = check_ctx(c)) return r;
+    if (off == SHM_NULL_OFF) return SHM_OK;
+    if (!c->alloc.release(off)) return fail(SHM_EINVAL, "offset %llu is not a live block", (unsigned long long)off);
+    return SHM_OK;
+}
+
+void *shm_ptr(const shm_ctx *c, uint64_t off, int pe)
+{
+    if (!c || pe < 0 || pe >= c->npes || off >= c->part_bytes) return nullptr;
+    return c->base + static_cast<size_t>(pe) * c->part_bytes + off;
+}
+
+int shm_write(shm_ctx *c, int pe, uint64_t off, const void *host, size_t n)
+{
+    if (int r = check_ctx(c)) return r;
+    if (int r = check_pe(c, pe, "PE")) return r;
+    if (int r = check_range(c, off, n, "destination")) return r;
+    if (n && !host) return fail(SHM_EINVAL, "null host buffer");
+    if (c->no_device) return no_device("shm_write");
+    if (n) HIP_TRY(hipMemcpy(shm_ptr(c, off, pe), host, n, hipMemcpyHostToDevice));
+    return SHM_OK;
+}
+
+int shm_read(shm_ctx *c, int pe, uint64_t off, void *host, size_t n)
+{
+    if (int r = check_ctx(c)) return r;
+    if (int r = check_pe(c, pe, "PE")) return r;
+    if (int r = check_range(c, off, n, "source")) return r;
+    if (n && !host) return fail(SHM_EINVAL, "null host buffer");
+    if (c->no_device) return no_device("shm_read");
+    if (n) HIP_TRY(hipMemcpy(host, shm_ptr(c, off, pe), n, hipMemcpyDeviceToHost));
+    return SHM_OK;
+}
+
+int shm_putmem(shm_ctx *c, int me, uint64_t dst_off, uint64_t src_off, size_t n, int pe)
+{
+    if (int r = check_ctx(c)) return r;
+    if (int r = rma_args(c, me, pe, dst_off, src_off, n)) return r;
+    if (c->no_device) return no_device("shm_putmem");
+    return engine_copy(c, me, pe, dst_off, me, src_off, n);
+}
+
+int shm_getmem(shm_ctx *c, int me, uint64_t dst_off, uint64_t src_off, size_t n, int pe)
+{
+    if (int r = check_ctx(c)) return r;
+    if (int r = rma_args(c, me, pe, dst_off, src_off, n)) return r;
+    if (c->no_device) return no_device("shm_getmem");
+    return engine_copy(c, me, me, dst_off, pe, src_off, n);
+}
+
+int shm_quiet(shm_ctx *c, int me)
+{
+    if (int r = check_ctx(c)) return r;
+    if (int r = check_pe(c, me, "calling PE")) return r;
+    if (c->no_device) return no_device("shm_quiet");
+    HIP_TRY(hipStreamSynchronize(c->stream[me]));
+    return take_status(c);
+}
+
+int shm_fence(shm_ctx *c, int me)
+{
+    if (int r = check_ctx(c)) return r;
+    if (int r = check_pe(c, me, "calling PE")) return r;
+    if (c->no_device) return no_device("shm_fence");
+    return take_status(c);     // a stream executes in order: nothing to enqueue
+}
+
+int shm_barrier_all(shm_ctx *c)
+{
+    if (int r = check_ctx(c)) return r;
+    if (c->no_device) return no_device("shm_barrier_all");
+    for (int p = 0; p < c->npes; ++p) HIP_TRY(hipStreamSynchronize(c->stream[p]));
+    return take_status(c);
+}
+
+int shm_set_cutover(shm_ctx *c, int n_wg, size_t bytes)
+{
+    if (int r = check_ctx(c)) return r;
+    if (int r = check_n_wg(n_wg)) return r;
+    c->cutover[wg_class(n_wg)] = bytes;
+    return SHM_OK;
+}
+
+int shm_get_cutover(const shm_ctx *c, int n_wg, size_t *bytes)
+{
+    if (int r = check_ctx(c)) return r;
+    if (int r = check_n_wg(n_wg)) return r;
+    if (!bytes) return fail(SHM_EINVAL, "null out pointer");
+    *bytes = c->cutover[wg_class(n_wg)];
+    return SHM_OK;
+}
+
+int shm_choose_path(const shm_ctx *c, size_t n, int n_wg, int *path)
+{
+    if (int r = check_ctx(c)) return r;
+    if (int r = check_n_wg(n_wg)) return r;
+    if (!path) return fail(SHM_EINVAL, "null out pointer");
+    return resolve_path(c, SHM_PATH_AUTO, n, n_wg, path);
+}
+
+int shm_set_wait_timeout_us(shm_ctx *c, uint64_t us)
+{
+    if (int r = check_ctx(c)) return r;
+    if (us == 0 || us > 600ull * 1000 * 1000) return fail(SHM_EINVAL, "timeout must be 1 us .. 600 s");
+    c->wait_us = us;
+    return SHM_OK;
+}
+
+int shm_set_team_sync(shm_ctx *c, int on)
+{
+    if (int r = check_ctx(c)) return r;
+    c->team_sync = on != 0;
+    return SHM_OK;
+}
+
+int shm_launch_wg_put(shm_ctx *c, int me, int pe, uint64_t dst_off, uint64_t src_off, size_t n, int n_wg, int path)
+{
+    return wg_rma(c, me, pe, dst_off, src_off, n, n_wg, path, 0);
+}
+
+int shm_launch_wg_get(shm_ctx *c, int me, int pe, uint64_t dst_off, uint64_t src_off, size_t n, int n_wg, int path)
+{
+    return wg_rma(c, me, pe, dst_off, src_off, n, n_wg, path, 1);
+}
+
+int shm_launch_wg_put_all(shm_ctx *c, int pe_shift, uint64_t dst_off, uint64_t src_off, size_t n, int n_wg, int path)
+{
+    return wg_rma_all(c, pe_shift, dst_off, src_off, n, n_wg, path, 0);
+}
+
+int shm_launch_wg_get_all(shm_ctx *c, int pe_shift, uint64_t dst_off, uint64_t src_off, size_t n, int n_wg, int path)
+{
+    return wg_rma_all(c, pe_shift, dst_off, src_off, n, n_wg, path, 1);
+}
+
+int shm_launch_wg_put_signal(shm_ctx *c, int me, int pe, uint64_t dst_off, uint64_t src_off, size_t n, uint64_t sig_off,
+                             uint64_t sig_val, int sig_op, int n_wg)
+{
+    if (int r = check_ctx(c)) return r;
+    if (int r = rma_args(c, me, pe, dst_off, src_off, n)) return r;
+    if (int r = check_word(c, sig_off, "signal")) return r;
+    if (sig_op != SHM_SIGNAL_SET && sig_op != SHM_SIGNAL_ADD) return fail(SHM_EINVAL, "signal op %d is neither SET nor ADD", sig_op);
+    if (int r = check_n_wg(n_wg)) return r;
+    if (n && sig_off + 8 > dst_off && sig_off < dst_off + n)
+        return fail(SHM_EINVAL, "signal word lies inside the destination");
+    if (c->no_device) return no_device("shm_launch_wg_put_signal");
+    uint64_t *arrive = nullptr;
+    if (n_wg > 1) arrive = reinterpret_cast<uint64_t *>(shm_ptr(c, c->user_bytes, me)) + take_slots(c, me, 1);
+    hipLaunchKernelGGL(shmk_wg_put_signal, dim3(n_wg), dim3(SHMK_WG), 0, c->stream[me], dev_view(c), me, pe, dst_off, src_off, n,
+                       sig_off, sig_val, sig_op, arrive);
+    return launched("put with signal");
+}
+
+int shm_launch_signal_wait_until(shm_ctx *c, int me, uint64_t sig_off, int cmp, uint64_t val, uint64_t *dev_out)
+{
+    if (int r = check_ctx(c)) return r;
+    if (int r = check_pe(c, me, "calling PE")) return r;
+    if (int r = check_word(c, sig_off, "signal")) return r;
+    if (cmp < SHM_CMP_EQ || cmp > SHM_CMP_LE) return fail(SHM_EINVAL, "unknown comparison %d", cmp);
+    if (c->no_device) return no_device("shm_launch_signal_wait_until");
+    hipLaunchKernelGGL(shmk_signal_wait, dim3(1), dim3(SHMK_WG), 0, c->stream[me], dev_view(c), me, sig_off, cmp, val, dev_out);
+    return launched("signal wait");
+}
+
+int shm_launch_amo(shm_ctx *c, int me, int pe, uint64_t off, int op, int64_t operand, int64_t cond, int64_t *dev_out)
+{
+    if (int r = check_ctx(c)) return r;
+    if (int r = check_pe(c, me, "calling PE")) return r;
+    if (int r = check_pe(c, pe, "target PE")) return r;
+    if (int r = check_word(c, off, "atomic target")) return r;
+    if (op < SHM_AMO_FETCH || op > SHM_AMO_INC) return fail(SHM_EINVAL, "unknown atomic op %d", op);
+    if (c->no_device) return no_device("shm_launch_amo");
+    hipLaunchKernelGGL(shmk_amo, dim3(1), dim3(64), 0, c->stream[me], dev_view(c), pe, off, op, operand, cond, dev_out);
+    return launched("atomic");
+}
+
+int shm_launch_pingflag(shm_ctx *c, uint64_t data_off, uint64_t back_off, size_t n, uint64_t flag_off)
+{
+    if (int r = check_ctx(c)) return r;
+    if (c->npes < 2) return fail(SHM_EPE, "needs at least 2 PEs");
+    if (int r = check_range(c, data_off, n, "data")) return r;
+    if (int r = check_range(c, back_off, n, "get-back buffer")) return r;
+    if (int r = check_word(c, flag_off, "flag")) return r;
+    if (overlaps(data_off, back_off, n)) return fail(SHM_EINVAL, "data and get-back buffer overlap");
+    if ((flag_off + 8 > data_off && flag_off < data_off + n) || (flag_off + 8 > back_off && flag_off < back_off + n))
+        return fail(SHM_EINVAL, "flag lies inside a data buffer");
+    if (c->no_device) return no_device("shm_launch_pingflag");
+    const shm_dev_ctx d = dev_view(c);
+    // The producer is enqueued first: it never waits, so the consumer's bounded wait always ends.
+    hipLaunchKernelGGL(shmk_ping_producer, dim3(1), dim3(SHMK_WG), 0, c->stream[0], d, data_off, n, flag_off);
+    if (int r = launched("ping producer")) return r;
+    hipLaunchKernelGGL(shmk_ping_consumer, dim3(1), dim3(SHMK_WG), 0, c->stream[1], d, data_off, back_off, n, flag_off);
+    return launched("ping consumer");
+}
+
+int shm_launch_ring_pipeline(shm_ctx *c, uint64_t src_off, uint64_t slot_off, uint64_t sig_off, uint64_t acc_off, size_t chunk_bytes,
+                             int n_chunks, int n_wg_prod, int n_wg_cons)
+{
+    if (int r = check_ctx(c)) return r;
+    if (chunk_bytes == 0 || chunk_bytes % 16) return fail(SHM_EINVAL, "chunk_bytes must be a positive multiple of 16");
+    if (n_chunks < 1 || static_cast<uint32_t>(n_chunks) > ARRIVE_SLOTS) return fail(SHM_EINVAL, "n_chunks outside 1..%u", ARRIVE_SLOTS);
+    if (n_wg_prod < 1 || n_wg_cons < 1) return fail(SHM_EINVAL, "need at least one producer and one consumer group per PE");
+    if (chunk_bytes > c->user_bytes / n_chunks) return fail(SHM_ERANGE, "chunks leave the heap");
+    const size_t total = chunk_bytes * n_chunks;
+    if (int r = check_range(c, src_off, total, "chunk source")) return r;
+    if (int r = check_range(c, slot_off, total, "landing slots")) return r;
+    if (int r = check_range(c, acc_off, chunk_bytes * 2, "accumulator")) return r;
+    if (int r = check_word(c, sig_off, "signal")) return r;
+    if ((src_off | slot_off | acc_off) & 15) return fail(SHM_EINVAL, "offsets must be 16-byte aligned");
+    if (overlaps(src_off, slot_off, total) || (acc_off < slot_off + total && slot_off < acc_off + 2 * chunk_bytes) ||
+        (acc_off < src_off + total && src_off < acc_off + 2 * chunk_bytes))
+        return fail(SHM_EINVAL, "source, slots and accumulator must be disjoint");
+    const size_t nvec = chunk_bytes / 16;
+    if ((nvec + n_wg_cons - 1) / n_wg_cons > static_cast<size_t>(SHMK_WG) * SHMK_RING_VPT)
+        return fail(SHM_EINVAL, "n_wg_cons too small: a consumer group holds at most %d bytes of a chunk", SHMK_WG * SHMK_RING_VPT * 16);
+    if (c->no_device) return no_device("shm_launch_ring_pipeline");
+    int per_cu = 0;
+    HIP_TRY(hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, shmk_ring, SHMK_WG, 0));
+    const long long groups = static_cast<long long>(c->npes) * (n_wg_prod + n_wg_cons);
+    if (groups > static_cast<long long>(per_cu) * c->num_cu)
+        return fail(SHM_EINVAL, "%lld groups cannot all be resident (%d CUs x %d); consumers would wait on groups that never start",
+                    groups, c->num_cu, per_cu);
+    // one arrival counter per chunk, same slot range on every PE
+    uint32_t first = 0;
+    for (int p = 0; p < c->npes; ++p) c->next_slot[p] = 0;
+    for (int p = 0; p < c->npes; ++p) first = take_slots(c, p, n_chunks);
+    if (c->team_sync)
+        if (int r = team_join(c)) return r;
+    hipLaunchKernelGGL(shmk_ring, dim3(static_cast<unsigned>(groups)), dim3(SHMK_WG), 0, c->stream[0], dev_view(c), src_off, slot_off,
+                       sig_off, acc_off, chunk_bytes, n_chunks, n_wg_prod, n_wg_cons, c->user_bytes + 8ull * first);
+    if (int r = launched("ring pipeline")) return r;
+    if (c->team_sync)
+        if (int r = team_fork(c)) return r;
+    return SHM_OK;
+}
+
+int shm_launch_amo_storm(shm_ctx *c, uint64_t ctr_off, int n_ctr, const uint16_t *dev_targets, uint64_t n_items, int ops_per_item,
+                         int kind, int64_t *dev_fetched, uint64_t *dev_checksum)
+{
+    if (int r = check_ctx(c)) return r;
+    if (n_ctr < 1 || static_cast<long long>(n_ctr) * c->npes > 65536) return fail(SHM_EINVAL, "npes * n_ctr must be 1..65536 (16-bit targets)");
+    if (int r = check_range(c, ctr_off, 8ull * n_ctr, "counters")) return r;
+    if (ctr_off & 7) return fail(SHM_EINVAL, "counters must be 8-byte aligned");
+    if (!dev_targets) return fail(SHM_EINVAL, "null target table");
+    if (reinterpret_cast<uintptr_t>(dev_targets) & 15) return fail(SHM_EINVAL, "target table must be 16-byte aligned");
+    if (ops_per_item < 1 || ops_per_item > 4096) return fail(SHM_EINVAL, "ops_per_item outside 1..4096");
+    if (kind < SHM_STORM_FETCH_ADD || kind > SHM_STORM_PLAIN_STORE) return fail(SHM_EINVAL, "unknown storm kind %d", kind);
+    const uint64_t groups = (n_items + SHMK_WG - 1) / SHMK_WG;
+    if (n_items == 0 || groups > 0x7fffffffull) return fail(SHM_EINVAL, "n_items outside 1..2^31*256");
+    if (c->no_device) return no_device("shm_launch_amo_storm");
+    if (c->team_sync)
+        if (int r = team_join(c)) return r;
+    const shm_dev_ctx d = dev_view(c);
+    const dim3 grid(static_cast<unsigned>(groups)), block(SHMK_WG);
+    hipStream_t s = c->stream[0];
+    switch (kind) {
+    case SHM_STORM_FETCH_ADD:
+        hipLaunchKernelGGL(shmk_amo_storm<0>, grid, block, 0, s, d, ctr_off, n_ctr, dev_targets, n_items, ops_per_item, dev_fetched, dev_checksum);
+        break;
+    case SHM_STORM_ADD:
+        hipLaunchKernelGGL(shmk_amo_storm<1>, grid, block, 0, s, d, ctr_off, n_ctr, dev_targets, n_items, ops_per_item, dev_fetched, dev_checksum);
+        break;
+    case SHM_STORM_CSWAP_LOOP:
+        hipLaunchKernelGGL(shmk_amo_storm<2>, grid, block, 0, s, d, ctr_off, n_ctr, dev_targets, n_items, ops_per_item, dev_fetched, dev_checksum);
+        break;
+    default:
+        hipLaunchKernelGGL(shmk_amo_storm<3>, grid, block, 0, s, d, ctr_off, n_ctr, dev_targets, n_items, ops_per_item, dev_fetched, dev_checksum);
+        break;
+    }
+    if (int r = launched("atomic storm")) return r;
+    if (c->team_sync)
+        if (int r = team_fork(c)) return r;
+    return SHM_OK;
+}
+
+int shm_launch_fcollect(shm_ctx *c, uint64_t dst_off, uint64_t src_off, size_t bytes_per_pe, int n_wg, int path)
+{
+    if (int r = check_ctx(c)) return r;
+    if (bytes_per_pe > c->user_bytes / c->npes) return fail(SHM_ERANGE, "destination of %d blocks leaves the heap", c->npes);
+    const size_t total = bytes_per_pe * c->npes;
+    if (int r = check_range(c, src_off, bytes_per_pe, "source")) return r;
+    if (int r = check_range(c, dst_off, total, "destination")) return r;
+    if (bytes_per_pe && src_off < dst_off + total && dst_off < src_off + bytes_per_pe)
+        return fail(SHM_EINVAL, "source and destination overlap");
+    if (int r = check_n_wg(n_wg)) return r;
+    int use;
+    if (int r = resolve_path(c, path, bytes_per_pe, n_wg, &use)) return r;
+    if (c->no_device) return no_device("shm_launch_fcollect");
+    if (bytes_per_pe == 0) return SHM_OK;
+    if (use == SHM_PATH_SDMA) {
+        if (c->team_sync) {
+            if (int r = team_join(c)) return r;
+            if (int r = team_fork(c)) return r;
+        }
+        for (int j = 0; j < c->npes; ++j)          // destination index varies fastest across streams
+            for (int p = 0; p < c->npes; ++p) {
+                const int q = (p + 1 + j) % c->npes;
+                if (int r = engine_copy(c, p, q, dst_off + static_cast<uint64_t>(p) * bytes_per_pe, p, src_off, bytes_per_pe)) return r;
+            }
+        if (c->team_sync) {
+            if (int r = team_join(c)) return r;
+            if (int r = team_fork(c)) return r;
+        }
+        return SHM_OK;
+    }
+    if (c->team_sync)
+        if (int r = team_join(c)) return r;
+    const dim3 grid(n_wg, c->npes), block(SHMK_WG);
+    if (((dst_off | src_off | bytes_per_pe) & 15) == 0)
+        hipLaunchKernelGGL(shmk_fcollect_vec<4>, grid, block, 0, c->stream[0], dev_view(c), dst_off, src_off, bytes_per_pe);
+    else
+        hipLaunchKernelGGL(shmk_fcollect_any, grid, block, 0, c->stream[0], dev_view(c), dst_off, src_off, bytes_per_pe);
+    if (int r = launched("fcollect")) return r;
+    if (c->team_sync)
+        if (int r = team_fork(c)) return r;
+    return SHM_OK;
+}
+
+int shm_launch_reduce_sum_f32(shm_ctx *c, uint64_t dst_off, uint64_t src_off, size_t nelems, int n_wg, int algo)
+{
+    if (int r = check_ctx(c)) return r;
+    if (nelems > c->user_bytes / 4) return fail(SHM_ERANGE, "vector leaves the heap");
+    if (int r = check_range(c, src_off, nelems * 4, "source")) return r;
+    if (int r = check_range(c, dst_off, nelems * 4, "destination")) return r;
+    if ((src_off | dst_off) & 3) return fail(SHM_EINVAL, "float32 vectors must be 4-byte aligned");
+    if (overlaps(dst_off, src_off, nelems * 4)) return fail(SHM_EINVAL, "source and destination overlap");
+    if (int r = check_n_wg(n_wg)) return r;
+    if (algo != SHM_REDUCE_DUPLICATE && algo != SHM_REDUCE_SPLIT) return fail(SHM_EINVAL, "unknown reduce algorithm %d", algo);
+    if (c->no_device) return no_device("shm_launch_reduce_sum_f32");
+    if (nelems == 0) return SHM_OK;
+    if (c->team_sync)
+        if (int r = team_join(c)) return r;
+    const shm_dev_ctx d = dev_view(c);
+    const dim3 grid(n_wg, c->npes), block(SHMK_WG);
+    size_t done = 0;
+    if (((src_off | dst_off) & 15) == 0 && nelems >= 4) {
+        const size_t nvec = nelems / 4;
+        if (algo == SHM_REDUCE_SPLIT)
+            hipLaunchKernelGGL(shmk_reduce_sum_f32_vec<true>, grid, block, 0, c->stream[0], d, dst_off, src_off, nvec);
+        else
+            hipLaunchKernelGGL(shmk_reduce_sum_f32_vec<false>, grid, block, 0, c->stream[0], d, dst_off, src_off, nvec);
+        if (int r = launched("sum-reduce")) return r;
+        done = nvec * 4;
+    }
+    if (done < nelems) {
+        const dim3 sgrid(done ? 1 : n_wg, c->npes);
+        hipLaunchKernelGGL(shmk_reduce_sum_f32_scalar, sgrid, block, 0, c->stream[0], d, dst_off, src_off, done, nelems);
+        if (int r = launched("sum-reduce tail")) return r;
+    }
+    if (c->team_sync)
+        if (int r = team_fork(c)) return r;
+    return SHM_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,313 @@
+// Device-side OpenSHMEM API for gfx950: the functions a kernel embeds to move data between
+// logical PEs.  Header-only; every function is __device__ and inlined into its caller.
+//
+// Naming follows the paper's section "Proposed Device APIs": shm_* are per-thread calls, shmx_*
+// are the collaborative extensions, which EVERY thread of the wave / work-group must reach with
+// identical arguments.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#define SHM_MAX_PES 32
+
+// Per-launch view of the context, passed to kernels by value (it lives in the kernel-argument
+// segment and is read with scalar loads).  base[] plays the role of the paper's local-PE table
+// plus heap-offset array (section "Inter-node and Intra-node Communication"): one lookup gives
+// the target heap's base address.
+struct shm_dev_ctx {
+    char *base[SHM_MAX_PES];
+    uint64_t *status;        // host-pinned word; set to 1 when a bounded wait expired
+    uint64_t wait_ticks;     // bound for every wait, in wall_clock64() ticks
+    int npes;
+};
+
+typedef uint32_t shm_u32x4 __attribute__((ext_vector_type(4)));
+
+enum { SHMD_SIGNAL_SET = 0, SHMD_SIGNAL_ADD = 1 };
+enum { SHMD_CMP_EQ = 0, SHMD_CMP_NE = 1, SHMD_CMP_GT = 2, SHMD_CMP_GE = 3, SHMD_CMP_LT = 4, SHMD_CMP_LE = 5 };
+
+// Address rule of the paper's section "Remote Memory Access": same offset, target PE's base.
+__device__ __forceinline__ char *shm_ptr(const shm_dev_ctx &c, uint64_t off, int pe) { return c.base[pe] + off; }
+
+// ------------------------------------------------------------------------------------------
+// Cooperative byte copy: `nthr` threads (this one is `tid`) copy n bytes, any alignment.
+// Destination-aligned 16-byte nontemporal stores; 16-byte nontemporal loads, U of them in flight
+// per lane before the first store.  When source and destination disagree modulo 16 the source is
+// read as aligned 16-byte words and re-aligned in registers, so no access is ever misaligned.
+// ------------------------------------------------------------------------------------------
+__device__ __forceinline__ shm_u32x4 shm_ld16(const shm_u32x4 *p) { return __builtin_nontemporal_load(p); }
+__device__ __forceinline__ void shm_st16(shm_u32x4 *p, shm_u32x4 v) { __builtin_nontemporal_store(v, p); }
+
+// bytes [8*sh .. 8*sh+32) of the 64-bit value hi:lo, sh in 0..3
+__device__ __forceinline__ uint32_t shm_alignbyte(uint32_t hi, uint32_t lo, uint32_t sh)
+{
+    return __builtin_amdgcn_alignbyte(hi, lo, sh);
+}
+
+template <int W>   // W = whole words of shift (0..3); sh = remaining bytes (0..3)
+__device__ __forceinline__ shm_u32x4 shm_realign(shm_u32x4 lo, shm_u32x4 hi, uint32_t sh)
+{
+    const uint32_t w[8] = {lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
+    shm_u32x4 r;
+    r.x = shm_alignbyte(w[W + 1], w[W + 0], sh);
+    r.y = shm_alignbyte(w[W + 2], w[W + 1], sh);
+    r.z = shm_alignbyte(w[W + 3], w[W + 2], sh);
+    r.w = shm_alignbyte(w[W + 4], w[W + 3], sh);
+    return r;
+}
+
+template <int U>
+__device__ __forceinline__ void shm_copy_body_aligned(shm_u32x4 *d, const shm_u32x4 *s, size_t nvec, unsigned tid,
+                                                      unsigned nthr)
+{
+    size_t i = tid;
+    const size_t step = nthr;
+    for (; i + (U - 1) * step < nvec; i += U * step) {
+        shm_u32x4 r[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) r[u] = shm_ld16(s + i + u * step);
+#pragma unroll
+        for (int u = 0; u < U; ++u) shm_st16(d + i + u * step, r[u]);
+    }
+    for (; i < nvec; i += step) shm_st16(d + i, shm_ld16(s + i));
+}
+
+template <int W>
+__device__ __forceinline__ void shm_copy_body_shifted(shm_u32x4 *d, const shm_u32x4 *sa, size_t nvec, uint32_t sh,
+                                                      unsigned tid, unsigned nthr)
+{
+    // sa is the aligned word holding the first source byte; vector i needs words i and i+1.
+    // Word i+1 always contains at least one byte of the source range, so it is mapped.
+    for (size_t i = tid; i < nvec; i += nthr) {
+        const shm_u32x4 lo = shm_ld16(sa + i);
+        const shm_u32x4 hi = shm_ld16(sa + i + 1);
+        shm_st16(d + i, shm_realign<W>(lo, hi, sh));
+    }
+}
+
+template <int U = 8>
+__device__ __forceinline__ void shm_copy_coop(char *dst, const char *src, size_t n, unsigned tid, unsigned nthr)
+{
+    if (n == 0) return;
+    size_t head = (16 - (reinterpret_cast<uintptr_t>(dst) & 15)) & 15;
+    if (head > n) head = n;
+    const size_t body = (n - head) & ~static_cast<size_t>(15);
+    const size_t tail = n - head - body;
+    for (size_t i = tid; i < head; i += nthr) dst[i] = src[i];
+    for (size_t i = tid; i < tail; i += nthr) dst[head + body + i] = src[head + body + i];
+    if (body == 0) return;
+    shm_u32x4 *d = reinterpret_cast<shm_u32x4 *>(dst + head);
+    const char *bs = src + head;
+    const uint32_t mis = static_cast<uint32_t>(reinterpret_cast<uintptr_t>(bs) & 15);
+    const size_t nvec = body >> 4;
+    if (mis == 0) {
+        shm_copy_body_aligned<U>(d, reinterpret_cast<const shm_u32x4 *>(bs), nvec, tid, nthr);
+        return;
+    }
+    const shm_u32x4 *sa = reinterpret_cast<const shm_u32x4 *>(bs - mis);
+    const uint32_t sh = mis & 3;
+    switch (mis >> 2) {       // uniform over the group: all threads share src and dst
+    case 0: shm_copy_body_shifted<0>(d, sa, nvec, sh, tid, nthr); break;
+    case 1: shm_copy_body_shifted<1>(d, sa, nvec, sh, tid, nthr); break;
+    case 2: shm_copy_body_shifted<2>(d, sa, nvec, sh, tid, nthr); break;
+    default: shm_copy_body_shifted<3>(d, sa, nvec, sh, tid, nthr); break;
+    }
+}
+
+// ------------------------------------------------------------------------------------------
+// RMA.  A put returns when the source may be reused; its bytes are delivered (visible to other
+// PEs) after the caller's quiet.  A get returns with the bytes in place for the calling thread(s).
+// ------------------------------------------------------------------------------------------
+__device__ __forceinline__ void shm_putmem(const shm_dev_ctx &c, int me, uint64_t dst_off, uint64_t src_off, size_t n, int pe)
+{
+    shm_copy_coop<4>(shm_ptr(c, dst_off, pe), shm_ptr(c, src_off, me), n, 0, 1);
+}
+__device__ __forceinline__ void shm_getmem(const shm_dev_ctx &c, int me, uint64_t dst_off, uint64_t src_off, size_t n, int pe)
+{
+    shm_copy_coop<4>(shm_ptr(c, dst_off, me), shm_ptr(c, src_off, pe), n, 0, 1);
+}
+
+// Sub-group (wave64) forms: the 64 lanes of the calling wave share the copy.
+__device__ __forceinline__ void shmx_putmem_wave(const shm_dev_ctx &c, int me, uint64_t dst_off, uint64_t src_off, size_t n, int pe)
+{
+    shm_copy_coop<8>(shm_ptr(c, dst_off, pe), shm_ptr(c, src_off, me), n, __lane_id(), 64);
+}
+__device__ __forceinline__ void shmx_getmem_wave(const shm_dev_ctx &c, int me, uint64_t dst_off, uint64_t src_off, size_t n, int pe)
+{
+    shm_copy_coop<8>(shm_ptr(c, dst_off, me), shm_ptr(c, src_off, pe), n, __lane_id(), 64);
+}
+
+// Work-group forms (paper section "Proposed Device APIs").  The entry barrier makes every
+// thread's earlier writes to the source part of the message; the exit barrier lets any thread
+// reuse the source (put) or read the destination (get) on return.
+__device__ __forceinline__ void shmx_putmem_wg(const shm_dev_ctx &c, int me, uint64_t dst_off, uint64_t src_off, size_t n, int pe)
+{
+    __syncthreads();
+    shm_copy_coop<8>(shm_ptr(c, dst_off, pe), shm_ptr(c, src_off, me), n, threadIdx.x, blockDim.x);
+    __syncthreads();
+}
+__device__ __forceinline__ void shmx_getmem_wg(const shm_dev_ctx &c, int me, uint64_t dst_off, uint64_t src_off, size_t n, int pe)
+{
+    __syncthreads();
+    shm_copy_coop<8>(shm_ptr(c, dst_off, me), shm_ptr(c, src_off, pe), n, threadIdx.x, blockDim.x);
+    __syncthreads();
+}
+
+// ------------------------------------------------------------------------------------------
+// Ordering.  All logical PEs live on one GPU, so agent scope is the widest scope ever needed
+// between PEs.  quiet = the calling thread's puts and atomics are complete and visible to every
+// PE; fence = they are ordered before its later ones (same instruction here).
+// ------------------------------------------------------------------------------------------
+__device__ __forceinline__ void shm_quiet() { __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent"); }
+__device__ __forceinline__ void shm_fence() { __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent"); }
+__device__ __forceinline__ void shmx_quiet_wg()
+{
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
+    __syncthreads();
+}
+
+// ------------------------------------------------------------------------------------------
+// Signals: 64-bit unsigned words on the symmetric heap.
+// ------------------------------------------------------------------------------------------
+__device__ __forceinline__ void shm_signal_update(uint64_t *sig, uint64_t v, int op)
+{
+    if (op == SHMD_SIGNAL_SET)
+        __hip_atomic_store(sig, v, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
+    else
+        __hip_atomic_fetch_add(sig, v, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+__device__ __forceinline__ uint64_t shm_signal_fetch(const shm_dev_ctx &c, int me, uint64_t sig_off)
+{
+    return __hip_atomic_load(reinterpret_cast<uint64_t *>(shm_ptr(c, sig_off, me)), __ATOMIC_ACQUIRE,
+                             __HIP_MEMORY_SCOPE_AGENT);
+}
+
+__device__ __forceinline__ bool shm_cmp(uint64_t a, int cmp, uint64_t b)
+{
+    switch (cmp) {
+    case SHMD_CMP_EQ: return a == b;
+    case SHMD_CMP_NE: return a != b;
+    case SHMD_CMP_GT: return a > b;
+    case SHMD_CMP_GE: return a >= b;
+    case SHMD_CMP_LT: return a < b;
+    default: return a <= b;
+    }
+}
+
+// Spin until cmp(signal, val) holds; acquire.  Bounded: after wait_ticks the status word
+// is set and the call returns the last value read, so a kernel can never hang on a signal that
+// is not coming.
+__device__ __forceinline__ uint64_t shm_signal_wait_until(const shm_dev_ctx &c, int me, uint64_t sig_off, int cmp, uint64_t val)
+{
+    uint64_t *sig = reinterpret_cast<uint64_t *>(shm_ptr(c, sig_off, me));
+    const uint64_t t0 = wall_clock64();
+    uint64_t cur;
+    for (;;) {
+        cur = __hip_atomic_load(sig, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if (shm_cmp(cur, cmp, val)) break;
+        if (wall_clock64() - t0 > c.wait_ticks) {
+            __hip_atomic_store(c.status, 1ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+            break;
+        }
+        __builtin_amdgcn_s_sleep(2);
+    }
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+    return cur;
+}
+
+// Work-group form: one thread polls (the paper's leader-thread pattern), the value is shared
+// through LDS, and every thread leaves with acquire ordering.
+__device__ __forceinline__ uint64_t shmx_signal_wait_until_wg(const shm_dev_ctx &c, int me, uint64_t sig_off, int cmp, uint64_t val)
+{
+    __shared__ uint64_t seen;
+    if (threadIdx.x == 0) seen = shm_signal_wait_until(c, me, sig_off, cmp, val);
+    __syncthreads();
+    const uint64_t v = seen;
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+    __syncthreads();          // `seen` may be overwritten by the next wait only after everyone read it
+    return v;
+}
+
+// Put with signal for one work-group, or for `nparts` work-groups sharing one message: group
+// `part` copies its slice; every thread releases its stores; the group whose arrival completes the
+// message (counted in *arrive, which it resets to zero) updates the signal.  With nparts == 1 the
+// counter is not touched and may be null.
+__device__ __forceinline__ void shm_wg_slice(size_t n, unsigned part, unsigned nparts, size_t &lo, size_t &hi)
+{
+    size_t per = (n + nparts - 1) / nparts;
+    per = (per + 15) & ~static_cast<size_t>(15);
+    lo = static_cast<size_t>(part) * per;
+    if (lo > n) lo = n;
+    hi = lo + per;
+    if (hi > n) hi = n;
+}
+
+__device__ __forceinline__ void shmx_putmem_signal_parts(const shm_dev_ctx &c, int me, uint64_t dst_off, uint64_t src_off,
+                                                         size_t n, uint64_t sig_off, uint64_t sig_val, int sig_op, int pe,
+                                                         uint64_t *arrive, unsigned part, unsigned nparts)
+{
+    size_t lo, hi;
+    shm_wg_slice(n, part, nparts, lo, hi);
+    __syncthreads();
+    shm_copy_coop<8>(shm_ptr(c, dst_off + lo, pe), shm_ptr(c, src_off + lo, me), hi - lo, threadIdx.x, blockDim.x);
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        bool last = true;
+        if (nparts > 1) {
+            const uint64_t old = __hip_atomic_fetch_add(arrive, 1ull, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_AGENT);
+            last = (old == nparts - 1);
+            if (last) __hip_atomic_store(arrive, 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+        if (last) shm_signal_update(reinterpret_cast<uint64_t *>(shm_ptr(c, sig_off, pe)), sig_val, sig_op);
+    }
+}
+
+__device__ __forceinline__ void shmx_putmem_signal_wg(const shm_dev_ctx &c, int me, uint64_t dst_off, uint64_t src_off, size_t n,
+                                                      uint64_t sig_off, uint64_t sig_val, int sig_op, int pe)
+{
+    shmx_putmem_signal_parts(c, me, dst_off, src_off, n, sig_off, sig_val, sig_op, pe, nullptr, 0, 1);
+}
+
+// ------------------------------------------------------------------------------------------
+// 64-bit atomics on any PE's heap (paper section "Proposed Device APIs": scalar, no group form).
+// Relaxed, agent scope; order them with shm_fence/shm_quiet like any other operation.
+// ------------------------------------------------------------------------------------------
+__device__ __forceinline__ int64_t *shm_i64(const shm_dev_ctx &c, uint64_t off, int pe)
+{
+    return reinterpret_cast<int64_t *>(shm_ptr(c, off, pe));
+}
+__device__ __forceinline__ int64_t shm_atomic_fetch(const shm_dev_ctx &c, uint64_t off, int pe)
+{
+    return __hip_atomic_load(shm_i64(c, off, pe), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ void shm_atomic_set(const shm_dev_ctx &c, uint64_t off, int64_t v, int pe)
+{
+    __hip_atomic_store(shm_i64(c, off, pe), v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ int64_t shm_atomic_swap(const shm_dev_ctx &c, uint64_t off, int64_t v, int pe)
+{
+    return __hip_atomic_exchange(shm_i64(c, off, pe), v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ int64_t shm_atomic_compare_swap(const shm_dev_ctx &c, uint64_t off, int64_t cond, int64_t v, int pe)
+{
+    int64_t expected = cond;
+    __hip_atomic_compare_exchange_strong(shm_i64(c, off, pe), &expected, v, __ATOMIC_RELAXED, __ATOMIC_RELAXED,
+                                         __HIP_MEMORY_SCOPE_AGENT);
+    return expected;      // the value found: equals cond exactly when the swap happened
+}
+__device__ __forceinline__ int64_t shm_atomic_fetch_add(const shm_dev_ctx &c, uint64_t off, int64_t v, int pe)
+{
+    return __hip_atomic_fetch_add(shm_i64(c, off, pe), v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ void shm_atomic_add(const shm_dev_ctx &c, uint64_t off, int64_t v, int pe)
+{
+    (void)__hip_atomic_fetch_add(shm_i64(c, off, pe), v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ int64_t shm_atomic_fetch_inc(const shm_dev_ctx &c, uint64_t off, int pe)
+{
+    return shm_atomic_fetch_add(c, off, 1, pe);
+}
+__device__ __forceinline__ void shm_atomic_inc(const shm_dev_ctx &c, uint64_t off, int pe) { shm_atomic_add(c, off, 1, pe); }

@@ -1,0 +1,300 @@
+// __global__ drivers around the device API of shm_device.hpp.  One work-group = 256 threads
+// (4 wave64).  Grids are (groups per PE, PEs) so that blockIdx.y names the calling PE.
+#pragma once
+
+#include "shm_device.hpp"
+
+#define SHMK_WG 256
+
+typedef float shm_f32x4 __attribute__((ext_vector_type(4)));
+
+// ---- work-group put / get, one PE or a team of PEs in one grid ----------------------------
+// PE me = me0 + blockIdx.y targets PE (me + shift) mod npes; group blockIdx.x of gridDim.x takes
+// its slice of the message.
+__global__ __launch_bounds__(SHMK_WG) void shmk_wg_rma(shm_dev_ctx c, uint64_t dst_off, uint64_t src_off, size_t n, int me0,
+                                                       int shift, int is_get)
+{
+    const int me = me0 + blockIdx.y;
+    int pe = me + shift;
+    if (pe >= c.npes) pe -= c.npes;
+    size_t lo, hi;
+    shm_wg_slice(n, blockIdx.x, gridDim.x, lo, hi);
+    if (is_get)
+        shmx_getmem_wg(c, me, dst_off + lo, src_off + lo, hi - lo, pe);
+    else
+        shmx_putmem_wg(c, me, dst_off + lo, src_off + lo, hi - lo, pe);
+}
+
+__global__ __launch_bounds__(SHMK_WG) void shmk_wg_put_signal(shm_dev_ctx c, int me, int pe, uint64_t dst_off, uint64_t src_off,
+                                                              size_t n, uint64_t sig_off, uint64_t sig_val, int sig_op,
+                                                              uint64_t *arrive)
+{
+    shmx_putmem_signal_parts(c, me, dst_off, src_off, n, sig_off, sig_val, sig_op, pe, arrive, blockIdx.x, gridDim.x);
+}
+
+__global__ __launch_bounds__(SHMK_WG) void shmk_signal_wait(shm_dev_ctx c, int me, uint64_t sig_off, int cmp, uint64_t val,
+                                                            uint64_t *out)
+{
+    const uint64_t v = shmx_signal_wait_until_wg(c, me, sig_off, cmp, val);
+    if (out != nullptr && threadIdx.x == 0) *out = v;
+}
+
+// ---- one atomic by one work-item ---------------------------------------------------------
+__global__ void shmk_amo(shm_dev_ctx c, int pe, uint64_t off, int op, int64_t operand, int64_t cond, int64_t *out)
+{
+    if (threadIdx.x != 0 || blockIdx.x != 0) return;
+    int64_t r = 0;
+    switch (op) {
+    case 0: r = shm_atomic_fetch(c, off, pe); break;
+    case 1: shm_atomic_set(c, off, operand, pe); break;
+    case 2: r = shm_atomic_swap(c, off, operand, pe); break;
+    case 3: r = shm_atomic_compare_swap(c, off, cond, operand, pe); break;
+    case 4: r = shm_atomic_fetch_add(c, off, operand, pe); break;
+    case 5: shm_atomic_add(c, off, operand, pe); break;
+    case 6: r = shm_atomic_fetch_inc(c, off, pe); break;
+    default: shm_atomic_inc(c, off, pe); break;
+    }
+    if (out != nullptr) *out = r;
+}
+
+// ---- configuration 1: put, quiet, flag / wait, get back -----------------------------------
+__global__ __launch_bounds__(SHMK_WG) void shmk_ping_producer(shm_dev_ctx c, uint64_t data_off, size_t n, uint64_t flag_off)
+{
+    shmx_putmem_wg(c, 0, data_off, data_off, n, 1);
+    shmx_quiet_wg();                                                                  // orders the payload before the flag
+    shmx_putmem_signal_wg(c, 0, data_off, data_off, 0, flag_off, 1, SHMD_SIGNAL_SET, 1);  // zero-byte payload, flag := 1
+}
+
+__global__ __launch_bounds__(SHMK_WG) void shmk_ping_consumer(shm_dev_ctx c, uint64_t data_off, uint64_t back_off, size_t n,
+                                                              uint64_t flag_off)
+{
+    shmx_signal_wait_until_wg(c, 1, flag_off, SHMD_CMP_EQ, 1);
+    shmx_getmem_wg(c, 1, back_off, data_off, n, 0);
+}
+
+// ---- configuration 3: pipelined ring --------------------------------------------------------
+// Blocks [0, npes*n_prod) are producers, the rest consumers; PE = index mod npes so that the
+// groups of one PE are spread over the dispatch order.  Producers never wait, and they come first
+// in the grid, so consumers cannot starve them.
+#define SHMK_RING_VPT 8      // 16-byte vectors (8 bf16) per consumer thread held in registers
+
+__global__ __launch_bounds__(SHMK_WG) void shmk_ring(shm_dev_ctx c, uint64_t src_off, uint64_t slot_off, uint64_t sig_off,
+                                                     uint64_t acc_off, size_t chunk_bytes, int n_chunks, int n_prod, int n_cons,
+                                                     uint64_t arrive_off)
+{
+    const int npes = c.npes;
+    const int b = blockIdx.x;
+    if (b < npes * n_prod) {
+        const int me = b % npes, part = b / npes;
+        int pe = me + 1;
+        if (pe >= npes) pe = 0;
+        uint64_t *arrive = reinterpret_cast<uint64_t *>(shm_ptr(c, arrive_off, me));
+        for (int k = 0; k < n_chunks; ++k)
+            shmx_putmem_signal_parts(c, me, slot_off + k * chunk_bytes, src_off + k * chunk_bytes, chunk_bytes, sig_off, 1,
+                                     SHMD_SIGNAL_ADD, pe, arrive + k, part, n_prod);
+        return;
+    }
+    const int cb = b - npes * n_prod;
+    const int me = cb % npes, part = cb / npes;
+    const size_t nvec = chunk_bytes >> 4;
+    const size_t per = (nvec + n_cons - 1) / n_cons;           // host guarantees per <= SHMK_WG * SHMK_RING_VPT
+    const size_t lo = min(nvec, part * per), hi = min(nvec, lo + per);
+    float acc[SHMK_RING_VPT][8];
+#pragma unroll
+    for (int j = 0; j < SHMK_RING_VPT; ++j)
+#pragma unroll
+        for (int e = 0; e < 8; ++e) acc[j][e] = 0.0f;
+    for (int k = 0; k < n_chunks; ++k) {
+        shmx_signal_wait_until_wg(c, me, sig_off, SHMD_CMP_GE, static_cast<uint64_t>(k) + 1);
+        const shm_u32x4 *slot = reinterpret_cast<const shm_u32x4 *>(shm_ptr(c, slot_off + k * chunk_bytes, me));
+        shm_u32x4 w[SHMK_RING_VPT];
+#pragma unroll
+        for (int j = 0; j < SHMK_RING_VPT; ++j) {
+            const size_t v = lo + threadIdx.x + static_cast<size_t>(j) * SHMK_WG;
+            w[j] = (v < hi) ? shm_ld16(slot + v) : shm_u32x4{0, 0, 0, 0};
+        }
+#pragma unroll
+        for (int j = 0; j < SHMK_RING_VPT; ++j) {
+            const uint32_t ws[4] = {w[j].x, w[j].y, w[j].z, w[j].w};
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {      // bf16 -> f32 is a 16-bit left shift: exact
+                acc[j][2 * q] += __uint_as_float(ws[q] << 16);
+                acc[j][2 * q + 1] += __uint_as_float(ws[q] & 0xffff0000u);
+            }
+        }
+    }
+    shm_u32x4 *out = reinterpret_cast<shm_u32x4 *>(shm_ptr(c, acc_off, me));
+#pragma unroll
+    for (int j = 0; j < SHMK_RING_VPT; ++j) {
+        const size_t v = lo + threadIdx.x + static_cast<size_t>(j) * SHMK_WG;
+        if (v < hi) {
+            shm_u32x4 a, bq;
+            a.x = __float_as_uint(acc[j][0]), a.y = __float_as_uint(acc[j][1]);
+            a.z = __float_as_uint(acc[j][2]), a.w = __float_as_uint(acc[j][3]);
+            bq.x = __float_as_uint(acc[j][4]), bq.y = __float_as_uint(acc[j][5]);
+            bq.z = __float_as_uint(acc[j][6]), bq.w = __float_as_uint(acc[j][7]);
+            out[2 * v] = a;
+            out[2 * v + 1] = bq;
+        }
+    }
+}
+
+// ---- configuration 4: atomic storm -----------------------------------------------------------
+template <int KIND>
+__device__ __forceinline__ int64_t shmk_storm_op(const shm_dev_ctx &c, uint64_t off, int pe)
+{
+    if (KIND == 0) return shm_atomic_fetch_add(c, off, 1, pe);
+    if (KIND == 1) {
+        shm_atomic_add(c, off, 1, pe);
+        return 0;
+    }
+    if (KIND == 2) {   // increment built from compare-swap; every failed attempt means another thread succeeded
+        int64_t cur = shm_atomic_fetch(c, off, pe);
+        for (;;) {
+            const int64_t found = shm_atomic_compare_swap(c, off, cur, cur + 1, pe);
+            if (found == cur) return cur;
+            cur = found;
+        }
+    }
+    *reinterpret_cast<volatile int64_t *>(shm_ptr(c, off, pe)) = 1;   // plain store: timing ceiling only
+    return 0;
+}
+
+template <int KIND>
+__global__ __launch_bounds__(SHMK_WG) void shmk_amo_storm(shm_dev_ctx c, uint64_t ctr_off, uint32_t n_ctr,
+                                                          const uint16_t *__restrict__ targets, uint64_t n_items, int ops,
+                                                          int64_t *__restrict__ fetched, uint64_t *__restrict__ checksum)
+{
+    __shared__ unsigned long long wg_sum;
+    if (threadIdx.x == 0) wg_sum = 0;
+    __syncthreads();
+    const uint64_t g = static_cast<uint64_t>(blockIdx.x) * SHMK_WG + threadIdx.x;
+    uint64_t sum = 0;
+    if (g < n_items) {
+        const uint16_t *t = targets + g * ops;
+        int64_t *f = fetched ? fetched + g * ops : nullptr;
+        int j = 0;
+        if ((ops & 7) == 0) {
+            for (; j < ops; j += 8) {
+                const shm_u32x4 tv = *reinterpret_cast<const shm_u32x4 *>(t + j);
+                const uint32_t tw[4] = {tv.x, tv.y, tv.z, tv.w};
+                int64_t old[8];
+#pragma unroll
+                for (int q = 0; q < 8; ++q) {
+                    const uint32_t tt = (q & 1) ? (tw[q >> 1] >> 16) : (tw[q >> 1] & 0xffffu);
+                    old[q] = shmk_storm_op<KIND>(c, ctr_off + 8ull * (tt % n_ctr), static_cast<int>(tt / n_ctr));
+                }
+#pragma unroll
+                for (int q = 0; q < 8; ++q) {
+                    if (f) f[j + q] = old[q];
+                    sum += static_cast<uint64_t>(old[q]);
+                }
+            }
+        }
+        for (; j < ops; ++j) {
+            const uint32_t tt = t[j];
+            const int64_t old = shmk_storm_op<KIND>(c, ctr_off + 8ull * (tt % n_ctr), static_cast<int>(tt / n_ctr));
+            if (f) f[j] = old;
+            sum += static_cast<uint64_t>(old);
+        }
+    }
+    if (checksum != nullptr) {
+        atomicAdd(&wg_sum, static_cast<unsigned long long>(sum));
+        __syncthreads();
+        if (threadIdx.x == 0) checksum[blockIdx.x] = wg_sum;
+    }
+}
+
+// ---- configuration 5a: fcollect, push --------------------------------------------------------
+// PE p = blockIdx.y reads its block once and stores every vector to all PEs (inner loop over
+// destinations, outer loop over addresses), starting with its right-hand neighbour.
+template <int U>
+__global__ __launch_bounds__(SHMK_WG) void shmk_fcollect_vec(shm_dev_ctx c, uint64_t dst_off, uint64_t src_off, size_t bytes_per_pe)
+{
+    const int p = blockIdx.y, npes = c.npes;
+    size_t lo, hi;
+    shm_wg_slice(bytes_per_pe, blockIdx.x, gridDim.x, lo, hi);
+    const shm_u32x4 *s = reinterpret_cast<const shm_u32x4 *>(shm_ptr(c, src_off + lo, p));
+    const uint64_t d0 = dst_off + static_cast<uint64_t>(p) * bytes_per_pe + lo;
+    const size_t nvec = (hi - lo) >> 4;
+    size_t i = threadIdx.x;
+    for (; i + (U - 1) * SHMK_WG < nvec; i += U * SHMK_WG) {
+        shm_u32x4 r[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) r[u] = shm_ld16(s + i + u * SHMK_WG);
+        for (int j = 0; j < npes; ++j) {
+            int q = p + 1 + j;
+            if (q >= npes) q -= npes;
+            shm_u32x4 *d = reinterpret_cast<shm_u32x4 *>(shm_ptr(c, d0, q));
+#pragma unroll
+            for (int u = 0; u < U; ++u) shm_st16(d + i + u * SHMK_WG, r[u]);
+        }
+    }
+    for (; i < nvec; i += SHMK_WG) {
+        const shm_u32x4 r = shm_ld16(s + i);
+        for (int j = 0; j < npes; ++j) {
+            int q = p + 1 + j;
+            if (q >= npes) q -= npes;
+            shm_st16(reinterpret_cast<shm_u32x4 *>(shm_ptr(c, d0, q)) + i, r);
+        }
+    }
+}
+
+// Any alignment or length: one work-group put per destination.
+__global__ __launch_bounds__(SHMK_WG) void shmk_fcollect_any(shm_dev_ctx c, uint64_t dst_off, uint64_t src_off, size_t bytes_per_pe)
+{
+    const int p = blockIdx.y, npes = c.npes;
+    size_t lo, hi;
+    shm_wg_slice(bytes_per_pe, blockIdx.x, gridDim.x, lo, hi);
+    for (int j = 0; j < npes; ++j) {
+        int q = p + 1 + j;
+        if (q >= npes) q -= npes;
+        shmx_putmem_wg(c, p, dst_off + static_cast<uint64_t>(p) * bytes_per_pe + lo, src_off + lo, hi - lo, q);
+    }
+}
+
+// ---- configuration 5b: float32 sum-reduce ---------------------------------------------------
+// Element i of the result is ((x0[i] + x1[i]) + x2[i]) + ... in PE order, on every PE.
+// SPLIT = false: PE q = blockIdx.y computes all elements and stores to its own destination.
+// SPLIT = true : PE q computes the q-th share of the vectors and stores it to every PE.
+template <bool SPLIT>
+__global__ __launch_bounds__(SHMK_WG) void shmk_reduce_sum_f32_vec(shm_dev_ctx c, uint64_t dst_off, uint64_t src_off, size_t nvec)
+{
+    const int q = blockIdx.y, npes = c.npes;
+    size_t first = 0, count = nvec;
+    if (SPLIT) {
+        const size_t share = (nvec + npes - 1) / npes;
+        first = min(nvec, q * share);
+        count = min(nvec, first + share) - first;
+    }
+    const size_t per = (count + gridDim.x - 1) / gridDim.x;
+    const size_t lo = first + min(count, blockIdx.x * per), hi = min(first + count, lo + per);
+    for (size_t i = lo + threadIdx.x; i < hi; i += SHMK_WG) {
+        const shm_f32x4 *s0 = reinterpret_cast<const shm_f32x4 *>(shm_ptr(c, src_off, 0));
+        shm_f32x4 r = __builtin_nontemporal_load(s0 + i);
+        for (int p = 1; p < npes; ++p) {
+            const shm_f32x4 v = __builtin_nontemporal_load(reinterpret_cast<const shm_f32x4 *>(shm_ptr(c, src_off, p)) + i);
+            r.x += v.x, r.y += v.y, r.z += v.z, r.w += v.w;
+        }
+        if (SPLIT) {
+            for (int t = 0; t < npes; ++t)
+                __builtin_nontemporal_store(r, reinterpret_cast<shm_f32x4 *>(shm_ptr(c, dst_off, t)) + i);
+        } else {
+            __builtin_nontemporal_store(r, reinterpret_cast<shm_f32x4 *>(shm_ptr(c, dst_off, q)) + i);
+        }
+    }
+}
+
+// Scalar form for the last nelems % 4 elements and for offsets that are not 16-byte aligned:
+// elements [first, nelems), every PE q = blockIdx.y writes its own destination.
+__global__ __launch_bounds__(SHMK_WG) void shmk_reduce_sum_f32_scalar(shm_dev_ctx c, uint64_t dst_off, uint64_t src_off, size_t first,
+                                                                      size_t nelems)
+{
+    const int q = blockIdx.y, npes = c.npes;
+    const size_t stride = static_cast<size_t>(gridDim.x) * SHMK_WG;
+    for (size_t i = first + static_cast<size_t>(blockIdx.x) * SHMK_WG + threadIdx.x; i < nelems; i += stride) {
+        float r = reinterpret_cast<const float *>(shm_ptr(c, src_off, 0))[i];
+        for (int p = 1; p < npes; ++p) r += reinterpret_cast<const float *>(shm_ptr(c, src_off, p))[i];
+        reinterpret_cast<float *>(shm_ptr(c, dst_off, q))[i] = r;
+    }
+}

@@ -1,0 +1,108 @@
+"""GPU parity: work-group put/get, team forms, both transfer paths, host RMA -- bit-exact against the oracle."""
+import numpy as np
+import pytest
+
+from paper_2409_20476_amd import shm as S
+from parity_util import assert_heaps_equal, fill_random, make_pair
+
+pytestmark = pytest.mark.gpu
+
+MiB = 1 << 20
+
+
+def test_alignment_sweep_single_group():
+    """Every (src mod 16, dst mod 16) pair, every length 0..96, one work-group; canaries are the rest of the heap."""
+    g, o = make_pair(2, MiB)
+    with g:
+        fill_random(g, o, 1)
+        for s in range(16):
+            for d in range(16):
+                for n in range(97):
+                    src = 1024 + s + 16 * (n % 5)
+                    dst = 65536 + (d * 97 + n) * 256 + 64 + d        # own 256-byte slot per (d, n); dst mod 16 == d
+                    g.launch_wg_put(0, 1, dst, src, n, 1)
+                    o.wg_put(0, dst, src, n, 1, 1)
+            g.barrier_all()
+            assert_heaps_equal(g, o, what=f"src mod 16 = {s}")
+
+
+@pytest.mark.parametrize("n_wg", [1, 3, 4, 64])
+def test_put_get_sizes_tiles_and_ragged_tails(n_wg):
+    g, o = make_pair(3, 8 * MiB)
+    with g:
+        fill_random(g, o, 2, upto=6 * MiB)
+        cases = [(0, 0, 0), (4096 + 3, 0, 0), (65536 + 17, 5, 5), (MiB - 5, 3, 11), (MiB + 1, 16, 0), (300000, 1, 2),
+                 (12345, 15, 15), (256 * 16 * 8 * 3 + 16, 0, 0), (15, 9, 2), (16, 0, 0), (4080, 8, 8)]
+        for i, (n, sa, da) in enumerate(cases):
+            me, pe = i % 3, (i + 1 + i // 3) % 3
+            src, dst = 1024 + sa, 2 * MiB + 4096 + da
+            g.launch_wg_put(me, pe, dst, src, n, n_wg)
+            o.wg_put(me, dst, src, n, pe, n_wg)
+            g.barrier_all()
+            g.launch_wg_get(pe, me, 4 * MiB + 8192 + sa, 2 * MiB + 4096 + da, n, n_wg)
+            o.wg_get(pe, 4 * MiB + 8192 + sa, 2 * MiB + 4096 + da, n, me, n_wg)
+            g.barrier_all()
+            assert_heaps_equal(g, o, upto=6 * MiB, what=f"case {i} n={n}")
+
+
+def test_self_target_and_overlap_rejected():
+    g, o = make_pair(2, MiB)
+    with g:
+        fill_random(g, o, 3)
+        g.launch_wg_put(0, 0, 8192, 100, 5000, 2)
+        o.wg_put(0, 8192, 100, 5000, 0, 2)
+        g.barrier_all()
+        assert_heaps_equal(g, o)
+        with pytest.raises(S.ShmError) as e:
+            g.launch_wg_put(0, 0, 200, 100, 5000, 2)
+        assert e.value.code == S.SHM_EINVAL
+
+
+@pytest.mark.parametrize("path", [S.SHM_PATH_LDST, S.SHM_PATH_SDMA])
+def test_team_put_get_all_paths(path):
+    g, o = make_pair(8, 4 * MiB)
+    with g:
+        fill_random(g, o, 4)
+        n = MiB + 48
+        for shift in (1, 3, 0):
+            dst = 2 * MiB - 64 if shift else MiB + 4096 + MiB // 2
+            src = 16 if shift else 0
+            if shift == 0:
+                n = MiB // 4
+            g.launch_wg_put_all(shift, dst, src, n, 16, path)
+            for p in range(8):
+                o.wg_put(p, dst, src, n, (p + shift) % 8, 16)
+            g.barrier_all()
+            assert_heaps_equal(g, o, upto=4 * MiB - 65536, what=f"put_all shift {shift}")
+        g.launch_wg_get_all(5, 0, 2 * MiB, 70000, 7, path)
+        before = [h.copy() for h in o.heap]
+        for p in range(8):
+            o.heap[p][0:70000] = before[(p + 5) % 8][2 * MiB:2 * MiB + 70000]
+        g.barrier_all()
+        assert_heaps_equal(g, o, upto=4 * MiB - 65536, what="get_all")
+
+
+def test_host_rma_sdma_single_and_auto_policy():
+    g, o = make_pair(4, 2 * MiB)
+    with g:
+        fill_random(g, o, 5)
+        g.putmem(1, MiB, 7, 30001, 3)
+        o.putmem(1, MiB, 7, 30001, 3)
+        g.quiet(1)
+        g.getmem(2, MiB + 65536, 3, 999, 0)
+        o.getmem(2, MiB + 65536, 3, 999, 0)
+        g.quiet(2)
+        g.launch_wg_put(0, 2, MiB + 200000, 11, 12345, 4, S.SHM_PATH_SDMA)
+        o.wg_put(0, MiB + 200000, 11, 12345, 2, 4)
+        g.launch_wg_get(0, 2, MiB + 300000, 64, 4096, 4, S.SHM_PATH_SDMA)
+        o.wg_get(0, MiB + 300000, 64, 4096, 2, 4)
+        g.quiet(0)
+        # AUTO: below the cutover the kernel runs, at or above it the engine; bytes are the same either way
+        g.set_cutover(4, 8192)
+        assert g.get_cutover(4) == 8192 and g.get_cutover(3) == 8192 and g.get_cutover(64) == (1 << 64) - 1
+        assert g.choose_path(8191, 4) == S.SHM_PATH_LDST and g.choose_path(8192, 4) == S.SHM_PATH_SDMA
+        for n in (100, 8191, 8192, 50000):
+            g.launch_wg_put(3, 1, MiB + 400000, 0, n, 4, S.SHM_PATH_AUTO)
+            o.wg_put(3, MiB + 400000, 0, n, 1, 4)
+        g.quiet(3)
+        assert_heaps_equal(g, o)
