@@ -116,6 +116,103 @@ __device__ __forceinline__ void shm_copy_coop(char *dst, const char *src, size_t
 }
 
 // ------------------------------------------------------------------------------------------
+// Several work-groups sharing one message.  How the bytes are dealt to groups and lanes cannot be
+// observed, so it is chosen for the memory system: on MI355X a wave sustains the highest HBM
+// write rate when its successive 1 KiB accesses lie 32 KiB apart.  Up to 8 groups of 256 threads
+// therefore form a "virtual block" whose 32 waves each own one 1 KiB column of a 32 KiB row; the
+// virtual block walks tiles of U rows (256 KiB for U = 8), lane addresses advancing one row per
+// unrolled access.  Vectors past the last whole tile are dealt 16 bytes per lane, round-robin
+// over all groups.
+// ------------------------------------------------------------------------------------------
+struct shm_deal {
+    size_t rowv;      // 16-byte vectors per row
+    size_t tilev;     // vectors per tile (U rows)
+    size_t ntiles;    // whole tiles in the message
+    size_t vb, nvb;   // this group's virtual block, number of virtual blocks
+    size_t col;       // this lane's vector within a row
+    size_t rem_first; // first vector after the whole tiles
+    size_t rem_lane;  // this lane's first remainder vector
+    size_t rem_step;  // lanes in all groups together
+};
+
+template <int U>
+__device__ __forceinline__ shm_deal shm_deal_make(size_t nvec, unsigned part, unsigned nparts, unsigned tid, unsigned nthr)
+{
+    unsigned vw = nparts & (0u - nparts);      // largest power of two dividing nparts ...
+    if (vw > 8) vw = 8;                        // ... capped at 8 groups = 32 KiB rows of 256-thread groups
+    shm_deal d;
+    d.rowv = static_cast<size_t>(vw) * nthr;
+    d.tilev = d.rowv * U;
+    d.ntiles = nvec / d.tilev;
+    d.vb = part / vw;
+    d.nvb = nparts / vw;
+    d.col = static_cast<size_t>(part % vw) * nthr + tid;
+    d.rem_first = d.ntiles * d.tilev;
+    d.rem_lane = d.rem_first + static_cast<size_t>(part) * nthr + tid;
+    d.rem_step = static_cast<size_t>(nparts) * nthr;
+    return d;
+}
+
+template <int U>
+__device__ __forceinline__ void shm_copy_body_dealt(shm_u32x4 *d, const shm_u32x4 *s, size_t nvec, unsigned part,
+                                                    unsigned nparts, unsigned tid, unsigned nthr)
+{
+    const shm_deal k = shm_deal_make<U>(nvec, part, nparts, tid, nthr);
+    for (size_t t = k.vb; t < k.ntiles; t += k.nvb) {
+        const size_t i = t * k.tilev + k.col;
+        shm_u32x4 r[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) r[u] = shm_ld16(s + i + u * k.rowv);
+#pragma unroll
+        for (int u = 0; u < U; ++u) shm_st16(d + i + u * k.rowv, r[u]);
+    }
+    for (size_t i = k.rem_lane; i < nvec; i += 4 * k.rem_step) {
+        shm_u32x4 r[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+            if (i + u * k.rem_step < nvec) r[u] = shm_ld16(s + i + u * k.rem_step);
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+            if (i + u * k.rem_step < nvec) shm_st16(d + i + u * k.rem_step, r[u]);
+    }
+}
+
+// Group `part` of `nparts` does its share of copying n bytes, any alignment.  All threads of all
+// groups call this with the same dst/src/n.
+template <int U = 8>
+__device__ __forceinline__ void shm_copy_parts(char *dst, const char *src, size_t n, unsigned part, unsigned nparts)
+{
+    if (n == 0) return;
+    const unsigned tid = threadIdx.x, nthr = blockDim.x;
+    size_t head = (16 - (reinterpret_cast<uintptr_t>(dst) & 15)) & 15;
+    if (head > n) head = n;
+    const size_t body = (n - head) & ~static_cast<size_t>(15);
+    const size_t tail = n - head - body;
+    if (part == 0) {
+        for (size_t i = tid; i < head; i += nthr) dst[i] = src[i];
+        for (size_t i = tid; i < tail; i += nthr) dst[head + body + i] = src[head + body + i];
+    }
+    if (body == 0) return;
+    shm_u32x4 *d = reinterpret_cast<shm_u32x4 *>(dst + head);
+    const char *bs = src + head;
+    const uint32_t mis = static_cast<uint32_t>(reinterpret_cast<uintptr_t>(bs) & 15);
+    const size_t nvec = body >> 4;
+    if (mis == 0) {
+        shm_copy_body_dealt<U>(d, reinterpret_cast<const shm_u32x4 *>(bs), nvec, part, nparts, tid, nthr);
+        return;
+    }
+    const shm_u32x4 *sa = reinterpret_cast<const shm_u32x4 *>(bs - mis);
+    const uint32_t sh = mis & 3;
+    const unsigned gtid = part * nthr + tid, gthr = nparts * nthr;
+    switch (mis >> 2) {
+    case 0: shm_copy_body_shifted<0>(d, sa, nvec, sh, gtid, gthr); break;
+    case 1: shm_copy_body_shifted<1>(d, sa, nvec, sh, gtid, gthr); break;
+    case 2: shm_copy_body_shifted<2>(d, sa, nvec, sh, gtid, gthr); break;
+    default: shm_copy_body_shifted<3>(d, sa, nvec, sh, gtid, gthr); break;
+    }
+}
+
+// ------------------------------------------------------------------------------------------
 // RMA.  A put returns when the source may be reused; its bytes are delivered (visible to other
 // PEs) after the caller's quiet.  A get returns with the bytes in place for the calling thread(s).
 // ------------------------------------------------------------------------------------------
@@ -144,13 +241,31 @@ __device__ __forceinline__ void shmx_getmem_wave(const shm_dev_ctx &c, int me, u
 __device__ __forceinline__ void shmx_putmem_wg(const shm_dev_ctx &c, int me, uint64_t dst_off, uint64_t src_off, size_t n, int pe)
 {
     __syncthreads();
-    shm_copy_coop<8>(shm_ptr(c, dst_off, pe), shm_ptr(c, src_off, me), n, threadIdx.x, blockDim.x);
+    shm_copy_parts<8>(shm_ptr(c, dst_off, pe), shm_ptr(c, src_off, me), n, 0, 1);
     __syncthreads();
 }
 __device__ __forceinline__ void shmx_getmem_wg(const shm_dev_ctx &c, int me, uint64_t dst_off, uint64_t src_off, size_t n, int pe)
 {
     __syncthreads();
-    shm_copy_coop<8>(shm_ptr(c, dst_off, me), shm_ptr(c, src_off, pe), n, threadIdx.x, blockDim.x);
+    shm_copy_parts<8>(shm_ptr(c, dst_off, me), shm_ptr(c, src_off, pe), n, 0, 1);
+    __syncthreads();
+}
+
+// The same for `nparts` work-groups of one PE sharing one message; this group is number `part`.
+// Every thread of every group passes the same offsets and n.  On return this group's share is
+// done; the message is complete when all groups have returned (and delivered after their quiet).
+__device__ __forceinline__ void shmx_putmem_parts(const shm_dev_ctx &c, int me, uint64_t dst_off, uint64_t src_off, size_t n,
+                                                  int pe, unsigned part, unsigned nparts)
+{
+    __syncthreads();
+    shm_copy_parts<8>(shm_ptr(c, dst_off, pe), shm_ptr(c, src_off, me), n, part, nparts);
+    __syncthreads();
+}
+__device__ __forceinline__ void shmx_getmem_parts(const shm_dev_ctx &c, int me, uint64_t dst_off, uint64_t src_off, size_t n,
+                                                  int pe, unsigned part, unsigned nparts)
+{
+    __syncthreads();
+    shm_copy_parts<8>(shm_ptr(c, dst_off, me), shm_ptr(c, src_off, pe), n, part, nparts);
     __syncthreads();
 }
 
@@ -231,27 +346,15 @@ __device__ __forceinline__ uint64_t shmx_signal_wait_until_wg(const shm_dev_ctx 
 }
 
 // Put with signal for one work-group, or for `nparts` work-groups sharing one message: group
-// `part` copies its slice; every thread releases its stores; the group whose arrival completes the
+// `part` copies its share; every thread releases its stores; the group whose arrival completes the
 // message (counted in *arrive, which it resets to zero) updates the signal.  With nparts == 1 the
 // counter is not touched and may be null.
-__device__ __forceinline__ void shm_wg_slice(size_t n, unsigned part, unsigned nparts, size_t &lo, size_t &hi)
-{
-    size_t per = (n + nparts - 1) / nparts;
-    per = (per + 15) & ~static_cast<size_t>(15);
-    lo = static_cast<size_t>(part) * per;
-    if (lo > n) lo = n;
-    hi = lo + per;
-    if (hi > n) hi = n;
-}
-
 __device__ __forceinline__ void shmx_putmem_signal_parts(const shm_dev_ctx &c, int me, uint64_t dst_off, uint64_t src_off,
                                                          size_t n, uint64_t sig_off, uint64_t sig_val, int sig_op, int pe,
                                                          uint64_t *arrive, unsigned part, unsigned nparts)
 {
-    size_t lo, hi;
-    shm_wg_slice(n, part, nparts, lo, hi);
     __syncthreads();
-    shm_copy_coop<8>(shm_ptr(c, dst_off + lo, pe), shm_ptr(c, src_off + lo, me), hi - lo, threadIdx.x, blockDim.x);
+    shm_copy_parts<8>(shm_ptr(c, dst_off, pe), shm_ptr(c, src_off, me), n, part, nparts);
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
     __syncthreads();
     if (threadIdx.x == 0) {

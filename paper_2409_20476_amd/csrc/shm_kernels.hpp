@@ -10,19 +10,17 @@ typedef float shm_f32x4 __attribute__((ext_vector_type(4)));
 
 // ---- work-group put / get, one PE or a team of PEs in one grid ----------------------------
 // PE me = me0 + blockIdx.y targets PE (me + shift) mod npes; group blockIdx.x of gridDim.x takes
-// its slice of the message.
+// its share of the message.
 __global__ __launch_bounds__(SHMK_WG) void shmk_wg_rma(shm_dev_ctx c, uint64_t dst_off, uint64_t src_off, size_t n, int me0,
                                                        int shift, int is_get)
 {
     const int me = me0 + blockIdx.y;
     int pe = me + shift;
     if (pe >= c.npes) pe -= c.npes;
-    size_t lo, hi;
-    shm_wg_slice(n, blockIdx.x, gridDim.x, lo, hi);
     if (is_get)
-        shmx_getmem_wg(c, me, dst_off + lo, src_off + lo, hi - lo, pe);
+        shmx_getmem_parts(c, me, dst_off, src_off, n, pe, blockIdx.x, gridDim.x);
     else
-        shmx_putmem_wg(c, me, dst_off + lo, src_off + lo, hi - lo, pe);
+        shmx_putmem_parts(c, me, dst_off, src_off, n, pe, blockIdx.x, gridDim.x);
 }
 
 __global__ __launch_bounds__(SHMK_WG) void shmk_wg_put_signal(shm_dev_ctx c, int me, int pe, uint64_t dst_off, uint64_t src_off,
@@ -207,30 +205,30 @@ __global__ __launch_bounds__(SHMK_WG) void shmk_amo_storm(shm_dev_ctx c, uint64_
 
 // ---- configuration 5a: fcollect, push --------------------------------------------------------
 // PE p = blockIdx.y reads its block once and stores every vector to all PEs (inner loop over
-// destinations, outer loop over addresses), starting with its right-hand neighbour.
+// destinations, outer loop over addresses), starting with its right-hand neighbour.  The block is
+// dealt to the PE's groups like a put.
 template <int U>
 __global__ __launch_bounds__(SHMK_WG) void shmk_fcollect_vec(shm_dev_ctx c, uint64_t dst_off, uint64_t src_off, size_t bytes_per_pe)
 {
     const int p = blockIdx.y, npes = c.npes;
-    size_t lo, hi;
-    shm_wg_slice(bytes_per_pe, blockIdx.x, gridDim.x, lo, hi);
-    const shm_u32x4 *s = reinterpret_cast<const shm_u32x4 *>(shm_ptr(c, src_off + lo, p));
-    const uint64_t d0 = dst_off + static_cast<uint64_t>(p) * bytes_per_pe + lo;
-    const size_t nvec = (hi - lo) >> 4;
-    size_t i = threadIdx.x;
-    for (; i + (U - 1) * SHMK_WG < nvec; i += U * SHMK_WG) {
+    const shm_u32x4 *s = reinterpret_cast<const shm_u32x4 *>(shm_ptr(c, src_off, p));
+    const uint64_t d0 = dst_off + static_cast<uint64_t>(p) * bytes_per_pe;
+    const size_t nvec = bytes_per_pe >> 4;
+    const shm_deal k = shm_deal_make<U>(nvec, blockIdx.x, gridDim.x, threadIdx.x, SHMK_WG);
+    for (size_t t = k.vb; t < k.ntiles; t += k.nvb) {
+        const size_t i = t * k.tilev + k.col;
         shm_u32x4 r[U];
 #pragma unroll
-        for (int u = 0; u < U; ++u) r[u] = shm_ld16(s + i + u * SHMK_WG);
+        for (int u = 0; u < U; ++u) r[u] = shm_ld16(s + i + u * k.rowv);
         for (int j = 0; j < npes; ++j) {
             int q = p + 1 + j;
             if (q >= npes) q -= npes;
             shm_u32x4 *d = reinterpret_cast<shm_u32x4 *>(shm_ptr(c, d0, q));
 #pragma unroll
-            for (int u = 0; u < U; ++u) shm_st16(d + i + u * SHMK_WG, r[u]);
+            for (int u = 0; u < U; ++u) shm_st16(d + i + u * k.rowv, r[u]);
         }
     }
-    for (; i < nvec; i += SHMK_WG) {
+    for (size_t i = k.rem_lane; i < nvec; i += k.rem_step) {
         const shm_u32x4 r = shm_ld16(s + i);
         for (int j = 0; j < npes; ++j) {
             int q = p + 1 + j;
@@ -240,16 +238,14 @@ __global__ __launch_bounds__(SHMK_WG) void shmk_fcollect_vec(shm_dev_ctx c, uint
     }
 }
 
-// Any alignment or length: one work-group put per destination.
+// Any alignment or length: one multi-group put per destination.
 __global__ __launch_bounds__(SHMK_WG) void shmk_fcollect_any(shm_dev_ctx c, uint64_t dst_off, uint64_t src_off, size_t bytes_per_pe)
 {
     const int p = blockIdx.y, npes = c.npes;
-    size_t lo, hi;
-    shm_wg_slice(bytes_per_pe, blockIdx.x, gridDim.x, lo, hi);
     for (int j = 0; j < npes; ++j) {
         int q = p + 1 + j;
         if (q >= npes) q -= npes;
-        shmx_putmem_wg(c, p, dst_off + static_cast<uint64_t>(p) * bytes_per_pe + lo, src_off + lo, hi - lo, q);
+        shmx_putmem_parts(c, p, dst_off + static_cast<uint64_t>(p) * bytes_per_pe, src_off, bytes_per_pe, q, blockIdx.x, gridDim.x);
     }
 }
 
@@ -260,6 +256,7 @@ __global__ __launch_bounds__(SHMK_WG) void shmk_fcollect_any(shm_dev_ctx c, uint
 template <bool SPLIT>
 __global__ __launch_bounds__(SHMK_WG) void shmk_reduce_sum_f32_vec(shm_dev_ctx c, uint64_t dst_off, uint64_t src_off, size_t nvec)
 {
+    constexpr int U = 2;
     const int q = blockIdx.y, npes = c.npes;
     size_t first = 0, count = nvec;
     if (SPLIT) {
@@ -267,21 +264,43 @@ __global__ __launch_bounds__(SHMK_WG) void shmk_reduce_sum_f32_vec(shm_dev_ctx c
         first = min(nvec, q * share);
         count = min(nvec, first + share) - first;
     }
-    const size_t per = (count + gridDim.x - 1) / gridDim.x;
-    const size_t lo = first + min(count, blockIdx.x * per), hi = min(first + count, lo + per);
-    for (size_t i = lo + threadIdx.x; i < hi; i += SHMK_WG) {
-        const shm_f32x4 *s0 = reinterpret_cast<const shm_f32x4 *>(shm_ptr(c, src_off, 0));
-        shm_f32x4 r = __builtin_nontemporal_load(s0 + i);
+    const uint64_t so = src_off + 16 * first, dof = dst_off + 16 * first;
+    const shm_deal k = shm_deal_make<U>(count, blockIdx.x, gridDim.x, threadIdx.x, SHMK_WG);
+    auto emit = [&](size_t i, shm_f32x4 r) {
+        if (SPLIT) {
+            for (int t = 0; t < npes; ++t) {
+                int w = q + t;                      // own copy first, then the others in ring order
+                if (w >= npes) w -= npes;
+                __builtin_nontemporal_store(r, reinterpret_cast<shm_f32x4 *>(shm_ptr(c, dof, w)) + i);
+            }
+        } else {
+            __builtin_nontemporal_store(r, reinterpret_cast<shm_f32x4 *>(shm_ptr(c, dof, q)) + i);
+        }
+    };
+    for (size_t t = k.vb; t < k.ntiles; t += k.nvb) {
+        const size_t i = t * k.tilev + k.col;
+        shm_f32x4 r[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+            r[u] = __builtin_nontemporal_load(reinterpret_cast<const shm_f32x4 *>(shm_ptr(c, so, 0)) + i + u * k.rowv);
         for (int p = 1; p < npes; ++p) {
-            const shm_f32x4 v = __builtin_nontemporal_load(reinterpret_cast<const shm_f32x4 *>(shm_ptr(c, src_off, p)) + i);
+            const shm_f32x4 *sp = reinterpret_cast<const shm_f32x4 *>(shm_ptr(c, so, p));
+            shm_f32x4 v[U];
+#pragma unroll
+            for (int u = 0; u < U; ++u) v[u] = __builtin_nontemporal_load(sp + i + u * k.rowv);
+#pragma unroll
+            for (int u = 0; u < U; ++u) r[u].x += v[u].x, r[u].y += v[u].y, r[u].z += v[u].z, r[u].w += v[u].w;
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) emit(i + u * k.rowv, r[u]);
+    }
+    for (size_t i = k.rem_lane; i < count; i += k.rem_step) {
+        shm_f32x4 r = __builtin_nontemporal_load(reinterpret_cast<const shm_f32x4 *>(shm_ptr(c, so, 0)) + i);
+        for (int p = 1; p < npes; ++p) {
+            const shm_f32x4 v = __builtin_nontemporal_load(reinterpret_cast<const shm_f32x4 *>(shm_ptr(c, so, p)) + i);
             r.x += v.x, r.y += v.y, r.z += v.z, r.w += v.w;
         }
-        if (SPLIT) {
-            for (int t = 0; t < npes; ++t)
-                __builtin_nontemporal_store(r, reinterpret_cast<shm_f32x4 *>(shm_ptr(c, dst_off, t)) + i);
-        } else {
-            __builtin_nontemporal_store(r, reinterpret_cast<shm_f32x4 *>(shm_ptr(c, dst_off, q)) + i);
-        }
+        emit(i, r);
     }
 }
 

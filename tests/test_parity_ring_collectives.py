@@ -1,0 +1,147 @@
+"""GPU parity: pipelined ring (configuration 3), fcollect and float32 sum-reduce (configuration 5)."""
+import numpy as np
+import pytest
+
+from paper_2409_20476_amd import shm as S, synth
+from parity_util import assert_heaps_equal, fill_random, make_pair, write_both
+
+pytestmark = pytest.mark.gpu
+
+MiB = 1 << 20
+GiB = 1 << 30
+
+
+def _ring_case(npes, n_chunks, chunk_elems, n_prod, n_cons, heap, reps=1):
+    g, o = make_pair(npes, heap)
+    with g:
+        cb = 2 * chunk_elems
+        src, slot, acc, sig = g.malloc(cb * n_chunks), g.malloc(cb * n_chunks), g.malloc(4 * chunk_elems), g.calloc(8, 8)
+        for p in range(npes):
+            chunks = synth.c3_chunks(p, n_chunks, chunk_elems)
+            write_both(g, o, p, src, chunks)
+            write_both(g, o, p, slot, np.full(cb * n_chunks, 0xEE, np.uint8))     # stale landing slots
+            write_both(g, o, p, acc, np.full(4 * chunk_elems, 0x7F, np.uint8))
+        for rep in range(reps):
+            for p in range(npes):
+                write_both(g, o, p, sig, np.zeros(8, np.uint8))
+            g.launch_ring_pipeline(src, slot, sig, acc, cb, n_chunks, n_prod, n_cons)
+            g.barrier_all()
+            o.ring_pipeline(src, slot, sig, acc, cb, n_chunks, n_prod)
+            for p in range(npes):
+                assert g.read(p, sig, 8, np.uint64)[0] == n_chunks
+                assert np.array_equal(g.read(p, slot, cb * n_chunks), o.read(p, slot, cb * n_chunks)), f"slots of PE {p}"
+                got, want = g.read(p, acc, 4 * chunk_elems, np.uint32), o.read(p, acc, 4 * chunk_elems, np.uint32)
+                assert np.array_equal(got, want), f"accumulator of PE {p} (rep {rep})"
+            # next repetition sends different data through the same (now stale) slots
+            for p in range(npes):
+                chunks = synth.c3_chunks(p + 100 * (rep + 1), n_chunks, chunk_elems)
+                write_both(g, o, p, src, chunks)
+
+
+@pytest.mark.parametrize("npes,n_chunks,chunk_elems,n_prod,n_cons", [
+    (2, 3, 8, 1, 1), (3, 5, 2048 + 8, 2, 3), (8, 16, 16384, 4, 4), (4, 7, 8 * 2048 * 3 + 8 * 5, 3, 4), (1, 4, 4096, 2, 2)])
+def test_ring_small(npes, n_chunks, chunk_elems, n_prod, n_cons):
+    _ring_case(npes, n_chunks, chunk_elems, n_prod, n_cons, 8 * MiB, reps=3)
+
+
+@pytest.mark.timeout(600)
+def test_config3_full_size():
+    """8 PEs, 64 chunks of 1 MiB bf16 each, in the launch shape the benchmark times."""
+    _ring_case(8, 64, 524288, 32, 32, 256 * MiB, reps=2)
+
+
+def test_ring_rejects_grids_that_cannot_be_resident():
+    g, o = make_pair(8, 8 * MiB)
+    with g:
+        with pytest.raises(S.ShmError) as e:
+            g.launch_ring_pipeline(0, MiB, 4 * MiB, 2 * MiB, 65536, 4, 4096, 4096)
+        assert e.value.code == S.SHM_EINVAL
+        with pytest.raises(S.ShmError):
+            g.launch_ring_pipeline(0, 2 * MiB, 6 * MiB, 5 * MiB, 1 << 20, 2, 1, 1)     # consumer share too big for registers
+
+
+@pytest.mark.parametrize("path", [S.SHM_PATH_LDST, S.SHM_PATH_SDMA])
+@pytest.mark.parametrize("npes,n,n_wg,soff,doff", [(8, 4096 * 17 + 16, 8, 0, 0), (3, 1000, 2, 3, 5), (8, 300016, 64, 0, 0),
+                                                  (5, 7, 1, 1, 2), (2, 0, 4, 0, 0), (4, 262144 * 3 + 48, 16, 0, 0)])
+def test_fcollect(path, npes, n, n_wg, soff, doff):
+    g, o = make_pair(npes, 16 * MiB)
+    with g:
+        fill_random(g, o, 21, upto=12 * MiB)
+        src, dst = 256 + soff, 2 * MiB + doff
+        g.launch_fcollect(dst, src, n, n_wg, path)
+        g.barrier_all()
+        o.fcollect(dst, src, n)
+        assert_heaps_equal(g, o, upto=12 * MiB)
+
+
+@pytest.mark.parametrize("algo", [S.SHM_REDUCE_DUPLICATE, S.SHM_REDUCE_SPLIT])
+@pytest.mark.parametrize("npes,nelems,n_wg,soff,doff", [(8, 4096 * 5 + 3, 8, 0, 0), (3, 1001, 2, 4, 8), (8, 65536 * 9 + 4, 64, 0, 0),
+                                                       (1, 777, 3, 0, 0), (5, 2, 1, 0, 0), (4, 131072 * 3 + 1, 16, 16, 32)])
+def test_reduce_sum_f32(algo, npes, nelems, n_wg, soff, doff):
+    g, o = make_pair(npes, 16 * MiB)
+    with g:
+        fill_random(g, o, 22, upto=12 * MiB)
+        src, dst = 1024 + soff, 6 * MiB + doff
+        for p in range(npes):
+            write_both(g, o, p, src, synth.c5_reduce_source(p, nelems))
+        g.launch_reduce_sum_f32(dst, src, nelems, n_wg, algo)
+        g.barrier_all()
+        r = o.reduce_sum_f32(dst, src, nelems)
+        assert_heaps_equal(g, o, upto=12 * MiB)                       # bit-exact, every PE, canaries intact
+        got = g.read(npes - 1, dst, 4 * nelems, np.float32).astype(np.float64)
+        assert (np.abs(got - r["f64"]) <= 1e-6 * r["abs"]).all()      # and within the stated tolerance of the exact sum
+
+
+@pytest.mark.timeout(900)
+def test_config5_full_size():
+    """8 PEs: fcollect of 64 MiB int32 per PE into 512 MiB, and a 16M-element float32 sum-reduce."""
+    npes, nel = 8, 16 * MiB
+    g, o = make_pair(npes, GiB)
+    with g:
+        fsrc, fdst = g.malloc(4 * nel), g.malloc(4 * nel * npes)
+        rsrc, rdst = g.malloc(4 * nel), g.malloc(4 * nel)
+        for p in range(npes):
+            write_both(g, o, p, fsrc, synth.c5_fcollect_source(p, nel))
+            write_both(g, o, p, rsrc, synth.c5_reduce_source(p, nel))
+        g.launch_fcollect(fdst, fsrc, 4 * nel, 1024, S.SHM_PATH_LDST)
+        g.barrier_all()
+        o.fcollect(fdst, fsrc, 4 * nel)
+        for q in range(npes):
+            assert np.array_equal(g.read(q, fdst, 4 * nel * npes), o.heap[q][fdst:fdst + 4 * nel * npes]), f"fcollect on PE {q}"
+        r = None
+        for algo in (S.SHM_REDUCE_DUPLICATE, S.SHM_REDUCE_SPLIT):
+            for q in range(npes):
+                g.write(q, rdst, np.zeros(16, np.uint8))
+            g.launch_reduce_sum_f32(rdst, rsrc, nel, 1024, algo)
+            g.barrier_all()
+            r = r or o.reduce_sum_f32(rdst, rsrc, nel)
+            for q in range(npes):
+                got = g.read(q, rdst, 4 * nel, np.uint32)
+                assert np.array_equal(got, r["f32"].view(np.uint32)), f"reduce algo {algo} on PE {q}"
+            got = g.read(0, rdst, 4 * nel, np.float32).astype(np.float64)
+            assert (np.abs(got - r["f64"]) <= 1e-6 * r["abs"]).all()
+
+
+@pytest.mark.timeout(900)
+def test_config2_full_size_team_put():
+    """8 PEs x 256 MiB float32, 1024 work-groups each, to PE (p+1) mod 8 -- the benchmark's launch."""
+    npes, n = 8, 256 * MiB
+    g, o = make_pair(npes, GiB)
+    with g:
+        src, dst = g.malloc(n), g.malloc(n)
+        data = [synth.c2_source(p, n) for p in range(npes)]
+        for p in range(npes):
+            g.write(p, src, data[p])
+            g.write(p, dst, np.zeros(4096, np.uint8))
+        g.launch_wg_put_all(1, dst, src, n, 1024, S.SHM_PATH_LDST)
+        g.barrier_all()
+        for p in range(npes):
+            assert np.array_equal(g.read((p + 1) % npes, dst, n), data[p]), f"put of PE {p}"
+        # per-PE streams, copy-engine path, smaller message with a ragged tail
+        m = 64 * MiB + 1000
+        for p in range(npes):
+            g.launch_wg_put(p, (p + 3) % npes, dst, src, m, 1024, S.SHM_PATH_SDMA)
+        g.barrier_all()
+        for p in range(npes):
+            got = g.read((p + 3) % npes, dst, n)
+            assert np.array_equal(got[:m], data[p][:m]) and np.array_equal(got[m:], data[(p + 2) % npes][m:])

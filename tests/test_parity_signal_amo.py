@@ -1,0 +1,144 @@
+"""GPU parity: put-with-signal, signal_wait_until, bounded waits, 64-bit atomics and the atomic storm."""
+import numpy as np
+import pytest
+import torch
+
+from oracle.shmem_oracle import SIGNAL_ADD, SIGNAL_SET
+from paper_2409_20476_amd import shm as S, synth
+from parity_util import assert_heaps_equal, fill_random, make_pair, write_both
+
+pytestmark = pytest.mark.gpu
+
+MiB = 1 << 20
+
+
+@pytest.mark.parametrize("n_wg", [1, 2, 5, 64])
+def test_put_signal_then_wait_sees_data(n_wg):
+    g, o = make_pair(4, 4 * MiB)
+    with g:
+        fill_random(g, o, 11)
+        sig = 3 * MiB
+        for p in range(4):
+            write_both(g, o, p, sig, np.zeros(16, np.uint8))
+        out = torch.zeros(4, dtype=torch.int64, device="cuda")
+        cases = [(0, 1, 100003, SIGNAL_SET, 7, S.SHM_CMP_EQ, 7), (2, 1, 0, SIGNAL_ADD, 5, S.SHM_CMP_GE, 12),
+                 (3, 0, MiB + 16, SIGNAL_ADD, (1 << 64) - 1, S.SHM_CMP_NE, 0), (1, 1, 4096, SIGNAL_SET, 1 << 63, S.SHM_CMP_GT, 1)]
+        for i, (me, pe, n, op, val, cmp, cval) in enumerate(cases):
+            dst, src = MiB + MiB // 2 + 8 * i, 24 + i
+            g.launch_wg_put_signal(me, pe, dst, src, n, sig, val, op, n_wg)      # producer first: it never waits
+            g.launch_signal_wait_until(pe, sig, cmp, cval, out[i:i + 1])
+            # the waiter's stream then copies the payload onward: after the wait it must already be there
+            if 0 < n <= 200000:
+                g.launch_wg_put(pe, (pe + 1) % 4, 2 * MiB + MiB // 2, dst, n, 1)
+            g.barrier_all()
+            o.put_signal(me, dst, src, n, sig, val, op, pe, n_wg)
+            want = o.signal_wait_until(pe, sig, cmp, cval)
+            if 0 < n <= 200000:
+                o.wg_put(pe, 2 * MiB + MiB // 2, dst, n, (pe + 1) % 4, 1)
+            assert int(out[i].item()) & ((1 << 64) - 1) == want
+            assert_heaps_equal(g, o, what=f"case {i}")
+
+
+def test_wait_before_signal_on_other_stream_and_timeout_is_reported():
+    g, o = make_pair(2, MiB)
+    with g:
+        fill_random(g, o, 12)
+        write_both(g, o, 1, 4096, np.zeros(8, np.uint8))
+        # a wait nobody satisfies: bounded, reported by the next quiet, and the context stays usable
+        g.set_wait_timeout_us(2000)
+        g.launch_signal_wait_until(1, 4096, S.SHM_CMP_EQ, 99)
+        with pytest.raises(S.ShmError) as e:
+            g.quiet(1)
+        assert e.value.code == S.SHM_ETIMEOUT
+        g.quiet(1)                              # status was cleared
+        g.set_wait_timeout_us(2_000_000)
+        g.launch_wg_put_signal(0, 1, 8192, 0, 1000, 4096, 99, SIGNAL_SET, 1)
+        g.launch_signal_wait_until(1, 4096, S.SHM_CMP_EQ, 99)
+        g.barrier_all()
+        o.put_signal(0, 8192, 0, 1000, 4096, 99, SIGNAL_SET, 1)
+        assert_heaps_equal(g, o)
+
+
+def test_every_atomic_matches_the_oracle():
+    g, o = make_pair(3, MiB)
+    with g:
+        fill_random(g, o, 13, upto=8192)
+        out = torch.zeros(1, dtype=torch.int64, device="cuda")
+        I64_MAX = 2 ** 63 - 1
+        ops = [(S.SHM_AMO_SET, 64, 5, 0, 2), (S.SHM_AMO_FETCH, 64, 0, 0, 2), (S.SHM_AMO_FETCH_ADD, 64, -9, 0, 2),
+               (S.SHM_AMO_ADD, 64, 100, 0, 2), (S.SHM_AMO_FETCH_INC, 64, 0, 0, 2), (S.SHM_AMO_INC, 64, 0, 0, 2),
+               (S.SHM_AMO_SWAP, 64, I64_MAX, 0, 2), (S.SHM_AMO_FETCH_ADD, 64, 1, 0, 2), (S.SHM_AMO_FETCH, 64, 0, 0, 2),
+               (S.SHM_AMO_COMPARE_SWAP, 64, 77, -2 ** 63, 2), (S.SHM_AMO_COMPARE_SWAP, 64, 78, 5, 2),
+               (S.SHM_AMO_FETCH, 64, 0, 0, 2), (S.SHM_AMO_FETCH_ADD, 8, 3, 0, 0), (S.SHM_AMO_COMPARE_SWAP, 8, -1, 12345, 1)]
+        names = {S.SHM_AMO_SET: "atomic_set", S.SHM_AMO_FETCH: "atomic_fetch", S.SHM_AMO_FETCH_ADD: "atomic_fetch_add",
+                 S.SHM_AMO_ADD: "atomic_add", S.SHM_AMO_FETCH_INC: "atomic_fetch_inc", S.SHM_AMO_INC: "atomic_inc",
+                 S.SHM_AMO_SWAP: "atomic_swap", S.SHM_AMO_COMPARE_SWAP: "atomic_compare_swap"}
+        for i, (op, off, operand, cond, pe) in enumerate(ops):
+            me = i % 3
+            out.fill_(-12345)
+            torch.cuda.synchronize()
+            g.launch_amo(me, pe, off, op, operand, cond, out)
+            g.quiet(me)
+            fn = getattr(o, names[op])
+            if op in (S.SHM_AMO_FETCH, S.SHM_AMO_FETCH_INC):
+                want = fn(me, off, pe)
+            elif op == S.SHM_AMO_INC:
+                want = fn(me, off, pe)
+            elif op == S.SHM_AMO_COMPARE_SWAP:
+                want = fn(me, off, cond, operand, pe)
+            else:
+                want = fn(me, off, operand, pe)
+            if want is not None:
+                assert int(out.item()) == want, (i, op)
+            assert_heaps_equal(g, o, upto=8192, what=f"amo {i}")
+        with pytest.raises(S.ShmError):
+            g.launch_amo(0, 1, 12, S.SHM_AMO_FETCH)       # misaligned target
+
+
+def _check_storm(g, o, npes, n_ctr, n_items, ops, kind, ctr_off):
+    targets = synth.c4_targets(n_items, ops, npes, n_ctr)
+    t_dev = torch.from_numpy(targets.view(np.int16)).cuda()
+    fetched = torch.empty(n_items * ops, dtype=torch.int64, device="cuda")
+    n_groups = (n_items + 255) // 256
+    checksum = torch.zeros(n_groups, dtype=torch.int64, device="cuda")
+    g.launch_amo_storm(ctr_off, n_ctr, t_dev, n_items, ops, kind, fetched, checksum)
+    g.barrier_all()
+    init = np.concatenate([o.read(p, ctr_off, 8 * n_ctr, np.int64) for p in range(npes)])
+    o.amo_storm(ctr_off, n_ctr, targets)           # final counters; its fetched values are one witness only
+    for p in range(npes):
+        assert np.array_equal(g.read(p, ctr_off, 8 * n_ctr, np.int64), o.read(p, ctr_off, 8 * n_ctr, np.int64)), f"counters of PE {p}"
+    if kind == S.SHM_STORM_ADD:
+        return
+    flat = targets.reshape(-1).astype(np.int64)
+    got = fetched.cpu().numpy() - init[flat]
+    counts = np.bincount(flat, minlength=npes * n_ctr)
+    assert got.min() >= 0 and (got < counts[flat]).all(), "a fetched value outside 0..n-1"
+    start = np.concatenate([[0], np.cumsum(counts)[:-1]])
+    hits = np.bincount(start[flat] + got, minlength=flat.size)
+    assert (hits == 1).all(), "fetched values of a counter are not a permutation of 0..n-1"
+    # per-group checksums equal the sum of what the group's items fetched (mod 2^64)
+    per_item = fetched.cpu().numpy().reshape(n_items, ops).sum(axis=1)
+    pad = np.zeros(n_groups * 256, dtype=np.int64)
+    pad[:n_items] = per_item
+    assert np.array_equal(checksum.cpu().numpy(), pad.reshape(n_groups, 256).sum(axis=1))
+
+
+@pytest.mark.parametrize("kind", [S.SHM_STORM_FETCH_ADD, S.SHM_STORM_ADD, S.SHM_STORM_CSWAP_LOOP])
+@pytest.mark.parametrize("npes,n_ctr,n_items,ops", [(2, 4, 1000, 10), (16, 1024, 1 << 14, 64), (3, 7, 300, 3)])
+def test_storm_small(kind, npes, n_ctr, n_items, ops):
+    g, o = make_pair(npes, MiB)
+    with g:
+        rng = np.random.default_rng(5)
+        for p in range(npes):
+            write_both(g, o, p, 512, rng.integers(-3, 3, n_ctr, dtype=np.int64))
+        _check_storm(g, o, npes, n_ctr, n_items, ops, kind, 512)
+
+
+@pytest.mark.timeout(900)
+def test_config4_full_size():
+    """16 PEs x 1024 counters, 2^20 work-items x 64 fetch-adds."""
+    g, o = make_pair(16, MiB)
+    with g:
+        for p in range(16):
+            write_both(g, o, p, 0, np.zeros(1024, np.int64))
+        _check_storm(g, o, 16, 1024, 1 << 20, 64, S.SHM_STORM_FETCH_ADD, 0)
