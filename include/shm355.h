@@ -46,7 +46,7 @@ extern "C" {
 enum { SHM_OK = 0, SHM_EINVAL = -1, SHM_EPE = -2, SHM_ERANGE = -3, SHM_ENOMEM = -4,
        SHM_EHIP = -5, SHM_ETIMEOUT = -6, SHM_ENODEV = -7 };
 
-enum { SHM_PATH_AUTO = 0, SHM_PATH_LDST = 1, SHM_PATH_SDMA = 2 };
+enum { SHM_PATH_AUTO = 0, SHM_PATH_LDST = 1, SHM_PATH_SDMA = 2, SHM_PATH_MEMCPY = 3 };
 enum { SHM_SIGNAL_SET = 0, SHM_SIGNAL_ADD = 1 };
 enum { SHM_CMP_EQ = 0, SHM_CMP_NE = 1, SHM_CMP_GT = 2, SHM_CMP_GE = 3, SHM_CMP_LT = 4, SHM_CMP_LE = 5 };
 enum { SHM_INIT_DEFAULT = 0, SHM_INIT_NO_DEVICE = 1 };
@@ -101,14 +101,15 @@ int shm_read(shm_ctx *ctx, int pe, uint64_t off, void *host, size_t n);
  *      non-blocking transfers) ----------------------------------------------------------------- */
 
 /* PE `me` copies n bytes from its offset src_off to offset dst_off of PE `pe` (put), or from PE
- * `pe`'s src_off to its own dst_off (get), with the copy engine path (hipMemcpyAsync on me's
- * stream).  Overlapping ranges on one PE are SHM_EINVAL. */
+ * `pe`'s src_off to its own dst_off (get), with hipMemcpyAsync in order on me's stream.
+ * Overlapping ranges on one PE are SHM_EINVAL. */
 int shm_putmem(shm_ctx *ctx, int me, uint64_t dst_off, uint64_t src_off, size_t n, int pe);
 int shm_getmem(shm_ctx *ctx, int me, uint64_t dst_off, uint64_t src_off, size_t n, int pe);
 
-/* quiet: all of PE me's outstanding operations are complete and visible (host wait on its stream).
- * fence: orders me's earlier operations before its later ones per target; streams are in-order, so
- * this only validates.  barrier_all: quiet for every PE.  All three report an expired device wait. */
+/* quiet: all of PE me's outstanding operations are complete and visible (host wait on its stream
+ * and on its copy-engine transfers).  fence: orders me's earlier operations before its later ones;
+ * the stream is in-order, so only engine transfers need waiting for.  barrier_all: quiet for every
+ * PE.  All three report an expired device wait. */
 int shm_quiet(shm_ctx *ctx, int me);
 int shm_fence(shm_ctx *ctx, int me);
 int shm_barrier_all(shm_ctx *ctx);
@@ -116,7 +117,12 @@ int shm_barrier_all(shm_ctx *ctx);
 /* ---- policy (paper section "Performance Evaluation": the cutover between stores from kernel
  *      threads and the copy engine depends on message size and on the number of active work-items) */
 
-/* With SHM_PATH_AUTO a transfer of n bytes by n_wg work-groups uses the copy engine iff
+/* Transfer paths.  LDST: loads/stores from kernel threads.  SDMA: the GPU's copy engines (driven
+ * through the HSA runtime; the host first waits for the calling PE's stream, the transfer then runs
+ * asynchronously, like a non-blocking put, until that PE's quiet/fence/barrier or next launch).
+ * MEMCPY: hipMemcpyAsync in stream order -- on one device the runtime executes it as a copy kernel
+ * of its own, not on an engine; kept as a reference curve.
+ * With SHM_PATH_AUTO a transfer of n bytes by n_wg work-groups uses SDMA iff
  * n >= cutover(class of n_wg); classes are n_wg <= 1, <= 4, <= 64, > 64.  SIZE_MAX = never. */
 int shm_set_cutover(shm_ctx *ctx, int n_wg, size_t bytes);
 int shm_get_cutover(const shm_ctx *ctx, int n_wg, size_t *bytes);
@@ -133,15 +139,15 @@ int shm_set_team_sync(shm_ctx *ctx, int on);
 
 /* Work-group put/get (paper section "Proposed Device APIs", the work_group extensions; section
  * "Remote Memory Access": multi-threaded vectorised copy).  n_wg work-groups of SHM_WG_SIZE
- * threads share the message: group g takes bytes [g*s, min(n,(g+1)*s)) with s = ceil(n/n_wg)
- * rounded up to 16.  path: LDST = kernel on me's stream, SDMA = hipMemcpyAsync on me's stream,
- * AUTO = by cutover.  Any byte alignment; n may be 0. */
+ * threads share the message; which bytes a group moves is not observable and is chosen for the
+ * memory system (see shm_device.hpp).  path: LDST = kernel on me's stream, SDMA = copy engine, MEMCPY = runtime copy
+ * on me's stream, AUTO = LDST or SDMA by cutover.  Any byte alignment; n may be 0. */
 int shm_launch_wg_put(shm_ctx *ctx, int me, int pe, uint64_t dst_off, uint64_t src_off, size_t n, int n_wg, int path);
 int shm_launch_wg_get(shm_ctx *ctx, int me, int pe, uint64_t dst_off, uint64_t src_off, size_t n, int n_wg, int path);
 
 /* Team form: every PE p does the same put/get towards PE (p + pe_shift) mod npes, each with n_wg
- * work-groups, as ONE grid of npes*n_wg groups on the team stream (LDST) or as npes engine copies
- * on the PEs' own streams (SDMA). */
+ * work-groups, as ONE grid of npes*n_wg groups on the team stream (LDST) or as npes copies, one
+ * per PE, on the engines (SDMA) or the PEs' own streams (MEMCPY). */
 int shm_launch_wg_put_all(shm_ctx *ctx, int pe_shift, uint64_t dst_off, uint64_t src_off, size_t n, int n_wg, int path);
 int shm_launch_wg_get_all(shm_ctx *ctx, int pe_shift, uint64_t dst_off, uint64_t src_off, size_t n, int n_wg, int path);
 
@@ -191,8 +197,8 @@ int shm_launch_amo_storm(shm_ctx *ctx, uint64_t ctr_off, int n_ctr, const uint16
 
 /* Benchmark configuration 5a: fcollect (paper section "Collective Operations": push, inner loop
  * over destinations).  Every PE q receives at dst_off + p*bytes_per_pe the block at src_off of
- * every PE p.  LDST: one grid, each source vector loaded once and stored to all PEs.  SDMA:
- * npes*npes engine copies.  AUTO uses the cutover of n_wg on bytes_per_pe. */
+ * every PE p.  LDST: one grid, each source vector loaded once and stored to all PEs.  SDMA /
+ * MEMCPY: npes*npes copies.  AUTO uses the cutover of n_wg on bytes_per_pe. */
 int shm_launch_fcollect(shm_ctx *ctx, uint64_t dst_off, uint64_t src_off, size_t bytes_per_pe, int n_wg, int path);
 
 /* Benchmark configuration 5b: float32 sum over PEs, operand order PE 0, 1, ..., npes-1 for every

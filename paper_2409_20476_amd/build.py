@@ -20,7 +20,7 @@ def build(verbose: bool = False) -> str:
     """Always compiles; returns the path of the shared library."""
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
     cmd = [hipcc, *HIPCC_FLAGS, "-I", os.path.join(REPO_DIR, "include"), "-I", os.path.join(PKG_DIR, "csrc"),
-           *SOURCES, "-o", LIB_PATH]
+           *SOURCES, "-o", LIB_PATH, "-L/opt/rocm/lib", "-lhsa-runtime64"]
     if verbose:
         print(" ".join(cmd), flush=True)
     proc = subprocess.run(cmd, capture_output=True, text=True)

@@ -10,6 +10,7 @@
 #include <new>
 #include <string>
 
+#include "shm_engine.hpp"
 #include "shm_heap.hpp"
 #include "shm_kernels.hpp"
 
@@ -52,6 +53,8 @@ struct shm_ctx {
     int num_cu = 0;
     uint32_t next_slot[SHM_MAX_PES] = {};
     shm_heap_allocator alloc;
+    shm_copy_engines engines;     // SDMA engines through HSA; unused by a no-device context
+    std::string engine_err;       // why the engines are unavailable, if they are
 };
 
 namespace {
@@ -109,7 +112,7 @@ int resolve_path(const shm_ctx *c, int path, size_t n, int n_wg, int *out)
 {
     if (path == SHM_PATH_AUTO)
         *out = (n >= c->cutover[wg_class(n_wg)]) ? SHM_PATH_SDMA : SHM_PATH_LDST;
-    else if (path == SHM_PATH_LDST || path == SHM_PATH_SDMA)
+    else if (path == SHM_PATH_LDST || path == SHM_PATH_SDMA || path == SHM_PATH_MEMCPY)
         *out = path;
     else
         return fail(SHM_EINVAL, "unknown path %d", path);
@@ -170,11 +173,49 @@ int rma_args(const shm_ctx *c, int me, int pe, uint64_t dst_off, uint64_t src_of
     return SHM_OK;
 }
 
-int engine_copy(shm_ctx *c, int on_pe, int dst_pe, uint64_t dst_off, int src_pe, uint64_t src_off, size_t n)
+// Wait for the copy-engine transfers PE `pe` has in flight, so that whatever is enqueued next on
+// its stream finds them done.
+int drain_engines(shm_ctx *c, int pe)
+{
+    if (!c->engines.ready() || !c->engines.busy(pe)) return SHM_OK;
+    std::string err;
+    if (!c->engines.drain(pe, err)) return fail(SHM_EHIP, "%s", err.c_str());
+    return SHM_OK;
+}
+
+int drain_all_engines(shm_ctx *c)
+{
+    for (int p = 0; p < c->npes; ++p)
+        if (int r = drain_engines(c, p)) return r;
+    return SHM_OK;
+}
+
+// Runtime copy: hipMemcpyAsync in stream order on PE `on_pe`'s stream.
+int memcpy_copy(shm_ctx *c, int on_pe, int dst_pe, uint64_t dst_off, int src_pe, uint64_t src_off, size_t n)
 {
     if (n == 0) return SHM_OK;
+    if (int r = drain_engines(c, on_pe)) return r;
     HIP_TRY(hipMemcpyAsync(shm_ptr(c, dst_off, dst_pe), shm_ptr(c, src_off, src_pe), n, hipMemcpyDeviceToDevice, c->stream[on_pe]));
     return SHM_OK;
+}
+
+// Copy engine: the host waits until PE `on_pe`'s stream is idle (the engines are not part of the
+// stream), then starts the SDMA transfer; it runs asynchronously until that PE's quiet.
+int sdma_copy(shm_ctx *c, int on_pe, int dst_pe, uint64_t dst_off, int src_pe, uint64_t src_off, size_t n)
+{
+    if (!c->engines.ready()) return fail(SHM_EHIP, "copy engines unavailable: %s", c->engine_err.c_str());
+    if (n == 0) return SHM_OK;
+    HIP_TRY(hipStreamSynchronize(c->stream[on_pe]));
+    std::string err;
+    if (!c->engines.submit(shm_ptr(c, dst_off, dst_pe), shm_ptr(c, src_off, src_pe), n, on_pe, c->npes, err))
+        return fail(SHM_EHIP, "%s", err.c_str());
+    return SHM_OK;
+}
+
+int transfer_copy(shm_ctx *c, int path, int on_pe, int dst_pe, uint64_t dst_off, int src_pe, uint64_t src_off, size_t n)
+{
+    return path == SHM_PATH_SDMA ? sdma_copy(c, on_pe, dst_pe, dst_off, src_pe, src_off, n)
+                                 : memcpy_copy(c, on_pe, dst_pe, dst_off, src_pe, src_off, n);
 }
 
 int wg_rma(shm_ctx *c, int me, int pe, uint64_t dst_off, uint64_t src_off, size_t n, int n_wg, int path, int is_get)
@@ -185,8 +226,9 @@ int wg_rma(shm_ctx *c, int me, int pe, uint64_t dst_off, uint64_t src_off, size_
     int use;
     if (int r = resolve_path(c, path, n, n_wg, &use)) return r;
     if (c->no_device) return no_device(is_get ? "shm_launch_wg_get" : "shm_launch_wg_put");
-    if (use == SHM_PATH_SDMA)
-        return is_get ? engine_copy(c, me, me, dst_off, pe, src_off, n) : engine_copy(c, me, pe, dst_off, me, src_off, n);
+    if (use != SHM_PATH_LDST)
+        return is_get ? transfer_copy(c, use, me, me, dst_off, pe, src_off, n) : transfer_copy(c, use, me, pe, dst_off, me, src_off, n);
+    if (int r = drain_engines(c, me)) return r;
     const int shift = (pe - me + c->npes) % c->npes;
     hipLaunchKernelGGL(shmk_wg_rma, dim3(n_wg, 1), dim3(SHMK_WG), 0, c->stream[me], dev_view(c), dst_off, src_off, n, me, shift,
                        is_get);
@@ -202,14 +244,16 @@ int wg_rma_all(shm_ctx *c, int pe_shift, uint64_t dst_off, uint64_t src_off, siz
     int use;
     if (int r = resolve_path(c, path, n, n_wg, &use)) return r;
     if (c->no_device) return no_device("team put/get");
-    if (use == SHM_PATH_SDMA) {
+    if (int r = drain_all_engines(c)) return r;
+    if (use != SHM_PATH_LDST) {
         if (c->team_sync) {
             if (int r = team_join(c)) return r;
             if (int r = team_fork(c)) return r;
         }
         for (int p = 0; p < c->npes; ++p) {
             const int t = (p + pe_shift) % c->npes;
-            if (int r = is_get ? engine_copy(c, p, p, dst_off, t, src_off, n) : engine_copy(c, p, t, dst_off, p, src_off, n)) return r;
+            if (int r = is_get ? transfer_copy(c, use, p, p, dst_off, t, src_off, n) : transfer_copy(c, use, p, t, dst_off, p, src_off, n))
+                return r;
         }
         if (c->team_sync) {
             if (int r = team_join(c)) return r;
@@ -304,6 +348,14 @@ int shm_init_ex(int npes, size_t heap_bytes, void *heap_base, void *const *strea
     for (int p = 0; p < npes; ++p)
         INIT_TRY(hipMemset(c->base + static_cast<size_t>(p) * heap_bytes + c->user_bytes, 0, SHM_INTERNAL_BYTES));
     INIT_TRY(hipDeviceSynchronize());
+    {
+        int dom = 0, bus = 0, slot = 0;
+        (void)hipDeviceGetAttribute(&dom, hipDeviceAttributePciDomainId, dev);
+        (void)hipDeviceGetAttribute(&bus, hipDeviceAttributePciBusId, dev);
+        (void)hipDeviceGetAttribute(&slot, hipDeviceAttributePciDeviceId, dev);
+        // a device without usable engines keeps working; only SHM_PATH_SDMA then reports an error
+        (void)c->engines.init(dom, bus, slot, dev, SHM_MAX_PES, c->engine_err);
+    }
 #undef INIT_TRY
     *out = c;
     return SHM_OK;
@@ -315,6 +367,7 @@ int shm_finalize(shm_ctx *c)
     if (!c->no_device) {
         for (int p = 0; p < c->npes; ++p)
             if (c->stream[p] || !c->own_streams) (void)hipStreamSynchronize(c->stream[p]);
+        c->engines.shutdown();
         for (int p = 0; p < c->npes; ++p) {
             if (c->event[p]) (void)hipEventDestroy(c->event[p]);
             if (c->own_streams && c->stream[p]) (void)hipStreamDestroy(c->stream[p]);
@@ -396,7 +449,7 @@ int shm_putmem(shm_ctx *c, int me, uint64_t dst_off, uint64_t src_off, size_t n,
     if (int r = check_ctx(c)) return r;
     if (int r = rma_args(c, me, pe, dst_off, src_off, n)) return r;
     if (c->no_device) return no_device("shm_putmem");
-    return engine_copy(c, me, pe, dst_off, me, src_off, n);
+    return memcpy_copy(c, me, pe, dst_off, me, src_off, n);
 }
 
 int shm_getmem(shm_ctx *c, int me, uint64_t dst_off, uint64_t src_off, size_t n, int pe)
@@ -404,7 +457,7 @@ int shm_getmem(shm_ctx *c, int me, uint64_t dst_off, uint64_t src_off, size_t n,
     if (int r = check_ctx(c)) return r;
     if (int r = rma_args(c, me, pe, dst_off, src_off, n)) return r;
     if (c->no_device) return no_device("shm_getmem");
-    return engine_copy(c, me, me, dst_off, pe, src_off, n);
+    return memcpy_copy(c, me, me, dst_off, pe, src_off, n);
 }
 
 int shm_quiet(shm_ctx *c, int me)
@@ -413,6 +466,7 @@ int shm_quiet(shm_ctx *c, int me)
     if (int r = check_pe(c, me, "calling PE")) return r;
     if (c->no_device) return no_device("shm_quiet");
     HIP_TRY(hipStreamSynchronize(c->stream[me]));
+    if (int r = drain_engines(c, me)) return r;
     return take_status(c);
 }
 
@@ -421,7 +475,8 @@ int shm_fence(shm_ctx *c, int me)
     if (int r = check_ctx(c)) return r;
     if (int r = check_pe(c, me, "calling PE")) return r;
     if (c->no_device) return no_device("shm_fence");
-    return take_status(c);     // a stream executes in order: nothing to enqueue
+    if (int r = drain_engines(c, me)) return r;     // engine transfers are not in the stream: finish them
+    return take_status(c);                          // the stream itself executes in order
 }
 
 int shm_barrier_all(shm_ctx *c)
@@ -429,6 +484,7 @@ int shm_barrier_all(shm_ctx *c)
     if (int r = check_ctx(c)) return r;
     if (c->no_device) return no_device("shm_barrier_all");
     for (int p = 0; p < c->npes; ++p) HIP_TRY(hipStreamSynchronize(c->stream[p]));
+    if (int r = drain_all_engines(c)) return r;
     return take_status(c);
 }
 
@@ -503,6 +559,7 @@ int shm_launch_wg_put_signal(shm_ctx *c, int me, int pe, uint64_t dst_off, uint6
     if (n && sig_off + 8 > dst_off && sig_off < dst_off + n)
         return fail(SHM_EINVAL, "signal word lies inside the destination");
     if (c->no_device) return no_device("shm_launch_wg_put_signal");
+    if (int r = drain_engines(c, me)) return r;
     uint64_t *arrive = nullptr;
     if (n_wg > 1) arrive = reinterpret_cast<uint64_t *>(shm_ptr(c, c->user_bytes, me)) + take_slots(c, me, 1);
     hipLaunchKernelGGL(shmk_wg_put_signal, dim3(n_wg), dim3(SHMK_WG), 0, c->stream[me], dev_view(c), me, pe, dst_off, src_off, n,
@@ -517,6 +574,7 @@ int shm_launch_signal_wait_until(shm_ctx *c, int me, uint64_t sig_off, int cmp, 
     if (int r = check_word(c, sig_off, "signal")) return r;
     if (cmp < SHM_CMP_EQ || cmp > SHM_CMP_LE) return fail(SHM_EINVAL, "unknown comparison %d", cmp);
     if (c->no_device) return no_device("shm_launch_signal_wait_until");
+    if (int r = drain_engines(c, me)) return r;
     hipLaunchKernelGGL(shmk_signal_wait, dim3(1), dim3(SHMK_WG), 0, c->stream[me], dev_view(c), me, sig_off, cmp, val, dev_out);
     return launched("signal wait");
 }
@@ -529,6 +587,7 @@ int shm_launch_amo(shm_ctx *c, int me, int pe, uint64_t off, int op, int64_t ope
     if (int r = check_word(c, off, "atomic target")) return r;
     if (op < SHM_AMO_FETCH || op > SHM_AMO_INC) return fail(SHM_EINVAL, "unknown atomic op %d", op);
     if (c->no_device) return no_device("shm_launch_amo");
+    if (int r = drain_engines(c, me)) return r;
     hipLaunchKernelGGL(shmk_amo, dim3(1), dim3(64), 0, c->stream[me], dev_view(c), pe, off, op, operand, cond, dev_out);
     return launched("atomic");
 }
@@ -544,6 +603,7 @@ int shm_launch_pingflag(shm_ctx *c, uint64_t data_off, uint64_t back_off, size_t
     if ((flag_off + 8 > data_off && flag_off < data_off + n) || (flag_off + 8 > back_off && flag_off < back_off + n))
         return fail(SHM_EINVAL, "flag lies inside a data buffer");
     if (c->no_device) return no_device("shm_launch_pingflag");
+    if (int r = drain_all_engines(c)) return r;
     const shm_dev_ctx d = dev_view(c);
     // The producer is enqueued first: it never waits, so the consumer's bounded wait always ends.
     hipLaunchKernelGGL(shmk_ping_producer, dim3(1), dim3(SHMK_WG), 0, c->stream[0], d, data_off, n, flag_off);
@@ -573,6 +633,7 @@ int shm_launch_ring_pipeline(shm_ctx *c, uint64_t src_off, uint64_t slot_off, ui
     if ((nvec + n_wg_cons - 1) / n_wg_cons > static_cast<size_t>(SHMK_WG) * SHMK_RING_VPT)
         return fail(SHM_EINVAL, "n_wg_cons too small: a consumer group holds at most %d bytes of a chunk", SHMK_WG * SHMK_RING_VPT * 16);
     if (c->no_device) return no_device("shm_launch_ring_pipeline");
+    if (int r = drain_all_engines(c)) return r;
     int per_cu = 0;
     HIP_TRY(hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, shmk_ring, SHMK_WG, 0));
     const long long groups = static_cast<long long>(c->npes) * (n_wg_prod + n_wg_cons);
@@ -607,6 +668,7 @@ int shm_launch_amo_storm(shm_ctx *c, uint64_t ctr_off, int n_ctr, const uint16_t
     const uint64_t groups = (n_items + SHMK_WG - 1) / SHMK_WG;
     if (n_items == 0 || groups > 0x7fffffffull) return fail(SHM_EINVAL, "n_items outside 1..2^31*256");
     if (c->no_device) return no_device("shm_launch_amo_storm");
+    if (int r = drain_all_engines(c)) return r;
     if (c->team_sync)
         if (int r = team_join(c)) return r;
     const shm_dev_ctx d = dev_view(c);
@@ -646,7 +708,8 @@ int shm_launch_fcollect(shm_ctx *c, uint64_t dst_off, uint64_t src_off, size_t b
     if (int r = resolve_path(c, path, bytes_per_pe, n_wg, &use)) return r;
     if (c->no_device) return no_device("shm_launch_fcollect");
     if (bytes_per_pe == 0) return SHM_OK;
-    if (use == SHM_PATH_SDMA) {
+    if (int r = drain_all_engines(c)) return r;
+    if (use != SHM_PATH_LDST) {
         if (c->team_sync) {
             if (int r = team_join(c)) return r;
             if (int r = team_fork(c)) return r;
@@ -654,7 +717,8 @@ int shm_launch_fcollect(shm_ctx *c, uint64_t dst_off, uint64_t src_off, size_t b
         for (int j = 0; j < c->npes; ++j)          // destination index varies fastest across streams
             for (int p = 0; p < c->npes; ++p) {
                 const int q = (p + 1 + j) % c->npes;
-                if (int r = engine_copy(c, p, q, dst_off + static_cast<uint64_t>(p) * bytes_per_pe, p, src_off, bytes_per_pe)) return r;
+                if (int r = transfer_copy(c, use, p, q, dst_off + static_cast<uint64_t>(p) * bytes_per_pe, p, src_off, bytes_per_pe))
+                    return r;
             }
         if (c->team_sync) {
             if (int r = team_join(c)) return r;
@@ -686,6 +750,7 @@ int shm_launch_reduce_sum_f32(shm_ctx *c, uint64_t dst_off, uint64_t src_off, si
     if (int r = check_n_wg(n_wg)) return r;
     if (algo != SHM_REDUCE_DUPLICATE && algo != SHM_REDUCE_SPLIT) return fail(SHM_EINVAL, "unknown reduce algorithm %d", algo);
     if (c->no_device) return no_device("shm_launch_reduce_sum_f32");
+    if (int r = drain_all_engines(c)) return r;
     if (nelems == 0) return SHM_OK;
     if (c->team_sync)
         if (int r = team_join(c)) return r;

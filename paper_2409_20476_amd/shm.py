@@ -19,7 +19,7 @@ SHM_INTERNAL_BYTES = 65536
 SHM_NULL_OFF = (1 << 64) - 1
 
 SHM_OK, SHM_EINVAL, SHM_EPE, SHM_ERANGE, SHM_ENOMEM, SHM_EHIP, SHM_ETIMEOUT, SHM_ENODEV = 0, -1, -2, -3, -4, -5, -6, -7
-SHM_PATH_AUTO, SHM_PATH_LDST, SHM_PATH_SDMA = 0, 1, 2
+SHM_PATH_AUTO, SHM_PATH_LDST, SHM_PATH_SDMA, SHM_PATH_MEMCPY = 0, 1, 2, 3
 SHM_SIGNAL_SET, SHM_SIGNAL_ADD = 0, 1
 SHM_CMP_EQ, SHM_CMP_NE, SHM_CMP_GT, SHM_CMP_GE, SHM_CMP_LT, SHM_CMP_LE = range(6)
 SHM_INIT_DEFAULT, SHM_INIT_NO_DEVICE = 0, 1

@@ -60,7 +60,7 @@ def test_ring_rejects_grids_that_cannot_be_resident():
             g.launch_ring_pipeline(0, 2 * MiB, 6 * MiB, 5 * MiB, 1 << 20, 2, 1, 1)     # consumer share too big for registers
 
 
-@pytest.mark.parametrize("path", [S.SHM_PATH_LDST, S.SHM_PATH_SDMA])
+@pytest.mark.parametrize("path", [S.SHM_PATH_LDST, S.SHM_PATH_SDMA, S.SHM_PATH_MEMCPY])
 @pytest.mark.parametrize("npes,n,n_wg,soff,doff", [(8, 4096 * 17 + 16, 8, 0, 0), (3, 1000, 2, 3, 5), (8, 300016, 64, 0, 0),
                                                   (5, 7, 1, 1, 2), (2, 0, 4, 0, 0), (4, 262144 * 3 + 48, 16, 0, 0)])
 def test_fcollect(path, npes, n, n_wg, soff, doff):

@@ -58,7 +58,7 @@ def test_self_target_and_overlap_rejected():
         assert e.value.code == S.SHM_EINVAL
 
 
-@pytest.mark.parametrize("path", [S.SHM_PATH_LDST, S.SHM_PATH_SDMA])
+@pytest.mark.parametrize("path", [S.SHM_PATH_LDST, S.SHM_PATH_SDMA, S.SHM_PATH_MEMCPY])
 def test_team_put_get_all_paths(path):
     g, o = make_pair(8, 4 * MiB)
     with g:
@@ -96,6 +96,13 @@ def test_host_rma_sdma_single_and_auto_policy():
         o.wg_put(0, MiB + 200000, 11, 12345, 2, 4)
         g.launch_wg_get(0, 2, MiB + 300000, 64, 4096, 4, S.SHM_PATH_SDMA)
         o.wg_get(0, MiB + 300000, 64, 4096, 2, 4)
+        g.launch_wg_put(0, 1, MiB + 500000, 1, 7777, 4, S.SHM_PATH_MEMCPY)
+        o.wg_put(0, MiB + 500000, 1, 7777, 1, 4)
+        # an engine transfer followed, without quiet, by a kernel on the same PE that reads its result
+        g.launch_wg_put(0, 3, MiB + 600000, 5, 50001, 2, S.SHM_PATH_SDMA)
+        o.wg_put(0, MiB + 600000, 5, 50001, 3, 2)
+        g.launch_wg_get(0, 3, MiB + 700000, MiB + 600000, 50001, 3, S.SHM_PATH_LDST)
+        o.wg_get(0, MiB + 700000, MiB + 600000, 50001, 3, 3)
         g.quiet(0)
         # AUTO: below the cutover the kernel runs, at or above it the engine; bytes are the same either way
         g.set_cutover(4, 8192)
