@@ -141,48 +141,98 @@ def cpu_put_baseline(oracle_mod, data0, n, n_wg, budget_s=12.0):
                       f"host has {os.cpu_count()} logical CPUs"}
 
 
+def host_timed_trial(torch, g, launch_pe, npes, iters):
+    """Host clock from the first enqueue to completion of everything on all PEs (what a caller of
+    the library sees; also the only clock that covers copy-engine transfers, which are not in a
+    stream)."""
+    g.barrier_all()
+    t0 = time.perf_counter()
+    for _ in range(iters):
+        for p in range(npes):
+            launch_pe(p)
+    g.barrier_all()
+    return (time.perf_counter() - t0) * 1e3 / iters
+
+
+def in_kernel_put_us(torch, S, g, npes, dst, src, n, n_wg, ticks, khz):
+    """Microseconds per put as seen by the issuing kernel (device clock inside the kernel, no launch
+    cost): every PE's kernel repeats its put `reps` times, all eight kernels overlapping."""
+    def run(reps):
+        ticks[:, 0] = -1          # UINT64_MAX
+        ticks[:, 1] = 0
+        torch.cuda.synchronize()
+        for p in range(npes):
+            g.launch_wg_put_timed(p, (p + 1) % npes, dst, src, n, n_wg, reps, ticks[p])
+        g.barrier_all()
+        t = ticks.cpu().numpy().astype(np.uint64)
+        per_put = float(np.mean((t[:, 1] - t[:, 0]).astype(np.float64))) / reps / khz * 1e3
+        span = float(t[:, 1].max() - t[:, 0].min()) / reps / khz * 1e3      # all PEs: first start to last end
+        return per_put, span
+    est = run(4)[0]
+    reps = int(min(512, max(4, 300.0 / max(est, 0.05))))
+    return min(run(reps) for _ in range(5))
+
+
 def put_sweep(torch, S, g, args):
-    """Configuration 2: message sizes 8 B .. 256 MiB, 8 PEs concurrently on their own streams."""
+    """Configuration 2: message sizes 8 B .. 256 MiB, 8 PEs concurrently, each on its own stream
+    (or engine), through loads/stores with 1, 4, 64, 1024 work-groups, through the SDMA copy
+    engines, and through hipMemcpyAsync (a runtime copy kernel on one device)."""
     npes = 8
     max_n = args.sweep_max_mib * MiB
     src, dst = g.malloc(max_n), g.malloc(max_n)
     sizes = [1 << k for k in range(3, 29) if (1 << k) <= max_n]
+    ticks = torch.zeros((npes, 2), dtype=torch.int64, device="cuda")
+    khz = g.wall_clock_khz()
     rows = []
-    curves = [("ldst", w) for w in (1, 4, 64, 1024)] + [("sdma", 0)]
+    wgs = (1, 4, 64, 1024)
     for n in sizes:
         row = {"bytes": n}
-        for kind, n_wg in curves:
-            path = S.SHM_PATH_LDST if kind == "ldst" else S.SHM_PATH_SDMA
-            ms = paper_timing(torch, lambda iters: concurrent_pe_trial(
-                torch, g, lambda p: g.launch_wg_put(p, (p + 1) % npes, dst, src, n, max(n_wg, 1), path), npes, iters))
-            key = f"ldst_wg{n_wg}" if kind == "ldst" else "sdma"
-            row[key + "_us"] = ms * 1e3
-            row[key + "_gbs"] = npes * n / ms / 1e6
+        for n_wg in wgs:
+            us, span = in_kernel_put_us(torch, S, g, npes, dst, src, n, n_wg, ticks, khz)
+            row[f"ldst_wg{n_wg}_us"], row[f"ldst_wg{n_wg}_gbs"] = us, npes * n / span / 1e3
+            launch = lambda p: g.launch_wg_put(p, (p + 1) % npes, dst, src, n, n_wg, S.SHM_PATH_LDST)
+            ms = paper_timing(torch, lambda iters: host_timed_trial(torch, g, launch, npes, iters))
+            row[f"ldst_wg{n_wg}_host_us"] = ms * 1e3
+        for key, path in (("sdma", S.SHM_PATH_SDMA), ("memcpy", S.SHM_PATH_MEMCPY)):
+            launch = lambda p: g.launch_wg_put(p, (p + 1) % npes, dst, src, n, 1, path)
+            ms = paper_timing(torch, lambda iters: host_timed_trial(torch, g, launch, npes, iters))
+            row[key + "_us"], row[key + "_gbs"] = ms * 1e3, npes * n / ms / 1e6
         rows.append(row)
-        log("[sweep] " + " ".join(f"{k}={v:.4g}" if isinstance(v, float) else f"{k}={v}" for k, v in row.items() if not k.endswith("_us")))
+        log("[sweep] " + " ".join(f"{k}={v:.4g}" if isinstance(v, float) else f"{k}={v}" for k, v in row.items() if k.endswith("_gbs") or k == "bytes"))
     # team-launch curve for the largest work-group count (one grid for all PEs)
     g.set_team_sync(False)
     for row in rows:
         n = row["bytes"]
         ms = paper_timing(torch, lambda iters: time_on_stream(
             torch, g.streams[0], lambda: g.launch_wg_put_all(1, dst, src, n, 1024, S.SHM_PATH_LDST), iters))
-        row["team_wg1024_us"], row["team_wg1024_gbs"] = ms * 1e3, npes * n / ms / 1e6
+        row["team_wg1024_event_us"], row["team_wg1024_event_gbs"] = ms * 1e3, npes * n / ms / 1e6
     g.set_team_sync(True)
-    # crossover per work-group count: first size from which the engine is at least as fast, for good
-    cross = {}
-    for n_wg in (1, 4, 64, 1024):
-        key, c = f"ldst_wg{n_wg}_gbs", None
+
+    def crossover(ld_key):
         for i, row in enumerate(rows):
-            if key in row and all(r["sdma_gbs"] >= r[key] for r in rows[i:] if key in r):
-                c = row["bytes"]
-                break
-        cross[str(n_wg)] = c
-        g.set_cutover(n_wg, c if c is not None else (1 << 64) - 1)
+            if all(r["sdma_us"] <= r[ld_key] for r in rows[i:]):
+                return row["bytes"]
+        return None
+
+    cross_dev = {str(w): crossover(f"ldst_wg{w}_us") for w in wgs}
+    cross_host = {str(w): crossover(f"ldst_wg{w}_host_us") for w in wgs}
+    for w in wgs:
+        c = cross_dev[str(w)]
+        g.set_cutover(w, c if c is not None else (1 << 64) - 1)
+    auto = [{"bytes": r["bytes"], **{f"wg{w}": ("sdma" if g.choose_path(r["bytes"], w) == S.SHM_PATH_SDMA else "ldst") for w in wgs}}
+            for r in rows]
     g.free(src), g.free(dst)
-    return {"pes": npes, "timing": "warm-up doubling to >2 ms, best of 10 (events: common start to latest end)",
-            "rows": rows, "crossover_bytes": cross,
-            "crossover_note": "smallest message from which the copy-engine path stays at least as fast as "
-                              "loads/stores; null = loads/stores win at every measured size"}
+    return {"pes": npes,
+            "timing": "8 PEs concurrently. ldst_wgK_us: device clock inside the issuing kernel, per put incl. its quiet, mean over "
+                      "PEs (a put issued from a running kernel, as in the paper's experiment; ldst_wgK_gbs uses the span from "
+                      "the first PE's start to the last PE's end); ldst_wgK_host_us, sdma_us, memcpy_us: host "
+                      "clock from first enqueue to completion on all PEs, warm-up doubling to >2 ms then best of 10; "
+                      "team_wg1024_event_us: HIP events around one grid for all PEs; gbs = payload of all 8 PEs",
+            "rows": rows, "crossover_bytes": cross_dev, "crossover_bytes_host_launched": cross_host, "auto_path": auto,
+            "crossover_note": "smallest message from which an SDMA copy-engine transfer (host submit to completion) stays at "
+                              "least as fast as the put done with loads/stores by that many work-groups per PE; the first table "
+                              "compares against the in-kernel put time, the second against a host-launched put kernel; "
+                              "null = loads/stores win at every measured size"}
 
 
 def pingflag(torch, S, synth, args):
@@ -215,12 +265,12 @@ def pingflag(torch, S, synth, args):
 def ring(torch, S, synth, g, args):
     npes, n_chunks, nel = 8, 64, 524288
     cb = 2 * nel
-    src, slot, acc, sig = g.malloc(cb * n_chunks), g.malloc(cb * n_chunks), g.malloc(4 * nel), g.calloc(8, 8)
+    src, slot, acc, sig = g.malloc(cb * n_chunks), g.malloc(cb * n_chunks), g.malloc(4 * nel), g.calloc(8 * 64, 8)
     for p in range(npes):
         g.write(p, src, synth.c3_chunks(p, n_chunks, nel))
-    zero = np.zeros(8, np.uint8)
+    zero = np.zeros(8 * 64, np.uint8)
     out = {}
-    for n_prod, n_cons in ((32, 32), (16, 32), (32, 64), (64, 64)):
+    for n_prod, n_cons, n_sig in ((8, 32, 1), (16, 32, 1), (32, 32, 1), (32, 32, 32)):
         best = float("inf")
         for i in range(12):
             for p in range(npes):
@@ -228,13 +278,13 @@ def ring(torch, S, synth, g, args):
             torch.cuda.synchronize()
             e0, e1 = event_pair(torch)
             e0.record(g.streams[0])
-            g.launch_ring_pipeline(src, slot, sig, acc, cb, n_chunks, n_prod, n_cons)
+            g.launch_ring_pipeline(src, slot, sig, acc, cb, n_chunks, n_prod, n_cons, n_sig)
             e1.record(g.streams[0])
             g.barrier_all()
             if i >= 2:
                 best = min(best, e0.elapsed_time(e1))
         algo = npes * (n_chunks * 3 * cb + 4 * nel)
-        out[f"prod{n_prod}_cons{n_cons}"] = {"ms": best, "payload_gbs": npes * n_chunks * cb / best / 1e6,
+        out[f"prod{n_prod}_cons{n_cons}_sig{n_sig}"] = {"ms": best, "payload_gbs": npes * n_chunks * cb / best / 1e6,
                                            "algorithmic_gbs": algo / best / 1e6, "frac_hbm": algo / best / 1e6 / HBM_PEAK_GBS}
     for off in (src, slot, acc, sig):
         g.free(off)
@@ -292,10 +342,19 @@ def collectives(torch, S, synth, g, args):
     for n_wg in (256, 1024):
         ms = best_of(lambda: g.launch_fcollect(fdst, fsrc, 4 * nel, n_wg, S.SHM_PATH_LDST))
         out[f"fcollect_ldst_wg{n_wg}"] = {"ms": ms, "algorithmic_gbs": fc_bytes / ms / 1e6, "frac_hbm": fc_bytes / ms / 1e6 / HBM_PEAK_GBS}
-    ms = best_of(lambda: g.launch_fcollect(fdst, fsrc, 4 * nel, 1024, S.SHM_PATH_SDMA))
     sd_bytes = 2 * npes * npes * 4 * nel
-    out["fcollect_sdma"] = {"ms": ms, "algorithmic_gbs": sd_bytes / ms / 1e6, "frac_hbm": sd_bytes / ms / 1e6 / HBM_PEAK_GBS,
-                            "note": "64 engine copies of 64 MiB: 8 GiB of traffic for the same result"}
+    ms = best_of(lambda: g.launch_fcollect(fdst, fsrc, 4 * nel, 1024, S.SHM_PATH_MEMCPY))
+    out["fcollect_memcpy"] = {"ms": ms, "traffic_gbs": sd_bytes / ms / 1e6,
+                              "note": "64 runtime copies of 64 MiB: 8 GiB of traffic for the same result"}
+    best = float("inf")
+    for i in range(4):
+        g.barrier_all()
+        t0 = time.perf_counter()
+        g.launch_fcollect(fdst, fsrc, 4 * nel, 1024, S.SHM_PATH_SDMA)
+        g.barrier_all()
+        if i >= 1:
+            best = min(best, (time.perf_counter() - t0) * 1e3)
+    out["fcollect_sdma"] = {"ms": best, "traffic_gbs": sd_bytes / best / 1e6, "note": "64 SDMA engine copies of 64 MiB, host clock"}
     dup_bytes = npes * npes * 4 * nel + npes * 4 * nel
     spl_bytes = npes * 4 * nel + npes * 4 * nel
     for n_wg in (256, 1024):
@@ -318,6 +377,8 @@ def main():
     ap.add_argument("--sweep-max-mib", type=int, default=256)
     ap.add_argument("--no-extras", action="store_true", help="headline only (used for profiling runs)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibration-copy", action="store_true",
+                    help="also run a plain 2 GiB tensor copy five times (reference reading for HBM byte counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (its PEs are logical partitions of that GPU's HBM); "
@@ -329,6 +390,15 @@ def main():
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)
         return 2
+
+    if args.calibration_copy:
+        a = torch.zeros(2 * GiB, dtype=torch.uint8, device="cuda")
+        b = torch.ones(2 * GiB, dtype=torch.uint8, device="cuda")
+        for _ in range(5):
+            a.copy_(b)
+        torch.cuda.synchronize()
+        del a, b
+        torch.cuda.empty_cache()
 
     g = S.Shm.on_torch(8, GiB)
     head, data0 = headline(torch, S, synth, g, args)
@@ -356,11 +426,12 @@ def main():
         log(f"[bench] c5: {extras['config5_collectives']}")
     g.finalize()
 
-    traffic = None
-    tpath = os.path.join(ROOT, "profiles", "shmk_wg_rma_traffic.json")
+    traffic = None        # measured with rocprofv3 --pmc in a separate run; the summary is committed under profiles/
+    tpath = os.path.join(ROOT, "profiles", "shmk_wg_rma_config2_256MiB_hbm_counters.txt")
     if os.path.exists(tpath) and args.size_mib == 256 and args.n_wg == 1024:
-        with open(tpath) as f:
-            traffic = json.load(f).get("hbm_bytes_per_launch")
+        import re
+        m = re.search(r"^hbm_bytes_per_launch:\s*(\d+)", open(tpath).read(), re.M)
+        traffic = int(m.group(1)) if m else None
 
     line = {
         "metric": "work-group put GB/s vs msg size (% of HBM copy roofline); AMO ops/s",

@@ -151,6 +151,17 @@ int shm_launch_wg_get(shm_ctx *ctx, int me, int pe, uint64_t dst_off, uint64_t s
 int shm_launch_wg_put_all(shm_ctx *ctx, int pe_shift, uint64_t dst_off, uint64_t src_off, size_t n, int n_wg, int path);
 int shm_launch_wg_get_all(shm_ctx *ctx, int pe_shift, uint64_t dst_off, uint64_t src_off, size_t n, int n_wg, int path);
 
+/* Measurement aid for the paper's put experiment (section "Performance Evaluation": bandwidth and
+ * latency of the work-group put as issued from a running kernel): one kernel of n_wg groups on
+ * me's stream performs the same put `reps` times, each followed by the group's quiet, and reads
+ * the device wall clock before and after.  dev_ticks (device pointer to two uint64, initialised by
+ * the caller to UINT64_MAX and 0) receives the earliest start and the latest end over all groups,
+ * combined with atomic min/max so that several launches can share one pair.  shm_wall_clock_khz
+ * gives the tick rate. */
+int shm_launch_wg_put_timed(shm_ctx *ctx, int me, int pe, uint64_t dst_off, uint64_t src_off, size_t n, int n_wg, int reps,
+                            uint64_t *dev_ticks);
+int shm_wall_clock_khz(const shm_ctx *ctx);
+
 /* Put with signal (OpenSHMEM 1.5 semantics, which the paper's feature list adopts): after all n
  * bytes are visible on PE `pe`, its 64-bit word at sig_off (8-byte aligned) is set to sig_val
  * (SET) or increased by it modulo 2^64 (ADD), exactly once however many groups shared the copy.
@@ -175,16 +186,22 @@ int shm_launch_amo(shm_ctx *ctx, int me, int pe, uint64_t off, int op, int64_t o
  * back_off.  Needs npes >= 2. */
 int shm_launch_pingflag(shm_ctx *ctx, uint64_t data_off, uint64_t back_off, size_t n, uint64_t flag_off);
 
-/* Benchmark configuration 3, one grid on the team stream.  For every PE p and chunk k <
- * n_chunks: n_wg_prod producer groups put chunk k (chunk_bytes at src_off + k*chunk_bytes) into
- * slot k (slot_off + k*chunk_bytes) of PE (p+1) mod npes with a put-with-signal ADD 1 on sig_off;
- * n_wg_cons consumer groups of every PE wait for signal >= k+1 and add chunk k, read as bf16 and
- * widened exactly, into a float32 accumulator kept in registers, in chunk order; at the end the
- * accumulator is stored at acc_off (chunk_bytes/2 floats).  chunk_bytes must be a multiple of 16
- * and all offsets 16-byte aligned; the signal word must be zero on entry; the grid must fit on the
- * GPU at once (else SHM_EINVAL). */
+/* Benchmark configuration 3, one grid on the team stream.  Every PE p sends n_chunks chunks
+ * (chunk k = chunk_bytes at src_off + k*chunk_bytes) to slot k (slot_off + k*chunk_bytes) of PE
+ * (p+1) mod npes with put-with-signal ADD 1, using n_wg_prod producer groups; n_wg_cons consumer
+ * groups of every PE wait for chunk k (signal >= k+1) and add it, read as bf16 and widened
+ * exactly, into a float32 accumulator kept in registers, in chunk order; at the end the
+ * accumulator is stored at acc_off (chunk_bytes/2 floats).
+ *   n_sig == 1: one signal word at sig_off; the producer groups share every chunk, count their
+ *     arrivals, and the last one signals.
+ *   n_sig == n_wg_prod == n_wg_cons: lanes.  Producer group j puts the j-th share of every chunk
+ *     with its own put-with-signal on word sig_off + 8*j; consumer group j waits on that word and
+ *     accumulates that share.
+ * chunk_bytes must be a multiple of 16 and all offsets 16-byte aligned; the n_sig signal words
+ * must be zero on entry (each ends at n_chunks); the grid must fit on the GPU at once (else
+ * SHM_EINVAL). */
 int shm_launch_ring_pipeline(shm_ctx *ctx, uint64_t src_off, uint64_t slot_off, uint64_t sig_off, uint64_t acc_off,
-                             size_t chunk_bytes, int n_chunks, int n_wg_prod, int n_wg_cons);
+                             size_t chunk_bytes, int n_chunks, int n_wg_prod, int n_wg_cons, int n_sig);
 
 /* Benchmark configuration 4, one grid on the team stream.  Work-item g < n_items performs
  * ops_per_item atomics; its j-th target is dev_targets[g*ops_per_item + j] = pe*n_ctr + index,

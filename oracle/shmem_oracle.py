@@ -353,11 +353,16 @@ class ShmemOracle:
         return (bits.astype(np.uint32) << np.uint32(16)).view(np.float32)
 
     def ring_pipeline(self, src: int, slot: int, sig: int, acc: int, chunk_bytes: int, n_chunks: int,
-                      n_wg_prod: int = 1) -> None:
+                      n_wg_prod: int = 1, n_sig: int = 1) -> None:
         """Pipelined ring: PE p sends chunk k to slot k of PE (p+1) mod npes with
         put-with-signal (ADD 1); the receiver waits ``signal >= k+1`` and adds the
         bf16 chunk, widened to binary32, into its binary32 accumulator, k ascending.
-        The accumulator is zeroed first; the signal word must start at zero.
+        The accumulator is zeroed first; the signal words must start at zero.
+
+        n_sig == 1: one signal word; the chunk travels as one put-with-signal shared
+        by n_wg_prod groups.  n_sig > 1: lanes -- the chunk is cut into n_sig shares,
+        share j travels with its own put-with-signal on word ``sig + 8*j`` and the
+        receiver waits on that word before adding that share.
         """
         if chunk_bytes % 2:
             raise OracleError("a chunk holds whole bf16 values")
@@ -365,16 +370,19 @@ class ShmemOracle:
         self._range(src, chunk_bytes * n_chunks)
         self._range(slot, chunk_bytes * n_chunks)
         self._range(acc, 4 * nel)
+        shares = [(0, chunk_bytes)] if n_sig == 1 else self.wg_slices(chunk_bytes, n_sig)
         # one legal sequential schedule: all sends of chunk k, then all consumes of chunk k
         accs = [np.zeros(nel, dtype=np.float32) for _ in range(self.npes)]
         for k in range(n_chunks):
             for p in range(self.npes):
-                self.put_signal(p, slot + k * chunk_bytes, src + k * chunk_bytes, chunk_bytes,
-                                sig, 1, SIGNAL_ADD, (p + 1) % self.npes, n_wg_prod)
+                for j, (lo, hi) in enumerate(shares):
+                    self.put_signal(p, slot + k * chunk_bytes + lo, src + k * chunk_bytes + lo, hi - lo,
+                                    sig + 8 * j, 1, SIGNAL_ADD, (p + 1) % self.npes, n_wg_prod if n_sig == 1 else 1)
             for p in range(self.npes):
-                self.signal_wait_until(p, sig, CMP_GE, k + 1)
-                bits = self.heap[p][slot + k * chunk_bytes:slot + (k + 1) * chunk_bytes].copy().view(np.uint16)
-                accs[p] = (accs[p] + self.bf16_bits_to_f32(bits)).astype(np.float32)
+                for j, (lo, hi) in enumerate(shares):
+                    self.signal_wait_until(p, sig + 8 * j, CMP_GE, k + 1)
+                    bits = self.heap[p][slot + k * chunk_bytes + lo:slot + k * chunk_bytes + hi].copy().view(np.uint16)
+                    accs[p][lo // 2:hi // 2] = (accs[p][lo // 2:hi // 2] + self.bf16_bits_to_f32(bits)).astype(np.float32)
         for p in range(self.npes):
             self.heap[p][acc:acc + 4 * nel] = accs[p].view(np.uint8)
 

@@ -548,6 +548,27 @@ int shm_launch_wg_get_all(shm_ctx *c, int pe_shift, uint64_t dst_off, uint64_t s
     return wg_rma_all(c, pe_shift, dst_off, src_off, n, n_wg, path, 1);
 }
 
+int shm_launch_wg_put_timed(shm_ctx *c, int me, int pe, uint64_t dst_off, uint64_t src_off, size_t n, int n_wg, int reps,
+                            uint64_t *dev_ticks)
+{
+    if (int r = check_ctx(c)) return r;
+    if (int r = rma_args(c, me, pe, dst_off, src_off, n)) return r;
+    if (int r = check_n_wg(n_wg)) return r;
+    if (reps < 1 || reps > (1 << 20)) return fail(SHM_EINVAL, "reps outside 1..2^20");
+    if (!dev_ticks) return fail(SHM_EINVAL, "null tick buffer");
+    if (c->no_device) return no_device("shm_launch_wg_put_timed");
+    if (int r = drain_engines(c, me)) return r;
+    hipLaunchKernelGGL(shmk_wg_put_timed, dim3(n_wg), dim3(SHMK_WG), 0, c->stream[me], dev_view(c), dst_off, src_off, n, me, pe, reps,
+                       reinterpret_cast<unsigned long long *>(dev_ticks));
+    return launched("timed work-group put");
+}
+
+int shm_wall_clock_khz(const shm_ctx *c)
+{
+    if (int r = check_ctx(c)) return r;
+    return static_cast<int>(c->ticks_per_us * 1000);
+}
+
 int shm_launch_wg_put_signal(shm_ctx *c, int me, int pe, uint64_t dst_off, uint64_t src_off, size_t n, uint64_t sig_off,
                              uint64_t sig_val, int sig_op, int n_wg)
 {
@@ -613,7 +634,7 @@ int shm_launch_pingflag(shm_ctx *c, uint64_t data_off, uint64_t back_off, size_t
 }
 
 int shm_launch_ring_pipeline(shm_ctx *c, uint64_t src_off, uint64_t slot_off, uint64_t sig_off, uint64_t acc_off, size_t chunk_bytes,
-                             int n_chunks, int n_wg_prod, int n_wg_cons)
+                             int n_chunks, int n_wg_prod, int n_wg_cons, int n_sig)
 {
     if (int r = check_ctx(c)) return r;
     if (chunk_bytes == 0 || chunk_bytes % 16) return fail(SHM_EINVAL, "chunk_bytes must be a positive multiple of 16");
@@ -624,7 +645,10 @@ int shm_launch_ring_pipeline(shm_ctx *c, uint64_t src_off, uint64_t slot_off, ui
     if (int r = check_range(c, src_off, total, "chunk source")) return r;
     if (int r = check_range(c, slot_off, total, "landing slots")) return r;
     if (int r = check_range(c, acc_off, chunk_bytes * 2, "accumulator")) return r;
-    if (int r = check_word(c, sig_off, "signal")) return r;
+    if (n_sig != 1 && !(n_sig == n_wg_prod && n_sig == n_wg_cons))
+        return fail(SHM_EINVAL, "n_sig must be 1 or equal to both n_wg_prod and n_wg_cons");
+    if (int r = check_range(c, sig_off, 8ull * n_sig, "signals")) return r;
+    if (sig_off & 7) return fail(SHM_EINVAL, "signal words must be 8-byte aligned");
     if ((src_off | slot_off | acc_off) & 15) return fail(SHM_EINVAL, "offsets must be 16-byte aligned");
     if (overlaps(src_off, slot_off, total) || (acc_off < slot_off + total && slot_off < acc_off + 2 * chunk_bytes) ||
         (acc_off < src_off + total && src_off < acc_off + 2 * chunk_bytes))
@@ -647,7 +671,7 @@ int shm_launch_ring_pipeline(shm_ctx *c, uint64_t src_off, uint64_t slot_off, ui
     if (c->team_sync)
         if (int r = team_join(c)) return r;
     hipLaunchKernelGGL(shmk_ring, dim3(static_cast<unsigned>(groups)), dim3(SHMK_WG), 0, c->stream[0], dev_view(c), src_off, slot_off,
-                       sig_off, acc_off, chunk_bytes, n_chunks, n_wg_prod, n_wg_cons, c->user_bytes + 8ull * first);
+                       sig_off, acc_off, chunk_bytes, n_chunks, n_wg_prod, n_wg_cons, c->user_bytes + 8ull * first, n_sig > 1 || (n_wg_prod == 1 && n_wg_cons == 1));
     if (int r = launched("ring pipeline")) return r;
     if (c->team_sync)
         if (int r = team_fork(c)) return r;

@@ -23,6 +23,25 @@ __global__ __launch_bounds__(SHMK_WG) void shmk_wg_rma(shm_dev_ctx c, uint64_t d
         shmx_putmem_parts(c, me, dst_off, src_off, n, pe, blockIdx.x, gridDim.x);
 }
 
+// The same put repeated `reps` times inside one kernel, each followed by the group's quiet, with the
+// device clock read before the first and after the last: the cost of a put issued from a running
+// kernel, free of any launch overhead.  ticks[0] = earliest start, ticks[1] = latest end over groups.
+__global__ __launch_bounds__(SHMK_WG) void shmk_wg_put_timed(shm_dev_ctx c, uint64_t dst_off, uint64_t src_off, size_t n, int me, int pe,
+                                                             int reps, unsigned long long *ticks)
+{
+    const bool mine = shm_deal_has_share<8>(n, blockIdx.x, gridDim.x, SHMK_WG);   // groups without a share have nothing to complete
+    const unsigned long long t0 = wall_clock64();
+    for (int r = 0; r < reps; ++r) {
+        shmx_putmem_parts(c, me, dst_off, src_off, n, pe, blockIdx.x, gridDim.x);
+        if (mine) shmx_quiet_wg();
+    }
+    const unsigned long long t1 = wall_clock64();
+    if (threadIdx.x == 0) {
+        atomicMin(&ticks[0], t0);
+        atomicMax(&ticks[1], t1);
+    }
+}
+
 __global__ __launch_bounds__(SHMK_WG) void shmk_wg_put_signal(shm_dev_ctx c, int me, int pe, uint64_t dst_off, uint64_t src_off,
                                                               size_t n, uint64_t sig_off, uint64_t sig_val, int sig_op,
                                                               uint64_t *arrive)
@@ -78,14 +97,24 @@ __global__ __launch_bounds__(SHMK_WG) void shmk_ping_consumer(shm_dev_ctx c, uin
 
 __global__ __launch_bounds__(SHMK_WG) void shmk_ring(shm_dev_ctx c, uint64_t src_off, uint64_t slot_off, uint64_t sig_off,
                                                      uint64_t acc_off, size_t chunk_bytes, int n_chunks, int n_prod, int n_cons,
-                                                     uint64_t arrive_off)
+                                                     uint64_t arrive_off, int lanes)
 {
     const int npes = c.npes;
     const int b = blockIdx.x;
+    const size_t nvec = chunk_bytes >> 4;
+    const size_t per = (nvec + n_cons - 1) / n_cons;           // host guarantees per <= SHMK_WG * SHMK_RING_VPT
     if (b < npes * n_prod) {
         const int me = b % npes, part = b / npes;
         int pe = me + 1;
         if (pe >= npes) pe = 0;
+        if (lanes) {
+            // lane `part`: its own share of every chunk, its own signal word, no arrival counting
+            const size_t lo = min(nvec, part * per), hi = min(nvec, lo + per);
+            for (int k = 0; k < n_chunks; ++k)
+                shmx_putmem_signal_wg(c, me, slot_off + k * chunk_bytes + 16 * lo, src_off + k * chunk_bytes + 16 * lo, 16 * (hi - lo),
+                                      sig_off + 8ull * part, 1, SHMD_SIGNAL_ADD, pe);
+            return;
+        }
         uint64_t *arrive = reinterpret_cast<uint64_t *>(shm_ptr(c, arrive_off, me));
         for (int k = 0; k < n_chunks; ++k)
             shmx_putmem_signal_parts(c, me, slot_off + k * chunk_bytes, src_off + k * chunk_bytes, chunk_bytes, sig_off, 1,
@@ -94,16 +123,15 @@ __global__ __launch_bounds__(SHMK_WG) void shmk_ring(shm_dev_ctx c, uint64_t src
     }
     const int cb = b - npes * n_prod;
     const int me = cb % npes, part = cb / npes;
-    const size_t nvec = chunk_bytes >> 4;
-    const size_t per = (nvec + n_cons - 1) / n_cons;           // host guarantees per <= SHMK_WG * SHMK_RING_VPT
     const size_t lo = min(nvec, part * per), hi = min(nvec, lo + per);
+    const uint64_t my_sig = sig_off + (lanes ? 8ull * part : 0ull);
     float acc[SHMK_RING_VPT][8];
 #pragma unroll
     for (int j = 0; j < SHMK_RING_VPT; ++j)
 #pragma unroll
         for (int e = 0; e < 8; ++e) acc[j][e] = 0.0f;
     for (int k = 0; k < n_chunks; ++k) {
-        shmx_signal_wait_until_wg(c, me, sig_off, SHMD_CMP_GE, static_cast<uint64_t>(k) + 1);
+        shmx_signal_wait_until_wg(c, me, my_sig, SHMD_CMP_GE, static_cast<uint64_t>(k) + 1);
         const shm_u32x4 *slot = reinterpret_cast<const shm_u32x4 *>(shm_ptr(c, slot_off + k * chunk_bytes, me));
         shm_u32x4 w[SHMK_RING_VPT];
 #pragma unroll

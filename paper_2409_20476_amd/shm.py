@@ -60,11 +60,13 @@ PROTOTYPES = {
     "shm_launch_wg_get": (c_int, [c_void_p, c_int, c_int, c_uint64, c_uint64, c_size_t, c_int, c_int]),
     "shm_launch_wg_put_all": (c_int, [c_void_p, c_int, c_uint64, c_uint64, c_size_t, c_int, c_int]),
     "shm_launch_wg_get_all": (c_int, [c_void_p, c_int, c_uint64, c_uint64, c_size_t, c_int, c_int]),
+    "shm_launch_wg_put_timed": (c_int, [c_void_p, c_int, c_int, c_uint64, c_uint64, c_size_t, c_int, c_int, c_void_p]),
+    "shm_wall_clock_khz": (c_int, [c_void_p]),
     "shm_launch_wg_put_signal": (c_int, [c_void_p, c_int, c_int, c_uint64, c_uint64, c_size_t, c_uint64, c_uint64, c_int, c_int]),
     "shm_launch_signal_wait_until": (c_int, [c_void_p, c_int, c_uint64, c_int, c_uint64, c_void_p]),
     "shm_launch_amo": (c_int, [c_void_p, c_int, c_int, c_uint64, c_int, c_int64, c_int64, c_void_p]),
     "shm_launch_pingflag": (c_int, [c_void_p, c_uint64, c_uint64, c_size_t, c_uint64]),
-    "shm_launch_ring_pipeline": (c_int, [c_void_p, c_uint64, c_uint64, c_uint64, c_uint64, c_size_t, c_int, c_int, c_int]),
+    "shm_launch_ring_pipeline": (c_int, [c_void_p, c_uint64, c_uint64, c_uint64, c_uint64, c_size_t, c_int, c_int, c_int, c_int]),
     "shm_launch_amo_storm": (c_int, [c_void_p, c_uint64, c_int, c_void_p, c_uint64, c_int, c_int, c_void_p, c_void_p]),
     "shm_launch_fcollect": (c_int, [c_void_p, c_uint64, c_uint64, c_size_t, c_int, c_int]),
     "shm_launch_reduce_sum_f32": (c_int, [c_void_p, c_uint64, c_uint64, c_size_t, c_int, c_int]),
@@ -227,6 +229,12 @@ class Shm:
     def launch_wg_get_all(self, pe_shift, dst_off, src_off, n, n_wg=1, path=SHM_PATH_LDST):
         self._check(self.lib.shm_launch_wg_get_all(self.ctx, pe_shift, dst_off, src_off, n, n_wg, path))
 
+    def launch_wg_put_timed(self, me, pe, dst_off, src_off, n, n_wg, reps, dev_ticks):
+        self._check(self.lib.shm_launch_wg_put_timed(self.ctx, me, pe, dst_off, src_off, n, n_wg, reps, _ptr(dev_ticks)))
+
+    def wall_clock_khz(self) -> int:
+        return self._check(self.lib.shm_wall_clock_khz(self.ctx))
+
     def launch_wg_put_signal(self, me, pe, dst_off, src_off, n, sig_off, sig_val, sig_op, n_wg=1):
         self._check(self.lib.shm_launch_wg_put_signal(self.ctx, me, pe, dst_off, src_off, n, sig_off, sig_val, sig_op, n_wg))
 
@@ -239,9 +247,9 @@ class Shm:
     def launch_pingflag(self, data_off, back_off, n, flag_off):
         self._check(self.lib.shm_launch_pingflag(self.ctx, data_off, back_off, n, flag_off))
 
-    def launch_ring_pipeline(self, src_off, slot_off, sig_off, acc_off, chunk_bytes, n_chunks, n_wg_prod, n_wg_cons):
+    def launch_ring_pipeline(self, src_off, slot_off, sig_off, acc_off, chunk_bytes, n_chunks, n_wg_prod, n_wg_cons, n_sig=1):
         self._check(self.lib.shm_launch_ring_pipeline(self.ctx, src_off, slot_off, sig_off, acc_off, chunk_bytes, n_chunks,
-                                                      n_wg_prod, n_wg_cons))
+                                                      n_wg_prod, n_wg_cons, n_sig))
 
     def launch_amo_storm(self, ctr_off, n_ctr, dev_targets, n_items, ops_per_item, kind=SHM_STORM_FETCH_ADD,
                          dev_fetched=None, dev_checksum=None):

@@ -1,0 +1,169 @@
+"""CPU-only tests of the C ABI's host side: symbols, argument checking, allocator, policy.
+
+They use a context built with SHM_INIT_NO_DEVICE, which makes no HIP call; nothing is computed.
+"""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+from paper_2409_20476_amd import shm as S
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+MiB = 1 << 20
+
+
+def _ctx(npes=4, heap=MiB):
+    return S.Shm(npes, heap, heap_base=4096, flags=S.SHM_INIT_NO_DEVICE)
+
+
+def test_library_exports_every_declared_symbol_and_binding_covers_them():
+    header = open(os.path.join(ROOT, "include", "shm355.h")).read()
+    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+    declared = set(re.findall(r"\b(shm_[a-z0-9_]+)\s*\(", header))
+    assert len(declared) >= 30
+    lib = ctypes.CDLL(os.path.join(ROOT, "paper_2409_20476_amd", "libshm355.so"))
+    for name in declared:
+        assert hasattr(lib, name), f"{name} is declared but not exported"
+    assert declared == set(S.PROTOTYPES), declared ^ set(S.PROTOTYPES)
+
+
+def test_constants_match_header():
+    header = open(os.path.join(ROOT, "include", "shm355.h")).read()
+    for name, val in re.findall(r"\b(SHM_[A-Z0-9_]+)\s*=\s*(-?\d+)", header):
+        assert getattr(S, name) == int(val), name
+    assert f"#define SHM_MAX_PES        {S.SHM_MAX_PES}" in header
+    assert f"#define SHM_INTERNAL_BYTES {S.SHM_INTERNAL_BYTES}" in header
+
+
+def test_init_argument_checks():
+    for npes, heap, code in [(0, MiB, S.SHM_EPE), (33, MiB, S.SHM_EPE), (2, 65536, S.SHM_EINVAL), (2, MiB + 1, S.SHM_EINVAL)]:
+        with pytest.raises(S.ShmError) as e:
+            _ctx(npes, heap)
+        assert e.value.code == code
+    with pytest.raises(S.ShmError):
+        S.Shm(2, MiB, heap_base=4096 + 8, flags=S.SHM_INIT_NO_DEVICE)      # misaligned base
+    with pytest.raises(S.ShmError):
+        S.Shm(2, MiB, heap_base=4096, flags=64)
+    g = _ctx()
+    assert g.n_pes() == 4 and g.heap_bytes() == MiB - S.SHM_INTERNAL_BYTES
+    assert g.ptr(0, 0) == 4096 and g.ptr(16, 3) == 4096 + 3 * MiB + 16 and g.ptr(0, 4) == 0 and g.ptr(MiB, 0) == 0
+    g.finalize()
+
+
+def test_allocator_invariants_through_the_abi():
+    g = _ctx(4, 4 * MiB)
+    rng = np.random.default_rng(3)
+    live = {}
+    for _ in range(2000):
+        if live and rng.random() < 0.45:
+            off = list(live)[int(rng.integers(len(live)))]
+            g.free(off)
+            del live[off]
+            continue
+        n = int(rng.integers(1, 60000))
+        align = int(2 ** rng.integers(0, 13))
+        try:
+            off = g.malloc(n, align)
+        except S.ShmError as e:
+            assert e.code == S.SHM_ENOMEM
+            continue
+        assert off % align == 0 and off + n <= g.heap_bytes()
+        for o2, n2 in live.items():
+            assert off + n <= o2 or o2 + n2 <= off, "live blocks overlap"
+        live[off] = n
+    for off in list(live):
+        g.free(off)
+    assert g.malloc(g.heap_bytes(), 1) == 0            # everything coalesced back into one extent
+    with pytest.raises(S.ShmError) as e:
+        g.malloc(1)
+    assert e.value.code == S.SHM_ENOMEM
+    g.finalize()
+
+
+def test_allocator_edge_cases():
+    g = _ctx()
+    assert g.malloc(0) == S.SHM_NULL_OFF
+    g.free(S.SHM_NULL_OFF)
+    a = g.malloc(10)
+    assert a % 256 == 0                                  # default alignment
+    b = g.calloc(100, 64)                                # no device: allocates, zeroing is skipped
+    assert b % 64 == 0 and b != a
+    for bad in (lambda: g.free(a + 16), lambda: g.malloc(8, 3), lambda: g.malloc(2 * MiB)):
+        with pytest.raises(S.ShmError):
+            bad()
+    g.free(a)
+    with pytest.raises(S.ShmError):
+        g.free(a)                                        # double free
+    g.finalize()
+
+
+def test_every_entry_point_validates_before_touching_the_device():
+    g = _ctx(4, MiB)
+    H = g.heap_bytes()
+    E = S.ShmError
+
+    def code(fn):
+        with pytest.raises(E) as e:
+            fn()
+        return e.value.code
+
+    # valid arguments reach the device step, which a no-device context refuses
+    assert code(lambda: g.launch_wg_put(0, 1, 4096, 0, 100, 4)) == S.SHM_ENODEV
+    assert code(lambda: g.launch_wg_put_all(1, 4096, 0, 100, 4)) == S.SHM_ENODEV
+    assert code(lambda: g.putmem(0, 4096, 0, 100, 1)) == S.SHM_ENODEV
+    assert code(lambda: g.quiet(0)) == S.SHM_ENODEV
+    assert code(lambda: g.write(0, 0, np.zeros(4, np.uint8))) == S.SHM_ENODEV
+    assert code(lambda: g.launch_pingflag(0, 16384, 16384, 40000)) == S.SHM_ENODEV
+    assert code(lambda: g.launch_ring_pipeline(0, 65536, 262144, 131072, 4096, 4, 2, 2, 1)) == S.SHM_ENODEV
+    assert code(lambda: g.launch_amo_storm(0, 16, 4096, 100, 8)) == S.SHM_ENODEV
+    assert code(lambda: g.launch_fcollect(65536, 0, 1000, 2)) == S.SHM_ENODEV
+    assert code(lambda: g.launch_reduce_sum_f32(65536, 0, 1000, 2)) == S.SHM_ENODEV
+    # bad PEs
+    assert code(lambda: g.launch_wg_put(4, 1, 4096, 0, 100, 4)) == S.SHM_EPE
+    assert code(lambda: g.launch_wg_put(0, -1, 4096, 0, 100, 4)) == S.SHM_EPE
+    assert code(lambda: g.launch_wg_put_all(4, 4096, 0, 100, 4)) == S.SHM_EPE
+    assert code(lambda: g.quiet(9)) == S.SHM_EPE
+    # ranges: the library's own tail of the partition is off limits
+    assert code(lambda: g.launch_wg_put(0, 1, H - 50, 0, 100, 4)) == S.SHM_ERANGE
+    assert code(lambda: g.launch_wg_get(0, 1, 0, H, 1, 4)) == S.SHM_ERANGE
+    assert code(lambda: g.launch_wg_put(0, 1, 0, 0, 1 << 62, 4)) == S.SHM_ERANGE
+    assert code(lambda: g.launch_fcollect(0, H - 8, H // 2, 2)) == S.SHM_ERANGE
+    assert code(lambda: g.launch_reduce_sum_f32(0, 65536, H, 2)) == S.SHM_ERANGE
+    # overlap, alignment, enumerations, counts
+    assert code(lambda: g.launch_wg_put(1, 1, 50, 0, 100, 4)) == S.SHM_EINVAL
+    assert code(lambda: g.launch_wg_put(0, 1, 4096, 0, 100, 0)) == S.SHM_EINVAL
+    assert code(lambda: g.launch_wg_put(0, 1, 4096, 0, 100, 4, 7)) == S.SHM_EINVAL
+    assert code(lambda: g.launch_wg_put_signal(0, 1, 4096, 0, 100, 8196, 1, S.SHM_SIGNAL_SET)) == S.SHM_EINVAL     # misaligned
+    assert code(lambda: g.launch_wg_put_signal(0, 1, 4096, 0, 100, 4104, 1, S.SHM_SIGNAL_SET)) == S.SHM_EINVAL     # inside payload
+    assert code(lambda: g.launch_wg_put_signal(0, 1, 4096, 0, 100, 8192, 1, 5)) == S.SHM_EINVAL
+    assert code(lambda: g.launch_signal_wait_until(0, 8192, 9, 1)) == S.SHM_EINVAL
+    assert code(lambda: g.launch_amo(0, 1, 12, S.SHM_AMO_FETCH)) == S.SHM_EINVAL
+    assert code(lambda: g.launch_amo(0, 1, 16, 99)) == S.SHM_EINVAL
+    assert code(lambda: g.launch_ring_pipeline(0, 65536, 262144, 131072, 4100, 4, 2, 2, 1)) == S.SHM_EINVAL     # chunk not x16
+    assert code(lambda: g.launch_ring_pipeline(0, 65536, 262144, 131072, 4096, 4, 2, 3, 2)) == S.SHM_EINVAL     # lanes need equal groups
+    assert code(lambda: g.launch_ring_pipeline(0, 8192, 262144, 131072, 4096, 4, 2, 2, 1)) == S.SHM_EINVAL      # src/slots overlap
+    assert code(lambda: g.launch_amo_storm(0, 16, 4096 + 2, 100, 8)) == S.SHM_EINVAL                            # table alignment
+    assert code(lambda: g.launch_amo_storm(0, 1 << 15, 4096, 100, 8)) == S.SHM_EINVAL                           # 16-bit ids
+    assert code(lambda: g.launch_reduce_sum_f32(65538, 0, 1000, 2)) == S.SHM_EINVAL
+    assert code(lambda: g.launch_reduce_sum_f32(0, 0, 1000, 2, 5)) == S.SHM_EINVAL
+    assert code(lambda: g.launch_fcollect(100, 0, 1000, 2)) == S.SHM_EINVAL                                     # overlap
+    assert code(lambda: g.set_wait_timeout_us(0)) == S.SHM_EINVAL
+    g.finalize()
+
+
+def test_cutover_policy_classes():
+    g = _ctx()
+    never = (1 << 64) - 1
+    assert [g.get_cutover(w) for w in (1, 4, 64, 1024)] == [never] * 4
+    assert g.choose_path(1 << 40, 1) == S.SHM_PATH_LDST
+    g.set_cutover(1, 4096), g.set_cutover(3, 65536), g.set_cutover(64, MiB), g.set_cutover(65, 16 * MiB)
+    assert [g.get_cutover(w) for w in (1, 2, 4, 5, 64, 100, 1 << 20)] == [4096, 65536, 65536, MiB, MiB, 16 * MiB, 16 * MiB]
+    assert g.choose_path(4095, 1) == S.SHM_PATH_LDST and g.choose_path(4096, 1) == S.SHM_PATH_SDMA
+    assert g.choose_path(MiB - 1, 64) == S.SHM_PATH_LDST and g.choose_path(MiB, 33) == S.SHM_PATH_SDMA
+    assert g.choose_path(8 * MiB, 1024) == S.SHM_PATH_LDST and g.choose_path(16 * MiB, 1024) == S.SHM_PATH_SDMA
+    with pytest.raises(S.ShmError):
+        g.get_cutover(0)
+    g.finalize()

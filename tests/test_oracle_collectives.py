@@ -159,6 +159,22 @@ def test_ring_equals_composition_of_pinned_ops():
     assert all((x == y).all() for x, y in zip(a.heap, b.heap))
 
 
+def test_ring_lanes_give_the_same_data_and_one_counter_per_lane():
+    """Cutting every chunk into shares that travel with their own signal changes neither slots nor sums."""
+    npes, n_chunks, nel = 3, 5, 72
+    a, b = ShmemOracle(npes, 4096), ShmemOracle(npes, 4096)
+    for p in range(npes):
+        c = synth.c3_chunks(p, n_chunks, nel)
+        a.write(p, 0, c), b.write(p, 0, c)
+    a.ring_pipeline(0, 1024, 2048, 2304, 2 * nel, n_chunks)
+    b.ring_pipeline(0, 1024, 2048, 2304, 2 * nel, n_chunks, n_sig=4)
+    for p in range(npes):
+        assert (a.read(p, 1024, 2 * nel * n_chunks) == b.read(p, 1024, 2 * nel * n_chunks)).all()
+        assert (a.read(p, 2304, 4 * nel) == b.read(p, 2304, 4 * nel)).all()
+        assert a.read(p, 2048, 32, np.uint64).tolist() == [n_chunks, 0, 0, 0]
+        assert b.read(p, 2048, 32, np.uint64).tolist() == [n_chunks] * 4
+
+
 def test_synth_is_seeded_and_in_range():
     assert (synth.c1_payload() == synth.c1_payload()).all()
     v = synth.c1_payload()

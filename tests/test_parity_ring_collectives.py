@@ -11,11 +11,11 @@ MiB = 1 << 20
 GiB = 1 << 30
 
 
-def _ring_case(npes, n_chunks, chunk_elems, n_prod, n_cons, heap, reps=1):
+def _ring_case(npes, n_chunks, chunk_elems, n_prod, n_cons, heap, reps=1, n_sig=1):
     g, o = make_pair(npes, heap)
     with g:
         cb = 2 * chunk_elems
-        src, slot, acc, sig = g.malloc(cb * n_chunks), g.malloc(cb * n_chunks), g.malloc(4 * chunk_elems), g.calloc(8, 8)
+        src, slot, acc, sig = g.malloc(cb * n_chunks), g.malloc(cb * n_chunks), g.malloc(4 * chunk_elems), g.calloc(8 * n_sig, 8)
         for p in range(npes):
             chunks = synth.c3_chunks(p, n_chunks, chunk_elems)
             write_both(g, o, p, src, chunks)
@@ -23,12 +23,13 @@ def _ring_case(npes, n_chunks, chunk_elems, n_prod, n_cons, heap, reps=1):
             write_both(g, o, p, acc, np.full(4 * chunk_elems, 0x7F, np.uint8))
         for rep in range(reps):
             for p in range(npes):
-                write_both(g, o, p, sig, np.zeros(8, np.uint8))
-            g.launch_ring_pipeline(src, slot, sig, acc, cb, n_chunks, n_prod, n_cons)
+                write_both(g, o, p, sig, np.zeros(8 * n_sig, np.uint8))
+            g.launch_ring_pipeline(src, slot, sig, acc, cb, n_chunks, n_prod, n_cons, n_sig)
             g.barrier_all()
-            o.ring_pipeline(src, slot, sig, acc, cb, n_chunks, n_prod)
+            o.ring_pipeline(src, slot, sig, acc, cb, n_chunks, n_prod, n_sig)
             for p in range(npes):
-                assert g.read(p, sig, 8, np.uint64)[0] == n_chunks
+                assert g.read(p, sig, 8 * n_sig, np.uint64).tolist() == [n_chunks] * n_sig
+                assert np.array_equal(g.read(p, sig, 8 * n_sig), o.read(p, sig, 8 * n_sig))
                 assert np.array_equal(g.read(p, slot, cb * n_chunks), o.read(p, slot, cb * n_chunks)), f"slots of PE {p}"
                 got, want = g.read(p, acc, 4 * chunk_elems, np.uint32), o.read(p, acc, 4 * chunk_elems, np.uint32)
                 assert np.array_equal(got, want), f"accumulator of PE {p} (rep {rep})"
@@ -44,10 +45,22 @@ def test_ring_small(npes, n_chunks, chunk_elems, n_prod, n_cons):
     _ring_case(npes, n_chunks, chunk_elems, n_prod, n_cons, 8 * MiB, reps=3)
 
 
+@pytest.mark.parametrize("npes,n_chunks,chunk_elems,lanes", [(2, 3, 8, 1), (3, 5, 2048 + 8, 3), (8, 16, 16384, 8),
+                                                            (4, 7, 8 * 2048 * 3 + 8 * 5, 5), (2, 4, 64, 16)])
+def test_ring_lanes_small(npes, n_chunks, chunk_elems, lanes):
+    _ring_case(npes, n_chunks, chunk_elems, lanes, lanes, 8 * MiB, reps=3, n_sig=lanes)
+
+
 @pytest.mark.timeout(600)
 def test_config3_full_size():
     """8 PEs, 64 chunks of 1 MiB bf16 each, in the launch shape the benchmark times."""
-    _ring_case(8, 64, 524288, 32, 32, 256 * MiB, reps=2)
+    _ring_case(8, 64, 524288, 8, 32, 256 * MiB, reps=2)
+
+
+@pytest.mark.timeout(600)
+def test_config3_full_size_lanes():
+    """The same with one signal counter per producer/consumer group pair."""
+    _ring_case(8, 64, 524288, 32, 32, 256 * MiB, reps=2, n_sig=32)
 
 
 def test_ring_rejects_grids_that_cannot_be_resident():
@@ -58,6 +71,8 @@ def test_ring_rejects_grids_that_cannot_be_resident():
         assert e.value.code == S.SHM_EINVAL
         with pytest.raises(S.ShmError):
             g.launch_ring_pipeline(0, 2 * MiB, 6 * MiB, 5 * MiB, 1 << 20, 2, 1, 1)     # consumer share too big for registers
+        with pytest.raises(S.ShmError):
+            g.launch_ring_pipeline(0, MiB, 4 * MiB, 2 * MiB, 65536, 4, 4, 8, 4)        # lanes need equal group counts
 
 
 @pytest.mark.parametrize("path", [S.SHM_PATH_LDST, S.SHM_PATH_SDMA, S.SHM_PATH_MEMCPY])

@@ -113,3 +113,19 @@ def test_host_rma_sdma_single_and_auto_policy():
             o.wg_put(3, MiB + 400000, 0, n, 1, 4)
         g.quiet(3)
         assert_heaps_equal(g, o)
+
+
+def test_timed_put_moves_the_same_bytes_and_reports_device_time():
+    import torch
+    g, o = make_pair(2, 4 * MiB)
+    with g:
+        fill_random(g, o, 6)
+        ticks = torch.zeros(2, dtype=torch.int64, device="cuda")
+        ticks[0] = -1
+        g.launch_wg_put_timed(0, 1, 2 * MiB + 3, 17, 300001, 8, 5, ticks)
+        g.quiet(0)
+        o.wg_put(0, 2 * MiB + 3, 17, 300001, 1, 8)
+        assert_heaps_equal(g, o)
+        t0, t1 = (int(v) & ((1 << 64) - 1) for v in ticks.tolist())
+        us = (t1 - t0) / g.wall_clock_khz() * 1e3
+        assert 0 < us < 1e5, us
