@@ -270,7 +270,7 @@ def ring(torch, S, synth, g, args):
         g.write(p, src, synth.c3_chunks(p, n_chunks, nel))
     zero = np.zeros(8 * 64, np.uint8)
     out = {}
-    for n_prod, n_cons, n_sig in ((8, 32, 1), (16, 32, 1), (32, 32, 1), (32, 32, 32)):
+    for n_prod, n_cons, n_sig in ((8, 32, 1), (16, 32, 1), (32, 32, 32), (64, 64, 64)):
         best = float("inf")
         for i in range(12):
             for p in range(npes):

@@ -130,6 +130,15 @@ __device__ __forceinline__ void shm_copy_coop(char *dst, const char *src, size_t
     }
 }
 
+template <int POLICY = SHM_ST_STREAM>
+__device__ __forceinline__ void shm_st1(char *p, char v)
+{
+    if (POLICY == SHM_ST_THROUGH)
+        asm volatile("global_store_byte %0, %1, off sc1" ::"v"(p), "v"(static_cast<int>(v)) : "memory");
+    else
+        *p = v;
+}
+
 // ------------------------------------------------------------------------------------------
 // Several work-groups sharing one message.  How the bytes are dealt to groups and lanes cannot be
 // observed, so it is chosen for the memory system: on MI355X a wave sustains the highest HBM
@@ -214,8 +223,8 @@ __device__ __forceinline__ void shm_copy_parts(char *dst, const char *src, size_
     const size_t body = (n - head) & ~static_cast<size_t>(15);
     const size_t tail = n - head - body;
     if (part == 0) {
-        for (size_t i = tid; i < head; i += nthr) dst[i] = src[i];
-        for (size_t i = tid; i < tail; i += nthr) dst[head + body + i] = src[head + body + i];
+        for (size_t i = tid; i < head; i += nthr) shm_st1<POLICY>(dst + i, src[i]);
+        for (size_t i = tid; i < tail; i += nthr) shm_st1<POLICY>(dst + head + body + i, src[head + body + i]);
     }
     if (body == 0) return;
     shm_u32x4 *d = reinterpret_cast<shm_u32x4 *>(dst + head);
@@ -373,29 +382,47 @@ __device__ __forceinline__ uint64_t shmx_signal_wait_until_wg(const shm_dev_ctx 
     return v;
 }
 
-// Put with signal for one work-group, or for `nparts` work-groups sharing one message: group
-// `part` copies its share; after the group barrier its leader releases the group's stores at agent
-// scope (one cache write-back per group instead of one per wave) by arriving on *arrive; the group
-// whose arrival completes the message resets the counter and updates the signal (release).  With
-// nparts == 1 the counter is not touched and may be null.
+// Put with signal for one work-group, or for `nparts` work-groups sharing one message.
+//
+// OpenSHMEM orders the signal after THIS put's payload only (earlier puts need fence/quiet), so a
+// full agent-scope release -- whose cache write-back costs about a quarter of a microsecond and
+// serialises over every group of an XCD -- is not required, only that the payload is performed at
+// agent scope before the signal is.  That is arranged directly: every payload store is written
+// through the XCD's L2 (sc1, the encoding of an agent-scope atomic store), every wave waits for the
+// acknowledgement of its own stores (s_waitcnt vmcnt(0): for a store of that scope the
+// acknowledgement means it is performed at agent scope), the group barrier collects the waves, and
+// only then does the leader touch the arrival counter and the signal, with relaxed agent-scope
+// atomics.  Group `part` copies its share; the group whose arrival completes the message (counted
+// in *arrive, which it resets to zero) updates the signal.  With nparts == 1 the counter is not
+// touched and may be null.  Define SHM_SIGNAL_FULL_RELEASE to use release/acquire atomics (and the
+// cache write-backs they imply) instead.
 __device__ __forceinline__ void shmx_putmem_signal_parts(const shm_dev_ctx &c, int me, uint64_t dst_off, uint64_t src_off,
                                                          size_t n, uint64_t sig_off, uint64_t sig_val, int sig_op, int pe,
                                                          uint64_t *arrive, unsigned part, unsigned nparts)
 {
+#ifdef SHM_SIGNAL_FULL_RELEASE
+    constexpr int arrive_order = __ATOMIC_ACQ_REL, signal_order = __ATOMIC_RELEASE;
+#else
+    constexpr int arrive_order = __ATOMIC_RELAXED, signal_order = __ATOMIC_RELAXED;
+#endif
     __syncthreads();
     shm_copy_parts<8, SHM_ST_THROUGH>(shm_ptr(c, dst_off, pe), shm_ptr(c, src_off, me), n, part, nparts);
-    // Each wave waits for its own write-through stores to be acknowledged, so that after the barrier
-    // every store of the group is performed at agent scope, whatever the leader's fence then covers.
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    __syncthreads();      // every thread's stores happen before the leader's release below
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");     // this wave's payload is performed at agent scope
+    __syncthreads();                                      // ... and so is every other wave's of the group
     if (threadIdx.x == 0) {
         bool last = true;
         if (nparts > 1) {
-            const uint64_t old = __hip_atomic_fetch_add(arrive, 1ull, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_AGENT);
+            const uint64_t old = __hip_atomic_fetch_add(arrive, 1ull, arrive_order, __HIP_MEMORY_SCOPE_AGENT);
             last = (old == nparts - 1);
             if (last) __hip_atomic_store(arrive, 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         }
-        if (last) shm_signal_update(reinterpret_cast<uint64_t *>(shm_ptr(c, sig_off, pe)), sig_val, sig_op);
+        if (last) {
+            uint64_t *sig = reinterpret_cast<uint64_t *>(shm_ptr(c, sig_off, pe));
+            if (sig_op == SHMD_SIGNAL_SET)
+                __hip_atomic_store(sig, sig_val, signal_order, __HIP_MEMORY_SCOPE_AGENT);
+            else
+                __hip_atomic_fetch_add(sig, sig_val, signal_order, __HIP_MEMORY_SCOPE_AGENT);
+        }
     }
 }
 

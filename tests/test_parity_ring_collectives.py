@@ -63,6 +63,14 @@ def test_config3_full_size_lanes():
     _ring_case(8, 64, 524288, 32, 32, 256 * MiB, reps=2, n_sig=32)
 
 
+@pytest.mark.timeout(600)
+@pytest.mark.parametrize("n_prod,n_cons,n_sig", [(16, 16, 16), (4, 16, 1)])
+def test_ring_many_rounds_never_reads_a_stale_slot(n_prod, n_cons, n_sig):
+    """Ten rounds through the same slots with fresh data each time: a signal seen before its payload
+    would leave a previous round's bytes in an accumulator."""
+    _ring_case(8, 32, 131072, n_prod, n_cons, 64 * MiB, reps=10, n_sig=n_sig)
+
+
 def test_ring_rejects_grids_that_cannot_be_resident():
     g, o = make_pair(8, 8 * MiB)
     with g:
