@@ -162,6 +162,31 @@ int shm_launch_wg_put_timed(shm_ctx *ctx, int me, int pe, uint64_t dst_off, uint
                             uint64_t *dev_ticks);
 int shm_wall_clock_khz(const shm_ctx *ctx);
 
+/* ---- device-initiated copy-engine transfers (paper section "Synchronization with Host": the
+ *      reverse-offload ring; section "Performance Evaluation": the cutover taken inside the kernel) */
+
+/* Start / stop the host proxy thread and its ring (64-byte messages in pinned host memory).  While
+ * it runs, kernels can ask the host to start an SDMA transfer.  Start waits for all streams and
+ * resets the ring; stop waits for all streams, then joins the thread.  shm_finalize stops it too.
+ * shm_proxy_stats reports how many requests and how many engine copies the proxy has served since
+ * its start (either pointer may be NULL). */
+int shm_proxy_start(shm_ctx *ctx);
+int shm_proxy_stop(shm_ctx *ctx);
+int shm_proxy_stats(const shm_ctx *ctx, uint64_t *requests, uint64_t *copies);
+
+/* One kernel of n_wg groups (1..1024) on me's stream puts n bytes from me's src_off to pe's dst_off
+ * `reps` times; group g owns the g-th contiguous 256-byte-aligned share.  mode 0: loads/stores and
+ * group quiet; 1: reverse offload to a copy engine, blocking; 2: cutover inside the kernel (share
+ * size >= cutover bytes -> engine, else loads/stores); 3: non-blocking offload followed by an
+ * offload quiet.  Modes 1-3 need the proxy.  dev_ticks as for shm_launch_wg_put_timed. */
+int shm_launch_put_device_initiated(shm_ctx *ctx, int me, int pe, uint64_t dst_off, uint64_t src_off, size_t n, int n_wg, int mode,
+                                    size_t cutover, int reps, uint64_t *dev_ticks);
+
+/* Ring micro-benchmark: the leader wave of each of n_wg groups (1..4096) sends `reps` empty
+ * requests; blocking != 0: it waits for every answer (round trips), else it fires them and waits
+ * once at the end (request rate).  dev_ticks as above. */
+int shm_launch_offload_nop(shm_ctx *ctx, int me, int n_wg, int reps, int blocking, uint64_t *dev_ticks);
+
 /* Put with signal (OpenSHMEM 1.5 semantics, which the paper's feature list adopts): after all n
  * bytes are visible on PE `pe`, its 64-bit word at sig_off (8-byte aligned) is set to sig_val
  * (SET) or increased by it modulo 2^64 (ADD), exactly once however many groups shared the copy.

@@ -13,6 +13,7 @@
 #include "shm_engine.hpp"
 #include "shm_heap.hpp"
 #include "shm_kernels.hpp"
+#include "shm_proxy.hpp"
 
 namespace {
 
@@ -20,6 +21,10 @@ constexpr uint32_t ARRIVE_SLOTS = 4096;                       // 8-byte arrival 
 static_assert(ARRIVE_SLOTS * 8 <= SHM_INTERNAL_BYTES, "arrival counters must fit the internal tail");
 static_assert(SHM_WG_SIZE == SHMK_WG, "one work-group size everywhere");
 constexpr int MAX_N_WG = 1 << 20;
+constexpr uint64_t OFFLOAD_COUNTERS = 32768;                  // offset of the ring's two index words in PE 0's internal tail
+static_assert(ARRIVE_SLOTS * 8 <= OFFLOAD_COUNTERS && OFFLOAD_COUNTERS + 16 <= SHM_INTERNAL_BYTES, "internal tail layout");
+static_assert(SHM_OFFLOAD_SLOTS == SHMD_OFFLOAD_SLOTS && SHM_OFFLOAD_COMPLETIONS == SHMD_OFFLOAD_COMPLETIONS &&
+                  SHM_OFFLOAD_NO_COMPLETION == SHMD_OFFLOAD_NONE, "host and device agree on the ring");
 
 thread_local std::string g_err = "";
 
@@ -55,6 +60,9 @@ struct shm_ctx {
     shm_heap_allocator alloc;
     shm_copy_engines engines;     // SDMA engines through HSA; unused by a no-device context
     std::string engine_err;       // why the engines are unavailable, if they are
+    shm_offload_shared *off_host = nullptr;   // pinned block of the reverse-offload ring
+    shm_offload_shared *off_dev = nullptr;    // the same block at its device-visible address
+    shm_proxy proxy;                          // host thread serving the ring
 };
 
 namespace {
@@ -73,6 +81,13 @@ shm_dev_ctx dev_view(const shm_ctx *c)
     d.status = c->status_dev;
     d.wait_ticks = c->wait_us * c->ticks_per_us;
     d.npes = c->npes;
+    if (c->off_dev && c->proxy.running()) {
+        d.off.ring = &c->off_dev->ring[0][0];
+        d.off.completion = &c->off_dev->completion[0];
+        d.off.consumed = const_cast<const uint64_t *>(&c->off_dev->consumed);
+        d.off.head = reinterpret_cast<unsigned long long *>(c->base + c->user_bytes + OFFLOAD_COUNTERS);
+        d.off.comp_head = d.off.head + 1;
+    }
     return d;
 }
 
@@ -367,6 +382,8 @@ int shm_finalize(shm_ctx *c)
     if (!c->no_device) {
         for (int p = 0; p < c->npes; ++p)
             if (c->stream[p] || !c->own_streams) (void)hipStreamSynchronize(c->stream[p]);
+        c->proxy.stop();
+        if (c->off_host) (void)hipHostFree(c->off_host);
         c->engines.shutdown();
         for (int p = 0; p < c->npes; ++p) {
             if (c->event[p]) (void)hipEventDestroy(c->event[p]);
@@ -561,6 +578,75 @@ int shm_launch_wg_put_timed(shm_ctx *c, int me, int pe, uint64_t dst_off, uint64
     hipLaunchKernelGGL(shmk_wg_put_timed, dim3(n_wg), dim3(SHMK_WG), 0, c->stream[me], dev_view(c), dst_off, src_off, n, me, pe, reps,
                        reinterpret_cast<unsigned long long *>(dev_ticks));
     return launched("timed work-group put");
+}
+
+int shm_proxy_start(shm_ctx *c)
+{
+    if (int r = check_ctx(c)) return r;
+    if (c->no_device) return no_device("shm_proxy_start");
+    if (c->proxy.running()) return SHM_OK;
+    if (!c->engines.ready()) return fail(SHM_EHIP, "copy engines unavailable: %s", c->engine_err.c_str());
+    for (int p = 0; p < c->npes; ++p) HIP_TRY(hipStreamSynchronize(c->stream[p]));
+    if (!c->off_host) {
+        void *h = nullptr, *d = nullptr;
+        HIP_TRY(hipHostMalloc(&h, sizeof(shm_offload_shared), hipHostMallocMapped));
+        c->off_host = static_cast<shm_offload_shared *>(h);
+        HIP_TRY(hipHostGetDevicePointer(&d, h, 0));
+        c->off_dev = static_cast<shm_offload_shared *>(d);
+    }
+    memset(c->off_host, 0, sizeof(shm_offload_shared));
+    HIP_TRY(hipMemset(c->base + c->user_bytes + OFFLOAD_COUNTERS, 0, 16));
+    HIP_TRY(hipDeviceSynchronize());
+    c->proxy.start(c->off_host, c->engines.agent(), c->engines.engine_ids(), c->npes);
+    return SHM_OK;
+}
+
+int shm_proxy_stop(shm_ctx *c)
+{
+    if (int r = check_ctx(c)) return r;
+    if (c->no_device) return no_device("shm_proxy_stop");
+    for (int p = 0; p < c->npes; ++p) HIP_TRY(hipStreamSynchronize(c->stream[p]));
+    c->proxy.stop();
+    return take_status(c);
+}
+
+int shm_proxy_stats(const shm_ctx *c, uint64_t *requests, uint64_t *copies)
+{
+    if (int r = check_ctx(c)) return r;
+    if (requests) *requests = c->proxy.requests();
+    if (copies) *copies = c->proxy.copies();
+    return SHM_OK;
+}
+
+int shm_launch_put_device_initiated(shm_ctx *c, int me, int pe, uint64_t dst_off, uint64_t src_off, size_t n, int n_wg, int mode,
+                                    size_t cutover, int reps, uint64_t *dev_ticks)
+{
+    if (int r = check_ctx(c)) return r;
+    if (int r = rma_args(c, me, pe, dst_off, src_off, n)) return r;
+    if (n_wg < 1 || n_wg > 1024) return fail(SHM_EINVAL, "n_wg outside 1..1024");
+    if (mode < 0 || mode > 3) return fail(SHM_EINVAL, "mode outside 0..3");
+    if (reps < 1 || reps > (1 << 20)) return fail(SHM_EINVAL, "reps outside 1..2^20");
+    if (!dev_ticks) return fail(SHM_EINVAL, "null tick buffer");
+    if (c->no_device) return no_device("shm_launch_put_device_initiated");
+    if (mode != 0 && !c->proxy.running()) return fail(SHM_EINVAL, "the host proxy is not running (shm_proxy_start)");
+    if (int r = drain_engines(c, me)) return r;
+    hipLaunchKernelGGL(shmk_put_device_initiated, dim3(n_wg), dim3(SHMK_WG), 0, c->stream[me], dev_view(c), dst_off, src_off, n, me, pe,
+                       mode, cutover, reps, reinterpret_cast<unsigned long long *>(dev_ticks));
+    return launched("device-initiated put");
+}
+
+int shm_launch_offload_nop(shm_ctx *c, int me, int n_wg, int reps, int blocking, uint64_t *dev_ticks)
+{
+    if (int r = check_ctx(c)) return r;
+    if (int r = check_pe(c, me, "calling PE")) return r;
+    if (n_wg < 1 || n_wg > 4096) return fail(SHM_EINVAL, "n_wg outside 1..4096");
+    if (reps < 1 || reps > (1 << 20)) return fail(SHM_EINVAL, "reps outside 1..2^20");
+    if (!dev_ticks) return fail(SHM_EINVAL, "null tick buffer");
+    if (c->no_device) return no_device("shm_launch_offload_nop");
+    if (!c->proxy.running()) return fail(SHM_EINVAL, "the host proxy is not running (shm_proxy_start)");
+    hipLaunchKernelGGL(shmk_offload_nop, dim3(n_wg), dim3(SHMK_WG), 0, c->stream[me], dev_view(c), me, reps, blocking,
+                       reinterpret_cast<unsigned long long *>(dev_ticks));
+    return launched("offload ring test");
 }
 
 int shm_wall_clock_khz(const shm_ctx *c)

@@ -15,10 +15,20 @@
 // segment and is read with scalar loads).  base[] plays the role of the paper's local-PE table
 // plus heap-offset array (section "Inter-node and Intra-node Communication"): one lookup gives
 // the target heap's base address.
+// Device view of the reverse-offload ring (all null when the host proxy is not running).
+struct shm_offload_dev {
+    uint32_t *ring;                  // pinned host memory: SHM_OFFLOAD_SLOTS messages of 16 words
+    uint32_t *completion;            // pinned host memory: completion words, written by the host
+    const uint64_t *consumed;        // pinned host memory: requests the host has taken (flow control)
+    unsigned long long *head;        // device memory: next request index
+    unsigned long long *comp_head;   // device memory: next completion index
+};
+
 struct shm_dev_ctx {
     char *base[SHM_MAX_PES];
     uint64_t *status;        // host-pinned word; set to 1 when a bounded wait expired
     uint64_t wait_ticks;     // bound for every wait, in wall_clock64() ticks
+    shm_offload_dev off;
     int npes;
 };
 
@@ -472,3 +482,123 @@ __device__ __forceinline__ int64_t shm_atomic_fetch_inc(const shm_dev_ctx &c, ui
     return shm_atomic_fetch_add(c, off, 1, pe);
 }
 __device__ __forceinline__ void shm_atomic_inc(const shm_dev_ctx &c, uint64_t off, int pe) { shm_atomic_add(c, off, 1, pe); }
+
+// ------------------------------------------------------------------------------------------
+// Reverse offload (paper section "Synchronization with Host"): a request to the host proxy is one
+// 64-byte message in a ring in pinned host memory.  The sender takes a slot with one atomic
+// fetch-and-increment, writes the message with one store instruction (four lanes x 16 bytes, every
+// quarter tagged with the slot's generation), and -- if it wants an answer -- polls a completion
+// word that it allocated independently of the slot.  The host's consumed count is only read when
+// the ring could be full.  shm_offload_send must be called by all 64 lanes of one wave.
+// ------------------------------------------------------------------------------------------
+#define SHMD_OFFLOAD_SLOTS 4096u
+#define SHMD_OFFLOAD_COMPLETIONS 65536u
+#define SHMD_OFFLOAD_NONE 0xffffffffu
+enum { SHMD_OFFLOAD_NOP = 0, SHMD_OFFLOAD_COPY = 1, SHMD_OFFLOAD_QUIET = 2 };
+
+__device__ __forceinline__ uint64_t shm_wave_first_u64(uint64_t v)
+{
+    const uint32_t lo = __builtin_amdgcn_readfirstlane(static_cast<uint32_t>(v));
+    const uint32_t hi = __builtin_amdgcn_readfirstlane(static_cast<uint32_t>(v >> 32));
+    return (static_cast<uint64_t>(hi) << 32) | lo;
+}
+
+// Returns the completion ticket, or SHMD_OFFLOAD_NONE if none was asked for.
+__device__ __forceinline__ uint64_t shm_offload_send(const shm_dev_ctx &c, uint32_t op, uint32_t me, uint64_t dst, uint64_t src,
+                                                     uint64_t n, bool want_completion)
+{
+    const unsigned lane = __lane_id();
+    uint64_t idx = 0, ticket = SHMD_OFFLOAD_NONE;
+    if (lane == 0) {
+        idx = __hip_atomic_fetch_add(c.off.head, 1ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if (want_completion) {
+            ticket = __hip_atomic_fetch_add(c.off.comp_head, 1ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            if ((ticket & 0xffffffffull) == SHMD_OFFLOAD_NONE)       // the one value that means "none": take the next
+                ticket = __hip_atomic_fetch_add(c.off.comp_head, 1ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+        // flow control: wait (bounded) only if the ring could be full
+        if (idx >= SHMD_OFFLOAD_SLOTS) {
+            const uint64_t t0 = wall_clock64();
+            while (idx - __hip_atomic_load(c.off.consumed, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM) >= SHMD_OFFLOAD_SLOTS) {
+                if (wall_clock64() - t0 > c.wait_ticks) {
+                    __hip_atomic_store(c.status, 1ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+                    break;
+                }
+                __builtin_amdgcn_s_sleep(8);
+            }
+        }
+    }
+    idx = shm_wave_first_u64(idx);
+    ticket = shm_wave_first_u64(ticket);
+    const uint32_t tag = static_cast<uint32_t>(idx / SHMD_OFFLOAD_SLOTS) + 1u;
+    if (lane < 4) {
+        shm_u32x4 q;
+        q.w = tag;
+        q.z = 0;
+        if (lane == 0) {
+            q.x = op, q.y = me, q.z = static_cast<uint32_t>(ticket);
+        } else {
+            const uint64_t v = lane == 1 ? dst : lane == 2 ? src : n;
+            q.x = static_cast<uint32_t>(v), q.y = static_cast<uint32_t>(v >> 32);
+        }
+        shm_u32x4 *slot = reinterpret_cast<shm_u32x4 *>(c.off.ring + (idx & (SHMD_OFFLOAD_SLOTS - 1)) * 16) + lane;
+        asm volatile("global_store_dwordx4 %0, %1, off sc0 sc1" ::"v"(slot), "v"(q) : "memory");   // system scope: straight to host memory
+    }
+    return ticket;
+}
+
+// Lane 0 of the calling wave polls the completion word of `ticket` (bounded).
+__device__ __forceinline__ void shm_offload_wait(const shm_dev_ctx &c, uint64_t ticket)
+{
+    if (__lane_id() != 0 || (ticket & 0xffffffffull) == SHMD_OFFLOAD_NONE) return;
+    const uint32_t t32 = static_cast<uint32_t>(ticket);
+    const uint32_t *word = c.off.completion + (t32 & (SHMD_OFFLOAD_COMPLETIONS - 1));
+    const uint32_t want = t32 / SHMD_OFFLOAD_COMPLETIONS + 1u;
+    const uint64_t t0 = wall_clock64();
+    while (__hip_atomic_load(word, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM) != want) {
+        if (wall_clock64() - t0 > c.wait_ticks) {
+            __hip_atomic_store(c.status, 1ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+            break;
+        }
+        __builtin_amdgcn_s_sleep(1);
+    }
+}
+
+// Work-group put through the host-started copy engine (the paper's leader pattern: group barrier so
+// that the source is complete, one wave talks to the host, group barrier).  Blocking: returns when
+// the bytes are delivered.  The non-blocking form returns at once; shmx_quiet_offload_wg completes
+// everything this PE has offloaded.
+__device__ __forceinline__ void shmx_putmem_offload_wg(const shm_dev_ctx &c, int me, uint64_t dst_off, uint64_t src_off, size_t n,
+                                                       int pe, bool blocking)
+{
+    __syncthreads();
+    if (threadIdx.x < 64 && n != 0) {
+        if (threadIdx.x == 0) __builtin_amdgcn_fence(__ATOMIC_RELEASE, "");      // the engine reads memory, not our caches
+        const uint64_t ticket = shm_offload_send(c, SHMD_OFFLOAD_COPY, me, reinterpret_cast<uint64_t>(shm_ptr(c, dst_off, pe)),
+                                                 reinterpret_cast<uint64_t>(shm_ptr(c, src_off, me)), n, blocking);
+        if (blocking) shm_offload_wait(c, ticket);
+    }
+    __syncthreads();
+}
+
+__device__ __forceinline__ void shmx_quiet_offload_wg(const shm_dev_ctx &c, int me)
+{
+    __syncthreads();
+    if (threadIdx.x < 64) {
+        const uint64_t ticket = shm_offload_send(c, SHMD_OFFLOAD_QUIET, me, 0, 0, 0, true);
+        shm_offload_wait(c, ticket);
+        if (threadIdx.x == 0) __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "");
+    }
+    __syncthreads();
+}
+
+// The cutover inside the kernel (paper section "Performance Evaluation"): loads/stores below
+// `cutover` bytes, the host-started copy engine from there on.
+__device__ __forceinline__ void shmx_putmem_auto_wg(const shm_dev_ctx &c, int me, uint64_t dst_off, uint64_t src_off, size_t n, int pe,
+                                                    size_t cutover)
+{
+    if (c.off.ring != nullptr && n >= cutover)
+        shmx_putmem_offload_wg(c, me, dst_off, src_off, n, pe, true);
+    else
+        shmx_putmem_wg(c, me, dst_off, src_off, n, pe);
+}

@@ -57,6 +57,8 @@ public:
 
     bool ready() const { return ready_; }
     size_t n_engines() const { return engines_.size(); }
+    hsa_agent_t agent() const { return agent_; }
+    const std::vector<uint32_t> &engine_ids() const { return engines_; }
 
     // Start copying n bytes on behalf of PE `pe` of `npes`.  Large transfers are split over the
     // engines that PE's share of the engine set allows.

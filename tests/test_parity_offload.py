@@ -1,0 +1,89 @@
+"""GPU parity: device-initiated copy-engine transfers through the reverse-offload ring."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2409_20476_amd import shm as S
+from parity_util import assert_heaps_equal, fill_random, make_pair
+
+pytestmark = pytest.mark.gpu
+
+MiB = 1 << 20
+MASK = (1 << 64) - 1
+
+
+def _ticks():
+    t = torch.zeros(2, dtype=torch.int64, device="cuda")
+    t[0] = -1
+    torch.cuda.synchronize()
+    return t
+
+
+def _elapsed_us(g, t):
+    t0, t1 = (int(v) & MASK for v in t.tolist())
+    return (t1 - t0) / g.wall_clock_khz() * 1e3
+
+
+@pytest.mark.parametrize("mode", [0, 1, 2, 3])
+def test_device_initiated_put_matches_oracle(mode):
+    g, o = make_pair(3, 16 * MiB)
+    with g:
+        fill_random(g, o, 31, upto=12 * MiB)
+        g.proxy_start()
+        cases = [(100003, 1, 17, 5), (MiB + 256, 4, 0, 0), (4096, 1, 3, 3), (3 * MiB + 1000, 16, 256, 512), (0, 2, 0, 0), (700, 8, 1, 2)]
+        copies_before = g.proxy_stats()[1]
+        for i, (n, n_wg, sa, da) in enumerate(cases):
+            me, pe = i % 3, (i + 1) % 3
+            src, dst = 1024 + sa, 6 * MiB + da
+            t = _ticks()
+            g.launch_put_device_initiated(me, pe, dst, src, n, n_wg, mode, 65536, 2, t)
+            g.quiet(me)
+            o.wg_put(me, dst, src, n, pe, n_wg)
+            assert_heaps_equal(g, o, upto=12 * MiB, what=f"mode {mode} case {i}")
+            assert 0 < _elapsed_us(g, t) < 1e6
+        requests, copies = g.proxy_stats()
+        if mode == 0:
+            assert copies == copies_before
+        if mode in (1, 3):
+            assert copies - copies_before >= 2 * (1 + 4 + 1 + 16 + 1)      # every non-empty share, twice
+        g.proxy_stop()
+
+
+def test_ring_round_trips_rate_and_wraparound():
+    g, o = make_pair(2, MiB)
+    with g:
+        g.proxy_start()
+        t = _ticks()
+        g.launch_offload_nop(0, 1, 200, True, t)                 # 200 round trips by one wave
+        g.quiet(0)
+        rtt = _elapsed_us(g, t) / 200
+        assert 0.5 < rtt < 500, rtt
+        req0 = g.proxy_stats()[0]
+        assert req0 == 200
+        t = _ticks()
+        g.launch_offload_nop(1, 64, 300, False, t)               # 19264 requests: the 4096-slot ring wraps four times
+        g.quiet(1)
+        assert g.proxy_stats()[0] - req0 == 64 * 301
+        rate = 64 * 301 / _elapsed_us(g, t)
+        assert rate > 0.05, f"{rate} M requests/s"
+        g.proxy_stop()
+        # stop / start: the ring restarts from zero
+        g.proxy_start()
+        t = _ticks()
+        g.launch_offload_nop(0, 4, 10, True, t)
+        g.quiet(0)
+        assert g.proxy_stats()[0] == 40
+        g.proxy_stop()
+
+
+def test_offload_needs_the_proxy():
+    g, o = make_pair(2, MiB)
+    with g:
+        t = _ticks()
+        with pytest.raises(S.ShmError) as e:
+            g.launch_put_device_initiated(0, 1, 65536, 0, 4096, 1, 1, 0, 1, t)
+        assert e.value.code == S.SHM_EINVAL
+        with pytest.raises(S.ShmError):
+            g.launch_offload_nop(0, 1, 1, True, t)
+        g.launch_put_device_initiated(0, 1, 65536, 0, 4096, 1, 0, 0, 1, t)     # loads/stores need no proxy
+        g.quiet(0)
