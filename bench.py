@@ -235,6 +235,62 @@ def put_sweep(torch, S, g, args):
                               "null = loads/stores win at every measured size"}
 
 
+def reverse_offload(torch, S, args):
+    """The paper's reverse-offload ring and its cutover experiment: round trip and request rate of the
+    ring, and one work-group (64 / 256 / 1024 work-items) putting 8 B .. 128 MiB from inside a kernel,
+    once with loads/stores and once by asking the host proxy for a copy engine."""
+    g = S.Shm.on_torch(2, 512 * MiB)
+    g.proxy_start()
+    khz = g.wall_clock_khz()
+    t = torch.zeros(2, dtype=torch.int64, device="cuda")
+
+    def timed(launch):
+        t[0], t[1] = -1, 0
+        torch.cuda.synchronize()
+        launch()
+        g.quiet(0)
+        a, b = (int(v) & ((1 << 64) - 1) for v in t.tolist())
+        return (b - a) / khz * 1e3
+
+    out = {"round_trip_us": {}, "request_rate_mreq_s": {}}
+    for n_wg in (1, 8, 64):
+        out["round_trip_us"][str(n_wg)] = min(timed(lambda: g.launch_offload_nop(0, n_wg, 500, True, t)) for _ in range(3)) / 500
+    for n_wg in (1, 8, 64, 256):
+        out["request_rate_mreq_s"][str(n_wg)] = max(n_wg * 2001 / timed(lambda: g.launch_offload_nop(0, n_wg, 2000, False, t))
+                                                    for _ in range(3))
+    src, dst = g.malloc(128 * MiB), g.malloc(128 * MiB)
+    rows = []
+    for k in range(3, 28):
+        n = 1 << k
+        row = {"bytes": n}
+        reps = 4 if n >= 8 * MiB else 20
+        for wg in (64, 256, 1024):
+            row[f"ldst_wi{wg}_us"] = min(timed(lambda: g.launch_put_device_initiated(0, 1, dst, src, n, 1, 0, 0, reps, t, wg))
+                                         for _ in range(3)) / reps
+        row["engine_us"] = min(timed(lambda: g.launch_put_device_initiated(0, 1, dst, src, n, 1, 1, 0, reps, t, 256))
+                               for _ in range(3)) / reps
+        rows.append(row)
+    cross = {}
+    for wg in (64, 256, 1024):
+        cross[str(wg)] = next((r["bytes"] for i, r in enumerate(rows)
+                               if all(q["engine_us"] <= q[f"ldst_wi{wg}_us"] for q in rows[i:])), None)
+    # the cutover taken inside the kernel, with the threshold just measured for 256 work-items
+    cut = cross["256"] or (1 << 62)
+    for row in rows:
+        n = row["bytes"]
+        reps = 4 if n >= 8 * MiB else 20
+        row["auto_wi256_us"] = min(timed(lambda: g.launch_put_device_initiated(0, 1, dst, src, n, 1, 2, cut, reps, t, 256))
+                                   for _ in range(3)) / reps
+    requests, copies = g.proxy_stats()
+    g.proxy_stop()
+    g.finalize()
+    out.update({"single_group_put": rows, "cutover_bytes_by_work_items": cross, "proxy_requests": requests, "proxy_copies": copies,
+                "note": "device clock inside the kernel, per put including completion (loads/stores: group quiet; engine: the "
+                        "host's completion message); round trips: one wave per group waiting for each answer; rate: "
+                        "fire-and-forget, one host thread"})
+    return out
+
+
 def pingflag(torch, S, synth, args):
     g = S.Shm.on_torch(2, MiB)
     payload = synth.c1_payload(4096)
@@ -418,6 +474,9 @@ def main():
         log(f"[bench] c1: {extras['config1_pingflag']}")
         extras["config2_put_sweep"] = put_sweep(torch, S, g, args)
         log(f"[bench] crossover: {extras['config2_put_sweep']['crossover_bytes']}")
+        extras["reverse_offload"] = reverse_offload(torch, S, args)
+        log(f"[bench] reverse offload: rtt {extras['reverse_offload']['round_trip_us']} rate {extras['reverse_offload']['request_rate_mreq_s']} "
+            f"cutover {extras['reverse_offload']['cutover_bytes_by_work_items']}")
         extras["config3_ring"] = ring(torch, S, synth, g, args)
         log(f"[bench] c3: {extras['config3_ring']}")
         extras["config4_amo_storm"] = storm(torch, S, synth, args)

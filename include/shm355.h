@@ -174,13 +174,14 @@ int shm_proxy_start(shm_ctx *ctx);
 int shm_proxy_stop(shm_ctx *ctx);
 int shm_proxy_stats(const shm_ctx *ctx, uint64_t *requests, uint64_t *copies);
 
-/* One kernel of n_wg groups (1..1024) on me's stream puts n bytes from me's src_off to pe's dst_off
- * `reps` times; group g owns the g-th contiguous 256-byte-aligned share.  mode 0: loads/stores and
+/* One kernel of n_wg groups (1..1024) of wg_size threads (a multiple of 64, 64..1024: the paper
+ * varies the work-items per work-group) on me's stream puts n bytes from me's src_off to pe's
+ * dst_off `reps` times; group g owns the g-th contiguous 256-byte-aligned share.  mode 0: loads/stores and
  * group quiet; 1: reverse offload to a copy engine, blocking; 2: cutover inside the kernel (share
  * size >= cutover bytes -> engine, else loads/stores); 3: non-blocking offload followed by an
  * offload quiet.  Modes 1-3 need the proxy.  dev_ticks as for shm_launch_wg_put_timed. */
-int shm_launch_put_device_initiated(shm_ctx *ctx, int me, int pe, uint64_t dst_off, uint64_t src_off, size_t n, int n_wg, int mode,
-                                    size_t cutover, int reps, uint64_t *dev_ticks);
+int shm_launch_put_device_initiated(shm_ctx *ctx, int me, int pe, uint64_t dst_off, uint64_t src_off, size_t n, int n_wg, int wg_size,
+                                    int mode, size_t cutover, int reps, uint64_t *dev_ticks);
 
 /* Ring micro-benchmark: the leader wave of each of n_wg groups (1..4096) sends `reps` empty
  * requests; blocking != 0: it waits for every answer (round trips), else it fires them and waits

@@ -618,19 +618,20 @@ int shm_proxy_stats(const shm_ctx *c, uint64_t *requests, uint64_t *copies)
     return SHM_OK;
 }
 
-int shm_launch_put_device_initiated(shm_ctx *c, int me, int pe, uint64_t dst_off, uint64_t src_off, size_t n, int n_wg, int mode,
-                                    size_t cutover, int reps, uint64_t *dev_ticks)
+int shm_launch_put_device_initiated(shm_ctx *c, int me, int pe, uint64_t dst_off, uint64_t src_off, size_t n, int n_wg, int wg_size,
+                                    int mode, size_t cutover, int reps, uint64_t *dev_ticks)
 {
     if (int r = check_ctx(c)) return r;
     if (int r = rma_args(c, me, pe, dst_off, src_off, n)) return r;
     if (n_wg < 1 || n_wg > 1024) return fail(SHM_EINVAL, "n_wg outside 1..1024");
+    if (wg_size < 64 || wg_size > 1024 || wg_size % 64) return fail(SHM_EINVAL, "wg_size must be a multiple of 64 in 64..1024");
     if (mode < 0 || mode > 3) return fail(SHM_EINVAL, "mode outside 0..3");
     if (reps < 1 || reps > (1 << 20)) return fail(SHM_EINVAL, "reps outside 1..2^20");
     if (!dev_ticks) return fail(SHM_EINVAL, "null tick buffer");
     if (c->no_device) return no_device("shm_launch_put_device_initiated");
     if (mode != 0 && !c->proxy.running()) return fail(SHM_EINVAL, "the host proxy is not running (shm_proxy_start)");
     if (int r = drain_engines(c, me)) return r;
-    hipLaunchKernelGGL(shmk_put_device_initiated, dim3(n_wg), dim3(SHMK_WG), 0, c->stream[me], dev_view(c), dst_off, src_off, n, me, pe,
+    hipLaunchKernelGGL(shmk_put_device_initiated, dim3(n_wg), dim3(wg_size), 0, c->stream[me], dev_view(c), dst_off, src_off, n, me, pe,
                        mode, cutover, reps, reinterpret_cast<unsigned long long *>(dev_ticks));
     return launched("device-initiated put");
 }

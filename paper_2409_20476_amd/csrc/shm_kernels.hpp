@@ -42,10 +42,10 @@ __global__ __launch_bounds__(SHMK_WG) void shmk_wg_put_timed(shm_dev_ctx c, uint
     }
 }
 
-// Device-initiated put, `reps` times, by gridDim.x groups that each own a contiguous 256-byte-
-// aligned share of the message.  mode 0: loads/stores + group quiet; 1: host-started copy engine,
+// Device-initiated put, `reps` times, by gridDim.x groups (of 64..1024 threads: the paper varies the
+// work-items per work-group) that each own a contiguous 256-byte-aligned share of the message.  mode 0: loads/stores + group quiet; 1: host-started copy engine,
 // blocking; 2: cutover on the share size; 3: non-blocking engine put, offload quiet after each.
-__global__ __launch_bounds__(SHMK_WG) void shmk_put_device_initiated(shm_dev_ctx c, uint64_t dst_off, uint64_t src_off, size_t n, int me,
+__global__ __launch_bounds__(1024) void shmk_put_device_initiated(shm_dev_ctx c, uint64_t dst_off, uint64_t src_off, size_t n, int me,
                                                                      int pe, int mode, size_t cutover, int reps, unsigned long long *ticks)
 {
     size_t per = (n + gridDim.x - 1) / gridDim.x;

@@ -65,7 +65,7 @@ PROTOTYPES = {
     "shm_proxy_start": (c_int, [c_void_p]),
     "shm_proxy_stop": (c_int, [c_void_p]),
     "shm_proxy_stats": (c_int, [c_void_p, _u64p, _u64p]),
-    "shm_launch_put_device_initiated": (c_int, [c_void_p, c_int, c_int, c_uint64, c_uint64, c_size_t, c_int, c_int, c_size_t, c_int, c_void_p]),
+    "shm_launch_put_device_initiated": (c_int, [c_void_p, c_int, c_int, c_uint64, c_uint64, c_size_t, c_int, c_int, c_int, c_size_t, c_int, c_void_p]),
     "shm_launch_offload_nop": (c_int, [c_void_p, c_int, c_int, c_int, c_int, c_void_p]),
     "shm_launch_wg_put_signal": (c_int, [c_void_p, c_int, c_int, c_uint64, c_uint64, c_size_t, c_uint64, c_uint64, c_int, c_int]),
     "shm_launch_signal_wait_until": (c_int, [c_void_p, c_int, c_uint64, c_int, c_uint64, c_void_p]),
@@ -251,9 +251,9 @@ class Shm:
         self._check(self.lib.shm_proxy_stats(self.ctx, byref(r), byref(c)))
         return r.value, c.value
 
-    def launch_put_device_initiated(self, me, pe, dst_off, src_off, n, n_wg, mode, cutover, reps, dev_ticks):
-        self._check(self.lib.shm_launch_put_device_initiated(self.ctx, me, pe, dst_off, src_off, n, n_wg, mode, cutover, reps,
-                                                             _ptr(dev_ticks)))
+    def launch_put_device_initiated(self, me, pe, dst_off, src_off, n, n_wg, mode, cutover, reps, dev_ticks, wg_size=256):
+        self._check(self.lib.shm_launch_put_device_initiated(self.ctx, me, pe, dst_off, src_off, n, n_wg, wg_size, mode, cutover,
+                                                             reps, _ptr(dev_ticks)))
 
     def launch_offload_nop(self, me, n_wg, reps, blocking, dev_ticks):
         self._check(self.lib.shm_launch_offload_nop(self.ctx, me, n_wg, reps, int(blocking), _ptr(dev_ticks)))

@@ -36,7 +36,7 @@ def test_device_initiated_put_matches_oracle(mode):
             me, pe = i % 3, (i + 1) % 3
             src, dst = 1024 + sa, 6 * MiB + da
             t = _ticks()
-            g.launch_put_device_initiated(me, pe, dst, src, n, n_wg, mode, 65536, 2, t)
+            g.launch_put_device_initiated(me, pe, dst, src, n, n_wg, mode, 65536, 2, t, wg_size=(64, 256, 1024)[i % 3])
             g.quiet(me)
             o.wg_put(me, dst, src, n, pe, n_wg)
             assert_heaps_equal(g, o, upto=12 * MiB, what=f"mode {mode} case {i}")
