@@ -326,6 +326,7 @@ def ring(torch, S, synth, g, args):
         g.write(p, src, synth.c3_chunks(p, n_chunks, nel))
     zero = np.zeros(8 * 64, np.uint8)
     out = {}
+    g.set_team_sync(False)      # all PE streams are idle here; time the grid, not the stream join/fork events
     for n_prod, n_cons, n_sig in ((8, 32, 1), (16, 32, 1), (32, 32, 32), (64, 64, 64)):
         best = float("inf")
         for i in range(12):
@@ -342,6 +343,7 @@ def ring(torch, S, synth, g, args):
         algo = npes * (n_chunks * 3 * cb + 4 * nel)
         out[f"prod{n_prod}_cons{n_cons}_sig{n_sig}"] = {"ms": best, "payload_gbs": npes * n_chunks * cb / best / 1e6,
                                            "algorithmic_gbs": algo / best / 1e6, "frac_hbm": algo / best / 1e6 / HBM_PEAK_GBS}
+    g.set_team_sync(True)
     for off in (src, slot, acc, sig):
         g.free(off)
     return out
@@ -354,6 +356,7 @@ def storm(torch, S, synth, args):
     targets = torch.from_numpy(synth.c4_targets(n_items, ops, npes, n_ctr).view(np.int16)).cuda()
     checksum = torch.zeros(n_items // 256, dtype=torch.int64, device="cuda")
     out = {}
+    g.set_team_sync(False)
     for name, kind in (("fetch_add", S.SHM_STORM_FETCH_ADD), ("add_no_return", S.SHM_STORM_ADD),
                        ("plain_store_ceiling", S.SHM_STORM_PLAIN_STORE)):
         best = float("inf")
@@ -380,6 +383,7 @@ def collectives(torch, S, synth, g, args):
         g.write(p, fsrc, synth.c5_fcollect_source(p, nel))
         g.write(p, rsrc, synth.c5_reduce_source(p, nel))
     out = {}
+    g.set_team_sync(False)      # streams are idle; the MEMCPY and SDMA forms below order themselves with barrier_all
 
     def best_of(fn, stream_timed=True):
         best = float("inf")
@@ -399,18 +403,18 @@ def collectives(torch, S, synth, g, args):
         ms = best_of(lambda: g.launch_fcollect(fdst, fsrc, 4 * nel, n_wg, S.SHM_PATH_LDST))
         out[f"fcollect_ldst_wg{n_wg}"] = {"ms": ms, "algorithmic_gbs": fc_bytes / ms / 1e6, "frac_hbm": fc_bytes / ms / 1e6 / HBM_PEAK_GBS}
     sd_bytes = 2 * npes * npes * 4 * nel
-    ms = best_of(lambda: g.launch_fcollect(fdst, fsrc, 4 * nel, 1024, S.SHM_PATH_MEMCPY))
-    out["fcollect_memcpy"] = {"ms": ms, "traffic_gbs": sd_bytes / ms / 1e6,
-                              "note": "64 runtime copies of 64 MiB: 8 GiB of traffic for the same result"}
-    best = float("inf")
-    for i in range(4):
-        g.barrier_all()
-        t0 = time.perf_counter()
-        g.launch_fcollect(fdst, fsrc, 4 * nel, 1024, S.SHM_PATH_SDMA)
-        g.barrier_all()
-        if i >= 1:
-            best = min(best, (time.perf_counter() - t0) * 1e3)
-    out["fcollect_sdma"] = {"ms": best, "traffic_gbs": sd_bytes / best / 1e6, "note": "64 SDMA engine copies of 64 MiB, host clock"}
+    for key, path, note in (("fcollect_memcpy", S.SHM_PATH_MEMCPY, "64 runtime copies of 64 MiB on the 8 PE streams, host clock: "
+                                                                   "8 GiB of traffic for the same result"),
+                            ("fcollect_sdma", S.SHM_PATH_SDMA, "64 SDMA engine copies of 64 MiB, host clock")):
+        best = float("inf")
+        for i in range(4):
+            g.barrier_all()
+            t0 = time.perf_counter()
+            g.launch_fcollect(fdst, fsrc, 4 * nel, 1024, path)
+            g.barrier_all()
+            if i >= 1:
+                best = min(best, (time.perf_counter() - t0) * 1e3)
+        out[key] = {"ms": best, "traffic_gbs": sd_bytes / best / 1e6, "note": note}
     dup_bytes = npes * npes * 4 * nel + npes * 4 * nel
     spl_bytes = npes * 4 * nel + npes * 4 * nel
     for n_wg in (256, 1024):
@@ -418,6 +422,7 @@ def collectives(torch, S, synth, g, args):
         out[f"reduce_duplicate_wg{n_wg}"] = {"ms": ms, "algorithmic_gbs": dup_bytes / ms / 1e6, "frac_hbm": dup_bytes / ms / 1e6 / HBM_PEAK_GBS}
         ms = best_of(lambda: g.launch_reduce_sum_f32(rdst, rsrc, nel, n_wg, S.SHM_REDUCE_SPLIT))
         out[f"reduce_split_wg{n_wg}"] = {"ms": ms, "algorithmic_gbs": spl_bytes / ms / 1e6, "frac_hbm": spl_bytes / ms / 1e6 / HBM_PEAK_GBS}
+    g.set_team_sync(True)
     for off in (fsrc, fdst, rsrc, rdst):
         g.free(off)
     return out

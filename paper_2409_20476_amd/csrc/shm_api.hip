@@ -21,6 +21,13 @@ constexpr uint32_t ARRIVE_SLOTS = 4096;                       // 8-byte arrival 
 static_assert(ARRIVE_SLOTS * 8 <= SHM_INTERNAL_BYTES, "arrival counters must fit the internal tail");
 static_assert(SHM_WG_SIZE == SHMK_WG, "one work-group size everywhere");
 constexpr int MAX_N_WG = 1 << 20;
+// Group-owned tiles pay off for long messages moved by enough groups (measured on MI355X, 8 PEs:
+// from 8 MiB with 64 groups per PE, from 64 MiB with 1024; with 4 groups the 8-group virtual blocks
+// stay ahead at every size).
+constexpr size_t TILES_MIN_BYTES = 8u << 20;
+constexpr size_t TILES_MIN_BYTES_PER_GROUP = 64u << 10;
+constexpr int TILES_MIN_GROUPS = 32;
+constexpr unsigned TILES_LDS_BYTES = 54000;                   // unused LDS that caps a CU at 3 resident groups
 constexpr uint64_t OFFLOAD_COUNTERS = 32768;                  // offset of the ring's two index words in PE 0's internal tail
 static_assert(ARRIVE_SLOTS * 8 <= OFFLOAD_COUNTERS && OFFLOAD_COUNTERS + 16 <= SHM_INTERNAL_BYTES, "internal tail layout");
 static_assert(SHM_OFFLOAD_SLOTS == SHMD_OFFLOAD_SLOTS && SHM_OFFLOAD_COMPLETIONS == SHMD_OFFLOAD_COMPLETIONS &&
@@ -227,6 +234,13 @@ int sdma_copy(shm_ctx *c, int on_pe, int dst_pe, uint64_t dst_off, int src_pe, u
     return SHM_OK;
 }
 
+// Long, 16-byte-aligned messages take the group-owned-tile kernel.
+bool use_tiles(uint64_t dst_off, uint64_t src_off, size_t n, int n_wg)
+{
+    return ((dst_off | src_off) & 15) == 0 && n_wg >= TILES_MIN_GROUPS && n >= TILES_MIN_BYTES &&
+           n / static_cast<size_t>(n_wg) >= TILES_MIN_BYTES_PER_GROUP;
+}
+
 int transfer_copy(shm_ctx *c, int path, int on_pe, int dst_pe, uint64_t dst_off, int src_pe, uint64_t src_off, size_t n)
 {
     return path == SHM_PATH_SDMA ? sdma_copy(c, on_pe, dst_pe, dst_off, src_pe, src_off, n)
@@ -245,6 +259,11 @@ int wg_rma(shm_ctx *c, int me, int pe, uint64_t dst_off, uint64_t src_off, size_
         return is_get ? transfer_copy(c, use, me, me, dst_off, pe, src_off, n) : transfer_copy(c, use, me, pe, dst_off, me, src_off, n);
     if (int r = drain_engines(c, me)) return r;
     const int shift = (pe - me + c->npes) % c->npes;
+    if (use_tiles(dst_off, src_off, n, n_wg)) {
+        hipLaunchKernelGGL(shmk_wg_rma_tiles, dim3(n_wg, 1), dim3(SHMK_WG), TILES_LDS_BYTES, c->stream[me], dev_view(c), dst_off, src_off,
+                           n, me, shift, is_get);
+        return launched("work-group put/get (tiles)");
+    }
     hipLaunchKernelGGL(shmk_wg_rma, dim3(n_wg, 1), dim3(SHMK_WG), 0, c->stream[me], dev_view(c), dst_off, src_off, n, me, shift,
                        is_get);
     return launched("work-group put/get");
@@ -278,8 +297,13 @@ int wg_rma_all(shm_ctx *c, int pe_shift, uint64_t dst_off, uint64_t src_off, siz
     }
     if (c->team_sync)
         if (int r = team_join(c)) return r;
-    hipLaunchKernelGGL(shmk_wg_rma, dim3(n_wg, c->npes), dim3(SHMK_WG), 0, c->stream[0], dev_view(c), dst_off, src_off, n, 0,
-                       pe_shift, is_get);
+    if (use_tiles(dst_off, src_off, n, n_wg)) {
+        hipLaunchKernelGGL(shmk_wg_rma_tiles, dim3(n_wg, c->npes), dim3(SHMK_WG), TILES_LDS_BYTES, c->stream[0], dev_view(c), dst_off,
+                           src_off, n, 0, pe_shift, is_get);
+    } else {
+        hipLaunchKernelGGL(shmk_wg_rma, dim3(n_wg, c->npes), dim3(SHMK_WG), 0, c->stream[0], dev_view(c), dst_off, src_off, n, 0,
+                           pe_shift, is_get);
+    }
     if (int r = launched("team put/get")) return r;
     if (c->team_sync)
         if (int r = team_fork(c)) return r;

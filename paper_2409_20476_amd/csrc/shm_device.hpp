@@ -257,6 +257,69 @@ __device__ __forceinline__ void shm_copy_parts(char *dst, const char *src, size_
 }
 
 // ------------------------------------------------------------------------------------------
+// Group-owned tiles: the dealing used for long messages.  A tile is U rows of 32 KiB (64 KiB for
+// U = 2) and ONE group owns a whole tile: wave w walks columns 8w..8w+7 (for 4 waves), its U
+// accesses per column again 32 KiB apart, each column's U loads followed at once by its U stores;
+// group `part` takes tiles part, part + nparts, ...  Launched with enough (unused) LDS to hold a CU
+// to three resident groups, this is what sustains the highest HBM copy rate measured on MI355X
+// (82 % of peak at 256 MiB x 8 PEs, against 76 % for the 8-group virtual blocks above): few
+// resident groups, each streaming long runs, started by the dispatcher in address order.
+// dst and src are 16-byte aligned, n is a multiple of 16.
+// ------------------------------------------------------------------------------------------
+template <int U, int NWAVES>
+__device__ __forceinline__ void shm_copy_tiles_impl(char *dst, const char *src, size_t n, unsigned part, unsigned nparts)
+{
+    const shm_u32x4 *s = reinterpret_cast<const shm_u32x4 *>(src);
+    shm_u32x4 *d = reinterpret_cast<shm_u32x4 *>(dst);
+    const size_t nvec = n >> 4;
+    constexpr size_t rowv = 2048;                        // 32 KiB
+    constexpr size_t tilev = rowv * U;
+    const size_t ntiles = (nvec + tilev - 1) / tilev;
+    const unsigned wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    constexpr unsigned cols_per_wave = 32 / NWAVES;      // compile-time trip count: the column loop unrolls
+    for (size_t t = part; t < ntiles; t += nparts) {
+        const size_t base = t * tilev;
+        if (base + tilev <= nvec) {
+            // Column by column: U loads, then their U stores, then the next column.  Keeping reads and
+            // writes interleaved this finely is worth ten points of HBM bandwidth over issuing all of
+            // a tile's loads first (measured: 82 % against 70 %).
+#pragma unroll
+            for (unsigned cc = 0; cc < cols_per_wave; ++cc) {
+                const size_t i = base + static_cast<size_t>(wave * cols_per_wave + cc) * 64 + lane;
+                shm_u32x4 r[U];
+#pragma unroll
+                for (int u = 0; u < U; ++u) r[u] = shm_ld16(s + i + u * rowv);
+#pragma unroll
+                for (int u = 0; u < U; ++u) shm_st16(d + i + u * rowv, r[u]);
+            }
+        } else {                                          // the last, partial tile
+            for (unsigned cc = 0; cc < cols_per_wave; ++cc) {
+                const size_t i = base + static_cast<size_t>(wave * cols_per_wave + cc) * 64 + lane;
+                shm_u32x4 r[U];
+#pragma unroll
+                for (int u = 0; u < U; ++u)
+                    if (i + u * rowv < nvec) r[u] = shm_ld16(s + i + u * rowv);
+#pragma unroll
+                for (int u = 0; u < U; ++u)
+                    if (i + u * rowv < nvec) shm_st16(d + i + u * rowv, r[u]);
+            }
+        }
+    }
+}
+
+template <int U = 2>
+__device__ __forceinline__ void shm_copy_tiles(char *dst, const char *src, size_t n, unsigned part, unsigned nparts)
+{
+    switch (blockDim.x >> 6) {       // groups are 64, 128, 256, 512 or 1024 threads
+    case 1: shm_copy_tiles_impl<U, 1>(dst, src, n, part, nparts); break;
+    case 2: shm_copy_tiles_impl<U, 2>(dst, src, n, part, nparts); break;
+    case 4: shm_copy_tiles_impl<U, 4>(dst, src, n, part, nparts); break;
+    case 8: shm_copy_tiles_impl<U, 8>(dst, src, n, part, nparts); break;
+    default: shm_copy_tiles_impl<U, 16>(dst, src, n, part, nparts); break;
+    }
+}
+
+// ------------------------------------------------------------------------------------------
 // RMA.  A put returns when the source may be reused; its bytes are delivered (visible to other
 // PEs) after the caller's quiet.  A get returns with the bytes in place for the calling thread(s).
 // ------------------------------------------------------------------------------------------
@@ -310,6 +373,31 @@ __device__ __forceinline__ void shmx_getmem_parts(const shm_dev_ctx &c, int me, 
 {
     __syncthreads();
     shm_copy_parts<8>(shm_ptr(c, dst_off, me), shm_ptr(c, src_off, pe), n, part, nparts);
+    __syncthreads();
+}
+
+// The same with group-owned tiles (see shm_copy_tiles): for long messages.  Offsets 16-byte aligned;
+// the last n mod 16 bytes are copied by group 0.
+__device__ __forceinline__ void shmx_putmem_tiles(const shm_dev_ctx &c, int me, uint64_t dst_off, uint64_t src_off, size_t n, int pe,
+                                                  unsigned part, unsigned nparts)
+{
+    __syncthreads();
+    char *d = shm_ptr(c, dst_off, pe);
+    const char *s = shm_ptr(c, src_off, me);
+    const size_t body = n & ~static_cast<size_t>(15);
+    shm_copy_tiles<2>(d, s, body, part, nparts);
+    if (part == 0 && threadIdx.x < n - body) d[body + threadIdx.x] = s[body + threadIdx.x];
+    __syncthreads();
+}
+__device__ __forceinline__ void shmx_getmem_tiles(const shm_dev_ctx &c, int me, uint64_t dst_off, uint64_t src_off, size_t n, int pe,
+                                                  unsigned part, unsigned nparts)
+{
+    __syncthreads();
+    char *d = shm_ptr(c, dst_off, me);
+    const char *s = shm_ptr(c, src_off, pe);
+    const size_t body = n & ~static_cast<size_t>(15);
+    shm_copy_tiles<2>(d, s, body, part, nparts);
+    if (part == 0 && threadIdx.x < n - body) d[body + threadIdx.x] = s[body + threadIdx.x];
     __syncthreads();
 }
 

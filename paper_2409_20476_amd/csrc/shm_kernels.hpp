@@ -23,6 +23,20 @@ __global__ __launch_bounds__(SHMK_WG) void shmk_wg_rma(shm_dev_ctx c, uint64_t d
         shmx_putmem_parts(c, me, dst_off, src_off, n, pe, blockIdx.x, gridDim.x);
 }
 
+// Long messages: group-owned tiles.  The dynamic LDS the host asks for is never touched: it only
+// caps how many groups a CU holds at once.
+__global__ __launch_bounds__(SHMK_WG) void shmk_wg_rma_tiles(shm_dev_ctx c, uint64_t dst_off, uint64_t src_off, size_t n, int me0,
+                                                             int shift, int is_get)
+{
+    const int me = me0 + blockIdx.y;
+    int pe = me + shift;
+    if (pe >= c.npes) pe -= c.npes;
+    if (is_get)
+        shmx_getmem_tiles(c, me, dst_off, src_off, n, pe, blockIdx.x, gridDim.x);
+    else
+        shmx_putmem_tiles(c, me, dst_off, src_off, n, pe, blockIdx.x, gridDim.x);
+}
+
 // The same put repeated `reps` times inside one kernel, each followed by the group's quiet, with the
 // device clock read before the first and after the last: the cost of a put issued from a running
 // kernel, free of any launch overhead.  ticks[0] = earliest start, ticks[1] = latest end over groups.

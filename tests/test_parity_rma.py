@@ -129,3 +129,34 @@ def test_timed_put_moves_the_same_bytes_and_reports_device_time():
         t0, t1 = (int(v) & ((1 << 64) - 1) for v in ticks.tolist())
         us = (t1 - t0) / g.wall_clock_khz() * 1e3
         assert 0 < us < 1e5, us
+
+
+@pytest.mark.parametrize("n_wg", [32, 33, 100, 160])
+def test_long_messages_take_group_owned_tiles(n_wg):
+    """8 MiB or more, 32 groups or more, 64 KiB or more per group, 16-byte-aligned offsets: every
+    group owns whole 64 KiB tiles.  Ragged last tile, byte tail, put and get, team form."""
+    g, o = make_pair(4, 32 * MiB)
+    with g:
+        fill_random(g, o, 8, upto=28 * MiB)
+        sizes = [10 * MiB, 10 * MiB + 48, 11 * MiB + 131072 + 16, 10 * MiB + 7, 12 * MiB]
+        for rep, n in enumerate(sizes):
+            me, pe = rep % 4, (rep + 1) % 4
+            src, dst = 4096 + 16 * rep, 14 * MiB + 32 * rep
+            g.launch_wg_put(me, pe, dst, src, n, n_wg)
+            o.wg_put(me, dst, src, n, pe, n_wg)
+            g.quiet(me)
+            g.launch_wg_get(pe, me, 64, dst, n, n_wg)           # read it back into the start of the caller's heap
+            o.wg_get(pe, 64, dst, n, me, n_wg)
+            g.quiet(pe)
+            assert_heaps_equal(g, o, upto=28 * MiB, what=f"n_wg {n_wg} size {n}")
+        n = 11 * MiB + 65536 + 5
+        g.launch_wg_put_all(3, 14 * MiB, 0, n, n_wg)
+        for p in range(4):
+            o.wg_put(p, 14 * MiB, 0, n, (p + 3) % 4, n_wg)
+        g.barrier_all()
+        g.launch_wg_get_all(1, 64, 14 * MiB, n, n_wg)
+        before = [h.copy() for h in o.heap]
+        for p in range(4):
+            o.heap[p][64:64 + n] = before[(p + 1) % 4][14 * MiB:14 * MiB + n]
+        g.barrier_all()
+        assert_heaps_equal(g, o, upto=28 * MiB, what="team forms")
