@@ -87,6 +87,7 @@ shm_dev_ctx dev_view(const shm_ctx *c)
     for (int p = 0; p < c->npes; ++p) d.base[p] = c->base + static_cast<size_t>(p) * c->part_bytes;
     d.status = c->status_dev;
     d.wait_ticks = c->wait_us * c->ticks_per_us;
+    d.stride = c->part_bytes;     // logical PEs are equal partitions of one allocation
     d.npes = c->npes;
     if (c->off_dev && c->proxy.running()) {
         d.off.ring = &c->off_dev->ring[0][0];
@@ -864,9 +865,12 @@ int shm_launch_fcollect(shm_ctx *c, uint64_t dst_off, uint64_t src_off, size_t b
     if (c->team_sync)
         if (int r = team_join(c)) return r;
     const dim3 grid(n_wg, c->npes), block(SHMK_WG);
-    if (((dst_off | src_off | bytes_per_pe) & 15) == 0)
-        hipLaunchKernelGGL(shmk_fcollect_vec<4>, grid, block, 0, c->stream[0], dev_view(c), dst_off, src_off, bytes_per_pe);
-    else
+    if (((dst_off | src_off | bytes_per_pe) & 15) == 0) {
+        if (c->npes == 8)
+            hipLaunchKernelGGL((shmk_fcollect_vec<2, 8>), grid, block, 0, c->stream[0], dev_view(c), dst_off, src_off, bytes_per_pe);
+        else
+            hipLaunchKernelGGL((shmk_fcollect_vec<2, 0>), grid, block, 0, c->stream[0], dev_view(c), dst_off, src_off, bytes_per_pe);
+    } else
         hipLaunchKernelGGL(shmk_fcollect_any, grid, block, 0, c->stream[0], dev_view(c), dst_off, src_off, bytes_per_pe);
     if (int r = launched("fcollect")) return r;
     if (c->team_sync)

@@ -28,6 +28,7 @@ struct shm_dev_ctx {
     char *base[SHM_MAX_PES];
     uint64_t *status;        // host-pinned word; set to 1 when a bounded wait expired
     uint64_t wait_ticks;     // bound for every wait, in wall_clock64() ticks
+    uint64_t stride;         // base[p] == base[0] + p * stride for every p (equally spaced partitions), else 0
     shm_offload_dev off;
     int npes;
 };
@@ -37,8 +38,14 @@ typedef uint32_t shm_u32x4 __attribute__((ext_vector_type(4)));
 enum { SHMD_SIGNAL_SET = 0, SHMD_SIGNAL_ADD = 1 };
 enum { SHMD_CMP_EQ = 0, SHMD_CMP_NE = 1, SHMD_CMP_GT = 2, SHMD_CMP_GE = 3, SHMD_CMP_LT = 4, SHMD_CMP_LE = 5 };
 
-// Address rule of the paper's section "Remote Memory Access": same offset, target PE's base.
-__device__ __forceinline__ char *shm_ptr(const shm_dev_ctx &c, uint64_t off, int pe) { return c.base[pe] + off; }
+// Address rule of the paper's section "Remote Memory Access": same offset, target PE's base.  With
+// equally spaced partitions the base is computed instead of looked up, which keeps table loads out
+// of inner loops that visit every PE.
+__device__ __forceinline__ char *shm_ptr(const shm_dev_ctx &c, uint64_t off, int pe)
+{
+    if (__builtin_expect(c.stride != 0, 1)) return c.base[0] + static_cast<uint64_t>(pe) * c.stride + off;
+    return c.base[pe] + off;
+}
 
 // ------------------------------------------------------------------------------------------
 // Cooperative byte copy: `nthr` threads (this one is `tid`) copy n bytes, any alignment.

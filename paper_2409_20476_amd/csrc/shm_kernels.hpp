@@ -301,33 +301,62 @@ __global__ __launch_bounds__(SHMK_WG) void shmk_amo_storm(shm_dev_ctx c, uint64_
 // PE p = blockIdx.y reads its block once and stores every vector to all PEs (inner loop over
 // destinations, outer loop over addresses), starting with its right-hand neighbour.  The block is
 // dealt to the PE's groups like a put.
-template <int U>
+// NPES > 0 fixes the number of PEs at compile time, so that the destination loop unrolls and the
+// base-pointer lookups leave the tile loop; NPES == 0 is the general form.
+template <int U, int NPES>
 __global__ __launch_bounds__(SHMK_WG) void shmk_fcollect_vec(shm_dev_ctx c, uint64_t dst_off, uint64_t src_off, size_t bytes_per_pe)
 {
-    const int p = blockIdx.y, npes = c.npes;
+    // Group-owned tiles of U rows x 32 KiB, as in shm_copy_tiles: per column U loads, then those
+    // U vectors to every destination, then the next column.
+    const int p = blockIdx.y, npes = NPES ? NPES : c.npes;
     const shm_u32x4 *s = reinterpret_cast<const shm_u32x4 *>(shm_ptr(c, src_off, p));
     const uint64_t d0 = dst_off + static_cast<uint64_t>(p) * bytes_per_pe;
-    const size_t nvec = bytes_per_pe >> 4;
-    const shm_deal k = shm_deal_make<U>(nvec, blockIdx.x, gridDim.x, threadIdx.x, SHMK_WG);
-    for (size_t t = k.vb; t < k.ntiles; t += k.nvb) {
-        const size_t i = t * k.tilev + k.col;
-        shm_u32x4 r[U];
+    constexpr int NQ = NPES ? NPES : 1;
+    shm_u32x4 *dq[NQ];
+    if (NPES) {
 #pragma unroll
-        for (int u = 0; u < U; ++u) r[u] = shm_ld16(s + i + u * k.rowv);
-        for (int j = 0; j < npes; ++j) {
-            int q = p + 1 + j;
-            if (q >= npes) q -= npes;
-            shm_u32x4 *d = reinterpret_cast<shm_u32x4 *>(shm_ptr(c, d0, q));
-#pragma unroll
-            for (int u = 0; u < U; ++u) shm_st16(d + i + u * k.rowv, r[u]);
-        }
+        for (int j = 0; j < NQ; ++j) dq[j] = reinterpret_cast<shm_u32x4 *>(shm_ptr(c, d0, (p + 1 + j) % NQ));
     }
-    for (size_t i = k.rem_lane; i < nvec; i += k.rem_step) {
-        const shm_u32x4 r = shm_ld16(s + i);
-        for (int j = 0; j < npes; ++j) {
-            int q = p + 1 + j;
-            if (q >= npes) q -= npes;
-            shm_st16(reinterpret_cast<shm_u32x4 *>(shm_ptr(c, d0, q)) + i, r);
+    const size_t nvec = bytes_per_pe >> 4;
+    constexpr size_t rowv = 2048, tilev = rowv * U;
+    const size_t ntiles = (nvec + tilev - 1) / tilev;
+    const unsigned wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    for (size_t t = blockIdx.x; t < ntiles; t += gridDim.x) {
+        if ((t + 1) * tilev <= nvec) {            // whole tile: no predicates anywhere in the hot loop
+#pragma unroll
+            for (unsigned cc = 0; cc < 8; ++cc) {
+                const size_t i = t * tilev + static_cast<size_t>(wave * 8 + cc) * 64 + lane;
+                shm_u32x4 r[U];
+#pragma unroll
+                for (int u = 0; u < U; ++u) r[u] = shm_ld16(s + i + u * rowv);
+                if (NPES) {
+#pragma unroll
+                    for (int j = 0; j < NQ; ++j)
+#pragma unroll
+                        for (int u = 0; u < U; ++u) shm_st16(dq[j] + i + u * rowv, r[u]);
+                } else {
+                    for (int j = 0; j < npes; ++j) {
+                        int q = p + 1 + j;
+                        if (q >= npes) q -= npes;
+                        shm_u32x4 *d = reinterpret_cast<shm_u32x4 *>(shm_ptr(c, d0, q));
+#pragma unroll
+                        for (int u = 0; u < U; ++u) shm_st16(d + i + u * rowv, r[u]);
+                    }
+                }
+            }
+        } else {                                  // the last, partial tile
+            for (unsigned cc = 0; cc < 8; ++cc) {
+                for (int u = 0; u < U; ++u) {
+                    const size_t i = t * tilev + static_cast<size_t>(wave * 8 + cc) * 64 + lane + u * rowv;
+                    if (i >= nvec) continue;
+                    const shm_u32x4 r = shm_ld16(s + i);
+                    for (int j = 0; j < npes; ++j) {
+                        int q = p + 1 + j;
+                        if (q >= npes) q -= npes;
+                        shm_st16(reinterpret_cast<shm_u32x4 *>(shm_ptr(c, d0, q)) + i, r);
+                    }
+                }
+            }
         }
     }
 }
