@@ -491,7 +491,7 @@ def main():
     g.finalize()
 
     traffic = None        # measured with rocprofv3 --pmc in a separate run; the summary is committed under profiles/
-    tpath = os.path.join(ROOT, "profiles", "shmk_wg_rma_config2_256MiB_hbm_counters.txt")
+    tpath = os.path.join(ROOT, "profiles", "shmk_wg_rma_tiles_config2_256MiB_hbm_counters.txt")
     if os.path.exists(tpath) and args.size_mib == 256 and args.n_wg == 1024:
         import re
         m = re.search(r"^hbm_bytes_per_launch:\s*(\d+)", open(tpath).read(), re.M)
@@ -508,7 +508,7 @@ def main():
         "value_note": "payload bytes delivered per second, all 8 PEs together; % of roofline counts read + written bytes",
         "pct_of_hbm_copy_roofline": 100.0 * 2 * head["value_gbs"] / HBM_PEAK_GBS,
         "spot_check_ok": head["spot_check_ok"],
-        "roofline": {"bound": "hbm", "kernel": "shmk_wg_rma", "achieved": head["achieved_gbs"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
+        "roofline": {"bound": "hbm", "kernel": "shmk_wg_rma_tiles", "achieved": head["achieved_gbs"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": head["achieved_gbs"] / HBM_PEAK_GBS, "traffic": traffic,
                      "algorithmic_bytes_per_launch": 2 * head["payload_bytes"], "kernel_ms": head["kernel_ms"]},
         "cpu_baseline": cpu,
