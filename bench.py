@@ -291,6 +291,66 @@ def reverse_offload(torch, S, args):
     return out
 
 
+def collective_sweeps(torch, S, args):
+    """The paper's collective experiments: fcollect against elements, work-groups and PEs with the
+    host copy paths beside it; broadcast against the number of PEs; the device-side sync."""
+    out = {"fcollect": {}, "broadcast_us_by_pes": {}, "sync_us_by_pes": {}, "barrier_us_by_pes": {}}
+    t = torch.zeros(2, dtype=torch.int64, device="cuda")
+    for npes in (4, 8, 12):
+        g = S.Shm.on_torch(npes, 128 * MiB)
+        g.set_team_sync(False)
+        src, dst = g.malloc(4 * MiB), g.malloc(4 * MiB * npes)
+        rows = []
+        for k in range(4, 23):
+            n = 1 << k
+            row = {"bytes_per_pe": n, "nelems_int32": n // 4}
+            for n_wg in (1, 4, 64):
+                ms = paper_timing(torch, lambda iters: time_on_stream(
+                    torch, g.streams[0], lambda: g.launch_fcollect(dst, src, n, n_wg, S.SHM_PATH_LDST), iters))
+                row[f"ldst_wg{n_wg}_us"] = ms * 1e3
+            for key, path in (("memcpy", S.SHM_PATH_MEMCPY), ("sdma", S.SHM_PATH_SDMA)):
+                def trial(iters):
+                    g.barrier_all()
+                    t0 = time.perf_counter()
+                    for _ in range(iters):
+                        g.launch_fcollect(dst, src, n, 1, path)
+                    g.barrier_all()
+                    return (time.perf_counter() - t0) * 1e3 / iters
+                row[key + "_us"] = paper_timing(torch, trial) * 1e3
+            rows.append(row)
+        cut = {}
+        for n_wg in (1, 4, 64):
+            key = f"ldst_wg{n_wg}_us"
+            cut[str(n_wg)] = next((r["bytes_per_pe"] for i, r in enumerate(rows)
+                                   if all(min(q["memcpy_us"], q["sdma_us"]) <= q[key] for q in rows[i:])), None)
+        out["fcollect"][str(npes)] = {"rows": rows, "cutover_bytes_per_pe": cut}
+        g.finalize()
+    for npes in (2, 4, 8, 12, 16):
+        g = S.Shm.on_torch(npes, 64 * MiB)
+        g.set_team_sync(False)
+        src, dst = g.malloc(MiB), g.malloc(MiB)
+        out["broadcast_us_by_pes"][str(npes)] = {
+            str(n): paper_timing(torch, lambda iters: time_on_stream(
+                torch, g.streams[0], lambda: g.launch_broadcast(dst, src, n, 0, 2, S.SHM_PATH_LDST), iters)) * 1e3
+            for n in (4096, 65536, MiB)}
+        for key, quiet in (("sync_us_by_pes", 0), ("barrier_us_by_pes", 1)):
+            best = float("inf")
+            for _ in range(3):
+                t[0], t[1] = -1, 0
+                torch.cuda.synchronize()
+                g.launch_sync_all(200, quiet, t)
+                g.barrier_all()
+                a, b = (int(v) & ((1 << 64) - 1) for v in t.tolist())
+                best = min(best, (b - a) / g.wall_clock_khz() * 1e3 / 200)
+            out[key][str(npes)] = best
+        g.finalize()
+    out["note"] = ("fcollect: ldst_wgK_us = one grid with K groups of 256 threads per PE (HIP events, launch included); memcpy_us / "
+                   "sdma_us = npes^2 host-started copies, host clock; cutover = smallest block from which a host copy path stays "
+                   "at least as fast. broadcast: root PE 0, 2 groups (the paper uses 128 work-items), device time per call. "
+                   "sync / barrier: device clock inside one kernel of npes groups, per operation")
+    return out
+
+
 def pingflag(torch, S, synth, args):
     g = S.Shm.on_torch(2, MiB)
     payload = synth.c1_payload(4096)
@@ -482,6 +542,9 @@ def main():
         extras["reverse_offload"] = reverse_offload(torch, S, args)
         log(f"[bench] reverse offload: rtt {extras['reverse_offload']['round_trip_us']} rate {extras['reverse_offload']['request_rate_mreq_s']} "
             f"cutover {extras['reverse_offload']['cutover_bytes_by_work_items']}")
+        extras["collective_sweeps"] = collective_sweeps(torch, S, args)
+        log(f"[bench] sync us by PEs {extras['collective_sweeps']['sync_us_by_pes']} barrier {extras['collective_sweeps']['barrier_us_by_pes']} "
+            f"fcollect cutover {{k: v['cutover_bytes_per_pe'] for k, v in extras['collective_sweeps']['fcollect'].items()}}")
         extras["config3_ring"] = ring(torch, S, synth, g, args)
         log(f"[bench] c3: {extras['config3_ring']}")
         extras["config4_amo_storm"] = storm(torch, S, synth, args)

@@ -244,6 +244,22 @@ int shm_launch_amo_storm(shm_ctx *ctx, uint64_t ctr_off, int n_ctr, const uint16
  * MEMCPY: npes*npes copies.  AUTO uses the cutover of n_wg on bytes_per_pe. */
 int shm_launch_fcollect(shm_ctx *ctx, uint64_t dst_off, uint64_t src_off, size_t bytes_per_pe, int n_wg, int path);
 
+/* Broadcast (paper section "Collective Operations": push, inner loop over destinations): every
+ * PE's dst_off receives the n bytes at src_off of PE `root` (the root's own dst_off too).  LDST:
+ * n_wg groups of the root store to all PEs from one grid on the team stream.  SDMA / MEMCPY: one
+ * copy per destination.  AUTO by the cutover of n_wg on n. */
+int shm_launch_broadcast(shm_ctx *ctx, uint64_t dst_off, uint64_t src_off, size_t n, int root, int n_wg, int path);
+
+/* Device-side synchronisation among PEs (same section: every PE pushes an atomic increment to every
+ * other PE's counter and waits on its own).  One grid of npes groups on the team stream, group p
+ * acting as PE p.  shm_launch_sync_all: `rounds` syncs (with_quiet != 0: barriers = quiet + sync +
+ * acquire); dev_ticks as for shm_launch_wg_put_timed.  shm_launch_barrier_exchange, a barrier that
+ * data depends on: in round r < rounds <= npes PE p puts its n bytes at src_off into slot p
+ * (dst_off + p*n) of PE (p+1+r) mod npes, all PEs meet in a device barrier, then p copies the slot
+ * just filled for it (that of PE (p-1-r) mod npes) to acc_off + r*n. */
+int shm_launch_sync_all(shm_ctx *ctx, int rounds, int with_quiet, uint64_t *dev_ticks);
+int shm_launch_barrier_exchange(shm_ctx *ctx, uint64_t dst_off, uint64_t src_off, uint64_t acc_off, size_t n, int rounds);
+
 /* Benchmark configuration 5b: float32 sum over PEs, operand order PE 0, 1, ..., npes-1 for every
  * element, so all PEs get bit-identical results.  DUPLICATE: every PE computes every element from
  * one local and npes-1 remote loads (paper section "Collective Operations", reduction paragraph).

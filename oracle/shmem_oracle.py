@@ -321,6 +321,31 @@ class ShmemOracle:
             for p in range(self.npes):
                 self.heap[q][dst + p * n:dst + (p + 1) * n] = blocks[p]
 
+    def broadcast(self, dst: int, src: int, n: int, root: int) -> None:
+        """Bytes [src, src+n) of PE ``root`` land at [dst, dst+n) of every PE, the root included."""
+        self._pe(root)
+        self._range(src, n), self._range(dst, n)
+        if n and src < dst + n and dst < src + n:
+            raise OracleError("overlapping source and destination")
+        block = self.heap[root][src:src + n].copy()
+        for q in range(self.npes):
+            self.heap[q][dst:dst + n] = block
+
+    def sync_all(self) -> None:
+        """Every PE waits for every other; no data moves and nothing is ordered."""
+        self.log.append(("sync_all",))
+
+    def barrier_exchange(self, dst: int, src: int, acc: int, n: int, rounds: int) -> None:
+        """Round r: every PE p puts its block into slot p of PE (p+1+r) mod npes; barrier; every PE
+        copies the slot just filled for it (that of PE (p-1-r) mod npes) to ``acc + r*n``."""
+        for r in range(rounds):
+            for p in range(self.npes):
+                self.putmem(p, dst + p * n, src, n, (p + 1 + r) % self.npes)
+            self.barrier_all()
+            for p in range(self.npes):
+                frm = (p - 1 - r) % self.npes
+                self.getmem(p, acc + r * n, dst + frm * n, n, p)
+
     def reduce_sum_f32(self, dst: int, src: int, nelems: int) -> dict:
         """Element-wise binary32 sum over PEs in the order 0, 1, ..., npes-1.
 

@@ -29,7 +29,8 @@ constexpr size_t TILES_MIN_BYTES_PER_GROUP = 64u << 10;
 constexpr int TILES_MIN_GROUPS = 32;
 constexpr unsigned TILES_LDS_BYTES = 54000;                   // unused LDS that caps a CU at 3 resident groups
 constexpr uint64_t OFFLOAD_COUNTERS = 32768;                  // offset of the ring's two index words in PE 0's internal tail
-static_assert(ARRIVE_SLOTS * 8 <= OFFLOAD_COUNTERS && OFFLOAD_COUNTERS + 16 <= SHM_INTERNAL_BYTES, "internal tail layout");
+static_assert(ARRIVE_SLOTS * 8 <= OFFLOAD_COUNTERS && OFFLOAD_COUNTERS + 16 <= SHMD_INTERNAL_SYNC_COUNT &&
+                  SHMD_INTERNAL_SYNC_EPOCH + 8 <= SHM_INTERNAL_BYTES, "internal tail layout");
 static_assert(SHM_OFFLOAD_SLOTS == SHMD_OFFLOAD_SLOTS && SHM_OFFLOAD_COMPLETIONS == SHMD_OFFLOAD_COMPLETIONS &&
                   SHM_OFFLOAD_NO_COMPLETION == SHMD_OFFLOAD_NONE, "host and device agree on the ring");
 
@@ -88,6 +89,7 @@ shm_dev_ctx dev_view(const shm_ctx *c)
     d.status = c->status_dev;
     d.wait_ticks = c->wait_us * c->ticks_per_us;
     d.stride = c->part_bytes;     // logical PEs are equal partitions of one allocation
+    d.internal_off = c->user_bytes;
     d.npes = c->npes;
     if (c->off_dev && c->proxy.running()) {
         d.off.ring = &c->off_dev->ring[0][0];
@@ -873,6 +875,82 @@ int shm_launch_fcollect(shm_ctx *c, uint64_t dst_off, uint64_t src_off, size_t b
     } else
         hipLaunchKernelGGL(shmk_fcollect_any, grid, block, 0, c->stream[0], dev_view(c), dst_off, src_off, bytes_per_pe);
     if (int r = launched("fcollect")) return r;
+    if (c->team_sync)
+        if (int r = team_fork(c)) return r;
+    return SHM_OK;
+}
+
+int shm_launch_barrier_exchange(shm_ctx *c, uint64_t dst_off, uint64_t src_off, uint64_t acc_off, size_t n, int rounds)
+{
+    if (int r = check_ctx(c)) return r;
+    if (rounds < 1 || rounds > c->npes) return fail(SHM_EINVAL, "rounds outside 1..npes");
+    if (n > c->user_bytes / c->npes) return fail(SHM_ERANGE, "slots leave the heap");
+    if (int r = check_range(c, src_off, n, "source")) return r;
+    if (int r = check_range(c, dst_off, n * c->npes, "slots")) return r;
+    if (int r = check_range(c, acc_off, n * rounds, "result")) return r;
+    const size_t dn = n * c->npes, an = n * rounds;
+    if (n && ((src_off < dst_off + dn && dst_off < src_off + n) || (src_off < acc_off + an && acc_off < src_off + n) ||
+              (dst_off < acc_off + an && acc_off < dst_off + dn)))
+        return fail(SHM_EINVAL, "source, slots and result must be disjoint");
+    if (c->no_device) return no_device("shm_launch_barrier_exchange");
+    if (int r = drain_all_engines(c)) return r;
+    if (c->team_sync)
+        if (int r = team_join(c)) return r;
+    hipLaunchKernelGGL(shmk_barrier_exchange, dim3(c->npes), dim3(SHMK_WG), 0, c->stream[0], dev_view(c), dst_off, src_off, acc_off, n,
+                       rounds);
+    if (int r = launched("barrier exchange")) return r;
+    if (c->team_sync)
+        if (int r = team_fork(c)) return r;
+    return SHM_OK;
+}
+
+int shm_launch_sync_all(shm_ctx *c, int rounds, int with_quiet, uint64_t *dev_ticks)
+{
+    if (int r = check_ctx(c)) return r;
+    if (rounds < 1 || rounds > (1 << 20)) return fail(SHM_EINVAL, "rounds outside 1..2^20");
+    if (!dev_ticks) return fail(SHM_EINVAL, "null tick buffer");
+    if (c->no_device) return no_device("shm_launch_sync_all");
+    if (int r = drain_all_engines(c)) return r;
+    if (c->team_sync)
+        if (int r = team_join(c)) return r;
+    hipLaunchKernelGGL(shmk_sync_all, dim3(c->npes), dim3(SHMK_WG), 0, c->stream[0], dev_view(c), rounds, with_quiet,
+                       reinterpret_cast<unsigned long long *>(dev_ticks));
+    if (int r = launched("sync")) return r;
+    if (c->team_sync)
+        if (int r = team_fork(c)) return r;
+    return SHM_OK;
+}
+
+int shm_launch_broadcast(shm_ctx *c, uint64_t dst_off, uint64_t src_off, size_t n, int root, int n_wg, int path)
+{
+    if (int r = check_ctx(c)) return r;
+    if (int r = check_pe(c, root, "root PE")) return r;
+    if (int r = check_range(c, src_off, n, "source")) return r;
+    if (int r = check_range(c, dst_off, n, "destination")) return r;
+    if (overlaps(dst_off, src_off, n)) return fail(SHM_EINVAL, "source and destination overlap");
+    if (int r = check_n_wg(n_wg)) return r;
+    int use;
+    if (int r = resolve_path(c, path, n, n_wg, &use)) return r;
+    if (c->no_device) return no_device("shm_launch_broadcast");
+    if (int r = drain_all_engines(c)) return r;
+    if (n == 0) return SHM_OK;
+    if (c->team_sync)
+        if (int r = team_join(c)) return r;
+    if (use != SHM_PATH_LDST) {
+        if (c->team_sync)
+            if (int r = team_fork(c)) return r;
+        for (int j = 0; j < c->npes; ++j) {          // one copy per destination, spread over the PE streams / engines
+            const int q = (root + 1 + j) % c->npes;
+            if (int r = transfer_copy(c, use, q, q, dst_off, root, src_off, n)) return r;
+        }
+        if (c->team_sync) {
+            if (int r = team_join(c)) return r;
+            if (int r = team_fork(c)) return r;
+        }
+        return SHM_OK;
+    }
+    hipLaunchKernelGGL(shmk_broadcast, dim3(n_wg), dim3(SHMK_WG), 0, c->stream[0], dev_view(c), dst_off, src_off, n, root);
+    if (int r = launched("broadcast")) return r;
     if (c->team_sync)
         if (int r = team_fork(c)) return r;
     return SHM_OK;

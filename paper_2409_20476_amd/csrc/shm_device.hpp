@@ -29,9 +29,14 @@ struct shm_dev_ctx {
     uint64_t *status;        // host-pinned word; set to 1 when a bounded wait expired
     uint64_t wait_ticks;     // bound for every wait, in wall_clock64() ticks
     uint64_t stride;         // base[p] == base[0] + p * stride for every p (equally spaced partitions), else 0
+    uint64_t internal_off;   // offset of the library's own tail of every partition
     shm_offload_dev off;
     int npes;
 };
+
+// Words in the library's tail of every partition (byte offsets from internal_off).
+#define SHMD_INTERNAL_SYNC_COUNT 33024u   // uint64: increments received from the other PEs' syncs
+#define SHMD_INTERNAL_SYNC_EPOCH 33032u   // uint64: syncs this PE has completed
 
 typedef uint32_t shm_u32x4 __attribute__((ext_vector_type(4)));
 
@@ -696,4 +701,59 @@ __device__ __forceinline__ void shmx_putmem_auto_wg(const shm_dev_ctx &c, int me
         shmx_putmem_offload_wg(c, me, dst_off, src_off, n, pe, true);
     else
         shmx_putmem_wg(c, me, dst_off, src_off, n, pe);
+}
+
+// ------------------------------------------------------------------------------------------
+// Synchronisation among PEs from inside kernels (paper section "Collective Operations", sync and
+// broadcast paragraph): every PE pushes one atomic increment to every other PE's counter -- fire and
+// forget, pipelined -- and then waits on its OWN counter for the running total.  Counters only grow;
+// the number of syncs a PE has completed is kept next to its counter, so nothing is ever reset.
+// One work-group per PE takes part at a time; all of them must be resident together (the team
+// launches see to that).  sync orders nothing; barrier = group quiet + sync + acquire.
+// ------------------------------------------------------------------------------------------
+__device__ __forceinline__ void shmx_sync_all_wg(const shm_dev_ctx &c, int me)
+{
+    __syncthreads();
+    if (threadIdx.x == 0 && c.npes > 1) {
+        uint64_t *epoch = reinterpret_cast<uint64_t *>(shm_ptr(c, c.internal_off + SHMD_INTERNAL_SYNC_EPOCH, me));
+        const uint64_t e = __hip_atomic_load(epoch, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) + 1;
+        for (int j = 1; j < c.npes; ++j) {
+            int q = me + j;
+            if (q >= c.npes) q -= c.npes;
+            (void)__hip_atomic_fetch_add(reinterpret_cast<uint64_t *>(shm_ptr(c, c.internal_off + SHMD_INTERNAL_SYNC_COUNT, q)), 1ull,
+                                         __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+        const uint64_t *mine = reinterpret_cast<const uint64_t *>(shm_ptr(c, c.internal_off + SHMD_INTERNAL_SYNC_COUNT, me));
+        const uint64_t want = e * static_cast<uint64_t>(c.npes - 1);
+        const uint64_t t0 = wall_clock64();
+        while (__hip_atomic_load(mine, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < want) {
+            if (wall_clock64() - t0 > c.wait_ticks) {
+                __hip_atomic_store(c.status, 1ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+                break;
+            }
+            __builtin_amdgcn_s_sleep(1);
+        }
+        __hip_atomic_store(epoch, e, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+    __syncthreads();
+}
+
+__device__ __forceinline__ void shmx_barrier_all_wg(const shm_dev_ctx &c, int me)
+{
+    shmx_quiet_wg();                    // this group's puts are complete and visible ...
+    shmx_sync_all_wg(c, me);            // ... before anyone leaves the barrier
+    if (threadIdx.x == 0) __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+    __syncthreads();
+}
+
+// Broadcast, push form (same paragraph): the root's groups store the block to every PE, inner loop
+// over destinations.  Called by the nparts groups of the root only.
+__device__ __forceinline__ void shmx_broadcast_push(const shm_dev_ctx &c, int root, uint64_t dst_off, uint64_t src_off, size_t n,
+                                                    unsigned part, unsigned nparts)
+{
+    for (int j = 0; j < c.npes; ++j) {
+        int q = root + 1 + j;           // the right-hand neighbour first, the root's own copy last
+        if (q >= c.npes) q -= c.npes;
+        shmx_putmem_parts(c, root, dst_off, src_off, n, q, part, nparts);
+    }
 }

@@ -440,3 +440,45 @@ __global__ __launch_bounds__(SHMK_WG) void shmk_reduce_sum_f32_scalar(shm_dev_ct
         reinterpret_cast<float *>(shm_ptr(c, dst_off, q))[i] = r;
     }
 }
+
+// ---- device-side synchronisation among PEs ------------------------------------------------------
+// One group per PE (blockIdx.x = PE).  Round r: PE p puts its block into slot p of PE (p+1+r) mod
+// npes, all PEs meet in a device barrier, then p copies the slot that was just filled for it (the
+// block of PE (p-1-r) mod npes) to acc_off + r*n.  Without a working barrier the copy reads stale
+// bytes.
+__global__ __launch_bounds__(SHMK_WG) void shmk_barrier_exchange(shm_dev_ctx c, uint64_t dst_off, uint64_t src_off, uint64_t acc_off,
+                                                                 size_t n, int rounds)
+{
+    const int me = blockIdx.x, npes = c.npes;
+    for (int r = 0; r < rounds; ++r) {
+        const int to = (me + 1 + r) % npes;
+        int from = (me - 1 - r) % npes;
+        if (from < 0) from += npes;
+        shmx_putmem_wg(c, me, dst_off + static_cast<uint64_t>(me) * n, src_off, n, to);
+        shmx_barrier_all_wg(c, me);
+        shmx_getmem_wg(c, me, acc_off + static_cast<uint64_t>(r) * n, dst_off + static_cast<uint64_t>(from) * n, n, me);
+    }
+}
+
+// `rounds` syncs by one group per PE; device clock around them.
+__global__ __launch_bounds__(SHMK_WG) void shmk_sync_all(shm_dev_ctx c, int rounds, int with_quiet, unsigned long long *ticks)
+{
+    const int me = blockIdx.x;
+    const unsigned long long t0 = wall_clock64();
+    for (int r = 0; r < rounds; ++r) {
+        if (with_quiet)
+            shmx_barrier_all_wg(c, me);
+        else
+            shmx_sync_all_wg(c, me);
+    }
+    const unsigned long long t1 = wall_clock64();
+    if (threadIdx.x == 0) {
+        atomicMin(&ticks[0], t0);
+        atomicMax(&ticks[1], t1);
+    }
+}
+
+__global__ __launch_bounds__(SHMK_WG) void shmk_broadcast(shm_dev_ctx c, uint64_t dst_off, uint64_t src_off, size_t n, int root)
+{
+    shmx_broadcast_push(c, root, dst_off, src_off, n, blockIdx.x, gridDim.x);
+}

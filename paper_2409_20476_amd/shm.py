@@ -74,6 +74,9 @@ PROTOTYPES = {
     "shm_launch_ring_pipeline": (c_int, [c_void_p, c_uint64, c_uint64, c_uint64, c_uint64, c_size_t, c_int, c_int, c_int, c_int]),
     "shm_launch_amo_storm": (c_int, [c_void_p, c_uint64, c_int, c_void_p, c_uint64, c_int, c_int, c_void_p, c_void_p]),
     "shm_launch_fcollect": (c_int, [c_void_p, c_uint64, c_uint64, c_size_t, c_int, c_int]),
+    "shm_launch_broadcast": (c_int, [c_void_p, c_uint64, c_uint64, c_size_t, c_int, c_int, c_int]),
+    "shm_launch_sync_all": (c_int, [c_void_p, c_int, c_int, c_void_p]),
+    "shm_launch_barrier_exchange": (c_int, [c_void_p, c_uint64, c_uint64, c_uint64, c_size_t, c_int]),
     "shm_launch_reduce_sum_f32": (c_int, [c_void_p, c_uint64, c_uint64, c_size_t, c_int, c_int]),
 }
 
@@ -281,6 +284,15 @@ class Shm:
 
     def launch_fcollect(self, dst_off, src_off, bytes_per_pe, n_wg=64, path=SHM_PATH_LDST):
         self._check(self.lib.shm_launch_fcollect(self.ctx, dst_off, src_off, bytes_per_pe, n_wg, path))
+
+    def launch_broadcast(self, dst_off, src_off, n, root, n_wg=64, path=SHM_PATH_LDST):
+        self._check(self.lib.shm_launch_broadcast(self.ctx, dst_off, src_off, n, root, n_wg, path))
+
+    def launch_sync_all(self, rounds, with_quiet, dev_ticks):
+        self._check(self.lib.shm_launch_sync_all(self.ctx, rounds, int(with_quiet), _ptr(dev_ticks)))
+
+    def launch_barrier_exchange(self, dst_off, src_off, acc_off, n, rounds):
+        self._check(self.lib.shm_launch_barrier_exchange(self.ctx, dst_off, src_off, acc_off, n, rounds))
 
     def launch_reduce_sum_f32(self, dst_off, src_off, nelems, n_wg=64, algo=SHM_REDUCE_DUPLICATE):
         self._check(self.lib.shm_launch_reduce_sum_f32(self.ctx, dst_off, src_off, nelems, n_wg, algo))

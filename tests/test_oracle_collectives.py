@@ -186,3 +186,31 @@ def test_synth_is_seeded_and_in_range():
     c = ShmemOracle.bf16_bits_to_f32(synth.c3_chunks(0, 2, 1000))
     assert c.min() >= -1.0 and c.max() <= 1.0
     assert synth.c5_fcollect_source(1, 10).dtype == np.int32 and synth.c5_reduce_source(1, 10).dtype == np.float32
+
+
+def test_broadcast_is_a_put_from_the_root_to_everyone():
+    a, b = ShmemOracle(5, 512), ShmemOracle(5, 512)
+    _fill(a, 9), _fill(b, 9)
+    a.broadcast(300, 17, 101, 3)
+    for q in range(5):
+        if q == 3:
+            b.heap[3][300:401] = b.heap[3][17:118].copy()       # the root's own copy, byte for byte
+        else:
+            b.putmem(3, 300, 17, 101, q)
+    assert all((x == y).all() for x, y in zip(a.heap, b.heap))
+    with pytest.raises(OracleError):
+        a.broadcast(20, 17, 101, 3)
+    with pytest.raises(OracleError):
+        a.broadcast(300, 17, 101, 5)
+
+
+def test_barrier_exchange_delivers_every_neighbours_block():
+    npes, n = 4, 24
+    o = ShmemOracle(npes, 1024)
+    _fill(o, 4)
+    blocks = [o.heap[p][8:8 + n].copy() for p in range(npes)]
+    o.barrier_exchange(256, 8, 512, n, 3)
+    for p in range(npes):
+        for r in range(3):
+            assert (o.heap[p][512 + r * n:512 + (r + 1) * n] == blocks[(p - 1 - r) % npes]).all()
+    assert o.log.count(("barrier_all",)) == 3

@@ -1,0 +1,52 @@
+"""GPU parity: device-side sync/barrier among PEs and broadcast."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2409_20476_amd import shm as S
+from parity_util import assert_heaps_equal, fill_random, make_pair
+
+pytestmark = pytest.mark.gpu
+
+MiB = 1 << 20
+
+
+@pytest.mark.parametrize("npes,n,rounds", [(2, 1000, 2), (8, 65536 + 24, 8), (16, 4096, 5), (1, 100, 1), (5, 300001, 4)])
+def test_barrier_exchange(npes, n, rounds):
+    g, o = make_pair(npes, 16 * MiB)
+    with g:
+        fill_random(g, o, 41, upto=14 * MiB)
+        src, dst, acc = 64, MiB, 8 * MiB
+        for rep in range(3):                      # the sync counters and epochs carry over from launch to launch
+            g.launch_barrier_exchange(dst, src + rep, acc, n, rounds)
+            g.barrier_all()
+            o.barrier_exchange(dst, src + rep, acc, n, rounds)
+            assert_heaps_equal(g, o, upto=14 * MiB, what=f"rep {rep}")
+
+
+def test_sync_all_counts_and_is_timed():
+    g, o = make_pair(8, MiB)
+    with g:
+        t = torch.zeros(2, dtype=torch.int64, device="cuda")
+        for with_quiet in (0, 1):
+            t[0], t[1] = -1, 0
+            torch.cuda.synchronize()
+            g.launch_sync_all(100, with_quiet, t)
+            g.barrier_all()
+            a, b = (int(v) & ((1 << 64) - 1) for v in t.tolist())
+            us = (b - a) / g.wall_clock_khz() * 1e3 / 100
+            assert 0.1 < us < 1000, us
+
+
+@pytest.mark.parametrize("path", [S.SHM_PATH_LDST, S.SHM_PATH_SDMA, S.SHM_PATH_MEMCPY])
+@pytest.mark.parametrize("npes,n,root,n_wg,soff,doff", [(8, 100003, 3, 4, 5, 9), (2, 16, 1, 1, 0, 0), (5, 3 * MiB + 64, 0, 64, 0, 0),
+                                                       (4, 0, 2, 8, 0, 0)])
+def test_broadcast(path, npes, n, root, n_wg, soff, doff):
+    g, o = make_pair(npes, 16 * MiB)
+    with g:
+        fill_random(g, o, 42, upto=12 * MiB)
+        src, dst = 1024 + soff, 6 * MiB + doff
+        g.launch_broadcast(dst, src, n, root, n_wg, path)
+        g.barrier_all()
+        o.broadcast(dst, src, n, root)
+        assert_heaps_equal(g, o, upto=12 * MiB)
