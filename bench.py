@@ -482,6 +482,16 @@ def collectives(torch, S, synth, g, args):
         out[f"reduce_duplicate_wg{n_wg}"] = {"ms": ms, "algorithmic_gbs": dup_bytes / ms / 1e6, "frac_hbm": dup_bytes / ms / 1e6 / HBM_PEAK_GBS}
         ms = best_of(lambda: g.launch_reduce_sum_f32(rdst, rsrc, nel, n_wg, S.SHM_REDUCE_SPLIT))
         out[f"reduce_split_wg{n_wg}"] = {"ms": ms, "algorithmic_gbs": spl_bytes / ms / 1e6, "frac_hbm": spl_bytes / ms / 1e6 / HBM_PEAK_GBS}
+    # the reduction matrix on the same 64 MiB per PE: one operator per element width (HBM-bound, so the
+    # type only changes the arithmetic per byte)
+    matrix = {}
+    for name, dtype, op, width in (("uint8_xor", S.SHM_UINT8, S.SHM_OP_XOR, 1), ("int8_max", S.SHM_INT8, S.SHM_OP_MAX, 1),
+                                   ("int16_sum", S.SHM_INT16, S.SHM_OP_SUM, 2), ("int32_sum", S.SHM_INT32, S.SHM_OP_SUM, 4),
+                                   ("float32_sum", S.SHM_FLOAT32, S.SHM_OP_SUM, 4), ("float32_max", S.SHM_FLOAT32, S.SHM_OP_MAX, 4),
+                                   ("int64_prod", S.SHM_INT64, S.SHM_OP_PROD, 8), ("float64_sum", S.SHM_FLOAT64, S.SHM_OP_SUM, 8)):
+        ms = best_of(lambda: g.launch_reduce(rdst, rsrc, 4 * nel // width, dtype, op, 1024))
+        matrix[name] = {"ms": ms, "algorithmic_gbs": dup_bytes / ms / 1e6, "frac_hbm": dup_bytes / ms / 1e6 / HBM_PEAK_GBS}
+    out["reduce_matrix_wg1024"] = matrix
     g.set_team_sync(True)
     for off in (fsrc, fdst, rsrc, rdst):
         g.free(off)
@@ -543,8 +553,9 @@ def main():
         log(f"[bench] reverse offload: rtt {extras['reverse_offload']['round_trip_us']} rate {extras['reverse_offload']['request_rate_mreq_s']} "
             f"cutover {extras['reverse_offload']['cutover_bytes_by_work_items']}")
         extras["collective_sweeps"] = collective_sweeps(torch, S, args)
-        log(f"[bench] sync us by PEs {extras['collective_sweeps']['sync_us_by_pes']} barrier {extras['collective_sweeps']['barrier_us_by_pes']} "
-            f"fcollect cutover {{k: v['cutover_bytes_per_pe'] for k, v in extras['collective_sweeps']['fcollect'].items()}}")
+        cs = extras["collective_sweeps"]
+        log(f"[bench] sync us by PEs {cs['sync_us_by_pes']} barrier {cs['barrier_us_by_pes']} fcollect cutover "
+            f"{dict((k, v['cutover_bytes_per_pe']) for k, v in cs['fcollect'].items())}")
         extras["config3_ring"] = ring(torch, S, synth, g, args)
         log(f"[bench] c3: {extras['config3_ring']}")
         extras["config4_amo_storm"] = storm(torch, S, synth, args)

@@ -54,6 +54,9 @@ enum { SHM_AMO_FETCH = 0, SHM_AMO_SET = 1, SHM_AMO_SWAP = 2, SHM_AMO_COMPARE_SWA
        SHM_AMO_FETCH_ADD = 4, SHM_AMO_ADD = 5, SHM_AMO_FETCH_INC = 6, SHM_AMO_INC = 7 };
 enum { SHM_STORM_FETCH_ADD = 0, SHM_STORM_ADD = 1, SHM_STORM_CSWAP_LOOP = 2, SHM_STORM_PLAIN_STORE = 3 };
 enum { SHM_REDUCE_DUPLICATE = 0, SHM_REDUCE_SPLIT = 1 };
+enum { SHM_OP_MIN = 0, SHM_OP_MAX = 1, SHM_OP_SUM = 2, SHM_OP_PROD = 3, SHM_OP_AND = 4, SHM_OP_OR = 5, SHM_OP_XOR = 6 };
+enum { SHM_INT8 = 0, SHM_UINT8 = 1, SHM_INT16 = 2, SHM_UINT16 = 3, SHM_INT32 = 4, SHM_UINT32 = 5, SHM_INT64 = 6, SHM_UINT64 = 7,
+       SHM_FLOAT32 = 8, SHM_FLOAT64 = 9 };
 
 typedef struct shm_ctx shm_ctx;
 
@@ -243,6 +246,14 @@ int shm_launch_amo_storm(shm_ctx *ctx, uint64_t ctr_off, int n_ctr, const uint16
  * every PE p.  LDST: one grid, each source vector loaded once and stored to all PEs.  SDMA /
  * MEMCPY: npes*npes copies.  AUTO uses the cutover of n_wg on bytes_per_pe. */
 int shm_launch_fcollect(shm_ctx *ctx, uint64_t dst_off, uint64_t src_off, size_t bytes_per_pe, int n_wg, int path);
+
+/* The reduction matrix (paper section "Collective Operations", reduction paragraph): min, max, sum,
+ * product, and, or, xor over 8..64-bit integers; min, max, sum, product over float and double
+ * (and/or/xor with a floating type: SHM_EINVAL).  Element i of every PE's dst_off becomes
+ * x0[i] op x1[i] op ... in PE order; every PE duplicates the computation from one local and npes-1
+ * remote vector loads.  Integer sums and products wrap; min/max keep the earlier operand on ties.
+ * Offsets 16-byte aligned. */
+int shm_launch_reduce(shm_ctx *ctx, uint64_t dst_off, uint64_t src_off, size_t nelems, int dtype, int op, int n_wg);
 
 /* Broadcast (paper section "Collective Operations": push, inner loop over destinations): every
  * PE's dst_off receives the n bytes at src_off of PE `root` (the root's own dst_off too).  LDST:

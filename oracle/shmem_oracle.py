@@ -321,6 +321,47 @@ class ShmemOracle:
             for p in range(self.npes):
                 self.heap[q][dst + p * n:dst + (p + 1) * n] = blocks[p]
 
+    REDUCE_OPS = ("min", "max", "sum", "prod", "and", "or", "xor")
+
+    def reduce(self, dst: int, src: int, nelems: int, dtype, op: str) -> np.ndarray:
+        """Element-wise ``x0 op x1 op ... `` over PEs in the order 0, 1, ..., npes-1; every PE's
+        destination receives the result.  Integer sum/prod wrap to the element width; min/max keep
+        the earlier operand on ties; and/or/xor are for integer types only."""
+        dt = np.dtype(dtype)
+        if op not in self.REDUCE_OPS:
+            raise OracleError("unknown reduction")
+        if op in ("and", "or", "xor") and dt.kind not in "iu":
+            raise OracleError("bitwise reductions need an integer type")
+        nb = dt.itemsize * nelems
+        self._range(src, nb), self._range(dst, nb)
+        if src % 16 or dst % 16:
+            raise OracleError("reduction buffers must be 16-byte aligned")
+        if nelems and src < dst + nb and dst < src + nb:
+            raise OracleError("overlapping source and destination")
+        vecs = [self.heap[p][src:src + nb].copy().view(dt) for p in range(self.npes)]
+        r = vecs[0].copy()
+        with np.errstate(over="ignore"):
+            for p in range(1, self.npes):
+                x = vecs[p]
+                if op == "min":
+                    r = np.where(x < r, x, r)
+                elif op == "max":
+                    r = np.where(x > r, x, r)
+                elif op == "sum":
+                    r = (r + x).astype(dt)
+                elif op == "prod":
+                    r = (r * x).astype(dt)
+                elif op == "and":
+                    r = r & x
+                elif op == "or":
+                    r = r | x
+                else:
+                    r = r ^ x
+        out = np.ascontiguousarray(r, dtype=dt).view(np.uint8)
+        for q in range(self.npes):
+            self.heap[q][dst:dst + nb] = out
+        return r
+
     def broadcast(self, dst: int, src: int, n: int, root: int) -> None:
         """Bytes [src, src+n) of PE ``root`` land at [dst, dst+n) of every PE, the root included."""
         self._pe(root)

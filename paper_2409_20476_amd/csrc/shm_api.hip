@@ -315,6 +315,47 @@ int wg_rma_all(shm_ctx *c, int pe_shift, uint64_t dst_off, uint64_t src_off, siz
 
 }  // namespace
 
+namespace {
+
+typedef void (*reduce_kernel)(shm_dev_ctx, uint64_t, uint64_t, size_t);
+
+template <typename T>
+reduce_kernel reduce_kernel_for(int op, bool bitwise_ok)
+{
+    switch (op) {
+    case SHM_OP_MIN: return shmk_reduce<T, SHMK_OP_MIN>;
+    case SHM_OP_MAX: return shmk_reduce<T, SHMK_OP_MAX>;
+    case SHM_OP_SUM: return shmk_reduce<T, SHMK_OP_SUM>;
+    case SHM_OP_PROD: return shmk_reduce<T, SHMK_OP_PROD>;
+    case SHM_OP_AND: return bitwise_ok ? shmk_reduce<T, SHMK_OP_AND> : nullptr;
+    case SHM_OP_OR: return bitwise_ok ? shmk_reduce<T, SHMK_OP_OR> : nullptr;
+    case SHM_OP_XOR: return bitwise_ok ? shmk_reduce<T, SHMK_OP_XOR> : nullptr;
+    default: return nullptr;
+    }
+}
+
+// Signed and unsigned integers of one width share every kernel except min and max.
+reduce_kernel pick_reduce(int dtype, int op, size_t *elem)
+{
+    const bool order = op == SHM_OP_MIN || op == SHM_OP_MAX;
+    switch (dtype) {
+    case SHM_INT8: *elem = 1; return order ? reduce_kernel_for<int8_t>(op, true) : reduce_kernel_for<uint8_t>(op, true);
+    case SHM_UINT8: *elem = 1; return reduce_kernel_for<uint8_t>(op, true);
+    case SHM_INT16: *elem = 2; return order ? reduce_kernel_for<int16_t>(op, true) : reduce_kernel_for<uint16_t>(op, true);
+    case SHM_UINT16: *elem = 2; return reduce_kernel_for<uint16_t>(op, true);
+    case SHM_INT32: *elem = 4; return order ? reduce_kernel_for<int32_t>(op, true) : reduce_kernel_for<uint32_t>(op, true);
+    case SHM_UINT32: *elem = 4; return reduce_kernel_for<uint32_t>(op, true);
+    case SHM_INT64: *elem = 8; return order ? reduce_kernel_for<int64_t>(op, true) : reduce_kernel_for<uint64_t>(op, true);
+    case SHM_UINT64: *elem = 8; return reduce_kernel_for<uint64_t>(op, true);
+    case SHM_FLOAT32: *elem = 4; return reduce_kernel_for<float>(op, false);
+    case SHM_FLOAT64: *elem = 8; return reduce_kernel_for<double>(op, false);
+    default: *elem = 0; return nullptr;
+    }
+}
+
+}  // namespace
+
+
 extern "C" {
 
 const char *shm_last_error(void) { return g_err.c_str(); }
@@ -875,6 +916,32 @@ int shm_launch_fcollect(shm_ctx *c, uint64_t dst_off, uint64_t src_off, size_t b
     } else
         hipLaunchKernelGGL(shmk_fcollect_any, grid, block, 0, c->stream[0], dev_view(c), dst_off, src_off, bytes_per_pe);
     if (int r = launched("fcollect")) return r;
+    if (c->team_sync)
+        if (int r = team_fork(c)) return r;
+    return SHM_OK;
+}
+
+int shm_launch_reduce(shm_ctx *c, uint64_t dst_off, uint64_t src_off, size_t nelems, int dtype, int op, int n_wg)
+{
+    if (int r = check_ctx(c)) return r;
+    size_t elem = 0;
+    const reduce_kernel k = pick_reduce(dtype, op, &elem);
+    if (elem == 0) return fail(SHM_EINVAL, "unknown element type %d", dtype);
+    if (op < SHM_OP_MIN || op > SHM_OP_XOR) return fail(SHM_EINVAL, "unknown reduction %d", op);
+    if (!k) return fail(SHM_EINVAL, "and/or/xor are defined for integer types only");
+    if (nelems > c->user_bytes / elem) return fail(SHM_ERANGE, "vector leaves the heap");
+    if (int r = check_range(c, src_off, nelems * elem, "source")) return r;
+    if (int r = check_range(c, dst_off, nelems * elem, "destination")) return r;
+    if ((src_off | dst_off) & 15) return fail(SHM_EINVAL, "reduction buffers must be 16-byte aligned");
+    if (overlaps(dst_off, src_off, nelems * elem)) return fail(SHM_EINVAL, "source and destination overlap");
+    if (int r = check_n_wg(n_wg)) return r;
+    if (c->no_device) return no_device("shm_launch_reduce");
+    if (int r = drain_all_engines(c)) return r;
+    if (nelems == 0) return SHM_OK;
+    if (c->team_sync)
+        if (int r = team_join(c)) return r;
+    hipLaunchKernelGGL(k, dim3(n_wg, c->npes), dim3(SHMK_WG), 0, c->stream[0], dev_view(c), dst_off, src_off, nelems);
+    if (int r = launched("reduce")) return r;
     if (c->team_sync)
         if (int r = team_fork(c)) return r;
     return SHM_OK;

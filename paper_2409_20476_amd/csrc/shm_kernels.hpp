@@ -482,3 +482,73 @@ __global__ __launch_bounds__(SHMK_WG) void shmk_broadcast(shm_dev_ctx c, uint64_
 {
     shmx_broadcast_push(c, root, dst_off, src_off, n, blockIdx.x, gridDim.x);
 }
+
+// ---- the reduction matrix (paper section "Collective Operations", reduction paragraph) ------------
+// min, max, sum, product, and, or, xor over 8..64-bit integers; min, max, sum, product over float
+// and double.  Work is split by address across threads; every thread loads one 16-byte vector from
+// each PE in PE order 0..npes-1, folds them element by element and stores the result to its own
+// PE's destination; every PE (blockIdx.y) duplicates the computation, so no PE waits for another.
+// Integer sums and products wrap (computed in the unsigned type); min/max keep the earlier operand
+// on ties, which also fixes the sign of a zero.
+enum { SHMK_OP_MIN = 0, SHMK_OP_MAX = 1, SHMK_OP_SUM = 2, SHMK_OP_PROD = 3, SHMK_OP_AND = 4, SHMK_OP_OR = 5, SHMK_OP_XOR = 6 };
+
+template <typename T> struct shmk_arith { typedef T type; };
+template <> struct shmk_arith<int8_t> { typedef uint8_t type; };
+template <> struct shmk_arith<int16_t> { typedef uint16_t type; };
+template <> struct shmk_arith<int32_t> { typedef uint32_t type; };
+template <> struct shmk_arith<int64_t> { typedef uint64_t type; };
+
+template <typename T> __device__ __forceinline__ T shmk_bits_and(T a, T b) { return static_cast<T>(a & b); }
+template <typename T> __device__ __forceinline__ T shmk_bits_or(T a, T b) { return static_cast<T>(a | b); }
+template <typename T> __device__ __forceinline__ T shmk_bits_xor(T a, T b) { return static_cast<T>(a ^ b); }
+template <> __device__ __forceinline__ float shmk_bits_and<float>(float a, float) { return a; }      // never selected for
+template <> __device__ __forceinline__ float shmk_bits_or<float>(float a, float) { return a; }       // floating types: the
+template <> __device__ __forceinline__ float shmk_bits_xor<float>(float a, float) { return a; }      // host rejects them
+template <> __device__ __forceinline__ double shmk_bits_and<double>(double a, double) { return a; }
+template <> __device__ __forceinline__ double shmk_bits_or<double>(double a, double) { return a; }
+template <> __device__ __forceinline__ double shmk_bits_xor<double>(double a, double) { return a; }
+
+template <typename T, int OP>
+__device__ __forceinline__ T shmk_combine(T a, T b)
+{
+    typedef typename shmk_arith<T>::type A;
+    if (OP == SHMK_OP_MIN) return b < a ? b : a;
+    if (OP == SHMK_OP_MAX) return b > a ? b : a;
+    if (OP == SHMK_OP_SUM) return static_cast<T>(static_cast<A>(static_cast<A>(a) + static_cast<A>(b)));
+    if (OP == SHMK_OP_PROD) return static_cast<T>(static_cast<A>(static_cast<A>(a) * static_cast<A>(b)));
+    if (OP == SHMK_OP_AND) return shmk_bits_and<T>(a, b);
+    if (OP == SHMK_OP_OR) return shmk_bits_or<T>(a, b);
+    return shmk_bits_xor<T>(a, b);
+}
+
+template <typename T, int OP>
+__global__ __launch_bounds__(SHMK_WG) void shmk_reduce(shm_dev_ctx c, uint64_t dst_off, uint64_t src_off, size_t nelems)
+{
+    constexpr int EPV = 16 / sizeof(T);
+    union vec {
+        shm_u32x4 v;
+        T e[EPV];
+    };
+    const int q = blockIdx.y, npes = c.npes;
+    const size_t nvec = nelems / EPV;
+    const size_t per = (nvec + gridDim.x - 1) / gridDim.x;
+    const size_t lo = min(nvec, blockIdx.x * per), hi = min(nvec, lo + per);
+    for (size_t i = lo + threadIdx.x; i < hi; i += SHMK_WG) {
+        vec r;
+        r.v = shm_ld16(reinterpret_cast<const shm_u32x4 *>(shm_ptr(c, src_off, 0)) + i);
+        for (int p = 1; p < npes; ++p) {
+            vec x;
+            x.v = shm_ld16(reinterpret_cast<const shm_u32x4 *>(shm_ptr(c, src_off, p)) + i);
+#pragma unroll
+            for (int k = 0; k < EPV; ++k) r.e[k] = shmk_combine<T, OP>(r.e[k], x.e[k]);
+        }
+        shm_st16(reinterpret_cast<shm_u32x4 *>(shm_ptr(c, dst_off, q)) + i, r.v);
+    }
+    // the last nelems mod EPV elements, one thread each
+    const size_t i = nvec * EPV + threadIdx.x;
+    if (blockIdx.x == 0 && i < nelems) {
+        T r = reinterpret_cast<const T *>(shm_ptr(c, src_off, 0))[i];
+        for (int p = 1; p < npes; ++p) r = shmk_combine<T, OP>(r, reinterpret_cast<const T *>(shm_ptr(c, src_off, p))[i]);
+        reinterpret_cast<T *>(shm_ptr(c, dst_off, q))[i] = r;
+    }
+}

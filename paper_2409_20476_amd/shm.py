@@ -27,6 +27,9 @@ SHM_INIT_DEFAULT, SHM_INIT_NO_DEVICE = 0, 1
  SHM_AMO_INC) = range(8)
 SHM_STORM_FETCH_ADD, SHM_STORM_ADD, SHM_STORM_CSWAP_LOOP, SHM_STORM_PLAIN_STORE = range(4)
 SHM_REDUCE_DUPLICATE, SHM_REDUCE_SPLIT = 0, 1
+SHM_OP_MIN, SHM_OP_MAX, SHM_OP_SUM, SHM_OP_PROD, SHM_OP_AND, SHM_OP_OR, SHM_OP_XOR = range(7)
+(SHM_INT8, SHM_UINT8, SHM_INT16, SHM_UINT16, SHM_INT32, SHM_UINT32, SHM_INT64, SHM_UINT64, SHM_FLOAT32,
+ SHM_FLOAT64) = range(10)
 
 _ERR_NAMES = {SHM_EINVAL: "SHM_EINVAL", SHM_EPE: "SHM_EPE", SHM_ERANGE: "SHM_ERANGE", SHM_ENOMEM: "SHM_ENOMEM",
               SHM_EHIP: "SHM_EHIP", SHM_ETIMEOUT: "SHM_ETIMEOUT", SHM_ENODEV: "SHM_ENODEV"}
@@ -74,6 +77,7 @@ PROTOTYPES = {
     "shm_launch_ring_pipeline": (c_int, [c_void_p, c_uint64, c_uint64, c_uint64, c_uint64, c_size_t, c_int, c_int, c_int, c_int]),
     "shm_launch_amo_storm": (c_int, [c_void_p, c_uint64, c_int, c_void_p, c_uint64, c_int, c_int, c_void_p, c_void_p]),
     "shm_launch_fcollect": (c_int, [c_void_p, c_uint64, c_uint64, c_size_t, c_int, c_int]),
+    "shm_launch_reduce": (c_int, [c_void_p, c_uint64, c_uint64, c_size_t, c_int, c_int, c_int]),
     "shm_launch_broadcast": (c_int, [c_void_p, c_uint64, c_uint64, c_size_t, c_int, c_int, c_int]),
     "shm_launch_sync_all": (c_int, [c_void_p, c_int, c_int, c_void_p]),
     "shm_launch_barrier_exchange": (c_int, [c_void_p, c_uint64, c_uint64, c_uint64, c_size_t, c_int]),
@@ -284,6 +288,9 @@ class Shm:
 
     def launch_fcollect(self, dst_off, src_off, bytes_per_pe, n_wg=64, path=SHM_PATH_LDST):
         self._check(self.lib.shm_launch_fcollect(self.ctx, dst_off, src_off, bytes_per_pe, n_wg, path))
+
+    def launch_reduce(self, dst_off, src_off, nelems, dtype, op, n_wg=64):
+        self._check(self.lib.shm_launch_reduce(self.ctx, dst_off, src_off, nelems, dtype, op, n_wg))
 
     def launch_broadcast(self, dst_off, src_off, n, root, n_wg=64, path=SHM_PATH_LDST):
         self._check(self.lib.shm_launch_broadcast(self.ctx, dst_off, src_off, n, root, n_wg, path))

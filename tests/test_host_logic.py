@@ -150,6 +150,16 @@ def test_every_entry_point_validates_before_touching_the_device():
     assert code(lambda: g.launch_reduce_sum_f32(65538, 0, 1000, 2)) == S.SHM_EINVAL
     assert code(lambda: g.launch_reduce_sum_f32(0, 0, 1000, 2, 5)) == S.SHM_EINVAL
     assert code(lambda: g.launch_fcollect(100, 0, 1000, 2)) == S.SHM_EINVAL                                     # overlap
+    # the reduction matrix
+    assert code(lambda: g.launch_reduce(65536, 0, 1000, S.SHM_INT16, S.SHM_OP_XOR, 2)) == S.SHM_ENODEV
+    assert code(lambda: g.launch_reduce(65536, 0, 1000, S.SHM_FLOAT64, S.SHM_OP_PROD, 2)) == S.SHM_ENODEV
+    assert code(lambda: g.launch_reduce(65536, 0, 1000, S.SHM_FLOAT32, S.SHM_OP_AND, 2)) == S.SHM_EINVAL       # bitwise on float
+    assert code(lambda: g.launch_reduce(65536, 0, 1000, S.SHM_FLOAT64, S.SHM_OP_XOR, 2)) == S.SHM_EINVAL
+    assert code(lambda: g.launch_reduce(65536, 0, 1000, 10, S.SHM_OP_SUM, 2)) == S.SHM_EINVAL
+    assert code(lambda: g.launch_reduce(65536, 0, 1000, S.SHM_INT8, 7, 2)) == S.SHM_EINVAL
+    assert code(lambda: g.launch_reduce(65536, 8, 1000, S.SHM_INT8, S.SHM_OP_SUM, 2)) == S.SHM_EINVAL         # alignment
+    assert code(lambda: g.launch_reduce(512, 0, 1000, S.SHM_INT8, S.SHM_OP_SUM, 2)) == S.SHM_EINVAL           # overlap
+    assert code(lambda: g.launch_reduce(0, 65536, H, S.SHM_UINT64, S.SHM_OP_SUM, 2)) == S.SHM_ERANGE
     assert code(lambda: g.set_wait_timeout_us(0)) == S.SHM_EINVAL
     g.finalize()
 

@@ -1,0 +1,85 @@
+"""GPU parity: the reduction matrix, every element type with every operator, bit for bit."""
+import numpy as np
+import pytest
+
+from paper_2409_20476_amd import shm as S
+from parity_util import assert_heaps_equal, fill_random, make_pair, write_both
+
+pytestmark = pytest.mark.gpu
+
+MiB = 1 << 20
+DTYPES = {S.SHM_INT8: np.int8, S.SHM_UINT8: np.uint8, S.SHM_INT16: np.int16, S.SHM_UINT16: np.uint16, S.SHM_INT32: np.int32,
+          S.SHM_UINT32: np.uint32, S.SHM_INT64: np.int64, S.SHM_UINT64: np.uint64, S.SHM_FLOAT32: np.float32,
+          S.SHM_FLOAT64: np.float64}
+OPS = {S.SHM_OP_MIN: "min", S.SHM_OP_MAX: "max", S.SHM_OP_SUM: "sum", S.SHM_OP_PROD: "prod", S.SHM_OP_AND: "and", S.SHM_OP_OR: "or",
+       S.SHM_OP_XOR: "xor"}
+
+
+def _source(rng, dt, n):
+    """Integers: any bit pattern.  Floats: finite values of mixed sign and magnitude (no NaN, so the
+    result does not depend on how a NaN's payload travels), with exact ties and signed zeros."""
+    if dt.kind in "iu":
+        return rng.integers(0, 256, n * dt.itemsize, dtype=np.uint8).view(dt)
+    x = (rng.standard_normal(n) * np.exp2(rng.integers(-6, 6, n))).astype(dt)
+    x[rng.integers(0, n, max(1, n // 8))] = dt.type(1.5)
+    x[rng.integers(0, n, max(1, n // 16))] = dt.type(0.0)
+    x[rng.integers(0, n, max(1, n // 16))] = dt.type(-0.0)
+    return x
+
+
+@pytest.mark.parametrize("dtype", sorted(DTYPES))
+def test_every_operator(dtype):
+    dt = np.dtype(DTYPES[dtype])
+    npes, n = 8, 300007                                   # many groups' shares, whole vectors and a tail
+    g, o = make_pair(npes, 16 * MiB)
+    with g:
+        fill_random(g, o, 50 + dtype, upto=12 * MiB)
+        src, dst = 4096, 6 * MiB
+        rng = np.random.default_rng(500 + dtype)
+        for p in range(npes):
+            write_both(g, o, p, src, _source(rng, dt, n).view(np.uint8))
+        for op, name in OPS.items():
+            if dt.kind == "f" and op >= S.SHM_OP_AND:
+                with pytest.raises(S.ShmError):
+                    g.launch_reduce(dst, src, n, dtype, op, 16)
+                continue
+            g.launch_reduce(dst, src, n, dtype, op, 16)
+            g.barrier_all()
+            o.reduce(dst, src, n, dt, name)
+            assert_heaps_equal(g, o, upto=12 * MiB, what=f"{dt.name} {name}")
+
+
+@pytest.mark.parametrize("npes,n,n_wg", [(1, 1000, 4), (2, 1, 1), (3, 15, 64), (16, 4097, 1024), (5, 0, 8), (12, 65536, 3)])
+def test_shapes(npes, n, n_wg):
+    g, o = make_pair(npes, 4 * MiB)
+    with g:
+        fill_random(g, o, 77, upto=3 * MiB)
+        for dtype, op in [(S.SHM_INT16, S.SHM_OP_MAX), (S.SHM_UINT64, S.SHM_OP_PROD), (S.SHM_UINT8, S.SHM_OP_XOR)]:
+            g.launch_reduce(2 * MiB, 16, n, dtype, op, n_wg)
+            g.barrier_all()
+            o.reduce(2 * MiB, 16, n, DTYPES[dtype], OPS[op])
+            assert_heaps_equal(g, o, upto=3 * MiB, what=f"{dtype} {op}")
+
+
+def test_full_size_sum_matches_the_f32_entry_point_and_the_oracle():
+    # configuration 5's vector length (16 Mi elements, 8 PEs): int32 sum against the oracle, and the
+    # float32 sum of the matrix against the dedicated float32 entry point
+    npes, n = 8, 16 << 20
+    g, o = make_pair(npes, 200 * MiB)
+    with g:
+        src, dst, dst2 = 0, 64 * MiB, 128 * MiB
+        rng = np.random.default_rng(5)
+        for p in range(npes):
+            write_both(g, o, p, src, rng.integers(0, 256, 4 * n, dtype=np.uint8))
+        g.launch_reduce(dst, src, n, S.SHM_INT32, S.SHM_OP_SUM, 1024)
+        g.barrier_all()
+        want = o.reduce(dst, src, n, np.int32, "sum")
+        for p in (0, 3, 7):
+            assert np.array_equal(g.read(p, dst, 4 * n).view(np.int32), want)
+        for p in range(npes):
+            g.write(p, src, rng.standard_normal(n).astype(np.float32).view(np.uint8))
+        g.launch_reduce(dst, src, n, S.SHM_FLOAT32, S.SHM_OP_SUM, 1024)
+        g.launch_reduce_sum_f32(dst2, src, n, 1024)
+        g.barrier_all()
+        for p in (0, 7):
+            assert np.array_equal(g.read(p, dst, 4 * n), g.read(p, dst2, 4 * n))
