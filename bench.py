@@ -489,8 +489,10 @@ def collectives(torch, S, synth, g, args):
                                    ("int16_sum", S.SHM_INT16, S.SHM_OP_SUM, 2), ("int32_sum", S.SHM_INT32, S.SHM_OP_SUM, 4),
                                    ("float32_sum", S.SHM_FLOAT32, S.SHM_OP_SUM, 4), ("float32_max", S.SHM_FLOAT32, S.SHM_OP_MAX, 4),
                                    ("int64_prod", S.SHM_INT64, S.SHM_OP_PROD, 8), ("float64_sum", S.SHM_FLOAT64, S.SHM_OP_SUM, 8)):
-        ms = best_of(lambda: g.launch_reduce(rdst, rsrc, 4 * nel // width, dtype, op, 1024))
-        matrix[name] = {"ms": ms, "algorithmic_gbs": dup_bytes / ms / 1e6, "frac_hbm": dup_bytes / ms / 1e6 / HBM_PEAK_GBS}
+        ms = best_of(lambda: g.launch_reduce(rdst, rsrc, 4 * nel // width, dtype, op, 1024, S.SHM_REDUCE_DUPLICATE))
+        ms2 = best_of(lambda: g.launch_reduce(rdst, rsrc, 4 * nel // width, dtype, op, 1024, S.SHM_REDUCE_SPLIT))
+        matrix[name] = {"duplicate_ms": ms, "duplicate_frac_hbm": dup_bytes / ms / 1e6 / HBM_PEAK_GBS,
+                        "split_ms": ms2, "split_frac_hbm": spl_bytes / ms2 / 1e6 / HBM_PEAK_GBS}
     out["reduce_matrix_wg1024"] = matrix
     g.set_team_sync(True)
     for off in (fsrc, fdst, rsrc, rdst):

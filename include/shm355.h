@@ -251,9 +251,11 @@ int shm_launch_fcollect(shm_ctx *ctx, uint64_t dst_off, uint64_t src_off, size_t
  * product, and, or, xor over 8..64-bit integers; min, max, sum, product over float and double
  * (and/or/xor with a floating type: SHM_EINVAL).  Element i of every PE's dst_off becomes
  * x0[i] op x1[i] op ... in PE order; every PE duplicates the computation from one local and npes-1
- * remote vector loads.  Integer sums and products wrap; min/max keep the earlier operand on ties.
- * Offsets 16-byte aligned. */
-int shm_launch_reduce(shm_ctx *ctx, uint64_t dst_off, uint64_t src_off, size_t nelems, int dtype, int op, int n_wg);
+ * remote vector loads (algo SHM_REDUCE_DUPLICATE), or -- the method the same section names for very
+ * large reductions, algo SHM_REDUCE_SPLIT -- the vector is divided by address across PEs, each PE
+ * folds its slice and pushes the result to every PE.  Both give the same bits.  Integer sums and
+ * products wrap; min/max keep the earlier operand on ties.  Offsets 16-byte aligned. */
+int shm_launch_reduce(shm_ctx *ctx, uint64_t dst_off, uint64_t src_off, size_t nelems, int dtype, int op, int n_wg, int algo);
 
 /* Broadcast (paper section "Collective Operations": push, inner loop over destinations): every
  * PE's dst_off receives the n bytes at src_off of PE `root` (the root's own dst_off too).  LDST:

@@ -317,7 +317,7 @@ int wg_rma_all(shm_ctx *c, int pe_shift, uint64_t dst_off, uint64_t src_off, siz
 
 namespace {
 
-typedef void (*reduce_kernel)(shm_dev_ctx, uint64_t, uint64_t, size_t);
+typedef void (*reduce_kernel)(shm_dev_ctx, uint64_t, uint64_t, size_t, int);
 
 template <typename T>
 reduce_kernel reduce_kernel_for(int op, bool bitwise_ok)
@@ -921,7 +921,7 @@ int shm_launch_fcollect(shm_ctx *c, uint64_t dst_off, uint64_t src_off, size_t b
     return SHM_OK;
 }
 
-int shm_launch_reduce(shm_ctx *c, uint64_t dst_off, uint64_t src_off, size_t nelems, int dtype, int op, int n_wg)
+int shm_launch_reduce(shm_ctx *c, uint64_t dst_off, uint64_t src_off, size_t nelems, int dtype, int op, int n_wg, int algo)
 {
     if (int r = check_ctx(c)) return r;
     size_t elem = 0;
@@ -929,6 +929,7 @@ int shm_launch_reduce(shm_ctx *c, uint64_t dst_off, uint64_t src_off, size_t nel
     if (elem == 0) return fail(SHM_EINVAL, "unknown element type %d", dtype);
     if (op < SHM_OP_MIN || op > SHM_OP_XOR) return fail(SHM_EINVAL, "unknown reduction %d", op);
     if (!k) return fail(SHM_EINVAL, "and/or/xor are defined for integer types only");
+    if (algo != SHM_REDUCE_DUPLICATE && algo != SHM_REDUCE_SPLIT) return fail(SHM_EINVAL, "unknown reduction algorithm %d", algo);
     if (nelems > c->user_bytes / elem) return fail(SHM_ERANGE, "vector leaves the heap");
     if (int r = check_range(c, src_off, nelems * elem, "source")) return r;
     if (int r = check_range(c, dst_off, nelems * elem, "destination")) return r;
@@ -940,7 +941,8 @@ int shm_launch_reduce(shm_ctx *c, uint64_t dst_off, uint64_t src_off, size_t nel
     if (nelems == 0) return SHM_OK;
     if (c->team_sync)
         if (int r = team_join(c)) return r;
-    hipLaunchKernelGGL(k, dim3(n_wg, c->npes), dim3(SHMK_WG), 0, c->stream[0], dev_view(c), dst_off, src_off, nelems);
+    hipLaunchKernelGGL(k, dim3(n_wg, c->npes), dim3(SHMK_WG), 0, c->stream[0], dev_view(c), dst_off, src_off, nelems,
+                       algo == SHM_REDUCE_SPLIT ? 1 : 0);
     if (int r = launched("reduce")) return r;
     if (c->team_sync)
         if (int r = team_fork(c)) return r;

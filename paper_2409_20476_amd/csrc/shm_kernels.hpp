@@ -522,17 +522,28 @@ __device__ __forceinline__ T shmk_combine(T a, T b)
 }
 
 template <typename T, int OP>
-__global__ __launch_bounds__(SHMK_WG) void shmk_reduce(shm_dev_ctx c, uint64_t dst_off, uint64_t src_off, size_t nelems)
+__global__ __launch_bounds__(SHMK_WG) void shmk_reduce(shm_dev_ctx c, uint64_t dst_off, uint64_t src_off, size_t nelems, int split)
 {
+    // split == 0: every PE folds the whole vector into its own destination (the paper's method: no
+    // PE waits for another).  split != 0: the method the paper names for very large reductions --
+    // the vector is divided by address across PEs; PE q folds only its slice and pushes the result
+    // to every PE's destination, so each source byte is read once instead of npes times.
     constexpr int EPV = 16 / sizeof(T);
     union vec {
         shm_u32x4 v;
         T e[EPV];
     };
     const int q = blockIdx.y, npes = c.npes;
+    const int d0 = split ? 0 : q, d1 = split ? npes : q + 1;
     const size_t nvec = nelems / EPV;
-    const size_t per = (nvec + gridDim.x - 1) / gridDim.x;
-    const size_t lo = min(nvec, blockIdx.x * per), hi = min(nvec, lo + per);
+    size_t vlo = 0, vhi = nvec;
+    if (split) {
+        const size_t per_pe = (nvec + npes - 1) / npes;
+        vlo = min(nvec, q * per_pe);
+        vhi = min(nvec, vlo + per_pe);
+    }
+    const size_t per = (vhi - vlo + gridDim.x - 1) / gridDim.x;
+    const size_t lo = min(vhi, vlo + blockIdx.x * per), hi = min(vhi, lo + per);
     for (size_t i = lo + threadIdx.x; i < hi; i += SHMK_WG) {
         vec r;
         r.v = shm_ld16(reinterpret_cast<const shm_u32x4 *>(shm_ptr(c, src_off, 0)) + i);
@@ -542,13 +553,13 @@ __global__ __launch_bounds__(SHMK_WG) void shmk_reduce(shm_dev_ctx c, uint64_t d
 #pragma unroll
             for (int k = 0; k < EPV; ++k) r.e[k] = shmk_combine<T, OP>(r.e[k], x.e[k]);
         }
-        shm_st16(reinterpret_cast<shm_u32x4 *>(shm_ptr(c, dst_off, q)) + i, r.v);
+        for (int d = d0; d < d1; ++d) shm_st16(reinterpret_cast<shm_u32x4 *>(shm_ptr(c, dst_off, d)) + i, r.v);
     }
     // the last nelems mod EPV elements, one thread each
     const size_t i = nvec * EPV + threadIdx.x;
-    if (blockIdx.x == 0 && i < nelems) {
+    if (blockIdx.x == 0 && (!split || q == 0) && i < nelems) {
         T r = reinterpret_cast<const T *>(shm_ptr(c, src_off, 0))[i];
         for (int p = 1; p < npes; ++p) r = shmk_combine<T, OP>(r, reinterpret_cast<const T *>(shm_ptr(c, src_off, p))[i]);
-        reinterpret_cast<T *>(shm_ptr(c, dst_off, q))[i] = r;
+        for (int d = d0; d < d1; ++d) reinterpret_cast<T *>(shm_ptr(c, dst_off, d))[i] = r;
     }
 }

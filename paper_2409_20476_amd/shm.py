@@ -77,7 +77,7 @@ PROTOTYPES = {
     "shm_launch_ring_pipeline": (c_int, [c_void_p, c_uint64, c_uint64, c_uint64, c_uint64, c_size_t, c_int, c_int, c_int, c_int]),
     "shm_launch_amo_storm": (c_int, [c_void_p, c_uint64, c_int, c_void_p, c_uint64, c_int, c_int, c_void_p, c_void_p]),
     "shm_launch_fcollect": (c_int, [c_void_p, c_uint64, c_uint64, c_size_t, c_int, c_int]),
-    "shm_launch_reduce": (c_int, [c_void_p, c_uint64, c_uint64, c_size_t, c_int, c_int, c_int]),
+    "shm_launch_reduce": (c_int, [c_void_p, c_uint64, c_uint64, c_size_t, c_int, c_int, c_int, c_int]),
     "shm_launch_broadcast": (c_int, [c_void_p, c_uint64, c_uint64, c_size_t, c_int, c_int, c_int]),
     "shm_launch_sync_all": (c_int, [c_void_p, c_int, c_int, c_void_p]),
     "shm_launch_barrier_exchange": (c_int, [c_void_p, c_uint64, c_uint64, c_uint64, c_size_t, c_int]),
@@ -289,8 +289,8 @@ class Shm:
     def launch_fcollect(self, dst_off, src_off, bytes_per_pe, n_wg=64, path=SHM_PATH_LDST):
         self._check(self.lib.shm_launch_fcollect(self.ctx, dst_off, src_off, bytes_per_pe, n_wg, path))
 
-    def launch_reduce(self, dst_off, src_off, nelems, dtype, op, n_wg=64):
-        self._check(self.lib.shm_launch_reduce(self.ctx, dst_off, src_off, nelems, dtype, op, n_wg))
+    def launch_reduce(self, dst_off, src_off, nelems, dtype, op, n_wg=64, algo=SHM_REDUCE_DUPLICATE):
+        self._check(self.lib.shm_launch_reduce(self.ctx, dst_off, src_off, nelems, dtype, op, n_wg, algo))
 
     def launch_broadcast(self, dst_off, src_off, n, root, n_wg=64, path=SHM_PATH_LDST):
         self._check(self.lib.shm_launch_broadcast(self.ctx, dst_off, src_off, n, root, n_wg, path))

@@ -157,6 +157,8 @@ def test_every_entry_point_validates_before_touching_the_device():
     assert code(lambda: g.launch_reduce(65536, 0, 1000, S.SHM_FLOAT64, S.SHM_OP_XOR, 2)) == S.SHM_EINVAL
     assert code(lambda: g.launch_reduce(65536, 0, 1000, 10, S.SHM_OP_SUM, 2)) == S.SHM_EINVAL
     assert code(lambda: g.launch_reduce(65536, 0, 1000, S.SHM_INT8, 7, 2)) == S.SHM_EINVAL
+    assert code(lambda: g.launch_reduce(65536, 0, 1000, S.SHM_INT8, S.SHM_OP_SUM, 2, 2)) == S.SHM_EINVAL      # algorithm
+    assert code(lambda: g.launch_reduce(65536, 0, 1000, S.SHM_INT8, S.SHM_OP_SUM, 2, S.SHM_REDUCE_SPLIT)) == S.SHM_ENODEV
     assert code(lambda: g.launch_reduce(65536, 8, 1000, S.SHM_INT8, S.SHM_OP_SUM, 2)) == S.SHM_EINVAL         # alignment
     assert code(lambda: g.launch_reduce(512, 0, 1000, S.SHM_INT8, S.SHM_OP_SUM, 2)) == S.SHM_EINVAL           # overlap
     assert code(lambda: g.launch_reduce(0, 65536, H, S.SHM_UINT64, S.SHM_OP_SUM, 2)) == S.SHM_ERANGE

@@ -43,10 +43,13 @@ def test_every_operator(dtype):
                 with pytest.raises(S.ShmError):
                     g.launch_reduce(dst, src, n, dtype, op, 16)
                 continue
-            g.launch_reduce(dst, src, n, dtype, op, 16)
-            g.barrier_all()
             o.reduce(dst, src, n, dt, name)
-            assert_heaps_equal(g, o, upto=12 * MiB, what=f"{dt.name} {name}")
+            for algo in (S.SHM_REDUCE_DUPLICATE, S.SHM_REDUCE_SPLIT):
+                g.launch_reduce(dst, src, n, dtype, op, 16, algo)
+                g.barrier_all()
+                assert_heaps_equal(g, o, upto=12 * MiB, what=f"{dt.name} {name} algo {algo}")
+                for p in range(npes):                     # spoil the result so the second algorithm has to write it again
+                    g.write(p, dst, np.full(n * dt.itemsize, 0xA5, np.uint8))
 
 
 @pytest.mark.parametrize("npes,n,n_wg", [(1, 1000, 4), (2, 1, 1), (3, 15, 64), (16, 4097, 1024), (5, 0, 8), (12, 65536, 3)])
@@ -55,10 +58,13 @@ def test_shapes(npes, n, n_wg):
     with g:
         fill_random(g, o, 77, upto=3 * MiB)
         for dtype, op in [(S.SHM_INT16, S.SHM_OP_MAX), (S.SHM_UINT64, S.SHM_OP_PROD), (S.SHM_UINT8, S.SHM_OP_XOR)]:
-            g.launch_reduce(2 * MiB, 16, n, dtype, op, n_wg)
-            g.barrier_all()
-            o.reduce(2 * MiB, 16, n, DTYPES[dtype], OPS[op])
-            assert_heaps_equal(g, o, upto=3 * MiB, what=f"{dtype} {op}")
+            for algo in (S.SHM_REDUCE_DUPLICATE, S.SHM_REDUCE_SPLIT):
+                o.reduce(2 * MiB, 16, n, DTYPES[dtype], OPS[op])
+                g.launch_reduce(2 * MiB, 16, n, dtype, op, n_wg, algo)
+                g.barrier_all()
+                assert_heaps_equal(g, o, upto=3 * MiB, what=f"{dtype} {op} algo {algo}")
+                for p in range(npes if n else 0):         # spoil the result so the next launch has to write it again
+                    write_both(g, o, p, 2 * MiB, np.full(n * np.dtype(DTYPES[dtype]).itemsize, 0x5A, np.uint8))
 
 
 def test_full_size_sum_matches_the_f32_entry_point_and_the_oracle():
@@ -71,11 +77,13 @@ def test_full_size_sum_matches_the_f32_entry_point_and_the_oracle():
         rng = np.random.default_rng(5)
         for p in range(npes):
             write_both(g, o, p, src, rng.integers(0, 256, 4 * n, dtype=np.uint8))
-        g.launch_reduce(dst, src, n, S.SHM_INT32, S.SHM_OP_SUM, 1024)
-        g.barrier_all()
         want = o.reduce(dst, src, n, np.int32, "sum")
-        for p in (0, 3, 7):
-            assert np.array_equal(g.read(p, dst, 4 * n).view(np.int32), want)
+        for algo in (S.SHM_REDUCE_DUPLICATE, S.SHM_REDUCE_SPLIT):
+            g.launch_reduce(dst, src, n, S.SHM_INT32, S.SHM_OP_SUM, 1024, algo)
+            g.barrier_all()
+            for p in (0, 3, 7):
+                assert np.array_equal(g.read(p, dst, 4 * n).view(np.int32), want)
+                g.write(p, dst, np.zeros(4096, np.uint8))
         for p in range(npes):
             g.write(p, src, rng.standard_normal(n).astype(np.float32).view(np.uint8))
         g.launch_reduce(dst, src, n, S.SHM_FLOAT32, S.SHM_OP_SUM, 1024)
