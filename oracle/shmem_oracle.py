@@ -185,6 +185,44 @@ class ShmemOracle:
             raise OracleError("overlapping source and destination on one PE")
         self.heap[me][dst:dst + n] = self.heap[pe][src:src + n].copy()
 
+    def _strided(self, me, pe, dst, src, dst_stride, src_stride, nelems, elem_bytes):
+        self._pe(me), self._pe(pe)
+        if elem_bytes not in (1, 2, 4, 8, 16):
+            raise OracleError("element size must be 1, 2, 4, 8 or 16 bytes")
+        if dst_stride < 1 or src_stride < 1:
+            raise OracleError("strides are counted in elements and are at least 1")
+        if dst % elem_bytes or src % elem_bytes:
+            raise OracleError("strided transfers need element-aligned addresses")
+        dspan = ((nelems - 1) * dst_stride + 1) * elem_bytes if nelems else 0
+        sspan = ((nelems - 1) * src_stride + 1) * elem_bytes if nelems else 0
+        self._range(src, sspan), self._range(dst, dspan)
+        if me == pe and nelems and src < dst + dspan and dst < src + sspan:
+            raise OracleError("overlapping source and destination on one PE")
+
+    def iput(self, me: int, dst: int, src: int, dst_stride: int, src_stride: int, nelems: int, elem_bytes: int,
+             pe: int) -> None:
+        """Strided put (paper section "Implementation", blocked and strided RMA; OpenSHMEM iput):
+        element i of the source, taken every ``src_stride`` elements on PE ``me``, becomes element
+        i of the destination, placed every ``dst_stride`` elements on PE ``pe``.  Bytes between the
+        destination elements are not touched."""
+        self._strided(me, pe, dst, src, dst_stride, src_stride, nelems, elem_bytes)
+        picked = [self.heap[me][src + i * src_stride * elem_bytes: src + i * src_stride * elem_bytes + elem_bytes].copy()
+                  for i in range(nelems)]
+        for i in range(nelems):
+            at = dst + i * dst_stride * elem_bytes
+            self.heap[pe][at:at + elem_bytes] = picked[i]
+
+    def iget(self, me: int, dst: int, src: int, dst_stride: int, src_stride: int, nelems: int, elem_bytes: int,
+             pe: int) -> None:
+        """Strided get: as iput with the roles exchanged -- the source is on PE ``pe``, the
+        destination on the calling PE ``me``."""
+        self._strided(pe, me, dst, src, dst_stride, src_stride, nelems, elem_bytes)
+        picked = [self.heap[pe][src + i * src_stride * elem_bytes: src + i * src_stride * elem_bytes + elem_bytes].copy()
+                  for i in range(nelems)]
+        for i in range(nelems):
+            at = dst + i * dst_stride * elem_bytes
+            self.heap[me][at:at + elem_bytes] = picked[i]
+
     @staticmethod
     def wg_slices(n: int, n_wg: int) -> list[tuple[int, int]]:
         """How ``n_wg`` work-groups share one message of ``n`` bytes.
