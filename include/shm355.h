@@ -186,6 +186,39 @@ int shm_proxy_stats(const shm_ctx *ctx, uint64_t *requests, uint64_t *copies);
 int shm_launch_put_device_initiated(shm_ctx *ctx, int me, int pe, uint64_t dst_off, uint64_t src_off, size_t n, int n_wg, int wg_size,
                                     int mode, size_t cutover, int reps, uint64_t *dev_ticks);
 
+/* The general form: put (is_get 0) or get (is_get 1; n bytes from pe's src_off to me's dst_off:
+ * the paper's get_work_group and get_nbi_work_group, section "Proposed Device APIs").  Modes 0-3 as
+ * above (a get by loads/stores needs no quiet); mode 4 is the refinement the paper's implementation
+ * notes sketch for the cutover: the engine moves all but the first `cover` bytes of a group's share
+ * while the group moves those first bytes with loads and stores, covering the engine's start-up
+ * time; then both are waited for.  consume_off (get only; SHM_NO_CONSUME = none): offset on PE me
+ * of n bytes that do not overlap the transfer; the group copies its share of the destination there
+ * before the first get and after every get, from inside the kernel, so the buffer shows what the
+ * kernel itself reads after a get.  dev_ticks may be NULL. */
+#define SHM_NO_CONSUME UINT64_MAX
+int shm_launch_rma_device_initiated(shm_ctx *ctx, int me, int pe, uint64_t dst_off, uint64_t src_off, size_t n, int n_wg, int wg_size,
+                                    int is_get, int mode, size_t cutover, size_t cover, uint64_t consume_off, int reps,
+                                    uint64_t *dev_ticks);
+
+/* Single-thread put/get (paper section "Performance Evaluation", first experiment: ishmem_put and
+ * ishmem_get called by one work-item): one thread of one kernel on me's stream moves n bytes `reps`
+ * times, a quiet after each put.  dev_ticks as above, or NULL. */
+int shm_launch_thread_rma(shm_ctx *ctx, int me, int pe, uint64_t dst_off, uint64_t src_off, size_t n, int is_get, int reps,
+                          uint64_t *dev_ticks);
+
+/* Strided put/get (paper section "Implementation": blocked and strided RMA on vector copies;
+ * OpenSHMEM iput/iget).  iput: element i of me's source, i = 0..nelems-1, taken every src_stride
+ * elements from src_off, becomes the element at dst_off + i * dst_stride elements on pe; bytes
+ * between destination elements are untouched.  iget: the source is on pe, the destination on me.
+ * elem_bytes in {1, 2, 4, 8, 16}; strides >= 1, in elements; offsets multiples of elem_bytes.
+ * n_wg = 0: one work-item does it all (the single-thread call); n_wg >= 1: that many work-groups
+ * share the elements (the work-group call).  Delivered after shm_quiet(me).  SHM_EINVAL for a bad
+ * element size, stride, alignment or overlap on one PE; SHM_ERANGE if either side leaves the heap. */
+int shm_launch_iput(shm_ctx *ctx, int me, int pe, uint64_t dst_off, uint64_t src_off, int64_t dst_stride, int64_t src_stride,
+                    size_t nelems, int elem_bytes, int n_wg);
+int shm_launch_iget(shm_ctx *ctx, int me, int pe, uint64_t dst_off, uint64_t src_off, int64_t dst_stride, int64_t src_stride,
+                    size_t nelems, int elem_bytes, int n_wg);
+
 /* Ring micro-benchmark: the leader wave of each of n_wg groups (1..4096) sends `reps` empty
  * requests; blocking != 0: it waits for every answer (round trips), else it fires them and waits
  * once at the end (request rate).  dev_ticks as above. */

@@ -686,22 +686,98 @@ int shm_proxy_stats(const shm_ctx *c, uint64_t *requests, uint64_t *copies)
     return SHM_OK;
 }
 
-int shm_launch_put_device_initiated(shm_ctx *c, int me, int pe, uint64_t dst_off, uint64_t src_off, size_t n, int n_wg, int wg_size,
-                                    int mode, size_t cutover, int reps, uint64_t *dev_ticks)
+int shm_launch_rma_device_initiated(shm_ctx *c, int me, int pe, uint64_t dst_off, uint64_t src_off, size_t n, int n_wg, int wg_size,
+                                    int is_get, int mode, size_t cutover, size_t cover, uint64_t consume_off, int reps,
+                                    uint64_t *dev_ticks)
 {
     if (int r = check_ctx(c)) return r;
     if (int r = rma_args(c, me, pe, dst_off, src_off, n)) return r;
     if (n_wg < 1 || n_wg > 1024) return fail(SHM_EINVAL, "n_wg outside 1..1024");
     if (wg_size < 64 || wg_size > 1024 || wg_size % 64) return fail(SHM_EINVAL, "wg_size must be a multiple of 64 in 64..1024");
-    if (mode < 0 || mode > 3) return fail(SHM_EINVAL, "mode outside 0..3");
+    if (mode < 0 || mode > 4) return fail(SHM_EINVAL, "mode outside 0..4");
     if (reps < 1 || reps > (1 << 20)) return fail(SHM_EINVAL, "reps outside 1..2^20");
-    if (!dev_ticks) return fail(SHM_EINVAL, "null tick buffer");
-    if (c->no_device) return no_device("shm_launch_put_device_initiated");
+    if (consume_off != SHM_NO_CONSUME) {
+        if (!is_get) return fail(SHM_EINVAL, "only a get has a local destination to consume");
+        if (int r = check_range(c, consume_off, n, "consume buffer")) return r;
+        if (overlaps(consume_off, dst_off, n) || (me == pe && overlaps(consume_off, src_off, n)))
+            return fail(SHM_EINVAL, "the consume buffer overlaps the transfer");
+    }
+    if (c->no_device) return no_device("shm_launch_rma_device_initiated");
     if (mode != 0 && !c->proxy.running()) return fail(SHM_EINVAL, "the host proxy is not running (shm_proxy_start)");
     if (int r = drain_engines(c, me)) return r;
-    hipLaunchKernelGGL(shmk_put_device_initiated, dim3(n_wg), dim3(wg_size), 0, c->stream[me], dev_view(c), dst_off, src_off, n, me, pe,
-                       mode, cutover, reps, reinterpret_cast<unsigned long long *>(dev_ticks));
-    return launched("device-initiated put");
+    hipLaunchKernelGGL(shmk_rma_device_initiated, dim3(n_wg), dim3(wg_size), 0, c->stream[me], dev_view(c), dst_off, src_off, n, me, pe,
+                       is_get ? 1 : 0, mode, cutover, cover, consume_off, reps, reinterpret_cast<unsigned long long *>(dev_ticks));
+    return launched("device-initiated transfer");
+}
+
+int shm_launch_put_device_initiated(shm_ctx *c, int me, int pe, uint64_t dst_off, uint64_t src_off, size_t n, int n_wg, int wg_size,
+                                    int mode, size_t cutover, int reps, uint64_t *dev_ticks)
+{
+    if (mode < 0 || mode > 3) return fail(SHM_EINVAL, "mode outside 0..3");
+    if (!dev_ticks) return fail(SHM_EINVAL, "null tick buffer");
+    return shm_launch_rma_device_initiated(c, me, pe, dst_off, src_off, n, n_wg, wg_size, 0, mode, cutover, 0, SHM_NO_CONSUME, reps,
+                                           dev_ticks);
+}
+
+int shm_launch_thread_rma(shm_ctx *c, int me, int pe, uint64_t dst_off, uint64_t src_off, size_t n, int is_get, int reps,
+                          uint64_t *dev_ticks)
+{
+    if (int r = check_ctx(c)) return r;
+    if (int r = rma_args(c, me, pe, dst_off, src_off, n)) return r;
+    if (reps < 1 || reps > (1 << 20)) return fail(SHM_EINVAL, "reps outside 1..2^20");
+    if (c->no_device) return no_device("shm_launch_thread_rma");
+    if (int r = drain_engines(c, me)) return r;
+    hipLaunchKernelGGL(shmk_thread_rma, dim3(1), dim3(64), 0, c->stream[me], dev_view(c), dst_off, src_off, n, me, pe, is_get ? 1 : 0,
+                       reps, reinterpret_cast<unsigned long long *>(dev_ticks));
+    return launched("single-thread transfer");
+}
+
+namespace {
+int launch_strided(shm_ctx *c, int me, int pe, uint64_t dst_off, uint64_t src_off, int64_t dst_stride, int64_t src_stride, size_t nelems,
+                   int elem_bytes, int n_wg, int is_get)
+{
+    if (int r = check_ctx(c)) return r;
+    if (int r = check_pe(c, me, "calling PE")) return r;
+    if (int r = check_pe(c, pe, "target PE")) return r;
+    if (elem_bytes != 1 && elem_bytes != 2 && elem_bytes != 4 && elem_bytes != 8 && elem_bytes != 16)
+        return fail(SHM_EINVAL, "element size %d is not 1, 2, 4, 8 or 16", elem_bytes);
+    if (dst_stride < 1 || src_stride < 1) return fail(SHM_EINVAL, "strides are counted in elements and are at least 1");
+    if ((dst_off | src_off) % static_cast<uint64_t>(elem_bytes)) return fail(SHM_EINVAL, "strided transfers need element-aligned offsets");
+    if (n_wg < 0 || n_wg > 65535) return fail(SHM_EINVAL, "n_wg outside 0..65535");
+    const uint64_t e = static_cast<uint64_t>(elem_bytes), limit = c->user_bytes / e + 1;
+    uint64_t dspan = 0, sspan = 0;
+    if (nelems) {
+        // (nelems - 1) * stride + 1 elements, computed without overflow
+        if (nelems - 1 > limit || static_cast<uint64_t>(dst_stride) > limit || static_cast<uint64_t>(src_stride) > limit ||
+            (nelems - 1) * static_cast<unsigned __int128>(dst_stride) > limit || (nelems - 1) * static_cast<unsigned __int128>(src_stride) > limit)
+            return fail(SHM_ERANGE, "the strided transfer leaves the heap");
+        dspan = ((nelems - 1) * static_cast<uint64_t>(dst_stride) + 1) * e;
+        sspan = ((nelems - 1) * static_cast<uint64_t>(src_stride) + 1) * e;
+    }
+    if (int r = check_range(c, dst_off, dspan, "destination")) return r;
+    if (int r = check_range(c, src_off, sspan, "source")) return r;
+    if (me == pe && nelems && src_off < dst_off + dspan && dst_off < src_off + sspan)
+        return fail(SHM_EINVAL, "source and destination overlap on PE %d", me);
+    if (c->no_device) return no_device("strided transfer");
+    if (int r = drain_engines(c, me)) return r;
+    if (nelems == 0) return SHM_OK;
+    hipLaunchKernelGGL(shmk_strided, dim3(n_wg ? n_wg : 1), dim3(n_wg ? SHMK_WG : 64), 0, c->stream[me], dev_view(c), dst_off, src_off,
+                       static_cast<size_t>(dst_stride), static_cast<size_t>(src_stride), nelems, static_cast<uint32_t>(elem_bytes), me, pe,
+                       is_get, n_wg ? 0 : 1);
+    return launched("strided transfer");
+}
+}  // namespace
+
+int shm_launch_iput(shm_ctx *c, int me, int pe, uint64_t dst_off, uint64_t src_off, int64_t dst_stride, int64_t src_stride, size_t nelems,
+                    int elem_bytes, int n_wg)
+{
+    return launch_strided(c, me, pe, dst_off, src_off, dst_stride, src_stride, nelems, elem_bytes, n_wg, 0);
+}
+
+int shm_launch_iget(shm_ctx *c, int me, int pe, uint64_t dst_off, uint64_t src_off, int64_t dst_stride, int64_t src_stride, size_t nelems,
+                    int elem_bytes, int n_wg)
+{
+    return launch_strided(c, me, pe, dst_off, src_off, dst_stride, src_stride, nelems, elem_bytes, n_wg, 1);
 }
 
 int shm_launch_offload_nop(shm_ctx *c, int me, int n_wg, int reps, int blocking, uint64_t *dev_ticks)

@@ -335,13 +335,18 @@ __device__ __forceinline__ void shm_copy_tiles(char *dst, const char *src, size_
 // RMA.  A put returns when the source may be reused; its bytes are delivered (visible to other
 // PEs) after the caller's quiet.  A get returns with the bytes in place for the calling thread(s).
 // ------------------------------------------------------------------------------------------
+// Single-thread forms.  One lane's bandwidth is (bytes in flight) / (memory latency), so U, the
+// number of 16-byte loads issued before the first store, is what a caller with registers to spare
+// can raise (at most 63 loads can be outstanding per wave).
+template <int U = 4>
 __device__ __forceinline__ void shm_putmem(const shm_dev_ctx &c, int me, uint64_t dst_off, uint64_t src_off, size_t n, int pe)
 {
-    shm_copy_coop<4>(shm_ptr(c, dst_off, pe), shm_ptr(c, src_off, me), n, 0, 1);
+    shm_copy_coop<U>(shm_ptr(c, dst_off, pe), shm_ptr(c, src_off, me), n, 0, 1);
 }
+template <int U = 4>
 __device__ __forceinline__ void shm_getmem(const shm_dev_ctx &c, int me, uint64_t dst_off, uint64_t src_off, size_t n, int pe)
 {
-    shm_copy_coop<4>(shm_ptr(c, dst_off, me), shm_ptr(c, src_off, pe), n, 0, 1);
+    shm_copy_coop<U>(shm_ptr(c, dst_off, me), shm_ptr(c, src_off, pe), n, 0, 1);
 }
 
 // Sub-group (wave64) forms: the 64 lanes of the calling wave share the copy.
@@ -668,17 +673,34 @@ __device__ __forceinline__ void shm_offload_wait(const shm_dev_ctx &c, uint64_t 
 // that the source is complete, one wave talks to the host, group barrier).  Blocking: returns when
 // the bytes are delivered.  The non-blocking form returns at once; shmx_quiet_offload_wg completes
 // everything this PE has offloaded.
-__device__ __forceinline__ void shmx_putmem_offload_wg(const shm_dev_ctx &c, int me, uint64_t dst_off, uint64_t src_off, size_t n,
-                                                       int pe, bool blocking)
+__device__ __forceinline__ void shmx_copy_offload_wg(const shm_dev_ctx &c, int me, char *dst, const char *src, size_t n, bool blocking)
 {
     __syncthreads();
     if (threadIdx.x < 64 && n != 0) {
         if (threadIdx.x == 0) __builtin_amdgcn_fence(__ATOMIC_RELEASE, "");      // the engine reads memory, not our caches
-        const uint64_t ticket = shm_offload_send(c, SHMD_OFFLOAD_COPY, me, reinterpret_cast<uint64_t>(shm_ptr(c, dst_off, pe)),
-                                                 reinterpret_cast<uint64_t>(shm_ptr(c, src_off, me)), n, blocking);
-        if (blocking) shm_offload_wait(c, ticket);
+        const uint64_t ticket = shm_offload_send(c, SHMD_OFFLOAD_COPY, me, reinterpret_cast<uint64_t>(dst),
+                                                 reinterpret_cast<uint64_t>(src), n, blocking);
+        if (blocking) {
+            shm_offload_wait(c, ticket);
+            if (threadIdx.x == 0) __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "");  // the engine wrote memory, not our caches
+        }
     }
     __syncthreads();
+}
+
+__device__ __forceinline__ void shmx_putmem_offload_wg(const shm_dev_ctx &c, int me, uint64_t dst_off, uint64_t src_off, size_t n,
+                                                       int pe, bool blocking)
+{
+    shmx_copy_offload_wg(c, me, shm_ptr(c, dst_off, pe), shm_ptr(c, src_off, me), n, blocking);
+}
+
+// The get through the engine: same request with the roles of the two PEs exchanged.  The blocking
+// form returns with the bytes readable by every thread of the group; the non-blocking form
+// (get_nbi_work_group) leaves them undefined until shmx_quiet_offload_wg.
+__device__ __forceinline__ void shmx_getmem_offload_wg(const shm_dev_ctx &c, int me, uint64_t dst_off, uint64_t src_off, size_t n,
+                                                       int pe, bool blocking)
+{
+    shmx_copy_offload_wg(c, me, shm_ptr(c, dst_off, me), shm_ptr(c, src_off, pe), n, blocking);
 }
 
 __device__ __forceinline__ void shmx_quiet_offload_wg(const shm_dev_ctx &c, int me)
@@ -701,6 +723,113 @@ __device__ __forceinline__ void shmx_putmem_auto_wg(const shm_dev_ctx &c, int me
         shmx_putmem_offload_wg(c, me, dst_off, src_off, n, pe, true);
     else
         shmx_putmem_wg(c, me, dst_off, src_off, n, pe);
+}
+__device__ __forceinline__ void shmx_getmem_auto_wg(const shm_dev_ctx &c, int me, uint64_t dst_off, uint64_t src_off, size_t n, int pe,
+                                                    size_t cutover)
+{
+    if (c.off.ring != nullptr && n >= cutover)
+        shmx_getmem_offload_wg(c, me, dst_off, src_off, n, pe, true);
+    else
+        shmx_getmem_wg(c, me, dst_off, src_off, n, pe);
+}
+
+// The refinement the paper's implementation notes sketch for the cutover: the engine needs several
+// microseconds to start, so the group asks for the engine to move everything past the first
+// `cover` bytes, moves those first bytes itself with loads and stores while the engine starts, and
+// then waits for both.  is_get exchanges the roles of the PEs.
+__device__ __forceinline__ void shmx_rma_covered_wg(const shm_dev_ctx &c, int me, uint64_t dst_off, uint64_t src_off, size_t n, int pe,
+                                                    size_t cover, bool is_get)
+{
+    const size_t head = min(n, (cover + 255) & ~static_cast<size_t>(255));
+    const int dpe = is_get ? me : pe, spe = is_get ? pe : me;
+    if (c.off.ring != nullptr && n > head)
+        shmx_copy_offload_wg(c, me, shm_ptr(c, dst_off + head, dpe), shm_ptr(c, src_off + head, spe), n - head, false);
+    else if (n > head)
+        return;        // no proxy: the host refuses this mode, nothing is half-done here
+    __syncthreads();
+    shm_copy_parts<8>(shm_ptr(c, dst_off, dpe), shm_ptr(c, src_off, spe), head, 0, 1);
+    __syncthreads();
+}
+
+// ------------------------------------------------------------------------------------------
+// Strided put/get (paper section "Implementation": blocked and strided RMA use vector copies;
+// semantics of OpenSHMEM's iput/iget).  Element i of the source, taken every src_stride elements,
+// lands at element i * dst_stride of the destination; elements are 1, 2, 4, 8 or 16 bytes and are
+// moved with one load and one store of that width, four elements in flight per thread.  Unit
+// strides on both sides are a contiguous block and take the vector copy.
+// ------------------------------------------------------------------------------------------
+template <typename T>
+__device__ __forceinline__ void shm_copy_strided_typed(char *dst, const char *src, size_t dst_stride, size_t src_stride, size_t nelems,
+                                                       size_t tid, size_t nthr)
+{
+    T *d = reinterpret_cast<T *>(dst);
+    const T *s = reinterpret_cast<const T *>(src);
+    constexpr int U = 4;
+    size_t i = tid;
+    for (; i + (U - 1) * nthr < nelems; i += U * nthr) {
+        T r[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) r[u] = s[(i + u * nthr) * src_stride];
+#pragma unroll
+        for (int u = 0; u < U; ++u) d[(i + u * nthr) * dst_stride] = r[u];
+    }
+    for (; i < nelems; i += nthr) d[i * dst_stride] = s[i * src_stride];
+}
+
+// Elements [first, first + count) of a strided transfer by threads tid of nthr.
+__device__ __forceinline__ void shm_copy_strided(char *dst, const char *src, size_t dst_stride, size_t src_stride, size_t first,
+                                                 size_t count, uint32_t elem_bytes, size_t tid, size_t nthr)
+{
+    dst += first * dst_stride * elem_bytes;
+    src += first * src_stride * elem_bytes;
+    if (dst_stride == 1 && src_stride == 1) {
+        shm_copy_coop<4>(dst, src, count * elem_bytes, static_cast<unsigned>(tid), static_cast<unsigned>(nthr));
+        return;
+    }
+    switch (elem_bytes) {
+    case 1: shm_copy_strided_typed<uint8_t>(dst, src, dst_stride, src_stride, count, tid, nthr); break;
+    case 2: shm_copy_strided_typed<uint16_t>(dst, src, dst_stride, src_stride, count, tid, nthr); break;
+    case 4: shm_copy_strided_typed<uint32_t>(dst, src, dst_stride, src_stride, count, tid, nthr); break;
+    case 8: shm_copy_strided_typed<uint64_t>(dst, src, dst_stride, src_stride, count, tid, nthr); break;
+    default: shm_copy_strided_typed<shm_u32x4>(dst, src, dst_stride, src_stride, count, tid, nthr); break;
+    }
+}
+
+// Single-thread forms.
+__device__ __forceinline__ void shm_iput(const shm_dev_ctx &c, int me, uint64_t dst_off, uint64_t src_off, size_t dst_stride,
+                                         size_t src_stride, size_t nelems, uint32_t elem_bytes, int pe)
+{
+    shm_copy_strided(shm_ptr(c, dst_off, pe), shm_ptr(c, src_off, me), dst_stride, src_stride, 0, nelems, elem_bytes, 0, 1);
+}
+__device__ __forceinline__ void shm_iget(const shm_dev_ctx &c, int me, uint64_t dst_off, uint64_t src_off, size_t dst_stride,
+                                         size_t src_stride, size_t nelems, uint32_t elem_bytes, int pe)
+{
+    shm_copy_strided(shm_ptr(c, dst_off, me), shm_ptr(c, src_off, pe), dst_stride, src_stride, 0, nelems, elem_bytes, 0, 1);
+}
+
+// Work-group forms for `nparts` groups sharing one transfer (this group is `part`): consecutive
+// threads take consecutive elements, groups take consecutive blocks of elements.
+__device__ __forceinline__ void shmx_iput_parts(const shm_dev_ctx &c, int me, uint64_t dst_off, uint64_t src_off, size_t dst_stride,
+                                                size_t src_stride, size_t nelems, uint32_t elem_bytes, int pe, unsigned part,
+                                                unsigned nparts)
+{
+    const size_t per = (nelems + nparts - 1) / nparts;
+    const size_t lo = min(nelems, static_cast<size_t>(part) * per), cnt = min(nelems, lo + per) - lo;
+    __syncthreads();
+    shm_copy_strided(shm_ptr(c, dst_off, pe), shm_ptr(c, src_off, me), dst_stride, src_stride, lo, cnt, elem_bytes, threadIdx.x,
+                     blockDim.x);
+    __syncthreads();
+}
+__device__ __forceinline__ void shmx_iget_parts(const shm_dev_ctx &c, int me, uint64_t dst_off, uint64_t src_off, size_t dst_stride,
+                                                size_t src_stride, size_t nelems, uint32_t elem_bytes, int pe, unsigned part,
+                                                unsigned nparts)
+{
+    const size_t per = (nelems + nparts - 1) / nparts;
+    const size_t lo = min(nelems, static_cast<size_t>(part) * per), cnt = min(nelems, lo + per) - lo;
+    __syncthreads();
+    shm_copy_strided(shm_ptr(c, dst_off, me), shm_ptr(c, src_off, pe), dst_stride, src_stride, lo, cnt, elem_bytes, threadIdx.x,
+                     blockDim.x);
+    __syncthreads();
 }
 
 // ------------------------------------------------------------------------------------------

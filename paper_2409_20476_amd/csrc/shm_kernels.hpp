@@ -56,36 +56,109 @@ __global__ __launch_bounds__(SHMK_WG) void shmk_wg_put_timed(shm_dev_ctx c, uint
     }
 }
 
-// Device-initiated put, `reps` times, by gridDim.x groups (of 64..1024 threads: the paper varies the
-// work-items per work-group) that each own a contiguous 256-byte-aligned share of the message.  mode 0: loads/stores + group quiet; 1: host-started copy engine,
-// blocking; 2: cutover on the share size; 3: non-blocking engine put, offload quiet after each.
-__global__ __launch_bounds__(1024) void shmk_put_device_initiated(shm_dev_ctx c, uint64_t dst_off, uint64_t src_off, size_t n, int me,
-                                                                     int pe, int mode, size_t cutover, int reps, unsigned long long *ticks)
+// Device-initiated put or get, `reps` times, by gridDim.x groups (of 64..1024 threads: the paper
+// varies the work-items per work-group) that each own a contiguous 256-byte-aligned share of the
+// message.  mode 0: loads/stores (put: + group quiet); 1: host-started copy engine, blocking;
+// 2: cutover on the share size; 3: non-blocking engine transfer (put_nbi / get_nbi), offload quiet
+// after each; 4: engine for all but the first `cover` bytes of the share, loads/stores for those,
+// then both quiets.  consume_off (get only, else UINT64_MAX): before the first get the group copies
+// its share of the destination to consume_off -- which pulls the old bytes into the caches -- and
+// after every get it copies the share again, so the copy shows what a thread of the group reads.
+constexpr uint64_t SHMK_NO_CONSUME = ~0ull;
+
+__global__ __launch_bounds__(1024) void shmk_rma_device_initiated(shm_dev_ctx c, uint64_t dst_off, uint64_t src_off, size_t n, int me,
+                                                                     int pe, int is_get, int mode, size_t cutover, size_t cover,
+                                                                     uint64_t consume_off, int reps, unsigned long long *ticks)
 {
     size_t per = (n + gridDim.x - 1) / gridDim.x;
     per = (per + 255) & ~static_cast<size_t>(255);
     const size_t lo = min(n, blockIdx.x * per), len = min(n, lo + per) - lo;
+    const uint64_t d = dst_off + lo, s = src_off + lo;
+    const bool consume = is_get && consume_off != SHMK_NO_CONSUME;
+    if (consume) shmx_putmem_wg(c, me, consume_off + lo, d, len, me);
     const unsigned long long t0 = wall_clock64();
     for (int r = 0; r < reps; ++r) {
         if (mode == 0) {
-            shmx_putmem_wg(c, me, dst_off + lo, src_off + lo, len, pe);
-            if (len) shmx_quiet_wg();
+            if (is_get) {
+                shmx_getmem_wg(c, me, d, s, len, pe);
+            } else {
+                shmx_putmem_wg(c, me, d, s, len, pe);
+                if (len) shmx_quiet_wg();
+            }
         } else if (mode == 1) {
-            shmx_putmem_offload_wg(c, me, dst_off + lo, src_off + lo, len, pe, true);
+            if (is_get)
+                shmx_getmem_offload_wg(c, me, d, s, len, pe, true);
+            else
+                shmx_putmem_offload_wg(c, me, d, s, len, pe, true);
         } else if (mode == 2) {
             const bool engine = c.off.ring != nullptr && len >= cutover;
-            shmx_putmem_auto_wg(c, me, dst_off + lo, src_off + lo, len, pe, cutover);
-            if (!engine && len) shmx_quiet_wg();
+            if (is_get) {
+                shmx_getmem_auto_wg(c, me, d, s, len, pe, cutover);
+            } else {
+                shmx_putmem_auto_wg(c, me, d, s, len, pe, cutover);
+                if (!engine && len) shmx_quiet_wg();
+            }
+        } else if (mode == 3) {
+            if (is_get)
+                shmx_getmem_offload_wg(c, me, d, s, len, pe, false);
+            else
+                shmx_putmem_offload_wg(c, me, d, s, len, pe, false);
+            shmx_quiet_offload_wg(c, me);
         } else {
-            shmx_putmem_offload_wg(c, me, dst_off + lo, src_off + lo, len, pe, false);
+            shmx_rma_covered_wg(c, me, d, s, len, pe, cover, is_get != 0);
+            if (!is_get && len) shmx_quiet_wg();
             shmx_quiet_offload_wg(c, me);
         }
+        if (consume) shmx_putmem_wg(c, me, consume_off + lo, d, len, me);
     }
     const unsigned long long t1 = wall_clock64();
-    if (threadIdx.x == 0) {
+    if (ticks != nullptr && threadIdx.x == 0) {
         atomicMin(&ticks[0], t0);
         atomicMax(&ticks[1], t1);
     }
+}
+
+// One work-item of the whole device calls the single-thread put or get `reps` times (the paper's
+// first experiment: bandwidth of ishmem_put / ishmem_get issued by one thread), quiet after each put.
+__global__ __launch_bounds__(64) void shmk_thread_rma(shm_dev_ctx c, uint64_t dst_off, uint64_t src_off, size_t n, int me, int pe,
+                                                      int is_get, int reps, unsigned long long *ticks)
+{
+    if (threadIdx.x != 0 || blockIdx.x != 0) return;
+    const unsigned long long t0 = wall_clock64();
+    for (int r = 0; r < reps; ++r) {
+        if (is_get) {
+            shm_getmem<32>(c, me, dst_off, src_off, n, pe);
+            __builtin_amdgcn_s_waitcnt(0);          // a get returns with the bytes in place
+        } else {
+            shm_putmem<32>(c, me, dst_off, src_off, n, pe);
+            shm_quiet();
+        }
+    }
+    const unsigned long long t1 = wall_clock64();
+    if (ticks != nullptr) {
+        atomicMin(&ticks[0], t0);
+        atomicMax(&ticks[1], t1);
+    }
+}
+
+// Strided put/get.  single != 0: one work-item does the whole transfer (ishmem_iput / ishmem_iget);
+// otherwise the gridDim.x groups share the elements (the work-group forms).
+__global__ __launch_bounds__(SHMK_WG) void shmk_strided(shm_dev_ctx c, uint64_t dst_off, uint64_t src_off, size_t dst_stride,
+                                                        size_t src_stride, size_t nelems, uint32_t elem_bytes, int me, int pe,
+                                                        int is_get, int single)
+{
+    if (single) {
+        if (threadIdx.x != 0 || blockIdx.x != 0) return;
+        if (is_get)
+            shm_iget(c, me, dst_off, src_off, dst_stride, src_stride, nelems, elem_bytes, pe);
+        else
+            shm_iput(c, me, dst_off, src_off, dst_stride, src_stride, nelems, elem_bytes, pe);
+        return;
+    }
+    if (is_get)
+        shmx_iget_parts(c, me, dst_off, src_off, dst_stride, src_stride, nelems, elem_bytes, pe, blockIdx.x, gridDim.x);
+    else
+        shmx_iput_parts(c, me, dst_off, src_off, dst_stride, src_stride, nelems, elem_bytes, pe, blockIdx.x, gridDim.x);
 }
 
 // Ring micro-benchmark: wave 0 of every group sends `reps` empty requests.  blocking: waits for

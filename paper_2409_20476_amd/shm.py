@@ -27,6 +27,7 @@ SHM_INIT_DEFAULT, SHM_INIT_NO_DEVICE = 0, 1
  SHM_AMO_INC) = range(8)
 SHM_STORM_FETCH_ADD, SHM_STORM_ADD, SHM_STORM_CSWAP_LOOP, SHM_STORM_PLAIN_STORE = range(4)
 SHM_REDUCE_DUPLICATE, SHM_REDUCE_SPLIT = 0, 1
+SHM_NO_CONSUME = (1 << 64) - 1
 SHM_OP_MIN, SHM_OP_MAX, SHM_OP_SUM, SHM_OP_PROD, SHM_OP_AND, SHM_OP_OR, SHM_OP_XOR = range(7)
 (SHM_INT8, SHM_UINT8, SHM_INT16, SHM_UINT16, SHM_INT32, SHM_UINT32, SHM_INT64, SHM_UINT64, SHM_FLOAT32,
  SHM_FLOAT64) = range(10)
@@ -69,6 +70,11 @@ PROTOTYPES = {
     "shm_proxy_stop": (c_int, [c_void_p]),
     "shm_proxy_stats": (c_int, [c_void_p, _u64p, _u64p]),
     "shm_launch_put_device_initiated": (c_int, [c_void_p, c_int, c_int, c_uint64, c_uint64, c_size_t, c_int, c_int, c_int, c_size_t, c_int, c_void_p]),
+    "shm_launch_rma_device_initiated": (c_int, [c_void_p, c_int, c_int, c_uint64, c_uint64, c_size_t, c_int, c_int, c_int, c_int, c_size_t,
+                                                c_size_t, c_uint64, c_int, c_void_p]),
+    "shm_launch_thread_rma": (c_int, [c_void_p, c_int, c_int, c_uint64, c_uint64, c_size_t, c_int, c_int, c_void_p]),
+    "shm_launch_iput": (c_int, [c_void_p, c_int, c_int, c_uint64, c_uint64, c_int64, c_int64, c_size_t, c_int, c_int]),
+    "shm_launch_iget": (c_int, [c_void_p, c_int, c_int, c_uint64, c_uint64, c_int64, c_int64, c_size_t, c_int, c_int]),
     "shm_launch_offload_nop": (c_int, [c_void_p, c_int, c_int, c_int, c_int, c_void_p]),
     "shm_launch_wg_put_signal": (c_int, [c_void_p, c_int, c_int, c_uint64, c_uint64, c_size_t, c_uint64, c_uint64, c_int, c_int]),
     "shm_launch_signal_wait_until": (c_int, [c_void_p, c_int, c_uint64, c_int, c_uint64, c_void_p]),
@@ -261,6 +267,20 @@ class Shm:
     def launch_put_device_initiated(self, me, pe, dst_off, src_off, n, n_wg, mode, cutover, reps, dev_ticks, wg_size=256):
         self._check(self.lib.shm_launch_put_device_initiated(self.ctx, me, pe, dst_off, src_off, n, n_wg, wg_size, mode, cutover,
                                                              reps, _ptr(dev_ticks)))
+
+    def launch_rma_device_initiated(self, me, pe, dst_off, src_off, n, n_wg, is_get, mode, cutover=0, cover=0,
+                                    consume_off=SHM_NO_CONSUME, reps=1, dev_ticks=None, wg_size=256):
+        self._check(self.lib.shm_launch_rma_device_initiated(self.ctx, me, pe, dst_off, src_off, n, n_wg, wg_size, int(is_get), mode,
+                                                             cutover, cover, consume_off, reps, _ptr(dev_ticks)))
+
+    def launch_thread_rma(self, me, pe, dst_off, src_off, n, is_get=False, reps=1, dev_ticks=None):
+        self._check(self.lib.shm_launch_thread_rma(self.ctx, me, pe, dst_off, src_off, n, int(is_get), reps, _ptr(dev_ticks)))
+
+    def launch_iput(self, me, pe, dst_off, src_off, dst_stride, src_stride, nelems, elem_bytes, n_wg=0):
+        self._check(self.lib.shm_launch_iput(self.ctx, me, pe, dst_off, src_off, dst_stride, src_stride, nelems, elem_bytes, n_wg))
+
+    def launch_iget(self, me, pe, dst_off, src_off, dst_stride, src_stride, nelems, elem_bytes, n_wg=0):
+        self._check(self.lib.shm_launch_iget(self.ctx, me, pe, dst_off, src_off, dst_stride, src_stride, nelems, elem_bytes, n_wg))
 
     def launch_offload_nop(self, me, n_wg, reps, blocking, dev_ticks):
         self._check(self.lib.shm_launch_offload_nop(self.ctx, me, n_wg, reps, int(blocking), _ptr(dev_ticks)))

@@ -150,6 +150,23 @@ def test_every_entry_point_validates_before_touching_the_device():
     assert code(lambda: g.launch_reduce_sum_f32(65538, 0, 1000, 2)) == S.SHM_EINVAL
     assert code(lambda: g.launch_reduce_sum_f32(0, 0, 1000, 2, 5)) == S.SHM_EINVAL
     assert code(lambda: g.launch_fcollect(100, 0, 1000, 2)) == S.SHM_EINVAL                                     # overlap
+    # strided, single-thread and general device-initiated transfers
+    assert code(lambda: g.launch_iput(0, 1, 4096, 0, 2, 3, 100, 4, 0)) == S.SHM_ENODEV
+    assert code(lambda: g.launch_iget(0, 1, 4096, 0, 2, 3, 100, 16, 8)) == S.SHM_ENODEV
+    assert code(lambda: g.launch_iput(0, 1, 4096, 0, 0, 3, 100, 4, 0)) == S.SHM_EINVAL                        # stride < 1
+    assert code(lambda: g.launch_iput(0, 1, 4096, 0, 2, 3, 100, 5, 0)) == S.SHM_EINVAL                        # element size
+    assert code(lambda: g.launch_iput(0, 1, 4098, 0, 2, 3, 100, 4, 0)) == S.SHM_EINVAL                        # alignment
+    assert code(lambda: g.launch_iput(0, 0, 0, 16, 8, 1, 100, 4, 0)) == S.SHM_EINVAL                          # spans overlap on one PE
+    assert code(lambda: g.launch_iput(0, 1, 0, 0, H // 400 + 1, 1, 101, 4, 0)) == S.SHM_ERANGE
+    assert code(lambda: g.launch_iget(0, 1, 0, 0, 1, (1 << 62), 3, 8, 0)) == S.SHM_ERANGE
+    assert code(lambda: g.launch_iget(0, 1, 0, 0, 1, 1, (1 << 63), 16, 0)) == S.SHM_ERANGE
+    assert code(lambda: g.launch_thread_rma(0, 1, 4096, 0, 100)) == S.SHM_ENODEV
+    assert code(lambda: g.launch_thread_rma(0, 0, 50, 0, 100)) == S.SHM_EINVAL
+    assert code(lambda: g.launch_rma_device_initiated(0, 1, 4096, 0, 100, 2, True, 0)) == S.SHM_ENODEV
+    assert code(lambda: g.launch_rma_device_initiated(0, 1, 4096, 0, 100, 2, True, 5)) == S.SHM_EINVAL
+    assert code(lambda: g.launch_rma_device_initiated(0, 1, 4096, 0, 100, 2, False, 0, consume_off=8192)) == S.SHM_EINVAL
+    assert code(lambda: g.launch_rma_device_initiated(0, 1, 4096, 0, 100, 2, True, 0, consume_off=4100)) == S.SHM_EINVAL
+    assert code(lambda: g.launch_rma_device_initiated(0, 1, 4096, 0, 100, 2, True, 0, consume_off=H - 10)) == S.SHM_ERANGE
     # the reduction matrix
     assert code(lambda: g.launch_reduce(65536, 0, 1000, S.SHM_INT16, S.SHM_OP_XOR, 2)) == S.SHM_ENODEV
     assert code(lambda: g.launch_reduce(65536, 0, 1000, S.SHM_FLOAT64, S.SHM_OP_PROD, 2)) == S.SHM_ENODEV

@@ -1,0 +1,122 @@
+"""GPU parity: single-thread put/get, strided put/get, and device-initiated gets (blocking,
+non-blocking, engine start-up covered by loads/stores) with the landed bytes read inside the kernel."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2409_20476_amd import shm as S
+from parity_util import assert_heaps_equal, fill_random, make_pair
+
+pytestmark = pytest.mark.gpu
+
+MiB = 1 << 20
+
+
+@pytest.mark.parametrize("is_get", [False, True])
+@pytest.mark.parametrize("n,sa,da", [(0, 0, 0), (1, 3, 5), (15, 1, 0), (4096, 0, 0), (100003, 7, 9), (65536 + 48, 16, 32), (513, 0, 8)])
+def test_single_thread_put_get(is_get, n, sa, da):
+    g, o = make_pair(3, 4 * MiB)
+    with g:
+        fill_random(g, o, 61, upto=3 * MiB)
+        src, dst = 4096 + sa, 2 * MiB + da
+        g.launch_thread_rma(1, 2, dst, src, n, is_get, reps=2)
+        g.quiet(1)
+        (o.getmem if is_get else o.putmem)(1, dst, src, n, 2)
+        assert_heaps_equal(g, o, upto=3 * MiB)
+        # same PE, disjoint ranges
+        g.launch_thread_rma(0, 0, dst, src, n, is_get)
+        g.quiet(0)
+        (o.getmem if is_get else o.putmem)(0, dst, src, n, 0)
+        assert_heaps_equal(g, o, upto=3 * MiB)
+
+
+@pytest.mark.parametrize("elem", [1, 2, 4, 8, 16])
+@pytest.mark.parametrize("n_wg", [0, 1, 7, 64])
+def test_strided_put_get(elem, n_wg):
+    g, o = make_pair(3, 8 * MiB)
+    with g:
+        fill_random(g, o, 62 + elem, upto=6 * MiB)
+        cases = [(3, 2, 10007), (1, 5, 4099), (7, 1, 2500), (1, 1, 30011), (2, 2, 1), (4, 4, 0), (13, 11, 777)]
+        if n_wg == 0:
+            cases = [(d, s, min(n, 1200)) for d, s, n in cases]           # one work-item: keep it short
+        for i, (ds, ss, n) in enumerate(cases):
+            me, pe = i % 3, (i + 2) % 3
+            src, dst = 16 * elem, 3 * MiB + elem
+            g.launch_iput(me, pe, dst, src, ds, ss, n, elem, n_wg)
+            g.quiet(me)
+            o.iput(me, dst, src, ds, ss, n, elem, pe)
+            assert_heaps_equal(g, o, upto=6 * MiB, what=f"iput case {i}")
+            g.launch_iget(me, pe, dst + 1 * MiB, src + elem, ds, ss, n, elem, n_wg)
+            g.quiet(me)
+            o.iget(me, dst + 1 * MiB, src + elem, ds, ss, n, elem, pe)
+            assert_heaps_equal(g, o, upto=6 * MiB, what=f"iget case {i}")
+
+
+def test_strided_same_pe_and_errors():
+    g, o = make_pair(2, 2 * MiB)
+    with g:
+        fill_random(g, o, 63, upto=MiB + 4096)
+        g.launch_iput(0, 0, MiB // 2, 0, 2, 3, 5000, 4, 4)        # scatter within one PE, disjoint spans
+        g.quiet(0)
+        o.iput(0, MiB // 2, 0, 2, 3, 5000, 4, 0)
+        assert_heaps_equal(g, o, upto=MiB + 4096)
+        for bad in (lambda: g.launch_iput(0, 1, 0, 0, 0, 1, 10, 4), lambda: g.launch_iput(0, 1, 0, 0, 1, 1, 10, 3),
+                    lambda: g.launch_iput(0, 1, 2, 0, 1, 1, 10, 4), lambda: g.launch_iget(0, 1, 0, 0, 1 << 40, 1, 10, 4),
+                    lambda: g.launch_iput(0, 0, 0, 64, 8, 1, 100, 4)):
+            with pytest.raises(S.ShmError):
+                bad()
+
+
+@pytest.mark.parametrize("mode", [0, 1, 2, 3, 4])
+def test_device_initiated_get_is_readable_inside_the_kernel(mode):
+    """The kernel copies the destination to a consume buffer BEFORE the get (old bytes enter the
+    caches) and after it; the second copy must show the new bytes although a copy engine, not a
+    compute unit, may have written them."""
+    g, o = make_pair(3, 24 * MiB)
+    with g:
+        fill_random(g, o, 64, upto=20 * MiB)
+        g.proxy_start()
+        cases = [(100003, 1, 17, 5), (MiB + 256, 4, 0, 0), (4096, 1, 3, 3), (3 * MiB + 1000, 16, 256, 512), (0, 2, 0, 0), (700, 8, 1, 2),
+                 (2 * MiB, 2, 0, 0)]
+        for i, (n, n_wg, sa, da) in enumerate(cases):
+            me, pe = i % 3, (i + 1) % 3
+            src, dst, cons = 1024 + sa, 6 * MiB + da, 12 * MiB + da
+            g.launch_rma_device_initiated(me, pe, dst, src, n, n_wg, True, mode, cutover=65536, cover=128 * 1024, consume_off=cons,
+                                          reps=1, wg_size=(64, 256, 1024)[i % 3])
+            g.quiet(me)
+            o.getmem(me, dst, src, n, pe)
+            o.putmem(me, cons, dst, n, me)
+            assert_heaps_equal(g, o, upto=20 * MiB, what=f"mode {mode} case {i}")
+            # change the remote source and get again: the destination lines are now cached with the first result
+            fresh = np.random.default_rng(1000 + i).integers(0, 256, max(n, 1), dtype=np.uint8)[:n]
+            if n:
+                g.write(pe, src, fresh), o.write(pe, src, fresh)
+            g.launch_rma_device_initiated(me, pe, dst, src, n, n_wg, True, mode, cutover=65536, cover=128 * 1024, consume_off=cons,
+                                          reps=2)
+            g.quiet(me)
+            o.getmem(me, dst, src, n, pe)
+            o.putmem(me, cons, dst, n, me)
+            assert_heaps_equal(g, o, upto=20 * MiB, what=f"mode {mode} case {i} again")
+        g.proxy_stop()
+
+
+def test_covered_put_matches_oracle_and_uses_the_engine():
+    g, o = make_pair(2, 24 * MiB)
+    with g:
+        fill_random(g, o, 65, upto=20 * MiB)
+        g.proxy_start()
+        for i, (n, n_wg, cover) in enumerate([(4 * MiB + 100, 1, 256 * 1024), (4 * MiB, 4, 1000), (3000, 2, 65536), (MiB, 1, 0),
+                                              (MiB, 8, MiB)]):
+            before = g.proxy_stats()[1]
+            g.launch_rma_device_initiated(0, 1, 8 * MiB + 16, 4096, n, n_wg, False, 4, cover=cover, reps=1)
+            g.quiet(0)
+            o.wg_put(0, 8 * MiB + 16, 4096, n, 1, n_wg)
+            assert_heaps_equal(g, o, upto=20 * MiB, what=f"case {i}")
+            copies = g.proxy_stats()[1] - before
+            share = -(-n // n_wg)
+            assert (copies > 0) == (share > ((cover + 255) & ~255)), (i, copies)
+        g.proxy_stop()
+        with pytest.raises(S.ShmError):                             # mode 4 without the proxy
+            g.launch_rma_device_initiated(0, 1, 8 * MiB, 4096, MiB, 1, False, 4, cover=4096)
+        with pytest.raises(S.ShmError):                             # consume needs a get
+            g.launch_rma_device_initiated(0, 1, 8 * MiB, 4096, MiB, 1, False, 0, consume_off=12 * MiB)
