@@ -291,6 +291,77 @@ def reverse_offload(torch, S, args):
     return out
 
 
+def single_thread_and_strided(torch, S, args):
+    """The paper's first experiment (put/get called by ONE work-item, bandwidth against size; here to
+    the caller's own partition and to another PE's), the strided forms, the get through the ring, and
+    the transfer whose first bytes go by loads/stores while the copy engine starts."""
+    g = S.Shm.on_torch(2, 512 * MiB)
+    g.proxy_start()
+    khz = g.wall_clock_khz()
+    t = torch.zeros(2, dtype=torch.int64, device="cuda")
+
+    def timed(launch):
+        t[0], t[1] = -1, 0
+        torch.cuda.synchronize()
+        launch()
+        g.quiet(0)
+        a, b = (int(v) & ((1 << 64) - 1) for v in t.tolist())
+        return (b - a) / khz * 1e3
+
+    src, dst = g.malloc(128 * MiB), g.malloc(128 * MiB)
+    out = {}
+    rows = []
+    for k in range(3, 23):
+        n = 1 << k
+        reps = max(1, min(50, (1 << 20) // n))
+        row = {"bytes": n}
+        for name, pe, is_get in (("put_other_pe", 1, False), ("get_other_pe", 1, True), ("put_same_pe", 0, False)):
+            us = min(timed(lambda: g.launch_thread_rma(0, pe, dst, src, n, is_get, reps, t)) for _ in range(3)) / reps
+            row[f"{name}_us"] = us
+            row[f"{name}_gbs"] = n / us / 1e3
+        rows.append(row)
+    out["one_work_item"] = rows
+    # strided: 4 Mi elements moved by 64 groups (host clock on the stream: whole launch)
+    strided = []
+    nel = 1 << 20
+    for elem in (4, 16):
+        for ds, ss in ((1, 1), (2, 1), (1, 2), (4, 4), (16, 16)):
+            for name, fn in (("iput", g.launch_iput), ("iget", g.launch_iget)):
+                best = float("inf")
+                for i in range(5):
+                    e0, e1 = event_pair(torch)
+                    torch.cuda.synchronize()
+                    e0.record(g.streams[0])
+                    fn(0, 1, dst, src, ds, ss, nel, elem, 64)
+                    e1.record(g.streams[0])
+                    g.quiet(0)
+                    if i:
+                        best = min(best, e0.elapsed_time(e1) * 1e3)
+                strided.append({"op": name, "elem_bytes": elem, "dst_stride": ds, "src_stride": ss, "elements": nel, "us": best,
+                                "payload_gbs": nel * elem / best / 1e3})
+    out["strided_64_groups"] = strided
+    # one group of 256: get by loads/stores, by the engine, and the covered put/get against both
+    rows = []
+    for k in range(16, 28):
+        n = 1 << k
+        reps = 4 if n >= 8 * MiB else 10
+        row = {"bytes": n}
+        for name, is_get, mode, cover in (("put_ldst", False, 0, 0), ("put_engine", False, 1, 0), ("put_covered_256k", False, 4, 256 * 1024),
+                                          ("put_covered_512k", False, 4, 512 * 1024), ("get_ldst", True, 0, 0), ("get_engine", True, 1, 0),
+                                          ("get_nbi_quiet", True, 3, 0), ("get_covered_256k", True, 4, 256 * 1024)):
+            row[f"{name}_us"] = min(timed(lambda: g.launch_rma_device_initiated(0, 1, dst, src, n, 1, is_get, mode, 0, cover,
+                                                                                 S.SHM_NO_CONSUME, reps, t, 256))
+                                    for _ in range(3)) / reps
+        rows.append(row)
+    out["one_group_256_work_items"] = rows
+    g.proxy_stop()
+    g.finalize()
+    out["note"] = ("device clock inside the kernel; one work-item keeps 32 16-byte loads in flight, so its bandwidth is bytes in "
+                   "flight over memory latency; covered = copy engine for all but the first 256/512 KiB, which the group moves "
+                   "itself while the engine starts")
+    return out
+
+
 def collective_sweeps(torch, S, args):
     """The paper's collective experiments: fcollect against elements, work-groups and PEs with the
     host copy paths beside it; broadcast against the number of PEs; the device-side sync."""
@@ -554,6 +625,9 @@ def main():
         extras["reverse_offload"] = reverse_offload(torch, S, args)
         log(f"[bench] reverse offload: rtt {extras['reverse_offload']['round_trip_us']} rate {extras['reverse_offload']['request_rate_mreq_s']} "
             f"cutover {extras['reverse_offload']['cutover_bytes_by_work_items']}")
+        extras["single_thread_and_strided"] = single_thread_and_strided(torch, S, args)
+        st = extras["single_thread_and_strided"]
+        log(f"[bench] one work-item put GB/s: {[(r['bytes'], round(r['put_other_pe_gbs'], 3)) for r in st['one_work_item'][::4]]}")
         extras["collective_sweeps"] = collective_sweeps(torch, S, args)
         cs = extras["collective_sweeps"]
         log(f"[bench] sync us by PEs {cs['sync_us_by_pes']} barrier {cs['barrier_us_by_pes']} fcollect cutover "

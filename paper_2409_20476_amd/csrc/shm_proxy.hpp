@@ -48,6 +48,8 @@ public:
         agent_ = agent;
         engines_ = engines;
         in_flight_per_pe_.assign(npes, 0);
+        requests_in_flight_.clear();
+        free_requests_.clear();
         stop_.store(false);
         requests_ = copies_ = 0;
         thread_ = std::thread([this] { run(); });
@@ -67,9 +69,14 @@ public:
     uint64_t copies() const { return copies_; }
 
 private:
+    // One request may be split into pieces that run on several engines; the requester is answered
+    // when the last piece has finished.
     struct copy_in_flight {
         hsa_signal_t sig;
-        uint32_t pe, comp, tag;
+        uint32_t request;      // index into requests_in_flight_
+    };
+    struct request_in_flight {
+        uint32_t pieces_left, pe, comp, tag;
     };
     struct quiet_waiting {
         uint32_t pe, comp, tag;
@@ -99,8 +106,12 @@ private:
         for (size_t i = 0; i < copies_in_flight_.size();) {
             copy_in_flight &c = copies_in_flight_[i];
             if (hsa_signal_load_scacquire(c.sig) < 1) {
-                reply(c.comp, c.tag);
-                --in_flight_per_pe_[c.pe];
+                request_in_flight &r = requests_in_flight_[c.request];
+                if (--r.pieces_left == 0) {
+                    reply(r.comp, r.tag);
+                    --in_flight_per_pe_[r.pe];
+                    free_requests_.push_back(c.request);
+                }
                 free_.push_back(c.sig);
                 copies_in_flight_[i] = copies_in_flight_.back();
                 copies_in_flight_.pop_back();
@@ -131,22 +142,49 @@ private:
             void *dst = reinterpret_cast<void *>(static_cast<uint64_t>(m[4]) | (static_cast<uint64_t>(m[5]) << 32));
             const void *src = reinterpret_cast<const void *>(static_cast<uint64_t>(m[8]) | (static_cast<uint64_t>(m[9]) << 32));
             const size_t n = static_cast<uint64_t>(m[12]) | (static_cast<uint64_t>(m[13]) << 32);
-            hsa_signal_t sig;
-            if (n == 0 || engines_.empty() || !take_signal(sig)) {
+            if (n == 0 || engines_.empty()) {
                 reply(comp, comp_tag);
                 return;
             }
-            const uint32_t eng = engines_[next_engine_++ % engines_.size()];
-            if (hsa_amd_memory_async_copy_on_engine(dst, agent_, src, agent_, n, 0, nullptr, sig,
-                                                    static_cast<hsa_amd_sdma_engine_id_t>(eng), true) != HSA_STATUS_SUCCESS) {
-                free_.push_back(sig);
-                reply(comp, comp_tag);      // the requester is released; its data is not moved (reported by tests, not hidden)
-                ++failed_;
+            // pieces of at least kMinPiece, 256-byte aligned, on successive engines
+            size_t pieces = n / kMinPiece;
+            if (pieces < 1) pieces = 1;
+            if (pieces > engines_.size()) pieces = engines_.size();
+            if (pieces > kMaxPieces) pieces = kMaxPieces;
+            const size_t per = ((n + pieces - 1) / pieces + 255) & ~static_cast<size_t>(255);
+            uint32_t request;
+            if (!free_requests_.empty()) {
+                request = free_requests_.back();
+                free_requests_.pop_back();
+            } else {
+                request = static_cast<uint32_t>(requests_in_flight_.size());
+                requests_in_flight_.push_back({});
+            }
+            uint32_t started = 0;
+            for (size_t off = 0; off < n; off += per) {
+                const size_t len = n - off < per ? n - off : per;
+                hsa_signal_t sig;
+                if (!take_signal(sig)) break;
+                const uint32_t eng = engines_[next_engine_++ % engines_.size()];
+                if (hsa_amd_memory_async_copy_on_engine(static_cast<char *>(dst) + off, agent_, static_cast<const char *>(src) + off, agent_,
+                                                        len, 0, nullptr, sig, static_cast<hsa_amd_sdma_engine_id_t>(eng),
+                                                        true) != HSA_STATUS_SUCCESS) {
+                    free_.push_back(sig);
+                    break;
+                }
+                copies_in_flight_.push_back({sig, request});
+                ++started;
+                ++copies_;
+            }
+            const bool all = static_cast<size_t>(started) * per >= n;
+            if (!all) ++failed_;      // the requester is still released below; its data is incomplete (counted, reported by tests)
+            if (started == 0) {
+                free_requests_.push_back(request);
+                reply(comp, comp_tag);
                 return;
             }
-            ++copies_;
+            requests_in_flight_[request] = {started, pe, comp, comp_tag};
             ++in_flight_per_pe_[pe];
-            copies_in_flight_.push_back({sig, pe, comp, comp_tag});
         } else if (op == SHM_OFFLOAD_QUIET) {
             if (in_flight_per_pe_[pe] == 0)
                 reply(comp, comp_tag);
@@ -192,7 +230,12 @@ private:
     hsa_agent_t agent_{};
     std::vector<uint32_t> engines_;
     std::vector<uint32_t> in_flight_per_pe_;
+    static constexpr size_t kMinPiece = 4u << 20;      // do not split below 4 MiB per engine
+    static constexpr size_t kMaxPieces = 8;
+
     std::vector<copy_in_flight> copies_in_flight_;
+    std::vector<request_in_flight> requests_in_flight_;
+    std::vector<uint32_t> free_requests_;
     std::vector<quiet_waiting> quiets_;
     std::vector<hsa_signal_t> free_;
     std::atomic<bool> stop_{false};

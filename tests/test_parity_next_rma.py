@@ -120,3 +120,25 @@ def test_covered_put_matches_oracle_and_uses_the_engine():
             g.launch_rma_device_initiated(0, 1, 8 * MiB, 4096, MiB, 1, False, 4, cover=4096)
         with pytest.raises(S.ShmError):                             # consume needs a get
             g.launch_rma_device_initiated(0, 1, 8 * MiB, 4096, MiB, 1, False, 0, consume_off=12 * MiB)
+
+
+def test_large_offloaded_transfers_are_split_over_engines():
+    g, o = make_pair(2, 64 * MiB)
+    with g:
+        fill_random(g, o, 66, upto=60 * MiB)
+        g.proxy_start()
+        n = 20 * MiB + 1000                                          # five pieces of at least 4 MiB
+        before = g.proxy_stats()[1]
+        g.launch_rma_device_initiated(0, 1, 30 * MiB + 16, 4096 + 3, n, 1, False, 1)
+        g.quiet(0)
+        o.putmem(0, 30 * MiB + 16, 4096 + 3, n, 1)
+        assert_heaps_equal(g, o, upto=60 * MiB, what="put")
+        mid = g.proxy_stats()[1]
+        assert mid - before >= 2
+        g.launch_rma_device_initiated(1, 0, 30 * MiB, 256, n, 2, True, 3, consume_off=5 * MiB)   # two shares of ~10 MiB: two pieces each
+        g.quiet(1)
+        o.getmem(1, 30 * MiB, 256, n, 0)
+        o.putmem(1, 5 * MiB, 30 * MiB, n, 1)
+        assert_heaps_equal(g, o, upto=60 * MiB, what="get_nbi")
+        assert g.proxy_stats()[1] - mid >= 4
+        g.proxy_stop()
