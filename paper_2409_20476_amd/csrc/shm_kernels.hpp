@@ -445,6 +445,23 @@ __global__ __launch_bounds__(SHMK_WG) void shmk_fcollect_any(shm_dev_ctx c, uint
     }
 }
 
+// Team grids (n_wg, npes) whose npes groups with the same blockIdx.x read the SAME source bytes
+// (the duplicate reduction): groups go to the 8 XCDs round-robin in linear order and each XCD has
+// its own L2, so the npes readers of one share are renumbered to be consecutive groups of one XCD
+// -- they run together and all but the first find the source in that L2 instead of in HBM.
+// Needs gridDim.x to be a multiple of 8; otherwise the plain numbering stays.
+__device__ __forceinline__ void shmk_duplicate_coords(int npes, unsigned &part, int &q)
+{
+    part = blockIdx.x;
+    q = blockIdx.y;
+    if ((gridDim.x & 7u) == 0) {
+        const unsigned lin = blockIdx.x + gridDim.x * blockIdx.y;
+        const unsigned xcd = lin & 7u, j = lin >> 3;
+        q = static_cast<int>(j % npes);
+        part = (j / npes) * 8 + xcd;
+    }
+}
+
 // ---- configuration 5b: float32 sum-reduce ---------------------------------------------------
 // Element i of the result is ((x0[i] + x1[i]) + x2[i]) + ... in PE order, on every PE.
 // SPLIT = false: PE q = blockIdx.y computes all elements and stores to its own destination.
@@ -453,7 +470,10 @@ template <bool SPLIT>
 __global__ __launch_bounds__(SHMK_WG) void shmk_reduce_sum_f32_vec(shm_dev_ctx c, uint64_t dst_off, uint64_t src_off, size_t nvec)
 {
     constexpr int U = 2;
-    const int q = blockIdx.y, npes = c.npes;
+    const int npes = c.npes;
+    int q = blockIdx.y;
+    unsigned part = blockIdx.x;
+    if (!SPLIT) shmk_duplicate_coords(npes, part, q);
     size_t first = 0, count = nvec;
     if (SPLIT) {
         const size_t share = (nvec + npes - 1) / npes;
@@ -461,7 +481,9 @@ __global__ __launch_bounds__(SHMK_WG) void shmk_reduce_sum_f32_vec(shm_dev_ctx c
         count = min(nvec, first + share) - first;
     }
     const uint64_t so = src_off + 16 * first, dof = dst_off + 16 * first;
-    const shm_deal k = shm_deal_make<U>(count, blockIdx.x, gridDim.x, threadIdx.x, SHMK_WG);
+    const shm_deal k = shm_deal_make<U>(count, part, gridDim.x, threadIdx.x, SHMK_WG);
+    // duplicate: the other PEs' groups on this XCD read the same vectors, so they are kept in L2
+    auto load = [&](const shm_f32x4 *a) { return SPLIT ? __builtin_nontemporal_load(a) : *a; };
     auto emit = [&](size_t i, shm_f32x4 r) {
         if (SPLIT) {
             for (int t = 0; t < npes; ++t) {
@@ -478,12 +500,12 @@ __global__ __launch_bounds__(SHMK_WG) void shmk_reduce_sum_f32_vec(shm_dev_ctx c
         shm_f32x4 r[U];
 #pragma unroll
         for (int u = 0; u < U; ++u)
-            r[u] = __builtin_nontemporal_load(reinterpret_cast<const shm_f32x4 *>(shm_ptr(c, so, 0)) + i + u * k.rowv);
+            r[u] = load(reinterpret_cast<const shm_f32x4 *>(shm_ptr(c, so, 0)) + i + u * k.rowv);
         for (int p = 1; p < npes; ++p) {
             const shm_f32x4 *sp = reinterpret_cast<const shm_f32x4 *>(shm_ptr(c, so, p));
             shm_f32x4 v[U];
 #pragma unroll
-            for (int u = 0; u < U; ++u) v[u] = __builtin_nontemporal_load(sp + i + u * k.rowv);
+            for (int u = 0; u < U; ++u) v[u] = load(sp + i + u * k.rowv);
 #pragma unroll
             for (int u = 0; u < U; ++u) r[u].x += v[u].x, r[u].y += v[u].y, r[u].z += v[u].z, r[u].w += v[u].w;
         }
@@ -491,9 +513,9 @@ __global__ __launch_bounds__(SHMK_WG) void shmk_reduce_sum_f32_vec(shm_dev_ctx c
         for (int u = 0; u < U; ++u) emit(i + u * k.rowv, r[u]);
     }
     for (size_t i = k.rem_lane; i < count; i += k.rem_step) {
-        shm_f32x4 r = __builtin_nontemporal_load(reinterpret_cast<const shm_f32x4 *>(shm_ptr(c, so, 0)) + i);
+        shm_f32x4 r = load(reinterpret_cast<const shm_f32x4 *>(shm_ptr(c, so, 0)) + i);
         for (int p = 1; p < npes; ++p) {
-            const shm_f32x4 v = __builtin_nontemporal_load(reinterpret_cast<const shm_f32x4 *>(shm_ptr(c, so, p)) + i);
+            const shm_f32x4 v = load(reinterpret_cast<const shm_f32x4 *>(shm_ptr(c, so, p)) + i);
             r.x += v.x, r.y += v.y, r.z += v.z, r.w += v.w;
         }
         emit(i, r);
@@ -606,7 +628,10 @@ __global__ __launch_bounds__(SHMK_WG) void shmk_reduce(shm_dev_ctx c, uint64_t d
         shm_u32x4 v;
         T e[EPV];
     };
-    const int q = blockIdx.y, npes = c.npes;
+    const int npes = c.npes;
+    int q = blockIdx.y;
+    unsigned part = blockIdx.x;
+    if (!split) shmk_duplicate_coords(npes, part, q);
     const int d0 = split ? 0 : q, d1 = split ? npes : q + 1;
     const size_t nvec = nelems / EPV;
     size_t vlo = 0, vhi = nvec;
@@ -616,13 +641,15 @@ __global__ __launch_bounds__(SHMK_WG) void shmk_reduce(shm_dev_ctx c, uint64_t d
         vhi = min(nvec, vlo + per_pe);
     }
     const size_t per = (vhi - vlo + gridDim.x - 1) / gridDim.x;
-    const size_t lo = min(vhi, vlo + blockIdx.x * per), hi = min(vhi, lo + per);
+    const size_t lo = min(vhi, vlo + part * per), hi = min(vhi, lo + per);
+    // duplicate: the other PEs' groups on this XCD read the same vectors, so they are kept in L2
+    auto load = [&](const shm_u32x4 *a) { return split ? shm_ld16(a) : *a; };
     for (size_t i = lo + threadIdx.x; i < hi; i += SHMK_WG) {
         vec r;
-        r.v = shm_ld16(reinterpret_cast<const shm_u32x4 *>(shm_ptr(c, src_off, 0)) + i);
+        r.v = load(reinterpret_cast<const shm_u32x4 *>(shm_ptr(c, src_off, 0)) + i);
         for (int p = 1; p < npes; ++p) {
             vec x;
-            x.v = shm_ld16(reinterpret_cast<const shm_u32x4 *>(shm_ptr(c, src_off, p)) + i);
+            x.v = load(reinterpret_cast<const shm_u32x4 *>(shm_ptr(c, src_off, p)) + i);
 #pragma unroll
             for (int k = 0; k < EPV; ++k) r.e[k] = shmk_combine<T, OP>(r.e[k], x.e[k]);
         }
@@ -630,7 +657,7 @@ __global__ __launch_bounds__(SHMK_WG) void shmk_reduce(shm_dev_ctx c, uint64_t d
     }
     // the last nelems mod EPV elements, one thread each
     const size_t i = nvec * EPV + threadIdx.x;
-    if (blockIdx.x == 0 && (!split || q == 0) && i < nelems) {
+    if (part == 0 && (!split || q == 0) && i < nelems) {
         T r = reinterpret_cast<const T *>(shm_ptr(c, src_off, 0))[i];
         for (int p = 1; p < npes; ++p) r = shmk_combine<T, OP>(r, reinterpret_cast<const T *>(shm_ptr(c, src_off, p))[i]);
         for (int d = d0; d < d1; ++d) reinterpret_cast<T *>(shm_ptr(c, dst_off, d))[i] = r;
