@@ -580,6 +580,7 @@ def main():
     ap.add_argument("--n-wg", type=int, default=1024, help="work-groups per PE of the headline put")
     ap.add_argument("--sweep-max-mib", type=int, default=256)
     ap.add_argument("--no-extras", action="store_true", help="headline only (used for profiling runs)")
+    ap.add_argument("--extras", default="all", help="comma-separated names of the extra measurements to run (default: all)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also run a plain 2 GiB tensor copy five times (reference reading for HBM byte counters)")
@@ -617,27 +618,30 @@ def main():
     del data0
 
     extras = {}
-    if not args.no_extras:
-        extras["config1_pingflag"] = pingflag(torch, S, synth, args)
-        log(f"[bench] c1: {extras['config1_pingflag']}")
-        extras["config2_put_sweep"] = put_sweep(torch, S, g, args)
-        log(f"[bench] crossover: {extras['config2_put_sweep']['crossover_bytes']}")
-        extras["reverse_offload"] = reverse_offload(torch, S, args)
-        log(f"[bench] reverse offload: rtt {extras['reverse_offload']['round_trip_us']} rate {extras['reverse_offload']['request_rate_mreq_s']} "
-            f"cutover {extras['reverse_offload']['cutover_bytes_by_work_items']}")
-        extras["single_thread_and_strided"] = single_thread_and_strided(torch, S, args)
-        st = extras["single_thread_and_strided"]
-        log(f"[bench] one work-item put GB/s: {[(r['bytes'], round(r['put_other_pe_gbs'], 3)) for r in st['one_work_item'][::4]]}")
-        extras["collective_sweeps"] = collective_sweeps(torch, S, args)
-        cs = extras["collective_sweeps"]
-        log(f"[bench] sync us by PEs {cs['sync_us_by_pes']} barrier {cs['barrier_us_by_pes']} fcollect cutover "
-            f"{dict((k, v['cutover_bytes_per_pe']) for k, v in cs['fcollect'].items())}")
-        extras["config3_ring"] = ring(torch, S, synth, g, args)
-        log(f"[bench] c3: {extras['config3_ring']}")
-        extras["config4_amo_storm"] = storm(torch, S, synth, args)
-        log(f"[bench] c4: {extras['config4_amo_storm']}")
-        extras["config5_collectives"] = collectives(torch, S, synth, g, args)
-        log(f"[bench] c5: {extras['config5_collectives']}")
+    table = [
+        ("config1_pingflag", lambda: pingflag(torch, S, synth, args), lambda r: f"c1: {r}"),
+        ("config2_put_sweep", lambda: put_sweep(torch, S, g, args), lambda r: f"crossover: {r['crossover_bytes']}"),
+        ("reverse_offload", lambda: reverse_offload(torch, S, args),
+         lambda r: f"reverse offload: rtt {r['round_trip_us']} rate {r['request_rate_mreq_s']} cutover {r['cutover_bytes_by_work_items']}"),
+        ("single_thread_and_strided", lambda: single_thread_and_strided(torch, S, args),
+         lambda r: f"one work-item put GB/s: {[(q['bytes'], round(q['put_other_pe_gbs'], 3)) for q in r['one_work_item'][::4]]}"),
+        ("collective_sweeps", lambda: collective_sweeps(torch, S, args),
+         lambda r: f"sync us by PEs {r['sync_us_by_pes']} barrier {r['barrier_us_by_pes']} fcollect cutover "
+                   f"{dict((k, v['cutover_bytes_per_pe']) for k, v in r['fcollect'].items())}"),
+        ("config3_ring", lambda: ring(torch, S, synth, g, args), lambda r: f"c3: {r}"),
+        ("config4_amo_storm", lambda: storm(torch, S, synth, args), lambda r: f"c4: {r}"),
+        ("config5_collectives", lambda: collectives(torch, S, synth, g, args), lambda r: f"c5: {r}"),
+    ]
+    wanted = None if args.extras == "all" else set(args.extras.split(","))
+    unknown = (wanted or set()) - {name for name, _, _ in table}
+    if unknown:
+        print(f"bench.py: unknown extras {sorted(unknown)}; known: {[name for name, _, _ in table]}", file=sys.stderr)
+        return 2
+    for name, run, describe in table:
+        if args.no_extras or (wanted is not None and name not in wanted):
+            continue
+        extras[name] = run()
+        log(f"[bench] {describe(extras[name])}")
     g.finalize()
 
     traffic = None        # measured with rocprofv3 --pmc in a separate run; the summary is committed under profiles/
