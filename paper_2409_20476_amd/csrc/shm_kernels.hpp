@@ -247,11 +247,43 @@ __global__ __launch_bounds__(SHMK_WG) void shmk_ring(shm_dev_ctx c, uint64_t src
         int pe = me + 1;
         if (pe >= npes) pe = 0;
         if (lanes) {
-            // lane `part`: its own share of every chunk, its own signal word, no arrival counting
+            // Lane `part`: its own share of every chunk, its own signal word, no arrival counting.
+            // A put_signal per chunk is a chain of two memory latencies (loads, then the stores'
+            // acknowledgements), so the group works as two halves that alternate: while one half
+            // stores chunk k and waits for the acknowledgements, the other half already loads
+            // chunk k+1.  The barrier that ends step k collects the acknowledgements of chunk k,
+            // and only then is signal k sent: the order of a put_signal per chunk, in half the time.
+            // Vector indices past the share are clamped to its last vector (that vector is then
+            // moved more than once, with the same bytes), which keeps the loop free of predicates.
             const size_t lo = min(nvec, part * per), hi = min(nvec, lo + per);
-            for (int k = 0; k < n_chunks; ++k)
-                shmx_putmem_signal_wg(c, me, slot_off + k * chunk_bytes + 16 * lo, src_off + k * chunk_bytes + 16 * lo, 16 * (hi - lo),
-                                      sig_off + 8ull * part, 1, SHMD_SIGNAL_ADD, pe);
+            constexpr int HALF = SHMK_WG / 2, J = 2 * SHMK_RING_VPT;      // HALF * J = SHMK_WG * SHMK_RING_VPT vectors
+            const int half = threadIdx.x / HALF, t = threadIdx.x % HALF;
+            const shm_u32x4 *s = reinterpret_cast<const shm_u32x4 *>(shm_ptr(c, src_off, me));
+            shm_u32x4 *d = reinterpret_cast<shm_u32x4 *>(shm_ptr(c, slot_off, pe));
+            uint64_t *sig = reinterpret_cast<uint64_t *>(shm_ptr(c, sig_off + 8ull * part, pe));
+            const bool any = hi > lo;
+            size_t v[J];
+#pragma unroll
+            for (int j = 0; j < J; ++j) v[j] = any ? min(hi - 1, lo + t + static_cast<size_t>(j) * HALF) : 0;
+            shm_u32x4 a[J];
+            if (any && half == 0) {
+#pragma unroll
+                for (int j = 0; j < J; ++j) a[j] = shm_ld16(s + v[j]);
+            }
+            for (int k = 0; k < n_chunks; ++k) {
+                if (any) {
+                    if ((k & 1) == half) {
+#pragma unroll
+                        for (int j = 0; j < J; ++j) shm_st16<SHM_ST_THROUGH>(d + k * nvec + v[j], a[j]);
+                        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // this wave's share of chunk k is performed at agent scope
+                    } else if (k + 1 < n_chunks) {
+#pragma unroll
+                        for (int j = 0; j < J; ++j) a[j] = shm_ld16(s + (k + 1) * nvec + v[j]);
+                    }
+                }
+                __syncthreads();
+                if (threadIdx.x == 0) __hip_atomic_fetch_add(sig, 1ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            }
             return;
         }
         uint64_t *arrive = reinterpret_cast<uint64_t *>(shm_ptr(c, arrive_off, me));
@@ -269,23 +301,44 @@ __global__ __launch_bounds__(SHMK_WG) void shmk_ring(shm_dev_ctx c, uint64_t src
     for (int j = 0; j < SHMK_RING_VPT; ++j)
 #pragma unroll
         for (int e = 0; e < 8; ++e) acc[j][e] = 0.0f;
+    // Chunk k may be read once the signal counts k+1.  The leader asks for the signal's value for
+    // chunk k+1 BEFORE the group loads chunk k, so that the answer travels while the data does; only
+    // if it was not yet there does the leader poll.  Leader's acquire, then the barrier extends it.
+    // Vector indices past the share are clamped (their sums are computed and never written).
+    uint64_t *sigp = reinterpret_cast<uint64_t *>(shm_ptr(c, my_sig, me));
+    size_t vi[SHMK_RING_VPT];
+#pragma unroll
+    for (int j = 0; j < SHMK_RING_VPT; ++j)
+        vi[j] = hi > lo ? min(hi - 1, lo + threadIdx.x + static_cast<size_t>(j) * SHMK_WG) : 0;
+    if (threadIdx.x == 0) (void)shm_signal_wait_until(c, me, my_sig, SHMD_CMP_GE, 1);
+    __syncthreads();
     for (int k = 0; k < n_chunks; ++k) {
-        shmx_signal_wait_until_wg(c, me, my_sig, SHMD_CMP_GE, static_cast<uint64_t>(k) + 1);
-        const shm_u32x4 *slot = reinterpret_cast<const shm_u32x4 *>(shm_ptr(c, slot_off + k * chunk_bytes, me));
-        shm_u32x4 w[SHMK_RING_VPT];
+        const bool more = k + 1 < n_chunks;
+        uint64_t early = 0;
+        if (more && threadIdx.x == 0) early = __hip_atomic_load(sigp, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if (hi > lo) {
+            const shm_u32x4 *slot = reinterpret_cast<const shm_u32x4 *>(shm_ptr(c, slot_off + k * chunk_bytes, me));
+            shm_u32x4 w[SHMK_RING_VPT];
 #pragma unroll
-        for (int j = 0; j < SHMK_RING_VPT; ++j) {
-            const size_t v = lo + threadIdx.x + static_cast<size_t>(j) * SHMK_WG;
-            w[j] = (v < hi) ? shm_ld16(slot + v) : shm_u32x4{0, 0, 0, 0};
-        }
+            for (int j = 0; j < SHMK_RING_VPT; ++j) w[j] = shm_ld16(slot + vi[j]);
 #pragma unroll
-        for (int j = 0; j < SHMK_RING_VPT; ++j) {
-            const uint32_t ws[4] = {w[j].x, w[j].y, w[j].z, w[j].w};
+            for (int j = 0; j < SHMK_RING_VPT; ++j) {
+                const uint32_t ws[4] = {w[j].x, w[j].y, w[j].z, w[j].w};
 #pragma unroll
-            for (int q = 0; q < 4; ++q) {      // bf16 -> f32 is a 16-bit left shift: exact
-                acc[j][2 * q] += __uint_as_float(ws[q] << 16);
-                acc[j][2 * q + 1] += __uint_as_float(ws[q] & 0xffff0000u);
+                for (int q = 0; q < 4; ++q) {      // bf16 -> f32 is a 16-bit left shift: exact
+                    acc[j][2 * q] += __uint_as_float(ws[q] << 16);
+                    acc[j][2 * q + 1] += __uint_as_float(ws[q] & 0xffff0000u);
+                }
             }
+        }
+        if (more) {
+            if (threadIdx.x == 0) {
+                if (early >= static_cast<uint64_t>(k) + 2)
+                    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+                else
+                    (void)shm_signal_wait_until(c, me, my_sig, SHMD_CMP_GE, static_cast<uint64_t>(k) + 2);
+            }
+            __syncthreads();
         }
     }
     shm_u32x4 *out = reinterpret_cast<shm_u32x4 *>(shm_ptr(c, acc_off, me));
