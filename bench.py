@@ -530,7 +530,7 @@ def collectives(torch, S, synth, g, args):
         return best
 
     fc_bytes = npes * 4 * nel + npes * npes * 4 * nel            # each source read once, every block written 8 times
-    for n_wg in (256, 1024):
+    for n_wg in (32, 256, 1024):           # 32 groups per PE = one group per compute unit
         ms = best_of(lambda: g.launch_fcollect(fdst, fsrc, 4 * nel, n_wg, S.SHM_PATH_LDST))
         out[f"fcollect_ldst_wg{n_wg}"] = {"ms": ms, "algorithmic_gbs": fc_bytes / ms / 1e6, "frac_hbm": fc_bytes / ms / 1e6 / HBM_PEAK_GBS}
     sd_bytes = 2 * npes * npes * 4 * nel
