@@ -234,7 +234,7 @@ __global__ __launch_bounds__(SHMK_WG) void shmk_ping_consumer(shm_dev_ctx c, uin
 // in the grid, so consumers cannot starve them.
 #define SHMK_RING_VPT 8      // 16-byte vectors (8 bf16) per consumer thread held in registers
 
-__global__ __launch_bounds__(SHMK_WG) void shmk_ring(shm_dev_ctx c, uint64_t src_off, uint64_t slot_off, uint64_t sig_off,
+__global__ __launch_bounds__(SHMK_WG, 4) void shmk_ring(shm_dev_ctx c, uint64_t src_off, uint64_t slot_off, uint64_t sig_off,
                                                      uint64_t acc_off, size_t chunk_bytes, int n_chunks, int n_prod, int n_cons,
                                                      uint64_t arrive_off, int lanes)
 {
@@ -262,23 +262,23 @@ __global__ __launch_bounds__(SHMK_WG) void shmk_ring(shm_dev_ctx c, uint64_t src
             shm_u32x4 *d = reinterpret_cast<shm_u32x4 *>(shm_ptr(c, slot_off, pe));
             uint64_t *sig = reinterpret_cast<uint64_t *>(shm_ptr(c, sig_off + 8ull * part, pe));
             const bool any = hi > lo;
-            size_t v[J];
-#pragma unroll
-            for (int j = 0; j < J; ++j) v[j] = any ? min(hi - 1, lo + t + static_cast<size_t>(j) * HALF) : 0;
+            const uint32_t last = any ? static_cast<uint32_t>(hi - 1 - lo) : 0;      // a share has at most 2048 vectors
+            s += lo, d += lo;
+            auto v = [&](int j) { return min(last, static_cast<uint32_t>(t + j * HALF)); };
             shm_u32x4 a[J];
             if (any && half == 0) {
 #pragma unroll
-                for (int j = 0; j < J; ++j) a[j] = shm_ld16(s + v[j]);
+                for (int j = 0; j < J; ++j) a[j] = shm_ld16(s + v(j));
             }
             for (int k = 0; k < n_chunks; ++k) {
                 if (any) {
                     if ((k & 1) == half) {
 #pragma unroll
-                        for (int j = 0; j < J; ++j) shm_st16<SHM_ST_THROUGH>(d + k * nvec + v[j], a[j]);
+                        for (int j = 0; j < J; ++j) shm_st16<SHM_ST_THROUGH>(d + k * nvec + v(j), a[j]);
                         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // this wave's share of chunk k is performed at agent scope
                     } else if (k + 1 < n_chunks) {
 #pragma unroll
-                        for (int j = 0; j < J; ++j) a[j] = shm_ld16(s + (k + 1) * nvec + v[j]);
+                        for (int j = 0; j < J; ++j) a[j] = shm_ld16(s + (k + 1) * nvec + v(j));
                     }
                 }
                 __syncthreads();
@@ -306,10 +306,8 @@ __global__ __launch_bounds__(SHMK_WG) void shmk_ring(shm_dev_ctx c, uint64_t src
     // if it was not yet there does the leader poll.  Leader's acquire, then the barrier extends it.
     // Vector indices past the share are clamped (their sums are computed and never written).
     uint64_t *sigp = reinterpret_cast<uint64_t *>(shm_ptr(c, my_sig, me));
-    size_t vi[SHMK_RING_VPT];
-#pragma unroll
-    for (int j = 0; j < SHMK_RING_VPT; ++j)
-        vi[j] = hi > lo ? min(hi - 1, lo + threadIdx.x + static_cast<size_t>(j) * SHMK_WG) : 0;
+    const uint32_t last = hi > lo ? static_cast<uint32_t>(hi - 1 - lo) : 0;
+    auto vi = [&](int j) { return lo + min(last, static_cast<uint32_t>(threadIdx.x + j * SHMK_WG)); };
     if (threadIdx.x == 0) (void)shm_signal_wait_until(c, me, my_sig, SHMD_CMP_GE, 1);
     __syncthreads();
     for (int k = 0; k < n_chunks; ++k) {
@@ -320,7 +318,7 @@ __global__ __launch_bounds__(SHMK_WG) void shmk_ring(shm_dev_ctx c, uint64_t src
             const shm_u32x4 *slot = reinterpret_cast<const shm_u32x4 *>(shm_ptr(c, slot_off + k * chunk_bytes, me));
             shm_u32x4 w[SHMK_RING_VPT];
 #pragma unroll
-            for (int j = 0; j < SHMK_RING_VPT; ++j) w[j] = shm_ld16(slot + vi[j]);
+            for (int j = 0; j < SHMK_RING_VPT; ++j) w[j] = shm_ld16(slot + vi(j));
 #pragma unroll
             for (int j = 0; j < SHMK_RING_VPT; ++j) {
                 const uint32_t ws[4] = {w[j].x, w[j].y, w[j].z, w[j].w};
