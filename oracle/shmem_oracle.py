@@ -359,6 +359,23 @@ class ShmemOracle:
             for p in range(self.npes):
                 self.heap[q][dst + p * n:dst + (p + 1) * n] = blocks[p]
 
+    def wave_exchange(self, me: int, pe: int, dst: int, src: int, back: int, n: int, n_waves: int, flag: int,
+                      out: int) -> None:
+        """The sub-group (wave) forms in one program (paper section "Proposed Device APIs": the
+        sub-group extensions): wave w of PE ``me`` puts the w-th slice of the message to PE ``pe``,
+        fences, and sets pe's w-th flag word to 1; wave w of PE ``pe`` waits for that flag, stores
+        the value it fetches from it to its w-th out word, and gets the slice from its own
+        destination into ``back``.  Slices as for work-groups (16-byte-rounded equal shares)."""
+        self._pe(me), self._pe(pe)
+        for w, (lo, hi) in enumerate(self.wg_slices(n, n_waves)):
+            self.putmem(me, dst + lo, src + lo, hi - lo, pe)
+            self.fence(me)
+            self.atomic_set(me, flag + 8 * w, 1, pe)
+        for w, (lo, hi) in enumerate(self.wg_slices(n, n_waves)):
+            self.signal_wait_until(pe, flag + 8 * w, CMP_EQ, 1)
+            self._store_u64(pe, out + 8 * w, self.signal_fetch(pe, flag + 8 * w))
+            self.getmem(pe, back + lo, dst + lo, hi - lo, pe)
+
     REDUCE_OPS = ("min", "max", "sum", "prod", "and", "or", "xor")
 
     def reduce(self, dst: int, src: int, nelems: int, dtype, op: str) -> np.ndarray:

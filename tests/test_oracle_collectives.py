@@ -214,3 +214,28 @@ def test_barrier_exchange_delivers_every_neighbours_block():
         for r in range(3):
             assert (o.heap[p][512 + r * n:512 + (r + 1) * n] == blocks[(p - 1 - r) % npes]).all()
     assert o.log.count(("barrier_all",)) == 3
+
+
+def test_wave_exchange_is_put_flag_wait_get_per_slice():
+    # closed form: destination and back buffer equal the source, flags and fetched values are 1,
+    # for ragged sizes and more waves than 16-byte units
+    for n, n_waves in [(1000, 7), (16, 4), (0, 3), (4096, 1), (100, 64)]:
+        o = ShmemOracle(3, 1 << 15)
+        _fill(o, n + n_waves)
+        before = [h.copy() for h in o.heap]
+        src, dst, back, flag, out = 64, 8192, 16384, 24576, 28672
+        for p in range(3):
+            o.heap[p][flag:flag + 8 * n_waves] = 0
+            before[p][flag:flag + 8 * n_waves] = 0
+        o.wave_exchange(2, 1, dst, src, back, n, n_waves, flag, out)
+        want = before[2][src:src + n]
+        assert np.array_equal(o.heap[1][dst:dst + n], want)
+        assert np.array_equal(o.heap[1][back:back + n], want)
+        assert np.all(o.heap[1][flag:flag + 8 * n_waves].view(np.uint64) == 1)
+        assert np.all(o.heap[1][out:out + 8 * n_waves].view(np.uint64) == 1)
+        # nothing else changed anywhere
+        touched = np.zeros(1 << 15, bool)
+        for a, m in ((dst, n), (back, n), (flag, 8 * n_waves), (out, 8 * n_waves)):
+            touched[a:a + m] = True
+        assert np.array_equal(o.heap[1][~touched], before[1][~touched])
+        assert np.array_equal(o.heap[0], before[0]) and np.array_equal(o.heap[2], before[2])
