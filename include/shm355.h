@@ -200,6 +200,17 @@ int shm_launch_rma_device_initiated(shm_ctx *ctx, int me, int pe, uint64_t dst_o
                                     int is_get, int mode, size_t cutover, size_t cover, uint64_t consume_off, int reps,
                                     uint64_t *dev_ticks);
 
+/* The sub-group forms (paper section "Proposed Device APIs": sub-group extensions; a sub-group is a
+ * 64-lane wave here) in one kernel on me's stream.  Wave w of n_waves (1..4096) owns the w-th
+ * 16-byte-rounded share of the n-byte message.  Producer waves (PE me): wave put of the share from
+ * src_off to pe's dst_off, fence, then pe's flag word flag_off + 8w := 1.  Consumer waves (PE pe):
+ * wait until that flag == 1 (bounded), store the value signal_fetch returns to out_off + 8w, then
+ * wave-get the share from pe's own dst_off into back_off.  The caller zeroes the flags first.
+ * All buffers on pe are pairwise disjoint (SHM_EINVAL otherwise); the grid must fit the device as a
+ * whole (SHM_EINVAL). */
+int shm_launch_wave_exchange(shm_ctx *ctx, int me, int pe, uint64_t dst_off, uint64_t src_off, uint64_t back_off, size_t n, int n_waves,
+                             uint64_t flag_off, uint64_t out_off);
+
 /* Single-thread put/get (paper section "Performance Evaluation", first experiment: ishmem_put and
  * ishmem_get called by one work-item): one thread of one kernel on me's stream moves n bytes `reps`
  * times, a quiet after each put.  dev_ticks as above, or NULL. */

@@ -719,6 +719,38 @@ int shm_launch_put_device_initiated(shm_ctx *c, int me, int pe, uint64_t dst_off
                                            dev_ticks);
 }
 
+int shm_launch_wave_exchange(shm_ctx *c, int me, int pe, uint64_t dst_off, uint64_t src_off, uint64_t back_off, size_t n, int n_waves,
+                             uint64_t flag_off, uint64_t out_off)
+{
+    if (int r = check_ctx(c)) return r;
+    if (int r = rma_args(c, me, pe, dst_off, src_off, n)) return r;
+    if (n_waves < 1 || n_waves > 4096) return fail(SHM_EINVAL, "n_waves outside 1..4096");
+    if (int r = check_range(c, back_off, n, "back buffer")) return r;
+    if (int r = check_range(c, flag_off, 8ull * n_waves, "flags")) return r;
+    if (int r = check_range(c, out_off, 8ull * n_waves, "fetched values")) return r;
+    if ((flag_off | out_off) & 7) return fail(SHM_EINVAL, "flag and out offsets must be 8-byte aligned");
+    // on PE pe: destination, back buffer, flags and out words are pairwise disjoint (and the source too if me == pe)
+    struct span {
+        uint64_t off;
+        size_t len;
+    };
+    const span on_pe[5] = {{dst_off, n}, {back_off, n}, {flag_off, 8ull * n_waves}, {out_off, 8ull * n_waves}, {src_off, me == pe ? n : 0}};
+    for (int i = 0; i < 5; ++i)
+        for (int j = i + 1; j < 5; ++j)
+            if (on_pe[i].len && on_pe[j].len && on_pe[i].off < on_pe[j].off + on_pe[j].len && on_pe[j].off < on_pe[i].off + on_pe[i].len)
+                return fail(SHM_EINVAL, "buffers overlap on PE %d", pe);
+    if (c->no_device) return no_device("shm_launch_wave_exchange");
+    if (int r = drain_engines(c, me)) return r;
+    int per_cu = 0;
+    HIP_TRY(hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, shmk_wave_exchange, SHMK_WG, 0));
+    const long long groups = 2ll * ((n_waves + 3) / 4);
+    if (groups > static_cast<long long>(per_cu) * c->num_cu)
+        return fail(SHM_EINVAL, "%lld groups cannot all be resident (%d CUs x %d)", groups, c->num_cu, per_cu);
+    hipLaunchKernelGGL(shmk_wave_exchange, dim3(static_cast<unsigned>(groups)), dim3(SHMK_WG), 0, c->stream[me], dev_view(c), dst_off,
+                       src_off, back_off, n, n_waves, flag_off, out_off, me, pe);
+    return launched("wave exchange");
+}
+
 int shm_launch_thread_rma(shm_ctx *c, int me, int pe, uint64_t dst_off, uint64_t src_off, size_t n, int is_get, int reps,
                           uint64_t *dev_ticks)
 {

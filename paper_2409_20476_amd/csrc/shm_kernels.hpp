@@ -228,6 +228,36 @@ __global__ __launch_bounds__(SHMK_WG) void shmk_ping_consumer(shm_dev_ctx c, uin
     shmx_getmem_wg(c, 1, back_off, data_off, n, 0);
 }
 
+// ---- the sub-group (wave) forms in one program --------------------------------------------------
+// Blocks [0, G) are producers of PE `me`, blocks [G, 2G) consumers of PE `pe`; wave w (4 per group)
+// owns the w-th 16-byte-rounded share of the message.  Producer wave: wave put, fence, lane 0 sets
+// flag w on pe.  Consumer wave: lane 0 waits for flag w (bounded) and records what signal_fetch
+// returns; the wave then gets its share from pe's own destination into `back`.  Producers come first
+// in the grid and never wait; the host refuses a grid that cannot be resident as a whole.
+__global__ __launch_bounds__(SHMK_WG) void shmk_wave_exchange(shm_dev_ctx c, uint64_t dst_off, uint64_t src_off, uint64_t back_off,
+                                                              size_t n, int n_waves, uint64_t flag_off, uint64_t out_off, int me, int pe)
+{
+    const int groups = (n_waves + 3) / 4;
+    const bool producer = static_cast<int>(blockIdx.x) < groups;
+    const int w = (producer ? blockIdx.x : blockIdx.x - groups) * 4 + (threadIdx.x >> 6);
+    if (w >= n_waves) return;
+    size_t per = (n + n_waves - 1) / n_waves;
+    per = (per + 15) & ~static_cast<size_t>(15);
+    const size_t lo = min(n, static_cast<size_t>(w) * per), len = min(n, lo + per) - lo;
+    const uint64_t flag = flag_off + 8ull * w;
+    if (producer) {
+        shmx_putmem_wave(c, me, dst_off + lo, src_off + lo, len, pe);
+        shm_fence();                                            // the share is delivered before the flag
+        if (__lane_id() == 0) shm_atomic_set(c, flag, 1, pe);
+        return;
+    }
+    if (__lane_id() == 0) {
+        (void)shm_signal_wait_until(c, pe, flag, SHMD_CMP_EQ, 1);
+        *reinterpret_cast<uint64_t *>(shm_ptr(c, out_off + 8ull * w, pe)) = shm_signal_fetch(c, pe, flag);
+    }
+    shmx_getmem_wave(c, pe, back_off + lo, dst_off + lo, len, pe);
+}
+
 // ---- configuration 3: pipelined ring --------------------------------------------------------
 // Blocks [0, npes*n_prod) are producers, the rest consumers; PE = index mod npes so that the
 // groups of one PE are spread over the dispatch order.  Producers never wait, and they come first

@@ -160,6 +160,11 @@ def test_every_entry_point_validates_before_touching_the_device():
     assert code(lambda: g.launch_iput(0, 1, 0, 0, H // 400 + 1, 1, 101, 4, 0)) == S.SHM_ERANGE
     assert code(lambda: g.launch_iget(0, 1, 0, 0, 1, (1 << 62), 3, 8, 0)) == S.SHM_ERANGE
     assert code(lambda: g.launch_iget(0, 1, 0, 0, 1, 1, (1 << 63), 16, 0)) == S.SHM_ERANGE
+    assert code(lambda: g.launch_wave_exchange(0, 1, 4096, 0, 8192, 100, 4, 16384, 20480)) == S.SHM_ENODEV
+    assert code(lambda: g.launch_wave_exchange(0, 1, 4096, 0, 4100, 100, 4, 16384, 20480)) == S.SHM_EINVAL    # back overlaps dst
+    assert code(lambda: g.launch_wave_exchange(0, 1, 4096, 0, 8192, 100, 4, 16388, 20480)) == S.SHM_EINVAL    # flag alignment
+    assert code(lambda: g.launch_wave_exchange(0, 1, 4096, 0, 8192, 100, 0, 16384, 20480)) == S.SHM_EINVAL
+    assert code(lambda: g.launch_wave_exchange(0, 1, 4096, 0, 8192, 100, 4, H - 8, 20480)) == S.SHM_ERANGE
     assert code(lambda: g.launch_thread_rma(0, 1, 4096, 0, 100)) == S.SHM_ENODEV
     assert code(lambda: g.launch_thread_rma(0, 0, 50, 0, 100)) == S.SHM_EINVAL
     assert code(lambda: g.launch_rma_device_initiated(0, 1, 4096, 0, 100, 2, True, 0)) == S.SHM_ENODEV

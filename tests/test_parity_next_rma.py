@@ -142,3 +142,24 @@ def test_large_offloaded_transfers_are_split_over_engines():
         assert_heaps_equal(g, o, upto=60 * MiB, what="get_nbi")
         assert g.proxy_stats()[1] - mid >= 4
         g.proxy_stop()
+
+
+@pytest.mark.parametrize("n,n_waves,sa,da", [(100003, 7, 5, 9), (16, 4, 0, 0), (0, 3, 0, 0), (4096, 1, 1, 0), (100, 64, 0, 3),
+                                            (3 * MiB + 17, 1024, 16, 32), (MiB, 256, 0, 0)])
+def test_wave_forms_put_fence_flag_wait_fetch_get(n, n_waves, sa, da):
+    g, o = make_pair(3, 16 * MiB)
+    with g:
+        fill_random(g, o, 67, upto=14 * MiB)
+        src, dst, back, flag, out = 4096 + sa, 4 * MiB + da, 8 * MiB + da, 12 * MiB, 12 * MiB + 65536
+        zeros = np.zeros(8 * n_waves, np.uint8)
+        for rep in range(2):                                   # the second round finds the first round's bytes in the caches
+            for p in range(3):
+                g.write(p, flag, zeros), o.write(p, flag, zeros)
+                g.write(p, out, zeros), o.write(p, out, zeros)
+            if rep and n:
+                fresh = np.random.default_rng(rep).integers(0, 256, n, dtype=np.uint8)
+                g.write(2, src, fresh), o.write(2, src, fresh)
+            g.launch_wave_exchange(2, 1, dst, src, back, n, n_waves, flag, out)
+            g.quiet(2)
+            o.wave_exchange(2, 1, dst, src, back, n, n_waves, flag, out)
+            assert_heaps_equal(g, o, upto=14 * MiB, what=f"round {rep}")
