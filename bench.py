@@ -264,16 +264,19 @@ def reverse_offload(torch, S, args):
         n = 1 << k
         row = {"bytes": n}
         reps = 4 if n >= 8 * MiB else 20
-        for wg in (64, 256, 1024):
+        for wg in (1, 16, 64, 128, 256, 1024):
+            if wg < 64 and n > (4 * MiB if wg == 16 else MiB):
+                continue                       # a few lanes move 0.3-4 GB/s: the curve is flat long before this
             row[f"ldst_wi{wg}_us"] = min(timed(lambda: g.launch_put_device_initiated(0, 1, dst, src, n, 1, 0, 0, reps, t, wg))
                                          for _ in range(3)) / reps
         row["engine_us"] = min(timed(lambda: g.launch_put_device_initiated(0, 1, dst, src, n, 1, 1, 0, reps, t, 256))
                                for _ in range(3)) / reps
         rows.append(row)
     cross = {}
-    for wg in (64, 256, 1024):
-        cross[str(wg)] = next((r["bytes"] for i, r in enumerate(rows)
-                               if all(q["engine_us"] <= q[f"ldst_wi{wg}_us"] for q in rows[i:])), None)
+    for wg in (1, 16, 64, 128, 256, 1024):
+        key = f"ldst_wi{wg}_us"
+        have = [r for r in rows if key in r]           # the few-lane curves stop early; sizes beyond are the engine's
+        cross[str(wg)] = next((r["bytes"] for i, r in enumerate(have) if all(q["engine_us"] <= q[key] for q in have[i:])), None)
     # the cutover taken inside the kernel, with the threshold just measured for 256 work-items
     cut = cross["256"] or (1 << 62)
     for row in rows:

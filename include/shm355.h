@@ -177,8 +177,8 @@ int shm_proxy_start(shm_ctx *ctx);
 int shm_proxy_stop(shm_ctx *ctx);
 int shm_proxy_stats(const shm_ctx *ctx, uint64_t *requests, uint64_t *copies);
 
-/* One kernel of n_wg groups (1..1024) of wg_size threads (a multiple of 64, 64..1024: the paper
- * varies the work-items per work-group) on me's stream puts n bytes from me's src_off to pe's
+/* One kernel of n_wg groups (1..1024) of wg_size threads (1..1024: the paper varies the work-items
+ * per work-group; modes 1-3 talk to the host with one whole wave and need a multiple of 64) on me's stream puts n bytes from me's src_off to pe's
  * dst_off `reps` times; group g owns the g-th contiguous 256-byte-aligned share.  mode 0: loads/stores and
  * group quiet; 1: reverse offload to a copy engine, blocking; 2: cutover inside the kernel (share
  * size >= cutover bytes -> engine, else loads/stores); 3: non-blocking offload followed by an

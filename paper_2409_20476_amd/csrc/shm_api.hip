@@ -693,8 +693,9 @@ int shm_launch_rma_device_initiated(shm_ctx *c, int me, int pe, uint64_t dst_off
     if (int r = check_ctx(c)) return r;
     if (int r = rma_args(c, me, pe, dst_off, src_off, n)) return r;
     if (n_wg < 1 || n_wg > 1024) return fail(SHM_EINVAL, "n_wg outside 1..1024");
-    if (wg_size < 64 || wg_size > 1024 || wg_size % 64) return fail(SHM_EINVAL, "wg_size must be a multiple of 64 in 64..1024");
     if (mode < 0 || mode > 4) return fail(SHM_EINVAL, "mode outside 0..4");
+    if (wg_size < 1 || wg_size > 1024) return fail(SHM_EINVAL, "wg_size outside 1..1024");
+    if (mode != 0 && wg_size % 64) return fail(SHM_EINVAL, "the copy-engine modes need whole waves: wg_size must be a multiple of 64");
     if (reps < 1 || reps > (1 << 20)) return fail(SHM_EINVAL, "reps outside 1..2^20");
     if (consume_off != SHM_NO_CONSUME) {
         if (!is_get) return fail(SHM_EINVAL, "only a get has a local destination to consume");

@@ -49,6 +49,22 @@ def test_device_initiated_put_matches_oracle(mode):
         g.proxy_stop()
 
 
+@pytest.mark.parametrize("wg_size", [1, 16, 100, 128])
+def test_device_initiated_put_by_partial_waves(wg_size):
+    """The paper's work-items axis below one wave: 1, 16, ... work-items per work-group, loads/stores."""
+    g, o = make_pair(2, 4 * MiB)
+    with g:
+        fill_random(g, o, 32, upto=3 * MiB)
+        for i, (n, n_wg, sa, da) in enumerate([(10007, 1, 3, 5), (65536 + 40, 2, 0, 0), (0, 1, 0, 0), (17, 3, 1, 2)]):
+            t = _ticks()
+            g.launch_put_device_initiated(0, 1, 2 * MiB + da, 256 + sa, n, n_wg, 0, 0, 2, t, wg_size=wg_size)
+            g.quiet(0)
+            o.wg_put(0, 2 * MiB + da, 256 + sa, n, 1, n_wg)
+            assert_heaps_equal(g, o, upto=3 * MiB, what=f"case {i}")
+        with pytest.raises(S.ShmError):
+            g.launch_put_device_initiated(0, 1, 2 * MiB, 256, 100, 1, 1, 0, 1, _ticks(), wg_size=wg_size)   # engine modes need whole waves... and the proxy
+
+
 def test_ring_round_trips_rate_and_wraparound():
     g, o = make_pair(2, MiB)
     with g:
