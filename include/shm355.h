@@ -126,7 +126,10 @@ int shm_barrier_all(shm_ctx *ctx);
  * MEMCPY: hipMemcpyAsync in stream order -- on one device the runtime executes it as a copy kernel
  * of its own, not on an engine; kept as a reference curve.
  * With SHM_PATH_AUTO a transfer of n bytes by n_wg work-groups uses SDMA iff
- * n >= cutover(class of n_wg); classes are n_wg <= 1, <= 4, <= 64, > 64.  SIZE_MAX = never. */
+ * n >= cutover(class of n_wg); classes are n_wg <= 1, <= 4, <= 64, > 64.  SIZE_MAX = never.
+ * Defaults are the thresholds measured on MI355X with 8 PEs transferring at once (the paper sets its
+ * own the same way, internally): 2 MiB for one group per PE, never for more.  A context whose copy
+ * engines are unavailable keeps AUTO on loads/stores. */
 int shm_set_cutover(shm_ctx *ctx, int n_wg, size_t bytes);
 int shm_get_cutover(const shm_ctx *ctx, int n_wg, size_t *bytes);
 /* Which path AUTO would take: writes SHM_PATH_LDST or SHM_PATH_SDMA to *path. */
@@ -196,6 +199,9 @@ int shm_launch_put_device_initiated(shm_ctx *ctx, int me, int pe, uint64_t dst_o
  * before the first get and after every get, from inside the kernel, so the buffer shows what the
  * kernel itself reads after a get.  dev_ticks may be NULL. */
 #define SHM_NO_CONSUME UINT64_MAX
+/* As `cutover` of mode 2: the threshold measured on MI355X for one work-group of wg_size work-items
+ * (16 KiB for 1, 256 KiB up to 16, 2 MiB up to 64, 4 MiB beyond). */
+#define SHM_CUTOVER_TUNED (SIZE_MAX - 1)
 int shm_launch_rma_device_initiated(shm_ctx *ctx, int me, int pe, uint64_t dst_off, uint64_t src_off, size_t n, int n_wg, int wg_size,
                                     int is_get, int mode, size_t cutover, size_t cover, uint64_t consume_off, int reps,
                                     uint64_t *dev_ticks);

@@ -61,7 +61,9 @@ struct shm_ctx {
     uint64_t *status_dev = nullptr;
     uint64_t wait_us = 2000000;
     uint64_t ticks_per_us = 100;
-    size_t cutover[4] = {SIZE_MAX, SIZE_MAX, SIZE_MAX, SIZE_MAX};
+    // AUTO thresholds per class of work-group count, as measured on MI355X with 8 PEs transferring at
+    // once: the engines win from 2 MiB with one group per PE and never against four or more groups.
+    size_t cutover[4] = {size_t(2) << 20, SIZE_MAX, SIZE_MAX, SIZE_MAX};
     bool team_sync = true;
     int num_cu = 0;
     uint32_t next_slot[SHM_MAX_PES] = {};
@@ -135,8 +137,8 @@ int wg_class(int n_wg) { return n_wg <= 1 ? 0 : n_wg <= 4 ? 1 : n_wg <= 64 ? 2 :
 
 int resolve_path(const shm_ctx *c, int path, size_t n, int n_wg, int *out)
 {
-    if (path == SHM_PATH_AUTO)
-        *out = (n >= c->cutover[wg_class(n_wg)]) ? SHM_PATH_SDMA : SHM_PATH_LDST;
+    if (path == SHM_PATH_AUTO)      // a context without usable engines keeps to loads/stores
+        *out = (n >= c->cutover[wg_class(n_wg)] && (c->no_device || c->engines.ready())) ? SHM_PATH_SDMA : SHM_PATH_LDST;
     else if (path == SHM_PATH_LDST || path == SHM_PATH_SDMA || path == SHM_PATH_MEMCPY)
         *out = path;
     else

@@ -715,11 +715,24 @@ __device__ __forceinline__ void shmx_quiet_offload_wg(const shm_dev_ctx &c, int 
 }
 
 // The cutover inside the kernel (paper section "Performance Evaluation"): loads/stores below
-// `cutover` bytes, the host-started copy engine from there on.
+// `cutover` bytes, the host-started copy engine from there on.  SHMD_CUTOVER_TUNED asks for the
+// threshold measured on MI355X for one work-group of the calling size: it grows with the number of
+// work-items, because more lanes move more bytes per microsecond while the engine's start-up time
+// (about 14 us through the host) and rate (61 GB/s) stay what they are.
+#define SHMD_CUTOVER_TUNED (~static_cast<size_t>(1))
+__device__ __forceinline__ size_t shm_tuned_cutover(unsigned work_items)
+{
+    return work_items <= 1 ? (size_t(16) << 10) : work_items <= 16 ? (size_t(256) << 10) : work_items <= 64 ? (size_t(2) << 20)
+                                                                                                             : (size_t(4) << 20);
+}
+__device__ __forceinline__ size_t shm_resolve_cutover(size_t cutover)
+{
+    return cutover == SHMD_CUTOVER_TUNED ? shm_tuned_cutover(blockDim.x) : cutover;
+}
 __device__ __forceinline__ void shmx_putmem_auto_wg(const shm_dev_ctx &c, int me, uint64_t dst_off, uint64_t src_off, size_t n, int pe,
                                                     size_t cutover)
 {
-    if (c.off.ring != nullptr && n >= cutover)
+    if (c.off.ring != nullptr && n >= shm_resolve_cutover(cutover))
         shmx_putmem_offload_wg(c, me, dst_off, src_off, n, pe, true);
     else
         shmx_putmem_wg(c, me, dst_off, src_off, n, pe);
@@ -727,7 +740,7 @@ __device__ __forceinline__ void shmx_putmem_auto_wg(const shm_dev_ctx &c, int me
 __device__ __forceinline__ void shmx_getmem_auto_wg(const shm_dev_ctx &c, int me, uint64_t dst_off, uint64_t src_off, size_t n, int pe,
                                                     size_t cutover)
 {
-    if (c.off.ring != nullptr && n >= cutover)
+    if (c.off.ring != nullptr && n >= shm_resolve_cutover(cutover))
         shmx_getmem_offload_wg(c, me, dst_off, src_off, n, pe, true);
     else
         shmx_getmem_wg(c, me, dst_off, src_off, n, pe);

@@ -91,7 +91,7 @@ __global__ __launch_bounds__(1024) void shmk_rma_device_initiated(shm_dev_ctx c,
             else
                 shmx_putmem_offload_wg(c, me, d, s, len, pe, true);
         } else if (mode == 2) {
-            const bool engine = c.off.ring != nullptr && len >= cutover;
+            const bool engine = c.off.ring != nullptr && len >= shm_resolve_cutover(cutover);
             if (is_get) {
                 shmx_getmem_auto_wg(c, me, d, s, len, pe, cutover);
             } else {

@@ -28,6 +28,7 @@ SHM_INIT_DEFAULT, SHM_INIT_NO_DEVICE = 0, 1
 SHM_STORM_FETCH_ADD, SHM_STORM_ADD, SHM_STORM_CSWAP_LOOP, SHM_STORM_PLAIN_STORE = range(4)
 SHM_REDUCE_DUPLICATE, SHM_REDUCE_SPLIT = 0, 1
 SHM_NO_CONSUME = (1 << 64) - 1
+SHM_CUTOVER_TUNED = (1 << 64) - 2
 SHM_OP_MIN, SHM_OP_MAX, SHM_OP_SUM, SHM_OP_PROD, SHM_OP_AND, SHM_OP_OR, SHM_OP_XOR = range(7)
 (SHM_INT8, SHM_UINT8, SHM_INT16, SHM_UINT16, SHM_INT32, SHM_UINT32, SHM_INT64, SHM_UINT64, SHM_FLOAT32,
  SHM_FLOAT64) = range(10)

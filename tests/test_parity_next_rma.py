@@ -163,3 +163,21 @@ def test_wave_forms_put_fence_flag_wait_fetch_get(n, n_waves, sa, da):
             g.quiet(2)
             o.wave_exchange(2, 1, dst, src, back, n, n_waves, flag, out)
             assert_heaps_equal(g, o, upto=14 * MiB, what=f"round {rep}")
+
+
+def test_tuned_in_kernel_cutover_follows_the_work_items():
+    """Mode 2 with SHM_CUTOVER_TUNED: a share below the threshold for the group's size moves by
+    loads/stores (no engine copy), at or above it through the engine."""
+    g, o = make_pair(2, 24 * MiB)
+    with g:
+        fill_random(g, o, 68, upto=20 * MiB)
+        g.proxy_start()
+        for wg_size, n, engine in [(64, 2 * MiB - 256, False), (64, 2 * MiB, True), (256, 2 * MiB, False), (256, 4 * MiB, True),
+                                   (1024, 4 * MiB - 256, False), (1024, 4 * MiB + 100, True)]:
+            before = g.proxy_stats()[1]
+            g.launch_rma_device_initiated(0, 1, 8 * MiB + 16, 4096, n, 1, False, 2, cutover=S.SHM_CUTOVER_TUNED, wg_size=wg_size)
+            g.quiet(0)
+            o.putmem(0, 8 * MiB + 16, 4096, n, 1)
+            assert_heaps_equal(g, o, upto=20 * MiB, what=f"{wg_size} work-items, {n} bytes")
+            assert (g.proxy_stats()[1] > before) == engine, (wg_size, n)
+        g.proxy_stop()
