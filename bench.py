@@ -461,7 +461,7 @@ def ring(torch, S, synth, g, args):
     zero = np.zeros(8 * 64, np.uint8)
     out = {}
     g.set_team_sync(False)      # all PE streams are idle here; time the grid, not the stream join/fork events
-    for n_prod, n_cons, n_sig in ((8, 32, 1), (16, 32, 1), (32, 32, 32), (64, 64, 64)):
+    for n_prod, n_cons, n_sig in ((8, 32, 1), (16, 32, 1), (32, 32, 1), (32, 32, 32), (64, 64, 64)):
         best = float("inf")
         for i in range(12):
             for p in range(npes):

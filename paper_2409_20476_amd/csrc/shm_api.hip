@@ -925,7 +925,9 @@ int shm_launch_ring_pipeline(shm_ctx *c, uint64_t src_off, uint64_t slot_off, ui
     if (c->no_device) return no_device("shm_launch_ring_pipeline");
     if (int r = drain_all_engines(c)) return r;
     int per_cu = 0;
-    HIP_TRY(hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, shmk_ring, SHMK_WG, 0));
+    const bool lanes = n_sig > 1 || (n_wg_prod == 1 && n_wg_cons == 1);
+    const auto kernel = lanes ? shmk_ring<1> : shmk_ring<0>;
+    HIP_TRY(hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kernel, SHMK_WG, 0));
     const long long groups = static_cast<long long>(c->npes) * (n_wg_prod + n_wg_cons);
     if (groups > static_cast<long long>(per_cu) * c->num_cu)
         return fail(SHM_EINVAL, "%lld groups cannot all be resident (%d CUs x %d); consumers would wait on groups that never start",
@@ -936,8 +938,8 @@ int shm_launch_ring_pipeline(shm_ctx *c, uint64_t src_off, uint64_t slot_off, ui
     for (int p = 0; p < c->npes; ++p) first = take_slots(c, p, n_chunks);
     if (c->team_sync)
         if (int r = team_join(c)) return r;
-    hipLaunchKernelGGL(shmk_ring, dim3(static_cast<unsigned>(groups)), dim3(SHMK_WG), 0, c->stream[0], dev_view(c), src_off, slot_off,
-                       sig_off, acc_off, chunk_bytes, n_chunks, n_wg_prod, n_wg_cons, c->user_bytes + 8ull * first, n_sig > 1 || (n_wg_prod == 1 && n_wg_cons == 1));
+    hipLaunchKernelGGL(kernel, dim3(static_cast<unsigned>(groups)), dim3(SHMK_WG), 0, c->stream[0], dev_view(c), src_off, slot_off, sig_off,
+                       acc_off, chunk_bytes, n_chunks, n_wg_prod, n_wg_cons, c->user_bytes + 8ull * first);
     if (int r = launched("ring pipeline")) return r;
     if (c->team_sync)
         if (int r = team_fork(c)) return r;

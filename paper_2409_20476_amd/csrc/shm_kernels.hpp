@@ -264,10 +264,14 @@ __global__ __launch_bounds__(SHMK_WG) void shmk_wave_exchange(shm_dev_ctx c, uin
 // in the grid, so consumers cannot starve them.
 #define SHMK_RING_VPT 8      // 16-byte vectors (8 bf16) per consumer thread held in registers
 
+// LANES: one signal word per producer/consumer group pair (compile-time, so that each form carries
+// only its own code and registers: both fit 128 VGPRs, four groups per compute unit).
+template <int LANES>
 __global__ __launch_bounds__(SHMK_WG, 4) void shmk_ring(shm_dev_ctx c, uint64_t src_off, uint64_t slot_off, uint64_t sig_off,
-                                                     uint64_t acc_off, size_t chunk_bytes, int n_chunks, int n_prod, int n_cons,
-                                                     uint64_t arrive_off, int lanes)
+                                                        uint64_t acc_off, size_t chunk_bytes, int n_chunks, int n_prod, int n_cons,
+                                                        uint64_t arrive_off)
 {
+    constexpr bool lanes = LANES != 0;
     const int npes = c.npes;
     const int b = blockIdx.x;
     const size_t nvec = chunk_bytes >> 4;
@@ -276,21 +280,27 @@ __global__ __launch_bounds__(SHMK_WG, 4) void shmk_ring(shm_dev_ctx c, uint64_t 
         const int me = b % npes, part = b / npes;
         int pe = me + 1;
         if (pe >= npes) pe = 0;
-        if (lanes) {
-            // Lane `part`: its own share of every chunk, its own signal word, no arrival counting.
-            // A put_signal per chunk is a chain of two memory latencies (loads, then the stores'
-            // acknowledgements), so the group works as two halves that alternate: while one half
-            // stores chunk k and waits for the acknowledgements, the other half already loads
-            // chunk k+1.  The barrier that ends step k collects the acknowledgements of chunk k,
-            // and only then is signal k sent: the order of a put_signal per chunk, in half the time.
+        const size_t pper = lanes ? per : (nvec + n_prod - 1) / n_prod;     // this producer's share of a chunk, in vectors
+        if (pper <= static_cast<size_t>(SHMK_WG) * SHMK_RING_VPT) {
+            // The share fits the group's registers.  A put_signal per chunk is a chain of two
+            // memory latencies (loads, then the stores' acknowledgements), so the group works as two
+            // halves that alternate: while one half stores chunk k and waits for the
+            // acknowledgements, the other half already loads chunk k+1.  The barrier that ends step
+            // k collects the acknowledgements of chunk k, and only then is chunk k signalled: the
+            // order of a put_signal per chunk, in half the time.  With lanes the group adds 1 to its
+            // own signal word; with one counter per PE it arrives on the chunk's arrival counter and
+            // the group whose arrival completes the chunk adds 1 to the signal (and resets the
+            // counter) -- done by the first thread of the half that loads in this step, whose wait
+            // for the counter's old value overlaps its own loads.
             // Vector indices past the share are clamped to its last vector (that vector is then
             // moved more than once, with the same bytes), which keeps the loop free of predicates.
-            const size_t lo = min(nvec, part * per), hi = min(nvec, lo + per);
+            const size_t lo = min(nvec, part * pper), hi = min(nvec, lo + pper);
             constexpr int HALF = SHMK_WG / 2, J = 2 * SHMK_RING_VPT;      // HALF * J = SHMK_WG * SHMK_RING_VPT vectors
             const int half = threadIdx.x / HALF, t = threadIdx.x % HALF;
             const shm_u32x4 *s = reinterpret_cast<const shm_u32x4 *>(shm_ptr(c, src_off, me));
             shm_u32x4 *d = reinterpret_cast<shm_u32x4 *>(shm_ptr(c, slot_off, pe));
-            uint64_t *sig = reinterpret_cast<uint64_t *>(shm_ptr(c, sig_off + 8ull * part, pe));
+            uint64_t *sig = reinterpret_cast<uint64_t *>(shm_ptr(c, sig_off + (lanes ? 8ull * part : 0ull), pe));
+            uint64_t *arrive = reinterpret_cast<uint64_t *>(shm_ptr(c, arrive_off, me));
             const bool any = hi > lo;
             const uint32_t last = any ? static_cast<uint32_t>(hi - 1 - lo) : 0;      // a share has at most 2048 vectors
             s += lo, d += lo;
@@ -312,10 +322,19 @@ __global__ __launch_bounds__(SHMK_WG, 4) void shmk_ring(shm_dev_ctx c, uint64_t 
                     }
                 }
                 __syncthreads();
-                if (threadIdx.x == 0) __hip_atomic_fetch_add(sig, 1ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                if (lanes) {
+                    if (threadIdx.x == 0) __hip_atomic_fetch_add(sig, 1ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                } else if (static_cast<int>(threadIdx.x) == ((k & 1) ? 0 : HALF)) {
+                    const uint64_t old = __hip_atomic_fetch_add(arrive + k, 1ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    if (old == static_cast<uint64_t>(n_prod) - 1) {
+                        __hip_atomic_store(arrive + k, 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                        __hip_atomic_fetch_add(sig, 1ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    }
+                }
             }
             return;
         }
+        // larger shares: one put_signal per chunk by all producer groups together
         uint64_t *arrive = reinterpret_cast<uint64_t *>(shm_ptr(c, arrive_off, me));
         for (int k = 0; k < n_chunks; ++k)
             shmx_putmem_signal_parts(c, me, slot_off + k * chunk_bytes, src_off + k * chunk_bytes, chunk_bytes, sig_off, 1,

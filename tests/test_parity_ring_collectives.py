@@ -58,13 +58,19 @@ def test_config3_full_size():
 
 
 @pytest.mark.timeout(600)
+def test_config3_full_size_one_counter_pipelined():
+    """One counter per PE with producer shares small enough for the two-half pipeline."""
+    _ring_case(8, 64, 524288, 32, 32, 256 * MiB, reps=2)
+
+
+@pytest.mark.timeout(600)
 def test_config3_full_size_lanes():
     """The same with one signal counter per producer/consumer group pair."""
     _ring_case(8, 64, 524288, 32, 32, 256 * MiB, reps=2, n_sig=32)
 
 
 @pytest.mark.timeout(600)
-@pytest.mark.parametrize("n_prod,n_cons,n_sig", [(16, 16, 16), (4, 16, 1)])
+@pytest.mark.parametrize("n_prod,n_cons,n_sig", [(16, 16, 16), (4, 16, 1), (16, 16, 1), (8, 32, 1)])
 def test_ring_many_rounds_never_reads_a_stale_slot(n_prod, n_cons, n_sig):
     """Ten rounds through the same slots with fresh data each time: a signal seen before its payload
     would leave a previous round's bytes in an accumulator."""
