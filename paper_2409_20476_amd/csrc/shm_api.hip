@@ -645,8 +645,9 @@ int shm_launch_wg_put_timed(shm_ctx *c, int me, int pe, uint64_t dst_off, uint64
     if (!dev_ticks) return fail(SHM_EINVAL, "null tick buffer");
     if (c->no_device) return no_device("shm_launch_wg_put_timed");
     if (int r = drain_engines(c, me)) return r;
-    hipLaunchKernelGGL(shmk_wg_put_timed, dim3(n_wg), dim3(SHMK_WG), 0, c->stream[me], dev_view(c), dst_off, src_off, n, me, pe, reps,
-                       reinterpret_cast<unsigned long long *>(dev_ticks));
+    const bool tiles = use_tiles(dst_off, src_off, n, n_wg);
+    hipLaunchKernelGGL(shmk_wg_put_timed, dim3(n_wg), dim3(SHMK_WG), tiles ? TILES_LDS_BYTES : 0, c->stream[me], dev_view(c), dst_off,
+                       src_off, n, me, pe, reps, reinterpret_cast<unsigned long long *>(dev_ticks), tiles ? 1 : 0);
     return launched("timed work-group put");
 }
 

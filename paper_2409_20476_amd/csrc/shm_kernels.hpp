@@ -40,13 +40,18 @@ __global__ __launch_bounds__(SHMK_WG) void shmk_wg_rma_tiles(shm_dev_ctx c, uint
 // The same put repeated `reps` times inside one kernel, each followed by the group's quiet, with the
 // device clock read before the first and after the last: the cost of a put issued from a running
 // kernel, free of any launch overhead.  ticks[0] = earliest start, ticks[1] = latest end over groups.
+// tiles != 0: long message on group-owned tiles (the launcher's choice, as for an untimed put).
 __global__ __launch_bounds__(SHMK_WG) void shmk_wg_put_timed(shm_dev_ctx c, uint64_t dst_off, uint64_t src_off, size_t n, int me, int pe,
-                                                             int reps, unsigned long long *ticks)
+                                                             int reps, unsigned long long *ticks, int tiles)
 {
-    const bool mine = shm_deal_has_share<8>(n, blockIdx.x, gridDim.x, SHMK_WG);   // groups without a share have nothing to complete
+    // groups without a share have nothing to complete
+    const bool mine = tiles ? blockIdx.x < (n + 65535) / 65536 : shm_deal_has_share<8>(n, blockIdx.x, gridDim.x, SHMK_WG);
     const unsigned long long t0 = wall_clock64();
     for (int r = 0; r < reps; ++r) {
-        shmx_putmem_parts(c, me, dst_off, src_off, n, pe, blockIdx.x, gridDim.x);
+        if (tiles)
+            shmx_putmem_tiles(c, me, dst_off, src_off, n, pe, blockIdx.x, gridDim.x);
+        else
+            shmx_putmem_parts(c, me, dst_off, src_off, n, pe, blockIdx.x, gridDim.x);
         if (mine) shmx_quiet_wg();
     }
     const unsigned long long t1 = wall_clock64();

@@ -131,6 +131,20 @@ def test_timed_put_moves_the_same_bytes_and_reports_device_time():
         assert 0 < us < 1e5, us
 
 
+def test_timed_put_of_a_long_message_uses_tiles_and_moves_the_same_bytes():
+    import torch
+    g, o = make_pair(2, 32 * MiB)
+    with g:
+        fill_random(g, o, 7, upto=28 * MiB)
+        ticks = torch.zeros(2, dtype=torch.int64, device="cuda")
+        ticks[0] = -1
+        n = 9 * MiB + 16 * 3 + 5                  # ragged last tile and a byte tail
+        g.launch_wg_put_timed(0, 1, 14 * MiB + 16, 32, n, 64, 3, ticks)
+        g.quiet(0)
+        o.wg_put(0, 14 * MiB + 16, 32, n, 1, 64)
+        assert_heaps_equal(g, o, upto=28 * MiB)
+
+
 @pytest.mark.parametrize("n_wg", [32, 33, 100, 160])
 def test_long_messages_take_group_owned_tiles(n_wg):
     """8 MiB or more, 32 groups or more, 64 KiB or more per group, 16-byte-aligned offsets: every
