@@ -206,6 +206,14 @@ int shm_launch_rma_device_initiated(shm_ctx *ctx, int me, int pe, uint64_t dst_o
                                     int is_get, int mode, size_t cutover, size_t cover, uint64_t consume_off, int reps,
                                     uint64_t *dev_ticks);
 
+/* Scalar put and get (paper section "Remote Memory Access": the ishmem_long_p example -- address
+ * translation, then one store; g is the matching load).  n_wg groups of 256 work-items on me's
+ * stream; work-item i handles elements i, i + 256 n_wg, ...  is_get 0: element i of me's src_off is
+ * p'ed to pe's dst_off.  is_get 1: element i of pe's src_off is g'ed and stored to me's dst_off.
+ * elem_bytes in {1, 2, 4, 8}; offsets element-aligned.  Delivered after shm_quiet(me). */
+int shm_launch_scalar_pg(shm_ctx *ctx, int me, int pe, uint64_t dst_off, uint64_t src_off, size_t nelems, int elem_bytes, int is_get,
+                         int n_wg);
+
 /* The sub-group forms (paper section "Proposed Device APIs": sub-group extensions; a sub-group is a
  * 64-lane wave here) in one kernel on me's stream.  Wave w of n_waves (1..4096) owns the w-th
  * 16-byte-rounded share of the n-byte message.  Producer waves (PE me): wave put of the share from

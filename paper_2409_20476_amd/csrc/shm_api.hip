@@ -723,6 +723,31 @@ int shm_launch_put_device_initiated(shm_ctx *c, int me, int pe, uint64_t dst_off
                                            dev_ticks);
 }
 
+int shm_launch_scalar_pg(shm_ctx *c, int me, int pe, uint64_t dst_off, uint64_t src_off, size_t nelems, int elem_bytes, int is_get,
+                         int n_wg)
+{
+    if (int r = check_ctx(c)) return r;
+    if (elem_bytes != 1 && elem_bytes != 2 && elem_bytes != 4 && elem_bytes != 8)
+        return fail(SHM_EINVAL, "element size %d is not 1, 2, 4 or 8", elem_bytes);
+    if (nelems > c->user_bytes / static_cast<size_t>(elem_bytes)) return fail(SHM_ERANGE, "the elements leave the heap");
+    if (int r = rma_args(c, me, pe, dst_off, src_off, nelems * elem_bytes)) return r;
+    if ((dst_off | src_off) % static_cast<uint64_t>(elem_bytes)) return fail(SHM_EINVAL, "scalar put/get needs element-aligned offsets");
+    if (int r = check_n_wg(n_wg)) return r;
+    if (c->no_device) return no_device("shm_launch_scalar_pg");
+    if (int r = drain_engines(c, me)) return r;
+    if (nelems == 0) return SHM_OK;
+    const dim3 grid(n_wg), block(SHMK_WG);
+    const shm_dev_ctx d = dev_view(c);
+    const int g = is_get ? 1 : 0;
+    switch (elem_bytes) {
+    case 1: hipLaunchKernelGGL(shmk_scalar_pg<uint8_t>, grid, block, 0, c->stream[me], d, dst_off, src_off, nelems, me, pe, g); break;
+    case 2: hipLaunchKernelGGL(shmk_scalar_pg<uint16_t>, grid, block, 0, c->stream[me], d, dst_off, src_off, nelems, me, pe, g); break;
+    case 4: hipLaunchKernelGGL(shmk_scalar_pg<uint32_t>, grid, block, 0, c->stream[me], d, dst_off, src_off, nelems, me, pe, g); break;
+    default: hipLaunchKernelGGL(shmk_scalar_pg<uint64_t>, grid, block, 0, c->stream[me], d, dst_off, src_off, nelems, me, pe, g); break;
+    }
+    return launched("scalar put/get");
+}
+
 int shm_launch_wave_exchange(shm_ctx *c, int me, int pe, uint64_t dst_off, uint64_t src_off, uint64_t back_off, size_t n, int n_waves,
                              uint64_t flag_off, uint64_t out_off)
 {

@@ -365,6 +365,46 @@ __device__ __forceinline__ void shm_put_parts(char *dst, const char *src, size_t
         shm_copy_parts<U, SHM_ST_STREAM>(dst, src, n, part, nparts);
 }
 
+// Scalar put and get (paper section "Remote Memory Access": the ishmem_long_p example -- translate
+// the symmetric address, then one store).  T is any 1-, 2-, 4- or 8-byte trivially copyable type.
+// p returns at once and is delivered after quiet; the store is write-through so that the quiet is
+// cheap.  g returns the remote element's current value (read at agent scope, past this compute
+// unit's cache).
+template <typename T>
+__device__ __forceinline__ void shm_p(const shm_dev_ctx &c, uint64_t dst_off, T value, int pe)
+{
+    static_assert(sizeof(T) == 1 || sizeof(T) == 2 || sizeof(T) == 4 || sizeof(T) == 8, "scalar put/get moves 1, 2, 4 or 8 bytes");
+    T *d = reinterpret_cast<T *>(shm_ptr(c, dst_off, pe));
+    if constexpr (sizeof(T) == 8) {
+        uint64_t bits;
+        __builtin_memcpy(&bits, &value, 8);
+        __hip_atomic_store(reinterpret_cast<uint64_t *>(d), bits, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    } else if constexpr (sizeof(T) == 4) {
+        uint32_t bits;
+        __builtin_memcpy(&bits, &value, 4);
+        __hip_atomic_store(reinterpret_cast<uint32_t *>(d), bits, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    } else {
+        *d = value;       // sub-word stores have no agent-scope spelling; quiet's release covers them
+    }
+}
+template <typename T>
+__device__ __forceinline__ T shm_g(const shm_dev_ctx &c, uint64_t src_off, int pe)
+{
+    static_assert(sizeof(T) == 1 || sizeof(T) == 2 || sizeof(T) == 4 || sizeof(T) == 8, "scalar put/get moves 1, 2, 4 or 8 bytes");
+    const T *s = reinterpret_cast<const T *>(shm_ptr(c, src_off, pe));
+    T value;
+    if constexpr (sizeof(T) == 8) {
+        const uint64_t bits = __hip_atomic_load(reinterpret_cast<const uint64_t *>(s), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __builtin_memcpy(&value, &bits, 8);
+    } else if constexpr (sizeof(T) == 4) {
+        const uint32_t bits = __hip_atomic_load(reinterpret_cast<const uint32_t *>(s), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __builtin_memcpy(&value, &bits, 4);
+    } else {
+        value = __builtin_nontemporal_load(s);
+    }
+    return value;
+}
+
 // Single-thread forms.  One lane's bandwidth is (bytes in flight) / (memory latency), so U, the
 // number of 16-byte loads issued before the first store, is what a caller with registers to spare
 // can raise (at most 63 loads can be outstanding per wave).

@@ -146,6 +146,22 @@ __global__ __launch_bounds__(64) void shmk_thread_rma(shm_dev_ctx c, uint64_t ds
     }
 }
 
+// Scalar p / g, one element per work-item (grid-stride).  is_get == 0: work-item i reads element i
+// of its own PE's source and p's it to the target PE's destination.  is_get != 0: it g's element i
+// of the target PE's source and stores it to its own PE's destination.
+template <typename T>
+__global__ __launch_bounds__(SHMK_WG) void shmk_scalar_pg(shm_dev_ctx c, uint64_t dst_off, uint64_t src_off, size_t nelems, int me,
+                                                          int pe, int is_get)
+{
+    const size_t step = static_cast<size_t>(gridDim.x) * SHMK_WG;
+    for (size_t i = static_cast<size_t>(blockIdx.x) * SHMK_WG + threadIdx.x; i < nelems; i += step) {
+        if (is_get)
+            reinterpret_cast<T *>(shm_ptr(c, dst_off, me))[i] = shm_g<T>(c, src_off + i * sizeof(T), pe);
+        else
+            shm_p<T>(c, dst_off + i * sizeof(T), reinterpret_cast<const T *>(shm_ptr(c, src_off, me))[i], pe);
+    }
+}
+
 // Strided put/get.  single != 0: one work-item does the whole transfer (ishmem_iput / ishmem_iget);
 // otherwise the gridDim.x groups share the elements (the work-group forms).
 __global__ __launch_bounds__(SHMK_WG) void shmk_strided(shm_dev_ctx c, uint64_t dst_off, uint64_t src_off, size_t dst_stride,

@@ -73,6 +73,7 @@ PROTOTYPES = {
     "shm_launch_put_device_initiated": (c_int, [c_void_p, c_int, c_int, c_uint64, c_uint64, c_size_t, c_int, c_int, c_int, c_size_t, c_int, c_void_p]),
     "shm_launch_rma_device_initiated": (c_int, [c_void_p, c_int, c_int, c_uint64, c_uint64, c_size_t, c_int, c_int, c_int, c_int, c_size_t,
                                                 c_size_t, c_uint64, c_int, c_void_p]),
+    "shm_launch_scalar_pg": (c_int, [c_void_p, c_int, c_int, c_uint64, c_uint64, c_size_t, c_int, c_int, c_int]),
     "shm_launch_wave_exchange": (c_int, [c_void_p, c_int, c_int, c_uint64, c_uint64, c_uint64, c_size_t, c_int, c_uint64, c_uint64]),
     "shm_launch_thread_rma": (c_int, [c_void_p, c_int, c_int, c_uint64, c_uint64, c_size_t, c_int, c_int, c_void_p]),
     "shm_launch_iput": (c_int, [c_void_p, c_int, c_int, c_uint64, c_uint64, c_int64, c_int64, c_size_t, c_int, c_int]),
@@ -274,6 +275,9 @@ class Shm:
                                     consume_off=SHM_NO_CONSUME, reps=1, dev_ticks=None, wg_size=256):
         self._check(self.lib.shm_launch_rma_device_initiated(self.ctx, me, pe, dst_off, src_off, n, n_wg, wg_size, int(is_get), mode,
                                                              cutover, cover, consume_off, reps, _ptr(dev_ticks)))
+
+    def launch_scalar_pg(self, me, pe, dst_off, src_off, nelems, elem_bytes, is_get=False, n_wg=1):
+        self._check(self.lib.shm_launch_scalar_pg(self.ctx, me, pe, dst_off, src_off, nelems, elem_bytes, int(is_get), n_wg))
 
     def launch_wave_exchange(self, me, pe, dst_off, src_off, back_off, n, n_waves, flag_off, out_off):
         self._check(self.lib.shm_launch_wave_exchange(self.ctx, me, pe, dst_off, src_off, back_off, n, n_waves, flag_off, out_off))

@@ -165,6 +165,10 @@ def test_every_entry_point_validates_before_touching_the_device():
     assert code(lambda: g.launch_wave_exchange(0, 1, 4096, 0, 8192, 100, 4, 16388, 20480)) == S.SHM_EINVAL    # flag alignment
     assert code(lambda: g.launch_wave_exchange(0, 1, 4096, 0, 8192, 100, 0, 16384, 20480)) == S.SHM_EINVAL
     assert code(lambda: g.launch_wave_exchange(0, 1, 4096, 0, 8192, 100, 4, H - 8, 20480)) == S.SHM_ERANGE
+    assert code(lambda: g.launch_scalar_pg(0, 1, 4096, 0, 100, 8)) == S.SHM_ENODEV
+    assert code(lambda: g.launch_scalar_pg(0, 1, 4096, 0, 100, 16)) == S.SHM_EINVAL
+    assert code(lambda: g.launch_scalar_pg(0, 1, 4098, 0, 100, 4)) == S.SHM_EINVAL
+    assert code(lambda: g.launch_scalar_pg(0, 1, 4096, 0, H, 8)) == S.SHM_ERANGE
     assert code(lambda: g.launch_thread_rma(0, 1, 4096, 0, 100)) == S.SHM_ENODEV
     assert code(lambda: g.launch_thread_rma(0, 0, 50, 0, 100)) == S.SHM_EINVAL
     assert code(lambda: g.launch_rma_device_initiated(0, 1, 4096, 0, 100, 2, True, 0)) == S.SHM_ENODEV

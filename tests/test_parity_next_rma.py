@@ -181,3 +181,21 @@ def test_tuned_in_kernel_cutover_follows_the_work_items():
             assert_heaps_equal(g, o, upto=20 * MiB, what=f"{wg_size} work-items, {n} bytes")
             assert (g.proxy_stats()[1] > before) == engine, (wg_size, n)
         g.proxy_stop()
+
+
+@pytest.mark.parametrize("elem", [1, 2, 4, 8])
+@pytest.mark.parametrize("is_get", [False, True])
+def test_scalar_p_and_g(elem, is_get):
+    g, o = make_pair(3, 4 * MiB)
+    with g:
+        fill_random(g, o, 69 + elem, upto=3 * MiB)
+        for nelems, n_wg, sa, da in [(1, 1, 0, 0), (1000, 1, 3, 5), (100003, 7, 1, 2), (0, 4, 0, 0), (65536, 64, 0, 0)]:
+            src, dst = 4096 + sa * elem, 2 * MiB + da * elem
+            g.launch_scalar_pg(0, 2, dst, src, nelems, elem, is_get, n_wg)
+            g.quiet(0)
+            (o.getmem if is_get else o.putmem)(0, dst, src, nelems * elem, 2)
+            assert_heaps_equal(g, o, upto=3 * MiB, what=f"{nelems} elements of {elem} bytes")
+        with pytest.raises(S.ShmError):
+            g.launch_scalar_pg(0, 2, 2 * MiB + 1, 4096, 10, 8, is_get, 1)      # misaligned
+        with pytest.raises(S.ShmError):
+            g.launch_scalar_pg(0, 2, 2 * MiB, 4096, 10, 3, is_get, 1)          # element size
