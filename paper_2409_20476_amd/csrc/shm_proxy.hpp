@@ -205,6 +205,10 @@ private:
             const volatile uint32_t *v = slot;
             if (v[3] == tag && v[7] == tag && v[11] == tag && v[15] == tag) {
                 std::atomic_thread_fence(std::memory_order_acquire);
+                // the GPU's store evicted this line from the host's caches, so every new message is a
+                // miss; asking for the slots ahead now overlaps those misses with this message's work
+                __builtin_prefetch(sh_->ring[(tail + 4) & (SHM_OFFLOAD_SLOTS - 1)], 0, 0);
+                __builtin_prefetch(sh_->ring[(tail + 8) & (SHM_OFFLOAD_SLOTS - 1)], 0, 0);
                 uint32_t m[16];
                 memcpy(m, slot, sizeof m);
                 // completion tags count completion-word generations: 1 + (completion index / words)
