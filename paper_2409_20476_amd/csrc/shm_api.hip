@@ -28,8 +28,8 @@ constexpr size_t TILES_MIN_BYTES = 8u << 20;
 constexpr size_t TILES_MIN_BYTES_PER_GROUP = 64u << 10;
 constexpr int TILES_MIN_GROUPS = 32;
 constexpr unsigned TILES_LDS_BYTES = 54000;                   // unused LDS that caps a CU at 3 resident groups
-constexpr uint64_t OFFLOAD_COUNTERS = 32768;                  // offset of the ring's two index words in PE 0's internal tail
-static_assert(ARRIVE_SLOTS * 8 <= OFFLOAD_COUNTERS && OFFLOAD_COUNTERS + 16 <= SHMD_INTERNAL_SYNC_COUNT &&
+constexpr uint64_t OFFLOAD_COUNTERS = 32768;                  // offset of the ring's three index words in PE 0's internal tail
+static_assert(ARRIVE_SLOTS * 8 <= OFFLOAD_COUNTERS && OFFLOAD_COUNTERS + 24 <= SHMD_INTERNAL_SYNC_COUNT &&
                   SHMD_INTERNAL_SYNC_EPOCH + 8 <= SHM_INTERNAL_BYTES, "internal tail layout");
 static_assert(SHM_OFFLOAD_SLOTS == SHMD_OFFLOAD_SLOTS && SHM_OFFLOAD_COMPLETIONS == SHMD_OFFLOAD_COMPLETIONS &&
                   SHM_OFFLOAD_NO_COMPLETION == SHMD_OFFLOAD_NONE, "host and device agree on the ring");
@@ -99,6 +99,7 @@ shm_dev_ctx dev_view(const shm_ctx *c)
         d.off.consumed = const_cast<const uint64_t *>(&c->off_dev->consumed);
         d.off.head = reinterpret_cast<unsigned long long *>(c->base + c->user_bytes + OFFLOAD_COUNTERS);
         d.off.comp_head = d.off.head + 1;
+        d.off.consumed_seen = d.off.head + 2;
     }
     return d;
 }
@@ -666,7 +667,7 @@ int shm_proxy_start(shm_ctx *c)
         c->off_dev = static_cast<shm_offload_shared *>(d);
     }
     memset(c->off_host, 0, sizeof(shm_offload_shared));
-    HIP_TRY(hipMemset(c->base + c->user_bytes + OFFLOAD_COUNTERS, 0, 16));
+    HIP_TRY(hipMemset(c->base + c->user_bytes + OFFLOAD_COUNTERS, 0, 24));
     HIP_TRY(hipDeviceSynchronize());
     c->proxy.start(c->off_host, c->engines.agent(), c->engines.engine_ids(), c->npes);
     return SHM_OK;

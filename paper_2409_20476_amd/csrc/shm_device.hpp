@@ -22,6 +22,7 @@ struct shm_offload_dev {
     const uint64_t *consumed;        // pinned host memory: requests the host has taken (flow control)
     unsigned long long *head;        // device memory: next request index
     unsigned long long *comp_head;   // device memory: next completion index
+    unsigned long long *consumed_seen;   // device memory: the largest `consumed` any sender has read from the host
 };
 
 struct shm_dev_ctx {
@@ -691,10 +692,17 @@ __device__ __forceinline__ uint64_t shm_offload_send(const shm_dev_ctx &c, uint3
             if ((ticket & 0xffffffffull) == SHMD_OFFLOAD_NONE)       // the one value that means "none": take the next
                 ticket = __hip_atomic_fetch_add(c.off.comp_head, 1ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         }
-        // flow control: wait (bounded) only if the ring could be full
-        if (idx >= SHMD_OFFLOAD_SLOTS) {
+        // Flow control, off the critical path: the host's consumed count lives in host memory and
+        // reading it crosses the bus, so senders share the largest value any of them has read in a
+        // device-memory word and go to the host only when, by that word, the ring could be full.
+        if (idx >= SHMD_OFFLOAD_SLOTS &&
+            idx - __hip_atomic_load(c.off.consumed_seen, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) >= SHMD_OFFLOAD_SLOTS) {
             const uint64_t t0 = wall_clock64();
-            while (idx - __hip_atomic_load(c.off.consumed, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM) >= SHMD_OFFLOAD_SLOTS) {
+            for (;;) {
+                const uint64_t seen = __hip_atomic_load(c.off.consumed, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+                __hip_atomic_fetch_max(c.off.consumed_seen, static_cast<unsigned long long>(seen), __ATOMIC_RELAXED,
+                                       __HIP_MEMORY_SCOPE_AGENT);
+                if (idx - seen < SHMD_OFFLOAD_SLOTS) break;
                 if (wall_clock64() - t0 > c.wait_ticks) {
                     __hip_atomic_store(c.status, 1ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
                     break;

@@ -200,27 +200,32 @@ private:
         uint64_t tail = 0;
         uint32_t idle = 0;
         while (!stop_.load(std::memory_order_relaxed)) {
-            const uint32_t *slot = sh_->ring[tail & (SHM_OFFLOAD_SLOTS - 1)];
-            const uint32_t tag = static_cast<uint32_t>(tail / SHM_OFFLOAD_SLOTS) + 1;
-            const volatile uint32_t *v = slot;
-            if (v[3] == tag && v[7] == tag && v[11] == tag && v[15] == tag) {
+            // Look at the next kBatch slots at once: their tag loads are independent, so the cache
+            // misses (the GPU's stores evicted these lines from the host's caches) overlap instead of
+            // being paid one message at a time.  Messages are taken strictly in ring order.
+            bool complete[kBatch];
+            for (unsigned i = 0; i < kBatch; ++i) {
+                const uint64_t at = tail + i;
+                const volatile uint32_t *v = sh_->ring[at & (SHM_OFFLOAD_SLOTS - 1)];
+                const uint32_t tag = static_cast<uint32_t>(at / SHM_OFFLOAD_SLOTS) + 1;
+                complete[i] = v[3] == tag && v[7] == tag && v[11] == tag && v[15] == tag;
+            }
+            unsigned ready = 0;
+            while (ready < kBatch && complete[ready]) ++ready;
+            if (ready) {
                 std::atomic_thread_fence(std::memory_order_acquire);
-                // the GPU's store evicted this line from the host's caches, so every new message is a
-                // miss; asking for the slots ahead now overlaps those misses with this message's work
-                __builtin_prefetch(sh_->ring[(tail + 4) & (SHM_OFFLOAD_SLOTS - 1)], 0, 0);
-                __builtin_prefetch(sh_->ring[(tail + 8) & (SHM_OFFLOAD_SLOTS - 1)], 0, 0);
-                uint32_t m[16];
-                memcpy(m, slot, sizeof m);
-                // completion tags count completion-word generations: 1 + (completion index / words)
-                handle(m, m[2] == SHM_OFFLOAD_NO_COMPLETION ? 0u : (m[2] / SHM_OFFLOAD_COMPLETIONS) + 1u);
-                ++tail;
-                if ((tail & 63) == 0) sh_->consumed = tail;     // flow control, off the critical path
-                idle = 0;
-            } else {
-                if (++idle == 64) {
-                    sh_->consumed = tail;
-                    idle = 0;
+                for (unsigned i = 0; i < ready; ++i) {
+                    uint32_t m[16];
+                    memcpy(m, sh_->ring[tail & (SHM_OFFLOAD_SLOTS - 1)], sizeof m);
+                    // completion tags count completion-word generations: 1 + (completion index / words)
+                    handle(m, m[2] == SHM_OFFLOAD_NO_COMPLETION ? 0u : (m[2] / SHM_OFFLOAD_COMPLETIONS) + 1u);
+                    ++tail;
+                    if ((tail & 63) == 0) sh_->consumed = tail;     // flow control, off the critical path
                 }
+                idle = 0;
+            } else if (++idle == 64) {
+                sh_->consumed = tail;
+                idle = 0;
             }
             if (!copies_in_flight_.empty() || !quiets_.empty()) retire_copies();
         }
@@ -234,6 +239,7 @@ private:
     hsa_agent_t agent_{};
     std::vector<uint32_t> engines_;
     std::vector<uint32_t> in_flight_per_pe_;
+    static constexpr unsigned kBatch = 8;              // ring slots examined per poll
     static constexpr size_t kMinPiece = 4u << 20;      // do not split below 4 MiB per engine
     static constexpr size_t kMaxPieces = 8;
 
