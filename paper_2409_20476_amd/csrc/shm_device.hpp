@@ -935,26 +935,33 @@ __device__ __forceinline__ void shmx_iget_parts(const shm_dev_ctx &c, int me, ui
 __device__ __forceinline__ void shmx_sync_all_wg(const shm_dev_ctx &c, int me)
 {
     __syncthreads();
-    if (threadIdx.x == 0 && c.npes > 1) {
-        uint64_t *epoch = reinterpret_cast<uint64_t *>(shm_ptr(c, c.internal_off + SHMD_INTERNAL_SYNC_EPOCH, me));
-        const uint64_t e = __hip_atomic_load(epoch, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) + 1;
-        for (int j = 1; j < c.npes; ++j) {
+    if (threadIdx.x < 64 && c.npes > 1) {
+        // lanes 1..npes-1 of the first wave: one increment each, to the other PEs, all in one instruction
+        const int j = static_cast<int>(threadIdx.x);
+        if (j >= 1 && j < c.npes) {
             int q = me + j;
             if (q >= c.npes) q -= c.npes;
             (void)__hip_atomic_fetch_add(reinterpret_cast<uint64_t *>(shm_ptr(c, c.internal_off + SHMD_INTERNAL_SYNC_COUNT, q)), 1ull,
                                          __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         }
-        const uint64_t *mine = reinterpret_cast<const uint64_t *>(shm_ptr(c, c.internal_off + SHMD_INTERNAL_SYNC_COUNT, me));
-        const uint64_t want = e * static_cast<uint64_t>(c.npes - 1);
-        const uint64_t t0 = wall_clock64();
-        while (__hip_atomic_load(mine, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < want) {
-            if (wall_clock64() - t0 > c.wait_ticks) {
-                __hip_atomic_store(c.status, 1ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
-                break;
+        if (j == 0) {
+            // the number of completed syncs and the first look at the own counter travel together
+            uint64_t *epoch = reinterpret_cast<uint64_t *>(shm_ptr(c, c.internal_off + SHMD_INTERNAL_SYNC_EPOCH, me));
+            const uint64_t *mine = reinterpret_cast<const uint64_t *>(shm_ptr(c, c.internal_off + SHMD_INTERNAL_SYNC_COUNT, me));
+            uint64_t cur = __hip_atomic_load(mine, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            const uint64_t e = __hip_atomic_load(epoch, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) + 1;
+            const uint64_t want = e * static_cast<uint64_t>(c.npes - 1);
+            const uint64_t t0 = wall_clock64();
+            while (cur < want) {
+                if (wall_clock64() - t0 > c.wait_ticks) {
+                    __hip_atomic_store(c.status, 1ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+                    break;
+                }
+                __builtin_amdgcn_s_sleep(1);
+                cur = __hip_atomic_load(mine, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             }
-            __builtin_amdgcn_s_sleep(1);
+            __hip_atomic_store(epoch, e, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         }
-        __hip_atomic_store(epoch, e, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
     __syncthreads();
 }
