@@ -359,6 +359,26 @@ class ShmemOracle:
             for p in range(self.npes):
                 self.heap[q][dst + p * n:dst + (p + 1) * n] = blocks[p]
 
+    def collect(self, dst: int, src: int, nbytes: list) -> None:
+        """Concatenation with a different block size per PE (paper section "Collective Operations":
+        push broadcast / collect / fcollect; OpenSHMEM collect): PE p contributes ``nbytes[p]``
+        bytes from ``src``; every PE's destination receives the blocks in PE order, block p at the
+        sum of the sizes before it."""
+        if len(nbytes) != self.npes or any(n < 0 for n in nbytes):
+            raise OracleError("one non-negative size per PE")
+        total = sum(nbytes)
+        self._range(dst, total)
+        for p in range(self.npes):
+            self._range(src, nbytes[p])
+            if nbytes[p] and total and src < dst + total and dst < src + nbytes[p]:
+                raise OracleError("overlapping source and destination")
+        blocks = [self.heap[p][src:src + nbytes[p]].copy() for p in range(self.npes)]
+        for q in range(self.npes):
+            at = dst
+            for p in range(self.npes):
+                self.heap[q][at:at + nbytes[p]] = blocks[p]
+                at += nbytes[p]
+
     def wave_exchange(self, me: int, pe: int, dst: int, src: int, back: int, n: int, n_waves: int, flag: int,
                       out: int) -> None:
         """The sub-group (wave) forms in one program (paper section "Proposed Device APIs": the

@@ -239,3 +239,24 @@ def test_wave_exchange_is_put_flag_wait_get_per_slice():
             touched[a:a + m] = True
         assert np.array_equal(o.heap[1][~touched], before[1][~touched])
         assert np.array_equal(o.heap[0], before[0]) and np.array_equal(o.heap[2], before[2])
+
+
+def test_collect_is_concatenate_of_unequal_blocks_and_reduces_to_fcollect():
+    o = ShmemOracle(4, 1 << 14)
+    _fill(o, 11)
+    before = [h.copy() for h in o.heap]
+    sizes = [100, 0, 37, 1]
+    o.collect(4096, 64, sizes)
+    want = np.concatenate([before[p][64:64 + sizes[p]] for p in range(4)])
+    for q in range(4):
+        assert np.array_equal(o.heap[q][4096:4096 + 138], want)
+        assert np.array_equal(o.heap[q][:4096], before[q][:4096]) and np.array_equal(o.heap[q][4096 + 138:], before[q][4096 + 138:])
+    # equal sizes: exactly fcollect
+    a, b = ShmemOracle(3, 8192), ShmemOracle(3, 8192)
+    _fill(a, 12), _fill(b, 12)
+    a.collect(4096, 0, [200] * 3), b.fcollect(4096, 0, 200)
+    assert all(np.array_equal(x, y) for x, y in zip(a.heap, b.heap))
+    for bad in (lambda: o.collect(4096, 64, [1, 2, 3]), lambda: o.collect(4096, 64, [1, 2, 3, -1]),
+                lambda: o.collect(100, 64, [100, 0, 0, 0]), lambda: o.collect(16000, 64, [200, 200, 0, 0])):
+        with pytest.raises(OracleError):
+            bad()
