@@ -305,6 +305,13 @@ int shm_launch_amo_storm(shm_ctx *ctx, uint64_t ctr_off, int n_ctr, const uint16
  * MEMCPY: npes*npes copies.  AUTO uses the cutover of n_wg on bytes_per_pe. */
 int shm_launch_fcollect(shm_ctx *ctx, uint64_t dst_off, uint64_t src_off, size_t bytes_per_pe, int n_wg, int path);
 
+/* collect (paper section "Collective Operations": push broadcast / collect / fcollect; OpenSHMEM
+ * collect): PE p contributes nbytes_per_pe[p] bytes from src_off (host array of npes sizes, read
+ * during the call); every PE's dst_off receives the blocks in PE order, block p at the sum of the
+ * sizes before it.  Push by loads/stores, n_wg groups per PE.  SHM_ERANGE if the concatenation or
+ * the largest source block leaves the heap, SHM_EINVAL on overlap. */
+int shm_launch_collect(shm_ctx *ctx, uint64_t dst_off, uint64_t src_off, const size_t *nbytes_per_pe, int n_wg);
+
 /* The reduction matrix (paper section "Collective Operations", reduction paragraph): min, max, sum,
  * product, and, or, xor over 8..64-bit integers; min, max, sum, product over float and double
  * (and/or/xor with a floating type: SHM_EINVAL).  Element i of every PE's dst_off becomes

@@ -1061,6 +1061,37 @@ int shm_launch_fcollect(shm_ctx *c, uint64_t dst_off, uint64_t src_off, size_t b
     return SHM_OK;
 }
 
+int shm_launch_collect(shm_ctx *c, uint64_t dst_off, uint64_t src_off, const size_t *nbytes_per_pe, int n_wg)
+{
+    if (int r = check_ctx(c)) return r;
+    if (!nbytes_per_pe) return fail(SHM_EINVAL, "null size array");
+    shmk_collect_table t;
+    memset(&t, 0, sizeof t);
+    size_t total = 0, largest = 0;
+    for (int p = 0; p < c->npes; ++p) {
+        if (nbytes_per_pe[p] > c->user_bytes - total) return fail(SHM_ERANGE, "the concatenation leaves the heap");
+        t.at[p] = total;
+        t.nbytes[p] = nbytes_per_pe[p];
+        total += nbytes_per_pe[p];
+        if (nbytes_per_pe[p] > largest) largest = nbytes_per_pe[p];
+    }
+    if (int r = check_range(c, dst_off, total, "destination")) return r;
+    if (int r = check_range(c, src_off, largest, "source")) return r;
+    if (total && largest && src_off < dst_off + total && dst_off < src_off + largest)
+        return fail(SHM_EINVAL, "source and destination overlap");
+    if (int r = check_n_wg(n_wg)) return r;
+    if (c->no_device) return no_device("shm_launch_collect");
+    if (int r = drain_all_engines(c)) return r;
+    if (total == 0) return SHM_OK;
+    if (c->team_sync)
+        if (int r = team_join(c)) return r;
+    hipLaunchKernelGGL(shmk_collect, dim3(n_wg, c->npes), dim3(SHMK_WG), 0, c->stream[0], dev_view(c), dst_off, src_off, t);
+    if (int r = launched("collect")) return r;
+    if (c->team_sync)
+        if (int r = team_fork(c)) return r;
+    return SHM_OK;
+}
+
 int shm_launch_reduce(shm_ctx *c, uint64_t dst_off, uint64_t src_off, size_t nelems, int dtype, int op, int n_wg, int algo)
 {
     if (int r = check_ctx(c)) return r;

@@ -566,6 +566,23 @@ __global__ __launch_bounds__(SHMK_WG) void shmk_fcollect_any(shm_dev_ctx c, uint
     }
 }
 
+// collect: as fcollect with a block size per PE; the launcher passes every PE's size and the offset
+// of its block in the destination (exclusive prefix sum of the sizes).
+struct shmk_collect_table {
+    uint64_t at[SHM_MAX_PES];        // destination offset of PE p's block, relative to dst_off
+    uint64_t nbytes[SHM_MAX_PES];
+};
+
+__global__ __launch_bounds__(SHMK_WG) void shmk_collect(shm_dev_ctx c, uint64_t dst_off, uint64_t src_off, shmk_collect_table t)
+{
+    const int p = blockIdx.y, npes = c.npes;
+    for (int j = 0; j < npes; ++j) {
+        int q = p + 1 + j;
+        if (q >= npes) q -= npes;
+        shmx_putmem_parts(c, p, dst_off + t.at[p], src_off, t.nbytes[p], q, blockIdx.x, gridDim.x);
+    }
+}
+
 // Team grids (n_wg, npes) whose npes groups with the same blockIdx.x read the SAME source bytes
 // (the duplicate reduction): groups go to the 8 XCDs round-robin in linear order and each XCD has
 // its own L2, so the npes readers of one share are renumbered to be consecutive groups of one XCD

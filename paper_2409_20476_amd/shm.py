@@ -86,6 +86,7 @@ PROTOTYPES = {
     "shm_launch_ring_pipeline": (c_int, [c_void_p, c_uint64, c_uint64, c_uint64, c_uint64, c_size_t, c_int, c_int, c_int, c_int]),
     "shm_launch_amo_storm": (c_int, [c_void_p, c_uint64, c_int, c_void_p, c_uint64, c_int, c_int, c_void_p, c_void_p]),
     "shm_launch_fcollect": (c_int, [c_void_p, c_uint64, c_uint64, c_size_t, c_int, c_int]),
+    "shm_launch_collect": (c_int, [c_void_p, c_uint64, c_uint64, POINTER(c_size_t), c_int]),
     "shm_launch_reduce": (c_int, [c_void_p, c_uint64, c_uint64, c_size_t, c_int, c_int, c_int, c_int]),
     "shm_launch_broadcast": (c_int, [c_void_p, c_uint64, c_uint64, c_size_t, c_int, c_int, c_int]),
     "shm_launch_sync_all": (c_int, [c_void_p, c_int, c_int, c_void_p]),
@@ -317,6 +318,12 @@ class Shm:
 
     def launch_fcollect(self, dst_off, src_off, bytes_per_pe, n_wg=64, path=SHM_PATH_LDST):
         self._check(self.lib.shm_launch_fcollect(self.ctx, dst_off, src_off, bytes_per_pe, n_wg, path))
+
+    def launch_collect(self, dst_off, src_off, nbytes_per_pe, n_wg=8):
+        sizes = (c_size_t * len(nbytes_per_pe))(*nbytes_per_pe)
+        if len(nbytes_per_pe) != self.n_pes():
+            raise ValueError("one size per PE")
+        self._check(self.lib.shm_launch_collect(self.ctx, dst_off, src_off, sizes, n_wg))
 
     def launch_reduce(self, dst_off, src_off, nelems, dtype, op, n_wg=64, algo=SHM_REDUCE_DUPLICATE):
         self._check(self.lib.shm_launch_reduce(self.ctx, dst_off, src_off, nelems, dtype, op, n_wg, algo))

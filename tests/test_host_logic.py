@@ -176,6 +176,9 @@ def test_every_entry_point_validates_before_touching_the_device():
     assert code(lambda: g.launch_rma_device_initiated(0, 1, 4096, 0, 100, 2, False, 0, consume_off=8192)) == S.SHM_EINVAL
     assert code(lambda: g.launch_rma_device_initiated(0, 1, 4096, 0, 100, 2, True, 0, consume_off=4100)) == S.SHM_EINVAL
     assert code(lambda: g.launch_rma_device_initiated(0, 1, 4096, 0, 100, 2, True, 0, consume_off=H - 10)) == S.SHM_ERANGE
+    assert code(lambda: g.launch_collect(65536, 0, [100, 0, 5, 7], 2)) == S.SHM_ENODEV
+    assert code(lambda: g.launch_collect(50, 0, [100, 0, 5, 7], 2)) == S.SHM_EINVAL                             # overlap
+    assert code(lambda: g.launch_collect(65536, 0, [H, 1, 0, 0], 2)) == S.SHM_ERANGE
     # the reduction matrix
     assert code(lambda: g.launch_reduce(65536, 0, 1000, S.SHM_INT16, S.SHM_OP_XOR, 2)) == S.SHM_ENODEV
     assert code(lambda: g.launch_reduce(65536, 0, 1000, S.SHM_FLOAT64, S.SHM_OP_PROD, 2)) == S.SHM_ENODEV

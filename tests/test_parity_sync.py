@@ -50,3 +50,19 @@ def test_broadcast(path, npes, n, root, n_wg, soff, doff):
         g.barrier_all()
         o.broadcast(dst, src, n, root)
         assert_heaps_equal(g, o, upto=12 * MiB)
+
+
+@pytest.mark.parametrize("npes,sizes,n_wg,soff,doff", [
+    (4, [100003, 0, 37, 1], 4, 5, 9), (8, [4096 * (p + 1) for p in range(8)], 16, 0, 0), (3, [0, 0, 0], 2, 0, 0),
+    (5, [MiB + 3, 17, MiB // 2, 0, 65536], 64, 16, 32), (1, [1000], 1, 1, 2)])
+def test_collect(npes, sizes, n_wg, soff, doff):
+    g, o = make_pair(npes, 16 * MiB)
+    with g:
+        fill_random(g, o, 43, upto=12 * MiB)
+        src, dst = 1024 + soff, 6 * MiB + doff
+        g.launch_collect(dst, src, sizes, n_wg)
+        g.barrier_all()
+        o.collect(dst, src, sizes)
+        assert_heaps_equal(g, o, upto=12 * MiB)
+        with pytest.raises(S.ShmError):
+            g.launch_collect(dst, src, [16 * MiB] + [0] * (npes - 1), n_wg)
