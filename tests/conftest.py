@@ -8,3 +8,12 @@ if ROOT not in sys.path:
 
 def pytest_configure(config):
     config.addinivalue_line("markers", "gpu: needs a real MI355X (run with -m gpu)")
+
+
+def pytest_sessionstart(session):
+    """The tests load the in-tree library; it is compiled here only if nothing has been built yet
+    (hipcc cross-compiles for gfx950 without a GPU)."""
+    lib = os.path.join(ROOT, "paper_2409_20476_amd", "libshm355.so")
+    if not os.path.exists(lib):
+        from paper_2409_20476_amd import build
+        build.build()
