@@ -425,7 +425,7 @@ int shm_init_ex(int npes, size_t heap_bytes, void *heap_base, void *const *strea
     }
     for (int p = 0; p < npes; ++p) INIT_TRY(hipEventCreateWithFlags(&c->event[p], hipEventDisableTiming));
     void *st = nullptr;
-    INIT_TRY(hipHostMalloc(&st, 64, hipHostMallocMapped));
+    INIT_TRY(hipHostMalloc(&st, 64, hipHostMallocMapped | hipHostMallocCoherent));
     c->status_host = static_cast<uint64_t *>(st);
     *c->status_host = 0;
     void *st_dev = nullptr;
@@ -661,7 +661,7 @@ int shm_proxy_start(shm_ctx *c)
     for (int p = 0; p < c->npes; ++p) HIP_TRY(hipStreamSynchronize(c->stream[p]));
     if (!c->off_host) {
         void *h = nullptr, *d = nullptr;
-        HIP_TRY(hipHostMalloc(&h, sizeof(shm_offload_shared), hipHostMallocMapped));
+        HIP_TRY(hipHostMalloc(&h, sizeof(shm_offload_shared), hipHostMallocMapped | hipHostMallocCoherent));
         c->off_host = static_cast<shm_offload_shared *>(h);
         HIP_TRY(hipHostGetDevicePointer(&d, h, 0));
         c->off_dev = static_cast<shm_offload_shared *>(d);
