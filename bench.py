@@ -208,14 +208,16 @@ def put_sweep(torch, S, g, args):
         row["team_wg1024_event_us"], row["team_wg1024_event_gbs"] = ms * 1e3, npes * n / ms / 1e6
     g.set_team_sync(True)
 
-    def crossover(ld_key):
+    def crossover(faster):
         for i, row in enumerate(rows):
-            if all(r["sdma_us"] <= r[ld_key] for r in rows[i:]):
+            if all(faster(r) for r in rows[i:]):
                 return row["bytes"]
         return None
 
-    cross_dev = {str(w): crossover(f"ldst_wg{w}_us") for w in wgs}
-    cross_host = {str(w): crossover(f"ldst_wg{w}_host_us") for w in wgs}
+    # all 8 PEs transfer at once: compare what they move together per second, either way
+    cross_dev = {str(w): crossover(lambda r, w=w: r["sdma_gbs"] >= r[f"ldst_wg{w}_gbs"]) for w in wgs}
+    cross_one = {str(w): crossover(lambda r, w=w: r["sdma_us"] <= r[f"ldst_wg{w}_us"]) for w in wgs}
+    cross_host = {str(w): crossover(lambda r, w=w: r["sdma_us"] <= r[f"ldst_wg{w}_host_us"]) for w in wgs}
     for w in wgs:
         c = cross_dev[str(w)]
         g.set_cutover(w, c if c is not None else (1 << 64) - 1)
@@ -228,10 +230,14 @@ def put_sweep(torch, S, g, args):
                       "the first PE's start to the last PE's end); ldst_wgK_host_us, sdma_us, memcpy_us: host "
                       "clock from first enqueue to completion on all PEs, warm-up doubling to >2 ms then best of 10; "
                       "team_wg1024_event_us: HIP events around one grid for all PEs; gbs = payload of all 8 PEs",
-            "rows": rows, "crossover_bytes": cross_dev, "crossover_bytes_host_launched": cross_host, "auto_path": auto,
-            "crossover_note": "smallest message from which an SDMA copy-engine transfer (host submit to completion) stays at "
-                              "least as fast as the put done with loads/stores by that many work-groups per PE; the first table "
-                              "compares against the in-kernel put time, the second against a host-launched put kernel; "
+            "rows": rows, "crossover_bytes": cross_dev, "crossover_bytes_one_pe_kernel_time": cross_one,
+            "crossover_bytes_host_launched": cross_host, "auto_path": auto,
+            "crossover_note": "smallest message from which the SDMA copy engines stay at least as fast as loads/stores by that "
+                              "many work-groups per PE, all 8 PEs transferring at once. crossover_bytes compares the bytes all "
+                              "PEs move per second (SDMA: host submit to completion of all; loads/stores: first kernel start "
+                              "to last kernel end on the device -- with 8 streams on 4 hardware queues the put kernels run in "
+                              "two rounds, which the engines do not); _one_pe_kernel_time compares the engines' completion "
+                              "time with ONE PE's in-kernel put time; _host_launched with host-launched put kernels. "
                               "null = loads/stores win at every measured size"}
 
 

@@ -60,11 +60,19 @@ public:
     hsa_agent_t agent() const { return agent_; }
     const std::vector<uint32_t> &engine_ids() const { return engines_; }
 
-    // Start copying n bytes on behalf of PE `pe` of `npes`.  Large transfers are split over the
-    // engines that PE's share of the engine set allows.
+    // Start copying n bytes on behalf of PE `pe`.  Large transfers are cut into pieces of at least
+    // kMinPiece bytes that run on several engines: as many as an equal share of the engines among
+    // the PEs that have transfers in flight right now (this one included) allows, so that one PE
+    // alone can use every engine and many PEs together still keep all of them busy.  Pieces go to
+    // the engines round-robin over all transfers.
     bool submit(void *dst, const void *src, size_t n, int pe, int npes, std::string &err)
     {
-        const size_t share = engines_.size() / static_cast<size_t>(npes) ? engines_.size() / npes : 1;
+        (void)npes;
+        size_t active = 1;
+        for (size_t p = 0; p < pending_.size(); ++p)
+            if (static_cast<int>(p) != pe && !pending_[p].empty()) ++active;
+        size_t share = (engines_.size() + active - 1) / active;
+        if (share < 1) share = 1;
         size_t pieces = n / kMinPiece;
         if (pieces < 1) pieces = 1;
         if (pieces > share) pieces = share;
@@ -76,7 +84,7 @@ public:
                 err = "hsa_signal_create failed";
                 return false;
             }
-            const uint32_t eng = engines_[(static_cast<size_t>(pe) * share + i) % engines_.size()];
+            const uint32_t eng = engines_[next_engine_++ % engines_.size()];
             const hsa_status_t rc = hsa_amd_memory_async_copy_on_engine(
                 static_cast<char *>(dst) + off, agent_, static_cast<const char *>(src) + off, agent_, len, 0, nullptr, sig,
                 static_cast<hsa_amd_sdma_engine_id_t>(eng), true);
@@ -176,6 +184,7 @@ private:
     }
 
     bool inited_ = false, ready_ = false;
+    size_t next_engine_ = 0;
     hsa_agent_t agent_{};
     std::vector<uint32_t> engines_;
     std::vector<hsa_signal_t> free_;
