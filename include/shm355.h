@@ -200,7 +200,7 @@ int shm_launch_put_device_initiated(shm_ctx *ctx, int me, int pe, uint64_t dst_o
  * kernel itself reads after a get.  dev_ticks may be NULL. */
 #define SHM_NO_CONSUME UINT64_MAX
 /* As `cutover` of mode 2: the threshold measured on MI355X for one work-group of wg_size work-items
- * (16 KiB for 1, 256 KiB up to 16, 2 MiB up to 64, 4 MiB beyond). */
+ * (16 KiB for 1, 256 KiB up to 16, 1 MiB up to 64, 2 MiB beyond). */
 #define SHM_CUTOVER_TUNED (SIZE_MAX - 1)
 int shm_launch_rma_device_initiated(shm_ctx *ctx, int me, int pe, uint64_t dst_off, uint64_t src_off, size_t n, int n_wg, int wg_size,
                                     int is_get, int mode, size_t cutover, size_t cover, uint64_t consume_off, int reps,

@@ -801,8 +801,8 @@ __device__ __forceinline__ void shmx_quiet_offload_wg(const shm_dev_ctx &c, int 
 #define SHMD_CUTOVER_TUNED (~static_cast<size_t>(1))
 __device__ __forceinline__ size_t shm_tuned_cutover(unsigned work_items)
 {
-    return work_items <= 1 ? (size_t(16) << 10) : work_items <= 16 ? (size_t(256) << 10) : work_items <= 64 ? (size_t(2) << 20)
-                                                                                                             : (size_t(4) << 20);
+    return work_items <= 1 ? (size_t(16) << 10) : work_items <= 16 ? (size_t(256) << 10) : work_items <= 64 ? (size_t(1) << 20)
+                                                                                                             : (size_t(2) << 20);
 }
 __device__ __forceinline__ size_t shm_resolve_cutover(size_t cutover)
 {

@@ -172,8 +172,8 @@ def test_tuned_in_kernel_cutover_follows_the_work_items():
     with g:
         fill_random(g, o, 68, upto=20 * MiB)
         g.proxy_start()
-        for wg_size, n, engine in [(64, 2 * MiB - 256, False), (64, 2 * MiB, True), (256, 2 * MiB, False), (256, 4 * MiB, True),
-                                   (1024, 4 * MiB - 256, False), (1024, 4 * MiB + 100, True)]:
+        for wg_size, n, engine in [(64, MiB - 256, False), (64, MiB, True), (256, MiB, False), (256, 2 * MiB, True),
+                                   (1024, 2 * MiB - 256, False), (1024, 2 * MiB + 100, True)]:
             before = g.proxy_stats()[1]
             g.launch_rma_device_initiated(0, 1, 8 * MiB + 16, 4096, n, 1, False, 2, cutover=S.SHM_CUTOVER_TUNED, wg_size=wg_size)
             g.quiet(0)
