@@ -782,7 +782,28 @@ __global__ __launch_bounds__(SHMK_WG) void shmk_reduce(shm_dev_ctx c, uint64_t d
     const size_t lo = min(vhi, vlo + part * per), hi = min(vhi, lo + per);
     // duplicate: the other PEs' groups on this XCD read the same vectors, so they are kept in L2
     auto load = [&](const shm_u32x4 *a) { return split ? shm_ld16(a) : *a; };
-    for (size_t i = lo + threadIdx.x; i < hi; i += SHMK_WG) {
+    // two vectors per thread and pass (the second one a group's width further on), so that twice as
+    // many loads are in flight; then whatever is left, one vector per thread
+    size_t i = lo + threadIdx.x;
+    for (; i + SHMK_WG < hi; i += 2 * SHMK_WG) {
+        vec r0, r1;
+        r0.v = load(reinterpret_cast<const shm_u32x4 *>(shm_ptr(c, src_off, 0)) + i);
+        r1.v = load(reinterpret_cast<const shm_u32x4 *>(shm_ptr(c, src_off, 0)) + i + SHMK_WG);
+        for (int p = 1; p < npes; ++p) {
+            vec x0, x1;
+            x0.v = load(reinterpret_cast<const shm_u32x4 *>(shm_ptr(c, src_off, p)) + i);
+            x1.v = load(reinterpret_cast<const shm_u32x4 *>(shm_ptr(c, src_off, p)) + i + SHMK_WG);
+#pragma unroll
+            for (int k = 0; k < EPV; ++k) r0.e[k] = shmk_combine<T, OP>(r0.e[k], x0.e[k]);
+#pragma unroll
+            for (int k = 0; k < EPV; ++k) r1.e[k] = shmk_combine<T, OP>(r1.e[k], x1.e[k]);
+        }
+        for (int d = d0; d < d1; ++d) {
+            shm_st16(reinterpret_cast<shm_u32x4 *>(shm_ptr(c, dst_off, d)) + i, r0.v);
+            shm_st16(reinterpret_cast<shm_u32x4 *>(shm_ptr(c, dst_off, d)) + i + SHMK_WG, r1.v);
+        }
+    }
+    for (; i < hi; i += SHMK_WG) {
         vec r;
         r.v = load(reinterpret_cast<const shm_u32x4 *>(shm_ptr(c, src_off, 0)) + i);
         for (int p = 1; p < npes; ++p) {
@@ -794,10 +815,10 @@ __global__ __launch_bounds__(SHMK_WG) void shmk_reduce(shm_dev_ctx c, uint64_t d
         for (int d = d0; d < d1; ++d) shm_st16(reinterpret_cast<shm_u32x4 *>(shm_ptr(c, dst_off, d)) + i, r.v);
     }
     // the last nelems mod EPV elements, one thread each
-    const size_t i = nvec * EPV + threadIdx.x;
-    if (part == 0 && (!split || q == 0) && i < nelems) {
-        T r = reinterpret_cast<const T *>(shm_ptr(c, src_off, 0))[i];
-        for (int p = 1; p < npes; ++p) r = shmk_combine<T, OP>(r, reinterpret_cast<const T *>(shm_ptr(c, src_off, p))[i]);
-        for (int d = d0; d < d1; ++d) reinterpret_cast<T *>(shm_ptr(c, dst_off, d))[i] = r;
+    const size_t t = nvec * EPV + threadIdx.x;
+    if (part == 0 && (!split || q == 0) && t < nelems) {
+        T r = reinterpret_cast<const T *>(shm_ptr(c, src_off, 0))[t];
+        for (int p = 1; p < npes; ++p) r = shmk_combine<T, OP>(r, reinterpret_cast<const T *>(shm_ptr(c, src_off, p))[t]);
+        for (int d = d0; d < d1; ++d) reinterpret_cast<T *>(shm_ptr(c, dst_off, d))[t] = r;
     }
 }
