@@ -103,3 +103,26 @@ def test_offload_needs_the_proxy():
             g.launch_offload_nop(0, 1, 1, True, t)
         g.launch_put_device_initiated(0, 1, 65536, 0, 4096, 1, 0, 0, 1, t)     # loads/stores need no proxy
         g.quiet(0)
+
+
+def test_device_initiated_put_random_sizes_and_alignments():
+    """Many small and medium in-kernel puts (the write-through store path up to 64 bytes per thread,
+    the streaming path beyond) at random sizes, alignments, group sizes and group counts."""
+    g, o = make_pair(2, 4 * MiB)
+    rng = np.random.default_rng(33)
+    with g:
+        fill_random(g, o, 33, upto=3 * MiB)
+        t = _ticks()
+        for i in range(150):
+            wg_size = int(rng.choice([1, 7, 64, 128, 192, 256, 512, 1024]))
+            n_wg = int(rng.choice([1, 2, 3, 8]))
+            n = int(rng.integers(0, 70000)) if i % 3 else int(rng.integers(0, 300))
+            sa, da = int(rng.integers(0, 48)), int(rng.integers(0, 48))
+            me = i & 1
+            g.launch_put_device_initiated(me, 1 - me, 2 * MiB + da, 1024 + sa, n, n_wg, 0, 0, 1, t, wg_size=wg_size)
+            o.wg_put(me, 2 * MiB + da, 1024 + sa, n, 1 - me, n_wg)
+            if i % 10 == 9:
+                g.barrier_all()
+                assert_heaps_equal(g, o, upto=3 * MiB, what=f"after case {i} (wg_size {wg_size}, n_wg {n_wg}, n {n}, src+{sa}, dst+{da})")
+        g.barrier_all()
+        assert_heaps_equal(g, o, upto=3 * MiB, what="end")
