@@ -39,6 +39,30 @@ def test_put_signal_then_wait_sees_data(n_wg):
             assert_heaps_equal(g, o, what=f"case {i}")
 
 
+def test_put_signal_random_sizes_alignments_and_group_counts():
+    """The write-through payload path of put_signal (aligned and re-aligned forms, head and tail
+    bytes, arrival counting by several groups) at random sizes and alignments."""
+    g, o = make_pair(2, 4 * MiB)
+    rng = np.random.default_rng(34)
+    with g:
+        fill_random(g, o, 34, upto=3 * MiB)
+        sig = 3 * MiB - 64
+        write_both(g, o, 0, sig, np.zeros(8, np.uint8)), write_both(g, o, 1, sig, np.zeros(8, np.uint8))
+        for i in range(120):
+            n_wg = int(rng.choice([1, 2, 3, 5, 8, 64]))
+            n = int(rng.integers(0, 200000)) if i % 3 else int(rng.integers(0, 200))
+            sa, da = int(rng.integers(0, 48)), int(rng.integers(0, 48))
+            me = i & 1
+            op, val = (SIGNAL_ADD, 3) if i % 4 else (SIGNAL_SET, 1000 + i)
+            g.launch_wg_put_signal(me, 1 - me, 2 * MiB + da, 1024 + sa, n, sig, val, op, n_wg)
+            o.put_signal(me, 2 * MiB + da, 1024 + sa, n, sig, val, op, 1 - me, n_wg)
+            if i % 10 == 9:
+                g.barrier_all()
+                assert_heaps_equal(g, o, upto=3 * MiB, what=f"after case {i} (n_wg {n_wg}, n {n}, src+{sa}, dst+{da})")
+        g.barrier_all()
+        assert_heaps_equal(g, o, upto=3 * MiB, what="end")
+
+
 def test_wait_before_signal_on_other_stream_and_timeout_is_reported():
     g, o = make_pair(2, MiB)
     with g:
