@@ -235,8 +235,7 @@ def put_sweep(torch, S, g, args):
             "crossover_note": "smallest message from which the SDMA copy engines stay at least as fast as loads/stores by that "
                               "many work-groups per PE, all 8 PEs transferring at once. crossover_bytes compares the bytes all "
                               "PEs move per second (SDMA: host submit to completion of all; loads/stores: first kernel start "
-                              "to last kernel end on the device -- with 8 streams on 4 hardware queues the put kernels run in "
-                              "two rounds, which the engines do not); _one_pe_kernel_time compares the engines' completion "
+                              "to last kernel end on the device); _one_pe_kernel_time compares the engines' completion "
                               "time with ONE PE's in-kernel put time; _host_launched with host-launched put kernels. "
                               "null = loads/stores win at every measured size"}
 
@@ -589,6 +588,10 @@ def main():
     ap.add_argument("--n-wg", type=int, default=1024, help="work-groups per PE of the headline put")
     ap.add_argument("--sweep-max-mib", type=int, default=256)
     ap.add_argument("--no-extras", action="store_true", help="headline only (used for profiling runs)")
+    ap.add_argument("--hw-queues", type=int, default=0,
+                    help="set GPU_MAX_HW_QUEUES for this run (HIP's default is 4: the kernels of 8 PE streams then run in two "
+                         "rounds and the per-PE curves of the sweep halve; 8 gives every PE stream a queue); 0 = leave the "
+                         "environment as it is")
     ap.add_argument("--extras", default="all", help="comma-separated names of the extra measurements to run (default: all)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibration-copy", action="store_true",
@@ -599,6 +602,8 @@ def main():
               "--gpus must be 1", file=sys.stderr)
         return 2
 
+    if args.hw_queues:       # read by the HIP runtime when it initialises, i.e. before torch touches the GPU
+        os.environ["GPU_MAX_HW_QUEUES"] = str(args.hw_queues)
     import torch
     from paper_2409_20476_amd import shm as S, synth
     if not torch.cuda.is_available():
@@ -667,7 +672,8 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "u8", "data": "synthetic",
         "config": {"workload": f"config 2: 8 logical PEs, work-group put of {args.size_mib} MiB float32 N(0,1) per PE to PE (p+1) mod 8, "
                                f"{args.n_wg} work-groups x 256 threads per PE, direct load/store, one team grid",
-                   "pes": 8, "bytes_per_pe": n, "n_wg_per_pe": args.n_wg, "path": "ldst"},
+                   "pes": 8, "bytes_per_pe": n, "n_wg_per_pe": args.n_wg, "path": "ldst",
+                   "hip_hardware_queues": int(os.environ.get("GPU_MAX_HW_QUEUES", "4"))},
         "value_note": "payload bytes delivered per second, all 8 PEs together; % of roofline counts read + written bytes",
         "pct_of_hbm_copy_roofline": 100.0 * 2 * head["value_gbs"] / HBM_PEAK_GBS,
         "spot_check_ok": head["spot_check_ok"],

@@ -128,7 +128,7 @@ int shm_barrier_all(shm_ctx *ctx);
  * With SHM_PATH_AUTO a transfer of n bytes by n_wg work-groups uses SDMA iff
  * n >= cutover(class of n_wg); classes are n_wg <= 1, <= 4, <= 64, > 64.  SIZE_MAX = never.
  * Defaults are the thresholds measured on MI355X with 8 PEs transferring at once (the paper sets its
- * own the same way, internally): 512 KiB for one group per PE, 8 MiB for up to four, never for more.  A context whose copy
+ * own the same way, internally): 512 KiB for one group per PE, never for more.  A context whose copy
  * engines are unavailable keeps AUTO on loads/stores. */
 int shm_set_cutover(shm_ctx *ctx, int n_wg, size_t bytes);
 int shm_get_cutover(const shm_ctx *ctx, int n_wg, size_t *bytes);

@@ -62,9 +62,10 @@ struct shm_ctx {
     uint64_t wait_us = 2000000;
     uint64_t ticks_per_us = 100;
     // AUTO thresholds per class of work-group count, as measured on MI355X with 8 PEs transferring at
-    // once: the engines move more from 512 KiB with one group per PE, from 8 MiB with up to four, and
-    // never against more groups.
-    size_t cutover[4] = {size_t(512) << 10, size_t(8) << 20, SIZE_MAX, SIZE_MAX};
+    // once: the engines move more from 512 KiB with one group per PE and never against four or more
+    // groups (given a hardware queue per PE stream; with fewer queues than PE streams the put kernels
+    // of different PEs take turns and the engines also overtake four groups, from about 8 MiB).
+    size_t cutover[4] = {size_t(512) << 10, SIZE_MAX, SIZE_MAX, SIZE_MAX};
     bool team_sync = true;
     int num_cu = 0;
     uint32_t next_slot[SHM_MAX_PES] = {};

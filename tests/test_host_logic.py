@@ -198,10 +198,9 @@ def test_every_entry_point_validates_before_touching_the_device():
 def test_cutover_policy_classes():
     g = _ctx()
     never = (1 << 64) - 1
-    assert [g.get_cutover(w) for w in (1, 4, 64, 1024)] == [MiB // 2, 8 * MiB, never, never]      # the measured defaults
+    assert [g.get_cutover(w) for w in (1, 4, 64, 1024)] == [MiB // 2, never, never, never]      # the measured defaults
     assert g.choose_path(MiB // 2 - 1, 1) == S.SHM_PATH_LDST and g.choose_path(MiB // 2, 1) == S.SHM_PATH_SDMA
-    assert g.choose_path(8 * MiB - 1, 4) == S.SHM_PATH_LDST and g.choose_path(8 * MiB, 3) == S.SHM_PATH_SDMA
-    assert g.choose_path(1 << 40, 5) == S.SHM_PATH_LDST and g.choose_path(1 << 40, 1024) == S.SHM_PATH_LDST
+    assert g.choose_path(1 << 40, 4) == S.SHM_PATH_LDST and g.choose_path(1 << 40, 1024) == S.SHM_PATH_LDST
     g.set_cutover(1, 4096), g.set_cutover(3, 65536), g.set_cutover(64, MiB), g.set_cutover(65, 16 * MiB)
     assert [g.get_cutover(w) for w in (1, 2, 4, 5, 64, 100, 1 << 20)] == [4096, 65536, 65536, MiB, MiB, 16 * MiB, 16 * MiB]
     assert g.choose_path(4095, 1) == S.SHM_PATH_LDST and g.choose_path(4096, 1) == S.SHM_PATH_SDMA
