@@ -206,6 +206,11 @@ def put_sweep(torch, S, g, args):
         ms = paper_timing(torch, lambda iters: time_on_stream(
             torch, g.streams[0], lambda: g.launch_wg_put_all(1, dst, src, n, 1024, S.SHM_PATH_LDST), iters))
         row["team_wg1024_event_us"], row["team_wg1024_event_gbs"] = ms * 1e3, npes * n / ms / 1e6
+    # the get of the same shape at the largest size: every PE reads its neighbour's block
+    n = rows[-1]["bytes"]
+    ms = paper_timing(torch, lambda iters: time_on_stream(
+        torch, g.streams[0], lambda: g.launch_wg_get_all(1, dst, src, n, 1024, S.SHM_PATH_LDST), iters))
+    team_get = {"bytes": n, "us": ms * 1e3, "gbs": npes * n / ms / 1e6, "frac_hbm": 2 * npes * n / ms / 1e6 / HBM_PEAK_GBS}
     g.set_team_sync(True)
 
     def crossover(faster):
@@ -230,7 +235,7 @@ def put_sweep(torch, S, g, args):
                       "the first PE's start to the last PE's end); ldst_wgK_host_us, sdma_us, memcpy_us: host "
                       "clock from first enqueue to completion on all PEs, warm-up doubling to >2 ms then best of 10; "
                       "team_wg1024_event_us: HIP events around one grid for all PEs; gbs = payload of all 8 PEs",
-            "rows": rows, "crossover_bytes": cross_dev, "crossover_bytes_one_pe_kernel_time": cross_one,
+            "rows": rows, "team_get_wg1024_event": team_get, "crossover_bytes": cross_dev, "crossover_bytes_one_pe_kernel_time": cross_one,
             "crossover_bytes_host_launched": cross_host, "auto_path": auto,
             "crossover_note": "smallest message from which the SDMA copy engines stay at least as fast as loads/stores by that "
                               "many work-groups per PE, all 8 PEs transferring at once. crossover_bytes compares the bytes all "
