@@ -109,10 +109,14 @@ int shm_read(shm_ctx *ctx, int pe, uint64_t off, void *host, size_t n);
 int shm_putmem(shm_ctx *ctx, int me, uint64_t dst_off, uint64_t src_off, size_t n, int pe);
 int shm_getmem(shm_ctx *ctx, int me, uint64_t dst_off, uint64_t src_off, size_t n, int pe);
 
-/* quiet: all of PE me's outstanding operations are complete and visible (host wait on its stream
- * and on its copy-engine transfers).  fence: orders me's earlier operations before its later ones;
- * the stream is in-order, so only engine transfers need waiting for.  barrier_all: quiet for every
- * PE.  All three report an expired device wait. */
+/* quiet: all of PE me's outstanding operations are complete and visible (host wait on its stream,
+ * on its copy-engine transfers, and -- while the host proxy runs -- on the engine transfers its
+ * kernels started through the ring without waiting for them: the PE-wide quiet that completes a
+ * kernel's put_nbi / get_nbi).  fence: orders me's earlier operations before its later ones;
+ * the stream is in-order, so only host-started engine transfers need waiting for.  barrier_all:
+ * quiet for every PE.  All three report an expired device wait (SHM_ETIMEOUT); quiet and
+ * barrier_all also report an engine transfer a kernel asked for and the proxy could not start
+ * (SHM_EHIP). */
 int shm_quiet(shm_ctx *ctx, int me);
 int shm_fence(shm_ctx *ctx, int me);
 int shm_barrier_all(shm_ctx *ctx);
@@ -173,7 +177,8 @@ int shm_wall_clock_khz(const shm_ctx *ctx);
 
 /* Start / stop the host proxy thread and its ring (64-byte messages in pinned host memory).  While
  * it runs, kernels can ask the host to start an SDMA transfer.  Start waits for all streams and
- * resets the ring; stop waits for all streams, then joins the thread.  shm_finalize stops it too.
+ * resets the ring; stop waits for all streams, lets the thread take what is still in the ring and
+ * finish the transfers it started, then joins it.  shm_finalize stops it too.
  * shm_proxy_stats reports how many requests and how many engine copies the proxy has served since
  * its start (either pointer may be NULL). */
 int shm_proxy_start(shm_ctx *ctx);
@@ -194,7 +199,8 @@ int shm_launch_put_device_initiated(shm_ctx *ctx, int me, int pe, uint64_t dst_o
  * above (a get by loads/stores needs no quiet); mode 4 is the refinement the paper's implementation
  * notes sketch for the cutover: the engine moves all but the first `cover` bytes of a group's share
  * while the group moves those first bytes with loads and stores, covering the engine's start-up
- * time; then both are waited for.  consume_off (get only; SHM_NO_CONSUME = none): offset on PE me
+ * time; then both are waited for; mode 5 is put_nbi / get_nbi with no quiet inside the kernel:
+ * the transfer is complete after shm_quiet(me) or shm_barrier_all (no consume_off then).  consume_off (get only; SHM_NO_CONSUME = none): offset on PE me
  * of n bytes that do not overlap the transfer; the group copies its share of the destination there
  * before the first get and after every get, from inside the kernel, so the buffer shows what the
  * kernel itself reads after a get.  dev_ticks may be NULL. */

@@ -167,6 +167,28 @@ int take_status(shm_ctx *c)
     return SHM_OK;
 }
 
+// Ring index the senders have allocated up to now (the word lives in device memory).
+int offload_head(const shm_ctx *c, uint64_t *head)
+{
+    *head = 0;
+    if (!c->proxy.running()) return SHM_OK;
+    HIP_TRY(hipMemcpy(head, c->base + c->user_bytes + OFFLOAD_COUNTERS, 8, hipMemcpyDeviceToHost));
+    return SHM_OK;
+}
+
+// Host side of quiet for the engine transfers that kernels of PE `pe` (all PEs if pe < 0) started
+// through the ring and did not wait for themselves.  The PE's stream must be idle already, so that
+// every request of its kernels is in the ring.
+int quiet_offloaded(shm_ctx *c, int pe)
+{
+    if (!c->proxy.running()) return SHM_OK;
+    uint64_t head = 0;
+    if (int r = offload_head(c, &head)) return r;
+    if (!c->proxy.wait_idle(head, pe, 60.0)) return fail(SHM_ETIMEOUT, "engine transfers started by kernels did not complete in time");
+    if (c->proxy.take_failed()) return fail(SHM_EHIP, "the host proxy could not start an engine transfer a kernel asked for");
+    return SHM_OK;
+}
+
 // All PE streams -> team stream (PE 0's).
 int team_join(shm_ctx *c)
 {
@@ -455,7 +477,9 @@ int shm_finalize(shm_ctx *c)
     if (!c->no_device) {
         for (int p = 0; p < c->npes; ++p)
             if (c->stream[p] || !c->own_streams) (void)hipStreamSynchronize(c->stream[p]);
-        c->proxy.stop();
+        uint64_t head = 0;
+        (void)offload_head(c, &head);
+        c->proxy.stop(head);
         if (c->off_host) (void)hipHostFree(c->off_host);
         c->engines.shutdown();
         for (int p = 0; p < c->npes; ++p) {
@@ -493,8 +517,14 @@ int shm_calloc(shm_ctx *c, size_t bytes, size_t align, uint64_t *off)
 {
     if (int r = shm_malloc(c, bytes, align, off)) return r;
     if (bytes == 0 || c->no_device) return SHM_OK;
-    for (int p = 0; p < c->npes; ++p) HIP_TRY(hipMemsetAsync(shm_ptr(c, *off, p), 0, bytes, c->stream[p]));
-    for (int p = 0; p < c->npes; ++p) HIP_TRY(hipStreamSynchronize(c->stream[p]));
+    hipError_t e = hipSuccess;
+    for (int p = 0; p < c->npes && e == hipSuccess; ++p) e = hipMemsetAsync(shm_ptr(c, *off, p), 0, bytes, c->stream[p]);
+    for (int p = 0; p < c->npes && e == hipSuccess; ++p) e = hipStreamSynchronize(c->stream[p]);
+    if (e != hipSuccess) {
+        (void)c->alloc.release(*off);
+        *off = SHM_NULL_OFF;
+        return fail(SHM_EHIP, "clearing the block: %s", hipGetErrorString(e));
+    }
     return SHM_OK;
 }
 
@@ -557,6 +587,7 @@ int shm_quiet(shm_ctx *c, int me)
     if (c->no_device) return no_device("shm_quiet");
     HIP_TRY(hipStreamSynchronize(c->stream[me]));
     if (int r = drain_engines(c, me)) return r;
+    if (int r = quiet_offloaded(c, me)) return r;
     return take_status(c);
 }
 
@@ -575,6 +606,7 @@ int shm_barrier_all(shm_ctx *c)
     if (c->no_device) return no_device("shm_barrier_all");
     for (int p = 0; p < c->npes; ++p) HIP_TRY(hipStreamSynchronize(c->stream[p]));
     if (int r = drain_all_engines(c)) return r;
+    if (int r = quiet_offloaded(c, -1)) return r;
     return take_status(c);
 }
 
@@ -680,7 +712,10 @@ int shm_proxy_stop(shm_ctx *c)
     if (int r = check_ctx(c)) return r;
     if (c->no_device) return no_device("shm_proxy_stop");
     for (int p = 0; p < c->npes; ++p) HIP_TRY(hipStreamSynchronize(c->stream[p]));
-    c->proxy.stop();
+    uint64_t head = 0;
+    if (int r = offload_head(c, &head)) return r;
+    c->proxy.stop(head);       // takes what is still in the ring and finishes the transfers first
+    if (c->proxy.take_failed()) return fail(SHM_EHIP, "the host proxy could not start an engine transfer a kernel asked for");
     return take_status(c);
 }
 
@@ -699,12 +734,13 @@ int shm_launch_rma_device_initiated(shm_ctx *c, int me, int pe, uint64_t dst_off
     if (int r = check_ctx(c)) return r;
     if (int r = rma_args(c, me, pe, dst_off, src_off, n)) return r;
     if (n_wg < 1 || n_wg > 1024) return fail(SHM_EINVAL, "n_wg outside 1..1024");
-    if (mode < 0 || mode > 4) return fail(SHM_EINVAL, "mode outside 0..4");
+    if (mode < 0 || mode > 5) return fail(SHM_EINVAL, "mode outside 0..5");
     if (wg_size < 1 || wg_size > 1024) return fail(SHM_EINVAL, "wg_size outside 1..1024");
     if (mode != 0 && wg_size % 64) return fail(SHM_EINVAL, "the copy-engine modes need whole waves: wg_size must be a multiple of 64");
     if (reps < 1 || reps > (1 << 20)) return fail(SHM_EINVAL, "reps outside 1..2^20");
     if (consume_off != SHM_NO_CONSUME) {
         if (!is_get) return fail(SHM_EINVAL, "only a get has a local destination to consume");
+        if (mode == 5) return fail(SHM_EINVAL, "a get left to the host's quiet has nothing to consume inside the kernel");
         if (int r = check_range(c, consume_off, n, "consume buffer")) return r;
         if (overlaps(consume_off, dst_off, n) || (me == pe && overlaps(consume_off, src_off, n)))
             return fail(SHM_EINVAL, "the consume buffer overlaps the transfer");
@@ -934,7 +970,8 @@ int shm_launch_ring_pipeline(shm_ctx *c, uint64_t src_off, uint64_t slot_off, ui
     if (int r = check_ctx(c)) return r;
     if (chunk_bytes == 0 || chunk_bytes % 16) return fail(SHM_EINVAL, "chunk_bytes must be a positive multiple of 16");
     if (n_chunks < 1 || static_cast<uint32_t>(n_chunks) > ARRIVE_SLOTS) return fail(SHM_EINVAL, "n_chunks outside 1..%u", ARRIVE_SLOTS);
-    if (n_wg_prod < 1 || n_wg_cons < 1) return fail(SHM_EINVAL, "need at least one producer and one consumer group per PE");
+    if (n_wg_prod < 1 || n_wg_cons < 1 || n_wg_prod > MAX_N_WG || n_wg_cons > MAX_N_WG)
+        return fail(SHM_EINVAL, "producer and consumer groups per PE outside 1..%d", MAX_N_WG);
     if (chunk_bytes > c->user_bytes / n_chunks) return fail(SHM_ERANGE, "chunks leave the heap");
     const size_t total = chunk_bytes * n_chunks;
     if (int r = check_range(c, src_off, total, "chunk source")) return r;
@@ -948,6 +985,12 @@ int shm_launch_ring_pipeline(shm_ctx *c, uint64_t src_off, uint64_t slot_off, ui
     if (overlaps(src_off, slot_off, total) || (acc_off < slot_off + total && slot_off < acc_off + 2 * chunk_bytes) ||
         (acc_off < src_off + total && src_off < acc_off + 2 * chunk_bytes))
         return fail(SHM_EINVAL, "source, slots and accumulator must be disjoint");
+    {
+        const uint64_t sig_end = sig_off + 8ull * n_sig;
+        if ((sig_off < src_off + total && src_off < sig_end) || (sig_off < slot_off + total && slot_off < sig_end) ||
+            (sig_off < acc_off + 2 * chunk_bytes && acc_off < sig_end))
+            return fail(SHM_EINVAL, "signal words lie inside a data buffer");
+    }
     const size_t nvec = chunk_bytes / 16;
     if ((nvec + n_wg_cons - 1) / n_wg_cons > static_cast<size_t>(SHMK_WG) * SHMK_RING_VPT)
         return fail(SHM_EINVAL, "n_wg_cons too small: a consumer group holds at most %d bytes of a chunk", SHMK_WG * SHMK_RING_VPT * 16);

@@ -66,7 +66,8 @@ __global__ __launch_bounds__(SHMK_WG) void shmk_wg_put_timed(shm_dev_ctx c, uint
 // message.  mode 0: loads/stores (put: + group quiet); 1: host-started copy engine, blocking;
 // 2: cutover on the share size; 3: non-blocking engine transfer (put_nbi / get_nbi), offload quiet
 // after each; 4: engine for all but the first `cover` bytes of the share, loads/stores for those,
-// then both quiets.  consume_off (get only, else UINT64_MAX): before the first get the group copies
+// then both quiets; 5: non-blocking engine transfer and no quiet at all inside the kernel -- the
+// transfer is complete after the host's quiet for this PE.  consume_off (get only, else UINT64_MAX): before the first get the group copies
 // its share of the destination to consume_off -- which pulls the old bytes into the caches -- and
 // after every get it copies the share again, so the copy shows what a thread of the group reads.
 constexpr uint64_t SHMK_NO_CONSUME = ~0ull;
@@ -109,6 +110,11 @@ __global__ __launch_bounds__(1024) void shmk_rma_device_initiated(shm_dev_ctx c,
             else
                 shmx_putmem_offload_wg(c, me, d, s, len, pe, false);
             shmx_quiet_offload_wg(c, me);
+        } else if (mode == 5) {
+            if (is_get)
+                shmx_getmem_offload_wg(c, me, d, s, len, pe, false);
+            else
+                shmx_putmem_offload_wg(c, me, d, s, len, pe, false);
         } else {
             shmx_rma_covered_wg(c, me, d, s, len, pe, cover, is_get != 0);
             if (!is_get && len) shmx_quiet_wg();

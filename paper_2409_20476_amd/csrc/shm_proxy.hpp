@@ -22,7 +22,7 @@
 #include <chrono>
 #include <cstdint>
 #include <cstring>
-#include <deque>
+#include <memory>
 #include <thread>
 #include <vector>
 
@@ -47,17 +47,26 @@ public:
         sh_ = shared;
         agent_ = agent;
         engines_ = engines;
-        in_flight_per_pe_.assign(npes, 0);
+        npes_ = static_cast<uint32_t>(npes);
+        in_flight_per_pe_.reset(new std::atomic<uint32_t>[npes_]);
+        for (uint32_t p = 0; p < npes_; ++p) in_flight_per_pe_[p].store(0);
         requests_in_flight_.clear();
         free_requests_.clear();
         stop_.store(false);
-        requests_ = copies_ = 0;
+        stop_at_.store(0);
+        taken_.store(0);
+        requests_.store(0);
+        copies_.store(0);
+        failed_.store(0);
         thread_ = std::thread([this] { run(); });
     }
 
-    void stop()
+    // Ends the thread once it has taken every message up to ring index `head` (what the senders
+    // have allocated so far) and the transfers it started have finished, both within a time limit.
+    void stop(uint64_t head = 0)
     {
         if (!thread_.joinable()) return;
+        stop_at_.store(head);
         stop_.store(true);
         thread_.join();
         for (hsa_signal_t s : free_) hsa_signal_destroy(s);
@@ -65,8 +74,29 @@ public:
     }
 
     bool running() const { return thread_.joinable(); }
-    uint64_t requests() const { return requests_; }
-    uint64_t copies() const { return copies_; }
+    uint64_t requests() const { return requests_.load(std::memory_order_relaxed); }
+    uint64_t copies() const { return copies_.load(std::memory_order_relaxed); }
+
+    // Requests whose engine transfer could not be started in full since the last call.
+    uint64_t take_failed() { return failed_.exchange(0); }
+
+    // The host side of quiet for transfers that kernels started through the ring: returns once the
+    // thread has taken every message below ring index `head` and PE `pe` (every PE if pe < 0) has no
+    // transfer in flight.  False if that has not happened after `limit_s` seconds.
+    bool wait_idle(uint64_t head, int pe, double limit_s) const
+    {
+        const auto t0 = std::chrono::steady_clock::now();
+        for (;;) {
+            if (taken_.load(std::memory_order_acquire) >= head) {
+                bool idle = true;
+                for (uint32_t p = 0; p < npes_; ++p)
+                    if ((pe < 0 || static_cast<uint32_t>(pe) == p) && in_flight_per_pe_[p].load(std::memory_order_acquire) != 0) idle = false;
+                if (idle) return true;
+            }
+            if (std::chrono::duration<double>(std::chrono::steady_clock::now() - t0).count() > limit_s) return false;
+            std::this_thread::yield();
+        }
+    }
 
 private:
     // One request may be split into pieces that run on several engines; the requester is answered
@@ -109,7 +139,7 @@ private:
                 request_in_flight &r = requests_in_flight_[c.request];
                 if (--r.pieces_left == 0) {
                     reply(r.comp, r.tag);
-                    --in_flight_per_pe_[r.pe];
+                    in_flight_per_pe_[r.pe].fetch_sub(1, std::memory_order_release);
                     free_requests_.push_back(c.request);
                 }
                 free_.push_back(c.sig);
@@ -120,7 +150,7 @@ private:
             }
         }
         for (size_t i = 0; i < quiets_.size();) {
-            if (in_flight_per_pe_[quiets_[i].pe] == 0) {
+            if (in_flight_per_pe_[quiets_[i].pe].load(std::memory_order_relaxed) == 0) {
                 reply(quiets_[i].comp, quiets_[i].tag);
                 quiets_[i] = quiets_.back();
                 quiets_.pop_back();
@@ -133,8 +163,8 @@ private:
     void handle(const uint32_t *m, uint32_t comp_tag)
     {
         const uint32_t op = m[0], pe = m[1], comp = m[2];
-        ++requests_;
-        if (pe >= in_flight_per_pe_.size()) {
+        requests_.fetch_add(1, std::memory_order_relaxed);
+        if (pe >= npes_) {
             reply(comp, comp_tag);
             return;
         }
@@ -174,19 +204,19 @@ private:
                 }
                 copies_in_flight_.push_back({sig, request});
                 ++started;
-                ++copies_;
+                copies_.fetch_add(1, std::memory_order_relaxed);
             }
             const bool all = static_cast<size_t>(started) * per >= n;
-            if (!all) ++failed_;      // the requester is still released below; its data is incomplete (counted, reported by tests)
+            if (!all) failed_.fetch_add(1);      // the requester is still released; the host's next quiet reports the failure
             if (started == 0) {
                 free_requests_.push_back(request);
                 reply(comp, comp_tag);
                 return;
             }
             requests_in_flight_[request] = {started, pe, comp, comp_tag};
-            ++in_flight_per_pe_[pe];
+            in_flight_per_pe_[pe].fetch_add(1, std::memory_order_relaxed);
         } else if (op == SHM_OFFLOAD_QUIET) {
-            if (in_flight_per_pe_[pe] == 0)
+            if (in_flight_per_pe_[pe].load(std::memory_order_relaxed) == 0)
                 reply(comp, comp_tag);
             else
                 quiets_.push_back({pe, comp, comp_tag});
@@ -199,7 +229,14 @@ private:
     {
         uint64_t tail = 0;
         uint32_t idle = 0;
-        while (!stop_.load(std::memory_order_relaxed)) {
+        std::chrono::steady_clock::time_point stop_seen{};
+        for (;;) {
+            if (stop_.load(std::memory_order_acquire)) {
+                // asked to end: first take what the senders had already put into the ring (bounded)
+                const auto now = std::chrono::steady_clock::now();
+                if (stop_seen == std::chrono::steady_clock::time_point{}) stop_seen = now;
+                if (tail >= stop_at_.load(std::memory_order_relaxed) || std::chrono::duration<double>(now - stop_seen).count() > 5.0) break;
+            }
             // Look at the next kBatch slots at once: their tag loads are independent, so the cache
             // misses (the GPU's stores evicted these lines from the host's caches) overlap instead of
             // being paid one message at a time.  Messages are taken strictly in ring order.
@@ -222,6 +259,7 @@ private:
                     ++tail;
                     if ((tail & 63) == 0) sh_->consumed = tail;     // flow control, off the critical path
                 }
+                taken_.store(tail, std::memory_order_release);
                 idle = 0;
             } else if (++idle == 64) {
                 sh_->consumed = tail;
@@ -238,7 +276,8 @@ private:
     shm_offload_shared *sh_ = nullptr;
     hsa_agent_t agent_{};
     std::vector<uint32_t> engines_;
-    std::vector<uint32_t> in_flight_per_pe_;
+    uint32_t npes_ = 0;
+    std::unique_ptr<std::atomic<uint32_t>[]> in_flight_per_pe_;     // requests with unfinished pieces; read by wait_idle
     static constexpr unsigned kBatch = 8;              // ring slots examined per poll
     static constexpr size_t kMinPiece = 4u << 20;      // do not split below 4 MiB per engine
     static constexpr size_t kMaxPieces = 8;
@@ -249,7 +288,9 @@ private:
     std::vector<quiet_waiting> quiets_;
     std::vector<hsa_signal_t> free_;
     std::atomic<bool> stop_{false};
+    std::atomic<uint64_t> stop_at_{0};
+    std::atomic<uint64_t> taken_{0};                   // ring messages handled so far
     std::thread thread_;
-    uint64_t requests_ = 0, copies_ = 0, failed_ = 0;
+    std::atomic<uint64_t> requests_{0}, copies_{0}, failed_{0};
     uint32_t next_engine_ = 0;
 };

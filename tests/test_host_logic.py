@@ -145,6 +145,8 @@ def test_every_entry_point_validates_before_touching_the_device():
     assert code(lambda: g.launch_ring_pipeline(0, 65536, 262144, 131072, 4100, 4, 2, 2, 1)) == S.SHM_EINVAL     # chunk not x16
     assert code(lambda: g.launch_ring_pipeline(0, 65536, 262144, 131072, 4096, 4, 2, 3, 2)) == S.SHM_EINVAL     # lanes need equal groups
     assert code(lambda: g.launch_ring_pipeline(0, 8192, 262144, 131072, 4096, 4, 2, 2, 1)) == S.SHM_EINVAL      # src/slots overlap
+    assert code(lambda: g.launch_ring_pipeline(0, 65536, 65536 + 4096, 131072, 4096, 4, 2, 2, 1)) == S.SHM_EINVAL     # signal inside the slots
+    assert code(lambda: g.launch_ring_pipeline(0, 65536, 262144, 131072, 4096, 4, 1 << 21, 2, 1)) == S.SHM_EINVAL     # too many groups
     assert code(lambda: g.launch_amo_storm(0, 16, 4096 + 2, 100, 8)) == S.SHM_EINVAL                            # table alignment
     assert code(lambda: g.launch_amo_storm(0, 1 << 15, 4096, 100, 8)) == S.SHM_EINVAL                           # 16-bit ids
     assert code(lambda: g.launch_reduce_sum_f32(65538, 0, 1000, 2)) == S.SHM_EINVAL
@@ -172,7 +174,9 @@ def test_every_entry_point_validates_before_touching_the_device():
     assert code(lambda: g.launch_thread_rma(0, 1, 4096, 0, 100)) == S.SHM_ENODEV
     assert code(lambda: g.launch_thread_rma(0, 0, 50, 0, 100)) == S.SHM_EINVAL
     assert code(lambda: g.launch_rma_device_initiated(0, 1, 4096, 0, 100, 2, True, 0)) == S.SHM_ENODEV
-    assert code(lambda: g.launch_rma_device_initiated(0, 1, 4096, 0, 100, 2, True, 5)) == S.SHM_EINVAL
+    assert code(lambda: g.launch_rma_device_initiated(0, 1, 4096, 0, 100, 2, True, 5)) == S.SHM_ENODEV
+    assert code(lambda: g.launch_rma_device_initiated(0, 1, 4096, 0, 100, 2, True, 6)) == S.SHM_EINVAL
+    assert code(lambda: g.launch_rma_device_initiated(0, 1, 4096, 0, 100, 2, True, 5, consume_off=8192)) == S.SHM_EINVAL   # nothing to consume before the host's quiet
     assert code(lambda: g.launch_rma_device_initiated(0, 1, 4096, 0, 100, 2, False, 0, consume_off=8192)) == S.SHM_EINVAL
     assert code(lambda: g.launch_rma_device_initiated(0, 1, 4096, 0, 100, 2, True, 0, consume_off=4100)) == S.SHM_EINVAL
     assert code(lambda: g.launch_rma_device_initiated(0, 1, 4096, 0, 100, 2, True, 0, consume_off=H - 10)) == S.SHM_ERANGE

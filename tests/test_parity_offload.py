@@ -126,3 +126,35 @@ def test_device_initiated_put_random_sizes_and_alignments():
                 assert_heaps_equal(g, o, upto=3 * MiB, what=f"after case {i} (wg_size {wg_size}, n_wg {n_wg}, n {n}, src+{sa}, dst+{da})")
         g.barrier_all()
         assert_heaps_equal(g, o, upto=3 * MiB, what="end")
+
+
+@pytest.mark.parametrize("is_get", [False, True])
+def test_nbi_transfers_of_a_kernel_complete_at_the_hosts_quiet(is_get):
+    """put_nbi / get_nbi issued by kernels that never wait for them (no quiet inside the kernel):
+    OpenSHMEM completes them at the PE's quiet, which here is the host's shm_quiet for that PE."""
+    g, o = make_pair(3, 16 * MiB)
+    with g:
+        fill_random(g, o, 34, upto=12 * MiB)
+        g.proxy_start()
+        cases = [(5 * MiB + 1000, 16, 256, 512), (100003, 1, 17, 5), (0, 2, 0, 0), (MiB + 256, 8, 0, 0), (4096, 3, 3, 3)]
+        for i, (n, n_wg, sa, da) in enumerate(cases):
+            me, pe = i % 3, (i + 2) % 3
+            src, dst = 1024 + sa, 6 * MiB + da
+            g.launch_rma_device_initiated(me, pe, dst, src, n, n_wg, is_get, 5, wg_size=(256, 64, 1024)[i % 3])
+            g.quiet(me)
+            (o.getmem if is_get else o.putmem)(me, dst, src, n, pe)
+            assert_heaps_equal(g, o, upto=12 * MiB, what=f"get={is_get} case {i}")
+        # several PEs' transfers left in flight together, completed by one barrier_all
+        for me in range(3):
+            g.launch_rma_device_initiated(me, (me + 1) % 3, 6 * MiB + me * MiB, 2048 + me * 512, MiB - 7, 4, is_get, 5)
+            (o.getmem if is_get else o.putmem)(me, 6 * MiB + me * MiB, 2048 + me * 512, MiB - 7, (me + 1) % 3)
+        g.barrier_all()
+        assert_heaps_equal(g, o, upto=12 * MiB, what=f"get={is_get} after barrier_all")
+        # stopping the proxy finishes what kernels left in the ring
+        g.launch_rma_device_initiated(0, 1, 9 * MiB, 4096, 2 * MiB, 8, is_get, 5)
+        o_call = o.getmem if is_get else o.putmem
+        o_call(0, 9 * MiB, 4096, 2 * MiB, 1)
+        g.proxy_stop()
+        assert_heaps_equal(g, o, upto=12 * MiB, what=f"get={is_get} after proxy_stop")
+        with pytest.raises(S.ShmError):
+            g.launch_rma_device_initiated(0, 1, 9 * MiB, 4096, 4096, 1, True, 5, consume_off=11 * MiB)
