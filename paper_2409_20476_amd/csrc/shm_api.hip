@@ -507,7 +507,12 @@ int shm_malloc(shm_ctx *c, size_t bytes, size_t align, uint64_t *off)
         *off = SHM_NULL_OFF;
         return SHM_OK;
     }
-    const uint64_t o = c->alloc.allocate(bytes, align);
+    uint64_t o = shm_heap_allocator::NPOS;
+    try {
+        o = c->alloc.allocate(bytes, align);
+    } catch (const std::bad_alloc &) {       // the allocator's own book-keeping; nothing crosses the C boundary
+        return fail(SHM_ENOMEM, "out of host memory");
+    }
     if (o == shm_heap_allocator::NPOS) return fail(SHM_ENOMEM, "no free extent of %zu bytes (align %zu) in the symmetric heap", bytes, align);
     *off = o;
     return SHM_OK;
@@ -532,7 +537,11 @@ int shm_free(shm_ctx *c, uint64_t off)
 {
     if (int r = check_ctx(c)) return r;
     if (off == SHM_NULL_OFF) return SHM_OK;
-    if (!c->alloc.release(off)) return fail(SHM_EINVAL, "offset %llu is not a live block", (unsigned long long)off);
+    try {
+        if (!c->alloc.release(off)) return fail(SHM_EINVAL, "offset %llu is not a live block", (unsigned long long)off);
+    } catch (const std::bad_alloc &) {
+        return fail(SHM_ENOMEM, "out of host memory");
+    }
     return SHM_OK;
 }
 

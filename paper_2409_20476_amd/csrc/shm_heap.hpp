@@ -7,6 +7,7 @@
 
 #include <cstddef>
 #include <cstdint>
+#include <iterator>
 #include <map>
 
 class shm_heap_allocator {
