@@ -73,3 +73,19 @@ def test_argument_errors():
         with pytest.raises(OracleError):
             bad()
     o.iput(0, 0, 4096 - 4, 1, 1000, 1, 4, 1)      # one element: strides do not matter
+
+
+def test_span_ends_at_the_last_element_not_a_stride_later():
+    """A strided transfer occupies (nelems - 1) * stride + 1 elements: the last element may end
+    exactly at the end of the heap, and on one PE the two spans may touch without overlapping."""
+    o = ShmemOracle(2, 4096)
+    o.write(0, 0, np.arange(40, dtype=np.uint8))
+    o.iput(0, 4096 - 37 * 4, 0, 4, 1, 10, 4, 1)             # destination elements at 3948, 3964, ..., 4092
+    assert np.array_equal(o.read(1, 4092, 4), np.arange(36, 40, dtype=np.uint8))
+    o.iget(0, 4096 - 19 * 2, 0, 2, 3, 10, 2, 1)             # both spans end where they must: source 56 bytes, destination 38
+    with pytest.raises(OracleError):
+        o.iput(0, 4096 - 37 * 4 + 4, 0, 4, 1, 10, 4, 1)     # one element further leaves the heap
+    # same PE: source span [0, 148), destination span starting right behind it
+    o.iput(0, 148, 0, 3, 4, 10, 4, 0)
+    with pytest.raises(OracleError):
+        o.iput(0, 144, 0, 3, 4, 10, 4, 0)
