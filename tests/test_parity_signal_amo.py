@@ -83,6 +83,41 @@ def test_wait_before_signal_on_other_stream_and_timeout_is_reported():
         assert_heaps_equal(g, o)
 
 
+def test_every_comparison_at_its_boundary_unsigned():
+    """All six comparisons of signal_wait_until one below, at and one above the signal's value, and
+    across 2^63 (the comparison is unsigned).  The oracle says whether the wait can be satisfied; on
+    the GPU a wait that cannot be satisfied runs into the (here tiny) bound and is reported."""
+    from oracle.shmem_oracle import OracleError
+    g, o = make_pair(2, MiB)
+    cmps = [S.SHM_CMP_EQ, S.SHM_CMP_NE, S.SHM_CMP_GT, S.SHM_CMP_GE, S.SHM_CMP_LT, S.SHM_CMP_LE]
+    pairs = [(5, 4), (5, 5), (5, 6), (2 ** 63 + 1, 1), (1, 2 ** 63 + 1), (2 ** 64 - 1, 2 ** 64 - 1), (0, 2 ** 64 - 1)]
+    with g:
+        out = torch.zeros(1, dtype=torch.int64, device="cuda")
+        g.set_wait_timeout_us(300)
+        satisfied = 0
+        for sig_value, value in pairs:
+            word = np.array([sig_value], dtype=np.uint64)
+            write_both(g, o, 1, 256, word)
+            for cmp in cmps:
+                try:
+                    want = o.signal_wait_until(1, 256, cmp, value)
+                except OracleError:
+                    want = None
+                out.fill_(-1)
+                torch.cuda.synchronize()
+                g.launch_signal_wait_until(1, 256, cmp, value, out)
+                if want is None:
+                    with pytest.raises(S.ShmError) as e:
+                        g.quiet(1)
+                    assert e.value.code == S.SHM_ETIMEOUT, (sig_value, value, cmp)
+                else:
+                    g.quiet(1)
+                    assert int(out.item()) & (2 ** 64 - 1) == want == sig_value, (sig_value, value, cmp)
+                    satisfied += 1
+        assert satisfied == 21          # EQ 2, NE 5, GT 2, GE 4, LT 3, LE 5 of the 7 pairs
+        g.set_wait_timeout_us(2_000_000)
+
+
 def test_every_atomic_matches_the_oracle():
     g, o = make_pair(3, MiB)
     with g:
