@@ -45,7 +45,8 @@ by a sequential schedule, so it raises instead of blocking.
 Readings taken where the paper is silent are listed in the repository's design
 notes; the ones that matter here: overlapping source and destination on one PE
 is an error; signal and atomic targets must be 8-byte aligned; ``put_signal``
-with zero bytes still updates the signal; a PE may target itself.
+with zero bytes still updates the signal; the signal word may not lie inside the
+destination (OpenSHMEM 1.5, put-with-signal); a PE may target itself.
 
 Parity status: every function here is pinned by the CPU tests (brute force on
 tiny heaps against an independent byte-at-a-time model, closed forms, library
@@ -273,6 +274,9 @@ class ShmemOracle:
         self._word(sig)
         if op not in (SIGNAL_SET, SIGNAL_ADD):
             raise OracleError("signal operation must be SET or ADD")
+        if n and sig < dst + n and dst < sig + 8:
+            # OpenSHMEM 1.5, put-with-signal: destination and signal word may not overlap
+            raise OracleError("the signal word lies inside the destination")
         self.wg_put(me, dst, src, n, pe, n_wg)
         if op == SIGNAL_SET:
             self._store_u64(pe, sig, value)
@@ -354,6 +358,9 @@ class ShmemOracle:
         """Every PE's block of ``n`` bytes, in PE order, lands in every PE's destination."""
         self._range(src, n)
         self._range(dst, n * self.npes)
+        if n and src < dst + n * self.npes and dst < src + n:
+            # peers write the destination while the owner's source is still being read: no unique result
+            raise OracleError("overlapping source and destination")
         blocks = [self.heap[p][src:src + n].copy() for p in range(self.npes)]
         for q in range(self.npes):
             for p in range(self.npes):

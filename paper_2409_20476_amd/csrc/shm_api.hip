@@ -856,9 +856,9 @@ int launch_strided(shm_ctx *c, int me, int pe, uint64_t dst_off, uint64_t src_of
     const uint64_t e = static_cast<uint64_t>(elem_bytes), limit = c->user_bytes / e + 1;
     uint64_t dspan = 0, sspan = 0;
     if (nelems) {
-        // (nelems - 1) * stride + 1 elements, computed without overflow
-        if (nelems - 1 > limit || static_cast<uint64_t>(dst_stride) > limit || static_cast<uint64_t>(src_stride) > limit ||
-            (nelems - 1) * static_cast<unsigned __int128>(dst_stride) > limit || (nelems - 1) * static_cast<unsigned __int128>(src_stride) > limit)
+        // (nelems - 1) * stride + 1 elements, computed without overflow; one element has no stride to speak of
+        if (nelems - 1 > limit || (nelems - 1) * static_cast<unsigned __int128>(dst_stride) > limit ||
+            (nelems - 1) * static_cast<unsigned __int128>(src_stride) > limit)
             return fail(SHM_ERANGE, "the strided transfer leaves the heap");
         dspan = ((nelems - 1) * static_cast<uint64_t>(dst_stride) + 1) * e;
         sspan = ((nelems - 1) * static_cast<uint64_t>(src_stride) + 1) * e;

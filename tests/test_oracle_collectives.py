@@ -43,6 +43,21 @@ def test_fcollect_equals_gets_by_every_pe():
     assert all((x == y).all() for x, y in zip(a.heap, b.heap))
 
 
+def test_fcollect_refuses_overlapping_buffers_and_accepts_touching_ones():
+    """Peers write a PE's destination while that PE's source is still being read, so an overlap has
+    no unique result; buffers that merely touch are fine."""
+    o = ShmemOracle(4, 1024)
+    _fill(o, 2)
+    before = [h.copy() for h in o.heap]
+    for dst, src, n in [(0, 0, 10), (0, 39, 10), (100, 95, 10), (100, 103, 1)]:
+        with pytest.raises(OracleError):
+            o.fcollect(dst, src, n)
+    assert all((x == y).all() for x, y in zip(before, o.heap))
+    o.fcollect(0, 40, 10)            # destination [0, 40), source [40, 50)
+    o.fcollect(100, 90, 10)          # source ends where the destination begins
+    o.fcollect(0, 0, 0)
+
+
 def test_reduce_golden_order_example():
     rows = [[float(x) for x in l.split()] for l in open(os.path.join(GOLDEN, "reduce_order_example.txt"))
             if not l.startswith("#")]

@@ -41,6 +41,15 @@ def test_signal_ops_set_add_wrap_and_zero_length():
         o.put_signal(0, 0, 0, 0, 60, 1, SIGNAL_SET, 1)  # misaligned signal word
     with pytest.raises(OracleError):
         o.put_signal(0, 0, 0, 0, 64, 1, 9, 1)
+    # OpenSHMEM 1.5, put-with-signal: the signal word may not overlap the destination; touching it is fine
+    before = [h.copy() for h in o.heap]
+    for dst, n in [(60, 8), (64, 1), (71, 3), (40, 30)]:
+        with pytest.raises(OracleError):
+            o.put_signal(0, dst, 0, n, 64, 1, SIGNAL_SET, 1)
+    assert all(np.array_equal(a, b) for a, b in zip(before, o.heap)), "a refused operation changed the heap"
+    o.put_signal(0, 56, 0, 8, 64, 1, SIGNAL_SET, 1)     # ends where the word begins
+    o.put_signal(0, 72, 0, 8, 64, 1, SIGNAL_SET, 1)     # begins where the word ends
+    o.put_signal(0, 64, 0, 0, 64, 1, SIGNAL_SET, 1)     # no payload, nothing to overlap
 
 
 def test_wait_until_unsigned_compare_and_illegal_schedule():
