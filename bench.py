@@ -380,34 +380,44 @@ def collective_sweeps(torch, S, args):
     host copy paths beside it; broadcast against the number of PEs; the device-side sync."""
     out = {"fcollect": {}, "broadcast_us_by_pes": {}, "sync_us_by_pes": {}, "barrier_us_by_pes": {}}
     t = torch.zeros(2, dtype=torch.int64, device="cuda")
-    for npes in (4, 8, 12):
-        g = S.Shm.on_torch(npes, 128 * MiB)
-        g.set_team_sync(False)
-        src, dst = g.malloc(4 * MiB), g.malloc(4 * MiB * npes)
+    def host_path_us(g, launch):
+        def trial(iters):
+            g.barrier_all()
+            t0 = time.perf_counter()
+            for _ in range(iters):
+                launch()
+            g.barrier_all()
+            return (time.perf_counter() - t0) * 1e3 / iters
+        return paper_timing(torch, trial) * 1e3
+
+    def sweep(g, launch, sizes):
+        """launch(n, n_wg, path); per size the three group counts by loads/stores and the two host-started paths."""
         rows = []
-        for k in range(4, 23):
-            n = 1 << k
-            row = {"bytes_per_pe": n, "nelems_int32": n // 4}
+        for n in sizes:
+            row = {"bytes_per_pe": n}
             for n_wg in (1, 4, 64):
-                ms = paper_timing(torch, lambda iters: time_on_stream(
-                    torch, g.streams[0], lambda: g.launch_fcollect(dst, src, n, n_wg, S.SHM_PATH_LDST), iters))
+                ms = paper_timing(torch, lambda iters: time_on_stream(torch, g.streams[0], lambda: launch(n, n_wg, S.SHM_PATH_LDST), iters))
                 row[f"ldst_wg{n_wg}_us"] = ms * 1e3
-            for key, path in (("memcpy", S.SHM_PATH_MEMCPY), ("sdma", S.SHM_PATH_SDMA)):
-                def trial(iters):
-                    g.barrier_all()
-                    t0 = time.perf_counter()
-                    for _ in range(iters):
-                        g.launch_fcollect(dst, src, n, 1, path)
-                    g.barrier_all()
-                    return (time.perf_counter() - t0) * 1e3 / iters
-                row[key + "_us"] = paper_timing(torch, trial) * 1e3
+            row["memcpy_us"] = host_path_us(g, lambda: launch(n, 1, S.SHM_PATH_MEMCPY))
+            row["sdma_us"] = host_path_us(g, lambda: launch(n, 1, S.SHM_PATH_SDMA))
+            for n_wg in (1, 4, 64):      # the tuned collective: the library's own choice, host clock
+                row[f"auto_wg{n_wg}_us"] = host_path_us(g, lambda: launch(n, n_wg, S.SHM_PATH_AUTO))
             rows.append(row)
         cut = {}
         for n_wg in (1, 4, 64):
             key = f"ldst_wg{n_wg}_us"
             cut[str(n_wg)] = next((r["bytes_per_pe"] for i, r in enumerate(rows)
                                    if all(min(q["memcpy_us"], q["sdma_us"]) <= q[key] for q in rows[i:])), None)
-        out["fcollect"][str(npes)] = {"rows": rows, "cutover_bytes_per_pe": cut}
+        return {"rows": rows, "cutover_bytes_per_pe": cut}
+
+    out["broadcast"] = {}
+    for npes in (4, 8, 12):
+        g = S.Shm.on_torch(npes, 512 * MiB)
+        g.set_team_sync(False)
+        src, dst = g.malloc(16 * MiB), g.malloc(16 * MiB * npes)
+        out["fcollect"][str(npes)] = sweep(g, lambda n, n_wg, path: g.launch_fcollect(dst, src, n, n_wg, path), [1 << k for k in range(4, 25)])
+        out["broadcast"][str(npes)] = sweep(g, lambda n, n_wg, path: g.launch_broadcast(dst, src, n, 0, n_wg, path),
+                                            [1 << k for k in range(10, 25, 2)])
         g.finalize()
     for npes in (2, 4, 8, 12, 16):
         g = S.Shm.on_torch(npes, 64 * MiB)
@@ -428,9 +438,10 @@ def collective_sweeps(torch, S, args):
                 best = min(best, (b - a) / g.wall_clock_khz() * 1e3 / 200)
             out[key][str(npes)] = best
         g.finalize()
-    out["note"] = ("fcollect: ldst_wgK_us = one grid with K groups of 256 threads per PE (HIP events, launch included); memcpy_us / "
-                   "sdma_us = npes^2 host-started copies, host clock; cutover = smallest block from which a host copy path stays "
-                   "at least as fast. broadcast: root PE 0, 2 groups (the paper uses 128 work-items), device time per call. "
+    out["note"] = ("fcollect / broadcast: ldst_wgK_us = one grid with K groups of 256 threads per PE (root only for broadcast; HIP events, "
+                   "launch included); memcpy_us / sdma_us = npes^2 (broadcast: npes) host-started copies, host clock; auto_wgK_us = "
+                   "SHM_PATH_AUTO with the library's per-collective thresholds, host clock; cutover = smallest block from which a host "
+                   "copy path stays at least as fast. broadcast_us_by_pes: root PE 0, 2 groups (the paper uses 128 work-items). "
                    "sync / barrier: device clock inside one kernel of npes groups, per operation")
     return out
 

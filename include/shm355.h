@@ -54,6 +54,7 @@ enum { SHM_AMO_FETCH = 0, SHM_AMO_SET = 1, SHM_AMO_SWAP = 2, SHM_AMO_COMPARE_SWA
        SHM_AMO_FETCH_ADD = 4, SHM_AMO_ADD = 5, SHM_AMO_FETCH_INC = 6, SHM_AMO_INC = 7 };
 enum { SHM_STORM_FETCH_ADD = 0, SHM_STORM_ADD = 1, SHM_STORM_CSWAP_LOOP = 2, SHM_STORM_PLAIN_STORE = 3 };
 enum { SHM_REDUCE_DUPLICATE = 0, SHM_REDUCE_SPLIT = 1 };
+enum { SHM_COLL_FCOLLECT = 0, SHM_COLL_BROADCAST = 1 };
 enum { SHM_OP_MIN = 0, SHM_OP_MAX = 1, SHM_OP_SUM = 2, SHM_OP_PROD = 3, SHM_OP_AND = 4, SHM_OP_OR = 5, SHM_OP_XOR = 6 };
 enum { SHM_INT8 = 0, SHM_UINT8 = 1, SHM_INT16 = 2, SHM_UINT16 = 3, SHM_INT32 = 4, SHM_UINT32 = 5, SHM_INT64 = 6, SHM_UINT64 = 7,
        SHM_FLOAT32 = 8, SHM_FLOAT64 = 9 };
@@ -138,6 +139,19 @@ int shm_set_cutover(shm_ctx *ctx, int n_wg, size_t bytes);
 int shm_get_cutover(const shm_ctx *ctx, int n_wg, size_t *bytes);
 /* Which path AUTO would take: writes SHM_PATH_LDST or SHM_PATH_SDMA to *path. */
 int shm_choose_path(const shm_ctx *ctx, size_t n, int n_wg, int *path);
+
+/* The cutover of the collectives (paper section "Performance Evaluation", the fcollect and broadcast
+ * experiments: the threshold of a collective also depends on the number of PEs and is tuned per
+ * collective).  `collective` is SHM_COLL_FCOLLECT or SHM_COLL_BROADCAST; classes of n_wg as above;
+ * bytes are per PE.  With SHM_PATH_AUTO a collective of bytes_per_pe >= the threshold is done by
+ * host-started copies -- SHM_PATH_MEMCPY, which on one device outruns the engines for these
+ * many-copy patterns -- and by the push kernel below it.  Defaults measured on MI355X:
+ * fcollect 512 KiB / 2 MiB / never / never up to 4 PEs and 2 MiB / 8 MiB / never / never beyond
+ * (n_wg <= 1, <= 4, <= 64, more); broadcast 256 KiB / 1 MiB / 16 MiB / never for any number of PEs. */
+int shm_set_collective_cutover(shm_ctx *ctx, int collective, int n_wg, size_t bytes);
+int shm_get_collective_cutover(const shm_ctx *ctx, int collective, int n_wg, size_t *bytes);
+/* Which path AUTO would take for that collective: SHM_PATH_LDST or SHM_PATH_MEMCPY. */
+int shm_choose_collective_path(const shm_ctx *ctx, int collective, size_t bytes_per_pe, int n_wg, int *path);
 
 /* Upper bound for every device-side wait, in microseconds (default 2 000 000; must be > 0). */
 int shm_set_wait_timeout_us(shm_ctx *ctx, uint64_t us);

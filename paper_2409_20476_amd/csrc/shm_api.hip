@@ -66,6 +66,10 @@ struct shm_ctx {
     // groups (given a hardware queue per PE stream; with fewer queues than PE streams the put kernels
     // of different PEs take turns and the engines also overtake four groups, from about 8 MiB).
     size_t cutover[4] = {size_t(512) << 10, SIZE_MAX, SIZE_MAX, SIZE_MAX};
+    // AUTO thresholds of the collectives, bytes per PE, per class of work-group count; set at init
+    // from the number of PEs (measured on MI355X with 4, 8 and 12 PEs; the host-started side of the
+    // comparison is the runtime-copy path, which outruns the engines for these many-copy patterns).
+    size_t coll_cutover[2][4] = {};
     bool team_sync = true;
     int num_cu = 0;
     uint32_t next_slot[SHM_MAX_PES] = {};
@@ -146,6 +150,31 @@ int resolve_path(const shm_ctx *c, int path, size_t n, int n_wg, int *out)
         *out = path;
     else
         return fail(SHM_EINVAL, "unknown path %d", path);
+    return SHM_OK;
+}
+
+void default_collective_cutovers(shm_ctx *c)
+{
+    const bool few = c->npes <= 4;
+    const size_t fc[4] = {few ? size_t(512) << 10 : size_t(2) << 20, few ? size_t(2) << 20 : size_t(8) << 20, SIZE_MAX, SIZE_MAX};
+    const size_t bc[4] = {size_t(256) << 10, size_t(1) << 20, size_t(16) << 20, SIZE_MAX};
+    for (int k = 0; k < 4; ++k) {
+        c->coll_cutover[SHM_COLL_FCOLLECT][k] = fc[k];
+        c->coll_cutover[SHM_COLL_BROADCAST][k] = bc[k];
+    }
+}
+
+int check_collective(int collective)
+{
+    if (collective != SHM_COLL_FCOLLECT && collective != SHM_COLL_BROADCAST) return fail(SHM_EINVAL, "unknown collective %d", collective);
+    return SHM_OK;
+}
+
+// AUTO for a collective: the push kernel below the collective's own threshold, runtime copies from it on.
+int resolve_collective_path(const shm_ctx *c, int collective, int path, size_t bytes_per_pe, int n_wg, int *out)
+{
+    if (path != SHM_PATH_AUTO) return resolve_path(c, path, bytes_per_pe, n_wg, out);
+    *out = bytes_per_pe >= c->coll_cutover[collective][wg_class(n_wg)] ? SHM_PATH_MEMCPY : SHM_PATH_LDST;
     return SHM_OK;
 }
 
@@ -408,6 +437,7 @@ int shm_init_ex(int npes, size_t heap_bytes, void *heap_base, void *const *strea
     c->part_bytes = heap_bytes;
     c->user_bytes = heap_bytes - SHM_INTERNAL_BYTES;
     c->alloc.reset(c->user_bytes);
+    default_collective_cutovers(c);
     c->no_device = (flags & SHM_INIT_NO_DEVICE) != 0;
     if (c->no_device) {
         if (!heap_base) {
@@ -642,6 +672,34 @@ int shm_choose_path(const shm_ctx *c, size_t n, int n_wg, int *path)
     if (int r = check_n_wg(n_wg)) return r;
     if (!path) return fail(SHM_EINVAL, "null out pointer");
     return resolve_path(c, SHM_PATH_AUTO, n, n_wg, path);
+}
+
+int shm_set_collective_cutover(shm_ctx *c, int collective, int n_wg, size_t bytes)
+{
+    if (int r = check_ctx(c)) return r;
+    if (int r = check_collective(collective)) return r;
+    if (int r = check_n_wg(n_wg)) return r;
+    c->coll_cutover[collective][wg_class(n_wg)] = bytes;
+    return SHM_OK;
+}
+
+int shm_get_collective_cutover(const shm_ctx *c, int collective, int n_wg, size_t *bytes)
+{
+    if (int r = check_ctx(c)) return r;
+    if (int r = check_collective(collective)) return r;
+    if (int r = check_n_wg(n_wg)) return r;
+    if (!bytes) return fail(SHM_EINVAL, "null out pointer");
+    *bytes = c->coll_cutover[collective][wg_class(n_wg)];
+    return SHM_OK;
+}
+
+int shm_choose_collective_path(const shm_ctx *c, int collective, size_t bytes_per_pe, int n_wg, int *path)
+{
+    if (int r = check_ctx(c)) return r;
+    if (int r = check_collective(collective)) return r;
+    if (int r = check_n_wg(n_wg)) return r;
+    if (!path) return fail(SHM_EINVAL, "null out pointer");
+    return resolve_collective_path(c, collective, SHM_PATH_AUTO, bytes_per_pe, n_wg, path);
 }
 
 int shm_set_wait_timeout_us(shm_ctx *c, uint64_t us)
@@ -1078,7 +1136,7 @@ int shm_launch_fcollect(shm_ctx *c, uint64_t dst_off, uint64_t src_off, size_t b
         return fail(SHM_EINVAL, "source and destination overlap");
     if (int r = check_n_wg(n_wg)) return r;
     int use;
-    if (int r = resolve_path(c, path, bytes_per_pe, n_wg, &use)) return r;
+    if (int r = resolve_collective_path(c, SHM_COLL_FCOLLECT, path, bytes_per_pe, n_wg, &use)) return r;
     if (c->no_device) return no_device("shm_launch_fcollect");
     if (bytes_per_pe == 0) return SHM_OK;
     if (int r = drain_all_engines(c)) return r;
@@ -1224,7 +1282,7 @@ int shm_launch_broadcast(shm_ctx *c, uint64_t dst_off, uint64_t src_off, size_t 
     if (overlaps(dst_off, src_off, n)) return fail(SHM_EINVAL, "source and destination overlap");
     if (int r = check_n_wg(n_wg)) return r;
     int use;
-    if (int r = resolve_path(c, path, n, n_wg, &use)) return r;
+    if (int r = resolve_collective_path(c, SHM_COLL_BROADCAST, path, n, n_wg, &use)) return r;
     if (c->no_device) return no_device("shm_launch_broadcast");
     if (int r = drain_all_engines(c)) return r;
     if (n == 0) return SHM_OK;

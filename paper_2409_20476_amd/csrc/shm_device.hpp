@@ -979,6 +979,44 @@ __device__ __forceinline__ void shmx_barrier_all_wg(const shm_dev_ctx &c, int me
 __device__ __forceinline__ void shmx_broadcast_push(const shm_dev_ctx &c, int root, uint64_t dst_off, uint64_t src_off, size_t n,
                                                     unsigned part, unsigned nparts)
 {
+    if (((dst_off | src_off) & 15) == 0) {
+        // 16-byte-aligned block: every source vector is loaded once and stored to all PEs (inner loop
+        // over destinations, the right-hand neighbour first, the root's own copy last); U loads in
+        // flight per thread, consecutive threads on consecutive vectors.
+        constexpr int U = 4;
+        __syncthreads();
+        const char *src = shm_ptr(c, src_off, root);
+        const shm_u32x4 *s = reinterpret_cast<const shm_u32x4 *>(src);
+        const size_t nvec = n >> 4, gthr = static_cast<size_t>(nparts) * blockDim.x;
+        size_t i = static_cast<size_t>(part) * blockDim.x + threadIdx.x;
+        for (; i + (U - 1) * gthr < nvec; i += U * gthr) {
+            shm_u32x4 r[U];
+#pragma unroll
+            for (int u = 0; u < U; ++u) r[u] = shm_ld16(s + i + u * gthr);
+            for (int j = 0; j < c.npes; ++j) {
+                int q = root + 1 + j;
+                if (q >= c.npes) q -= c.npes;
+                shm_u32x4 *d = reinterpret_cast<shm_u32x4 *>(shm_ptr(c, dst_off, q));
+#pragma unroll
+                for (int u = 0; u < U; ++u) shm_st16(d + i + u * gthr, r[u]);
+            }
+        }
+        for (; i < nvec; i += gthr) {
+            const shm_u32x4 r = shm_ld16(s + i);
+            for (int j = 0; j < c.npes; ++j) {
+                int q = root + 1 + j;
+                if (q >= c.npes) q -= c.npes;
+                shm_st16(reinterpret_cast<shm_u32x4 *>(shm_ptr(c, dst_off, q)) + i, r);
+            }
+        }
+        if (part == 0)
+            for (size_t b = (nvec << 4) + threadIdx.x; b < n; b += blockDim.x) {       // the last n mod 16 bytes
+                const char v = src[b];
+                for (int q = 0; q < c.npes; ++q) shm_ptr(c, dst_off, q)[b] = v;
+            }
+        __syncthreads();
+        return;
+    }
     for (int j = 0; j < c.npes; ++j) {
         int q = root + 1 + j;           // the right-hand neighbour first, the root's own copy last
         if (q >= c.npes) q -= c.npes;

@@ -27,6 +27,7 @@ SHM_INIT_DEFAULT, SHM_INIT_NO_DEVICE = 0, 1
  SHM_AMO_INC) = range(8)
 SHM_STORM_FETCH_ADD, SHM_STORM_ADD, SHM_STORM_CSWAP_LOOP, SHM_STORM_PLAIN_STORE = range(4)
 SHM_REDUCE_DUPLICATE, SHM_REDUCE_SPLIT = 0, 1
+SHM_COLL_FCOLLECT, SHM_COLL_BROADCAST = 0, 1
 SHM_NO_CONSUME = (1 << 64) - 1
 SHM_CUTOVER_TUNED = (1 << 64) - 2
 SHM_OP_MIN, SHM_OP_MAX, SHM_OP_SUM, SHM_OP_PROD, SHM_OP_AND, SHM_OP_OR, SHM_OP_XOR = range(7)
@@ -59,6 +60,9 @@ PROTOTYPES = {
     "shm_set_cutover": (c_int, [c_void_p, c_int, c_size_t]),
     "shm_get_cutover": (c_int, [c_void_p, c_int, _szp]),
     "shm_choose_path": (c_int, [c_void_p, c_size_t, c_int, _ip]),
+    "shm_set_collective_cutover": (c_int, [c_void_p, c_int, c_int, c_size_t]),
+    "shm_get_collective_cutover": (c_int, [c_void_p, c_int, c_int, _szp]),
+    "shm_choose_collective_path": (c_int, [c_void_p, c_int, c_size_t, c_int, _ip]),
     "shm_set_wait_timeout_us": (c_int, [c_void_p, c_uint64]),
     "shm_set_team_sync": (c_int, [c_void_p, c_int]),
     "shm_launch_wg_put": (c_int, [c_void_p, c_int, c_int, c_uint64, c_uint64, c_size_t, c_int, c_int]),
@@ -225,6 +229,19 @@ class Shm:
     def get_cutover(self, n_wg: int) -> int:
         v = c_size_t()
         self._check(self.lib.shm_get_cutover(self.ctx, n_wg, byref(v)))
+        return v.value
+
+    def set_collective_cutover(self, collective: int, n_wg: int, nbytes: int):
+        self._check(self.lib.shm_set_collective_cutover(self.ctx, collective, n_wg, nbytes))
+
+    def get_collective_cutover(self, collective: int, n_wg: int) -> int:
+        v = c_size_t()
+        self._check(self.lib.shm_get_collective_cutover(self.ctx, collective, n_wg, byref(v)))
+        return v.value
+
+    def choose_collective_path(self, collective: int, bytes_per_pe: int, n_wg: int) -> int:
+        v = c_int()
+        self._check(self.lib.shm_choose_collective_path(self.ctx, collective, bytes_per_pe, n_wg, byref(v)))
         return v.value
 
     def choose_path(self, n: int, n_wg: int) -> int:

@@ -213,3 +213,31 @@ def test_cutover_policy_classes():
     with pytest.raises(S.ShmError):
         g.get_cutover(0)
     g.finalize()
+
+
+def test_collective_cutover_depends_on_collective_groups_and_pes():
+    """The collectives have thresholds of their own (bytes per PE), tuned per collective and, for
+    fcollect, by the number of PEs; above them AUTO takes host-started runtime copies."""
+    never = (1 << 64) - 1
+    FC, BC = S.SHM_COLL_FCOLLECT, S.SHM_COLL_BROADCAST
+    for npes, want in [(2, [MiB // 2, 2 * MiB, never, never]), (4, [MiB // 2, 2 * MiB, never, never]),
+                       (5, [2 * MiB, 8 * MiB, never, never]), (12, [2 * MiB, 8 * MiB, never, never])]:
+        g = _ctx(npes)
+        assert [g.get_collective_cutover(FC, w) for w in (1, 4, 64, 1024)] == want
+        assert [g.get_collective_cutover(BC, w) for w in (1, 4, 64, 1024)] == [MiB // 4, MiB, 16 * MiB, never]
+        g.finalize()
+    g = _ctx(8)
+    assert g.choose_collective_path(FC, 2 * MiB - 1, 1) == S.SHM_PATH_LDST and g.choose_collective_path(FC, 2 * MiB, 1) == S.SHM_PATH_MEMCPY
+    assert g.choose_collective_path(FC, 8 * MiB, 2) == S.SHM_PATH_MEMCPY and g.choose_collective_path(FC, 1 << 40, 5) == S.SHM_PATH_LDST
+    assert g.choose_collective_path(BC, MiB // 4, 1) == S.SHM_PATH_MEMCPY and g.choose_collective_path(BC, MiB // 4, 2) == S.SHM_PATH_LDST
+    assert g.choose_collective_path(BC, 16 * MiB, 64) == S.SHM_PATH_MEMCPY and g.choose_collective_path(BC, 1 << 40, 65) == S.SHM_PATH_LDST
+    g.set_collective_cutover(FC, 64, 4096)
+    assert g.get_collective_cutover(FC, 33) == 4096 and g.get_collective_cutover(BC, 33) == 16 * MiB      # one table per collective
+    assert g.choose_collective_path(FC, 4096, 64) == S.SHM_PATH_MEMCPY and g.choose_collective_path(FC, 4095, 64) == S.SHM_PATH_LDST
+    assert g.get_cutover(64) == never                                                                      # the put policy is untouched
+    for bad in (lambda: g.get_collective_cutover(2, 1), lambda: g.set_collective_cutover(-1, 1, 0), lambda: g.get_collective_cutover(FC, 0),
+                lambda: g.choose_collective_path(7, 100, 1)):
+        with pytest.raises(S.ShmError) as e:
+            bad()
+        assert e.value.code == S.SHM_EINVAL
+    g.finalize()

@@ -40,7 +40,8 @@ def test_sync_all_counts_and_is_timed():
 
 @pytest.mark.parametrize("path", [S.SHM_PATH_LDST, S.SHM_PATH_SDMA, S.SHM_PATH_MEMCPY])
 @pytest.mark.parametrize("npes,n,root,n_wg,soff,doff", [(8, 100003, 3, 4, 5, 9), (2, 16, 1, 1, 0, 0), (5, 3 * MiB + 64, 0, 64, 0, 0),
-                                                       (4, 0, 2, 8, 0, 0)])
+                                                       (4, 0, 2, 8, 0, 0), (3, 100003, 1, 7, 16, 32), (16, 65536 + 5, 15, 2, 0, 48),
+                                                       (1, 1000, 0, 3, 0, 0), (6, 4 * 256 * 16 * 5 + 7, 2, 5, 0, 0)])
 def test_broadcast(path, npes, n, root, n_wg, soff, doff):
     g, o = make_pair(npes, 16 * MiB)
     with g:
@@ -66,3 +67,23 @@ def test_collect(npes, sizes, n_wg, soff, doff):
         assert_heaps_equal(g, o, upto=12 * MiB)
         with pytest.raises(S.ShmError):
             g.launch_collect(dst, src, [16 * MiB] + [0] * (npes - 1), n_wg)
+
+
+def test_collectives_on_auto_follow_their_own_cutover():
+    """AUTO below and above the collective's threshold (moved down so that small cases cross it):
+    the same bytes either way, and the answer of shm_choose_collective_path changes at the threshold."""
+    g, o = make_pair(4, 16 * MiB)
+    FC, BC = S.SHM_COLL_FCOLLECT, S.SHM_COLL_BROADCAST
+    with g:
+        fill_random(g, o, 44, upto=12 * MiB)
+        g.set_collective_cutover(FC, 2, 50000)
+        g.set_collective_cutover(BC, 8, 70000)
+        assert g.choose_collective_path(FC, 49999, 2) == S.SHM_PATH_LDST and g.choose_collective_path(FC, 50000, 2) == S.SHM_PATH_MEMCPY
+        assert g.choose_collective_path(BC, 69999, 8) == S.SHM_PATH_LDST and g.choose_collective_path(BC, 70000, 8) == S.SHM_PATH_MEMCPY
+        for n in (49999, 50000, 300007):
+            g.launch_fcollect(2 * MiB + 3, 256 + 1, n, 2, S.SHM_PATH_AUTO)
+            o.fcollect(2 * MiB + 3, 256 + 1, n)
+            g.launch_broadcast(6 * MiB + 5, 1024 + n % 7, n + 20000, n % 4, 8, S.SHM_PATH_AUTO)     # 69999, 70000, 320007 bytes
+            o.broadcast(6 * MiB + 5, 1024 + n % 7, n + 20000, n % 4)
+            g.barrier_all()
+            assert_heaps_equal(g, o, upto=12 * MiB, what=f"n {n}")
