@@ -521,7 +521,29 @@ __global__ __launch_bounds__(SHMK_WG) void shmk_fcollect_vec(shm_dev_ctx c, uint
     constexpr size_t rowv = 2048, tilev = rowv * U;
     const size_t ntiles = (nvec + tilev - 1) / tilev;
     const unsigned wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-    for (size_t t = blockIdx.x; t < ntiles; t += gridDim.x) {
+    // Which share this group takes is rotated by the PE number: the group that takes PE p's first
+    // share is number p (mod groups per PE), so that the first shares of the PEs -- all there is
+    // to do in a short block -- sit on different XCDs instead of all on the first one.
+    const unsigned first = (blockIdx.x + gridDim.x - static_cast<unsigned>(p) % gridDim.x) % gridDim.x;
+    if (ntiles < gridDim.x) {
+        // Short block, fewer tiles than groups: deal rows of one vector per thread instead, so that
+        // as many groups as there are rows take part.
+        for (size_t i = static_cast<size_t>(first) * SHMK_WG + threadIdx.x; i < nvec; i += static_cast<size_t>(gridDim.x) * SHMK_WG) {
+            const shm_u32x4 r = shm_ld16(s + i);
+            if (NPES) {
+#pragma unroll
+                for (int j = 0; j < NQ; ++j) shm_st16(dq[j] + i, r);
+            } else {
+                for (int j = 0; j < npes; ++j) {
+                    int q = p + 1 + j;
+                    if (q >= npes) q -= npes;
+                    shm_st16(reinterpret_cast<shm_u32x4 *>(shm_ptr(c, d0, q)) + i, r);
+                }
+            }
+        }
+        return;
+    }
+    for (size_t t = first; t < ntiles; t += gridDim.x) {
         if ((t + 1) * tilev <= nvec) {            // whole tile: no predicates anywhere in the hot loop
 #pragma unroll
             for (unsigned cc = 0; cc < 8; ++cc) {
