@@ -21,12 +21,14 @@ constexpr uint32_t ARRIVE_SLOTS = 4096;                       // 8-byte arrival 
 static_assert(ARRIVE_SLOTS * 8 <= SHM_INTERNAL_BYTES, "arrival counters must fit the internal tail");
 static_assert(SHM_WG_SIZE == SHMK_WG, "one work-group size everywhere");
 constexpr int MAX_N_WG = 1 << 20;
-// Group-owned tiles pay off for long messages moved by enough groups (measured on MI355X, 8 PEs:
-// from 8 MiB with 64 groups per PE, from 64 MiB with 1024; with 4 groups the 8-group virtual blocks
-// stay ahead at every size).
+// Group-owned tiles pay off for long messages moved by a grid that fills the chip (measured on
+// MI355X from 8 MiB: a team grid of 8 PEs x 64 or more groups gains 5-10 %, a grid of 1024 groups
+// of one PE about the same from 64 MiB; a grid of 32-256 groups -- one PE launching alone -- loses
+// 17-47 % against the 8-group virtual blocks, which keep four times as many loads in flight per
+// group, and stays on those).
 constexpr size_t TILES_MIN_BYTES = 8u << 20;
 constexpr size_t TILES_MIN_BYTES_PER_GROUP = 64u << 10;
-constexpr int TILES_MIN_GROUPS = 32;
+constexpr long long TILES_MIN_GRID_GROUPS = 512;
 constexpr unsigned TILES_LDS_BYTES = 54000;                   // unused LDS that caps a CU at 3 resident groups
 constexpr uint64_t OFFLOAD_COUNTERS = 32768;                  // offset of the ring's three index words in PE 0's internal tail
 static_assert(ARRIVE_SLOTS * 8 <= OFFLOAD_COUNTERS && OFFLOAD_COUNTERS + 24 <= SHMD_INTERNAL_SYNC_COUNT &&
@@ -293,10 +295,10 @@ int sdma_copy(shm_ctx *c, int on_pe, int dst_pe, uint64_t dst_off, int src_pe, u
     return SHM_OK;
 }
 
-// Long, 16-byte-aligned messages take the group-owned-tile kernel.
-bool use_tiles(uint64_t dst_off, uint64_t src_off, size_t n, int n_wg)
+// Long, 16-byte-aligned messages moved by a grid of grid_pes x n_wg groups take the group-owned-tile kernel.
+bool use_tiles(uint64_t dst_off, uint64_t src_off, size_t n, int n_wg, int grid_pes)
 {
-    return ((dst_off | src_off) & 15) == 0 && n_wg >= TILES_MIN_GROUPS && n >= TILES_MIN_BYTES &&
+    return ((dst_off | src_off) & 15) == 0 && static_cast<long long>(n_wg) * grid_pes >= TILES_MIN_GRID_GROUPS && n >= TILES_MIN_BYTES &&
            n / static_cast<size_t>(n_wg) >= TILES_MIN_BYTES_PER_GROUP;
 }
 
@@ -318,7 +320,7 @@ int wg_rma(shm_ctx *c, int me, int pe, uint64_t dst_off, uint64_t src_off, size_
         return is_get ? transfer_copy(c, use, me, me, dst_off, pe, src_off, n) : transfer_copy(c, use, me, pe, dst_off, me, src_off, n);
     if (int r = drain_engines(c, me)) return r;
     const int shift = (pe - me + c->npes) % c->npes;
-    if (use_tiles(dst_off, src_off, n, n_wg)) {
+    if (use_tiles(dst_off, src_off, n, n_wg, 1)) {
         hipLaunchKernelGGL(shmk_wg_rma_tiles, dim3(n_wg, 1), dim3(SHMK_WG), TILES_LDS_BYTES, c->stream[me], dev_view(c), dst_off, src_off,
                            n, me, shift, is_get);
         return launched("work-group put/get (tiles)");
@@ -356,7 +358,7 @@ int wg_rma_all(shm_ctx *c, int pe_shift, uint64_t dst_off, uint64_t src_off, siz
     }
     if (c->team_sync)
         if (int r = team_join(c)) return r;
-    if (use_tiles(dst_off, src_off, n, n_wg)) {
+    if (use_tiles(dst_off, src_off, n, n_wg, c->npes)) {
         hipLaunchKernelGGL(shmk_wg_rma_tiles, dim3(n_wg, c->npes), dim3(SHMK_WG), TILES_LDS_BYTES, c->stream[0], dev_view(c), dst_off,
                            src_off, n, 0, pe_shift, is_get);
     } else {
@@ -747,7 +749,7 @@ int shm_launch_wg_put_timed(shm_ctx *c, int me, int pe, uint64_t dst_off, uint64
     if (!dev_ticks) return fail(SHM_EINVAL, "null tick buffer");
     if (c->no_device) return no_device("shm_launch_wg_put_timed");
     if (int r = drain_engines(c, me)) return r;
-    const bool tiles = use_tiles(dst_off, src_off, n, n_wg);
+    const bool tiles = use_tiles(dst_off, src_off, n, n_wg, 1);
     hipLaunchKernelGGL(shmk_wg_put_timed, dim3(n_wg), dim3(SHMK_WG), tiles ? TILES_LDS_BYTES : 0, c->stream[me], dev_view(c), dst_off,
                        src_off, n, me, pe, reps, reinterpret_cast<unsigned long long *>(dev_ticks), tiles ? 1 : 0);
     return launched("timed work-group put");

@@ -131,38 +131,48 @@ def test_timed_put_moves_the_same_bytes_and_reports_device_time():
         assert 0 < us < 1e5, us
 
 
-def test_timed_put_of_a_long_message_uses_tiles_and_moves_the_same_bytes():
+def test_timed_put_of_long_messages_moves_the_same_bytes_on_both_long_message_paths():
+    """9 MiB by 64 groups stays on the virtual blocks, 33 MiB by 512 groups takes group-owned tiles."""
     import torch
-    g, o = make_pair(2, 32 * MiB)
+    g, o = make_pair(2, 80 * MiB)
     with g:
-        fill_random(g, o, 7, upto=28 * MiB)
-        ticks = torch.zeros(2, dtype=torch.int64, device="cuda")
-        ticks[0] = -1
-        n = 9 * MiB + 16 * 3 + 5                  # ragged last tile and a byte tail
-        g.launch_wg_put_timed(0, 1, 14 * MiB + 16, 32, n, 64, 3, ticks)
-        g.quiet(0)
-        o.wg_put(0, 14 * MiB + 16, 32, n, 1, 64)
-        assert_heaps_equal(g, o, upto=28 * MiB)
+        fill_random(g, o, 7, upto=72 * MiB)
+        for n, n_wg in [(9 * MiB + 16 * 3 + 5, 64), (33 * MiB + 16 * 3 + 5, 512)]:      # ragged last tile and a byte tail
+            ticks = torch.zeros(2, dtype=torch.int64, device="cuda")
+            ticks[0] = -1
+            g.launch_wg_put_timed(0, 1, 36 * MiB + 16, 32, n, n_wg, 3, ticks)
+            g.quiet(0)
+            o.wg_put(0, 36 * MiB + 16, 32, n, 1, n_wg)
+            assert_heaps_equal(g, o, upto=72 * MiB, what=f"n {n} by {n_wg} groups")
 
 
-@pytest.mark.parametrize("n_wg", [32, 33, 100, 160])
-def test_long_messages_take_group_owned_tiles(n_wg):
-    """8 MiB or more, 32 groups or more, 64 KiB or more per group, 16-byte-aligned offsets: every
-    group owns whole 64 KiB tiles.  Ragged last tile, byte tail, put and get, team form."""
-    g, o = make_pair(4, 32 * MiB)
+@pytest.mark.parametrize("n_wg", [512, 515, 600])
+def test_long_messages_by_a_chip_filling_grid_take_group_owned_tiles(n_wg):
+    """8 MiB or more, 512 groups or more in the grid, 64 KiB or more per group, 16-byte-aligned
+    offsets: every group owns whole 64 KiB tiles.  Ragged last tile, byte tail, put and get."""
+    g, o = make_pair(2, 96 * MiB)
     with g:
-        fill_random(g, o, 8, upto=28 * MiB)
-        sizes = [10 * MiB, 10 * MiB + 48, 11 * MiB + 131072 + 16, 10 * MiB + 7, 12 * MiB]
+        fill_random(g, o, 8, upto=90 * MiB)
+        sizes = [38 * MiB, 38 * MiB + 48, 39 * MiB + 131072 + 16, 38 * MiB + 7]
         for rep, n in enumerate(sizes):
-            me, pe = rep % 4, (rep + 1) % 4
-            src, dst = 4096 + 16 * rep, 14 * MiB + 32 * rep
+            me, pe = rep % 2, (rep + 1) % 2
+            src, dst = 4096 + 16 * rep, 45 * MiB + 32 * rep
             g.launch_wg_put(me, pe, dst, src, n, n_wg)
             o.wg_put(me, dst, src, n, pe, n_wg)
             g.quiet(me)
             g.launch_wg_get(pe, me, 64, dst, n, n_wg)           # read it back into the start of the caller's heap
             o.wg_get(pe, 64, dst, n, me, n_wg)
             g.quiet(pe)
-            assert_heaps_equal(g, o, upto=28 * MiB, what=f"n_wg {n_wg} size {n}")
+            assert_heaps_equal(g, o, upto=90 * MiB, what=f"n_wg {n_wg} size {n}")
+
+
+@pytest.mark.parametrize("n_wg", [32, 33, 100, 128, 160])
+def test_long_messages_team_forms_on_both_long_message_paths(n_wg):
+    """Team grids of 4 PEs: below 512 groups in the grid (32, 33, 100 per PE) the virtual blocks, from
+    128 per PE group-owned tiles; put_all and get_all, ragged last tile and byte tail."""
+    g, o = make_pair(4, 32 * MiB)
+    with g:
+        fill_random(g, o, 8, upto=28 * MiB)
         n = 11 * MiB + 65536 + 5
         g.launch_wg_put_all(3, 14 * MiB, 0, n, n_wg)
         for p in range(4):
