@@ -667,7 +667,32 @@ __global__ __launch_bounds__(SHMK_WG) void shmk_reduce_sum_f32_vec(shm_dev_ctx c
 #pragma unroll
         for (int u = 0; u < U; ++u)
             r[u] = load(reinterpret_cast<const shm_f32x4 *>(shm_ptr(c, so, 0)) + i + u * k.rowv);
-        for (int p = 1; p < npes; ++p) {
+        // The other PEs' vectors four PEs at a time (then two, then one): the loads of a batch are
+        // all issued before the first add waits for one, the adds stay in PE order.
+        int p = 1;
+        for (; p + 3 < npes; p += 4) {
+            shm_f32x4 v[4][U];
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+#pragma unroll
+                for (int u = 0; u < U; ++u) v[j][u] = load(reinterpret_cast<const shm_f32x4 *>(shm_ptr(c, so, p + j)) + i + u * k.rowv);
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+#pragma unroll
+                for (int u = 0; u < U; ++u) r[u].x += v[j][u].x, r[u].y += v[j][u].y, r[u].z += v[j][u].z, r[u].w += v[j][u].w;
+        }
+        for (; p + 1 < npes; p += 2) {
+            shm_f32x4 v[2][U];
+#pragma unroll
+            for (int j = 0; j < 2; ++j)
+#pragma unroll
+                for (int u = 0; u < U; ++u) v[j][u] = load(reinterpret_cast<const shm_f32x4 *>(shm_ptr(c, so, p + j)) + i + u * k.rowv);
+#pragma unroll
+            for (int j = 0; j < 2; ++j)
+#pragma unroll
+                for (int u = 0; u < U; ++u) r[u].x += v[j][u].x, r[u].y += v[j][u].y, r[u].z += v[j][u].z, r[u].w += v[j][u].w;
+        }
+        for (; p < npes; ++p) {
             const shm_f32x4 *sp = reinterpret_cast<const shm_f32x4 *>(shm_ptr(c, so, p));
             shm_f32x4 v[U];
 #pragma unroll
@@ -817,7 +842,40 @@ __global__ __launch_bounds__(SHMK_WG) void shmk_reduce(shm_dev_ctx c, uint64_t d
         vec r0, r1;
         r0.v = load(reinterpret_cast<const shm_u32x4 *>(shm_ptr(c, src_off, 0)) + i);
         r1.v = load(reinterpret_cast<const shm_u32x4 *>(shm_ptr(c, src_off, 0)) + i + SHMK_WG);
-        for (int p = 1; p < npes; ++p) {
+        // the other PEs' vectors four PEs at a time, then two, then one: a batch's loads are all
+        // issued before the first fold waits for one; the folds stay in PE order
+        int p = 1;
+        for (; p + 3 < npes; p += 4) {
+            vec x0[4], x1[4];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                x0[j].v = load(reinterpret_cast<const shm_u32x4 *>(shm_ptr(c, src_off, p + j)) + i);
+                x1[j].v = load(reinterpret_cast<const shm_u32x4 *>(shm_ptr(c, src_off, p + j)) + i + SHMK_WG);
+            }
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+#pragma unroll
+                for (int k = 0; k < EPV; ++k) r0.e[k] = shmk_combine<T, OP>(r0.e[k], x0[j].e[k]);
+#pragma unroll
+                for (int k = 0; k < EPV; ++k) r1.e[k] = shmk_combine<T, OP>(r1.e[k], x1[j].e[k]);
+            }
+        }
+        for (; p + 1 < npes; p += 2) {
+            vec x0[2], x1[2];
+#pragma unroll
+            for (int j = 0; j < 2; ++j) {
+                x0[j].v = load(reinterpret_cast<const shm_u32x4 *>(shm_ptr(c, src_off, p + j)) + i);
+                x1[j].v = load(reinterpret_cast<const shm_u32x4 *>(shm_ptr(c, src_off, p + j)) + i + SHMK_WG);
+            }
+#pragma unroll
+            for (int j = 0; j < 2; ++j) {
+#pragma unroll
+                for (int k = 0; k < EPV; ++k) r0.e[k] = shmk_combine<T, OP>(r0.e[k], x0[j].e[k]);
+#pragma unroll
+                for (int k = 0; k < EPV; ++k) r1.e[k] = shmk_combine<T, OP>(r1.e[k], x1[j].e[k]);
+            }
+        }
+        for (; p < npes; ++p) {
             vec x0, x1;
             x0.v = load(reinterpret_cast<const shm_u32x4 *>(shm_ptr(c, src_off, p)) + i);
             x1.v = load(reinterpret_cast<const shm_u32x4 *>(shm_ptr(c, src_off, p)) + i + SHMK_WG);
