@@ -21,6 +21,10 @@
  * Errors: every int function returns SHM_OK (0) or a negative code; nothing throws
  * or aborts.  shm_last_error() gives a thread-local text for the last failure.
  *
+ * Work-groups: n_wg is 1 .. 2^20 groups of SHM_WG_SIZE threads unless an entry point
+ * states a narrower range.  The team and collective entry points launch n_wg groups
+ * for EACH PE as one grid, which must stay below 2^32 threads (n_wg * npes < 2^24).
+ *
  * Completion: shm_launch_* and shm_putmem/shm_getmem are asynchronous on the
  * stream of the calling PE (team launches: on the team stream, PE 0's).  They are
  * complete, and their effects visible to every PE and to shm_read, after

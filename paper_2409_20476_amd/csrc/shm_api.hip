@@ -140,6 +140,15 @@ int check_n_wg(int n_wg)
     return SHM_OK;
 }
 
+// A team grid has n_wg x npes groups; a grid may not have 2^32 threads or more.
+int check_team_grid(const shm_ctx *c, int n_wg)
+{
+    if (int r = check_n_wg(n_wg)) return r;
+    if (static_cast<long long>(n_wg) * c->npes * SHMK_WG >= (1ll << 32))
+        return fail(SHM_EINVAL, "%d groups for each of %d PEs exceed what one grid can hold (2^32 threads)", n_wg, c->npes);
+    return SHM_OK;
+}
+
 bool overlaps(uint64_t a, uint64_t b, size_t n) { return n && a < b + n && b < a + n; }
 
 int wg_class(int n_wg) { return n_wg <= 1 ? 0 : n_wg <= 4 ? 1 : n_wg <= 64 ? 2 : 3; }
@@ -335,7 +344,7 @@ int wg_rma_all(shm_ctx *c, int pe_shift, uint64_t dst_off, uint64_t src_off, siz
     if (int r = check_ctx(c)) return r;
     if (pe_shift < 0 || pe_shift >= c->npes) return fail(SHM_EPE, "pe_shift %d outside 0..%d", pe_shift, c->npes - 1);
     if (int r = rma_args(c, 0, pe_shift, dst_off, src_off, n)) return r;   // shift 0 = every PE targets itself
-    if (int r = check_n_wg(n_wg)) return r;
+    if (int r = check_team_grid(c, n_wg)) return r;
     int use;
     if (int r = resolve_path(c, path, n, n_wg, &use)) return r;
     if (c->no_device) return no_device("team put/get");
@@ -1136,7 +1145,7 @@ int shm_launch_fcollect(shm_ctx *c, uint64_t dst_off, uint64_t src_off, size_t b
     if (int r = check_range(c, dst_off, total, "destination")) return r;
     if (bytes_per_pe && src_off < dst_off + total && dst_off < src_off + bytes_per_pe)
         return fail(SHM_EINVAL, "source and destination overlap");
-    if (int r = check_n_wg(n_wg)) return r;
+    if (int r = check_team_grid(c, n_wg)) return r;
     int use;
     if (int r = resolve_collective_path(c, SHM_COLL_FCOLLECT, path, bytes_per_pe, n_wg, &use)) return r;
     if (c->no_device) return no_device("shm_launch_fcollect");
@@ -1193,7 +1202,7 @@ int shm_launch_collect(shm_ctx *c, uint64_t dst_off, uint64_t src_off, const siz
     if (int r = check_range(c, src_off, largest, "source")) return r;
     if (total && largest && src_off < dst_off + total && dst_off < src_off + largest)
         return fail(SHM_EINVAL, "source and destination overlap");
-    if (int r = check_n_wg(n_wg)) return r;
+    if (int r = check_team_grid(c, n_wg)) return r;
     if (c->no_device) return no_device("shm_launch_collect");
     if (int r = drain_all_engines(c)) return r;
     if (total == 0) return SHM_OK;
@@ -1220,7 +1229,7 @@ int shm_launch_reduce(shm_ctx *c, uint64_t dst_off, uint64_t src_off, size_t nel
     if (int r = check_range(c, dst_off, nelems * elem, "destination")) return r;
     if ((src_off | dst_off) & 15) return fail(SHM_EINVAL, "reduction buffers must be 16-byte aligned");
     if (overlaps(dst_off, src_off, nelems * elem)) return fail(SHM_EINVAL, "source and destination overlap");
-    if (int r = check_n_wg(n_wg)) return r;
+    if (int r = check_team_grid(c, n_wg)) return r;
     if (c->no_device) return no_device("shm_launch_reduce");
     if (int r = drain_all_engines(c)) return r;
     if (nelems == 0) return SHM_OK;
@@ -1318,7 +1327,7 @@ int shm_launch_reduce_sum_f32(shm_ctx *c, uint64_t dst_off, uint64_t src_off, si
     if (int r = check_range(c, dst_off, nelems * 4, "destination")) return r;
     if ((src_off | dst_off) & 3) return fail(SHM_EINVAL, "float32 vectors must be 4-byte aligned");
     if (overlaps(dst_off, src_off, nelems * 4)) return fail(SHM_EINVAL, "source and destination overlap");
-    if (int r = check_n_wg(n_wg)) return r;
+    if (int r = check_team_grid(c, n_wg)) return r;
     if (algo != SHM_REDUCE_DUPLICATE && algo != SHM_REDUCE_SPLIT) return fail(SHM_EINVAL, "unknown reduce algorithm %d", algo);
     if (c->no_device) return no_device("shm_launch_reduce_sum_f32");
     if (int r = drain_all_engines(c)) return r;

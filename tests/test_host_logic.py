@@ -241,3 +241,22 @@ def test_collective_cutover_depends_on_collective_groups_and_pes():
             bad()
         assert e.value.code == S.SHM_EINVAL
     g.finalize()
+
+
+def test_team_grids_are_bounded_by_what_one_launch_can_hold():
+    """n_wg groups for each of npes PEs run as ONE grid, which may not reach 2^32 threads."""
+    g = _ctx(32, MiB)
+    ok, too_many = 1 << 18, 1 << 19                    # 2^19 groups x 32 PEs x 256 threads = 2^32
+    for call in (lambda w: g.launch_wg_put_all(1, 4096, 0, 100, w), lambda w: g.launch_fcollect(8192, 0, 100, w),
+                 lambda w: g.launch_collect(8192, 0, [10] * 32, w), lambda w: g.launch_reduce(8192, 0, 100, S.SHM_INT32, S.SHM_OP_SUM, w),
+                 lambda w: g.launch_reduce_sum_f32(8192, 0, 100, w)):
+        with pytest.raises(S.ShmError) as e:
+            call(ok)
+        assert e.value.code == S.SHM_ENODEV
+        with pytest.raises(S.ShmError) as e:
+            call(too_many)
+        assert e.value.code == S.SHM_EINVAL
+    with pytest.raises(S.ShmError) as e:
+        g.launch_wg_put(0, 1, 4096, 0, 100, 1 << 20)   # one PE's own grid may have 2^20 groups
+    assert e.value.code == S.SHM_ENODEV
+    g.finalize()
