@@ -319,7 +319,8 @@ int shm_launch_ring_pipeline(shm_ctx *ctx, uint64_t src_off, uint64_t slot_off, 
  * i.e. the int64 counter at ctr_off + 8*index on that PE.  kind: FETCH_ADD(+1) | ADD(+1, no
  * return) | CSWAP_LOOP (increment built from compare-swap) | PLAIN_STORE (not atomic; a timing
  * ceiling only).  dev_fetched (or NULL): [n_items*ops_per_item] fetched values.  dev_checksum (or
- * NULL): one uint64 per work-group, the sum of what its items fetched. */
+ * NULL): one uint64 per work-group, the sum of what its items fetched.  n_items is 1 .. 2^32 - 256
+ * (one grid); n_ctr * npes <= 65536; ops_per_item 1 .. 4096; dev_targets 16-byte aligned. */
 int shm_launch_amo_storm(shm_ctx *ctx, uint64_t ctr_off, int n_ctr, const uint16_t *dev_targets, uint64_t n_items,
                          int ops_per_item, int kind, int64_t *dev_fetched, uint64_t *dev_checksum);
 

@@ -1108,7 +1108,7 @@ int shm_launch_amo_storm(shm_ctx *c, uint64_t ctr_off, int n_ctr, const uint16_t
     if (ops_per_item < 1 || ops_per_item > 4096) return fail(SHM_EINVAL, "ops_per_item outside 1..4096");
     if (kind < SHM_STORM_FETCH_ADD || kind > SHM_STORM_PLAIN_STORE) return fail(SHM_EINVAL, "unknown storm kind %d", kind);
     const uint64_t groups = (n_items + SHMK_WG - 1) / SHMK_WG;
-    if (n_items == 0 || groups > 0x7fffffffull) return fail(SHM_EINVAL, "n_items outside 1..2^31*256");
+    if (n_items == 0 || groups >= (1ull << 24)) return fail(SHM_EINVAL, "n_items outside 1..2^32-256 (one grid holds fewer than 2^32 threads)");
     if (c->no_device) return no_device("shm_launch_amo_storm");
     if (int r = drain_all_engines(c)) return r;
     if (c->team_sync)
