@@ -163,6 +163,23 @@ int shm_set_wait_timeout_us(shm_ctx *ctx, uint64_t us);
  * streams and all PE streams then wait for them; off = the caller orders streams itself. */
 int shm_set_team_sync(shm_ctx *ctx, int on);
 
+/* ---- kernels of the caller's own (paper section "Proposed Device APIs": the operations are called
+ *      from inside application kernels) --------------------------------------------------------- */
+
+/* The device functions of csrc/shm_device.hpp take a small by-value view of the context, a
+ * `shm_dev_ctx`, as their first argument.  shm_device_context copies that view to the HOST buffer
+ * `out`; out_bytes must equal shm_device_context_bytes() (= sizeof(shm_dev_ctx) of the library's
+ * build, so a kernel built against another layout is refused instead of misread).  Pass the view to
+ * a kernel by value.  It names the heap partitions, the number of PEs, the bound of device-side
+ * waits in force and, while the host proxy runs, the reverse-offload ring: take a new one after
+ * shm_set_wait_timeout_us, shm_proxy_start or shm_proxy_stop.  shm_stream gives PE `pe`'s stream
+ * (a hipStream_t; NULL on error or for a context without a device), so that such kernels can be
+ * ordered with the library's own launches; a kernel on any other stream is the caller's to order.
+ * What such a kernel has put is complete after shm_quiet of the PE whose stream it ran on. */
+size_t shm_device_context_bytes(void);
+int    shm_device_context(const shm_ctx *ctx, void *out, size_t out_bytes);
+void  *shm_stream(const shm_ctx *ctx, int pe);
+
 /* ---- kernel-launch entry points that exercise the device API ---------------------------------- */
 
 /* Work-group put/get (paper section "Proposed Device APIs", the work_group extensions; section

@@ -1,4 +1,5 @@
-"""Compile libshm355.so for gfx950 with hipcc, in-tree."""
+"""Compile libshm355.so -- and the application-kernel example that uses its device header -- for
+gfx950 with hipcc, in-tree."""
 from __future__ import annotations
 
 import os
@@ -8,6 +9,8 @@ PKG_DIR = os.path.dirname(os.path.abspath(__file__))
 REPO_DIR = os.path.dirname(PKG_DIR)
 LIB_PATH = os.path.join(PKG_DIR, "libshm355.so")
 SOURCES = [os.path.join(PKG_DIR, "csrc", "shm_api.hip")]
+EXAMPLE_LIB_PATH = os.path.join(PKG_DIR, "libshm355_user_example.so")
+EXAMPLE_SOURCES = [os.path.join(PKG_DIR, "csrc", "shm_user_example.hip")]
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
@@ -28,6 +31,13 @@ def build(verbose: bool = False) -> str:
         raise RuntimeError("hipcc failed:\n" + proc.stdout + proc.stderr)
     if verbose and proc.stderr.strip():
         print(proc.stderr)
+    # the example is an application of its own: device header only, no link to the library
+    cmd = [hipcc, *HIPCC_FLAGS, "-I", os.path.join(PKG_DIR, "csrc"), *EXAMPLE_SOURCES, "-o", EXAMPLE_LIB_PATH]
+    if verbose:
+        print(" ".join(cmd), flush=True)
+    proc = subprocess.run(cmd, capture_output=True, text=True)
+    if proc.returncode != 0:
+        raise RuntimeError("hipcc failed:\n" + proc.stdout + proc.stderr)
     return LIB_PATH
 
 

@@ -728,6 +728,25 @@ int shm_set_team_sync(shm_ctx *c, int on)
     return SHM_OK;
 }
 
+size_t shm_device_context_bytes(void) { return sizeof(shm_dev_ctx); }
+
+int shm_device_context(const shm_ctx *c, void *out, size_t out_bytes)
+{
+    if (int r = check_ctx(c)) return r;
+    if (!out) return fail(SHM_EINVAL, "null out pointer");
+    if (out_bytes != sizeof(shm_dev_ctx))
+        return fail(SHM_EINVAL, "the device view has %zu bytes in this build, the caller expects %zu", sizeof(shm_dev_ctx), out_bytes);
+    const shm_dev_ctx d = dev_view(c);
+    memcpy(out, &d, sizeof d);
+    return SHM_OK;
+}
+
+void *shm_stream(const shm_ctx *c, int pe)
+{
+    if (!c || c->no_device || pe < 0 || pe >= c->npes) return nullptr;
+    return c->stream[pe];
+}
+
 int shm_launch_wg_put(shm_ctx *c, int me, int pe, uint64_t dst_off, uint64_t src_off, size_t n, int n_wg, int path)
 {
     return wg_rma(c, me, pe, dst_off, src_off, n, n_wg, path, 0);

@@ -1,0 +1,62 @@
+// An application kernel of the kind the paper's section "Proposed Device APIs" is about: code that
+// is NOT part of the library, includes only the device header, receives the device view that
+// shm_device_context() hands out, and calls the OpenSHMEM operations from inside its own kernel.
+// Built as a separate shared library (libshm355_user_example.so) that does not link the library.
+//
+// The kernel is an all-to-all exchange with a device-side barrier and an atomic tally:
+//   * one work-group per PE (blockIdx.x = PE p); block t of p's source goes to slot p of PE t's
+//     destination with a work-group put (p's own block included);
+//   * barrier_all_work_group: everybody's blocks have landed and are visible;
+//   * every PE gets its right-hand neighbour's slot 0 (the block PE 0 sent there) into `back` with a
+//     work-group get, and thread 0 adds p + 1 to a 64-bit tally on PE 0 with a fetch-add, storing
+//     what it fetched to its own `seen` word.
+// All npes groups must be resident together (they meet in the barrier); npes <= 32 groups always are.
+#include <hip/hip_runtime.h>
+
+#include <cstring>
+
+#include "shm_device.hpp"
+
+namespace {
+
+__global__ __launch_bounds__(256) void shmu_alltoall_kernel(shm_dev_ctx c, uint64_t dst_off, uint64_t src_off, size_t n, uint64_t back_off,
+                                                            uint64_t tally_off, uint64_t seen_off)
+{
+    const int me = blockIdx.x, npes = c.npes;
+    for (int j = 0; j < npes; ++j) {
+        int t = me + j;                       // own block first, then round the ring
+        if (t >= npes) t -= npes;
+        shmx_putmem_wg(c, me, dst_off + static_cast<uint64_t>(me) * n, src_off + static_cast<uint64_t>(t) * n, n, t);
+    }
+    shmx_barrier_all_wg(c, me);
+    int right = me + 1;
+    if (right >= npes) right -= npes;
+    shmx_getmem_wg(c, me, back_off, dst_off, n, right);
+    if (threadIdx.x == 0) {
+        const int64_t before = shm_atomic_fetch_add(c, tally_off, me + 1, 0);
+        *reinterpret_cast<int64_t *>(shm_ptr(c, seen_off, me)) = before;
+    }
+}
+
+}  // namespace
+
+extern "C" {
+
+// devctx: HOST pointer to the bytes shm_device_context() wrote; stream: a hipStream_t.  Offsets are
+// symmetric-heap byte offsets (tally_off and seen_off 8-byte aligned).  Returns 0, -1 for a view of
+// the wrong size or bad arguments, -5 for a HIP error.  Asynchronous on `stream`.
+int shmu_alltoall(const void *devctx, size_t devctx_bytes, void *stream, uint64_t dst_off, uint64_t src_off, size_t n, uint64_t back_off,
+                  uint64_t tally_off, uint64_t seen_off)
+{
+    if (!devctx || devctx_bytes != sizeof(shm_dev_ctx) || ((tally_off | seen_off) & 7)) return -1;
+    shm_dev_ctx c;
+    memcpy(&c, devctx, sizeof c);
+    if (c.npes < 1 || c.npes > SHM_MAX_PES) return -1;
+    hipLaunchKernelGGL(shmu_alltoall_kernel, dim3(c.npes), dim3(256), 0, static_cast<hipStream_t>(stream), c, dst_off, src_off, n, back_off,
+                       tally_off, seen_off);
+    return hipGetLastError() == hipSuccess ? 0 : -5;
+}
+
+size_t shmu_device_context_bytes(void) { return sizeof(shm_dev_ctx); }
+
+}  // extern "C"

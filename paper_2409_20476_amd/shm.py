@@ -60,6 +60,9 @@ PROTOTYPES = {
     "shm_set_cutover": (c_int, [c_void_p, c_int, c_size_t]),
     "shm_get_cutover": (c_int, [c_void_p, c_int, _szp]),
     "shm_choose_path": (c_int, [c_void_p, c_size_t, c_int, _ip]),
+    "shm_device_context_bytes": (c_size_t, []),
+    "shm_device_context": (c_int, [c_void_p, c_void_p, c_size_t]),
+    "shm_stream": (c_void_p, [c_void_p, c_int]),
     "shm_set_collective_cutover": (c_int, [c_void_p, c_int, c_int, c_size_t]),
     "shm_get_collective_cutover": (c_int, [c_void_p, c_int, c_int, _szp]),
     "shm_choose_collective_path": (c_int, [c_void_p, c_int, c_size_t, c_int, _ip]),
@@ -108,7 +111,11 @@ class ShmError(RuntimeError):
 
 
 def load_library() -> ctypes.CDLL:
-    """Load libshm355.so from the package directory.  No library, no product: raises."""
+    """Load libshm355.so from the package directory.  No library, no product: raises.
+
+    A process should hold ONE HIP runtime.  PyTorch brings its own copy; a program that uses both
+    imports torch (and touches the GPU) before the first context is made, as Shm.on_torch does, so
+    that the library binds to the runtime already in the process."""
     global _lib
     if _lib is None:
         if not os.path.exists(_LIB_PATH):
@@ -221,6 +228,18 @@ class Shm:
 
     def barrier_all(self):
         self._check(self.lib.shm_barrier_all(self.ctx))
+
+    # ---- kernels of the caller's own ------------------------------------------------------
+    def device_context(self) -> bytes:
+        """The by-value device view (a shm_dev_ctx) that kernels built against shm_device.hpp take."""
+        n = self.lib.shm_device_context_bytes()
+        buf = ctypes.create_string_buffer(n)
+        self._check(self.lib.shm_device_context(self.ctx, buf, n))
+        return buf.raw
+
+    def stream(self, pe: int) -> int:
+        """PE pe's hipStream_t as an integer (0 on error)."""
+        return self.lib.shm_stream(self.ctx, pe) or 0
 
     # ---- policy ---------------------------------------------------------------------------
     def set_cutover(self, n_wg: int, nbytes: int):

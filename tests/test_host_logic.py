@@ -260,3 +260,23 @@ def test_team_grids_are_bounded_by_what_one_launch_can_hold():
         g.launch_wg_put(0, 1, 4096, 0, 100, 1 << 20)   # one PE's own grid may have 2^20 groups
     assert e.value.code == S.SHM_ENODEV
     g.finalize()
+
+
+def test_device_view_for_application_kernels():
+    """The by-value view that kernels of the caller's own take: size-checked, filled from the context;
+    the separately built example application agrees with the library on its layout's size."""
+    g = _ctx(3, MiB)
+    n = g.lib.shm_device_context_bytes()
+    view = g.device_context()
+    assert len(view) == n and n >= 8 * S.SHM_MAX_PES + 8
+    bases = np.frombuffer(view[:8 * S.SHM_MAX_PES], dtype=np.uint64)
+    assert list(bases[:3]) == [4096, 4096 + MiB, 4096 + 2 * MiB] and not bases[3:].any()     # base[pe], then unused entries
+    buf = ctypes.create_string_buffer(n)
+    assert g.lib.shm_device_context(g.ctx, buf, n - 1) == S.SHM_EINVAL
+    assert g.lib.shm_device_context(g.ctx, None, n) == S.SHM_EINVAL
+    assert g.stream(0) == 0                                 # a context without a device has no streams
+    g.finalize()
+    example = ctypes.CDLL(os.path.join(ROOT, "paper_2409_20476_amd", "libshm355_user_example.so"))
+    example.shmu_device_context_bytes.restype = ctypes.c_size_t
+    assert example.shmu_device_context_bytes() == n
+    assert hasattr(example, "shmu_alltoall")

@@ -1,0 +1,78 @@
+"""GPU parity of an APPLICATION kernel: a separately built library that includes only the device
+header, gets the device view from shm_device_context() and calls the OpenSHMEM operations from its
+own kernel (all-to-all by work-group puts, device-side barrier, work-group get, fetch-add tally).
+Expected state: the oracle's composition of the same operations."""
+import ctypes
+import os
+
+import numpy as np
+import pytest
+
+from paper_2409_20476_amd import shm as S
+from parity_util import assert_heaps_equal, fill_random, make_pair
+
+pytestmark = pytest.mark.gpu
+
+MiB = 1 << 20
+EXAMPLE = os.path.join(os.path.dirname(os.path.abspath(S.__file__)), "libshm355_user_example.so")
+
+
+def _example():
+    """Load the example application.  Called once a context exists, so that the process already holds
+    the HIP runtime PyTorch brought and the example binds to that one."""
+    if not os.path.exists(EXAMPLE):
+        raise ImportError(f"{EXAMPLE} has not been built; run `python -m paper_2409_20476_amd.build`")
+    lib = ctypes.CDLL(EXAMPLE)
+    lib.shmu_alltoall.restype = ctypes.c_int
+    lib.shmu_alltoall.argtypes = [ctypes.c_char_p, ctypes.c_size_t, ctypes.c_void_p, ctypes.c_uint64, ctypes.c_uint64, ctypes.c_size_t,
+                                  ctypes.c_uint64, ctypes.c_uint64, ctypes.c_uint64]
+    lib.shmu_device_context_bytes.restype = ctypes.c_size_t
+    return lib
+
+
+@pytest.mark.parametrize("npes,n", [(2, 1000), (8, 100003), (5, 0), (16, 4096 + 7), (3, 262144)])
+def test_application_kernel_alltoall_barrier_get_tally(npes, n):
+    g, o = make_pair(npes, 16 * MiB)
+    with g:
+        lib = _example()            # after the context: PyTorch's HIP runtime is the one already in the process
+        fill_random(g, o, 51, upto=12 * MiB)
+        view = g.device_context()
+        assert len(view) == lib.shmu_device_context_bytes()
+        src, dst, back, tally, seen = 1024 + 3, 5 * MiB + 5, 10 * MiB + 1, 11 * MiB, 11 * MiB + 64
+        init = int(o.read(0, tally, 8, np.int64)[0])
+        for rep in range(2):                                 # twice: the barrier's counters carry over
+            rc = lib.shmu_alltoall(view, len(view), g.stream(0), dst, src, n, back, tally, seen)
+            assert rc == 0
+            g.barrier_all()
+            for p in range(npes):
+                for j in range(npes):
+                    t = (p + j) % npes
+                    o.putmem(p, dst + p * n, src + t * n, n, t)
+            o.barrier_all()
+            for p in range(npes):
+                o.getmem(p, back, dst, n, (p + 1) % npes)
+            for p in range(npes):
+                o.atomic_fetch_add(p, tally, p + 1, 0)
+            # what each PE fetched depends on the order the hardware served them: any order is right,
+            # as long as the values chain from the initial tally to the final one
+            got = {p: int(g.read(p, seen, 8, np.int64)[0]) for p in range(npes)}
+            at = init
+            for p in sorted(got, key=got.get):
+                assert got[p] == at, f"fetched values do not chain: {got}"
+                at += p + 1
+            init = at
+            for p in range(npes):
+                o.write(p, seen, np.array([got[p]], dtype=np.int64))
+            assert_heaps_equal(g, o, upto=12 * MiB, what=f"npes {npes}, n {n}, repetition {rep}")
+
+
+def test_device_view_is_refused_at_another_size_and_streams_are_the_contexts():
+    g, o = make_pair(2, MiB)
+    with g:
+        n = g.lib.shm_device_context_bytes()
+        buf = ctypes.create_string_buffer(n + 8)
+        assert g.lib.shm_device_context(g.ctx, buf, n + 8) == S.SHM_EINVAL
+        assert g.lib.shm_device_context(g.ctx, None, n) == S.SHM_EINVAL
+        assert g.stream(0) == g.streams[0].cuda_stream and g.stream(1) == g.streams[1].cuda_stream
+        assert g.stream(2) == 0 and g.stream(-1) == 0
+        assert _example().shmu_alltoall(buf, n + 8, g.stream(0), 0, 4096, 16, 8192, 16384, 16392) == -1
