@@ -446,6 +446,38 @@ def collective_sweeps(torch, S, args):
     return out
 
 
+def graph_replay(torch, S, args):
+    """Launch-bound loops recorded once as a HIP graph: 64 small puts issued one by one and as one replay."""
+    g = S.Shm.on_torch(2, 64 * MiB)
+    src, dst = g.malloc(MiB), g.malloc(MiB)
+    out = {}
+    for n, n_wg in ((8, 1), (4096, 1), (65536, 4)):
+        count = 64
+        issue = lambda: [g.launch_wg_put(0, 1, dst, src, n, n_wg) for _ in range(count)]
+        eager_us = paper_timing(torch, lambda iters: time_on_stream(torch, g.streams[0], issue, iters)) * 1e3 / count
+        graph = torch.cuda.CUDAGraph()
+        torch.cuda.synchronize()
+        with torch.cuda.graph(graph, stream=g.streams[0]):
+            issue()
+        torch.cuda.synchronize()
+
+        def replay_trial(iters):
+            e0, e1 = event_pair(torch)
+            with torch.cuda.stream(g.streams[0]):
+                e0.record()
+                for _ in range(iters):
+                    graph.replay()
+                e1.record()
+            e1.synchronize()
+            return e0.elapsed_time(e1) / iters
+        replay_us = paper_timing(torch, replay_trial) * 1e3 / count
+        out[f"{n}B_wg{n_wg}"] = {"eager_us_per_put": eager_us, "graph_us_per_put": replay_us}
+        del graph
+    g.finalize()
+    out["note"] = "64 work-group puts PE 0 -> PE 1 on one stream; eager = 64 launches, graph = one replay of the recorded 64"
+    return out
+
+
 def pingflag(torch, S, synth, args):
     g = S.Shm.on_torch(2, MiB)
     payload = synth.c1_payload(4096)
@@ -658,6 +690,7 @@ def main():
         ("collective_sweeps", lambda: collective_sweeps(torch, S, args),
          lambda r: f"sync us by PEs {r['sync_us_by_pes']} barrier {r['barrier_us_by_pes']} fcollect cutover "
                    f"{dict((k, v['cutover_bytes_per_pe']) for k, v in r['fcollect'].items())}"),
+        ("graph_replay", lambda: graph_replay(torch, S, args), lambda r: f"graph replay: {r}"),
         ("config3_ring", lambda: ring(torch, S, synth, g, args), lambda r: f"c3: {r}"),
         ("config4_amo_storm", lambda: storm(torch, S, synth, args), lambda r: f"c4: {r}"),
         ("config5_collectives", lambda: collectives(torch, S, synth, g, args), lambda r: f"c5: {r}"),
