@@ -160,7 +160,13 @@ int shm_choose_collective_path(const shm_ctx *ctx, int collective, size_t bytes_
 /* Upper bound for every device-side wait, in microseconds (default 2 000 000; must be > 0). */
 int shm_set_wait_timeout_us(shm_ctx *ctx, uint64_t us);
 /* Team launches run on PE 0's stream.  With team sync on (default) they first wait for all PE
- * streams and all PE streams then wait for them; off = the caller orders streams itself. */
+ * streams and all PE streams then wait for them: whatever was enqueued before a team launch, on any
+ * PE's stream, is ordered before it, and whatever is enqueued after it is ordered behind it.  That
+ * holds for a team launch with nothing to move (zero bytes or elements) too, and on the copy-engine
+ * path, where the call then returns only after the engines have finished (they are not on the
+ * streams, so only the host can order other PEs' later work behind them).  Off = the caller orders
+ * streams itself, engine transfers stay asynchronous until a quiet, and an empty team launch does
+ * nothing but wait for engine transfers in flight. */
 int shm_set_team_sync(shm_ctx *ctx, int on);
 
 /* ---- kernels of the caller's own (paper section "Proposed Device APIs": the operations are called

@@ -282,6 +282,17 @@ int drain_all_engines(shm_ctx *c)
     return SHM_OK;
 }
 
+// What a team launch with nothing to move still owes its callers: with team sync on, everything
+// enqueued before it on any PE stream is ordered before everything enqueued after it.
+int team_order_only(shm_ctx *c)
+{
+    if (int r = drain_all_engines(c)) return r;      // engine transfers are not on the streams
+    if (!c->team_sync) return SHM_OK;
+    if (int r = team_join(c)) return r;
+    return team_fork(c);
+}
+
+
 // Runtime copy: hipMemcpyAsync in stream order on PE `on_pe`'s stream.
 int memcpy_copy(shm_ctx *c, int on_pe, int dst_pe, uint64_t dst_off, int src_pe, uint64_t src_off, size_t n)
 {
@@ -360,6 +371,9 @@ int wg_rma_all(shm_ctx *c, int pe_shift, uint64_t dst_off, uint64_t src_off, siz
                 return r;
         }
         if (c->team_sync) {
+            // the engines are not on the streams: only the host can put later work of OTHER PEs behind them
+            if (use == SHM_PATH_SDMA)
+                if (int r = drain_all_engines(c)) return r;
             if (int r = team_join(c)) return r;
             if (int r = team_fork(c)) return r;
         }
@@ -1168,7 +1182,7 @@ int shm_launch_fcollect(shm_ctx *c, uint64_t dst_off, uint64_t src_off, size_t b
     int use;
     if (int r = resolve_collective_path(c, SHM_COLL_FCOLLECT, path, bytes_per_pe, n_wg, &use)) return r;
     if (c->no_device) return no_device("shm_launch_fcollect");
-    if (bytes_per_pe == 0) return SHM_OK;
+    if (bytes_per_pe == 0) return team_order_only(c);
     if (int r = drain_all_engines(c)) return r;
     if (use != SHM_PATH_LDST) {
         if (c->team_sync) {
@@ -1182,6 +1196,9 @@ int shm_launch_fcollect(shm_ctx *c, uint64_t dst_off, uint64_t src_off, size_t b
                     return r;
             }
         if (c->team_sync) {
+            // the engines are not on the streams: only the host can put later work of OTHER PEs behind them
+            if (use == SHM_PATH_SDMA)
+                if (int r = drain_all_engines(c)) return r;
             if (int r = team_join(c)) return r;
             if (int r = team_fork(c)) return r;
         }
@@ -1224,7 +1241,7 @@ int shm_launch_collect(shm_ctx *c, uint64_t dst_off, uint64_t src_off, const siz
     if (int r = check_team_grid(c, n_wg)) return r;
     if (c->no_device) return no_device("shm_launch_collect");
     if (int r = drain_all_engines(c)) return r;
-    if (total == 0) return SHM_OK;
+    if (total == 0) return team_order_only(c);
     if (c->team_sync)
         if (int r = team_join(c)) return r;
     hipLaunchKernelGGL(shmk_collect, dim3(n_wg, c->npes), dim3(SHMK_WG), 0, c->stream[0], dev_view(c), dst_off, src_off, t);
@@ -1251,7 +1268,7 @@ int shm_launch_reduce(shm_ctx *c, uint64_t dst_off, uint64_t src_off, size_t nel
     if (int r = check_team_grid(c, n_wg)) return r;
     if (c->no_device) return no_device("shm_launch_reduce");
     if (int r = drain_all_engines(c)) return r;
-    if (nelems == 0) return SHM_OK;
+    if (nelems == 0) return team_order_only(c);
     if (c->team_sync)
         if (int r = team_join(c)) return r;
     hipLaunchKernelGGL(k, dim3(n_wg, c->npes), dim3(SHMK_WG), 0, c->stream[0], dev_view(c), dst_off, src_off, nelems,
@@ -1315,7 +1332,7 @@ int shm_launch_broadcast(shm_ctx *c, uint64_t dst_off, uint64_t src_off, size_t 
     if (int r = resolve_collective_path(c, SHM_COLL_BROADCAST, path, n, n_wg, &use)) return r;
     if (c->no_device) return no_device("shm_launch_broadcast");
     if (int r = drain_all_engines(c)) return r;
-    if (n == 0) return SHM_OK;
+    if (n == 0) return team_order_only(c);
     if (c->team_sync)
         if (int r = team_join(c)) return r;
     if (use != SHM_PATH_LDST) {
@@ -1326,6 +1343,9 @@ int shm_launch_broadcast(shm_ctx *c, uint64_t dst_off, uint64_t src_off, size_t 
             if (int r = transfer_copy(c, use, q, q, dst_off, root, src_off, n)) return r;
         }
         if (c->team_sync) {
+            // the engines are not on the streams: only the host can put later work of OTHER PEs behind them
+            if (use == SHM_PATH_SDMA)
+                if (int r = drain_all_engines(c)) return r;
             if (int r = team_join(c)) return r;
             if (int r = team_fork(c)) return r;
         }
@@ -1350,7 +1370,7 @@ int shm_launch_reduce_sum_f32(shm_ctx *c, uint64_t dst_off, uint64_t src_off, si
     if (algo != SHM_REDUCE_DUPLICATE && algo != SHM_REDUCE_SPLIT) return fail(SHM_EINVAL, "unknown reduce algorithm %d", algo);
     if (c->no_device) return no_device("shm_launch_reduce_sum_f32");
     if (int r = drain_all_engines(c)) return r;
-    if (nelems == 0) return SHM_OK;
+    if (nelems == 0) return team_order_only(c);
     if (c->team_sync)
         if (int r = team_join(c)) return r;
     const shm_dev_ctx d = dev_view(c);

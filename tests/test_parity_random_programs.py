@@ -157,7 +157,7 @@ def _program(g, o, npes, seed, n_ops, with_engines):
 
 
 @pytest.mark.parametrize("npes,seed,with_engines", [(2, 101, False), (3, 102, True), (5, 103, False), (8, 104, True), (4, 105, True),
-                                                    (2, 106, True), (16, 107, False), (3, 108, True)])
+                                                    (2, 106, True), (16, 107, False), (3, 108, True), (4, 1038, True)])
 def test_random_program(npes, seed, with_engines):
     g, o = make_pair(npes, 2 * MiB)
     with g:

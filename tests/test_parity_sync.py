@@ -87,3 +87,61 @@ def test_collectives_on_auto_follow_their_own_cutover():
             o.broadcast(6 * MiB + 5, 1024 + n % 7, n + 20000, n % 4)
             g.barrier_all()
             assert_heaps_equal(g, o, upto=12 * MiB, what=f"n {n}")
+
+
+@pytest.mark.parametrize("empty", ["reduce", "reduce_sum_f32", "fcollect", "collect", "broadcast"])
+def test_an_empty_team_launch_still_orders_the_streams(empty):
+    """A slow put on PE 1's stream, a team launch with nothing to move, then -- with no host barrier --
+    a get on PE 0's stream that reads what the put wrote: the team launch's join/fork is what orders
+    the two, also when it has no kernel to run."""
+    g, o = make_pair(3, 80 * MiB)
+    with g:
+        fill_random(g, o, 45, upto=72 * MiB)
+        n = 20 * MiB + 5
+        for rep in range(3):
+            src, mid, dst = 1024 + rep, 24 * MiB + 16 * rep, 48 * MiB + 3 * rep
+            g.launch_wg_put(1, 2, mid, src, n, 1)                     # one group: slow enough to still be running
+            o.wg_put(1, mid, src, n, 2, 1)
+            if empty == "reduce":
+                g.launch_reduce(4096, 65536, 0, S.SHM_INT32, S.SHM_OP_SUM, 4)
+            elif empty == "reduce_sum_f32":
+                g.launch_reduce_sum_f32(4096, 65536, 0, 4)
+            elif empty == "fcollect":
+                g.launch_fcollect(4096, 65536, 0, 4)
+            elif empty == "collect":
+                g.launch_collect(4096, 65536, [0, 0, 0], 4)
+            else:
+                g.launch_broadcast(4096, 65536, 0, 1, 4)
+            g.launch_wg_get(0, 2, dst, mid, n, 64)
+            o.wg_get(0, dst, mid, n, 2, 64)
+            g.barrier_all()
+            assert_heaps_equal(g, o, upto=72 * MiB, what=f"{empty}, repetition {rep}")
+
+
+@pytest.mark.parametrize("kind", ["fcollect", "broadcast", "put_all"])
+def test_team_launch_on_the_engines_orders_other_pes_later_work(kind):
+    """Engine transfers are not on the streams.  With team sync on, work that another PE enqueues
+    right after a team launch on the copy engines -- here a get of what the engines deliver to a
+    third PE -- must find it delivered."""
+    g, o = make_pair(4, 136 * MiB)
+    with g:
+        fill_random(g, o, 46, upto=132 * MiB)
+        n = 20 * MiB + 48                                              # a third of a millisecond per engine transfer
+        src, dst, back = 4096, 24 * MiB, 108 * MiB
+        if kind == "fcollect":
+            g.launch_fcollect(dst, src, n, 1, S.SHM_PATH_SDMA)
+            o.fcollect(dst, src, n)
+            take = dst + 3 * n                                         # block of PE 3, delivered to PE 2 by PE 3's transfer
+        elif kind == "broadcast":
+            g.launch_broadcast(dst, src, n, 3, 1, S.SHM_PATH_SDMA)
+            o.broadcast(dst, src, n, 3)
+            take = dst
+        else:
+            g.launch_wg_put_all(1, dst, src, n, 1, S.SHM_PATH_SDMA)
+            for p in range(4):
+                o.putmem(p, dst, src, n, (p + 1) % 4)
+            take = dst
+        g.launch_wg_get(0, 2, back, take, n, 64)                      # PE 0 reads PE 2's copy at once
+        o.wg_get(0, back, take, n, 2, 64)
+        g.barrier_all()
+        assert_heaps_equal(g, o, upto=132 * MiB, what=kind)
