@@ -43,9 +43,13 @@ class Tracker:
 def _program(g, o, npes, seed, n_ops, with_engines):
     rng = np.random.default_rng(seed)
     tr = Tracker()
-    paths = [S.SHM_PATH_LDST, S.SHM_PATH_LDST, S.SHM_PATH_MEMCPY] + ([S.SHM_PATH_SDMA] if with_engines else [])
+    paths = [S.SHM_PATH_LDST, S.SHM_PATH_LDST, S.SHM_PATH_MEMCPY] + ([S.SHM_PATH_SDMA, S.SHM_PATH_AUTO] if with_engines else [])
+    modes = [0, 0, 1, 2, 3, 4] if with_engines else [0]        # device-initiated transfers: the engine modes need the proxy
     issued = barriers = 0
     counts = {}
+    if with_engines:
+        g.proxy_start()
+        g.set_cutover(1, 100000)          # AUTO by one group takes the engines from 100 000 bytes
 
     def off(align=1, span=ARENA):
         return int(rng.integers(0, span)) // align * align
@@ -55,7 +59,7 @@ def _program(g, o, npes, seed, n_ops, with_engines):
 
     for i in range(n_ops):
         kind = str(rng.choice(["wg_put", "wg_get", "host_put", "host_get", "put_signal", "amo", "fcollect", "collect", "broadcast", "reduce",
-                               "iput", "iget", "scalar", "thread", "dev_put", "dev_get"]))
+                               "iput", "iget", "scalar", "thread", "dev_put", "dev_get", "wave"]))
         me, pe = int(rng.integers(npes)), int(rng.integers(npes))
         team = kind in ("fcollect", "collect", "broadcast", "reduce")
         try:
@@ -75,8 +79,9 @@ def _program(g, o, npes, seed, n_ops, with_engines):
                 elif kind == "thread":
                     call = lambda: g.launch_thread_rma(me, pe, d, s, n, is_get)
                 else:
-                    wg_size = int(rng.choice([64, 256, 1024]))
-                    call = lambda: g.launch_rma_device_initiated(me, pe, d, s, n, min(n_wg, 16), is_get, 0, wg_size=wg_size)
+                    wg_size, mode = int(rng.choice([64, 256, 1024])), int(rng.choice(modes))
+                    call = lambda: g.launch_rma_device_initiated(me, pe, d, s, n, min(n_wg, 16), is_get, mode, cutover=50000, cover=4096,
+                                                                 wg_size=wg_size)
             elif kind == "put_signal":
                 d, s, n, sig = off(), off(), size(), off(8)
                 op = SIGNAL_ADD if rng.integers(2) else SIGNAL_SET
@@ -84,6 +89,23 @@ def _program(g, o, npes, seed, n_ops, with_engines):
                 o.put_signal(me, d, s, n, sig, val, op, pe, n_wg)
                 touched = [(me, s, s + n, False), (pe, d, d + n, True), (pe, sig, sig + 8, True)]
                 call = lambda: g.launch_wg_put_signal(me, pe, d, s, n, sig, val, op, n_wg)
+            elif kind == "wave":
+                d, s, back, n = off(), off(), off(), min(size(), 100000)
+                n_waves = int(rng.choice([1, 3, 8, 64]))
+                flag, out = off(8, ARENA - 8 * n_waves), off(8, ARENA - 8 * n_waves)
+                if me == pe or len({(flag, 8 * n_waves), (out, 8 * n_waves)}) < 2:
+                    continue                                  # producer and consumer waves are two PEs' work
+                regions = [(d, n), (back, n), (flag, 8 * n_waves), (out, 8 * n_waves)]
+                if any(a < b + lb and b < a + la for i, (a, la) in enumerate(regions) for (b, lb) in regions[i + 1:] if la and lb):
+                    continue                                  # the library wants them disjoint on the target PE
+                o.wave_exchange(me, pe, d, s, back, n, n_waves, flag, out)      # raises if it is not a defined operation ...
+                g.barrier_all()                                                 # ... else the flag words start at zero on both sides
+                barriers += 1
+                tr.clear()
+                g.write(pe, flag, np.zeros(8 * n_waves, np.uint8))
+                touched = [(me, s, s + n, False), (pe, d, d + n, True), (pe, back, back + n, True), (pe, flag, flag + 8 * n_waves, True),
+                           (pe, out, out + 8 * n_waves, True)]
+                call = lambda: g.launch_wave_exchange(me, pe, d, s, back, n, n_waves, flag, out)
             elif kind == "amo":
                 at, v = off(8), int(rng.integers(-1000, 1000))
                 o.atomic_fetch_add(me, at, v, pe)
@@ -151,6 +173,8 @@ def _program(g, o, npes, seed, n_ops, with_engines):
             g.barrier_all()
             tr.clear()
             assert_heaps_equal(g, o, what=f"seed {seed}, after operation {i} ({kind}); issued so far: {counts}")
+    if with_engines:
+        g.proxy_stop()
     g.barrier_all()
     assert_heaps_equal(g, o, what=f"seed {seed}, end")
     return issued, barriers, counts
@@ -164,5 +188,5 @@ def test_random_program(npes, seed, with_engines):
         fill_random(g, o, seed)
         issued, barriers, counts = _program(g, o, npes, seed, 600, with_engines)
         print(f"npes {npes}: {issued} operations, {barriers} barriers for conflicts, {counts}")
-        assert issued > 400 and len(counts) == 16, (issued, counts)
+        assert issued > 400 and len(counts) == 17, (issued, counts)
         assert barriers < issued // 2, "the program should mostly rely on stream order and team joins, not on host barriers"
