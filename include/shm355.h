@@ -59,6 +59,7 @@ enum { SHM_AMO_FETCH = 0, SHM_AMO_SET = 1, SHM_AMO_SWAP = 2, SHM_AMO_COMPARE_SWA
 enum { SHM_STORM_FETCH_ADD = 0, SHM_STORM_ADD = 1, SHM_STORM_CSWAP_LOOP = 2, SHM_STORM_PLAIN_STORE = 3 };
 enum { SHM_REDUCE_DUPLICATE = 0, SHM_REDUCE_SPLIT = 1 };
 enum { SHM_COLL_FCOLLECT = 0, SHM_COLL_BROADCAST = 1 };
+enum { SHM_TEAM_SYNC_OFF = 0, SHM_TEAM_SYNC_FULL = 1, SHM_TEAM_SYNC_TRACKED = 2 };
 enum { SHM_OP_MIN = 0, SHM_OP_MAX = 1, SHM_OP_SUM = 2, SHM_OP_PROD = 3, SHM_OP_AND = 4, SHM_OP_OR = 5, SHM_OP_XOR = 6 };
 enum { SHM_INT8 = 0, SHM_UINT8 = 1, SHM_INT16 = 2, SHM_UINT16 = 3, SHM_INT32 = 4, SHM_UINT32 = 5, SHM_INT64 = 6, SHM_UINT64 = 7,
        SHM_FLOAT32 = 8, SHM_FLOAT64 = 9 };
@@ -159,15 +160,21 @@ int shm_choose_collective_path(const shm_ctx *ctx, int collective, size_t bytes_
 
 /* Upper bound for every device-side wait, in microseconds (default 2 000 000; must be > 0). */
 int shm_set_wait_timeout_us(shm_ctx *ctx, uint64_t us);
-/* Team launches run on PE 0's stream.  With team sync on (default) they first wait for all PE
+/* Team launches run on PE 0's stream.  SHM_TEAM_SYNC_FULL (default): they first wait for all PE
  * streams and all PE streams then wait for them: whatever was enqueued before a team launch, on any
  * PE's stream, is ordered before it, and whatever is enqueued after it is ordered behind it.  That
  * holds for a team launch with nothing to move (zero bytes or elements) too, and on the copy-engine
  * path, where the call then returns only after the engines have finished (they are not on the
- * streams, so only the host can order other PEs' later work behind them).  Off = the caller orders
- * streams itself, engine transfers stay asynchronous until a quiet, and an empty team launch does
- * nothing but wait for engine transfers in flight. */
-int shm_set_team_sync(shm_ctx *ctx, int on);
+ * streams, so only the host can order other PEs' later work behind them).
+ * SHM_TEAM_SYNC_TRACKED gives the same ordering for everything enqueued THROUGH THIS LIBRARY at a
+ * fraction of the cost (a full join and fork of 8 streams costs about 80 us of host time per team
+ * launch): a team launch waits only for the PE streams the library has used since the last one,
+ * and a PE stream catches up with the team stream when the library next uses it (or in shm_quiet).
+ * Work the caller enqueues on a PE stream by other means (a kernel of its own on shm_stream(pe),
+ * a stream the context borrowed) is not seen by the tracking: order it yourself or use FULL.
+ * SHM_TEAM_SYNC_OFF: the caller orders streams itself, engine transfers stay asynchronous until a
+ * quiet, and an empty team launch does nothing but wait for engine transfers in flight. */
+int shm_set_team_sync(shm_ctx *ctx, int mode);
 
 /* ---- kernels of the caller's own (paper section "Proposed Device APIs": the operations are called
  *      from inside application kernels) --------------------------------------------------------- */

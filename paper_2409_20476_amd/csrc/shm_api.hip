@@ -72,7 +72,10 @@ struct shm_ctx {
     // from the number of PEs (measured on MI355X with 4, 8 and 12 PEs; the host-started side of the
     // comparison is the runtime-copy path, which outruns the engines for these many-copy patterns).
     size_t coll_cutover[2][4] = {};
-    bool team_sync = true;
+    bool team_sync = true;        // team launches order the PE streams (SHM_TEAM_SYNC_FULL or _TRACKED)
+    bool team_tracked = false;    // ... but only those the library itself has used since the last team launch, and lazily
+    bool pe_dirty[SHM_MAX_PES] = {};        // tracked mode: the library has enqueued work on this PE's stream since the last join
+    bool pe_needs_fork[SHM_MAX_PES] = {};   // tracked mode: this PE's stream has not yet waited for the latest team work
     int num_cu = 0;
     uint32_t next_slot[SHM_MAX_PES] = {};
     shm_heap_allocator alloc;
@@ -233,8 +236,10 @@ int quiet_offloaded(shm_ctx *c, int pe)
 int team_join(shm_ctx *c)
 {
     for (int p = 1; p < c->npes; ++p) {
+        if (c->team_tracked && !c->pe_dirty[p]) continue;      // nothing of the library's on that stream since the last join
         HIP_TRY(hipEventRecord(c->event[p], c->stream[p]));
         HIP_TRY(hipStreamWaitEvent(c->stream[0], c->event[p], 0));
+        c->pe_dirty[p] = false;
     }
     return SHM_OK;
 }
@@ -243,7 +248,22 @@ int team_join(shm_ctx *c)
 int team_fork(shm_ctx *c)
 {
     HIP_TRY(hipEventRecord(c->event[0], c->stream[0]));
-    for (int p = 1; p < c->npes; ++p) HIP_TRY(hipStreamWaitEvent(c->stream[p], c->event[0], 0));
+    for (int p = 1; p < c->npes; ++p) {
+        if (c->team_tracked)
+            c->pe_needs_fork[p] = true;         // the wait is enqueued when that PE's stream is next used
+        else
+            HIP_TRY(hipStreamWaitEvent(c->stream[p], c->event[0], 0));
+    }
+    return SHM_OK;
+}
+
+// Tracked mode: PE pe's stream catches up with the team stream before it is used again.
+int lazy_fork(shm_ctx *c, int pe)
+{
+    if (c->team_tracked && c->pe_needs_fork[pe]) {
+        HIP_TRY(hipStreamWaitEvent(c->stream[pe], c->event[0], 0));
+        c->pe_needs_fork[pe] = false;
+    }
     return SHM_OK;
 }
 
@@ -275,6 +295,17 @@ int drain_engines(shm_ctx *c, int pe)
     return SHM_OK;
 }
 
+// Every launch on one PE's own stream starts here: that PE's engine transfers are finished (they are
+// not on the stream) and, in tracked mode, the stream first catches up with the team stream and is
+// marked as used.
+int begin_pe_launch(shm_ctx *c, int pe)
+{
+    if (int r = drain_engines(c, pe)) return r;
+    if (int r = lazy_fork(c, pe)) return r;
+    c->pe_dirty[pe] = true;
+    return SHM_OK;
+}
+
 int drain_all_engines(shm_ctx *c)
 {
     for (int p = 0; p < c->npes; ++p)
@@ -297,7 +328,7 @@ int team_order_only(shm_ctx *c)
 int memcpy_copy(shm_ctx *c, int on_pe, int dst_pe, uint64_t dst_off, int src_pe, uint64_t src_off, size_t n)
 {
     if (n == 0) return SHM_OK;
-    if (int r = drain_engines(c, on_pe)) return r;
+    if (int r = begin_pe_launch(c, on_pe)) return r;
     HIP_TRY(hipMemcpyAsync(shm_ptr(c, dst_off, dst_pe), shm_ptr(c, src_off, src_pe), n, hipMemcpyDeviceToDevice, c->stream[on_pe]));
     return SHM_OK;
 }
@@ -308,6 +339,7 @@ int sdma_copy(shm_ctx *c, int on_pe, int dst_pe, uint64_t dst_off, int src_pe, u
 {
     if (!c->engines.ready()) return fail(SHM_EHIP, "copy engines unavailable: %s", c->engine_err.c_str());
     if (n == 0) return SHM_OK;
+    if (int r = lazy_fork(c, on_pe)) return r;
     HIP_TRY(hipStreamSynchronize(c->stream[on_pe]));
     std::string err;
     if (!c->engines.submit(shm_ptr(c, dst_off, dst_pe), shm_ptr(c, src_off, src_pe), n, on_pe, c->npes, err))
@@ -338,7 +370,7 @@ int wg_rma(shm_ctx *c, int me, int pe, uint64_t dst_off, uint64_t src_off, size_
     if (c->no_device) return no_device(is_get ? "shm_launch_wg_get" : "shm_launch_wg_put");
     if (use != SHM_PATH_LDST)
         return is_get ? transfer_copy(c, use, me, me, dst_off, pe, src_off, n) : transfer_copy(c, use, me, pe, dst_off, me, src_off, n);
-    if (int r = drain_engines(c, me)) return r;
+    if (int r = begin_pe_launch(c, me)) return r;
     const int shift = (pe - me + c->npes) % c->npes;
     if (use_tiles(dst_off, src_off, n, n_wg, 1)) {
         hipLaunchKernelGGL(shmk_wg_rma_tiles, dim3(n_wg, 1), dim3(SHMK_WG), TILES_LDS_BYTES, c->stream[me], dev_view(c), dst_off, src_off,
@@ -649,6 +681,7 @@ int shm_quiet(shm_ctx *c, int me)
     if (int r = check_ctx(c)) return r;
     if (int r = check_pe(c, me, "calling PE")) return r;
     if (c->no_device) return no_device("shm_quiet");
+    if (int r = lazy_fork(c, me)) return r;          // team work for this PE runs on the team stream: wait for it too
     HIP_TRY(hipStreamSynchronize(c->stream[me]));
     if (int r = drain_engines(c, me)) return r;
     if (int r = quiet_offloaded(c, me)) return r;
@@ -671,6 +704,7 @@ int shm_barrier_all(shm_ctx *c)
     for (int p = 0; p < c->npes; ++p) HIP_TRY(hipStreamSynchronize(c->stream[p]));
     if (int r = drain_all_engines(c)) return r;
     if (int r = quiet_offloaded(c, -1)) return r;
+    for (int p = 0; p < c->npes; ++p) c->pe_dirty[p] = c->pe_needs_fork[p] = false;      // every stream is idle: nothing left to order
     return take_status(c);
 }
 
@@ -735,10 +769,17 @@ int shm_set_wait_timeout_us(shm_ctx *c, uint64_t us)
     return SHM_OK;
 }
 
-int shm_set_team_sync(shm_ctx *c, int on)
+int shm_set_team_sync(shm_ctx *c, int mode)
 {
     if (int r = check_ctx(c)) return r;
-    c->team_sync = on != 0;
+    if (mode != SHM_TEAM_SYNC_OFF && mode != SHM_TEAM_SYNC_FULL && mode != SHM_TEAM_SYNC_TRACKED)
+        return fail(SHM_EINVAL, "unknown team sync mode %d", mode);
+    if (!c->no_device)
+        for (int p = 1; p < c->npes; ++p)
+            if (int r = lazy_fork(c, p)) return r;      // waits owed under the tracked mode are enqueued before it is left
+    for (int p = 0; p < c->npes; ++p) c->pe_needs_fork[p] = false, c->pe_dirty[p] = (mode == SHM_TEAM_SYNC_TRACKED);
+    c->team_sync = mode != SHM_TEAM_SYNC_OFF;
+    c->team_tracked = mode == SHM_TEAM_SYNC_TRACKED;
     return SHM_OK;
 }
 
@@ -790,7 +831,7 @@ int shm_launch_wg_put_timed(shm_ctx *c, int me, int pe, uint64_t dst_off, uint64
     if (reps < 1 || reps > (1 << 20)) return fail(SHM_EINVAL, "reps outside 1..2^20");
     if (!dev_ticks) return fail(SHM_EINVAL, "null tick buffer");
     if (c->no_device) return no_device("shm_launch_wg_put_timed");
-    if (int r = drain_engines(c, me)) return r;
+    if (int r = begin_pe_launch(c, me)) return r;
     const bool tiles = use_tiles(dst_off, src_off, n, n_wg, 1);
     hipLaunchKernelGGL(shmk_wg_put_timed, dim3(n_wg), dim3(SHMK_WG), tiles ? TILES_LDS_BYTES : 0, c->stream[me], dev_view(c), dst_off,
                        src_off, n, me, pe, reps, reinterpret_cast<unsigned long long *>(dev_ticks), tiles ? 1 : 0);
@@ -858,7 +899,7 @@ int shm_launch_rma_device_initiated(shm_ctx *c, int me, int pe, uint64_t dst_off
     }
     if (c->no_device) return no_device("shm_launch_rma_device_initiated");
     if (mode != 0 && !c->proxy.running()) return fail(SHM_EINVAL, "the host proxy is not running (shm_proxy_start)");
-    if (int r = drain_engines(c, me)) return r;
+    if (int r = begin_pe_launch(c, me)) return r;
     hipLaunchKernelGGL(shmk_rma_device_initiated, dim3(n_wg), dim3(wg_size), 0, c->stream[me], dev_view(c), dst_off, src_off, n, me, pe,
                        is_get ? 1 : 0, mode, cutover, cover, consume_off, reps, reinterpret_cast<unsigned long long *>(dev_ticks));
     return launched("device-initiated transfer");
@@ -884,7 +925,7 @@ int shm_launch_scalar_pg(shm_ctx *c, int me, int pe, uint64_t dst_off, uint64_t 
     if ((dst_off | src_off) % static_cast<uint64_t>(elem_bytes)) return fail(SHM_EINVAL, "scalar put/get needs element-aligned offsets");
     if (int r = check_n_wg(n_wg)) return r;
     if (c->no_device) return no_device("shm_launch_scalar_pg");
-    if (int r = drain_engines(c, me)) return r;
+    if (int r = begin_pe_launch(c, me)) return r;
     if (nelems == 0) return SHM_OK;
     const dim3 grid(n_wg), block(SHMK_WG);
     const shm_dev_ctx d = dev_view(c);
@@ -919,7 +960,7 @@ int shm_launch_wave_exchange(shm_ctx *c, int me, int pe, uint64_t dst_off, uint6
             if (on_pe[i].len && on_pe[j].len && on_pe[i].off < on_pe[j].off + on_pe[j].len && on_pe[j].off < on_pe[i].off + on_pe[i].len)
                 return fail(SHM_EINVAL, "buffers overlap on PE %d", pe);
     if (c->no_device) return no_device("shm_launch_wave_exchange");
-    if (int r = drain_engines(c, me)) return r;
+    if (int r = begin_pe_launch(c, me)) return r;
     int per_cu = 0;
     HIP_TRY(hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, shmk_wave_exchange, SHMK_WG, 0));
     const long long groups = 2ll * ((n_waves + 3) / 4);
@@ -937,7 +978,7 @@ int shm_launch_thread_rma(shm_ctx *c, int me, int pe, uint64_t dst_off, uint64_t
     if (int r = rma_args(c, me, pe, dst_off, src_off, n)) return r;
     if (reps < 1 || reps > (1 << 20)) return fail(SHM_EINVAL, "reps outside 1..2^20");
     if (c->no_device) return no_device("shm_launch_thread_rma");
-    if (int r = drain_engines(c, me)) return r;
+    if (int r = begin_pe_launch(c, me)) return r;
     hipLaunchKernelGGL(shmk_thread_rma, dim3(1), dim3(64), 0, c->stream[me], dev_view(c), dst_off, src_off, n, me, pe, is_get ? 1 : 0,
                        reps, reinterpret_cast<unsigned long long *>(dev_ticks));
     return launched("single-thread transfer");
@@ -970,7 +1011,7 @@ int launch_strided(shm_ctx *c, int me, int pe, uint64_t dst_off, uint64_t src_of
     if (me == pe && nelems && src_off < dst_off + dspan && dst_off < src_off + sspan)
         return fail(SHM_EINVAL, "source and destination overlap on PE %d", me);
     if (c->no_device) return no_device("strided transfer");
-    if (int r = drain_engines(c, me)) return r;
+    if (int r = begin_pe_launch(c, me)) return r;
     if (nelems == 0) return SHM_OK;
     hipLaunchKernelGGL(shmk_strided, dim3(n_wg ? n_wg : 1), dim3(n_wg ? SHMK_WG : 64), 0, c->stream[me], dev_view(c), dst_off, src_off,
                        static_cast<size_t>(dst_stride), static_cast<size_t>(src_stride), nelems, static_cast<uint32_t>(elem_bytes), me, pe,
@@ -1000,6 +1041,7 @@ int shm_launch_offload_nop(shm_ctx *c, int me, int n_wg, int reps, int blocking,
     if (!dev_ticks) return fail(SHM_EINVAL, "null tick buffer");
     if (c->no_device) return no_device("shm_launch_offload_nop");
     if (!c->proxy.running()) return fail(SHM_EINVAL, "the host proxy is not running (shm_proxy_start)");
+    if (int r = begin_pe_launch(c, me)) return r;
     hipLaunchKernelGGL(shmk_offload_nop, dim3(n_wg), dim3(SHMK_WG), 0, c->stream[me], dev_view(c), me, reps, blocking,
                        reinterpret_cast<unsigned long long *>(dev_ticks));
     return launched("offload ring test");
@@ -1022,7 +1064,7 @@ int shm_launch_wg_put_signal(shm_ctx *c, int me, int pe, uint64_t dst_off, uint6
     if (n && sig_off + 8 > dst_off && sig_off < dst_off + n)
         return fail(SHM_EINVAL, "signal word lies inside the destination");
     if (c->no_device) return no_device("shm_launch_wg_put_signal");
-    if (int r = drain_engines(c, me)) return r;
+    if (int r = begin_pe_launch(c, me)) return r;
     uint64_t *arrive = nullptr;
     if (n_wg > 1) arrive = reinterpret_cast<uint64_t *>(shm_ptr(c, c->user_bytes, me)) + take_slots(c, me, 1);
     hipLaunchKernelGGL(shmk_wg_put_signal, dim3(n_wg), dim3(SHMK_WG), 0, c->stream[me], dev_view(c), me, pe, dst_off, src_off, n,
@@ -1037,7 +1079,7 @@ int shm_launch_signal_wait_until(shm_ctx *c, int me, uint64_t sig_off, int cmp, 
     if (int r = check_word(c, sig_off, "signal")) return r;
     if (cmp < SHM_CMP_EQ || cmp > SHM_CMP_LE) return fail(SHM_EINVAL, "unknown comparison %d", cmp);
     if (c->no_device) return no_device("shm_launch_signal_wait_until");
-    if (int r = drain_engines(c, me)) return r;
+    if (int r = begin_pe_launch(c, me)) return r;
     hipLaunchKernelGGL(shmk_signal_wait, dim3(1), dim3(SHMK_WG), 0, c->stream[me], dev_view(c), me, sig_off, cmp, val, dev_out);
     return launched("signal wait");
 }
@@ -1050,7 +1092,7 @@ int shm_launch_amo(shm_ctx *c, int me, int pe, uint64_t off, int op, int64_t ope
     if (int r = check_word(c, off, "atomic target")) return r;
     if (op < SHM_AMO_FETCH || op > SHM_AMO_INC) return fail(SHM_EINVAL, "unknown atomic op %d", op);
     if (c->no_device) return no_device("shm_launch_amo");
-    if (int r = drain_engines(c, me)) return r;
+    if (int r = begin_pe_launch(c, me)) return r;
     hipLaunchKernelGGL(shmk_amo, dim3(1), dim3(64), 0, c->stream[me], dev_view(c), pe, off, op, operand, cond, dev_out);
     return launched("atomic");
 }
@@ -1067,6 +1109,8 @@ int shm_launch_pingflag(shm_ctx *c, uint64_t data_off, uint64_t back_off, size_t
         return fail(SHM_EINVAL, "flag lies inside a data buffer");
     if (c->no_device) return no_device("shm_launch_pingflag");
     if (int r = drain_all_engines(c)) return r;
+    if (int r = begin_pe_launch(c, 0)) return r;
+    if (int r = begin_pe_launch(c, 1)) return r;
     const shm_dev_ctx d = dev_view(c);
     // The producer is enqueued first: it never waits, so the consumer's bounded wait always ends.
     hipLaunchKernelGGL(shmk_ping_producer, dim3(1), dim3(SHMK_WG), 0, c->stream[0], d, data_off, n, flag_off);

@@ -28,6 +28,7 @@ SHM_INIT_DEFAULT, SHM_INIT_NO_DEVICE = 0, 1
 SHM_STORM_FETCH_ADD, SHM_STORM_ADD, SHM_STORM_CSWAP_LOOP, SHM_STORM_PLAIN_STORE = range(4)
 SHM_REDUCE_DUPLICATE, SHM_REDUCE_SPLIT = 0, 1
 SHM_COLL_FCOLLECT, SHM_COLL_BROADCAST = 0, 1
+SHM_TEAM_SYNC_OFF, SHM_TEAM_SYNC_FULL, SHM_TEAM_SYNC_TRACKED = 0, 1, 2
 SHM_NO_CONSUME = (1 << 64) - 1
 SHM_CUTOVER_TUNED = (1 << 64) - 2
 SHM_OP_MIN, SHM_OP_MAX, SHM_OP_SUM, SHM_OP_PROD, SHM_OP_AND, SHM_OP_OR, SHM_OP_XOR = range(7)
@@ -271,8 +272,9 @@ class Shm:
     def set_wait_timeout_us(self, us: int):
         self._check(self.lib.shm_set_wait_timeout_us(self.ctx, us))
 
-    def set_team_sync(self, on: bool):
-        self._check(self.lib.shm_set_team_sync(self.ctx, int(on)))
+    def set_team_sync(self, mode):
+        """False / SHM_TEAM_SYNC_OFF, True / SHM_TEAM_SYNC_FULL or SHM_TEAM_SYNC_TRACKED."""
+        self._check(self.lib.shm_set_team_sync(self.ctx, int(mode)))
 
     # ---- kernel launches --------------------------------------------------------------------
     def launch_wg_put(self, me, pe, dst_off, src_off, n, n_wg=1, path=SHM_PATH_LDST):

@@ -280,3 +280,14 @@ def test_device_view_for_application_kernels():
     example.shmu_device_context_bytes.restype = ctypes.c_size_t
     assert example.shmu_device_context_bytes() == n
     assert hasattr(example, "shmu_alltoall")
+
+
+def test_team_sync_modes():
+    g = _ctx()
+    for mode in (S.SHM_TEAM_SYNC_OFF, S.SHM_TEAM_SYNC_TRACKED, S.SHM_TEAM_SYNC_FULL, True, False):
+        g.set_team_sync(mode)
+    for bad in (3, -1, 17):
+        with pytest.raises(S.ShmError) as e:
+            g.set_team_sync(bad)
+        assert e.value.code == S.SHM_EINVAL
+    g.finalize()

@@ -41,6 +41,8 @@ class Tracker:
 
 
 def _program(g, o, npes, seed, n_ops, with_engines):
+    # every operation here goes through the library, so the cheap tracked ordering must serve as well as the full one
+    g.set_team_sync(S.SHM_TEAM_SYNC_TRACKED if seed % 2 else S.SHM_TEAM_SYNC_FULL)
     rng = np.random.default_rng(seed)
     tr = Tracker()
     paths = [S.SHM_PATH_LDST, S.SHM_PATH_LDST, S.SHM_PATH_MEMCPY] + ([S.SHM_PATH_SDMA, S.SHM_PATH_AUTO] if with_engines else [])

@@ -89,13 +89,15 @@ def test_collectives_on_auto_follow_their_own_cutover():
             assert_heaps_equal(g, o, upto=12 * MiB, what=f"n {n}")
 
 
+@pytest.mark.parametrize("mode", [S.SHM_TEAM_SYNC_FULL, S.SHM_TEAM_SYNC_TRACKED])
 @pytest.mark.parametrize("empty", ["reduce", "reduce_sum_f32", "fcollect", "collect", "broadcast"])
-def test_an_empty_team_launch_still_orders_the_streams(empty):
+def test_an_empty_team_launch_still_orders_the_streams(empty, mode):
     """A slow put on PE 1's stream, a team launch with nothing to move, then -- with no host barrier --
     a get on PE 0's stream that reads what the put wrote: the team launch's join/fork is what orders
     the two, also when it has no kernel to run."""
     g, o = make_pair(3, 80 * MiB)
     with g:
+        g.set_team_sync(mode)
         fill_random(g, o, 45, upto=72 * MiB)
         n = 20 * MiB + 5
         for rep in range(3):
@@ -118,13 +120,15 @@ def test_an_empty_team_launch_still_orders_the_streams(empty):
             assert_heaps_equal(g, o, upto=72 * MiB, what=f"{empty}, repetition {rep}")
 
 
+@pytest.mark.parametrize("mode", [S.SHM_TEAM_SYNC_FULL, S.SHM_TEAM_SYNC_TRACKED])
 @pytest.mark.parametrize("kind", ["fcollect", "broadcast", "put_all"])
-def test_team_launch_on_the_engines_orders_other_pes_later_work(kind):
+def test_team_launch_on_the_engines_orders_other_pes_later_work(kind, mode):
     """Engine transfers are not on the streams.  With team sync on, work that another PE enqueues
     right after a team launch on the copy engines -- here a get of what the engines deliver to a
     third PE -- must find it delivered."""
     g, o = make_pair(4, 136 * MiB)
     with g:
+        g.set_team_sync(mode)
         fill_random(g, o, 46, upto=132 * MiB)
         n = 20 * MiB + 48                                              # a third of a millisecond per engine transfer
         src, dst, back = 4096, 24 * MiB, 108 * MiB
