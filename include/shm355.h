@@ -192,6 +192,10 @@ int shm_set_team_sync(shm_ctx *ctx, int mode);
 size_t shm_device_context_bytes(void);
 int    shm_device_context(const shm_ctx *ctx, void *out, size_t out_bytes);
 void  *shm_stream(const shm_ctx *ctx, int pe);
+/* Announces that the caller is about to enqueue work of its own on PE `pe`'s stream.  Needed under
+ * SHM_TEAM_SYNC_TRACKED only (harmless otherwise): PE pe's engine transfers are finished, its
+ * stream catches up with the team stream, and the next team launch waits for that stream. */
+int    shm_stream_used(shm_ctx *ctx, int pe);
 
 /* ---- kernel-launch entry points that exercise the device API ---------------------------------- */
 

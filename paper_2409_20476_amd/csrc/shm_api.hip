@@ -802,6 +802,14 @@ void *shm_stream(const shm_ctx *c, int pe)
     return c->stream[pe];
 }
 
+int shm_stream_used(shm_ctx *c, int pe)
+{
+    if (int r = check_ctx(c)) return r;
+    if (int r = check_pe(c, pe, "PE")) return r;
+    if (c->no_device) return no_device("shm_stream_used");
+    return begin_pe_launch(c, pe);
+}
+
 int shm_launch_wg_put(shm_ctx *c, int me, int pe, uint64_t dst_off, uint64_t src_off, size_t n, int n_wg, int path)
 {
     return wg_rma(c, me, pe, dst_off, src_off, n, n_wg, path, 0);

@@ -64,6 +64,7 @@ PROTOTYPES = {
     "shm_device_context_bytes": (c_size_t, []),
     "shm_device_context": (c_int, [c_void_p, c_void_p, c_size_t]),
     "shm_stream": (c_void_p, [c_void_p, c_int]),
+    "shm_stream_used": (c_int, [c_void_p, c_int]),
     "shm_set_collective_cutover": (c_int, [c_void_p, c_int, c_int, c_size_t]),
     "shm_get_collective_cutover": (c_int, [c_void_p, c_int, c_int, _szp]),
     "shm_choose_collective_path": (c_int, [c_void_p, c_int, c_size_t, c_int, _ip]),
@@ -241,6 +242,10 @@ class Shm:
     def stream(self, pe: int) -> int:
         """PE pe's hipStream_t as an integer (0 on error)."""
         return self.lib.shm_stream(self.ctx, pe) or 0
+
+    def stream_used(self, pe: int):
+        """Tell the tracked team sync that work of the caller's own is about to go onto PE pe's stream."""
+        self._check(self.lib.shm_stream_used(self.ctx, pe))
 
     # ---- policy ---------------------------------------------------------------------------
     def set_cutover(self, n_wg: int, nbytes: int):

@@ -76,3 +76,38 @@ def test_device_view_is_refused_at_another_size_and_streams_are_the_contexts():
         assert g.stream(0) == g.streams[0].cuda_stream and g.stream(1) == g.streams[1].cuda_stream
         assert g.stream(2) == 0 and g.stream(-1) == 0
         assert _example().shmu_alltoall(buf, n + 8, g.stream(0), 0, 4096, 16, 8192, 16384, 16392) == -1
+
+
+@pytest.mark.parametrize("mode", [S.SHM_TEAM_SYNC_FULL, S.SHM_TEAM_SYNC_TRACKED])
+def test_application_kernel_between_team_launches_is_ordered(mode):
+    """A team put produces the application kernel's input, the kernel runs on PE 2's stream, a team
+    broadcast consumes its output -- no host barrier in between.  Under the tracked team sync the
+    caller announces its own use of the stream with shm_stream_used."""
+    npes, n = 4, 300000
+    g, o = make_pair(npes, 16 * MiB)
+    with g:
+        lib = _example()
+        g.set_team_sync(mode)
+        fill_random(g, o, 52, upto=14 * MiB)
+        view = g.device_context()
+        pre, src, dst, back, tally, seen, out = 64, 2 * MiB, 5 * MiB, 9 * MiB, 11 * MiB, 11 * MiB + 64, 12 * MiB
+        for rep in range(3):
+            g.launch_wg_put_all(1, src, pre + rep, npes * n, 16)                   # input of the kernel: every PE's source blocks
+            snap = [h.copy() for h in o.heap]
+            for p in range(npes):
+                o.heap[(p + 1) % npes][src:src + npes * n] = snap[p][pre + rep:pre + rep + npes * n]
+            g.stream_used(2)
+            assert lib.shmu_alltoall(view, len(view), g.stream(2), dst, src, n, back, tally, seen) == 0
+            for p in range(npes):
+                for j in range(npes):
+                    t = (p + j) % npes
+                    o.putmem(p, dst + p * n, src + t * n, n, t)
+            for p in range(npes):
+                o.getmem(p, back, dst, n, (p + 1) % npes)
+            g.launch_broadcast(out, dst + n, 2 * n, 3, 8)                          # consumes slots 1 and 2 of PE 3's destination
+            o.broadcast(out, dst + n, 2 * n, 3)
+            g.barrier_all()
+            for p in range(npes):                                                  # tally and fetched values: checked in the test above
+                for off in (tally, seen):
+                    o.write(p, off, g.read(p, off, 8))
+            assert_heaps_equal(g, o, upto=14 * MiB, what=f"mode {mode}, repetition {rep}")
