@@ -436,13 +436,13 @@ template <typename T>
 reduce_kernel reduce_kernel_for(int op, bool bitwise_ok)
 {
     switch (op) {
-    case SHM_OP_MIN: return shmk_reduce<T, SHMK_OP_MIN>;
-    case SHM_OP_MAX: return shmk_reduce<T, SHMK_OP_MAX>;
-    case SHM_OP_SUM: return shmk_reduce<T, SHMK_OP_SUM>;
-    case SHM_OP_PROD: return shmk_reduce<T, SHMK_OP_PROD>;
-    case SHM_OP_AND: return bitwise_ok ? shmk_reduce<T, SHMK_OP_AND> : nullptr;
-    case SHM_OP_OR: return bitwise_ok ? shmk_reduce<T, SHMK_OP_OR> : nullptr;
-    case SHM_OP_XOR: return bitwise_ok ? shmk_reduce<T, SHMK_OP_XOR> : nullptr;
+    case SHM_OP_MIN: return shmk_reduce<T, SHMD_OP_MIN>;
+    case SHM_OP_MAX: return shmk_reduce<T, SHMD_OP_MAX>;
+    case SHM_OP_SUM: return shmk_reduce<T, SHMD_OP_SUM>;
+    case SHM_OP_PROD: return shmk_reduce<T, SHMD_OP_PROD>;
+    case SHM_OP_AND: return bitwise_ok ? shmk_reduce<T, SHMD_OP_AND> : nullptr;
+    case SHM_OP_OR: return bitwise_ok ? shmk_reduce<T, SHMD_OP_OR> : nullptr;
+    case SHM_OP_XOR: return bitwise_ok ? shmk_reduce<T, SHMD_OP_XOR> : nullptr;
     default: return nullptr;
     }
 }

@@ -1023,3 +1023,82 @@ __device__ __forceinline__ void shmx_broadcast_push(const shm_dev_ctx &c, int ro
         shmx_putmem_parts(c, root, dst_off, src_off, n, q, part, nparts);
     }
 }
+
+// ------------------------------------------------------------------------------------------
+// Reduction operators (paper section "Collective Operations", reduction paragraph): min, max, sum,
+// product, and, or, xor over 8..64-bit integers; min, max, sum, product over float and double.
+// Integer sums and products wrap (computed in the unsigned type); min/max keep the earlier operand
+// on ties, which also fixes the sign of a zero; the bitwise operators are not defined for the
+// floating types (the forms below only keep templates instantiable).
+// ------------------------------------------------------------------------------------------
+enum { SHMD_OP_MIN = 0, SHMD_OP_MAX = 1, SHMD_OP_SUM = 2, SHMD_OP_PROD = 3, SHMD_OP_AND = 4, SHMD_OP_OR = 5, SHMD_OP_XOR = 6 };
+
+template <typename T> struct shm_arith { typedef T type; };
+template <> struct shm_arith<int8_t> { typedef uint8_t type; };
+template <> struct shm_arith<int16_t> { typedef uint16_t type; };
+template <> struct shm_arith<int32_t> { typedef uint32_t type; };
+template <> struct shm_arith<int64_t> { typedef uint64_t type; };
+
+template <typename T> __device__ __forceinline__ T shm_bits_and(T a, T b) { return static_cast<T>(a & b); }
+template <typename T> __device__ __forceinline__ T shm_bits_or(T a, T b) { return static_cast<T>(a | b); }
+template <typename T> __device__ __forceinline__ T shm_bits_xor(T a, T b) { return static_cast<T>(a ^ b); }
+template <> __device__ __forceinline__ float shm_bits_and<float>(float a, float) { return a; }      // never selected for
+template <> __device__ __forceinline__ float shm_bits_or<float>(float a, float) { return a; }       // floating types: the
+template <> __device__ __forceinline__ float shm_bits_xor<float>(float a, float) { return a; }      // host rejects them
+template <> __device__ __forceinline__ double shm_bits_and<double>(double a, double) { return a; }
+template <> __device__ __forceinline__ double shm_bits_or<double>(double a, double) { return a; }
+template <> __device__ __forceinline__ double shm_bits_xor<double>(double a, double) { return a; }
+
+template <typename T, int OP>
+__device__ __forceinline__ T shm_combine(T a, T b)
+{
+    typedef typename shm_arith<T>::type A;
+    if (OP == SHMD_OP_MIN) return b < a ? b : a;
+    if (OP == SHMD_OP_MAX) return b > a ? b : a;
+    if (OP == SHMD_OP_SUM) return static_cast<T>(static_cast<A>(static_cast<A>(a) + static_cast<A>(b)));
+    if (OP == SHMD_OP_PROD) return static_cast<T>(static_cast<A>(static_cast<A>(a) * static_cast<A>(b)));
+    if (OP == SHMD_OP_AND) return shm_bits_and<T>(a, b);
+    if (OP == SHMD_OP_OR) return shm_bits_or<T>(a, b);
+    return shm_bits_xor<T>(a, b);
+}
+
+// ------------------------------------------------------------------------------------------
+// Collectives callable from inside a kernel (paper section "Proposed Device APIs": broadcast, reduce,
+// barrier_all and sync_all have work_group forms).  ONE work-group per PE calls them, all with the
+// same arguments, and the groups of all PEs must be resident together: they meet in barriers.
+// Each call ends with a barrier, so on return every PE sees the result and may reuse the source.
+// ------------------------------------------------------------------------------------------
+__device__ __forceinline__ void shmx_broadcast_wg(const shm_dev_ctx &c, int me, uint64_t dst_off, uint64_t src_off, size_t n, int root)
+{
+    if (me == root) shmx_broadcast_push(c, root, dst_off, src_off, n, 0, 1);
+    shmx_barrier_all_wg(c, me);
+}
+
+// Every PE's n bytes at src_off land, in PE order, at dst_off of every PE (push: the caller's block
+// goes to all PEs, the right-hand neighbour first).
+__device__ __forceinline__ void shmx_fcollect_wg(const shm_dev_ctx &c, int me, uint64_t dst_off, uint64_t src_off, size_t n)
+{
+    for (int j = 0; j < c.npes; ++j) {
+        int q = me + 1 + j;
+        if (q >= c.npes) q -= c.npes;
+        shmx_putmem_wg(c, me, dst_off + static_cast<uint64_t>(me) * n, src_off, n, q);
+    }
+    shmx_barrier_all_wg(c, me);
+}
+
+// dst[i] = src_0[i] OP src_1[i] OP ... in PE order, on every PE (the paper's method: every PE folds
+// the whole vector itself from remote loads, so nobody waits for a partial result).  The entry
+// barrier makes every PE's source complete and visible; element-aligned offsets; source and
+// destination do not overlap.
+template <typename T, int OP>
+__device__ __forceinline__ void shmx_reduce_wg(const shm_dev_ctx &c, int me, uint64_t dst_off, uint64_t src_off, size_t nelems)
+{
+    shmx_barrier_all_wg(c, me);
+    T *d = reinterpret_cast<T *>(shm_ptr(c, dst_off, me));
+    for (size_t i = threadIdx.x; i < nelems; i += blockDim.x) {
+        T r = reinterpret_cast<const T *>(shm_ptr(c, src_off, 0))[i];
+        for (int p = 1; p < c.npes; ++p) r = shm_combine<T, OP>(r, reinterpret_cast<const T *>(shm_ptr(c, src_off, p))[i]);
+        d[i] = r;
+    }
+    shmx_barrier_all_wg(c, me);
+}

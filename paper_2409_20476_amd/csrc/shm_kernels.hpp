@@ -776,37 +776,6 @@ __global__ __launch_bounds__(SHMK_WG) void shmk_broadcast(shm_dev_ctx c, uint64_
 // PE's destination; every PE (blockIdx.y) duplicates the computation, so no PE waits for another.
 // Integer sums and products wrap (computed in the unsigned type); min/max keep the earlier operand
 // on ties, which also fixes the sign of a zero.
-enum { SHMK_OP_MIN = 0, SHMK_OP_MAX = 1, SHMK_OP_SUM = 2, SHMK_OP_PROD = 3, SHMK_OP_AND = 4, SHMK_OP_OR = 5, SHMK_OP_XOR = 6 };
-
-template <typename T> struct shmk_arith { typedef T type; };
-template <> struct shmk_arith<int8_t> { typedef uint8_t type; };
-template <> struct shmk_arith<int16_t> { typedef uint16_t type; };
-template <> struct shmk_arith<int32_t> { typedef uint32_t type; };
-template <> struct shmk_arith<int64_t> { typedef uint64_t type; };
-
-template <typename T> __device__ __forceinline__ T shmk_bits_and(T a, T b) { return static_cast<T>(a & b); }
-template <typename T> __device__ __forceinline__ T shmk_bits_or(T a, T b) { return static_cast<T>(a | b); }
-template <typename T> __device__ __forceinline__ T shmk_bits_xor(T a, T b) { return static_cast<T>(a ^ b); }
-template <> __device__ __forceinline__ float shmk_bits_and<float>(float a, float) { return a; }      // never selected for
-template <> __device__ __forceinline__ float shmk_bits_or<float>(float a, float) { return a; }       // floating types: the
-template <> __device__ __forceinline__ float shmk_bits_xor<float>(float a, float) { return a; }      // host rejects them
-template <> __device__ __forceinline__ double shmk_bits_and<double>(double a, double) { return a; }
-template <> __device__ __forceinline__ double shmk_bits_or<double>(double a, double) { return a; }
-template <> __device__ __forceinline__ double shmk_bits_xor<double>(double a, double) { return a; }
-
-template <typename T, int OP>
-__device__ __forceinline__ T shmk_combine(T a, T b)
-{
-    typedef typename shmk_arith<T>::type A;
-    if (OP == SHMK_OP_MIN) return b < a ? b : a;
-    if (OP == SHMK_OP_MAX) return b > a ? b : a;
-    if (OP == SHMK_OP_SUM) return static_cast<T>(static_cast<A>(static_cast<A>(a) + static_cast<A>(b)));
-    if (OP == SHMK_OP_PROD) return static_cast<T>(static_cast<A>(static_cast<A>(a) * static_cast<A>(b)));
-    if (OP == SHMK_OP_AND) return shmk_bits_and<T>(a, b);
-    if (OP == SHMK_OP_OR) return shmk_bits_or<T>(a, b);
-    return shmk_bits_xor<T>(a, b);
-}
-
 template <typename T, int OP>
 __global__ __launch_bounds__(SHMK_WG) void shmk_reduce(shm_dev_ctx c, uint64_t dst_off, uint64_t src_off, size_t nelems, int split)
 {
@@ -855,9 +824,9 @@ __global__ __launch_bounds__(SHMK_WG) void shmk_reduce(shm_dev_ctx c, uint64_t d
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
 #pragma unroll
-                for (int k = 0; k < EPV; ++k) r0.e[k] = shmk_combine<T, OP>(r0.e[k], x0[j].e[k]);
+                for (int k = 0; k < EPV; ++k) r0.e[k] = shm_combine<T, OP>(r0.e[k], x0[j].e[k]);
 #pragma unroll
-                for (int k = 0; k < EPV; ++k) r1.e[k] = shmk_combine<T, OP>(r1.e[k], x1[j].e[k]);
+                for (int k = 0; k < EPV; ++k) r1.e[k] = shm_combine<T, OP>(r1.e[k], x1[j].e[k]);
             }
         }
         for (; p + 1 < npes; p += 2) {
@@ -870,9 +839,9 @@ __global__ __launch_bounds__(SHMK_WG) void shmk_reduce(shm_dev_ctx c, uint64_t d
 #pragma unroll
             for (int j = 0; j < 2; ++j) {
 #pragma unroll
-                for (int k = 0; k < EPV; ++k) r0.e[k] = shmk_combine<T, OP>(r0.e[k], x0[j].e[k]);
+                for (int k = 0; k < EPV; ++k) r0.e[k] = shm_combine<T, OP>(r0.e[k], x0[j].e[k]);
 #pragma unroll
-                for (int k = 0; k < EPV; ++k) r1.e[k] = shmk_combine<T, OP>(r1.e[k], x1[j].e[k]);
+                for (int k = 0; k < EPV; ++k) r1.e[k] = shm_combine<T, OP>(r1.e[k], x1[j].e[k]);
             }
         }
         for (; p < npes; ++p) {
@@ -880,9 +849,9 @@ __global__ __launch_bounds__(SHMK_WG) void shmk_reduce(shm_dev_ctx c, uint64_t d
             x0.v = load(reinterpret_cast<const shm_u32x4 *>(shm_ptr(c, src_off, p)) + i);
             x1.v = load(reinterpret_cast<const shm_u32x4 *>(shm_ptr(c, src_off, p)) + i + SHMK_WG);
 #pragma unroll
-            for (int k = 0; k < EPV; ++k) r0.e[k] = shmk_combine<T, OP>(r0.e[k], x0.e[k]);
+            for (int k = 0; k < EPV; ++k) r0.e[k] = shm_combine<T, OP>(r0.e[k], x0.e[k]);
 #pragma unroll
-            for (int k = 0; k < EPV; ++k) r1.e[k] = shmk_combine<T, OP>(r1.e[k], x1.e[k]);
+            for (int k = 0; k < EPV; ++k) r1.e[k] = shm_combine<T, OP>(r1.e[k], x1.e[k]);
         }
         for (int d = d0; d < d1; ++d) {
             shm_st16(reinterpret_cast<shm_u32x4 *>(shm_ptr(c, dst_off, d)) + i, r0.v);
@@ -896,7 +865,7 @@ __global__ __launch_bounds__(SHMK_WG) void shmk_reduce(shm_dev_ctx c, uint64_t d
             vec x;
             x.v = load(reinterpret_cast<const shm_u32x4 *>(shm_ptr(c, src_off, p)) + i);
 #pragma unroll
-            for (int k = 0; k < EPV; ++k) r.e[k] = shmk_combine<T, OP>(r.e[k], x.e[k]);
+            for (int k = 0; k < EPV; ++k) r.e[k] = shm_combine<T, OP>(r.e[k], x.e[k]);
         }
         for (int d = d0; d < d1; ++d) shm_st16(reinterpret_cast<shm_u32x4 *>(shm_ptr(c, dst_off, d)) + i, r.v);
     }
@@ -904,7 +873,7 @@ __global__ __launch_bounds__(SHMK_WG) void shmk_reduce(shm_dev_ctx c, uint64_t d
     const size_t t = nvec * EPV + threadIdx.x;
     if (part == 0 && (!split || q == 0) && t < nelems) {
         T r = reinterpret_cast<const T *>(shm_ptr(c, src_off, 0))[t];
-        for (int p = 1; p < npes; ++p) r = shmk_combine<T, OP>(r, reinterpret_cast<const T *>(shm_ptr(c, src_off, p))[t]);
+        for (int p = 1; p < npes; ++p) r = shm_combine<T, OP>(r, reinterpret_cast<const T *>(shm_ptr(c, src_off, p))[t]);
         for (int d = d0; d < d1; ++d) reinterpret_cast<T *>(shm_ptr(c, dst_off, d))[t] = r;
     }
 }

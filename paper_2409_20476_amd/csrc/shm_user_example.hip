@@ -3,7 +3,7 @@
 // shm_device_context() hands out, and calls the OpenSHMEM operations from inside its own kernel.
 // Built as a separate shared library (libshm355_user_example.so) that does not link the library.
 //
-// The kernel is an all-to-all exchange with a device-side barrier and an atomic tally:
+// The first kernel is an all-to-all exchange with a device-side barrier and an atomic tally:
 //   * one work-group per PE (blockIdx.x = PE p); block t of p's source goes to slot p of PE t's
 //     destination with a work-group put (p's own block included);
 //   * barrier_all_work_group: everybody's blocks have landed and are visible;
@@ -38,6 +38,19 @@ __global__ __launch_bounds__(256) void shmu_alltoall_kernel(shm_dev_ctx c, uint6
     }
 }
 
+// The collectives called from inside a kernel, one work-group per PE: every PE's block gathered on
+// every PE, two reductions over the PEs' sources (int32 sum, int16 min), and the root's block
+// broadcast -- each a single device call ending in its own barrier.
+__global__ __launch_bounds__(256) void shmu_collectives_kernel(shm_dev_ctx c, uint64_t gather_off, uint64_t src_off, size_t n, uint64_t sum_off,
+                                                               uint64_t min_off, size_t nelems, uint64_t bcast_off, int root)
+{
+    const int me = blockIdx.x;
+    shmx_fcollect_wg(c, me, gather_off, src_off, n);
+    shmx_reduce_wg<int32_t, SHMD_OP_SUM>(c, me, sum_off, src_off, nelems);
+    shmx_reduce_wg<int16_t, SHMD_OP_MIN>(c, me, min_off, src_off, 2 * nelems);
+    shmx_broadcast_wg(c, me, bcast_off, src_off, n, root);
+}
+
 }  // namespace
 
 extern "C" {
@@ -54,6 +67,19 @@ int shmu_alltoall(const void *devctx, size_t devctx_bytes, void *stream, uint64_
     if (c.npes < 1 || c.npes > SHM_MAX_PES) return -1;
     hipLaunchKernelGGL(shmu_alltoall_kernel, dim3(c.npes), dim3(256), 0, static_cast<hipStream_t>(stream), c, dst_off, src_off, n, back_off,
                        tally_off, seen_off);
+    return hipGetLastError() == hipSuccess ? 0 : -5;
+}
+
+// n bytes per PE are gathered and broadcast; the first 4 * nelems of them are reduced.  Offsets 4-byte aligned.
+int shmu_collectives(const void *devctx, size_t devctx_bytes, void *stream, uint64_t gather_off, uint64_t src_off, size_t n, uint64_t sum_off,
+                     uint64_t min_off, size_t nelems, uint64_t bcast_off, int root)
+{
+    if (!devctx || devctx_bytes != sizeof(shm_dev_ctx) || ((src_off | sum_off | min_off) & 3) || 4 * nelems > n) return -1;
+    shm_dev_ctx c;
+    memcpy(&c, devctx, sizeof c);
+    if (c.npes < 1 || c.npes > SHM_MAX_PES || root < 0 || root >= c.npes) return -1;
+    hipLaunchKernelGGL(shmu_collectives_kernel, dim3(c.npes), dim3(256), 0, static_cast<hipStream_t>(stream), c, gather_off, src_off, n, sum_off,
+                       min_off, nelems, bcast_off, root);
     return hipGetLastError() == hipSuccess ? 0 : -5;
 }
 

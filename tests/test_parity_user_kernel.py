@@ -111,3 +111,25 @@ def test_application_kernel_between_team_launches_is_ordered(mode):
                 for off in (tally, seen):
                     o.write(p, off, g.read(p, off, 8))
             assert_heaps_equal(g, o, upto=14 * MiB, what=f"mode {mode}, repetition {rep}")
+
+
+@pytest.mark.parametrize("npes,n,nelems,root", [(2, 4096, 1000, 1), (8, 100000, 25000, 5), (5, 16, 4, 0), (16, 20000, 17, 15), (1, 64, 16, 0)])
+def test_application_kernel_calls_the_collectives(npes, n, nelems, root):
+    """fcollect, two reductions and a broadcast as single device calls from one kernel of one group per PE."""
+    g, o = make_pair(npes, 16 * MiB)
+    with g:
+        lib = _example()
+        lib.shmu_collectives.restype = ctypes.c_int
+        lib.shmu_collectives.argtypes = [ctypes.c_char_p, ctypes.c_size_t, ctypes.c_void_p, ctypes.c_uint64, ctypes.c_uint64, ctypes.c_size_t,
+                                         ctypes.c_uint64, ctypes.c_uint64, ctypes.c_size_t, ctypes.c_uint64, ctypes.c_int]
+        fill_random(g, o, 53, upto=12 * MiB)
+        view = g.device_context()
+        src, gather, sums, mins, bcast = 4096, 1 * MiB, 8 * MiB, 9 * MiB, 10 * MiB
+        for rep in range(2):
+            assert lib.shmu_collectives(view, len(view), g.stream(0), gather, src + 16 * rep, n, sums, mins, nelems, bcast, root) == 0
+            g.barrier_all()
+            o.fcollect(gather, src + 16 * rep, n)
+            o.reduce(sums, src + 16 * rep, nelems, np.int32, "sum")
+            o.reduce(mins, src + 16 * rep, 2 * nelems, np.int16, "min")
+            o.broadcast(bcast, src + 16 * rep, n, root)
+            assert_heaps_equal(g, o, upto=12 * MiB, what=f"repetition {rep}")
