@@ -15,17 +15,19 @@ pytestmark = pytest.mark.gpu
 
 MiB = 1 << 20
 ARENA = 3 * MiB // 2          # operations stay in the first 1.5 MiB; the rest of the heap is canary
+CHAIN = ARENA + 400 * 1024    # eight signal words per PE for the put-signal / wait chains, beyond the reach of every other
+                              # operation (those start inside the arena and are at most 300 000 bytes long)
 
 
 class Tracker:
     """What has been issued since the last point every stream was ordered behind."""
 
     def __init__(self):
-        self.pending = []      # (stream, [(pe, lo, hi, is_write)])
+        self.pending = []      # [stream, [(pe, lo, hi, is_write)], set of streams ordered behind this entry]
 
     def conflicts(self, stream, touched):
-        for other_stream, regions in self.pending:
-            if other_stream == stream:
+        for other_stream, regions, behind in self.pending:
+            if other_stream == stream or stream in behind:
                 continue
             for (p, lo, hi, w) in regions:
                 for (q, a, b, v) in touched:
@@ -34,7 +36,15 @@ class Tracker:
         return False
 
     def add(self, stream, touched):
-        self.pending.append((stream, touched))
+        self.pending.append([stream, touched, set()])
+        return len(self.pending) - 1
+
+    def order_behind(self, producer_stream, upto, consumer_stream):
+        """A satisfied wait on consumer_stream for a signal whose put was entry `upto` of producer_stream:
+        everything that stream enqueued up to that entry is now ordered before the consumer's later work."""
+        for entry in self.pending[:upto + 1]:
+            if entry[0] == producer_stream:
+                entry[2].add(consumer_stream)
 
     def clear(self):
         self.pending = []
@@ -49,9 +59,20 @@ def _program(g, o, npes, seed, n_ops, with_engines):
     modes = [0, 0, 1, 2, 3, 4] if with_engines else [0]        # device-initiated transfers: the engine modes need the proxy
     issued = barriers = 0
     counts = {}
+    # signal words of their own, outside the arena, only ever ADDed to by put-with-signal: a wait for the
+    # running total is then a wait for every put issued so far, and orders the waiting stream behind them
+    chain_total = {}           # (pe, k) -> total added so far
+    chain_producers = {}       # (pe, k) -> [(stream, tracker entry, payload offset, payload bytes)] since the streams were last ordered
+    for p in range(npes):
+        zero = np.zeros(64, np.uint8)
+        g.write(p, CHAIN, zero), o.write(p, CHAIN, zero)
     if with_engines:
         g.proxy_start()
         g.set_cutover(1, 100000)          # AUTO by one group takes the engines from 100 000 bytes
+
+    def clear_all():
+        tr.clear()                 # every stream has been ordered behind everything issued so far ...
+        chain_producers.clear()    # ... so there is no put left that a wait would still have to order
 
     def off(align=1, span=ARENA):
         return int(rng.integers(0, span)) // align * align
@@ -61,7 +82,7 @@ def _program(g, o, npes, seed, n_ops, with_engines):
 
     for i in range(n_ops):
         kind = str(rng.choice(["wg_put", "wg_get", "host_put", "host_get", "put_signal", "amo", "fcollect", "collect", "broadcast", "reduce",
-                               "iput", "iget", "scalar", "thread", "dev_put", "dev_get", "wave"]))
+                               "iput", "iget", "scalar", "thread", "dev_put", "dev_get", "wave", "chain_put", "chain_wait"]))
         me, pe = int(rng.integers(npes)), int(rng.integers(npes))
         team = kind in ("fcollect", "collect", "broadcast", "reduce")
         try:
@@ -91,6 +112,29 @@ def _program(g, o, npes, seed, n_ops, with_engines):
                 o.put_signal(me, d, s, n, sig, val, op, pe, n_wg)
                 touched = [(me, s, s + n, False), (pe, d, d + n, True), (pe, sig, sig + 8, True)]
                 call = lambda: g.launch_wg_put_signal(me, pe, d, s, n, sig, val, op, n_wg)
+            elif kind == "chain_put":
+                d, s, n, k = off(), off(), size(), int(rng.integers(8))
+                val, n_wg = int(rng.integers(1, 1000)), int(rng.choice([1, 3, 16]))
+                o.put_signal(me, d, s, n, CHAIN + 8 * k, val, SIGNAL_ADD, pe, n_wg)
+                touched = [(me, s, s + n, False), (pe, d, d + n, True)]
+                call = lambda: g.launch_wg_put_signal(me, pe, d, s, n, CHAIN + 8 * k, val, SIGNAL_ADD, n_wg)
+                chain = (pe, k, val, d, n)
+            elif kind == "chain_wait":
+                waiting = [key for key, producers in chain_producers.items() if producers]
+                if not waiting:
+                    continue
+                pe, k = waiting[int(rng.integers(len(waiting)))]
+                me = pe                                          # a PE waits on its own signal word ...
+                o.signal_wait_until(pe, CHAIN + 8 * k, S.SHM_CMP_GE, chain_total[(pe, k)])
+                _, _, d, n = chain_producers[(pe, k)][-1]
+                scratch = off(1, ARENA - n)
+                o.putmem(pe, scratch, d, n, pe)                  # ... and then reads the payload that came with it
+                for stream, entry, _, _ in chain_producers[(pe, k)]:
+                    tr.order_behind(stream, entry, pe)
+                chain_producers[(pe, k)] = []
+                touched = [(pe, d, d + n, False), (pe, scratch, scratch + n, True)]
+                total = chain_total[(pe, k)]
+                call = lambda: (g.launch_signal_wait_until(pe, CHAIN + 8 * k, S.SHM_CMP_GE, total), g.launch_wg_put(pe, pe, scratch, d, n, 4))
             elif kind == "wave":
                 d, s, back, n = off(), off(), off(), min(size(), 100000)
                 n_waves = int(rng.choice([1, 3, 8, 64]))
@@ -103,7 +147,7 @@ def _program(g, o, npes, seed, n_ops, with_engines):
                 o.wave_exchange(me, pe, d, s, back, n, n_waves, flag, out)      # raises if it is not a defined operation ...
                 g.barrier_all()                                                 # ... else the flag words start at zero on both sides
                 barriers += 1
-                tr.clear()
+                clear_all()
                 g.write(pe, flag, np.zeros(8 * n_waves, np.uint8))
                 touched = [(me, s, s + n, False), (pe, d, d + n, True), (pe, back, back + n, True), (pe, flag, flag + 8 * n_waves, True),
                            (pe, out, out + 8 * n_waves, True)]
@@ -161,19 +205,23 @@ def _program(g, o, npes, seed, n_ops, with_engines):
             continue                      # not a defined operation (overlap, range): not issued on either side
         if team:
             call()                        # joins and forks every PE stream: ordered against everything
-            tr.clear()
+            clear_all()
         else:
             if tr.conflicts(me, touched):
                 g.barrier_all()
                 barriers += 1
-                tr.clear()
+                clear_all()
             call()
-            tr.add(me, touched)
+            entry = tr.add(me, touched)
+            if kind == "chain_put":
+                pe_, k_, val_, d_, n_ = chain
+                chain_total[(pe_, k_)] = chain_total.get((pe_, k_), 0) + val_
+                chain_producers.setdefault((pe_, k_), []).append((me, entry, d_, n_))
         issued += 1
         counts[kind] = counts.get(kind, 0) + 1
         if i % 40 == 39:
             g.barrier_all()
-            tr.clear()
+            clear_all()
             assert_heaps_equal(g, o, what=f"seed {seed}, after operation {i} ({kind}); issued so far: {counts}")
     if with_engines:
         g.proxy_stop()
@@ -190,5 +238,5 @@ def test_random_program(npes, seed, with_engines):
         fill_random(g, o, seed)
         issued, barriers, counts = _program(g, o, npes, seed, 600, with_engines)
         print(f"npes {npes}: {issued} operations, {barriers} barriers for conflicts, {counts}")
-        assert issued > 400 and len(counts) == 17, (issued, counts)
+        assert issued > 400 and len(counts) == 19, (issued, counts)
         assert barriers < issued // 2, "the program should mostly rely on stream order and team joins, not on host barriers"
