@@ -583,15 +583,13 @@ __global__ __launch_bounds__(SHMK_WG) void shmk_fcollect_vec(shm_dev_ctx c, uint
     }
 }
 
-// Any alignment or length: one multi-group put per destination.
+// Any alignment or length: PE p's block is pushed to every PE like a broadcast rooted at p -- each
+// vector loaded once and stored to all PEs where source and destination are 16-byte aligned, one
+// multi-group put per destination otherwise.
 __global__ __launch_bounds__(SHMK_WG) void shmk_fcollect_any(shm_dev_ctx c, uint64_t dst_off, uint64_t src_off, size_t bytes_per_pe)
 {
-    const int p = blockIdx.y, npes = c.npes;
-    for (int j = 0; j < npes; ++j) {
-        int q = p + 1 + j;
-        if (q >= npes) q -= npes;
-        shmx_putmem_parts(c, p, dst_off + static_cast<uint64_t>(p) * bytes_per_pe, src_off, bytes_per_pe, q, blockIdx.x, gridDim.x);
-    }
+    const int p = blockIdx.y;
+    shmx_broadcast_push(c, p, dst_off + static_cast<uint64_t>(p) * bytes_per_pe, src_off, bytes_per_pe, blockIdx.x, gridDim.x);
 }
 
 // collect: as fcollect with a block size per PE; the launcher passes every PE's size and the offset
@@ -603,12 +601,8 @@ struct shmk_collect_table {
 
 __global__ __launch_bounds__(SHMK_WG) void shmk_collect(shm_dev_ctx c, uint64_t dst_off, uint64_t src_off, shmk_collect_table t)
 {
-    const int p = blockIdx.y, npes = c.npes;
-    for (int j = 0; j < npes; ++j) {
-        int q = p + 1 + j;
-        if (q >= npes) q -= npes;
-        shmx_putmem_parts(c, p, dst_off + t.at[p], src_off, t.nbytes[p], q, blockIdx.x, gridDim.x);
-    }
+    const int p = blockIdx.y;
+    shmx_broadcast_push(c, p, dst_off + t.at[p], src_off, t.nbytes[p], blockIdx.x, gridDim.x);
 }
 
 // Team grids (n_wg, npes) whose npes groups with the same blockIdx.x read the SAME source bytes
