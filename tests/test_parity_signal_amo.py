@@ -201,3 +201,39 @@ def test_config4_full_size():
         for p in range(16):
             write_both(g, o, p, 0, np.zeros(1024, np.int64))
         _check_storm(g, o, 16, 1024, 1 << 20, 64, S.SHM_STORM_FETCH_ADD, 0)
+
+
+@pytest.mark.parametrize("rounds,seed", [(150, 81), (150, 82)])
+def test_ping_pong_with_credits_many_rounds_without_host_synchronisation(rounds, seed):
+    """The protocol put-with-signal exists for, all of it enqueued up front on two PEs' streams:
+    PE 0 waits for a credit, puts the round's payload into ONE reused buffer on PE 1 with signal
+    'data += 1'; PE 1 waits for the data, copies the payload away and returns a credit with a
+    zero-byte put-with-signal.  Only the signals order the two streams: a payload read before it has
+    landed, or overwritten before it was read, shows in the copies."""
+    g, o = make_pair(2, 48 * MiB)
+    rng = np.random.default_rng(seed)
+    with g:
+        fill_random(g, o, seed, upto=40 * MiB)
+        data_sig, credit_sig, buf, keep = 39 * MiB, 39 * MiB + 64, 16 * MiB, 17 * MiB
+        for p in range(2):
+            write_both(g, o, p, 39 * MiB, np.zeros(128, np.uint8))
+        at = keep
+        for r in range(rounds):
+            n = int(rng.integers(0, 120000)) if r % 5 else int(rng.choice([0, 1, 8, 16, 4096]))
+            src, off, n_wg = int(rng.integers(0, 15 * MiB)), int(rng.integers(0, 16)), int(rng.choice([1, 2, 3, 16]))
+            # PE 0: wait until the buffer is free again (r credits returned), then send
+            g.launch_signal_wait_until(0, credit_sig, S.SHM_CMP_GE, r)
+            g.launch_wg_put_signal(0, 1, buf + off, src, n, data_sig, 1, SIGNAL_ADD, n_wg)
+            # PE 1: wait for round r's data, keep a copy, give the buffer back
+            g.launch_signal_wait_until(1, data_sig, S.SHM_CMP_GE, r + 1)
+            g.launch_wg_put(1, 1, at, buf + off, n, int(rng.choice([1, 4])))
+            g.launch_wg_put_signal(1, 0, 0, 0, 0, credit_sig, 1, SIGNAL_ADD, 1)
+            o.signal_wait_until(0, credit_sig, S.SHM_CMP_GE, r)
+            o.put_signal(0, buf + off, src, n, data_sig, 1, SIGNAL_ADD, 1, n_wg)
+            o.signal_wait_until(1, data_sig, S.SHM_CMP_GE, r + 1)
+            o.putmem(1, at, buf + off, n, 1)
+            o.put_signal(1, 0, 0, 0, credit_sig, 1, SIGNAL_ADD, 0, 1)
+            at += n + int(rng.integers(0, 64))
+        g.barrier_all()
+        assert o.signal_fetch(1, data_sig) == rounds and o.signal_fetch(0, credit_sig) == rounds
+        assert_heaps_equal(g, o, upto=40 * MiB, what=f"{rounds} rounds")
