@@ -21,6 +21,10 @@
  * Errors: every int function returns SHM_OK (0) or a negative code; nothing throws
  * or aborts.  shm_last_error() gives a thread-local text for the last failure.
  *
+ * Threads: a context is driven by one host thread at a time (the library takes no locks; the
+ * host proxy thread it starts itself shares nothing with the caller but the ring).  Different
+ * contexts may be used from different threads.  shm_last_error() is per thread.
+ *
  * Work-groups: n_wg is 1 .. 2^20 groups of SHM_WG_SIZE threads unless an entry point
  * states a narrower range.  The team and collective entry points launch n_wg groups
  * for EACH PE as one grid, which must stay below 2^32 threads (n_wg * npes < 2^24).
