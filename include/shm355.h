@@ -323,6 +323,22 @@ int shm_launch_wg_put_signal(shm_ctx *ctx, int me, int pe, uint64_t dst_off, uin
  * The wait is bounded by the wait timeout. */
 int shm_launch_signal_wait_until(shm_ctx *ctx, int me, uint64_t sig_off, int cmp, uint64_t val, uint64_t *dev_out);
 
+/* Point-to-point synchronisation on 64-bit SIGNED variables of PE me's own heap (paper section
+ * "Proposed Device APIs": callable from the device; semantics of OpenSHMEM 1.5 wait_until, test and
+ * their all / any / some forms).  One thread of PE me looks at the nelems int64 variables at
+ * ivars_off (8-byte aligned; the single forms use the first).  dev_status (device pointer or NULL):
+ * nelems ints, nonzero = that variable is not part of the set.  kind: SHM_SYNC_WAIT, _WAIT_ALL,
+ * _WAIT_ANY, _WAIT_SOME block (bounded by the wait timeout) until the variable / every selected
+ * variable / at least one satisfies cmp(variable, val); SHM_SYNC_TEST, _TEST_ALL, _TEST_ANY,
+ * _TEST_SOME look once.  dev_out (device pointer, 1 + nelems uint64): [0] = the satisfying value
+ * (WAIT), 1 or 0 (WAIT_ALL, TEST, TEST_ALL), the index of a satisfying variable or UINT64_MAX
+ * (the ANY forms), the number of satisfying variables (the SOME forms), whose indices follow in
+ * [1 ..].  An empty set: ALL is satisfied, ANY gives UINT64_MAX, SOME gives 0, without waiting. */
+enum { SHM_SYNC_WAIT = 0, SHM_SYNC_WAIT_ALL = 1, SHM_SYNC_WAIT_ANY = 2, SHM_SYNC_WAIT_SOME = 3,
+       SHM_SYNC_TEST = 4, SHM_SYNC_TEST_ALL = 5, SHM_SYNC_TEST_ANY = 6, SHM_SYNC_TEST_SOME = 7 };
+int shm_launch_sync_set(shm_ctx *ctx, int me, uint64_t ivars_off, size_t nelems, const int *dev_status, int kind, int cmp, int64_t val,
+                        uint64_t *dev_out);
+
 /* One work-item of PE `me` performs one 64-bit atomic `op` (SHM_AMO_*) on offset `off` (8-byte
  * aligned) of PE `pe` (paper section "Xe-Link Capabilities": atomics from GPU threads; section
  * "Proposed Device APIs": AMOs are scalar).  *dev_out (device pointer or NULL) receives the

@@ -27,6 +27,10 @@ What is modelled, and the passage each part follows
   word on the target *after* the payload; ``signal_wait_until`` compares
   unsigned; ``quiet``/``fence`` change no state in a model where every operation
   completes at once; atomics are indivisible 64-bit read-modify-writes.
+* Point-to-point synchronisation (OpenSHMEM 1.5 wait_until / test with their all, any and some
+  forms; the paper lists these routines as callable from the device): SIGNED comparison of 64-bit
+  variables of the caller's own heap; where several answers are correct (which index ``any``
+  returns) the model returns the set of correct answers.
 * Push collect (paper section "Collective Operations", sync-and-broadcast
   paragraph) and the duplicated reduction (same section, reduction paragraph):
   ``fcollect`` concatenates every PE's block in PE order into every PE's
@@ -300,6 +304,56 @@ class ShmemOracle:
                 f"wait on PE {me} (signal={cur}, cmp={cmp}, value={value}) can never be satisfied "
                 "in this sequential order")
         return cur
+
+    # ------------------------------------------------- point-to-point synchronisation
+    def _ivars(self, me: int, off: int, nelems: int, status) -> list:
+        """(index, value) of every selected 64-bit signed variable of PE ``me`` (OpenSHMEM 1.5 wait/test
+        sets: a nonzero status entry takes the variable out of the set)."""
+        self._pe(me)
+        if nelems < 0 or off % 8:
+            raise OracleError("variables are 8-byte aligned and their number is not negative")
+        self._range(off, 8 * nelems)
+        if status is not None and len(status) != nelems:
+            raise OracleError("one status entry per variable")
+        return [(i, self._load_i64(me, off + 8 * i)) for i in range(nelems) if status is None or not status[i]]
+
+    def test_some(self, me: int, off: int, nelems: int, status, cmp: int, value: int) -> list:
+        """Indices of the selected variables for which ``cmp(variable, value)`` holds now; SIGNED comparison."""
+        if cmp not in _CMP:
+            raise OracleError("unknown comparison")
+        return [i for i, v in self._ivars(me, off, nelems, status) if _CMP[cmp](v, _to_i64(value))]
+
+    def test_all(self, me: int, off: int, nelems: int, status, cmp: int, value: int) -> bool:
+        """True if every selected variable satisfies the comparison (trivially for an empty set)."""
+        return len(self.test_some(me, off, nelems, status, cmp, value)) == len(self._ivars(me, off, nelems, status))
+
+    def test_any(self, me: int, off: int, nelems: int, status, cmp: int, value: int) -> list:
+        """The indices any of which a correct test_any may return (empty: it returns 'none')."""
+        return self.test_some(me, off, nelems, status, cmp, value)
+
+    def test(self, me: int, off: int, cmp: int, value: int) -> bool:
+        return bool(self.test_some(me, off, 1, None, cmp, value))
+
+    def wait_until(self, me: int, off: int, cmp: int, value: int) -> int:
+        """Returns the satisfying value; a wait that nothing in this sequential order can satisfy raises."""
+        if not self.test(me, off, cmp, value):
+            raise OracleError("wait_until can never be satisfied in this sequential order")
+        return self._load_i64(me, off)
+
+    def wait_until_all(self, me: int, off: int, nelems: int, status, cmp: int, value: int) -> None:
+        if not self.test_all(me, off, nelems, status, cmp, value):
+            raise OracleError("wait_until_all can never be satisfied in this sequential order")
+
+    def wait_until_some(self, me: int, off: int, nelems: int, status, cmp: int, value: int) -> list:
+        """The satisfying indices; with a non-empty set at least one must satisfy, else the wait never ends."""
+        hits = self.test_some(me, off, nelems, status, cmp, value)
+        if not hits and self._ivars(me, off, nelems, status):
+            raise OracleError("wait_until_some / wait_until_any can never be satisfied in this sequential order")
+        return hits
+
+    def wait_until_any(self, me: int, off: int, nelems: int, status, cmp: int, value: int) -> list:
+        """The indices any of which a correct wait_until_any may return (empty set: it returns 'none')."""
+        return self.wait_until_some(me, off, nelems, status, cmp, value)
 
     # ---------------------------------------------------------------- ordering
     def quiet(self, me: int) -> None:

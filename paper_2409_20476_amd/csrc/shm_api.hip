@@ -1092,6 +1092,26 @@ int shm_launch_signal_wait_until(shm_ctx *c, int me, uint64_t sig_off, int cmp, 
     return launched("signal wait");
 }
 
+int shm_launch_sync_set(shm_ctx *c, int me, uint64_t ivars_off, size_t nelems, const int *dev_status, int kind, int cmp, int64_t val,
+                        uint64_t *dev_out)
+{
+    if (int r = check_ctx(c)) return r;
+    if (int r = check_pe(c, me, "calling PE")) return r;
+    if (kind < SHM_SYNC_WAIT || kind > SHM_SYNC_TEST_SOME) return fail(SHM_EINVAL, "unknown synchronisation kind %d", kind);
+    if (cmp < SHM_CMP_EQ || cmp > SHM_CMP_LE) return fail(SHM_EINVAL, "unknown comparison %d", cmp);
+    const bool single = kind == SHM_SYNC_WAIT || kind == SHM_SYNC_TEST;
+    if (single && nelems == 0) nelems = 1;
+    if (nelems > c->user_bytes / 8) return fail(SHM_ERANGE, "the variables leave the heap");
+    if (int r = check_range(c, ivars_off, 8 * nelems, "variables")) return r;
+    if (ivars_off & 7) return fail(SHM_EINVAL, "variables must be 8-byte aligned");
+    if (!dev_out) return fail(SHM_EINVAL, "null result buffer");
+    if (c->no_device) return no_device("shm_launch_sync_set");
+    if (int r = begin_pe_launch(c, me)) return r;
+    hipLaunchKernelGGL(shmk_sync_set, dim3(1), dim3(64), 0, c->stream[me], dev_view(c), me, ivars_off, nelems, dev_status, kind, cmp,
+                       static_cast<long long>(val), reinterpret_cast<unsigned long long *>(dev_out));
+    return launched("point-to-point synchronisation");
+}
+
 int shm_launch_amo(shm_ctx *c, int me, int pe, uint64_t off, int op, int64_t operand, int64_t cond, int64_t *dev_out)
 {
     if (int r = check_ctx(c)) return r;

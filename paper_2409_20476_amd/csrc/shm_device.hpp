@@ -568,6 +568,142 @@ __device__ __forceinline__ uint64_t shmx_signal_wait_until_wg(const shm_dev_ctx 
     return v;
 }
 
+// ------------------------------------------------------------------------------------------
+// Point-to-point synchronisation on 64-bit signed variables of the caller's own heap (paper section
+// "Proposed Device APIs": these routines are callable from the device; semantics of OpenSHMEM 1.5
+// wait_until / test and their all / any / some forms).  Comparisons are SIGNED here (signals compare
+// unsigned).  `status`, if not null, has one int per variable; a nonzero entry takes that variable
+// out of the set.  Waits are bounded like every wait of the library.  Called by ONE thread.
+// ------------------------------------------------------------------------------------------
+#define SHMD_NO_INDEX (~static_cast<size_t>(0))
+
+__device__ __forceinline__ bool shm_cmp_i64(int64_t a, int cmp, int64_t b)
+{
+    switch (cmp) {
+    case SHMD_CMP_EQ: return a == b;
+    case SHMD_CMP_NE: return a != b;
+    case SHMD_CMP_GT: return a > b;
+    case SHMD_CMP_GE: return a >= b;
+    case SHMD_CMP_LT: return a < b;
+    default: return a <= b;
+    }
+}
+
+__device__ __forceinline__ int64_t shm_ivar_load(const shm_dev_ctx &c, int me, uint64_t off, size_t i)
+{
+    return __hip_atomic_load(reinterpret_cast<const int64_t *>(shm_ptr(c, off, me)) + i, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+// One look at every selected variable.  Returns how many satisfy the comparison; writes their indices
+// to `indices` (if not null) and the first of them to *first.
+__device__ __forceinline__ size_t shm_test_scan(const shm_dev_ctx &c, int me, uint64_t off, size_t n, const int *status, int cmp,
+                                                int64_t val, size_t *indices, size_t *first, size_t *selected)
+{
+    size_t hits = 0, sel = 0;
+    *first = SHMD_NO_INDEX;
+    for (size_t i = 0; i < n; ++i) {
+        if (status != nullptr && status[i] != 0) continue;
+        ++sel;
+        if (shm_cmp_i64(shm_ivar_load(c, me, off, i), cmp, val)) {
+            if (hits == 0) *first = i;
+            if (indices != nullptr) indices[hits] = i;
+            ++hits;
+        }
+    }
+    *selected = sel;
+    return hits;
+}
+
+// test: true (with acquire) if the comparison holds now.
+__device__ __forceinline__ bool shm_test(const shm_dev_ctx &c, int me, uint64_t off, int cmp, int64_t val)
+{
+    const bool ok = shm_cmp_i64(shm_ivar_load(c, me, off, 0), cmp, val);
+    if (ok) __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+    return ok;
+}
+
+// wait_until: spins until the comparison holds; returns the satisfying value.
+__device__ __forceinline__ int64_t shm_wait_until(const shm_dev_ctx &c, int me, uint64_t off, int cmp, int64_t val)
+{
+    const uint64_t t0 = wall_clock64();
+    int64_t cur;
+    for (;;) {
+        cur = shm_ivar_load(c, me, off, 0);
+        if (shm_cmp_i64(cur, cmp, val)) break;
+        if (wall_clock64() - t0 > c.wait_ticks) {
+            __hip_atomic_store(c.status, 1ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+            break;
+        }
+        __builtin_amdgcn_s_sleep(2);
+    }
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+    return cur;
+}
+
+// The set forms.  need_all: every selected variable must satisfy (all), else at least one (any / some).
+// Returns the number of satisfying variables at the moment the condition was met (0 only if nothing is
+// selected or the wait ran into its bound); *first and indices as in shm_test_scan.
+__device__ __forceinline__ size_t shm_wait_until_set(const shm_dev_ctx &c, int me, uint64_t off, size_t n, const int *status, int cmp,
+                                                     int64_t val, bool need_all, size_t *indices, size_t *first)
+{
+    const uint64_t t0 = wall_clock64();
+    size_t hits, selected;
+    for (;;) {
+        hits = shm_test_scan(c, me, off, n, status, cmp, val, indices, first, &selected);
+        if (selected == 0 || (need_all ? hits == selected : hits > 0)) break;
+        if (wall_clock64() - t0 > c.wait_ticks) {
+            __hip_atomic_store(c.status, 1ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+            hits = 0;
+            break;
+        }
+        __builtin_amdgcn_s_sleep(2);
+    }
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+    return hits;
+}
+__device__ __forceinline__ void shm_wait_until_all(const shm_dev_ctx &c, int me, uint64_t off, size_t n, const int *status, int cmp, int64_t val)
+{
+    size_t first;
+    (void)shm_wait_until_set(c, me, off, n, status, cmp, val, true, nullptr, &first);
+}
+// Index of one satisfying variable, SHMD_NO_INDEX if none is selected.
+__device__ __forceinline__ size_t shm_wait_until_any(const shm_dev_ctx &c, int me, uint64_t off, size_t n, const int *status, int cmp, int64_t val)
+{
+    size_t first;
+    (void)shm_wait_until_set(c, me, off, n, status, cmp, val, false, nullptr, &first);
+    return first;
+}
+// Number of satisfying variables (at least one unless none is selected); their indices to `indices`.
+__device__ __forceinline__ size_t shm_wait_until_some(const shm_dev_ctx &c, int me, uint64_t off, size_t n, size_t *indices, const int *status,
+                                                      int cmp, int64_t val)
+{
+    size_t first;
+    return shm_wait_until_set(c, me, off, n, status, cmp, val, false, indices, &first);
+}
+// The non-blocking forms: one scan, acquire when the answer is positive.
+__device__ __forceinline__ bool shm_test_all(const shm_dev_ctx &c, int me, uint64_t off, size_t n, const int *status, int cmp, int64_t val)
+{
+    size_t first, selected;
+    const size_t hits = shm_test_scan(c, me, off, n, status, cmp, val, nullptr, &first, &selected);
+    const bool ok = hits == selected;              // an empty set is trivially satisfied
+    if (ok) __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+    return ok;
+}
+__device__ __forceinline__ size_t shm_test_any(const shm_dev_ctx &c, int me, uint64_t off, size_t n, const int *status, int cmp, int64_t val)
+{
+    size_t first, selected;
+    if (shm_test_scan(c, me, off, n, status, cmp, val, nullptr, &first, &selected) > 0) __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+    return first;
+}
+__device__ __forceinline__ size_t shm_test_some(const shm_dev_ctx &c, int me, uint64_t off, size_t n, size_t *indices, const int *status,
+                                                int cmp, int64_t val)
+{
+    size_t first, selected;
+    const size_t hits = shm_test_scan(c, me, off, n, status, cmp, val, indices, &first, &selected);
+    if (hits > 0) __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+    return hits;
+}
+
 // Put with signal for one work-group, or for `nparts` work-groups sharing one message.
 //
 // OpenSHMEM orders the signal after THIS put's payload only (earlier puts need fence/quiet), so a

@@ -222,6 +222,30 @@ __global__ __launch_bounds__(SHMK_WG) void shmk_signal_wait(shm_dev_ctx c, int m
     if (out != nullptr && threadIdx.x == 0) *out = v;
 }
 
+// ---- point-to-point synchronisation: wait_until / test and their all / any / some forms ------
+// One thread of PE `me`.  kind: 0 wait, 1 wait_all, 2 wait_any, 3 wait_some, 4 test, 5 test_all,
+// 6 test_any, 7 test_some.  out[0] = the call's result (the satisfying value for wait, 1/0 for the
+// tests that answer yes or no, the index for any -- UINT64_MAX if there is none --, the count for
+// some); for the some forms out[1 ..] = the indices.
+__global__ __launch_bounds__(64) void shmk_sync_set(shm_dev_ctx c, int me, uint64_t off, size_t n, const int *status, int kind, int cmp,
+                                                    long long val, unsigned long long *out)
+{
+    if (threadIdx.x != 0 || blockIdx.x != 0) return;
+    size_t *indices = reinterpret_cast<size_t *>(out + 1);
+    unsigned long long r = 0;
+    switch (kind) {
+    case 0: r = static_cast<unsigned long long>(shm_wait_until(c, me, off, cmp, val)); break;
+    case 1: shm_wait_until_all(c, me, off, n, status, cmp, val); r = 1; break;
+    case 2: r = shm_wait_until_any(c, me, off, n, status, cmp, val); break;
+    case 3: r = shm_wait_until_some(c, me, off, n, indices, status, cmp, val); break;
+    case 4: r = shm_test(c, me, off, cmp, val) ? 1 : 0; break;
+    case 5: r = shm_test_all(c, me, off, n, status, cmp, val) ? 1 : 0; break;
+    case 6: r = shm_test_any(c, me, off, n, status, cmp, val); break;
+    default: r = shm_test_some(c, me, off, n, indices, status, cmp, val); break;
+    }
+    out[0] = r;
+}
+
 // ---- one atomic by one work-item ---------------------------------------------------------
 __global__ void shmk_amo(shm_dev_ctx c, int pe, uint64_t off, int op, int64_t operand, int64_t cond, int64_t *out)
 {

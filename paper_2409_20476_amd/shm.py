@@ -29,6 +29,8 @@ SHM_STORM_FETCH_ADD, SHM_STORM_ADD, SHM_STORM_CSWAP_LOOP, SHM_STORM_PLAIN_STORE 
 SHM_REDUCE_DUPLICATE, SHM_REDUCE_SPLIT = 0, 1
 SHM_COLL_FCOLLECT, SHM_COLL_BROADCAST = 0, 1
 SHM_TEAM_SYNC_OFF, SHM_TEAM_SYNC_FULL, SHM_TEAM_SYNC_TRACKED = 0, 1, 2
+(SHM_SYNC_WAIT, SHM_SYNC_WAIT_ALL, SHM_SYNC_WAIT_ANY, SHM_SYNC_WAIT_SOME,
+ SHM_SYNC_TEST, SHM_SYNC_TEST_ALL, SHM_SYNC_TEST_ANY, SHM_SYNC_TEST_SOME) = range(8)
 SHM_NO_CONSUME = (1 << 64) - 1
 SHM_CUTOVER_TUNED = (1 << 64) - 2
 SHM_OP_MIN, SHM_OP_MAX, SHM_OP_SUM, SHM_OP_PROD, SHM_OP_AND, SHM_OP_OR, SHM_OP_XOR = range(7)
@@ -90,6 +92,7 @@ PROTOTYPES = {
     "shm_launch_offload_nop": (c_int, [c_void_p, c_int, c_int, c_int, c_int, c_void_p]),
     "shm_launch_wg_put_signal": (c_int, [c_void_p, c_int, c_int, c_uint64, c_uint64, c_size_t, c_uint64, c_uint64, c_int, c_int]),
     "shm_launch_signal_wait_until": (c_int, [c_void_p, c_int, c_uint64, c_int, c_uint64, c_void_p]),
+    "shm_launch_sync_set": (c_int, [c_void_p, c_int, c_uint64, c_size_t, c_void_p, c_int, c_int, c_int64, c_void_p]),
     "shm_launch_amo": (c_int, [c_void_p, c_int, c_int, c_uint64, c_int, c_int64, c_int64, c_void_p]),
     "shm_launch_pingflag": (c_int, [c_void_p, c_uint64, c_uint64, c_size_t, c_uint64]),
     "shm_launch_ring_pipeline": (c_int, [c_void_p, c_uint64, c_uint64, c_uint64, c_uint64, c_size_t, c_int, c_int, c_int, c_int]),
@@ -343,6 +346,9 @@ class Shm:
 
     def launch_signal_wait_until(self, me, sig_off, cmp, val, dev_out=None):
         self._check(self.lib.shm_launch_signal_wait_until(self.ctx, me, sig_off, cmp, val, _ptr(dev_out)))
+
+    def launch_sync_set(self, me, ivars_off, nelems, dev_status, kind, cmp, val, dev_out):
+        self._check(self.lib.shm_launch_sync_set(self.ctx, me, ivars_off, nelems, _ptr(dev_status), kind, cmp, val, _ptr(dev_out)))
 
     def launch_amo(self, me, pe, off, op, operand=0, cond=0, dev_out=None):
         self._check(self.lib.shm_launch_amo(self.ctx, me, pe, off, op, operand, cond, _ptr(dev_out)))

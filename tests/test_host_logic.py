@@ -291,3 +291,24 @@ def test_team_sync_modes():
             g.set_team_sync(bad)
         assert e.value.code == S.SHM_EINVAL
     g.finalize()
+
+
+def test_sync_set_argument_checks():
+    g = _ctx()
+    H = g.heap_bytes()
+
+    def code(fn):
+        with pytest.raises(S.ShmError) as e:
+            fn()
+        return e.value.code
+
+    assert code(lambda: g.launch_sync_set(0, 4096, 4, None, S.SHM_SYNC_WAIT_ALL, S.SHM_CMP_GE, 1, 8)) == S.SHM_ENODEV
+    assert code(lambda: g.launch_sync_set(0, 4096, 0, None, S.SHM_SYNC_TEST, S.SHM_CMP_EQ, -5, 8)) == S.SHM_ENODEV      # single forms look at one variable
+    assert code(lambda: g.launch_sync_set(4, 4096, 4, None, S.SHM_SYNC_WAIT_ALL, S.SHM_CMP_GE, 1, 8)) == S.SHM_EPE
+    assert code(lambda: g.launch_sync_set(0, 4100, 4, None, S.SHM_SYNC_WAIT_ALL, S.SHM_CMP_GE, 1, 8)) == S.SHM_EINVAL   # alignment
+    assert code(lambda: g.launch_sync_set(0, H - 16, 4, None, S.SHM_SYNC_TEST_SOME, S.SHM_CMP_GE, 1, 8)) == S.SHM_ERANGE
+    assert code(lambda: g.launch_sync_set(0, 4096, 1 << 62, None, S.SHM_SYNC_TEST_SOME, S.SHM_CMP_GE, 1, 8)) == S.SHM_ERANGE
+    assert code(lambda: g.launch_sync_set(0, 4096, 4, None, 8, S.SHM_CMP_GE, 1, 8)) == S.SHM_EINVAL
+    assert code(lambda: g.launch_sync_set(0, 4096, 4, None, S.SHM_SYNC_WAIT_ANY, 6, 1, 8)) == S.SHM_EINVAL
+    assert code(lambda: g.launch_sync_set(0, 4096, 4, None, S.SHM_SYNC_WAIT_ANY, S.SHM_CMP_GE, 1, None)) == S.SHM_EINVAL
+    g.finalize()
