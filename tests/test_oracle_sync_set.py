@@ -29,6 +29,7 @@ def test_hand_worked_example():
     assert o.test_some(1, 64, 4, None, CMP_GT, 0) == [0, 2]
     assert not o.test_all(1, 64, 4, status, CMP_GE, 0) and o.test_all(1, 64, 4, [0, 1, 0, 0], CMP_GE, 0)
     assert o.test_all(1, 64, 4, [1, 1, 1, 1], CMP_EQ, 99) and o.test_any(1, 64, 4, [1, 1, 1, 1], CMP_NE, 99) == []
+    assert o.wait_until(1, 80, CMP_GT, 3) == 7 and o.wait_until(1, 72, CMP_LE, 0) == -1          # the variable's value, not the threshold
     assert o.wait_until(1, 64, CMP_EQ, 5) == 5 and o.test(1, 72, CMP_EQ, -1) and not o.test(1, 72, CMP_GT, 0)
     assert o.wait_until_any(1, 64, 4, status, CMP_GE, 0) == [0, 3] and o.wait_until_some(1, 64, 4, None, CMP_LE, 0) == [1, 3]
     o.wait_until_all(1, 64, 4, [0, 1, 0, 1], CMP_GE, 5)
