@@ -438,11 +438,30 @@ def collective_sweeps(torch, S, args):
                 best = min(best, (b - a) / g.wall_clock_khz() * 1e3 / 200)
             out[key][str(npes)] = best
         g.finalize()
+    # host time per small team launch under the three ways of ordering it against the PE streams
+    out["team_launch_host_us"] = {}
+    for npes in (2, 8, 16):
+        g = S.Shm.on_torch(npes, 8 * MiB)
+        src, dst = g.malloc(4096), g.malloc(4096 * npes)
+        row = {}
+        for name, mode in (("full", S.SHM_TEAM_SYNC_FULL), ("tracked", S.SHM_TEAM_SYNC_TRACKED), ("off", S.SHM_TEAM_SYNC_OFF)):
+            g.set_team_sync(mode)
+            for _ in range(50):
+                g.launch_fcollect(dst, src, 64, 1)
+            g.barrier_all()
+            t0 = time.perf_counter()
+            for _ in range(1000):
+                g.launch_fcollect(dst, src, 64, 1)
+            g.barrier_all()
+            row[name] = (time.perf_counter() - t0) / 1000 * 1e6
+        out["team_launch_host_us"][str(npes)] = row
+        g.finalize()
     out["note"] = ("fcollect / broadcast: ldst_wgK_us = one grid with K groups of 256 threads per PE (root only for broadcast; HIP events, "
                    "launch included); memcpy_us / sdma_us = npes^2 (broadcast: npes) host-started copies, host clock; auto_wgK_us = "
                    "SHM_PATH_AUTO with the library's per-collective thresholds, host clock; cutover = smallest block from which a host "
                    "copy path stays at least as fast. broadcast_us_by_pes: root PE 0, 2 groups (the paper uses 128 work-items). "
-                   "sync / barrier: device clock inside one kernel of npes groups, per operation")
+                   "sync / barrier: device clock inside one kernel of npes groups, per operation. team_launch_host_us: host time per fcollect of "
+                   "64 bytes in a loop of 1000, by team sync mode and number of PEs")
     return out
 
 
