@@ -206,8 +206,9 @@ int    shm_stream_used(shm_ctx *ctx, int pe);
 /* Work-group put/get (paper section "Proposed Device APIs", the work_group extensions; section
  * "Remote Memory Access": multi-threaded vectorised copy).  n_wg work-groups of SHM_WG_SIZE
  * threads share the message; which bytes a group moves is not observable and is chosen for the
- * memory system (see shm_device.hpp).  path: LDST = kernel on me's stream, SDMA = copy engine, MEMCPY = runtime copy
- * on me's stream, AUTO = LDST or SDMA by cutover.  Any byte alignment; n may be 0. */
+ * memory system (see shm_device.hpp).  path: LDST = kernel on me's stream, SDMA = copy engine,
+ * MEMCPY = runtime copy on me's stream, AUTO = LDST or SDMA by cutover.  Any byte alignment; n may
+ * be 0. */
 int shm_launch_wg_put(shm_ctx *ctx, int me, int pe, uint64_t dst_off, uint64_t src_off, size_t n, int n_wg, int path);
 int shm_launch_wg_get(shm_ctx *ctx, int me, int pe, uint64_t dst_off, uint64_t src_off, size_t n, int n_wg, int path);
 
@@ -242,11 +243,11 @@ int shm_proxy_stop(shm_ctx *ctx);
 int shm_proxy_stats(const shm_ctx *ctx, uint64_t *requests, uint64_t *copies);
 
 /* One kernel of n_wg groups (1..1024) of wg_size threads (1..1024: the paper varies the work-items
- * per work-group; modes 1-3 talk to the host with one whole wave and need a multiple of 64) on me's stream puts n bytes from me's src_off to pe's
- * dst_off `reps` times; group g owns the g-th contiguous 256-byte-aligned share.  mode 0: loads/stores and
- * group quiet; 1: reverse offload to a copy engine, blocking; 2: cutover inside the kernel (share
- * size >= cutover bytes -> engine, else loads/stores); 3: non-blocking offload followed by an
- * offload quiet.  Modes 1-3 need the proxy.  dev_ticks as for shm_launch_wg_put_timed. */
+ * per work-group; modes 1-3 talk to the host with one whole wave and need a multiple of 64) on me's
+ * stream puts n bytes from me's src_off to pe's dst_off `reps` times; group g owns the g-th
+ * contiguous 256-byte-aligned share.  mode 0: loads/stores and group quiet; 1: reverse offload to
+ * a copy engine, blocking; 2: cutover inside the kernel (share size >= cutover bytes -> engine,
+ * else loads/stores); 3: non-blocking offload followed by an offload quiet.  Modes 1-3 need the proxy.  dev_ticks as for shm_launch_wg_put_timed. */
 int shm_launch_put_device_initiated(shm_ctx *ctx, int me, int pe, uint64_t dst_off, uint64_t src_off, size_t n, int n_wg, int wg_size,
                                     int mode, size_t cutover, int reps, uint64_t *dev_ticks);
 
@@ -256,8 +257,9 @@ int shm_launch_put_device_initiated(shm_ctx *ctx, int me, int pe, uint64_t dst_o
  * notes sketch for the cutover: the engine moves all but the first `cover` bytes of a group's share
  * while the group moves those first bytes with loads and stores, covering the engine's start-up
  * time; then both are waited for; mode 5 is put_nbi / get_nbi with no quiet inside the kernel:
- * the transfer is complete after shm_quiet(me) or shm_barrier_all (no consume_off then).  consume_off (get only; SHM_NO_CONSUME = none): offset on PE me
- * of n bytes that do not overlap the transfer; the group copies its share of the destination there
+ * the transfer is complete after shm_quiet(me) or shm_barrier_all (no consume_off then).
+ * consume_off (get only; SHM_NO_CONSUME = none): offset on PE me of n bytes that do not overlap the
+ * transfer; the group copies its share of the destination there
  * before the first get and after every get, from inside the kernel, so the buffer shows what the
  * kernel itself reads after a get.  dev_ticks may be NULL. */
 #define SHM_NO_CONSUME UINT64_MAX
