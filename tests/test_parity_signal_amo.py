@@ -203,13 +203,17 @@ def test_config4_full_size():
         _check_storm(g, o, 16, 1024, 1 << 20, 64, S.SHM_STORM_FETCH_ADD, 0)
 
 
+@pytest.mark.parametrize("how", ["put_signal", "put_then_atomic"])
 @pytest.mark.parametrize("rounds,seed", [(150, 81), (150, 82)])
-def test_ping_pong_with_credits_many_rounds_without_host_synchronisation(rounds, seed):
+def test_ping_pong_with_credits_many_rounds_without_host_synchronisation(rounds, seed, how):
     """The protocol put-with-signal exists for, all of it enqueued up front on two PEs' streams:
     PE 0 waits for a credit, puts the round's payload into ONE reused buffer on PE 1 with signal
     'data += 1'; PE 1 waits for the data, copies the payload away and returns a credit with a
     zero-byte put-with-signal.  Only the signals order the two streams: a payload read before it has
-    landed, or overwritten before it was read, shows in the copies."""
+    landed, or overwritten before it was read, shows in the copies.
+    how == "put_then_atomic": the payload travels with a plain work-group put and the signal is a
+    separate atomic add launched behind it on the same stream -- successive launches of one PE are
+    delivered in order (the host-side fence is the stream's order), which is what this form checks."""
     g, o = make_pair(2, 48 * MiB)
     rng = np.random.default_rng(seed)
     with g:
@@ -223,7 +227,12 @@ def test_ping_pong_with_credits_many_rounds_without_host_synchronisation(rounds,
             src, off, n_wg = int(rng.integers(0, 15 * MiB)), int(rng.integers(0, 16)), int(rng.choice([1, 2, 3, 16]))
             # PE 0: wait until the buffer is free again (r credits returned), then send
             g.launch_signal_wait_until(0, credit_sig, S.SHM_CMP_GE, r)
-            g.launch_wg_put_signal(0, 1, buf + off, src, n, data_sig, 1, SIGNAL_ADD, n_wg)
+            if how == "put_signal":
+                g.launch_wg_put_signal(0, 1, buf + off, src, n, data_sig, 1, SIGNAL_ADD, n_wg)
+            else:
+                g.launch_wg_put(0, 1, buf + off, src, n, n_wg)
+                g.fence(0)
+                g.launch_amo(0, 1, data_sig, S.SHM_AMO_ADD, 1)
             # PE 1: wait for round r's data, keep a copy, give the buffer back
             g.launch_signal_wait_until(1, data_sig, S.SHM_CMP_GE, r + 1)
             g.launch_wg_put(1, 1, at, buf + off, n, int(rng.choice([1, 4])))

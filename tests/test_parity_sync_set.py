@@ -5,7 +5,7 @@ import torch
 
 from oracle.shmem_oracle import OracleError
 from paper_2409_20476_amd import shm as S
-from parity_util import make_pair, write_both
+from parity_util import fill_random, make_pair, write_both
 
 pytestmark = pytest.mark.gpu
 
@@ -83,6 +83,7 @@ def test_wait_until_all_is_released_by_puts_from_other_pes():
     one of them put before its variable is readable after the wait."""
     g, o = make_pair(4, MiB)
     with g:
+        fill_random(g, o, 92, upto=65536)             # the heap is uninitialised device memory: give both sides the same bytes
         zeros = np.zeros(4, np.int64)
         write_both(g, o, 0, 4096, zeros)
         payload = np.arange(1000, dtype=np.uint8)
