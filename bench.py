@@ -671,6 +671,8 @@ def main():
 
     if args.hw_queues:       # read by the HIP runtime when it initialises, i.e. before torch touches the GPU
         os.environ["GPU_MAX_HW_QUEUES"] = str(args.hw_queues)
+    from paper_2409_20476_amd import build as shm_build
+    shm_build.ensure_built()            # loads what is built; compiles only if nothing is
     import torch
     from paper_2409_20476_amd import shm as S, synth
     if not torch.cuda.is_available():

@@ -41,5 +41,12 @@ def build(verbose: bool = False) -> str:
     return LIB_PATH
 
 
+def ensure_built() -> None:
+    """Compile only if nothing has been built yet (tests, the smoke check and the benchmark load what
+    is there; the build driver always compiles)."""
+    if not (os.path.exists(LIB_PATH) and os.path.exists(EXAMPLE_LIB_PATH)):
+        build()
+
+
 if __name__ == "__main__":
     print(build(verbose=True))

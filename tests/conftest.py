@@ -13,7 +13,5 @@ def pytest_configure(config):
 def pytest_sessionstart(session):
     """The tests load the in-tree libraries; they are compiled here only if nothing has been built yet
     (hipcc cross-compiles for gfx950 without a GPU)."""
-    libs = [os.path.join(ROOT, "paper_2409_20476_amd", name) for name in ("libshm355.so", "libshm355_user_example.so")]
-    if not all(os.path.exists(lib) for lib in libs):
-        from paper_2409_20476_amd import build
-        build.build()
+    from paper_2409_20476_amd import build
+    build.ensure_built()
