@@ -35,7 +35,7 @@ constexpr uint32_t SHM_OFFLOAD_COMPLETIONS = 65536;   // completion words (power
 struct shm_offload_shared {
     uint32_t ring[SHM_OFFLOAD_SLOTS][16];
     uint32_t completion[SHM_OFFLOAD_COMPLETIONS];
-    volatile uint64_t consumed;       // requests the host has taken out of the ring (flow control)
+    uint64_t consumed;                // requests the host has taken out of the ring (flow control)
     uint64_t pad[7];
 };
 
@@ -111,6 +111,14 @@ private:
     struct quiet_waiting {
         uint32_t pe, comp, tag;
     };
+
+    // Words that the other side (the GPU, or the CPU threads that play it in the host test)
+    // writes or polls while this thread runs are touched with atomic accesses only: one aligned
+    // load or store each (acquire and release cost nothing on the host), and a defined program
+    // for a thread sanitizer.  A tag is read before the message it closes, and the consumed
+    // count is published after the messages it covers have been copied out of their slots.
+    static uint32_t peek(const uint32_t *word) { return __atomic_load_n(word, __ATOMIC_ACQUIRE); }
+    void publish_consumed(uint64_t tail) { __atomic_store_n(&sh_->consumed, tail, __ATOMIC_RELEASE); }
 
     void reply(uint32_t comp, uint32_t tag)
     {
@@ -243,9 +251,9 @@ private:
             bool complete[kBatch];
             for (unsigned i = 0; i < kBatch; ++i) {
                 const uint64_t at = tail + i;
-                const volatile uint32_t *v = sh_->ring[at & (SHM_OFFLOAD_SLOTS - 1)];
+                const uint32_t *v = sh_->ring[at & (SHM_OFFLOAD_SLOTS - 1)];
                 const uint32_t tag = static_cast<uint32_t>(at / SHM_OFFLOAD_SLOTS) + 1;
-                complete[i] = v[3] == tag && v[7] == tag && v[11] == tag && v[15] == tag;
+                complete[i] = peek(v + 3) == tag && peek(v + 7) == tag && peek(v + 11) == tag && peek(v + 15) == tag;
             }
             unsigned ready = 0;
             while (ready < kBatch && complete[ready]) ++ready;
@@ -257,12 +265,12 @@ private:
                     // completion tags count completion-word generations: 1 + (completion index / words)
                     handle(m, m[2] == SHM_OFFLOAD_NO_COMPLETION ? 0u : (m[2] / SHM_OFFLOAD_COMPLETIONS) + 1u);
                     ++tail;
-                    if ((tail & 63) == 0) sh_->consumed = tail;     // flow control, off the critical path
+                    if ((tail & 63) == 0) publish_consumed(tail);   // flow control, off the critical path
                 }
                 taken_.store(tail, std::memory_order_release);
                 idle = 0;
             } else if (++idle == 64) {
-                sh_->consumed = tail;
+                publish_consumed(tail);
                 idle = 0;
             }
             if (!copies_in_flight_.empty() || !quiets_.empty()) retire_copies();

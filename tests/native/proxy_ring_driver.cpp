@@ -40,24 +40,23 @@ bool send(sender_side &s, uint32_t op, uint32_t pe, bool want_completion, unsign
         ticket = static_cast<uint32_t>(s.comp_head.fetch_add(1));
         if (ticket == SHM_OFFLOAD_NO_COMPLETION) ticket = static_cast<uint32_t>(s.comp_head.fetch_add(1));
     }
-    while (idx - s.sh->consumed >= SHM_OFFLOAD_SLOTS) {
+    while (idx - __atomic_load_n(&s.sh->consumed, __ATOMIC_ACQUIRE) >= SHM_OFFLOAD_SLOTS) {
         if (late()) return false;
         std::this_thread::yield();
     }
     const uint32_t tag = static_cast<uint32_t>(idx / SHM_OFFLOAD_SLOTS) + 1u;
     uint32_t m[16] = {op, pe, ticket, tag, 0x1000, 0, 0, tag, 0x2000, 0, 0, tag, 64, 0, 0, tag};
-    volatile uint32_t *slot = s.sh->ring[idx & (SHM_OFFLOAD_SLOTS - 1)];
+    uint32_t *slot = s.sh->ring[idx & (SHM_OFFLOAD_SLOTS - 1)];
     for (unsigned k = 0; k < 4; ++k) {
         const unsigned q = (k + scramble) & 3;
         for (unsigned w = 0; w < 3; ++w) slot[4 * q + w] = m[4 * q + w];
-        std::atomic_thread_fence(std::memory_order_release);
-        slot[4 * q + 3] = tag;                        // the tag of a quarter lands after its payload
+        __atomic_store_n(&slot[4 * q + 3], tag, __ATOMIC_RELEASE);      // the tag of a quarter lands after its payload
         if ((idx & 255) == 0) std::this_thread::yield();      // now and then leave a message half-written for a while
     }
     if (!want_completion) return true;
-    const volatile uint32_t *word = &s.sh->completion[ticket & (SHM_OFFLOAD_COMPLETIONS - 1)];
+    const uint32_t *word = &s.sh->completion[ticket & (SHM_OFFLOAD_COMPLETIONS - 1)];
     const uint32_t want = ticket / SHM_OFFLOAD_COMPLETIONS + 1u;
-    while (*word != want) {
+    while (__atomic_load_n(word, __ATOMIC_ACQUIRE) != want) {
         if (late()) return false;
         std::this_thread::yield();
     }
