@@ -563,14 +563,15 @@ def storm(torch, S, synth, args):
     checksum = torch.zeros(n_items // 256, dtype=torch.int64, device="cuda")
     out = {}
     g.set_team_sync(False)
+    returning = (S.SHM_STORM_FETCH_ADD, S.SHM_STORM_FETCH_ADD_WG)
     for name, kind in (("fetch_add", S.SHM_STORM_FETCH_ADD), ("add_no_return", S.SHM_STORM_ADD),
-                       ("plain_store_ceiling", S.SHM_STORM_PLAIN_STORE)):
+                       ("plain_store_ceiling", S.SHM_STORM_PLAIN_STORE), ("fetch_add_batched_by_work_group", S.SHM_STORM_FETCH_ADD_WG)):
         best = float("inf")
         for i in range(7):
             torch.cuda.synchronize()
             e0, e1 = event_pair(torch)
             e0.record(g.streams[0])
-            g.launch_amo_storm(ctr, n_ctr, targets, n_items, ops, kind, None, checksum if kind == S.SHM_STORM_FETCH_ADD else None)
+            g.launch_amo_storm(ctr, n_ctr, targets, n_items, ops, kind, None, checksum if kind in returning else None)
             e1.record(g.streams[0])
             g.barrier_all()
             if i >= 2:
@@ -754,7 +755,8 @@ def main():
     }
     if extras:
         if "config4_amo_storm" in extras:
-            line["amo_ops_per_s"] = extras["config4_amo_storm"]["fetch_add"]["gops"] * 1e9
+            line["amo_ops_per_s"] = extras["config4_amo_storm"]["fetch_add"]["gops"] * 1e9       # the scalar device API
+            line["amo_ops_per_s_batched_by_work_group"] = extras["config4_amo_storm"]["fetch_add_batched_by_work_group"]["gops"] * 1e9
         line["extras"] = extras
     print(json.dumps(line))
     return 0

@@ -60,7 +60,7 @@ enum { SHM_CMP_EQ = 0, SHM_CMP_NE = 1, SHM_CMP_GT = 2, SHM_CMP_GE = 3, SHM_CMP_L
 enum { SHM_INIT_DEFAULT = 0, SHM_INIT_NO_DEVICE = 1 };
 enum { SHM_AMO_FETCH = 0, SHM_AMO_SET = 1, SHM_AMO_SWAP = 2, SHM_AMO_COMPARE_SWAP = 3,
        SHM_AMO_FETCH_ADD = 4, SHM_AMO_ADD = 5, SHM_AMO_FETCH_INC = 6, SHM_AMO_INC = 7 };
-enum { SHM_STORM_FETCH_ADD = 0, SHM_STORM_ADD = 1, SHM_STORM_CSWAP_LOOP = 2, SHM_STORM_PLAIN_STORE = 3 };
+enum { SHM_STORM_FETCH_ADD = 0, SHM_STORM_ADD = 1, SHM_STORM_CSWAP_LOOP = 2, SHM_STORM_PLAIN_STORE = 3, SHM_STORM_FETCH_ADD_WG = 4 };
 enum { SHM_REDUCE_DUPLICATE = 0, SHM_REDUCE_SPLIT = 1 };
 enum { SHM_COLL_FCOLLECT = 0, SHM_COLL_BROADCAST = 1 };
 enum { SHM_TEAM_SYNC_OFF = 0, SHM_TEAM_SYNC_FULL = 1, SHM_TEAM_SYNC_TRACKED = 2 };
@@ -374,9 +374,15 @@ int shm_launch_ring_pipeline(shm_ctx *ctx, uint64_t src_off, uint64_t slot_off, 
  * ops_per_item atomics; its j-th target is dev_targets[g*ops_per_item + j] = pe*n_ctr + index,
  * i.e. the int64 counter at ctr_off + 8*index on that PE.  kind: FETCH_ADD(+1) | ADD(+1, no
  * return) | CSWAP_LOOP (increment built from compare-swap) | PLAIN_STORE (not atomic; a timing
- * ceiling only).  dev_fetched (or NULL): [n_items*ops_per_item] fetched values.  dev_checksum (or
- * NULL): one uint64 per work-group, the sum of what its items fetched.  n_items is 1 .. 2^32 - 256
- * (one grid); n_ctr * npes <= 65536; ops_per_item 1 .. 4096; dev_targets 16-byte aligned. */
+ * ceiling only) | FETCH_ADD_WG (the same fetch-adds batched by work-groups of 1024 work-items:
+ * a group counts its increments per counter in LDS and sends one fetch-add per counter it touched;
+ * an extension -- the paper, section "Proposed Device APIs", gives the atomics no group form --
+ * with the same observable result, i.e. the fetched values of a counter are those of one valid
+ * order of its increments; needs ops_per_item <= 64 and n_ctr * npes <= 16384, SHM_EINVAL
+ * otherwise).  dev_fetched (or NULL): [n_items*ops_per_item] fetched values.  dev_checksum (or
+ * NULL): one uint64 per 256 consecutive work-items, the sum of what they fetched.  n_items is
+ * 1 .. 2^32 - 256 (one grid); n_ctr * npes <= 65536; ops_per_item 1 .. 4096; dev_targets 16-byte
+ * aligned. */
 int shm_launch_amo_storm(shm_ctx *ctx, uint64_t ctr_off, int n_ctr, const uint16_t *dev_targets, uint64_t n_items,
                          int ops_per_item, int kind, int64_t *dev_fetched, uint64_t *dev_checksum);
 

@@ -1211,7 +1211,13 @@ int shm_launch_amo_storm(shm_ctx *c, uint64_t ctr_off, int n_ctr, const uint16_t
     if (!dev_targets) return fail(SHM_EINVAL, "null target table");
     if (reinterpret_cast<uintptr_t>(dev_targets) & 15) return fail(SHM_EINVAL, "target table must be 16-byte aligned");
     if (ops_per_item < 1 || ops_per_item > 4096) return fail(SHM_EINVAL, "ops_per_item outside 1..4096");
-    if (kind < SHM_STORM_FETCH_ADD || kind > SHM_STORM_PLAIN_STORE) return fail(SHM_EINVAL, "unknown storm kind %d", kind);
+    if (kind < SHM_STORM_FETCH_ADD || kind > SHM_STORM_FETCH_ADD_WG) return fail(SHM_EINVAL, "unknown storm kind %d", kind);
+    const bool batched = kind == SHM_STORM_FETCH_ADD_WG;
+    const size_t table_bytes = 8ull * n_ctr * c->npes;            // the batched kind's table in LDS
+    if (batched && ops_per_item > SHMK_STORM_MAXOPS)
+        return fail(SHM_EINVAL, "the batched storm holds at most %d operations per work-item", SHMK_STORM_MAXOPS);
+    if (batched && table_bytes > SHMK_STORM_TABLE_BYTES)
+        return fail(SHM_EINVAL, "the batched storm keeps npes * n_ctr <= %d counters in LDS", static_cast<int>(SHMK_STORM_TABLE_BYTES / 8));
     const uint64_t groups = (n_items + SHMK_WG - 1) / SHMK_WG;
     if (n_items == 0 || groups >= (1ull << 24)) return fail(SHM_EINVAL, "n_items outside 1..2^32-256 (one grid holds fewer than 2^32 threads)");
     if (c->no_device) return no_device("shm_launch_amo_storm");
@@ -1222,6 +1228,16 @@ int shm_launch_amo_storm(shm_ctx *c, uint64_t ctr_off, int n_ctr, const uint16_t
     const dim3 grid(static_cast<unsigned>(groups)), block(SHMK_WG);
     hipStream_t s = c->stream[0];
     switch (kind) {
+    case SHM_STORM_FETCH_ADD_WG: {
+        // more LDS than a kernel gets without asking
+        const auto kernel = ops_per_item == SHMK_STORM_MAXOPS ? shmk_amo_storm_wg<true> : shmk_amo_storm_wg<false>;
+        HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void *>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                    static_cast<int>(SHMK_STORM_TABLE_BYTES)));
+        const dim3 big_grid(static_cast<unsigned>((n_items + SHMK_STORM_WG - 1) / SHMK_STORM_WG)), big_block(SHMK_STORM_WG);
+        hipLaunchKernelGGL(kernel, big_grid, big_block, table_bytes, s, d, ctr_off, n_ctr, dev_targets, n_items, ops_per_item, dev_fetched,
+                           dev_checksum);
+        break;
+    }
     case SHM_STORM_FETCH_ADD:
         hipLaunchKernelGGL(shmk_amo_storm<0>, grid, block, 0, s, d, ctr_off, n_ctr, dev_targets, n_items, ops_per_item, dev_fetched, dev_checksum);
         break;

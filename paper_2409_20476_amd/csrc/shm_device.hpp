@@ -795,6 +795,77 @@ __device__ __forceinline__ int64_t shm_atomic_fetch_inc(const shm_dev_ctx &c, ui
 }
 __device__ __forceinline__ void shm_atomic_inc(const shm_dev_ctx &c, uint64_t off, int pe) { shm_atomic_add(c, off, 1, pe); }
 
+// Fetch-and-increment in batches by one work-group, on a symmetric table of n_ctr int64 counters
+// per PE.  The paper (section "Proposed Device APIs") gives the atomics no group form because on its
+// hardware scalar operations gain nothing from one; on this GPU the memory-side atomic units
+// (about 12 G operations per second for the whole chip) are the limit of a storm of scalar
+// fetch-adds, and a group that counts its own increments in LDS first sends one fetch-add per
+// counter it touched instead of one per increment.  Every thread of the group calls this with its
+// own list of nops <= MAXOPS counter ids (id_of(j) = pe * n_ctr + index for j < nops; nops may
+// differ from thread to thread and may be zero; j is a compile-time constant wherever id_of is
+// called, so a list held in registers stays there); sink(j, old) receives the value fetched by
+// the thread's j-th increment.
+// The values are those of one valid serialisation: the group's increments of a counter take
+// consecutive places in that counter's order.  `table` is LDS, npes * n_ctr entries of 8 bytes,
+// owned by the call from entry to return.  Relaxed, agent scope, like the scalar atomics.
+// FULL: every thread has either MAXOPS increments or none (nops is MAXOPS or 0), which leaves one
+// predicate per thread instead of one per list position.
+template <int MAXOPS, bool FULL, typename IdOf, typename Sink>
+__device__ __forceinline__ void shmx_atomic_fetch_inc_batch_wg(const shm_dev_ctx &c, uint64_t ctr_off, uint32_t n_ctr,
+                                                               unsigned long long *table, IdOf id_of, int nops, Sink sink)
+{
+    const bool any = nops > 0;
+    auto has = [&](int j) { return FULL ? any : j < nops; };
+    const uint32_t entries = static_cast<uint32_t>(c.npes) * n_ctr;
+    for (uint32_t e = threadIdx.x; e < entries; e += blockDim.x) table[e] = 0;
+    __syncthreads();
+    // The low half of an entry counts this group's increments; each increment learns its place,
+    // kept two to a register (a group has fewer than 65536 increments per thread list position:
+    // blockDim.x <= 1024 threads times MAXOPS <= 64).
+    static_assert(MAXOPS % 2 == 0 && MAXOPS <= 64, "places are packed in 16 bits");
+    uint32_t place[MAXOPS / 2];
+#pragma unroll
+    for (int w = 0; w < MAXOPS / 2; ++w) {
+        uint32_t lo = 0, hi = 0;
+        if (has(2 * w)) lo = atomicAdd(reinterpret_cast<unsigned int *>(table + id_of(2 * w)), 1u);
+        if (has(2 * w + 1)) hi = atomicAdd(reinterpret_cast<unsigned int *>(table + id_of(2 * w + 1)), 1u);
+        place[w] = lo | (hi << 16);
+        if ((w & 3) == 3) asm volatile("" ::: "memory");          // eight at a time: bounds the registers in use
+    }
+    __syncthreads();
+    // one fetch-add per touched counter, eight in flight per thread (sixteen measured slower); the entry then holds the value
+    // the counter had before the group's first increment
+    constexpr int Q = 8;
+    for (uint32_t e0 = threadIdx.x; e0 < entries; e0 += Q * blockDim.x) {
+        uint32_t count[Q];
+        int64_t before[Q];
+#pragma unroll
+        for (int q = 0; q < Q; ++q) {
+            const uint32_t e = e0 + q * blockDim.x;
+            count[q] = e < entries ? static_cast<uint32_t>(table[e]) : 0u;
+        }
+#pragma unroll
+        for (int q = 0; q < Q; ++q) {
+            const uint32_t e = e0 + q * blockDim.x;
+            if (count[q]) before[q] = shm_atomic_fetch_add(c, ctr_off + 8ull * (e % n_ctr), count[q], static_cast<int>(e / n_ctr));
+        }
+#pragma unroll
+        for (int q = 0; q < Q; ++q)
+            if (count[q]) table[e0 + q * blockDim.x] = static_cast<unsigned long long>(before[q]);
+    }
+    __syncthreads();
+#pragma unroll
+    for (int j = 0; j < MAXOPS; ++j) {
+        if (has(j)) {
+            uint32_t id = id_of(j);
+            asm volatile("" : "+v"(id));               // derive the LDS address again instead of keeping MAXOPS of them in registers
+            sink(j, static_cast<int64_t>(table[id] + ((place[j >> 1] >> (16 * (j & 1))) & 0xffffu)));
+        }
+        if ((j & 7) == 7) asm volatile("" ::: "memory");
+    }
+    __syncthreads();                                   // the table may be reused once everybody has read it
+}
+
 // ------------------------------------------------------------------------------------------
 // Reverse offload (paper section "Synchronization with Host"): a request to the host proxy is one
 // 64-byte message in a ring in pinned host memory.  The sender takes a slot with one atomic

@@ -25,7 +25,7 @@ SHM_CMP_EQ, SHM_CMP_NE, SHM_CMP_GT, SHM_CMP_GE, SHM_CMP_LT, SHM_CMP_LE = range(6
 SHM_INIT_DEFAULT, SHM_INIT_NO_DEVICE = 0, 1
 (SHM_AMO_FETCH, SHM_AMO_SET, SHM_AMO_SWAP, SHM_AMO_COMPARE_SWAP, SHM_AMO_FETCH_ADD, SHM_AMO_ADD, SHM_AMO_FETCH_INC,
  SHM_AMO_INC) = range(8)
-SHM_STORM_FETCH_ADD, SHM_STORM_ADD, SHM_STORM_CSWAP_LOOP, SHM_STORM_PLAIN_STORE = range(4)
+SHM_STORM_FETCH_ADD, SHM_STORM_ADD, SHM_STORM_CSWAP_LOOP, SHM_STORM_PLAIN_STORE, SHM_STORM_FETCH_ADD_WG = range(5)
 SHM_REDUCE_DUPLICATE, SHM_REDUCE_SPLIT = 0, 1
 SHM_COLL_FCOLLECT, SHM_COLL_BROADCAST = 0, 1
 SHM_TEAM_SYNC_OFF, SHM_TEAM_SYNC_FULL, SHM_TEAM_SYNC_TRACKED = 0, 1, 2

@@ -182,8 +182,9 @@ def _check_storm(g, o, npes, n_ctr, n_items, ops, kind, ctr_off):
     assert np.array_equal(checksum.cpu().numpy(), pad.reshape(n_groups, 256).sum(axis=1))
 
 
-@pytest.mark.parametrize("kind", [S.SHM_STORM_FETCH_ADD, S.SHM_STORM_ADD, S.SHM_STORM_CSWAP_LOOP])
-@pytest.mark.parametrize("npes,n_ctr,n_items,ops", [(2, 4, 1000, 10), (16, 1024, 1 << 14, 64), (3, 7, 300, 3)])
+@pytest.mark.parametrize("kind", [S.SHM_STORM_FETCH_ADD, S.SHM_STORM_ADD, S.SHM_STORM_CSWAP_LOOP, S.SHM_STORM_FETCH_ADD_WG])
+@pytest.mark.parametrize("npes,n_ctr,n_items,ops", [(2, 4, 1000, 10), (16, 1024, 1 << 14, 64), (3, 7, 300, 3), (5, 100, 2500, 64),
+                                                    (8, 2048, 5000, 16), (1, 1, 1025, 64)])
 def test_storm_small(kind, npes, n_ctr, n_items, ops):
     g, o = make_pair(npes, MiB)
     with g:
@@ -194,13 +195,25 @@ def test_storm_small(kind, npes, n_ctr, n_items, ops):
 
 
 @pytest.mark.timeout(900)
-def test_config4_full_size():
-    """16 PEs x 1024 counters, 2^20 work-items x 64 fetch-adds."""
+@pytest.mark.parametrize("kind", [S.SHM_STORM_FETCH_ADD, S.SHM_STORM_FETCH_ADD_WG])
+def test_config4_full_size(kind):
+    """16 PEs x 1024 counters, 2^20 work-items x 64 fetch-adds, scalar and batched by work-groups."""
     g, o = make_pair(16, MiB)
     with g:
         for p in range(16):
             write_both(g, o, p, 0, np.zeros(1024, np.int64))
-        _check_storm(g, o, 16, 1024, 1 << 20, 64, S.SHM_STORM_FETCH_ADD, 0)
+        _check_storm(g, o, 16, 1024, 1 << 20, 64, kind, 0)
+
+
+def test_batched_storm_carries_into_the_high_half_of_a_counter():
+    """Counters that start just below 2^32 and at the most negative value: the group's one fetch-add
+    per counter and the places added to what it fetched are 64-bit arithmetic."""
+    g, o = make_pair(2, MiB)
+    with g:
+        start = np.array([(1 << 32) - 5, -(1 << 63), -3, (1 << 62)], dtype=np.int64)
+        for p in range(2):
+            write_both(g, o, p, 1024, start)
+        _check_storm(g, o, 2, 4, 3000, 64, S.SHM_STORM_FETCH_ADD_WG, 1024)
 
 
 @pytest.mark.parametrize("how", ["put_signal", "put_then_atomic"])
