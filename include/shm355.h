@@ -374,15 +374,15 @@ int shm_launch_ring_pipeline(shm_ctx *ctx, uint64_t src_off, uint64_t slot_off, 
  * ops_per_item atomics; its j-th target is dev_targets[g*ops_per_item + j] = pe*n_ctr + index,
  * i.e. the int64 counter at ctr_off + 8*index on that PE.  kind: FETCH_ADD(+1) | ADD(+1, no
  * return) | CSWAP_LOOP (increment built from compare-swap) | PLAIN_STORE (not atomic; a timing
- * ceiling only) | FETCH_ADD_WG (the same fetch-adds batched by work-groups of 1024 work-items:
- * a group counts its increments per counter in LDS and sends one fetch-add per counter it touched;
- * an extension -- the paper, section "Proposed Device APIs", gives the atomics no group form --
+ * ceiling only) | FETCH_ADD_WG (the same fetch-adds batched by work-groups of 1024 work-items,
+ * at most one group per compute unit: a group counts its increments per counter in LDS, sends
+ * one fetch-add per counter it touched and hands every increment its own fetched value; an
+ * extension -- the paper, section "Proposed Device APIs", gives the atomics no group form --
  * with the same observable result, i.e. the fetched values of a counter are those of one valid
- * order of its increments; needs ops_per_item <= 64 and n_ctr * npes <= 16384, SHM_EINVAL
- * otherwise).  dev_fetched (or NULL): [n_items*ops_per_item] fetched values.  dev_checksum (or
- * NULL): one uint64 per 256 consecutive work-items, the sum of what they fetched.  n_items is
- * 1 .. 2^32 - 256 (one grid); n_ctr * npes <= 65536; ops_per_item 1 .. 4096; dev_targets 16-byte
- * aligned. */
+ * order of its increments; needs n_ctr * npes <= 16384, SHM_EINVAL otherwise).  dev_fetched (or
+ * NULL): [n_items*ops_per_item] fetched values.  dev_checksum (or NULL): one uint64 per 256
+ * consecutive work-items, the sum of what they fetched.  n_items is 1 .. 2^32 - 256 (one grid);
+ * n_ctr * npes <= 65536; ops_per_item 1 .. 4096; dev_targets 16-byte aligned. */
 int shm_launch_amo_storm(shm_ctx *ctx, uint64_t ctr_off, int n_ctr, const uint16_t *dev_targets, uint64_t n_items,
                          int ops_per_item, int kind, int64_t *dev_fetched, uint64_t *dev_checksum);
 

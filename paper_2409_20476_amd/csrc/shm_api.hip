@@ -1214,8 +1214,6 @@ int shm_launch_amo_storm(shm_ctx *c, uint64_t ctr_off, int n_ctr, const uint16_t
     if (kind < SHM_STORM_FETCH_ADD || kind > SHM_STORM_FETCH_ADD_WG) return fail(SHM_EINVAL, "unknown storm kind %d", kind);
     const bool batched = kind == SHM_STORM_FETCH_ADD_WG;
     const size_t table_bytes = 8ull * n_ctr * c->npes;            // the batched kind's table in LDS
-    if (batched && ops_per_item > SHMK_STORM_MAXOPS)
-        return fail(SHM_EINVAL, "the batched storm holds at most %d operations per work-item", SHMK_STORM_MAXOPS);
     if (batched && table_bytes > SHMK_STORM_TABLE_BYTES)
         return fail(SHM_EINVAL, "the batched storm keeps npes * n_ctr <= %d counters in LDS", static_cast<int>(SHMK_STORM_TABLE_BYTES / 8));
     const uint64_t groups = (n_items + SHMK_WG - 1) / SHMK_WG;
@@ -1229,13 +1227,15 @@ int shm_launch_amo_storm(shm_ctx *c, uint64_t ctr_off, int n_ctr, const uint16_t
     hipStream_t s = c->stream[0];
     switch (kind) {
     case SHM_STORM_FETCH_ADD_WG: {
-        // more LDS than a kernel gets without asking
-        const auto kernel = ops_per_item == SHMK_STORM_MAXOPS ? shmk_amo_storm_wg<true> : shmk_amo_storm_wg<false>;
-        HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void *>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
+        // more LDS than a kernel gets without asking; so one group per compute unit, and no more groups than those
+        HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void *>(shmk_amo_storm_wg), hipFuncAttributeMaxDynamicSharedMemorySize,
                                     static_cast<int>(SHMK_STORM_TABLE_BYTES)));
-        const dim3 big_grid(static_cast<unsigned>((n_items + SHMK_STORM_WG - 1) / SHMK_STORM_WG)), big_block(SHMK_STORM_WG);
-        hipLaunchKernelGGL(kernel, big_grid, big_block, table_bytes, s, d, ctr_off, n_ctr, dev_targets, n_items, ops_per_item, dev_fetched,
-                           dev_checksum);
+        const uint64_t rounds = (n_items + SHMK_STORM_WG - 1) / SHMK_STORM_WG;
+        const uint64_t want_groups = std::min<uint64_t>(rounds, std::max(1, c->num_cu));
+        const uint64_t items_per_group = (rounds + want_groups - 1) / want_groups * SHMK_STORM_WG;
+        const dim3 big_grid(static_cast<unsigned>((n_items + items_per_group - 1) / items_per_group)), big_block(SHMK_STORM_WG);
+        hipLaunchKernelGGL(shmk_amo_storm_wg, big_grid, big_block, table_bytes, s, d, ctr_off, n_ctr, dev_targets, n_items, ops_per_item,
+                           dev_fetched, dev_checksum, items_per_group);
         break;
     }
     case SHM_STORM_FETCH_ADD:

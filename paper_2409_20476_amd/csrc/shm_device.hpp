@@ -800,70 +800,54 @@ __device__ __forceinline__ void shm_atomic_inc(const shm_dev_ctx &c, uint64_t of
 // hardware scalar operations gain nothing from one; on this GPU the memory-side atomic units
 // (about 12 G operations per second for the whole chip) are the limit of a storm of scalar
 // fetch-adds, and a group that counts its own increments in LDS first sends one fetch-add per
-// counter it touched instead of one per increment.  Every thread of the group calls this with its
-// own list of nops <= MAXOPS counter ids (id_of(j) = pe * n_ctr + index for j < nops; nops may
-// differ from thread to thread and may be zero; j is a compile-time constant wherever id_of is
-// called, so a list held in registers stays there); sink(j, old) receives the value fetched by
-// the thread's j-th increment.
-// The values are those of one valid serialisation: the group's increments of a counter take
-// consecutive places in that counter's order.  `table` is LDS, npes * n_ctr entries of 8 bytes,
-// owned by the call from entry to return.  Relaxed, agent scope, like the scalar atomics.
-// FULL: every thread has either MAXOPS increments or none (nops is MAXOPS or 0), which leaves one
-// predicate per thread instead of one per list position.
-template <int MAXOPS, bool FULL, typename IdOf, typename Sink>
+// counter it touched instead of one per increment -- from consecutive lanes to consecutive
+// counters, so that a wave's 64 atomics fall on eight 64-byte lines.
+//
+// Every thread of the group calls this.  count_each(visit) calls visit(id) once for each of the
+// thread's increments (id = pe * n_ctr + index; any number of them, none included);
+// fetch_each(visit) walks the same increments again, and there visit(id) returns the value that
+// increment fetched.  Three steps: the increments are counted per counter in `table`; each touched
+// entry is replaced by what ONE global fetch-add of its count returns; the second walk increments
+// the entries again, now with return.  The values are those of one valid serialisation: the
+// group's increments of a counter take consecutive places in that counter's order.  `table` is
+// LDS, npes * n_ctr entries of 8 bytes, owned by the call from entry to return.  Relaxed, agent
+// scope, like the scalar atomics.
+template <typename CountEach, typename FetchEach>
 __device__ __forceinline__ void shmx_atomic_fetch_inc_batch_wg(const shm_dev_ctx &c, uint64_t ctr_off, uint32_t n_ctr,
-                                                               unsigned long long *table, IdOf id_of, int nops, Sink sink)
+                                                               unsigned long long *table, CountEach count_each, FetchEach fetch_each)
 {
-    const bool any = nops > 0;
-    auto has = [&](int j) { return FULL ? any : j < nops; };
     const uint32_t entries = static_cast<uint32_t>(c.npes) * n_ctr;
     for (uint32_t e = threadIdx.x; e < entries; e += blockDim.x) table[e] = 0;
     __syncthreads();
-    // The low half of an entry counts this group's increments; each increment learns its place,
-    // kept two to a register (a group has fewer than 65536 increments per thread list position:
-    // blockDim.x <= 1024 threads times MAXOPS <= 64).
-    static_assert(MAXOPS % 2 == 0 && MAXOPS <= 64, "places are packed in 16 bits");
-    uint32_t place[MAXOPS / 2];
-#pragma unroll
-    for (int w = 0; w < MAXOPS / 2; ++w) {
-        uint32_t lo = 0, hi = 0;
-        if (has(2 * w)) lo = atomicAdd(reinterpret_cast<unsigned int *>(table + id_of(2 * w)), 1u);
-        if (has(2 * w + 1)) hi = atomicAdd(reinterpret_cast<unsigned int *>(table + id_of(2 * w + 1)), 1u);
-        place[w] = lo | (hi << 16);
-        if ((w & 3) == 3) asm volatile("" ::: "memory");          // eight at a time: bounds the registers in use
-    }
+    count_each([&](uint32_t id) { (void)atomicAdd(table + id, 1ull); });
     __syncthreads();
-    // one fetch-add per touched counter, eight in flight per thread (sixteen measured slower); the entry then holds the value
-    // the counter had before the group's first increment
+    // One fetch-add per touched counter, eight in flight per thread.  The groups of a grid start at
+    // different entries (whole waves apart), so that they do not all queue at the same counters.
     constexpr int Q = 8;
-    for (uint32_t e0 = threadIdx.x; e0 < entries; e0 += Q * blockDim.x) {
-        uint32_t count[Q];
+    const uint32_t rot = static_cast<uint32_t>(static_cast<uint64_t>(blockIdx.x) * entries / gridDim.x) & ~63u;
+    auto entry = [&](uint32_t k) { return k + rot < entries ? k + rot : k + rot - entries; };      // k < entries
+    for (uint32_t k0 = threadIdx.x; k0 < entries; k0 += Q * blockDim.x) {
+        unsigned long long count[Q];
         int64_t before[Q];
 #pragma unroll
         for (int q = 0; q < Q; ++q) {
-            const uint32_t e = e0 + q * blockDim.x;
-            count[q] = e < entries ? static_cast<uint32_t>(table[e]) : 0u;
+            const uint32_t k = k0 + q * blockDim.x;
+            count[q] = k < entries ? table[entry(k)] : 0ull;
         }
 #pragma unroll
         for (int q = 0; q < Q; ++q) {
-            const uint32_t e = e0 + q * blockDim.x;
-            if (count[q]) before[q] = shm_atomic_fetch_add(c, ctr_off + 8ull * (e % n_ctr), count[q], static_cast<int>(e / n_ctr));
+            if (count[q]) {
+                const uint32_t e = entry(k0 + q * blockDim.x);
+                before[q] = shm_atomic_fetch_add(c, ctr_off + 8ull * (e % n_ctr), static_cast<int64_t>(count[q]), static_cast<int>(e / n_ctr));
+            }
         }
 #pragma unroll
         for (int q = 0; q < Q; ++q)
-            if (count[q]) table[e0 + q * blockDim.x] = static_cast<unsigned long long>(before[q]);
+            if (count[q]) table[entry(k0 + q * blockDim.x)] = static_cast<unsigned long long>(before[q]);
     }
     __syncthreads();
-#pragma unroll
-    for (int j = 0; j < MAXOPS; ++j) {
-        if (has(j)) {
-            uint32_t id = id_of(j);
-            asm volatile("" : "+v"(id));               // derive the LDS address again instead of keeping MAXOPS of them in registers
-            sink(j, static_cast<int64_t>(table[id] + ((place[j >> 1] >> (16 * (j & 1))) & 0xffffu)));
-        }
-        if ((j & 7) == 7) asm volatile("" ::: "memory");
-    }
-    __syncthreads();                                   // the table may be reused once everybody has read it
+    fetch_each([&](uint32_t id) { return static_cast<int64_t>(atomicAdd(table + id, 1ull)); });
+    __syncthreads();                                   // the table may be reused once everybody is through
 }
 
 // ------------------------------------------------------------------------------------------

@@ -521,53 +521,73 @@ __global__ __launch_bounds__(SHMK_WG) void shmk_amo_storm(shm_dev_ctx c, uint64_
     }
 }
 
-// The same storm with the fetch-adds batched by work-groups of SHMK_STORM_WG threads (one item per
-// thread, at most SHMK_STORM_MAXOPS operations per item; FULL: exactly that many).  Checksums stay
-// one per SHMK_WG items.
-constexpr int SHMK_STORM_WG = 1024, SHMK_STORM_MAXOPS = 64;
+// The same storm with the fetch-adds batched by work-groups of SHMK_STORM_WG threads.  Group b takes
+// the items [b * items_per_group, (b + 1) * items_per_group) -- a multiple of SHMK_STORM_WG, so
+// that the checksums stay one per SHMK_WG items -- in rounds of one item per thread, and flushes its
+// counts once.
+constexpr int SHMK_STORM_WG = 1024;
 constexpr size_t SHMK_STORM_TABLE_BYTES = 128 * 1024;      // 16384 counters of 8 bytes, out of 160 KiB of LDS
-template <bool FULL>
 __global__ __launch_bounds__(SHMK_STORM_WG) void shmk_amo_storm_wg(shm_dev_ctx c, uint64_t ctr_off, uint32_t n_ctr,
                                                                    const uint16_t *__restrict__ targets, uint64_t n_items, int ops,
-                                                                   int64_t *__restrict__ fetched, uint64_t *__restrict__ checksum)
+                                                                   int64_t *__restrict__ fetched, uint64_t *__restrict__ checksum,
+                                                                   uint64_t items_per_group)
 {
     extern __shared__ unsigned long long shmk_storm_table[];
     __shared__ unsigned long long part_sum[SHMK_STORM_WG / SHMK_WG];
-    if (threadIdx.x < SHMK_STORM_WG / SHMK_WG) part_sum[threadIdx.x] = 0;
-    const uint64_t g = static_cast<uint64_t>(blockIdx.x) * SHMK_STORM_WG + threadIdx.x;
-    const bool mine = g < n_items;
-    const uint16_t *t = targets + (mine ? g * ops : 0);
-    int64_t *f = fetched && mine ? fetched + g * ops : nullptr;
-    // the item's target ids, two to a register
-    uint32_t packed[SHMK_STORM_MAXOPS / 2];
+    const uint64_t first = blockIdx.x * items_per_group, last = min(n_items, first + items_per_group);
+    const unsigned part = threadIdx.x / SHMK_WG;
+    // Walks the group's items, calling visit(id) for every target of this thread's items.  With
+    // FETCHING the values that visit returns are stored and summed.  The round loop is uniform over
+    // the group (it holds barriers).
+    auto walk = [&](auto visit, auto fetching) {
+        constexpr bool FETCHING = decltype(fetching)::value;
+        for (uint64_t r = first; r < last; r += SHMK_STORM_WG) {
+            const uint64_t g = r + threadIdx.x;
+            uint64_t sum = 0;
+            if (g < last) {
+                const uint16_t *t = targets + g * ops;
+                int64_t *f = FETCHING && fetched ? fetched + g * ops : nullptr;
+                int j = 0;
+                if ((ops & 7) == 0) {                  // rows of whole 16-byte vectors (the table is 16-byte aligned)
+                    for (; j < ops; j += 8) {
+                        const shm_u32x4 tv = *reinterpret_cast<const shm_u32x4 *>(t + j);
+                        const uint32_t tw[4] = {tv.x, tv.y, tv.z, tv.w};
+                        int64_t old[8];
 #pragma unroll
-    for (int w = 0; w < SHMK_STORM_MAXOPS / 2; ++w) packed[w] = 0;
-    if (mine && (ops & 7) == 0) {                      // rows of whole 16-byte vectors (the table is 16-byte aligned)
+                        for (int q = 0; q < 8; ++q) old[q] = visit((q & 1) ? (tw[q >> 1] >> 16) : (tw[q >> 1] & 0xffffu));
+                        if (FETCHING) {
 #pragma unroll
-        for (int v = 0; v < SHMK_STORM_MAXOPS / 8; ++v)
-            if (8 * v < ops) {
-                const shm_u32x4 tv = reinterpret_cast<const shm_u32x4 *>(t)[v];
-                packed[4 * v] = tv.x, packed[4 * v + 1] = tv.y, packed[4 * v + 2] = tv.z, packed[4 * v + 3] = tv.w;
+                            for (int q = 0; q < 8; ++q) {
+                                if (f) f[j + q] = old[q];
+                                sum += static_cast<uint64_t>(old[q]);
+                            }
+                        }
+                    }
+                }
+                for (; j < ops; ++j) {
+                    const int64_t old = visit(t[j]);
+                    if (FETCHING) {
+                        if (f) f[j] = old;
+                        sum += static_cast<uint64_t>(old);
+                    }
+                }
             }
-    } else if (mine) {
-#pragma unroll
-        for (int j = 0; j < SHMK_STORM_MAXOPS; ++j)
-            if (j < ops) packed[j >> 1] |= static_cast<uint32_t>(t[j]) << (16 * (j & 1));
-    }
-    uint64_t sum = 0;
-    shmx_atomic_fetch_inc_batch_wg<SHMK_STORM_MAXOPS, FULL>(
-        c, ctr_off, n_ctr, shmk_storm_table, [&](int j) { return (packed[j >> 1] >> (16 * (j & 1))) & 0xffffu; }, mine ? ops : 0,
-        [&](int j, int64_t old) {
-            if (f) f[j] = old;
-            sum += static_cast<uint64_t>(old);
-        });
-    if (checksum != nullptr) {
-        const unsigned part = threadIdx.x / SHMK_WG;
-        atomicAdd(&part_sum[part], static_cast<unsigned long long>(sum));
-        __syncthreads();
-        const uint64_t slot = static_cast<uint64_t>(blockIdx.x) * (SHMK_STORM_WG / SHMK_WG) + part;
-        if (threadIdx.x % SHMK_WG == 0 && slot * SHMK_WG < n_items) checksum[slot] = part_sum[part];
-    }
+            if (FETCHING && checksum != nullptr) {
+                if (threadIdx.x < SHMK_STORM_WG / SHMK_WG) part_sum[threadIdx.x] = 0;
+                __syncthreads();
+                atomicAdd(&part_sum[part], static_cast<unsigned long long>(sum));
+                __syncthreads();
+                if (threadIdx.x % SHMK_WG == 0 && g < last) checksum[g / SHMK_WG] = part_sum[part];
+                __syncthreads();
+            }
+        }
+    };
+    shmx_atomic_fetch_inc_batch_wg(
+        c, ctr_off, n_ctr, shmk_storm_table,
+        [&](auto count) {
+            walk([&](uint32_t id) -> int64_t { count(id); return 0; }, std::false_type{});
+        },
+        [&](auto fetch) { walk(fetch, std::true_type{}); });
 }
 
 // ---- configuration 5a: fcollect, push --------------------------------------------------------

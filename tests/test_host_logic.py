@@ -149,7 +149,6 @@ def test_every_entry_point_validates_before_touching_the_device():
     assert code(lambda: g.launch_ring_pipeline(0, 65536, 262144, 131072, 4096, 4, 1 << 21, 2, 1)) == S.SHM_EINVAL     # too many groups
     assert code(lambda: g.launch_amo_storm(0, 16, 4096 + 2, 100, 8)) == S.SHM_EINVAL                            # table alignment
     assert code(lambda: g.launch_amo_storm(0, 1 << 15, 4096, 100, 8)) == S.SHM_EINVAL                           # 16-bit ids
-    assert code(lambda: g.launch_amo_storm(0, 16, 4096, 100, 65, S.SHM_STORM_FETCH_ADD_WG)) == S.SHM_EINVAL     # batched: list of 64
     assert code(lambda: g.launch_amo_storm(0, 4097, 4096, 100, 8, S.SHM_STORM_FETCH_ADD_WG)) == S.SHM_EINVAL    # batched: 4 x 4097 counters > LDS table
     assert code(lambda: g.launch_amo_storm(0, 4096, 4096, 100, 64, S.SHM_STORM_FETCH_ADD_WG)) == S.SHM_ENODEV   # ... 4 x 4096 fit
     assert code(lambda: g.launch_amo_storm(0, 16, 4096, 100, 8, S.SHM_STORM_FETCH_ADD_WG + 1)) == S.SHM_EINVAL   # unknown kind

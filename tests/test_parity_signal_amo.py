@@ -184,7 +184,7 @@ def _check_storm(g, o, npes, n_ctr, n_items, ops, kind, ctr_off):
 
 @pytest.mark.parametrize("kind", [S.SHM_STORM_FETCH_ADD, S.SHM_STORM_ADD, S.SHM_STORM_CSWAP_LOOP, S.SHM_STORM_FETCH_ADD_WG])
 @pytest.mark.parametrize("npes,n_ctr,n_items,ops", [(2, 4, 1000, 10), (16, 1024, 1 << 14, 64), (3, 7, 300, 3), (5, 100, 2500, 64),
-                                                    (8, 2048, 5000, 16), (1, 1, 1025, 64)])
+                                                    (8, 2048, 5000, 16), (1, 1, 1025, 64), (4, 300, 300000, 8), (3, 50, 2000, 100)])
 def test_storm_small(kind, npes, n_ctr, n_items, ops):
     g, o = make_pair(npes, MiB)
     with g:
