@@ -549,17 +549,28 @@ __global__ __launch_bounds__(SHMK_STORM_WG) void shmk_amo_storm_wg(shm_dev_ctx c
                 int64_t *f = FETCHING && fetched ? fetched + g * ops : nullptr;
                 int j = 0;
                 if ((ops & 7) == 0) {                  // rows of whole 16-byte vectors (the table is 16-byte aligned)
-                    for (; j < ops; j += 8) {
-                        const shm_u32x4 tv = *reinterpret_cast<const shm_u32x4 *>(t + j);
-                        const uint32_t tw[4] = {tv.x, tv.y, tv.z, tv.w};
-                        int64_t old[8];
+                    // up to eight vectors (64 targets) are loaded before the first of them is used:
+                    // one memory latency per 64 operations instead of one per eight
+                    for (; j < ops; j += 64) {
+                        const int nvec = min(8, (ops - j) >> 3);
+                        shm_u32x4 tv[8];
 #pragma unroll
-                        for (int q = 0; q < 8; ++q) old[q] = visit((q & 1) ? (tw[q >> 1] >> 16) : (tw[q >> 1] & 0xffffu));
-                        if (FETCHING) {
+                        for (int v = 0; v < 8; ++v)
+                            if (v < nvec) tv[v] = *reinterpret_cast<const shm_u32x4 *>(t + j + 8 * v);
 #pragma unroll
-                            for (int q = 0; q < 8; ++q) {
-                                if (f) f[j + q] = old[q];
-                                sum += static_cast<uint64_t>(old[q]);
+                        for (int v = 0; v < 8; ++v) {
+                            if (v < nvec) {
+                                const uint32_t tw[4] = {tv[v].x, tv[v].y, tv[v].z, tv[v].w};
+                                int64_t old[8];
+#pragma unroll
+                                for (int q = 0; q < 8; ++q) old[q] = visit((q & 1) ? (tw[q >> 1] >> 16) : (tw[q >> 1] & 0xffffu));
+                                if (FETCHING) {
+#pragma unroll
+                                    for (int q = 0; q < 8; ++q) {
+                                        if (f) f[j + 8 * v + q] = old[q];
+                                        sum += static_cast<uint64_t>(old[q]);
+                                    }
+                                }
                             }
                         }
                     }
