@@ -6,11 +6,14 @@ putting a 256 MiB float32 message to PE (p+1) mod 8 with 1024 work-groups of 256
 direct loads/stores, launched as one grid on the team stream.  One step = one such put by all
 eight PEs.  Inputs are seeded synthetic data resident in HBM before the timed region.
 
-The same line carries `roofline` (the put kernel against the HBM copy roofline, timed with HIP
-events on the stream it runs on), `cpu_baseline` (the oracle's work-group put timed on this host,
-context only) and `extras` with the other configurations: the put sweep over message sizes,
-work-group counts and both transfer paths with the measured crossover, the ping/flag latency, the
-pipelined ring, the atomic storm (ops/s) and the two collectives.
+The LAST line of stdout is one compact JSON object (a few KB): the headline, `roofline` (the put
+kernel against the HBM copy roofline, timed with HIP events on the stream it runs on),
+`cpu_baseline` (the oracle's work-group put timed on this host, context only), `amo_ops_per_s`, and
+`configs`, a short summary per configuration with the oracle's time beside each GPU figure.  The
+full measurements (the put sweep over message sizes, work-group counts and transfer paths, the
+ping/flag latency, the pipelined ring, the atomic storm, the collectives, the sweeps of the paper's
+other experiments) go to a JSON file (`--extras-out`, default gpurun_out/bench_extras.json) and, in
+short form, to stderr.
 """
 from __future__ import annotations
 
@@ -110,20 +113,106 @@ def headline(torch, S, synth, g, args):
     wall_ms = (t1 - t0) * 1e3 / args.steps
     kern_ms = e0.elapsed_time(e1) / args.steps
     g.set_team_sync(True)
-    ok = bool(np.array_equal(g.read(1, dst, 4096), data0[:4096]) and
+    # every delivered byte against its source, on the device (torch only compares), plus PE 1's first
+    # and last 4 KiB against the host's copy of PE 0's seeded data
+    H = g.heap_tensor.numel() // npes
+    ok = all(torch.equal(g.heap_tensor[((p + 1) % npes) * H + dst:((p + 1) % npes) * H + dst + n],
+                         g.heap_tensor[p * H + src:p * H + src + n]) for p in range(npes))
+    ok = bool(ok and np.array_equal(g.read(1, dst, 4096), data0[:4096]) and
               np.array_equal(g.read(1, dst + n - 4096, 4096), data0[n - 4096:]))
     payload = npes * n
     res = {
         "wall_ms": wall_ms, "kernel_ms": kern_ms, "payload_bytes": payload,
         "value_gbs": payload / wall_ms / 1e6,
         "achieved_gbs": 2 * payload / kern_ms / 1e6,
-        "spot_check_ok": ok,
+        "check_ok": ok, "kernel": "shmk_wg_rma_tiles",
     }
     g.free(src), g.free(dst)
     return res, data0
 
 
-def cpu_put_baseline(oracle_mod, data0, n, n_wg, budget_s=12.0):
+def best_of_3(fn):
+    best = float("inf")
+    for _ in range(3):
+        t0 = time.perf_counter()
+        fn()
+        best = min(best, time.perf_counter() - t0)
+    return best
+
+
+def cpu_config_baselines(oracle_mod, synth):
+    """The oracle, as it stands, timed on this host right after the GPU measurement of each
+    configuration: one core (numpy copies and adds are single-threaded), best of 3, on a bounded
+    sample of the configuration's workload.  Context only.  Returns {extra name: function}."""
+    O = oracle_mod
+
+    def c1():
+        o = O.ShmemOracle(2, MiB)
+        payload = synth.c1_payload(4096)
+        n = payload.nbytes
+        data, back, flag = o.malloc(n), o.malloc(n), o.calloc(8, 8)
+        o.write(0, data, payload)
+
+        def once():
+            o.write(1, flag, np.zeros(8, np.uint8))
+            o.wg_put(0, data, data, n, 1, 1)
+            o.quiet(0)
+            o.put_signal(0, data, data, 0, flag, 1, O.SIGNAL_SET, 1)
+            o.signal_wait_until(1, flag, O.CMP_EQ, 1)
+            o.wg_get(1, back, data, n, 0, 1)
+        t = min(best_of_3(once) for _ in range(20))
+        assert np.array_equal(o.read(1, back, n, np.int32), payload)
+        return {"us": t * 1e6, "sample": "the whole configuration (16 KiB put, quiet, flag, wait, get back), best of 60"}
+
+    def c3():
+        npes, n_chunks, nel = 8, 8, 524288          # 8 of the 64 chunks per PE
+        cb = 2 * nel
+        o = O.ShmemOracle(npes, 2 * cb * n_chunks + 4 * nel + (1 << 16))
+        src, slot, acc, sig = o.malloc(cb * n_chunks), o.malloc(cb * n_chunks), o.malloc(4 * nel), o.calloc(8, 8)
+        for p in range(npes):
+            o.write(p, src, synth.c3_chunks(p, n_chunks, nel))
+
+        def once():
+            for p in range(npes):
+                o.write(p, sig, np.zeros(8, np.uint8))
+            o.ring_pipeline(src, slot, sig, acc, cb, n_chunks, 32, 1)
+        t = best_of_3(once)
+        payload = npes * n_chunks * cb
+        return {"ms_scaled_to_64_chunks": t * 1e3 * 64 / n_chunks, "payload_gbs": payload / t / 1e9,
+                "sample": f"8 PEs x {n_chunks} of the 64 chunks of 1 MiB, best of 3"}
+
+    def c4():
+        npes, n_ctr, n_items, ops = 16, 1024, 1 << 17, 64     # 2^23 of the 2^26 operations
+        o = O.ShmemOracle(npes, MiB)
+        ctr = o.calloc(8 * n_ctr, 256)
+        targets = synth.c4_targets(n_items, ops, npes, n_ctr)
+        t = best_of_3(lambda: o.amo_storm(ctr, n_ctr, targets))
+        return {"mops": n_items * ops / t / 1e6, "sample": f"{n_items * ops} of the 2^26 fetch-adds (array form of the oracle), best of 3"}
+
+    def c5():
+        npes, nel = 8, 2 * MiB                              # 2 Mi of the 16 Mi elements per PE
+        o = O.ShmemOracle(npes, 4 * nel * (npes + 3) + (1 << 16))
+        fsrc, fdst, rsrc, rdst = o.malloc(4 * nel), o.malloc(4 * nel * npes), o.malloc(4 * nel), o.malloc(4 * nel)
+        for p in range(npes):
+            o.write(p, fsrc, synth.c5_fcollect_source(p, nel))
+            o.write(p, rsrc, synth.c5_reduce_source(p, nel))
+        tf = best_of_3(lambda: o.fcollect(fdst, fsrc, 4 * nel))
+        tr = best_of_3(lambda: o.reduce_sum_f32(rdst, rsrc, nel))
+        scale = 16 * MiB / nel
+        return {"fcollect_ms_scaled": tf * 1e3 * scale, "fcollect_algorithmic_gbs": (npes + npes * npes) * 4 * nel / tf / 1e9,
+                "reduce_ms_scaled": tr * 1e3 * scale, "reduce_melems_per_s": nel / tr / 1e6,
+                "sample": f"8 PEs x {nel >> 20} Mi of the 16 Mi elements, times scaled by {scale:g}, best of 3"}
+
+    def wrap(fn):
+        def run():
+            r = fn()
+            r.update({"cores": 1, "kind": "oracle", "host_logical_cpus": os.cpu_count()})
+            return r
+        return run
+    return {"config1_pingflag": wrap(c1), "config3_ring": wrap(c3), "config4_amo_storm": wrap(c4), "config5_collectives": wrap(c5)}
+
+
+def cpu_put_baseline(oracle_mod, data0, n, n_wg, budget_s=6.0):
     """The oracle's work-group put, one host core, on a bounded sample of the same workload:
     one PE's message at full size, repeated until the time budget is used."""
     o = oracle_mod.ShmemOracle(2, 2 * n)
@@ -173,6 +262,62 @@ def in_kernel_put_us(torch, S, g, npes, dst, src, n, n_wg, ticks, khz):
     return min(run(reps) for _ in range(5))
 
 
+def crossover_at_other_queue_count(queues):
+    """The hardware-queue count is read when the HIP runtime initialises, so the crossover at the other
+    count (8 PE streams on 4 queues run in two rounds; on 8 queues all at once) is measured by a child
+    process running this file's sweep alone."""
+    import subprocess
+    cmd = [sys.executable, os.path.abspath(__file__), "--hw-queues", str(queues), "--extras", "config2_put_sweep", "--size-mib", "16",
+           "--steps", "2", "--warmup", "1", "--no-cpu-baseline", "--no-other-queue-count", "--extras-out", ""]
+    try:
+        proc = subprocess.run(cmd, capture_output=True, text=True, timeout=300)
+        last = proc.stdout.strip().splitlines()[-1]
+        return {"hip_hardware_queues": queues, "crossover_bytes": json.loads(last)["configs"]["c2"]["crossover_bytes_ldst_to_sdma_by_wg_per_pe"]}
+    except Exception as e:          # the figure is an extra: its absence must not cost the headline
+        log(f"[bench] crossover at {queues} hardware queues not measured: {e!r}")
+        return None
+
+
+def placement_spread(torch, S, g, args):
+    """The headline put at nine placements of the destination relative to the source (HBM channel
+    hashing makes the copy rate depend on it): percent of the HBM copy roofline, HIP events."""
+    npes, n = 8, 256 * MiB
+    region = g.malloc(2 * n + 64 * MiB)
+    shifts = (0, 4096, 8192, 65536, MiB, MiB + 4096, 2 * MiB, 16 * MiB + 8192, 64 * MiB - 4096)
+    g.set_team_sync(False)
+    pcts = {}
+    for sh in shifts:
+        dst = region + n + sh
+        ms = min(time_on_stream(torch, g.streams[0], lambda: g.launch_wg_put_all(1, dst, region, n, 1024, S.SHM_PATH_LDST), 5)
+                 for _ in range(4))
+        pcts[str(sh)] = 100.0 * 2 * npes * n / ms / 1e6 / HBM_PEAK_GBS
+    g.set_team_sync(True)
+    g.free(region)
+    v = sorted(pcts.values())
+    return {"pct_by_destination_shift_bytes": pcts, "pct_min_med_max": [v[0], v[len(v) // 2], v[-1]],
+            "note": "8 PEs x 256 MiB x 1024 groups, destination = source + 256 MiB + shift"}
+
+
+def hbm_ceilings(torch, S, g, args):
+    """One-direction and copy ceilings of this chip measured with the library's own access forms
+    (group-owned 64 KiB tiles, 16-byte nontemporal loads and stores, the launch shape of the headline
+    put): what a kernel that only reads, only writes, or copies can reach."""
+    npes, n = 8, 256 * MiB
+    a, b = g.malloc(n), g.malloc(n)
+    g.set_team_sync(False)
+    out = {}
+    for name, kind, bytes_moved in (("read_only", S.SHM_PROBE_READ, npes * n), ("write_only", S.SHM_PROBE_WRITE, npes * n),
+                                    ("copy", S.SHM_PROBE_COPY, 2 * npes * n)):
+        ms = min(time_on_stream(torch, g.streams[0], lambda: g.launch_stream_probe(kind, b, a, n, 1024), 5) for _ in range(5))
+        out[name] = {"ms": ms, "gbs": bytes_moved / ms / 1e6, "frac_hbm": bytes_moved / ms / 1e6 / HBM_PEAK_GBS}
+    g.set_team_sync(True)
+    g.free(a), g.free(b)
+    r, w = out["read_only"]["gbs"], out["write_only"]["gbs"]
+    return {"kernels": out, "copy_bus_time_limit_frac_hbm": 2.0 / (1.0 / r + 1.0 / w) / HBM_PEAK_GBS,
+            "note": "8 PEs x 256 MiB x 1024 groups; copy_bus_time_limit = 2 / (1/read + 1/write): the rate of a copy whose reads and "
+                    "writes share the bus without overlapping"}
+
+
 def put_sweep(torch, S, g, args):
     """Configuration 2: message sizes 8 B .. 256 MiB, 8 PEs concurrently, each on its own stream
     (or engine), through loads/stores with 1, 4, 64, 1024 work-groups, through the SDMA copy
@@ -185,6 +330,8 @@ def put_sweep(torch, S, g, args):
     khz = g.wall_clock_khz()
     rows = []
     wgs = (1, 4, 64, 1024)
+    never = (1 << 64) - 1
+    defaults = {str(w): (None if g.get_cutover(w) >= never else g.get_cutover(w)) for w in wgs}     # before the sweep retunes them
     for n in sizes:
         row = {"bytes": n}
         for n_wg in wgs:
@@ -229,7 +376,13 @@ def put_sweep(torch, S, g, args):
     auto = [{"bytes": r["bytes"], **{f"wg{w}": ("sdma" if g.choose_path(r["bytes"], w) == S.SHM_PATH_SDMA else "ldst") for w in wgs}}
             for r in rows]
     g.free(src), g.free(dst)
-    return {"pes": npes,
+    placement = placement_spread(torch, S, g, args) if max_n >= 256 * MiB else None
+    queues = int(os.environ.get("GPU_MAX_HW_QUEUES", "4"))
+    other = None
+    if not args.no_other_queue_count:
+        other = crossover_at_other_queue_count(8 if queues < 8 else 4)
+    return {"pes": npes, "hip_hardware_queues": queues, "library_default_cutover_bytes": defaults,
+            "crossover_other_queue_count": other, **({"placement": placement} if placement else {}),
             "timing": "8 PEs concurrently. ldst_wgK_us: device clock inside the issuing kernel, per put incl. its quiet, mean over "
                       "PEs (a put issued from a running kernel, as in the paper's experiment; ldst_wgK_gbs uses the span from "
                       "the first PE's start to the last PE's end); ldst_wgK_host_us, sdma_us, memcpy_us: host "
@@ -624,9 +777,14 @@ def collectives(torch, S, synth, g, args):
         out[key] = {"ms": best, "traffic_gbs": sd_bytes / best / 1e6, "note": note}
     dup_bytes = npes * npes * 4 * nel + npes * 4 * nel
     spl_bytes = npes * 4 * nel + npes * 4 * nel
+    # The duplicate form loads every source npes times, but the npes readers of one share run side by
+    # side on one XCD and all but the first are served by that L2: the kernel is bound by L2 hit
+    # bandwidth, and what it must take from HBM is each source once plus the results (= spl_bytes).
+    dup_note = "bound: l2 (npes loads per element, all but one served by the XCD's L2); frac_hbm_min_traffic = (each source once + results) / time / 8 TB/s"
     for n_wg in (256, 1024):
         ms = best_of(lambda: g.launch_reduce_sum_f32(rdst, rsrc, nel, n_wg, S.SHM_REDUCE_DUPLICATE))
-        out[f"reduce_duplicate_wg{n_wg}"] = {"ms": ms, "algorithmic_gbs": dup_bytes / ms / 1e6, "frac_hbm": dup_bytes / ms / 1e6 / HBM_PEAK_GBS}
+        out[f"reduce_duplicate_wg{n_wg}"] = {"ms": ms, "bound": "l2", "algorithmic_load_store_gbs": dup_bytes / ms / 1e6,
+                                             "frac_hbm_min_traffic": spl_bytes / ms / 1e6 / HBM_PEAK_GBS, "note": dup_note}
         ms = best_of(lambda: g.launch_reduce_sum_f32(rdst, rsrc, nel, n_wg, S.SHM_REDUCE_SPLIT))
         out[f"reduce_split_wg{n_wg}"] = {"ms": ms, "algorithmic_gbs": spl_bytes / ms / 1e6, "frac_hbm": spl_bytes / ms / 1e6 / HBM_PEAK_GBS}
     # the reduction matrix on the same 64 MiB per PE: one operator per element width (HBM-bound, so the
@@ -638,13 +796,112 @@ def collectives(torch, S, synth, g, args):
                                    ("int64_prod", S.SHM_INT64, S.SHM_OP_PROD, 8), ("float64_sum", S.SHM_FLOAT64, S.SHM_OP_SUM, 8)):
         ms = best_of(lambda: g.launch_reduce(rdst, rsrc, 4 * nel // width, dtype, op, 1024, S.SHM_REDUCE_DUPLICATE))
         ms2 = best_of(lambda: g.launch_reduce(rdst, rsrc, 4 * nel // width, dtype, op, 1024, S.SHM_REDUCE_SPLIT))
-        matrix[name] = {"duplicate_ms": ms, "duplicate_frac_hbm": dup_bytes / ms / 1e6 / HBM_PEAK_GBS,
+        matrix[name] = {"duplicate_ms": ms, "duplicate_frac_hbm_min_traffic": spl_bytes / ms / 1e6 / HBM_PEAK_GBS,
                         "split_ms": ms2, "split_frac_hbm": spl_bytes / ms2 / 1e6 / HBM_PEAK_GBS}
     out["reduce_matrix_wg1024"] = matrix
     g.set_team_sync(True)
     for off in (fsrc, fdst, rsrc, rdst):
         g.free(off)
     return out
+
+
+def kernel_source_sha256():
+    """Hash of the device sources every kernel is built from: a profile summary made for other
+    sources says nothing about the kernels measured now."""
+    import hashlib
+    h = hashlib.sha256()
+    for name in ("shm_device.hpp", "shm_kernels.hpp"):
+        with open(os.path.join(ROOT, "paper_2409_20476_amd", "csrc", name), "rb") as f:
+            h.update(f.read())
+    return h.hexdigest()
+
+
+def traffic_from_profile(args):
+    """HBM bytes per launch of the headline kernel from the committed rocprofv3 counter summary
+    (FETCH_SIZE and WRITE_SIZE cannot be read from inside this process).  Reported only when the
+    summary was made for the device sources as they are now; otherwise null."""
+    tpath = os.path.join(ROOT, "profiles", "shmk_wg_rma_tiles_config2_256MiB_hbm_counters.txt")
+    if not (os.path.exists(tpath) and args.size_mib == 256 and args.n_wg == 1024):
+        return None, "not measured in this run"
+    import re
+    text = open(tpath).read()
+    m = re.search(r"^hbm_bytes_per_launch:\s*(\d+)", text, re.M)
+    sha = re.search(r"^kernel_source_sha256:\s*([0-9a-f]{64})", text, re.M)
+    if not m or not sha or sha.group(1) != kernel_source_sha256():
+        return None, "the committed counter summary was made for other kernel sources; not measured in this run"
+    return int(m.group(1)), "rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE summary under profiles/, made for these kernel sources (hash checked)"
+
+
+def rnd(x, digits=4):
+    """Short numbers for the compact line."""
+    if isinstance(x, float):
+        return float(f"{x:.{digits}g}")
+    if isinstance(x, dict):
+        return {k: rnd(v, digits) for k, v in x.items()}
+    if isinstance(x, (list, tuple)):
+        return [rnd(v, digits) for v in x]
+    return x
+
+
+def summarise(extras, cpu_legs):
+    """One short entry per configuration for the compact line: the GPU figure, its fraction of the HBM
+    roofline where that is the bound, and the oracle's time on this host beside it."""
+    out = {}
+    pct = lambda payload_gbs: 100.0 * 2 * payload_gbs / HBM_PEAK_GBS        # a copy reads and writes every byte
+    if "config1_pingflag" in extras:
+        r = extras["config1_pingflag"]
+        out["c1"] = {"device_us": r["device_us"], "host_round_trip_us": r["host_round_trip_us"], "ok": r["ok"],
+                     "cpu_oracle_us": cpu_legs.get("config1_pingflag", {}).get("us")}
+    if "config2_put_sweep" in extras:
+        r = extras["config2_put_sweep"]
+        rows = {q["bytes"] >> 20: q for q in r["rows"] if q["bytes"] >= 64 * MiB}
+        out["c2"] = {
+            "pct_of_hbm_roofline_by_mib": {
+                "team_grid_wg1024": {str(m): pct(q["team_wg1024_event_gbs"]) for m, q in rows.items()},
+                "per_pe_streams_wg1024": {str(m): pct(8 * q["bytes"] / q["ldst_wg1024_host_us"] / 1e3) for m, q in rows.items()},
+                "per_pe_streams_wg64": {str(m): pct(8 * q["bytes"] / q["ldst_wg64_host_us"] / 1e3) for m, q in rows.items()},
+                "put_plus_quiet_inside_kernel_wg1024": {str(m): pct(q["ldst_wg1024_gbs"]) for m, q in rows.items()},
+                "sdma_engines": {str(m): pct(q["sdma_gbs"]) for m, q in rows.items()},
+            },
+            "crossover_bytes_ldst_to_sdma_by_wg_per_pe": r["crossover_bytes"],
+            "hip_hardware_queues": r["hip_hardware_queues"],
+            "crossover_other_queue_count": r.get("crossover_other_queue_count"),
+            "library_default_cutover_bytes": r.get("library_default_cutover_bytes"),
+        }
+        if "placement" in r:
+            out["c2"]["placement_pct_min_med_max"] = r["placement"]["pct_min_med_max"]
+    if "hbm_ceilings" in extras:
+        out["hbm_ceilings_pct"] = {k: v["frac_hbm"] * 100 for k, v in extras["hbm_ceilings"]["kernels"].items()}
+    if "config3_ring" in extras:
+        r = extras["config3_ring"]
+        shapes = {k: q for k, q in r.items() if k.startswith("prod")}
+        best = min(shapes.values(), key=lambda q: q["ms"])
+        cpu = cpu_legs.get("config3_ring", {})
+        out["c3"] = {"ms": best["ms"], "frac_hbm": best["frac_hbm"], "payload_gbs": best["payload_gbs"],
+                     "ms_by_shape": {k: q["ms"] for k, q in shapes.items()},
+                     "cpu_oracle_ms_scaled": cpu.get("ms_scaled_to_64_chunks"), "cpu_oracle_payload_gbs": cpu.get("payload_gbs")}
+    if "config4_amo_storm" in extras:
+        r = extras["config4_amo_storm"]
+        out["c4"] = {"fetch_add_gops": r["fetch_add"]["gops"], "ms": r["fetch_add"]["ms"],
+                     "add_no_return_gops": r["add_no_return"]["gops"], "plain_store_ceiling_gops": r["plain_store_ceiling"]["gops"],
+                     "batched_by_work_group_gops": r["fetch_add_batched_by_work_group"]["gops"],
+                     "cpu_oracle_mops": cpu_legs.get("config4_amo_storm", {}).get("mops")}
+    if "config5_collectives" in extras:
+        r = extras["config5_collectives"]
+        fc = min((v for k, v in r.items() if k.startswith("fcollect_ldst_wg")), key=lambda q: q["ms"])
+        sp = min((v for k, v in r.items() if k.startswith("reduce_split_wg")), key=lambda q: q["ms"])
+        du = min((v for k, v in r.items() if k.startswith("reduce_duplicate_wg")), key=lambda q: q["ms"])
+        cpu = cpu_legs.get("config5_collectives", {})
+        out["c5"] = {"fcollect_ms": fc["ms"], "fcollect_frac_hbm": fc["frac_hbm"],
+                     "reduce_split_ms": sp["ms"], "reduce_split_frac_hbm": sp["frac_hbm"],
+                     "reduce_duplicate_ms": du["ms"], "reduce_duplicate_bound": "l2",
+                     "reduce_duplicate_frac_hbm_min_traffic": du["frac_hbm_min_traffic"],
+                     "cpu_oracle_fcollect_ms_scaled": cpu.get("fcollect_ms_scaled"), "cpu_oracle_reduce_ms_scaled": cpu.get("reduce_ms_scaled")}
+    if "reverse_offload" in extras:
+        r = extras["reverse_offload"]
+        out["reverse_offload"] = {"round_trip_us": r["round_trip_us"].get("1"), "mreq_per_s": max(r["request_rate_mreq_s"].values()),
+                                  "in_kernel_cutover_bytes_by_work_items": r["cutover_bytes_by_work_items"]}
+    return rnd(out)
 
 
 def main():
@@ -657,17 +914,24 @@ def main():
     ap.add_argument("--sweep-max-mib", type=int, default=256)
     ap.add_argument("--no-extras", action="store_true", help="headline only (used for profiling runs)")
     ap.add_argument("--hw-queues", type=int, default=0,
-                    help="set GPU_MAX_HW_QUEUES for this run (HIP's default is 4: the kernels of 8 PE streams then run in two "
-                         "rounds and the per-PE curves of the sweep halve; 8 gives every PE stream a queue); 0 = leave the "
+                    help="set GPU_MAX_HW_QUEUES for this run, 1..32 (HIP's default is 4: the kernels of 8 PE streams then run in "
+                         "two rounds and the per-PE curves of the sweep halve; 8 gives every PE stream a queue); 0 = leave the "
                          "environment as it is")
     ap.add_argument("--extras", default="all", help="comma-separated names of the extra measurements to run (default: all)")
+    ap.add_argument("--extras-out", default=os.path.join(ROOT, "gpurun_out", "bench_extras.json"),
+                    help="file that receives the full measurements as JSON ('' = do not write)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-other-queue-count", action="store_true",
+                    help="do not start the child process that measures the crossover at the other hardware-queue count")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also run a plain 2 GiB tensor copy five times (reference reading for HBM byte counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (its PEs are logical partitions of that GPU's HBM); "
               "--gpus must be 1", file=sys.stderr)
+        return 2
+    if args.hw_queues and not 1 <= args.hw_queues <= 32:
+        print("bench.py: --hw-queues must be 1..32", file=sys.stderr)
         return 2
 
     if args.hw_queues:       # read by the HIP runtime when it initialises, i.e. before torch touches the GPU
@@ -694,17 +958,19 @@ def main():
     log(f"[bench] headline: {head}")
     n = args.size_mib * MiB
 
-    cpu = None
+    cpu, cpu_fns, cpu_legs = None, {}, {}
     if not args.no_cpu_baseline:
         from oracle import shmem_oracle
         cpu = cpu_put_baseline(shmem_oracle, data0, n, args.n_wg)
         log(f"[bench] cpu baseline: {cpu}")
+        cpu_fns = cpu_config_baselines(shmem_oracle, synth)
     del data0
 
     extras = {}
     table = [
         ("config1_pingflag", lambda: pingflag(torch, S, synth, args), lambda r: f"c1: {r}"),
         ("config2_put_sweep", lambda: put_sweep(torch, S, g, args), lambda r: f"crossover: {r['crossover_bytes']}"),
+        ("hbm_ceilings", lambda: hbm_ceilings(torch, S, g, args), lambda r: f"ceilings: {r['kernels']}"),
         ("reverse_offload", lambda: reverse_offload(torch, S, args),
          lambda r: f"reverse offload: rtt {r['round_trip_us']} rate {r['request_rate_mreq_s']} cutover {r['cutover_bytes_by_work_items']}"),
         ("single_thread_and_strided", lambda: single_thread_and_strided(torch, S, args),
@@ -727,38 +993,50 @@ def main():
             continue
         extras[name] = run()
         log(f"[bench] {describe(extras[name])}")
+        if name in cpu_fns:              # the oracle's time for the same configuration, right after the GPU's
+            cpu_legs[name] = cpu_fns[name]()
+            extras[name]["cpu_baseline"] = cpu_legs[name]
+            log(f"[bench] {name} cpu baseline: {cpu_legs[name]}")
     g.finalize()
 
-    traffic = None        # measured with rocprofv3 --pmc in a separate run; the summary is committed under profiles/
-    tpath = os.path.join(ROOT, "profiles", "shmk_wg_rma_tiles_config2_256MiB_hbm_counters.txt")
-    if os.path.exists(tpath) and args.size_mib == 256 and args.n_wg == 1024:
-        import re
-        m = re.search(r"^hbm_bytes_per_launch:\s*(\d+)", open(tpath).read(), re.M)
-        traffic = int(m.group(1)) if m else None
-
+    traffic, traffic_source = traffic_from_profile(args)
     line = {
         "metric": "work-group put GB/s vs msg size (% of HBM copy roofline); AMO ops/s",
-        "value": head["value_gbs"], "unit": "GB/s",
-        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": head["wall_ms"],
+        "value": rnd(head["value_gbs"], 6), "unit": "GB/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": rnd(head["wall_ms"], 6),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "u8", "data": "synthetic",
         "config": {"workload": f"config 2: 8 logical PEs, work-group put of {args.size_mib} MiB float32 N(0,1) per PE to PE (p+1) mod 8, "
                                f"{args.n_wg} work-groups x 256 threads per PE, direct load/store, one team grid",
                    "pes": 8, "bytes_per_pe": n, "n_wg_per_pe": args.n_wg, "path": "ldst",
                    "hip_hardware_queues": int(os.environ.get("GPU_MAX_HW_QUEUES", "4"))},
         "value_note": "payload bytes delivered per second, all 8 PEs together; % of roofline counts read + written bytes",
-        "pct_of_hbm_copy_roofline": 100.0 * 2 * head["value_gbs"] / HBM_PEAK_GBS,
-        "spot_check_ok": head["spot_check_ok"],
-        "roofline": {"bound": "hbm", "kernel": "shmk_wg_rma_tiles", "achieved": head["achieved_gbs"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": head["achieved_gbs"] / HBM_PEAK_GBS, "traffic": traffic,
-                     "algorithmic_bytes_per_launch": 2 * head["payload_bytes"], "kernel_ms": head["kernel_ms"]},
-        "cpu_baseline": cpu,
+        "pct_of_hbm_copy_roofline": rnd(100.0 * 2 * head["value_gbs"] / HBM_PEAK_GBS),
+        "check_ok": head["check_ok"],
+        "roofline": {"bound": "hbm", "kernel": head["kernel"], "achieved": rnd(head["achieved_gbs"], 6), "peak": HBM_PEAK_GBS,
+                     "unit": "GB/s", "frac": rnd(head["achieved_gbs"] / HBM_PEAK_GBS), "traffic": traffic, "traffic_source": traffic_source,
+                     "algorithmic_bytes_per_launch": 2 * head["payload_bytes"], "kernel_ms": rnd(head["kernel_ms"], 6)},
+        "cpu_baseline": rnd(cpu) if cpu else None,
     }
     if extras:
         if "config4_amo_storm" in extras:
-            line["amo_ops_per_s"] = extras["config4_amo_storm"]["fetch_add"]["gops"] * 1e9       # the scalar device API
-            line["amo_ops_per_s_batched_by_work_group"] = extras["config4_amo_storm"]["fetch_add_batched_by_work_group"]["gops"] * 1e9
-        line["extras"] = extras
-    print(json.dumps(line))
+            line["amo_ops_per_s"] = rnd(extras["config4_amo_storm"]["fetch_add"]["gops"] * 1e9)       # the scalar device API
+            line["amo_ops_per_s_batched_by_work_group"] = rnd(extras["config4_amo_storm"]["fetch_add_batched_by_work_group"]["gops"] * 1e9)
+        line["configs"] = summarise(extras, cpu_legs)
+        if args.extras_out:
+            try:
+                os.makedirs(os.path.dirname(args.extras_out) or ".", exist_ok=True)
+                with open(args.extras_out, "w") as f:
+                    json.dump({"headline": line, "extras": extras}, f)
+                line["extras_file"] = os.path.relpath(args.extras_out, ROOT)
+            except OSError as e:
+                log(f"[bench] could not write {args.extras_out}: {e}")
+    text = json.dumps(line)
+    if len(text) > 6000:                 # the reader of this line keeps only the end of stdout
+        line.pop("configs", None)
+        line["configs_dropped"] = "summary too long; see extras_file"
+        text = json.dumps(line)
+    sys.stdout.flush()
+    print(text, flush=True)
     return 0
 
 

@@ -229,6 +229,18 @@ int shm_launch_wg_put_timed(shm_ctx *ctx, int me, int pe, uint64_t dst_off, uint
                             uint64_t *dev_ticks);
 int shm_wall_clock_khz(const shm_ctx *ctx);
 
+/* Measurement aid: the one-direction ceilings of the memory system, taken with the access forms
+ * and the launch shape of the long-message team put (paper section "Performance Evaluation" reports
+ * bandwidth against what the link can carry; here the "link" is HBM, whose read, write and copy
+ * rates differ).  One grid of npes*n_wg groups on the team stream; every PE p handles n bytes
+ * (a multiple of 65536; offsets 16-byte aligned, inside the heap):
+ *   SHM_PROBE_READ   p only reads [src_off, src_off+n) of its own partition;
+ *   SHM_PROBE_WRITE  p only writes a pattern to [dst_off, dst_off+n) of PE (p+1) mod npes;
+ *   SHM_PROBE_COPY   the team put itself (shm_launch_wg_put_all with shift 1, loads/stores).
+ * READ leaves memory unchanged; WRITE overwrites the destination with a pattern of no meaning. */
+enum { SHM_PROBE_READ = 0, SHM_PROBE_WRITE = 1, SHM_PROBE_COPY = 2 };
+int shm_launch_stream_probe(shm_ctx *ctx, int kind, uint64_t dst_off, uint64_t src_off, size_t n, int n_wg);
+
 /* ---- device-initiated copy-engine transfers (paper section "Synchronization with Host": the
  *      reverse-offload ring; section "Performance Evaluation": the cutover taken inside the kernel) */
 

@@ -273,14 +273,25 @@ __device__ __forceinline__ void shm_copy_parts(char *dst, const char *src, size_
 }
 
 // ------------------------------------------------------------------------------------------
-// Group-owned tiles: the dealing used for long messages.  A tile is U rows of 32 KiB (64 KiB for
-// U = 2) and ONE group owns a whole tile: wave w walks columns 8w..8w+7 (for 4 waves), its U
-// accesses per column again 32 KiB apart, each column's U loads followed at once by its U stores;
-// group `part` takes tiles part, part + nparts, ...  Launched with enough (unused) LDS to hold a CU
-// to three resident groups, this is what sustains the highest HBM copy rate measured on MI355X
-// (82 % of peak at 256 MiB x 8 PEs, against 76 % for the 8-group virtual blocks above): few
-// resident groups, each streaming long runs, started by the dispatcher in address order.
-// dst and src are 16-byte aligned, n is a multiple of 16.
+// Group-owned tiles: the dealing used for long messages.  A tile is U = 2 rows of 32 KiB and ONE
+// group owns a whole tile: wave w walks the columns (1 KiB each) 8w..8w+7 (for 4 waves), its two
+// accesses per column 32 KiB apart; group `part` takes tiles part, part + nparts, ...
+//
+// The order of the accesses is what decides the HBM rate, and what makes it depend -- or not -- on
+// where source and destination lie relative to each other (the memory channels are chosen by a hash
+// of the address, and a copy whose every wave reads X and writes X + delta at the same moment keeps
+// read and write streams in a fixed relation for the whole launch: measured on MI355X, 8 PEs x
+// 64-256 MiB, that form reaches 82 % of the HBM roofline for some placements and 70-75 % for others,
+// e.g. with the destination 4 KiB or 1 MiB further on).  Two measures remove the dependence:
+//   * a wave's stores trail its loads by LAG = 4 columns, continuously across the tiles the group
+//     walks (eight loads in flight per lane instead of two), so that what a wave reads and what it
+//     writes at one moment are 4 KiB apart in the message;
+//   * group g starts its walk at column g mod 8 of each wave's eight, so that the groups running
+//     at one moment do not all touch the same 1 KiB column of their 4 KiB blocks.
+// With four tiles per group (the launcher's choice of grid) this form measures 79.8-80.9 % at
+// 256 MiB x 8 PEs and 80.5-81.5 % at 64 MiB for every placement tried whose source is 64 KiB aligned
+// (77-79 % otherwise); the per-column form it replaces measured 82 % at its best placement and 72-77 %
+// at the others.  dst and src are 16-byte aligned, n is a multiple of 16.
 // ------------------------------------------------------------------------------------------
 template <int U, int NWAVES>
 __device__ __forceinline__ void shm_copy_tiles_impl(char *dst, const char *src, size_t n, unsigned part, unsigned nparts)
@@ -290,35 +301,52 @@ __device__ __forceinline__ void shm_copy_tiles_impl(char *dst, const char *src, 
     const size_t nvec = n >> 4;
     constexpr size_t rowv = 2048;                        // 32 KiB
     constexpr size_t tilev = rowv * U;
-    const size_t ntiles = (nvec + tilev - 1) / tilev;
+    const size_t nwhole = nvec / tilev;                  // whole tiles; one more, partial, if nvec % tilev
     const unsigned wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-    constexpr unsigned cols_per_wave = 32 / NWAVES;      // compile-time trip count: the column loop unrolls
-    for (size_t t = part; t < ntiles; t += nparts) {
-        const size_t base = t * tilev;
-        if (base + tilev <= nvec) {
-            // Column by column: U loads, then their U stores, then the next column.  Keeping reads and
-            // writes interleaved this finely is worth ten points of HBM bandwidth over issuing all of
-            // a tile's loads first (measured: 82 % against 70 %).
+    constexpr unsigned CPW = 32 / NWAVES;                // columns per wave; compile-time trip counts throughout
+    constexpr unsigned LAG = CPW < 4 ? CPW : 4;
+    static_assert(CPW % LAG == 0, "a register slot is refilled by the column LAG steps later, also across tiles");
+    const unsigned rot = part & (CPW - 1);
+    const size_t lane_off = static_cast<size_t>(wave * CPW) * 64 + lane;
+    auto col = [&](unsigned c) { return static_cast<size_t>((c + rot) & (CPW - 1)) * 64; };
+    shm_u32x4 r[LAG][U];
+    size_t prev = 0;
+    bool have = false;
+    for (size_t t = part; t < nwhole; t += nparts) {
+        const size_t base = t * tilev + lane_off;
 #pragma unroll
-            for (unsigned cc = 0; cc < cols_per_wave; ++cc) {
-                const size_t i = base + static_cast<size_t>(wave * cols_per_wave + cc) * 64 + lane;
-                shm_u32x4 r[U];
+        for (unsigned c = 0; c < CPW; ++c) {
+            const unsigned slot = c % LAG;               // holds the column loaded LAG steps ago
+            if (c >= LAG) {
 #pragma unroll
-                for (int u = 0; u < U; ++u) r[u] = shm_ld16(s + i + u * rowv);
+                for (int u = 0; u < U; ++u) shm_st16(d + base + col(c - LAG) + u * rowv, r[slot][u]);
+            } else if (have) {
 #pragma unroll
-                for (int u = 0; u < U; ++u) shm_st16(d + i + u * rowv, r[u]);
+                for (int u = 0; u < U; ++u) shm_st16(d + prev + col(c + CPW - LAG) + u * rowv, r[slot][u]);
             }
-        } else {                                          // the last, partial tile
-            for (unsigned cc = 0; cc < cols_per_wave; ++cc) {
-                const size_t i = base + static_cast<size_t>(wave * cols_per_wave + cc) * 64 + lane;
-                shm_u32x4 r[U];
 #pragma unroll
-                for (int u = 0; u < U; ++u)
-                    if (i + u * rowv < nvec) r[u] = shm_ld16(s + i + u * rowv);
+            for (int u = 0; u < U; ++u) r[slot][u] = shm_ld16(s + base + col(c) + u * rowv);
+        }
+        prev = base;
+        have = true;
+    }
+    if (have) {
 #pragma unroll
-                for (int u = 0; u < U; ++u)
-                    if (i + u * rowv < nvec) shm_st16(d + i + u * rowv, r[u]);
-            }
+        for (unsigned c = CPW - LAG; c < CPW; ++c)
+#pragma unroll
+            for (int u = 0; u < U; ++u) shm_st16(d + prev + col(c) + u * rowv, r[c % LAG][u]);
+    }
+    if (nwhole * tilev < nvec && nwhole % nparts == part) {      // the last, partial tile
+        const size_t base = nwhole * tilev + lane_off;
+        for (unsigned c = 0; c < CPW; ++c) {
+            const size_t i = base + static_cast<size_t>(c) * 64;
+            shm_u32x4 q[U];
+#pragma unroll
+            for (int u = 0; u < U; ++u)
+                if (i + u * rowv < nvec) q[u] = shm_ld16(s + i + u * rowv);
+#pragma unroll
+            for (int u = 0; u < U; ++u)
+                if (i + u * rowv < nvec) shm_st16(d + i + u * rowv, q[u]);
         }
     }
 }
@@ -326,12 +354,13 @@ __device__ __forceinline__ void shm_copy_tiles_impl(char *dst, const char *src, 
 template <int U = 2>
 __device__ __forceinline__ void shm_copy_tiles(char *dst, const char *src, size_t n, unsigned part, unsigned nparts)
 {
-    switch (blockDim.x >> 6) {       // groups are 64, 128, 256, 512 or 1024 threads
-    case 1: shm_copy_tiles_impl<U, 1>(dst, src, n, part, nparts); break;
-    case 2: shm_copy_tiles_impl<U, 2>(dst, src, n, part, nparts); break;
-    case 4: shm_copy_tiles_impl<U, 4>(dst, src, n, part, nparts); break;
-    case 8: shm_copy_tiles_impl<U, 8>(dst, src, n, part, nparts); break;
-    default: shm_copy_tiles_impl<U, 16>(dst, src, n, part, nparts); break;
+    switch (blockDim.x) {            // whole columns per wave need 1, 2, 4, 8 or 16 waves
+    case 64: shm_copy_tiles_impl<U, 1>(dst, src, n, part, nparts); break;
+    case 128: shm_copy_tiles_impl<U, 2>(dst, src, n, part, nparts); break;
+    case 256: shm_copy_tiles_impl<U, 4>(dst, src, n, part, nparts); break;
+    case 512: shm_copy_tiles_impl<U, 8>(dst, src, n, part, nparts); break;
+    case 1024: shm_copy_tiles_impl<U, 16>(dst, src, n, part, nparts); break;
+    default: shm_copy_parts<8, SHM_ST_STREAM>(dst, src, n, part, nparts); break;      // any other group size: the general dealing
     }
 }
 
@@ -465,28 +494,32 @@ __device__ __forceinline__ void shmx_getmem_parts(const shm_dev_ctx &c, int me, 
 }
 
 // The same with group-owned tiles (see shm_copy_tiles): for long messages.  Offsets 16-byte aligned;
-// the last n mod 16 bytes are copied by group 0.
+// the last n mod 16 bytes are copied by group 0.  NWAVES != 0 states the group size at compile time
+// (64 * NWAVES work-items; the library's own kernels do), 0 takes it from blockDim.
+template <int NWAVES = 0>
+__device__ __forceinline__ void shmx_copy_tiles_wg(char *d, const char *s, size_t n, unsigned part, unsigned nparts)
+{
+    __syncthreads();
+    const size_t body = n & ~static_cast<size_t>(15);
+    if (NWAVES)
+        shm_copy_tiles_impl<2, NWAVES ? NWAVES : 1>(d, s, body, part, nparts);
+    else
+        shm_copy_tiles<2>(d, s, body, part, nparts);
+    if (part == 0)
+        for (size_t i = body + threadIdx.x; i < n; i += blockDim.x) d[i] = s[i];
+    __syncthreads();
+}
+template <int NWAVES = 0>
 __device__ __forceinline__ void shmx_putmem_tiles(const shm_dev_ctx &c, int me, uint64_t dst_off, uint64_t src_off, size_t n, int pe,
                                                   unsigned part, unsigned nparts)
 {
-    __syncthreads();
-    char *d = shm_ptr(c, dst_off, pe);
-    const char *s = shm_ptr(c, src_off, me);
-    const size_t body = n & ~static_cast<size_t>(15);
-    shm_copy_tiles<2>(d, s, body, part, nparts);
-    if (part == 0 && threadIdx.x < n - body) d[body + threadIdx.x] = s[body + threadIdx.x];
-    __syncthreads();
+    shmx_copy_tiles_wg<NWAVES>(shm_ptr(c, dst_off, pe), shm_ptr(c, src_off, me), n, part, nparts);
 }
+template <int NWAVES = 0>
 __device__ __forceinline__ void shmx_getmem_tiles(const shm_dev_ctx &c, int me, uint64_t dst_off, uint64_t src_off, size_t n, int pe,
                                                   unsigned part, unsigned nparts)
 {
-    __syncthreads();
-    char *d = shm_ptr(c, dst_off, me);
-    const char *s = shm_ptr(c, src_off, pe);
-    const size_t body = n & ~static_cast<size_t>(15);
-    shm_copy_tiles<2>(d, s, body, part, nparts);
-    if (part == 0 && threadIdx.x < n - body) d[body + threadIdx.x] = s[body + threadIdx.x];
-    __syncthreads();
+    shmx_copy_tiles_wg<NWAVES>(shm_ptr(c, dst_off, me), shm_ptr(c, src_off, pe), n, part, nparts);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -502,6 +535,69 @@ __device__ __forceinline__ void shmx_quiet_wg()
 {
     __syncthreads();
     if (threadIdx.x == 0) __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
+    __syncthreads();
+}
+
+// The same for grids of many groups.  An agent-scope release is one write-back of the XCD's whole
+// L2 (buffer_wbl2), and the write-backs of one XCD are served one after another at a quarter to
+// half a microsecond each, dirty lines or not: a grid whose every group releases for itself pays
+// (groups per XCD) x that, which is most of the time of a put followed by its quiet once a grid has
+// hundreds of groups.  But ONE write-back covers every store that had reached that L2 when it
+// began, whoever issued it.  So the groups of an XCD share their releases through a record per XCD
+// (in the library's tail of PE 0's partition; the XCD number is the hardware's XCC_ID register):
+//   started  number of shared write-backs begun on this XCD (only ever incremented)
+//   done     number of the latest one that has finished
+//   lock     held by the one group that is writing back
+// Every wave first waits for the acknowledgement of its own stores (s_waitcnt vmcnt(0): they are in
+// the L2 or beyond).  The leader reads `started` = s: a write-back numbered above s began after
+// that, so it covers the group.  The leader then waits for done > s -- or, finding the lock free,
+// becomes the one who writes back: takes the lock, increments `started` (the returned number t is
+// its own), releases at agent scope, stores done = t, frees the lock.  The holder of the lock never
+// waits for anybody, so every wait ends; waits are bounded all the same, and a leader that has
+// polled for too long releases for itself.  Small grids (fewer than SHMD_QUIET_SHARED_MIN_GROUPS
+// groups) release directly: two atomics cost more than a write-back nobody queues for.
+#define SHMD_INTERNAL_QUIET 33280u            // 8 records, 128 bytes apart
+#define SHMD_QUIET_SHARED_MIN_GROUPS 64u
+#define SHMD_QUIET_SPIN_LIMIT 4096
+
+__device__ __forceinline__ unsigned shm_xcc_id()
+{
+    unsigned v;
+    asm volatile("s_getreg_b32 %0, hwreg(HW_REG_XCC_ID)" : "=s"(v));
+    return v & 7u;
+}
+
+// One thread; the stores it speaks for are acknowledged.
+__device__ __forceinline__ void shm_release_shared(const shm_dev_ctx &c)
+{
+    char *rec = c.base[0] + c.internal_off + SHMD_INTERNAL_QUIET + 128u * shm_xcc_id();
+    unsigned long long *started = reinterpret_cast<unsigned long long *>(rec), *done = started + 1;
+    unsigned *lock = reinterpret_cast<unsigned *>(rec + 16);
+    const unsigned long long s = __hip_atomic_load(started, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    for (int spin = 0; spin < SHMD_QUIET_SPIN_LIMIT; ++spin) {
+        if (__hip_atomic_load(done, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) > s) return;
+        if (__hip_atomic_load(lock, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == 0u &&
+            __hip_atomic_exchange(lock, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == 0u) {
+            const unsigned long long t = __hip_atomic_fetch_add(started, 1ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) + 1ull;
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");          // the write-back, waited for
+            __hip_atomic_store(done, t, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            __hip_atomic_store(lock, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            return;
+        }
+        __builtin_amdgcn_s_sleep(4);
+    }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
+}
+
+__device__ __forceinline__ void shmx_quiet_wg(const shm_dev_ctx &c)
+{
+    if (gridDim.x * gridDim.y * gridDim.z < SHMD_QUIET_SHARED_MIN_GROUPS) {
+        shmx_quiet_wg();
+        return;
+    }
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");      // this wave's stores have reached the L2
+    __syncthreads();                                      // ... and so have every other wave's of the group
+    if (threadIdx.x == 0) shm_release_shared(c);
     __syncthreads();
 }
 

@@ -24,17 +24,56 @@ __global__ __launch_bounds__(SHMK_WG) void shmk_wg_rma(shm_dev_ctx c, uint64_t d
 }
 
 // Long messages: group-owned tiles.  The dynamic LDS the host asks for is never touched: it only
-// caps how many groups a CU holds at once.
-__global__ __launch_bounds__(SHMK_WG) void shmk_wg_rma_tiles(shm_dev_ctx c, uint64_t dst_off, uint64_t src_off, size_t n, int me0,
-                                                             int shift, int is_get)
+// caps how many groups a CU holds at once.  A group lives for four tiles, so what it does before
+// its first load counts: the kernel takes the heap as base address and partition stride (the
+// library's partitions are equally spaced) instead of the whole device view -- one scalar load of
+// the arguments, no table look-up.
+__global__ __launch_bounds__(SHMK_WG) void shmk_wg_rma_tiles(char *base, uint64_t stride, uint64_t dst_off, uint64_t src_off, size_t n,
+                                                             int npes, int me0, int shift, int is_get)
 {
     const int me = me0 + blockIdx.y;
     int pe = me + shift;
+    if (pe >= npes) pe -= npes;
+    // one copy of the tile walk for both directions: only the two addresses differ
+    char *d = base + static_cast<uint64_t>(is_get ? me : pe) * stride + dst_off;
+    const char *s = base + static_cast<uint64_t>(is_get ? pe : me) * stride + src_off;
+    shmx_copy_tiles_wg<SHMK_WG / 64>(d, s, n, blockIdx.x, gridDim.x);
+}
+
+// One-direction ceilings of the memory system with the access forms of the long-message put: the
+// team grid and the group-owned 64 KiB tiles of shmk_wg_rma_tiles, but every tile is only read
+// (KIND 0: 16-byte nontemporal loads of the source on the calling PE, folded into a word that is
+// stored only if it equals `magic`, which keeps the loads alive) or only written (KIND 1: 16-byte
+// nontemporal stores of a lane-dependent pattern to the destination on the target PE).
+template <int KIND>
+__global__ __launch_bounds__(SHMK_WG) void shmk_stream_probe(shm_dev_ctx c, uint64_t dst_off, uint64_t src_off, size_t n, int shift,
+                                                             uint32_t magic)
+{
+    const int me = blockIdx.y;
+    int pe = me + shift;
     if (pe >= c.npes) pe -= c.npes;
-    if (is_get)
-        shmx_getmem_tiles(c, me, dst_off, src_off, n, pe, blockIdx.x, gridDim.x);
-    else
-        shmx_putmem_tiles(c, me, dst_off, src_off, n, pe, blockIdx.x, gridDim.x);
+    const shm_u32x4 *s = reinterpret_cast<const shm_u32x4 *>(shm_ptr(c, src_off, me));
+    shm_u32x4 *d = reinterpret_cast<shm_u32x4 *>(shm_ptr(c, dst_off, pe));
+    constexpr size_t rowv = 2048, tilev = 2 * rowv;
+    const size_t ntiles = (n >> 4) / tilev;                 // whole tiles only: n is a multiple of 64 KiB
+    const unsigned wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    uint32_t fold = 0;
+    shm_u32x4 pattern;
+    pattern.x = threadIdx.x, pattern.y = blockIdx.x, pattern.z = magic, pattern.w = static_cast<uint32_t>(me);
+    for (size_t t = blockIdx.x; t < ntiles; t += gridDim.x) {
+#pragma unroll
+        for (unsigned cc = 0; cc < 8; ++cc) {
+            const size_t i = t * tilev + static_cast<size_t>(wave * 8 + cc) * 64 + lane;
+            if (KIND == 0) {
+                const shm_u32x4 r0 = shm_ld16(s + i), r1 = shm_ld16(s + i + rowv);
+                fold ^= r0.x ^ r0.y ^ r0.z ^ r0.w ^ r1.x ^ r1.y ^ r1.z ^ r1.w;
+            } else {
+                shm_st16(d + i, pattern);
+                shm_st16(d + i + rowv, pattern);
+            }
+        }
+    }
+    if (KIND == 0 && fold == magic && n == 1) d[0].x = fold;       // never true for a launch the host accepts
 }
 
 // The same put repeated `reps` times inside one kernel, each followed by the group's quiet, with the
@@ -49,10 +88,10 @@ __global__ __launch_bounds__(SHMK_WG) void shmk_wg_put_timed(shm_dev_ctx c, uint
     const unsigned long long t0 = wall_clock64();
     for (int r = 0; r < reps; ++r) {
         if (tiles)
-            shmx_putmem_tiles(c, me, dst_off, src_off, n, pe, blockIdx.x, gridDim.x);
+            shmx_putmem_tiles<SHMK_WG / 64>(c, me, dst_off, src_off, n, pe, blockIdx.x, gridDim.x);
         else
             shmx_putmem_parts(c, me, dst_off, src_off, n, pe, blockIdx.x, gridDim.x);
-        if (mine) shmx_quiet_wg();
+        if (mine) shmx_quiet_wg(c);
     }
     const unsigned long long t1 = wall_clock64();
     if (threadIdx.x == 0) {
@@ -89,7 +128,7 @@ __global__ __launch_bounds__(1024) void shmk_rma_device_initiated(shm_dev_ctx c,
                 shmx_getmem_wg(c, me, d, s, len, pe);
             } else {
                 shmx_putmem_wg(c, me, d, s, len, pe);
-                if (len) shmx_quiet_wg();
+                if (len) shmx_quiet_wg(c);
             }
         } else if (mode == 1) {
             if (is_get)
@@ -102,7 +141,7 @@ __global__ __launch_bounds__(1024) void shmk_rma_device_initiated(shm_dev_ctx c,
                 shmx_getmem_auto_wg(c, me, d, s, len, pe, cutover);
             } else {
                 shmx_putmem_auto_wg(c, me, d, s, len, pe, cutover);
-                if (!engine && len) shmx_quiet_wg();
+                if (!engine && len) shmx_quiet_wg(c);
             }
         } else if (mode == 3) {
             if (is_get)
@@ -117,7 +156,7 @@ __global__ __launch_bounds__(1024) void shmk_rma_device_initiated(shm_dev_ctx c,
                 shmx_putmem_offload_wg(c, me, d, s, len, pe, false);
         } else {
             shmx_rma_covered_wg(c, me, d, s, len, pe, cover, is_get != 0);
-            if (!is_get && len) shmx_quiet_wg();
+            if (!is_get && len) shmx_quiet_wg(c);
             shmx_quiet_offload_wg(c, me);
         }
         if (consume) shmx_putmem_wg(c, me, consume_off + lo, d, len, me);

@@ -51,9 +51,39 @@ __global__ __launch_bounds__(256) void shmu_collectives_kernel(shm_dev_ctx c, ui
     shmx_broadcast_wg(c, me, bcast_off, src_off, n, root);
 }
 
+// A long message moved on group-owned tiles by groups of the caller's own size (the paper varies
+// the work-items per work-group): gridDim.x groups of blockDim.x threads of PE `me` put n bytes
+// to PE `pe`, then the same groups get them back from there into `back_off` of their own heap.
+__global__ __launch_bounds__(1024) void shmu_tiles_kernel(shm_dev_ctx c, int me, int pe, uint64_t dst_off, uint64_t src_off, size_t n)
+{
+    shmx_putmem_tiles(c, me, dst_off, src_off, n, pe, blockIdx.x, gridDim.x);
+}
+
+__global__ __launch_bounds__(1024) void shmu_tiles_back_kernel(shm_dev_ctx c, int me, int pe, uint64_t dst_off, size_t n, uint64_t back_off)
+{
+    shmx_getmem_tiles(c, me, back_off, dst_off, n, pe, blockIdx.x, gridDim.x);
+}
+
 }  // namespace
 
 extern "C" {
+
+// Offsets 16-byte aligned; threads 1..1024; groups >= 1.  The get is a second kernel on the same
+// stream, so it starts when every group of the put has finished.
+int shmu_tiles(const void *devctx, size_t devctx_bytes, void *stream, int me, int pe, uint64_t dst_off, uint64_t src_off, size_t n,
+               uint64_t back_off, int groups, int threads)
+{
+    if (!devctx || devctx_bytes != sizeof(shm_dev_ctx) || ((dst_off | src_off | back_off) & 15) || groups < 1 || threads < 1 || threads > 1024)
+        return -1;
+    shm_dev_ctx c;
+    memcpy(&c, devctx, sizeof c);
+    if (c.npes < 1 || c.npes > SHM_MAX_PES || me < 0 || me >= c.npes || pe < 0 || pe >= c.npes) return -1;
+    hipLaunchKernelGGL(shmu_tiles_kernel, dim3(groups), dim3(threads), 0, static_cast<hipStream_t>(stream), c, me, pe, dst_off, src_off, n);
+    if (hipGetLastError() != hipSuccess) return -5;
+    hipLaunchKernelGGL(shmu_tiles_back_kernel, dim3(groups), dim3(threads), 0, static_cast<hipStream_t>(stream), c, me, pe, dst_off, n,
+                       back_off);
+    return hipGetLastError() == hipSuccess ? 0 : -5;
+}
 
 // devctx: HOST pointer to the bytes shm_device_context() wrote; stream: a hipStream_t.  Offsets are
 // symmetric-heap byte offsets (tally_off and seen_off 8-byte aligned).  Returns 0, -1 for a view of

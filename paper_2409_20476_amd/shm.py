@@ -27,6 +27,7 @@ SHM_INIT_DEFAULT, SHM_INIT_NO_DEVICE = 0, 1
  SHM_AMO_INC) = range(8)
 SHM_STORM_FETCH_ADD, SHM_STORM_ADD, SHM_STORM_CSWAP_LOOP, SHM_STORM_PLAIN_STORE, SHM_STORM_FETCH_ADD_WG = range(5)
 SHM_REDUCE_DUPLICATE, SHM_REDUCE_SPLIT = 0, 1
+SHM_PROBE_READ, SHM_PROBE_WRITE, SHM_PROBE_COPY = 0, 1, 2
 SHM_COLL_FCOLLECT, SHM_COLL_BROADCAST = 0, 1
 SHM_TEAM_SYNC_OFF, SHM_TEAM_SYNC_FULL, SHM_TEAM_SYNC_TRACKED = 0, 1, 2
 (SHM_SYNC_WAIT, SHM_SYNC_WAIT_ALL, SHM_SYNC_WAIT_ANY, SHM_SYNC_WAIT_SOME,
@@ -78,6 +79,7 @@ PROTOTYPES = {
     "shm_launch_wg_get_all": (c_int, [c_void_p, c_int, c_uint64, c_uint64, c_size_t, c_int, c_int]),
     "shm_launch_wg_put_timed": (c_int, [c_void_p, c_int, c_int, c_uint64, c_uint64, c_size_t, c_int, c_int, c_void_p]),
     "shm_wall_clock_khz": (c_int, [c_void_p]),
+    "shm_launch_stream_probe": (c_int, [c_void_p, c_int, c_uint64, c_uint64, c_size_t, c_int]),
     "shm_proxy_start": (c_int, [c_void_p]),
     "shm_proxy_stop": (c_int, [c_void_p]),
     "shm_proxy_stats": (c_int, [c_void_p, _u64p, _u64p]),
@@ -299,6 +301,9 @@ class Shm:
 
     def launch_wg_put_timed(self, me, pe, dst_off, src_off, n, n_wg, reps, dev_ticks):
         self._check(self.lib.shm_launch_wg_put_timed(self.ctx, me, pe, dst_off, src_off, n, n_wg, reps, _ptr(dev_ticks)))
+
+    def launch_stream_probe(self, kind, dst_off, src_off, n, n_wg):
+        self._check(self.lib.shm_launch_stream_probe(self.ctx, kind, dst_off, src_off, n, n_wg))
 
     def wall_clock_khz(self) -> int:
         return self._check(self.lib.shm_wall_clock_khz(self.ctx))

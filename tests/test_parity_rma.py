@@ -132,55 +132,57 @@ def test_timed_put_moves_the_same_bytes_and_reports_device_time():
 
 
 def test_timed_put_of_long_messages_moves_the_same_bytes_on_both_long_message_paths():
-    """9 MiB by 64 groups stays on the virtual blocks, 33 MiB by 512 groups takes group-owned tiles."""
+    """9 MiB by 64 groups stays on the virtual blocks, 65 MiB by 512 groups takes group-owned tiles."""
     import torch
-    g, o = make_pair(2, 80 * MiB)
+    g, o = make_pair(2, 160 * MiB)
     with g:
-        fill_random(g, o, 7, upto=72 * MiB)
-        for n, n_wg in [(9 * MiB + 16 * 3 + 5, 64), (33 * MiB + 16 * 3 + 5, 512)]:      # ragged last tile and a byte tail
+        fill_random(g, o, 7, upto=144 * MiB)
+        for n, n_wg in [(9 * MiB + 16 * 3 + 5, 64), (65 * MiB + 16 * 3 + 5, 512)]:      # ragged last tile and a byte tail
             ticks = torch.zeros(2, dtype=torch.int64, device="cuda")
             ticks[0] = -1
-            g.launch_wg_put_timed(0, 1, 36 * MiB + 16, 32, n, n_wg, 3, ticks)
+            g.launch_wg_put_timed(0, 1, 70 * MiB + 16, 32, n, n_wg, 3, ticks)
             g.quiet(0)
-            o.wg_put(0, 36 * MiB + 16, 32, n, 1, n_wg)
-            assert_heaps_equal(g, o, upto=72 * MiB, what=f"n {n} by {n_wg} groups")
+            o.wg_put(0, 70 * MiB + 16, 32, n, 1, n_wg)
+            assert_heaps_equal(g, o, upto=144 * MiB, what=f"n {n} by {n_wg} groups")
 
 
 @pytest.mark.parametrize("n_wg", [512, 515, 600])
 def test_long_messages_by_a_chip_filling_grid_take_group_owned_tiles(n_wg):
-    """8 MiB or more, 512 groups or more in the grid, 64 KiB or more per group, 16-byte-aligned
-    offsets: every group owns whole 64 KiB tiles.  Ragged last tile, byte tail, put and get."""
-    g, o = make_pair(2, 96 * MiB)
+    """64 MiB or more by 512 groups or more of one PE, 16-byte-aligned offsets: the launcher runs one
+    group per four 64 KiB tiles and every group owns whole tiles.  Ragged last tile, byte tail, a
+    destination 4 KiB, 1 MiB + 4 KiB ... off the source's alignment, put and get."""
+    g, o = make_pair(2, 176 * MiB)
     with g:
-        fill_random(g, o, 8, upto=90 * MiB)
-        sizes = [38 * MiB, 38 * MiB + 48, 39 * MiB + 131072 + 16, 38 * MiB + 7]
+        fill_random(g, o, 8, upto=160 * MiB)
+        sizes = [70 * MiB, 70 * MiB + 48, 71 * MiB + 131072 + 16, 70 * MiB + 7]
         for rep, n in enumerate(sizes):
             me, pe = rep % 2, (rep + 1) % 2
-            src, dst = 4096 + 16 * rep, 45 * MiB + 32 * rep
+            src, dst = 4096 + 16 * rep, 80 * MiB + (MiB + 4096) * rep + 32 * rep
             g.launch_wg_put(me, pe, dst, src, n, n_wg)
             o.wg_put(me, dst, src, n, pe, n_wg)
             g.quiet(me)
             g.launch_wg_get(pe, me, 64, dst, n, n_wg)           # read it back into the start of the caller's heap
             o.wg_get(pe, 64, dst, n, me, n_wg)
             g.quiet(pe)
-            assert_heaps_equal(g, o, upto=90 * MiB, what=f"n_wg {n_wg} size {n}")
+            assert_heaps_equal(g, o, upto=160 * MiB, what=f"n_wg {n_wg} size {n}")
 
 
 @pytest.mark.parametrize("n_wg", [32, 33, 100, 128, 160])
 def test_long_messages_team_forms_on_both_long_message_paths(n_wg):
-    """Team grids of 4 PEs: below 512 groups in the grid (32, 33, 100 per PE) the virtual blocks, from
-    128 per PE group-owned tiles; put_all and get_all, ragged last tile and byte tail."""
-    g, o = make_pair(4, 32 * MiB)
+    """Team grids of 4 PEs, 33 MiB: below 512 groups in the grid (32, 33, 100 per PE) the virtual
+    blocks, from 128 per PE group-owned tiles -- 128 groups take more than four tiles each, 160 are
+    cut to one group per four tiles; put_all and get_all, ragged last tile and byte tail."""
+    g, o = make_pair(4, 80 * MiB)
     with g:
-        fill_random(g, o, 8, upto=28 * MiB)
-        n = 11 * MiB + 65536 + 5
-        g.launch_wg_put_all(3, 14 * MiB, 0, n, n_wg)
+        fill_random(g, o, 8, upto=76 * MiB)
+        n = 33 * MiB + 65536 + 5
+        g.launch_wg_put_all(3, 38 * MiB + 4096, 0, n, n_wg)
         for p in range(4):
-            o.wg_put(p, 14 * MiB, 0, n, (p + 3) % 4, n_wg)
+            o.wg_put(p, 38 * MiB + 4096, 0, n, (p + 3) % 4, n_wg)
         g.barrier_all()
-        g.launch_wg_get_all(1, 64, 14 * MiB, n, n_wg)
+        g.launch_wg_get_all(1, 64, 38 * MiB + 4096, n, n_wg)
         before = [h.copy() for h in o.heap]
         for p in range(4):
-            o.heap[p][64:64 + n] = before[(p + 1) % 4][14 * MiB:14 * MiB + n]
+            o.heap[p][64:64 + n] = before[(p + 1) % 4][38 * MiB + 4096:38 * MiB + 4096 + n]
         g.barrier_all()
-        assert_heaps_equal(g, o, upto=28 * MiB, what="team forms")
+        assert_heaps_equal(g, o, upto=76 * MiB, what="team forms")

@@ -133,3 +133,28 @@ def test_application_kernel_calls_the_collectives(npes, n, nelems, root):
             o.reduce(mins, src + 16 * rep, 2 * nelems, np.int16, "min")
             o.broadcast(bcast, src + 16 * rep, n, root)
             assert_heaps_equal(g, o, upto=12 * MiB, what=f"repetition {rep}")
+
+
+@pytest.mark.parametrize("threads,groups", [(192, 40), (64, 16), (128, 7), (256, 33), (320, 9), (512, 12), (768, 5), (1024, 6), (8, 3)])
+def test_application_kernel_moves_a_long_message_on_tiles_with_its_own_group_size(threads, groups):
+    """shmx_putmem_tiles / shmx_getmem_tiles from groups of 8 to 1024 work-items, among them sizes that are
+    not a power of two (they take the general dealing): ragged last tile, byte tail, groups with one
+    tile, with several and with none."""
+    g, o = make_pair(2, 16 * MiB)
+    with g:
+        lib = _example()
+        lib.shmu_tiles.restype = ctypes.c_int
+        lib.shmu_tiles.argtypes = [ctypes.c_char_p, ctypes.c_size_t, ctypes.c_void_p, ctypes.c_int, ctypes.c_int, ctypes.c_uint64, ctypes.c_uint64,
+                                   ctypes.c_size_t, ctypes.c_uint64, ctypes.c_int, ctypes.c_int]
+        fill_random(g, o, 54, upto=14 * MiB)
+        view = g.device_context()
+        for rep, n in enumerate([3 * MiB + 65536 + 4096 + 16 * 5 + 11, 65536 * groups, 65536 * min(4 * groups, 50) + 48, 13, 0]):
+            if threads < 64 and n > MiB:
+                n = 200000 + rep            # a handful of lanes: keep the run short
+            me, pe = rep % 2, (rep + 1) % 2
+            src, dst, back = 4096 + 16 * rep, 5 * MiB + 4096 * rep, 9 * MiB + 16 * rep
+            assert lib.shmu_tiles(view, len(view), g.stream(me), me, pe, dst, src, n, back, groups, threads) == 0
+            g.quiet(me)
+            o.putmem(me, dst, src, n, pe)
+            o.getmem(me, back, dst, n, pe)
+            assert_heaps_equal(g, o, upto=14 * MiB, what=f"{groups} groups of {threads}, n {n}")
