@@ -382,6 +382,21 @@ int shm_launch_pingflag(shm_ctx *ctx, uint64_t data_off, uint64_t back_off, size
 int shm_launch_ring_pipeline(shm_ctx *ctx, uint64_t src_off, uint64_t slot_off, uint64_t sig_off, uint64_t acc_off,
                              size_t chunk_bytes, int n_chunks, int n_wg_prod, int n_wg_cons, int n_sig);
 
+/* The same ring for callers that cannot allocate device memory or have the library do so on their
+ * behalf: code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  It
+ * allocates nothing and calls no allocating routine: the arrival counters of the chunks, which
+ * shm_launch_ring_pipeline keeps in the heap's library-owned tail, are taken from a static device
+ * array inside the library (32 PEs x SHM_STATIC_RING_MAX_CHUNKS counters of 8 bytes = 256 KiB,
+ * held by every GPU the library runs on until the process ends) and cleared by a small kernel
+ * before the ring starts.  n_chunks above SHM_STATIC_RING_MAX_CHUNKS is refused with SHM_EINVAL;
+ * everything else -- arguments, results, completion, errors -- is as for shm_launch_ring_pipeline.
+ * All calls on one GPU share the one array: two such calls that overlap in time on a GPU (from two
+ * contexts, or from streams the caller has not ordered) race on the counters and must be
+ * serialised by the caller. */
+#define SHM_STATIC_RING_MAX_CHUNKS 1024
+int shm_launch_ring_pipeline_static(shm_ctx *ctx, uint64_t src_off, uint64_t slot_off, uint64_t sig_off, uint64_t acc_off,
+                                    size_t chunk_bytes, int n_chunks, int n_wg_prod, int n_wg_cons, int n_sig);
+
 /* Benchmark configuration 4, one grid on the team stream.  Work-item g < n_items performs
  * ops_per_item atomics; its j-th target is dev_targets[g*ops_per_item + j] = pe*n_ctr + index,
  * i.e. the int64 counter at ctr_off + 8*index on that PE.  kind: FETCH_ADD(+1) | ADD(+1, no

@@ -7,6 +7,7 @@
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
+#include <mutex>
 #include <new>
 #include <string>
 
@@ -14,6 +15,13 @@
 #include "shm_heap.hpp"
 #include "shm_kernels.hpp"
 #include "shm_proxy.hpp"
+
+// Scratch memory of shm_launch_ring_pipeline_static, the entry point that allocates nothing: the
+// arrival counters of the ring (one per chunk and PE) live here instead of in the heap's tail.  Every
+// GPU the library runs on holds its own copy of the array until the process ends.  In host code the
+// name is only a handle for hipGetSymbolAddress: the device address it yields, kept per device, is
+// what kernels and clears are given.
+static __device__ __align__(256) unsigned long long scratch[SHM_MAX_PES * SHM_STATIC_RING_MAX_CHUNKS];
 
 namespace {
 
@@ -39,6 +47,10 @@ static_assert(SHM_OFFLOAD_SLOTS == SHMD_OFFLOAD_SLOTS && SHM_OFFLOAD_COMPLETIONS
                   SHM_OFFLOAD_NO_COMPLETION == SHMD_OFFLOAD_NONE, "host and device agree on the ring");
 
 thread_local std::string g_err = "";
+
+constexpr int MAX_DEVICES = 64;
+std::mutex g_scratch_mutex;
+unsigned long long *g_scratch_ptr[MAX_DEVICES] = {};          // device address of `scratch` on each device, once asked for
 
 int fail(int code, const char *fmt, ...)
 {
@@ -1189,10 +1201,34 @@ int shm_launch_pingflag(shm_ctx *c, uint64_t data_off, uint64_t back_off, size_t
     return launched("ping consumer");
 }
 
-int shm_launch_ring_pipeline(shm_ctx *c, uint64_t src_off, uint64_t slot_off, uint64_t sig_off, uint64_t acc_off, size_t chunk_bytes,
-                             int n_chunks, int n_wg_prod, int n_wg_cons, int n_sig)
+namespace {
+
+// Address of this device's copy of `scratch` (asked for once per device, with that device current).
+int static_scratch(unsigned long long **out)
+{
+    int dev = 0;
+    HIP_TRY(hipGetDevice(&dev));
+    if (dev < 0 || dev >= MAX_DEVICES) return fail(SHM_EHIP, "device %d is beyond the %d devices the library keeps scratch addresses for", dev, MAX_DEVICES);
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void *p = nullptr;
+        HIP_TRY(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+        if (!p) return fail(SHM_EHIP, "hipGetSymbolAddress returned no address for the scratch array");
+        g_scratch_ptr[dev] = static_cast<unsigned long long *>(p);
+    }
+    *out = g_scratch_ptr[dev];
+    return SHM_OK;
+}
+
+// static_counters: the arrival counters come from the library's static scratch array (and are cleared
+// by a kernel first) instead of from the heap's tail.
+int ring_pipeline(shm_ctx *c, uint64_t src_off, uint64_t slot_off, uint64_t sig_off, uint64_t acc_off, size_t chunk_bytes, int n_chunks,
+                  int n_wg_prod, int n_wg_cons, int n_sig, bool static_counters)
 {
     if (int r = check_ctx(c)) return r;
+    if (static_counters && n_chunks > SHM_STATIC_RING_MAX_CHUNKS)
+        return fail(SHM_EINVAL, "n_chunks %d exceeds the %d chunks the static scratch array has arrival counters for", n_chunks,
+                    SHM_STATIC_RING_MAX_CHUNKS);
     if (chunk_bytes == 0 || chunk_bytes % 16) return fail(SHM_EINVAL, "chunk_bytes must be a positive multiple of 16");
     if (n_chunks < 1 || static_cast<uint32_t>(n_chunks) > ARRIVE_SLOTS) return fail(SHM_EINVAL, "n_chunks outside 1..%u", ARRIVE_SLOTS);
     if (n_wg_prod < 1 || n_wg_cons < 1 || n_wg_prod > MAX_N_WG || n_wg_cons > MAX_N_WG)
@@ -1230,17 +1266,49 @@ int shm_launch_ring_pipeline(shm_ctx *c, uint64_t src_off, uint64_t slot_off, ui
         return fail(SHM_EINVAL, "%lld groups cannot all be resident (%d CUs x %d); consumers would wait on groups that never start",
                     groups, c->num_cu, per_cu);
     // one arrival counter per chunk, same slot range on every PE
-    uint32_t first = 0;
-    for (int p = 0; p < c->npes; ++p) c->next_slot[p] = 0;
-    for (int p = 0; p < c->npes; ++p) first = take_slots(c, p, n_chunks);
+    uint64_t *arrive_pe0 = nullptr;
+    uint64_t arrive_stride = 0;
+    unsigned long long *static_ptr = nullptr;
+    if (static_counters) {
+        if (int r = static_scratch(&static_ptr)) return r;
+        arrive_pe0 = reinterpret_cast<uint64_t *>(static_ptr);
+        arrive_stride = SHM_STATIC_RING_MAX_CHUNKS;
+    } else {
+        uint32_t first = 0;
+        for (int p = 0; p < c->npes; ++p) c->next_slot[p] = 0;
+        for (int p = 0; p < c->npes; ++p) first = take_slots(c, p, n_chunks);
+        arrive_pe0 = reinterpret_cast<uint64_t *>(c->base + c->user_bytes) + first;
+        arrive_stride = c->part_bytes / 8;
+    }
     if (c->team_sync)
         if (int r = team_join(c)) return r;
+    if (static_counters) {
+        // the array keeps what the last call left (a call that ran into a wait bound may have left counts): start from zero
+        const size_t words = static_cast<size_t>(c->npes) * SHM_STATIC_RING_MAX_CHUNKS;
+        hipLaunchKernelGGL(shmk_clear_words, dim3(static_cast<unsigned>((words + SHMK_WG - 1) / SHMK_WG)), dim3(SHMK_WG), 0, c->stream[0],
+                           static_ptr, words);
+        if (int r = launched("clearing the static arrival counters")) return r;
+    }
     hipLaunchKernelGGL(kernel, dim3(static_cast<unsigned>(groups)), dim3(SHMK_WG), 0, c->stream[0], dev_view(c), src_off, slot_off, sig_off,
-                       acc_off, chunk_bytes, n_chunks, n_wg_prod, n_wg_cons, c->user_bytes + 8ull * first);
+                       acc_off, chunk_bytes, n_chunks, n_wg_prod, n_wg_cons, arrive_pe0, arrive_stride);
     if (int r = launched("ring pipeline")) return r;
     if (c->team_sync)
         if (int r = team_fork(c)) return r;
     return SHM_OK;
+}
+
+}  // namespace
+
+int shm_launch_ring_pipeline(shm_ctx *c, uint64_t src_off, uint64_t slot_off, uint64_t sig_off, uint64_t acc_off, size_t chunk_bytes,
+                             int n_chunks, int n_wg_prod, int n_wg_cons, int n_sig)
+{
+    return ring_pipeline(c, src_off, slot_off, sig_off, acc_off, chunk_bytes, n_chunks, n_wg_prod, n_wg_cons, n_sig, false);
+}
+
+int shm_launch_ring_pipeline_static(shm_ctx *c, uint64_t src_off, uint64_t slot_off, uint64_t sig_off, uint64_t acc_off, size_t chunk_bytes,
+                                    int n_chunks, int n_wg_prod, int n_wg_cons, int n_sig)
+{
+    return ring_pipeline(c, src_off, slot_off, sig_off, acc_off, chunk_bytes, n_chunks, n_wg_prod, n_wg_cons, n_sig, true);
 }
 
 int shm_launch_amo_storm(shm_ctx *c, uint64_t ctr_off, int n_ctr, const uint16_t *dev_targets, uint64_t n_items, int ops_per_item,

@@ -359,8 +359,9 @@ __global__ __launch_bounds__(SHMK_WG) void shmk_wave_exchange(shm_dev_ctx c, uin
 template <int LANES>
 __global__ __launch_bounds__(SHMK_WG, 4) void shmk_ring(shm_dev_ctx c, uint64_t src_off, uint64_t slot_off, uint64_t sig_off,
                                                         uint64_t acc_off, size_t chunk_bytes, int n_chunks, int n_prod, int n_cons,
-                                                        uint64_t arrive_off)
+                                                        uint64_t *arrive_pe0, uint64_t arrive_pe_stride)
 {
+    // arrival counters, one per chunk: PE p's are at arrive_pe0 + p * arrive_pe_stride (in words)
     constexpr bool lanes = LANES != 0;
     const int npes = c.npes;
     const int b = blockIdx.x;
@@ -390,7 +391,7 @@ __global__ __launch_bounds__(SHMK_WG, 4) void shmk_ring(shm_dev_ctx c, uint64_t 
             const shm_u32x4 *s = reinterpret_cast<const shm_u32x4 *>(shm_ptr(c, src_off, me));
             shm_u32x4 *d = reinterpret_cast<shm_u32x4 *>(shm_ptr(c, slot_off, pe));
             uint64_t *sig = reinterpret_cast<uint64_t *>(shm_ptr(c, sig_off + (lanes ? 8ull * part : 0ull), pe));
-            uint64_t *arrive = reinterpret_cast<uint64_t *>(shm_ptr(c, arrive_off, me));
+            uint64_t *arrive = arrive_pe0 + static_cast<uint64_t>(me) * arrive_pe_stride;
             const bool any = hi > lo;
             const uint32_t last = any ? static_cast<uint32_t>(hi - 1 - lo) : 0;      // a share has at most 2048 vectors
             s += lo, d += lo;
@@ -425,7 +426,7 @@ __global__ __launch_bounds__(SHMK_WG, 4) void shmk_ring(shm_dev_ctx c, uint64_t 
             return;
         }
         // larger shares: one put_signal per chunk by all producer groups together
-        uint64_t *arrive = reinterpret_cast<uint64_t *>(shm_ptr(c, arrive_off, me));
+        uint64_t *arrive = arrive_pe0 + static_cast<uint64_t>(me) * arrive_pe_stride;
         for (int k = 0; k < n_chunks; ++k)
             shmx_putmem_signal_parts(c, me, slot_off + k * chunk_bytes, src_off + k * chunk_bytes, chunk_bytes, sig_off, 1,
                                      SHMD_SIGNAL_ADD, pe, arrive + k, part, n_prod);
@@ -492,6 +493,12 @@ __global__ __launch_bounds__(SHMK_WG, 4) void shmk_ring(shm_dev_ctx c, uint64_t 
             out[2 * v + 1] = bq;
         }
     }
+}
+
+// Clears n 64-bit words (a kernel, not a memset node: a caller may record the launch into a graph).
+__global__ __launch_bounds__(SHMK_WG) void shmk_clear_words(unsigned long long *p, size_t n)
+{
+    for (size_t i = static_cast<size_t>(blockIdx.x) * SHMK_WG + threadIdx.x; i < n; i += static_cast<size_t>(gridDim.x) * SHMK_WG) p[i] = 0;
 }
 
 // ---- configuration 4: atomic storm -----------------------------------------------------------

@@ -28,6 +28,7 @@ SHM_INIT_DEFAULT, SHM_INIT_NO_DEVICE = 0, 1
 SHM_STORM_FETCH_ADD, SHM_STORM_ADD, SHM_STORM_CSWAP_LOOP, SHM_STORM_PLAIN_STORE, SHM_STORM_FETCH_ADD_WG = range(5)
 SHM_REDUCE_DUPLICATE, SHM_REDUCE_SPLIT = 0, 1
 SHM_PROBE_READ, SHM_PROBE_WRITE, SHM_PROBE_COPY = 0, 1, 2
+SHM_STATIC_RING_MAX_CHUNKS = 1024
 SHM_COLL_FCOLLECT, SHM_COLL_BROADCAST = 0, 1
 SHM_TEAM_SYNC_OFF, SHM_TEAM_SYNC_FULL, SHM_TEAM_SYNC_TRACKED = 0, 1, 2
 (SHM_SYNC_WAIT, SHM_SYNC_WAIT_ALL, SHM_SYNC_WAIT_ANY, SHM_SYNC_WAIT_SOME,
@@ -98,6 +99,7 @@ PROTOTYPES = {
     "shm_launch_amo": (c_int, [c_void_p, c_int, c_int, c_uint64, c_int, c_int64, c_int64, c_void_p]),
     "shm_launch_pingflag": (c_int, [c_void_p, c_uint64, c_uint64, c_size_t, c_uint64]),
     "shm_launch_ring_pipeline": (c_int, [c_void_p, c_uint64, c_uint64, c_uint64, c_uint64, c_size_t, c_int, c_int, c_int, c_int]),
+    "shm_launch_ring_pipeline_static": (c_int, [c_void_p, c_uint64, c_uint64, c_uint64, c_uint64, c_size_t, c_int, c_int, c_int, c_int]),
     "shm_launch_amo_storm": (c_int, [c_void_p, c_uint64, c_int, c_void_p, c_uint64, c_int, c_int, c_void_p, c_void_p]),
     "shm_launch_fcollect": (c_int, [c_void_p, c_uint64, c_uint64, c_size_t, c_int, c_int]),
     "shm_launch_collect": (c_int, [c_void_p, c_uint64, c_uint64, POINTER(c_size_t), c_int]),
@@ -360,6 +362,10 @@ class Shm:
 
     def launch_pingflag(self, data_off, back_off, n, flag_off):
         self._check(self.lib.shm_launch_pingflag(self.ctx, data_off, back_off, n, flag_off))
+
+    def launch_ring_pipeline_static(self, src_off, slot_off, sig_off, acc_off, chunk_bytes, n_chunks, n_wg_prod, n_wg_cons, n_sig=1):
+        self._check(self.lib.shm_launch_ring_pipeline_static(self.ctx, src_off, slot_off, sig_off, acc_off, chunk_bytes, n_chunks,
+                                                             n_wg_prod, n_wg_cons, n_sig))
 
     def launch_ring_pipeline(self, src_off, slot_off, sig_off, acc_off, chunk_bytes, n_chunks, n_wg_prod, n_wg_cons, n_sig=1):
         self._check(self.lib.shm_launch_ring_pipeline(self.ctx, src_off, slot_off, sig_off, acc_off, chunk_bytes, n_chunks,
