@@ -142,8 +142,13 @@ int shm_barrier_all(shm_ctx *ctx);
  * With SHM_PATH_AUTO a transfer of n bytes by n_wg work-groups uses SDMA iff
  * n >= cutover(class of n_wg); classes are n_wg <= 1, <= 4, <= 64, > 64.  SIZE_MAX = never.
  * Defaults are the thresholds measured on MI355X with 8 PEs transferring at once (the paper sets its
- * own the same way, internally): 512 KiB for one group per PE, never for more.  A context whose copy
- * engines are unavailable keeps AUTO on loads/stores. */
+ * own the same way, internally), and they depend on whether every PE's stream has a hardware queue of
+ * its own: the HIP runtime creates GPU_MAX_HW_QUEUES queues per process (4 unless the environment
+ * says otherwise), and with fewer queues than PEs the put kernels of different PEs take turns, which
+ * halves what loads/stores deliver while the engines are not affected.  shm_init reads that variable:
+ *   queues >= npes: 512 KiB for one group per PE, never for more;
+ *   queues <  npes: 256 KiB for one group per PE, 2 MiB for up to four, never for more.
+ * A context whose copy engines are unavailable keeps AUTO on loads/stores. */
 int shm_set_cutover(shm_ctx *ctx, int n_wg, size_t bytes);
 int shm_get_cutover(const shm_ctx *ctx, int n_wg, size_t *bytes);
 /* Which path AUTO would take: writes SHM_PATH_LDST or SHM_PATH_SDMA to *path. */

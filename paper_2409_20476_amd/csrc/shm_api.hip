@@ -6,6 +6,7 @@
 
 #include <cstdarg>
 #include <cstdio>
+#include <cstdlib>
 #include <cstring>
 #include <mutex>
 #include <new>
@@ -79,8 +80,8 @@ struct shm_ctx {
     uint64_t ticks_per_us = 100;
     // AUTO thresholds per class of work-group count, as measured on MI355X with 8 PEs transferring at
     // once: the engines move more from 512 KiB with one group per PE and never against four or more
-    // groups (given a hardware queue per PE stream; with fewer queues than PE streams the put kernels
-    // of different PEs take turns and the engines also overtake four groups, from about 8 MiB).
+    // groups, given a hardware queue per PE stream; shm_init_ex lowers them when the process has
+    // fewer hardware queues than PEs (default_cutovers).
     size_t cutover[4] = {size_t(512) << 10, SIZE_MAX, SIZE_MAX, SIZE_MAX};
     // AUTO thresholds of the collectives, bytes per PE, per class of work-group count; set at init
     // from the number of PEs (measured on MI355X with 4, 8 and 12 PEs; the host-started side of the
@@ -179,6 +180,24 @@ int resolve_path(const shm_ctx *c, int path, size_t n, int n_wg, int *out)
     else
         return fail(SHM_EINVAL, "unknown path %d", path);
     return SHM_OK;
+}
+
+// The HIP runtime gives a process GPU_MAX_HW_QUEUES hardware queues (4 unless the environment says
+// otherwise) and spreads its streams over them.  With fewer queues than PEs the put kernels of
+// different PEs' streams take turns, every per-PE load/store curve halves, and the engines --
+// which are not in those queues -- win from smaller sizes: measured with 8 PEs on 4 queues, from
+// 256 KiB against one group per PE and from 1-8 MiB (2 MiB taken) against four.
+void default_cutovers(shm_ctx *c)
+{
+    int queues = 4;
+    if (const char *e = getenv("GPU_MAX_HW_QUEUES")) {
+        const int v = atoi(e);
+        if (v >= 1) queues = v;
+    }
+    if (queues < c->npes) {
+        c->cutover[0] = size_t(256) << 10;
+        c->cutover[1] = size_t(2) << 20;
+    }
 }
 
 void default_collective_cutovers(shm_ctx *c)
@@ -521,6 +540,7 @@ int shm_init_ex(int npes, size_t heap_bytes, void *heap_base, void *const *strea
     c->part_bytes = heap_bytes;
     c->user_bytes = heap_bytes - SHM_INTERNAL_BYTES;
     c->alloc.reset(c->user_bytes);
+    default_cutovers(c);
     default_collective_cutovers(c);
     c->no_device = (flags & SHM_INIT_NO_DEVICE) != 0;
     if (c->no_device) {

@@ -425,7 +425,10 @@ __global__ __launch_bounds__(SHMK_WG, 4) void shmk_ring(shm_dev_ctx c, uint64_t 
             }
             return;
         }
-        // larger shares: one put_signal per chunk by all producer groups together
+        // Larger shares: one put_signal per chunk by all producer groups together.  (Walking such a
+        // share block by block through the same two-half pipeline was measured and is slower: with
+        // 8 or 16 producer groups per PE -- 64 or 128 on the whole chip -- the rate is bound by the
+        // bytes those few groups keep in flight, 32 KiB each either way, not by the chain of latencies.)
         uint64_t *arrive = arrive_pe0 + static_cast<uint64_t>(me) * arrive_pe_stride;
         for (int k = 0; k < n_chunks; ++k)
             shmx_putmem_signal_parts(c, me, slot_off + k * chunk_bytes, src_off + k * chunk_bytes, chunk_bytes, sig_off, 1,

@@ -202,10 +202,27 @@ def test_every_entry_point_validates_before_touching_the_device():
     g.finalize()
 
 
-def test_cutover_policy_classes():
+def test_cutover_defaults_follow_the_hardware_queue_count(monkeypatch):
+    """The measured defaults come in two sets: a hardware queue per PE stream, or fewer queues than
+    PEs (HIP's default is 4 queues per process; shm_init reads GPU_MAX_HW_QUEUES)."""
+    never = (1 << 64) - 1
+    for env, npes, want in [(None, 4, [MiB // 2, never, never, never]), (None, 8, [MiB // 4, 2 * MiB, never, never]),
+                            ("8", 8, [MiB // 2, never, never, never]), ("8", 12, [MiB // 4, 2 * MiB, never, never]),
+                            ("junk", 8, [MiB // 4, 2 * MiB, never, never]), ("0", 4, [MiB // 2, never, never, never])]:
+        if env is None:
+            monkeypatch.delenv("GPU_MAX_HW_QUEUES", raising=False)
+        else:
+            monkeypatch.setenv("GPU_MAX_HW_QUEUES", env)
+        g = _ctx(npes)
+        assert [g.get_cutover(w) for w in (1, 4, 64, 1024)] == want, (env, npes)
+        g.finalize()
+
+
+def test_cutover_policy_classes(monkeypatch):
+    monkeypatch.delenv("GPU_MAX_HW_QUEUES", raising=False)
     g = _ctx()
     never = (1 << 64) - 1
-    assert [g.get_cutover(w) for w in (1, 4, 64, 1024)] == [MiB // 2, never, never, never]      # the measured defaults
+    assert [g.get_cutover(w) for w in (1, 4, 64, 1024)] == [MiB // 2, never, never, never]      # the measured defaults, 4 PEs on 4 queues
     assert g.choose_path(MiB // 2 - 1, 1) == S.SHM_PATH_LDST and g.choose_path(MiB // 2, 1) == S.SHM_PATH_SDMA
     assert g.choose_path(1 << 40, 4) == S.SHM_PATH_LDST and g.choose_path(1 << 40, 1024) == S.SHM_PATH_LDST
     g.set_cutover(1, 4096), g.set_cutover(3, 65536), g.set_cutover(64, MiB), g.set_cutover(65, 16 * MiB)
