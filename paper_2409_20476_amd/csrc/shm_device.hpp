@@ -42,6 +42,20 @@ struct shm_dev_ctx {
 typedef uint32_t shm_u32x4 __attribute__((ext_vector_type(4)));
 
 enum { SHMD_SIGNAL_SET = 0, SHMD_SIGNAL_ADD = 1 };
+
+// Memory orders of the atomics that publish a payload (the arrival counters of a message shared by
+// several groups, and the signal word).  The library's build stores such payloads write-through,
+// waits for their acknowledgement and then needs no ordering from the atomic itself (relaxed).
+// Built with -DSHM_SIGNAL_FULL_RELEASE the same atomics are release / acquire-release operations,
+// with the cache write-backs that implies: the textbook form, kept as a second library that the
+// signalling tests are run against as a cross-check of the relaxed form.
+#ifdef SHM_SIGNAL_FULL_RELEASE
+#define SHMD_ARRIVE_ORDER __ATOMIC_ACQ_REL
+#define SHMD_SIGNAL_ORDER __ATOMIC_RELEASE
+#else
+#define SHMD_ARRIVE_ORDER __ATOMIC_RELAXED
+#define SHMD_SIGNAL_ORDER __ATOMIC_RELAXED
+#endif
 enum { SHMD_CMP_EQ = 0, SHMD_CMP_NE = 1, SHMD_CMP_GT = 2, SHMD_CMP_GE = 3, SHMD_CMP_LT = 4, SHMD_CMP_LE = 5 };
 
 // Address rule of the paper's section "Remote Memory Access": same offset, target PE's base.  With
@@ -543,20 +557,23 @@ __device__ __forceinline__ void shmx_quiet_wg()
 // half a microsecond each, dirty lines or not: a grid whose every group releases for itself pays
 // (groups per XCD) x that, which is most of the time of a put followed by its quiet once a grid has
 // hundreds of groups.  But ONE write-back covers every store that had reached that L2 when it
-// began, whoever issued it.  So the groups of an XCD share their releases through a record per XCD
-// (in the library's tail of PE 0's partition; the XCD number is the hardware's XCC_ID register):
-//   started  number of shared write-backs begun on this XCD (only ever incremented)
-//   done     number of the latest one that has finished
-//   lock     held by the one group that is writing back
+// began, whoever issued it.  So the groups of an XCD share their releases through one 64-bit word
+// per XCD (in the library's tail of PE 0's partition; the XCD number is the hardware's XCC_ID
+// register):
+//   bit 0       set while one group is writing back (the lock)
+//   bits 63..1  number of shared write-backs that have FINISHED on this XCD
 // Every wave first waits for the acknowledgement of its own stores (s_waitcnt vmcnt(0): they are in
-// the L2 or beyond).  The leader reads `started` = s: a write-back numbered above s began after
-// that, so it covers the group.  The leader then waits for done > s -- or, finding the lock free,
-// becomes the one who writes back: takes the lock, increments `started` (the returned number t is
-// its own), releases at agent scope, stores done = t, frees the lock.  The holder of the lock never
-// waits for anybody, so every wait ends; waits are bounded all the same, and a leader that has
-// polled for too long releases for itself.  Small grids (fewer than SHMD_QUIET_SHARED_MIN_GROUPS
-// groups) release directly: two atomics cost more than a write-back nobody queues for.
-#define SHMD_INTERNAL_QUIET 33280u            // 8 records, 128 bytes apart
+// the L2 or beyond).  The leader then sets bit 0 with one fetch-or.  If the bit was clear the
+// leader is the one who writes back: agent-scope release, then ONE store that publishes count + 1
+// and clears the lock -- two memory round trips in all when nobody else is releasing.  If the bit
+// was set, with count c, write-back c + 1 is under way and may have begun before this group's
+// stores arrived; the group is covered by write-back c + 2, which can only begin after c + 1 has
+// ended, i.e. after this moment.  The leader polls the word: count >= c + 2 ends the wait; a clear
+// lock lets it try to become the one who writes back.  The holder of the lock never waits for
+// anybody, so every wait ends; waits are bounded all the same, and a leader that has polled for
+// too long releases for itself.  Small grids (fewer than SHMD_QUIET_SHARED_MIN_GROUPS groups)
+// release directly: an atomic costs more than a write-back nobody queues for.
+#define SHMD_INTERNAL_QUIET 33280u            // 8 words, 128 bytes apart
 #define SHMD_QUIET_SHARED_MIN_GROUPS 64u
 #define SHMD_QUIET_SPIN_LIMIT 4096
 
@@ -570,21 +587,36 @@ __device__ __forceinline__ unsigned shm_xcc_id()
 // One thread; the stores it speaks for are acknowledged.
 __device__ __forceinline__ void shm_release_shared(const shm_dev_ctx &c)
 {
-    char *rec = c.base[0] + c.internal_off + SHMD_INTERNAL_QUIET + 128u * shm_xcc_id();
-    unsigned long long *started = reinterpret_cast<unsigned long long *>(rec), *done = started + 1;
-    unsigned *lock = reinterpret_cast<unsigned *>(rec + 16);
-    const unsigned long long s = __hip_atomic_load(started, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    for (int spin = 0; spin < SHMD_QUIET_SPIN_LIMIT; ++spin) {
-        if (__hip_atomic_load(done, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) > s) return;
-        if (__hip_atomic_load(lock, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == 0u &&
-            __hip_atomic_exchange(lock, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == 0u) {
-            const unsigned long long t = __hip_atomic_fetch_add(started, 1ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) + 1ull;
+    unsigned long long *word =
+        reinterpret_cast<unsigned long long *>(c.base[0] + c.internal_off + SHMD_INTERNAL_QUIET + 128u * shm_xcc_id());
+    unsigned long long need = 0;                 // 0: no write-back was under way when this group arrived
+    // With the lock held (v = the word before our fetch-or): write back unless a write-back that
+    // covers this group has finished meanwhile, then publish the count and clear the lock.
+    auto as_holder = [&](unsigned long long v) {
+        if (need == 0 || (v >> 1) < need) {
             __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");          // the write-back, waited for
-            __hip_atomic_store(done, t, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            __hip_atomic_store(lock, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            return;
+            v += 2ull;
         }
-        __builtin_amdgcn_s_sleep(4);
+        __hip_atomic_store(word, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    };
+    unsigned long long v = __hip_atomic_fetch_or(word, 1ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if (!(v & 1ull)) {
+        as_holder(v);
+        return;
+    }
+    need = (v >> 1) + 2ull;
+    for (int spin = 0; spin < SHMD_QUIET_SPIN_LIMIT; ++spin) {
+        __builtin_amdgcn_s_sleep(2);
+        v = __hip_atomic_load(word, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if ((v >> 1) >= need) return;
+        if (!(v & 1ull)) {
+            v = __hip_atomic_fetch_or(word, 1ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            if (!(v & 1ull)) {
+                as_holder(v);
+                return;
+            }
+            if ((v >> 1) >= need) return;
+        }
     }
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
 }
@@ -812,17 +844,13 @@ __device__ __forceinline__ size_t shm_test_some(const shm_dev_ctx &c, int me, ui
 // only then does the leader touch the arrival counter and the signal, with relaxed agent-scope
 // atomics.  Group `part` copies its share; the group whose arrival completes the message (counted
 // in *arrive, which it resets to zero) updates the signal.  With nparts == 1 the counter is not
-// touched and may be null.  Define SHM_SIGNAL_FULL_RELEASE to use release/acquire atomics (and the
-// cache write-backs they imply) instead.
+// touched and may be null.  (SHMD_ARRIVE_ORDER / SHMD_SIGNAL_ORDER: relaxed here, release/acquire in
+// the cross-check build.)
 __device__ __forceinline__ void shmx_putmem_signal_parts(const shm_dev_ctx &c, int me, uint64_t dst_off, uint64_t src_off,
                                                          size_t n, uint64_t sig_off, uint64_t sig_val, int sig_op, int pe,
                                                          uint64_t *arrive, unsigned part, unsigned nparts)
 {
-#ifdef SHM_SIGNAL_FULL_RELEASE
-    constexpr int arrive_order = __ATOMIC_ACQ_REL, signal_order = __ATOMIC_RELEASE;
-#else
-    constexpr int arrive_order = __ATOMIC_RELAXED, signal_order = __ATOMIC_RELAXED;
-#endif
+    constexpr int arrive_order = SHMD_ARRIVE_ORDER, signal_order = SHMD_SIGNAL_ORDER;
     __syncthreads();
     shm_copy_parts<8, SHM_ST_THROUGH>(shm_ptr(c, dst_off, pe), shm_ptr(c, src_off, me), n, part, nparts);
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");     // this wave's payload is performed at agent scope
@@ -972,6 +1000,7 @@ __device__ __forceinline__ uint64_t shm_offload_send(const shm_dev_ctx &c, uint3
 {
     const unsigned lane = __lane_id();
     uint64_t idx = 0, ticket = SHMD_OFFLOAD_NONE;
+    uint32_t expired = 0;
     if (lane == 0) {
         idx = __hip_atomic_fetch_add(c.off.head, 1ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         if (want_completion) {
@@ -992,12 +1021,17 @@ __device__ __forceinline__ uint64_t shm_offload_send(const shm_dev_ctx &c, uint3
                 if (idx - seen < SHMD_OFFLOAD_SLOTS) break;
                 if (wall_clock64() - t0 > c.wait_ticks) {
                     __hip_atomic_store(c.status, 1ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+                    expired = 1;
                     break;
                 }
                 __builtin_amdgcn_s_sleep(8);
             }
         }
     }
+    // The host never freed the slot within the wait bound: the request is dropped rather than
+    // written over a message the host has not taken (the time-out flag is set; the context's next
+    // quiet reports it, and the ring stays stalled at this index).
+    if (__builtin_amdgcn_readfirstlane(expired)) return SHMD_OFFLOAD_NONE;
     idx = shm_wave_first_u64(idx);
     ticket = shm_wave_first_u64(ticket);
     const uint32_t tag = static_cast<uint32_t>(idx / SHMD_OFFLOAD_SLOTS) + 1u;

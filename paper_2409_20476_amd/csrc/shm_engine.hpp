@@ -12,6 +12,7 @@
 #include <hsa/hsa_ext_amd.h>
 
 #include <chrono>
+#include <cstddef>
 #include <cstdint>
 #include <string>
 #include <vector>
@@ -103,28 +104,45 @@ public:
     bool busy(int pe) const { return !pending_[pe].empty(); }
 
     // Wait for every transfer PE `pe` has started.  Bounded: a copy that has not finished after
-    // `limit_s` seconds is reported instead of waited for.
+    // `limit_s` seconds is reported instead of waited for; the transfers already retired leave the
+    // pending list, the others stay on it (each signal is recycled exactly once).  A transfer the
+    // engine ended with an error leaves its signal negative: it is retired and reported.
     bool drain(int pe, std::string &err, double limit_s = 60.0)
     {
         using clock = std::chrono::steady_clock;
         const auto t0 = clock::now();
-        for (hsa_signal_t sig : pending_[pe]) {
-            while (hsa_signal_wait_scacquire(sig, HSA_SIGNAL_CONDITION_LT, 1, 50000000ull, HSA_WAIT_STATE_ACTIVE) >= 1) {
+        std::vector<hsa_signal_t> &q = pending_[pe];
+        bool ok = true;
+        size_t done = 0;
+        for (; done < q.size(); ++done) {
+            hsa_signal_value_t v;
+            bool late = false;
+            while ((v = hsa_signal_wait_scacquire(q[done], HSA_SIGNAL_CONDITION_LT, 1, 50000000ull, HSA_WAIT_STATE_ACTIVE)) >= 1) {
                 if (std::chrono::duration<double>(clock::now() - t0).count() > limit_s) {
-                    err = "a copy-engine transfer did not complete in time";
-                    return false;     // the signals stay pending; the context should be finalized
+                    late = true;
+                    break;
                 }
             }
-            free_.push_back(sig);
+            if (late) {
+                err = "a copy-engine transfer did not complete in time";
+                ok = false;
+                break;
+            }
+            if (v < 0) {
+                err = "a copy-engine transfer ended with an error";
+                ok = false;
+            }
+            free_.push_back(q[done]);
         }
-        pending_[pe].clear();
-        return true;
+        q.erase(q.begin(), q.begin() + static_cast<std::ptrdiff_t>(done));
+        return ok;
     }
 
     void shutdown()
     {
         std::string ignore;
         for (size_t p = 0; p < pending_.size(); ++p) drain(static_cast<int>(p), ignore, 10.0);
+        // a signal whose transfer never ended is leaked rather than destroyed under the engine
         for (hsa_signal_t s : free_) hsa_signal_destroy(s);
         free_.clear();
         if (inited_) hsa_shut_down();

@@ -414,12 +414,12 @@ __global__ __launch_bounds__(SHMK_WG, 4) void shmk_ring(shm_dev_ctx c, uint64_t 
                 }
                 __syncthreads();
                 if (lanes) {
-                    if (threadIdx.x == 0) __hip_atomic_fetch_add(sig, 1ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    if (threadIdx.x == 0) __hip_atomic_fetch_add(sig, 1ull, SHMD_SIGNAL_ORDER, __HIP_MEMORY_SCOPE_AGENT);
                 } else if (static_cast<int>(threadIdx.x) == ((k & 1) ? 0 : HALF)) {
-                    const uint64_t old = __hip_atomic_fetch_add(arrive + k, 1ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    const uint64_t old = __hip_atomic_fetch_add(arrive + k, 1ull, SHMD_ARRIVE_ORDER, __HIP_MEMORY_SCOPE_AGENT);
                     if (old == static_cast<uint64_t>(n_prod) - 1) {
                         __hip_atomic_store(arrive + k, 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                        __hip_atomic_fetch_add(sig, 1ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                        __hip_atomic_fetch_add(sig, 1ull, SHMD_SIGNAL_ORDER, __HIP_MEMORY_SCOPE_AGENT);
                     }
                 }
             }

@@ -127,10 +127,13 @@ def load_library() -> ctypes.CDLL:
     that the library binds to the runtime already in the process."""
     global _lib
     if _lib is None:
-        if not os.path.exists(_LIB_PATH):
-            raise ImportError(f"{_LIB_PATH} has not been built; run `python -m paper_2409_20476_amd.build` "
+        path = _LIB_PATH
+        if os.environ.get("SHM355_LIBRARY_VARIANT"):      # e.g. "full_release": the cross-check build
+            path = _LIB_PATH[:-3] + "_" + os.environ["SHM355_LIBRARY_VARIANT"] + ".so"
+        if not os.path.exists(path):
+            raise ImportError(f"{path} has not been built; run `python -m paper_2409_20476_amd.build` "
                               "(there is no CPU fallback)")
-        lib = ctypes.CDLL(_LIB_PATH)
+        lib = ctypes.CDLL(path)
         for name, (res, args) in PROTOTYPES.items():
             fn = getattr(lib, name)
             fn.restype, fn.argtypes = res, args
