@@ -306,16 +306,28 @@ def hbm_ceilings(torch, S, g, args):
     a, b = g.malloc(n), g.malloc(n)
     g.set_team_sync(False)
     out = {}
-    for name, kind, bytes_moved in (("read_only", S.SHM_PROBE_READ, npes * n), ("write_only", S.SHM_PROBE_WRITE, npes * n),
-                                    ("copy", S.SHM_PROBE_COPY, 2 * npes * n)):
-        ms = min(time_on_stream(torch, g.streams[0], lambda: g.launch_stream_probe(kind, b, a, n, 1024), 5) for _ in range(5))
-        out[name] = {"ms": ms, "gbs": bytes_moved / ms / 1e6, "frac_hbm": bytes_moved / ms / 1e6 / HBM_PEAK_GBS}
+
+    def probe(kind, n_wg):
+        return min(time_on_stream(torch, g.streams[0], lambda: g.launch_stream_probe(kind, b, a, n, n_wg), 5) for _ in range(5))
+
+    # each direction in two access orders: the tiles of the put, and a front that sweeps the block;
+    # the better one is that direction's ceiling
+    for name, kinds in (("read_only", (("tiles", S.SHM_PROBE_READ, (1024,)), ("front", S.SHM_PROBE_READ_FRONT, (64, 256, 1024)))),
+                        ("write_only", (("tiles", S.SHM_PROBE_WRITE, (1024,)), ("front", S.SHM_PROBE_WRITE_FRONT, (64, 256, 1024))))):
+        forms = {f"{form}_wg{w}": probe(kind, w) for form, kind, wgs in kinds for w in wgs}
+        best = min(forms, key=forms.get)
+        ms = forms[best]
+        out[name] = {"ms": ms, "gbs": npes * n / ms / 1e6, "frac_hbm": npes * n / ms / 1e6 / HBM_PEAK_GBS, "form": best,
+                     "frac_hbm_by_form": {k: npes * n / v / 1e6 / HBM_PEAK_GBS for k, v in forms.items()}}
+    ms = probe(S.SHM_PROBE_COPY, 1024)
+    out["copy"] = {"ms": ms, "gbs": 2 * npes * n / ms / 1e6, "frac_hbm": 2 * npes * n / ms / 1e6 / HBM_PEAK_GBS}
     g.set_team_sync(True)
     g.free(a), g.free(b)
     r, w = out["read_only"]["gbs"], out["write_only"]["gbs"]
     return {"kernels": out, "copy_bus_time_limit_frac_hbm": 2.0 / (1.0 / r + 1.0 / w) / HBM_PEAK_GBS,
-            "note": "8 PEs x 256 MiB x 1024 groups; copy_bus_time_limit = 2 / (1/read + 1/write): the rate of a copy whose reads and "
-                    "writes share the bus without overlapping"}
+            "note": "8 PEs x 256 MiB; read_only / write_only: the better of two access orders (group-owned 64 KiB tiles as in the put; "
+                    "a front of n_wg x 4 KiB per PE sweeping the block); copy = the put itself; copy_bus_time_limit = "
+                    "2 / (1/read + 1/write): a copy whose reads and writes share the bus without overlapping or disturbing each other"}
 
 
 def put_sweep(torch, S, g, args):
@@ -871,7 +883,10 @@ def summarise(extras, cpu_legs):
         if "placement" in r:
             out["c2"]["placement_pct_min_med_max"] = r["placement"]["pct_min_med_max"]
     if "hbm_ceilings" in extras:
-        out["hbm_ceilings_pct"] = {k: v["frac_hbm"] * 100 for k, v in extras["hbm_ceilings"]["kernels"].items()}
+        hc = extras["hbm_ceilings"]
+        out["hbm_ceilings_pct"] = {**{k: v["frac_hbm"] * 100 for k, v in hc["kernels"].items()},
+                                   "copy_bus_time_limit": hc["copy_bus_time_limit_frac_hbm"] * 100,
+                                   "forms": {k: v["form"] for k, v in hc["kernels"].items() if "form" in v}}
     if "config3_ring" in extras:
         r = extras["config3_ring"]
         shapes = {k: q for k, q in r.items() if k.startswith("prod")}

@@ -899,7 +899,7 @@ int shm_launch_wg_put_timed(shm_ctx *c, int me, int pe, uint64_t dst_off, uint64
 int shm_launch_stream_probe(shm_ctx *c, int kind, uint64_t dst_off, uint64_t src_off, size_t n, int n_wg)
 {
     if (int r = check_ctx(c)) return r;
-    if (kind != SHM_PROBE_READ && kind != SHM_PROBE_WRITE && kind != SHM_PROBE_COPY) return fail(SHM_EINVAL, "unknown probe kind %d", kind);
+    if (kind < SHM_PROBE_READ || kind > SHM_PROBE_WRITE_FRONT) return fail(SHM_EINVAL, "unknown probe kind %d", kind);
     if (int r = rma_args(c, 0, c->npes > 1 ? 1 : 0, dst_off, src_off, n)) return r;
     if (n == 0 || n % 65536 || ((dst_off | src_off) & 15)) return fail(SHM_EINVAL, "the probe moves whole 64 KiB tiles at 16-byte aligned offsets");
     if (int r = check_team_grid(c, n_wg)) return r;
@@ -909,11 +909,16 @@ int shm_launch_stream_probe(shm_ctx *c, int kind, uint64_t dst_off, uint64_t src
     if (c->team_sync)
         if (int r = team_join(c)) return r;
     const int shift = c->npes > 1 ? 1 : 0;
-    const dim3 grid(tile_groups(n, n_wg), c->npes), block(SHMK_WG);
+    const bool front = kind == SHM_PROBE_READ_FRONT || kind == SHM_PROBE_WRITE_FRONT;
+    const dim3 grid(front ? n_wg : tile_groups(n, n_wg), c->npes), block(SHMK_WG);
     if (kind == SHM_PROBE_READ)
-        hipLaunchKernelGGL(shmk_stream_probe<0>, grid, block, TILES_LDS_BYTES, c->stream[0], dev_view(c), dst_off, src_off, n, shift, 0x5eedf00du);
+        hipLaunchKernelGGL((shmk_stream_probe<0, 0>), grid, block, TILES_LDS_BYTES, c->stream[0], dev_view(c), dst_off, src_off, n, shift, 0x5eedf00du);
+    else if (kind == SHM_PROBE_WRITE)
+        hipLaunchKernelGGL((shmk_stream_probe<1, 0>), grid, block, TILES_LDS_BYTES, c->stream[0], dev_view(c), dst_off, src_off, n, shift, 0x5eedf00du);
+    else if (kind == SHM_PROBE_READ_FRONT)
+        hipLaunchKernelGGL((shmk_stream_probe<0, 1>), grid, block, TILES_LDS_BYTES, c->stream[0], dev_view(c), dst_off, src_off, n, shift, 0x5eedf00du);
     else
-        hipLaunchKernelGGL(shmk_stream_probe<1>, grid, block, TILES_LDS_BYTES, c->stream[0], dev_view(c), dst_off, src_off, n, shift, 0x5eedf00du);
+        hipLaunchKernelGGL((shmk_stream_probe<1, 1>), grid, block, TILES_LDS_BYTES, c->stream[0], dev_view(c), dst_off, src_off, n, shift, 0x5eedf00du);
     if (int r = launched("stream probe")) return r;
     if (c->team_sync)
         if (int r = team_fork(c)) return r;

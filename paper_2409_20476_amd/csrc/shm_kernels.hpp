@@ -45,7 +45,10 @@ __global__ __launch_bounds__(SHMK_WG) void shmk_wg_rma_tiles(char *base, uint64_
 // (KIND 0: 16-byte nontemporal loads of the source on the calling PE, folded into a word that is
 // stored only if it equals `magic`, which keeps the loads alive) or only written (KIND 1: 16-byte
 // nontemporal stores of a lane-dependent pattern to the destination on the target PE).
-template <int KIND>
+// FRONT != 0: no tiles; the PE's groups sweep the block together, every group one 4 KiB piece of a
+// front of gridDim.x pieces that moves through the block (the pattern that writes fastest on this
+// chip: what runs at one moment touches a few compact windows instead of hundreds of scattered tiles).
+template <int KIND, int FRONT>
 __global__ __launch_bounds__(SHMK_WG) void shmk_stream_probe(shm_dev_ctx c, uint64_t dst_off, uint64_t src_off, size_t n, int shift,
                                                              uint32_t magic)
 {
@@ -60,6 +63,19 @@ __global__ __launch_bounds__(SHMK_WG) void shmk_stream_probe(shm_dev_ctx c, uint
     uint32_t fold = 0;
     shm_u32x4 pattern;
     pattern.x = threadIdx.x, pattern.y = blockIdx.x, pattern.z = magic, pattern.w = static_cast<uint32_t>(me);
+    if (FRONT) {
+        const size_t nvec = n >> 4, step = static_cast<size_t>(gridDim.x) * SHMK_WG;
+        for (size_t i = static_cast<size_t>(blockIdx.x) * SHMK_WG + threadIdx.x; i < nvec; i += step) {
+            if (KIND == 0) {
+                const shm_u32x4 r0 = shm_ld16(s + i);
+                fold ^= r0.x ^ r0.y ^ r0.z ^ r0.w;
+            } else {
+                shm_st16(d + i, pattern);
+            }
+        }
+        if (KIND == 0 && fold == magic && n == 1) d[0].x = fold;
+        return;
+    }
     for (size_t t = blockIdx.x; t < ntiles; t += gridDim.x) {
 #pragma unroll
         for (unsigned cc = 0; cc < 8; ++cc) {

@@ -2,8 +2,9 @@
 import numpy as np
 import pytest
 
+from oracle.shmem_oracle import SIGNAL_ADD
 from paper_2409_20476_amd import shm as S
-from parity_util import assert_heaps_equal, fill_random, make_pair
+from parity_util import assert_heaps_equal, fill_random, make_pair, write_both
 
 pytestmark = pytest.mark.gpu
 
@@ -129,6 +130,41 @@ def test_timed_put_moves_the_same_bytes_and_reports_device_time():
         t0, t1 = (int(v) & ((1 << 64) - 1) for v in ticks.tolist())
         us = (t1 - t0) / g.wall_clock_khz() * 1e3
         assert 0 < us < 1e5, us
+
+
+@pytest.mark.parametrize("n_wg", [65, 200, 1024])
+def test_more_groups_than_take_part(n_wg):
+    """Beyond 64 groups a message is dealt only to as many groups as get 128 KiB each; the others have
+    no share.  Sizes around the steps of that rule, shifted and aligned sources, put, get, put_signal
+    by all groups, and the timed put whose groups without a share skip their quiet."""
+    import torch
+    g, o = make_pair(2, 64 * MiB)
+    with g:
+        fill_random(g, o, 21, upto=48 * MiB)
+        sig = 47 * MiB
+        for i, (n, sa, da) in enumerate([(5, 0, 0), (300001, 3, 7), (8 * MiB - 16, 0, 0), (8 * MiB + 128 * 1024 * 3 + 48 + 5, 16, 32),
+                                         (9 * MiB + 1, 5, 5), (17 * MiB + 4096, 32, 0)]):
+            src, dst, back = 64 + sa, 20 * MiB + da, 40 * MiB - 7 * MiB * (i % 2) + sa
+            g.launch_wg_put(0, 1, dst, src, n, n_wg)
+            o.wg_put(0, dst, src, n, 1, n_wg)
+            g.barrier_all()
+            if n <= 7 * MiB:
+                g.launch_wg_get(0, 1, back, dst, n, n_wg)
+                o.wg_get(0, back, dst, n, 1, n_wg)
+                g.barrier_all()
+            assert_heaps_equal(g, o, upto=48 * MiB, what=f"n={n} by {n_wg} groups")
+        ticks = torch.zeros(2, dtype=torch.int64, device="cuda")
+        ticks[0] = -1
+        g.launch_wg_put_timed(1, 0, 20 * MiB + 16, 1 * MiB, 9 * MiB + 48 + 3, n_wg, 3, ticks)
+        g.quiet(1)
+        o.wg_put(1, 20 * MiB + 16, 1 * MiB, 9 * MiB + 48 + 3, 0, n_wg)
+        z = np.zeros(8, np.uint8)
+        for p in range(2):
+            write_both(g, o, p, sig, z)
+        g.launch_wg_put_signal(0, 1, 30 * MiB + 5, 2 * MiB + 1, 3 * MiB + 9, sig, 1, S.SHM_SIGNAL_ADD, min(n_wg, 1000))
+        o.put_signal(0, 30 * MiB + 5, 2 * MiB + 1, 3 * MiB + 9, sig, 1, SIGNAL_ADD, 1)
+        g.barrier_all()
+        assert_heaps_equal(g, o, upto=48 * MiB, what=f"timed put and put_signal by {n_wg} groups")
 
 
 def test_timed_put_of_long_messages_moves_the_same_bytes_on_both_long_message_paths():
