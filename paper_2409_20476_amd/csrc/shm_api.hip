@@ -30,15 +30,17 @@ constexpr uint32_t ARRIVE_SLOTS = 4096;                       // 8-byte arrival 
 static_assert(ARRIVE_SLOTS * 8 <= SHM_INTERNAL_BYTES, "arrival counters must fit the internal tail");
 static_assert(SHM_WG_SIZE == SHMK_WG, "one work-group size everywhere");
 constexpr int MAX_N_WG = 1 << 20;
-// Group-owned tiles pay off for long messages moved by a grid that fills the chip (measured on
-// MI355X from 8 MiB: a team grid of 8 PEs x 64 or more groups gains 5-10 %, a grid of 1024 groups
-// of one PE about the same from 64 MiB; a grid of 32-256 groups -- one PE launching alone -- loses
-// 17-47 % against the 8-group virtual blocks, which keep four times as many loads in flight per
-// group, and stays on those).
+// Group-owned tiles are the form for long messages moved by 64 or more groups (measured on MI355X,
+// 32-256 MiB per PE).  A grid that fills the chip gains 5-10 % over the 8-group virtual blocks; eight
+// PEs launching 64 groups each on their own streams gain 6-9 points of the HBM roofline (61 -> 67-70 %);
+// one PE launching 64 groups ALONE loses 6 % (3.3 -> 3.1 TB/s of traffic) and 256 groups alone are
+// level from 64 MiB -- the launcher cannot know who else is running and takes the case of all PEs at
+// work, which is what the PEs of a context are for.  Fewer than 64 groups stay on the virtual blocks,
+// which keep more loads in flight per group.
 constexpr size_t TILES_MIN_BYTES = 32u << 20;
 constexpr size_t TILE_BYTES = 64u << 10, TILES_PER_GROUP = 4;
-constexpr long long TILES_MIN_GRID_GROUPS = 512;              // groups asked for, all PEs of the grid together
-constexpr long long TILES_MIN_LAUNCHED_GROUPS = 256;          // groups launched, all PEs of the grid together
+constexpr long long TILES_MIN_GRID_GROUPS = 64;               // groups asked for, all PEs of the grid together
+constexpr long long TILES_MIN_LAUNCHED_GROUPS = 64;           // groups launched, all PEs of the grid together
 constexpr unsigned TILES_LDS_BYTES = 54000;                   // unused LDS that caps a CU at 3 resident groups
 constexpr uint64_t OFFLOAD_COUNTERS = 32768;                  // offset of the ring's three index words in PE 0's internal tail
 static_assert(ARRIVE_SLOTS * 8 <= OFFLOAD_COUNTERS && OFFLOAD_COUNTERS + 24 <= SHMD_INTERNAL_SYNC_COUNT &&

@@ -168,12 +168,14 @@ def test_more_groups_than_take_part(n_wg):
 
 
 def test_timed_put_of_long_messages_moves_the_same_bytes_on_both_long_message_paths():
-    """9 MiB by 64 groups stays on the virtual blocks, 65 MiB by 512 groups takes group-owned tiles."""
+    """9 MiB by 64 groups and 40 MiB by 48 groups stay on the virtual blocks (short message; fewer than 64
+    groups), 65 MiB by 512 groups and 33 MiB by 64 groups take group-owned tiles."""
     import torch
     g, o = make_pair(2, 160 * MiB)
     with g:
         fill_random(g, o, 7, upto=144 * MiB)
-        for n, n_wg in [(9 * MiB + 16 * 3 + 5, 64), (65 * MiB + 16 * 3 + 5, 512)]:      # ragged last tile and a byte tail
+        for n, n_wg in [(9 * MiB + 16 * 3 + 5, 64), (65 * MiB + 16 * 3 + 5, 512), (40 * MiB + 16 * 7 + 1, 48),
+                        (33 * MiB + 65536 + 16 + 3, 64)]:      # ragged last tile and a byte tail
             ticks = torch.zeros(2, dtype=torch.int64, device="cuda")
             ticks[0] = -1
             g.launch_wg_put_timed(0, 1, 70 * MiB + 16, 32, n, n_wg, 3, ticks)
@@ -182,10 +184,10 @@ def test_timed_put_of_long_messages_moves_the_same_bytes_on_both_long_message_pa
             assert_heaps_equal(g, o, upto=144 * MiB, what=f"n {n} by {n_wg} groups")
 
 
-@pytest.mark.parametrize("n_wg", [512, 515, 600])
-def test_long_messages_by_a_chip_filling_grid_take_group_owned_tiles(n_wg):
-    """64 MiB or more by 512 groups or more of one PE, 16-byte-aligned offsets: the launcher runs one
-    group per four 64 KiB tiles and every group owns whole tiles.  Ragged last tile, byte tail, a
+@pytest.mark.parametrize("n_wg", [64, 100, 512, 515, 600])
+def test_long_messages_by_64_groups_or_more_take_group_owned_tiles(n_wg):
+    """32 MiB or more by 64 groups or more of one PE, 16-byte-aligned offsets: the launcher runs at most
+    one group per four 64 KiB tiles and every group owns whole tiles.  Ragged last tile, byte tail, a
     destination 4 KiB, 1 MiB + 4 KiB ... off the source's alignment, put and get."""
     g, o = make_pair(2, 176 * MiB)
     with g:
@@ -203,11 +205,11 @@ def test_long_messages_by_a_chip_filling_grid_take_group_owned_tiles(n_wg):
             assert_heaps_equal(g, o, upto=160 * MiB, what=f"n_wg {n_wg} size {n}")
 
 
-@pytest.mark.parametrize("n_wg", [32, 33, 100, 128, 160])
+@pytest.mark.parametrize("n_wg", [8, 15, 16, 33, 100, 128, 160])
 def test_long_messages_team_forms_on_both_long_message_paths(n_wg):
-    """Team grids of 4 PEs, 33 MiB: below 512 groups in the grid (32, 33, 100 per PE) the virtual
-    blocks, from 128 per PE group-owned tiles -- 128 groups take more than four tiles each, 160 are
-    cut to one group per four tiles; put_all and get_all, ragged last tile and byte tail."""
+    """Team grids of 4 PEs, 33 MiB: below 64 groups in the grid (8, 15 per PE) the virtual blocks, from
+    16 per PE group-owned tiles -- up to 128 groups take more than four tiles each, 160 are cut to one
+    group per four tiles; put_all and get_all, ragged last tile and byte tail."""
     g, o = make_pair(4, 80 * MiB)
     with g:
         fill_random(g, o, 8, upto=76 * MiB)
