@@ -67,6 +67,28 @@ def test_shapes(npes, n, n_wg):
                     write_both(g, o, p, 2 * MiB, np.full(n * np.dtype(DTYPES[dtype]).itemsize, 0x5A, np.uint8))
 
 
+@pytest.mark.parametrize("npes,n_wg", [(2, 8), (2, 100), (3, 64)])
+def test_split_on_group_owned_tiles(npes, n_wg):
+    """Slices of 64 tiles of 64 KiB plus a ragged rest per PE (the split form then walks group-owned
+    tiles), an element tail, fewer and more groups than tiles; 2-byte and 8-byte elements."""
+    nvec = npes * (64 * 4096 + 1000) - 3
+    g, o = make_pair(npes, 40 * MiB)
+    with g:
+        fill_random(g, o, 78, upto=36 * MiB)
+        for dtype, op, tail in [(S.SHM_INT16, S.SHM_OP_MAX, 5), (S.SHM_UINT64, S.SHM_OP_SUM, 1)]:
+            width = np.dtype(DTYPES[dtype]).itemsize
+            n = nvec * (16 // width) + tail
+            o.reduce(18 * MiB + 16, 4096, n, DTYPES[dtype], OPS[op])
+            for algo in (S.SHM_REDUCE_SPLIT, S.SHM_REDUCE_DUPLICATE):
+                g.launch_reduce(18 * MiB + 16, 4096, n, dtype, op, n_wg, algo)
+                g.barrier_all()
+                assert_heaps_equal(g, o, upto=36 * MiB, what=f"{dtype} {op} algo {algo}")
+                for p in range(npes):
+                    g.write(p, 18 * MiB + 16, np.full(n * width, 0x5A, np.uint8))
+            for p in range(npes):
+                write_both(g, o, p, 18 * MiB + 16, np.full(n * width, 0x5A, np.uint8))
+
+
 def test_full_size_sum_matches_the_f32_entry_point_and_the_oracle():
     # configuration 5's vector length (16 Mi elements, 8 PEs): int32 sum against the oracle, and the
     # float32 sum of the matrix against the dedicated float32 entry point

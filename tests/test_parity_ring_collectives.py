@@ -121,6 +121,28 @@ def test_reduce_sum_f32(algo, npes, nelems, n_wg, soff, doff):
         assert (np.abs(got - r["f64"]) <= 1e-6 * r["abs"]).all()      # and within the stated tolerance of the exact sum
 
 
+@pytest.mark.parametrize("npes,n_wg", [(2, 8), (2, 100), (3, 64)])
+def test_reduce_sum_f32_split_on_group_owned_tiles(npes, n_wg):
+    """A split reduction whose per-PE slice has 64 or more 64 KiB tiles walks them as group-owned tiles:
+    slices of 64 tiles plus a ragged rest, a scalar tail, fewer and more groups than tiles; also the
+    duplicate form of the same size."""
+    nvec = npes * (64 * 4096 + 1000) - 3
+    nelems = 4 * nvec + 3
+    g, o = make_pair(npes, 40 * MiB)
+    with g:
+        fill_random(g, o, 23, upto=36 * MiB)
+        src, dst = 4096, 18 * MiB + 16
+        for p in range(npes):
+            write_both(g, o, p, src, synth.c5_reduce_source(p, nelems))
+        r = o.reduce_sum_f32(dst, src, nelems)
+        for algo in (S.SHM_REDUCE_SPLIT, S.SHM_REDUCE_DUPLICATE):
+            g.launch_reduce_sum_f32(dst, src, nelems, n_wg, algo)
+            g.barrier_all()
+            assert_heaps_equal(g, o, upto=36 * MiB, what=f"algo {algo}")
+            for p in range(npes):
+                g.write(p, dst, np.full(4 * nelems, 0x5A, np.uint8))
+
+
 @pytest.mark.timeout(900)
 def test_config5_full_size():
     """8 PEs: fcollect of 64 MiB int32 per PE into 512 MiB, and a 16M-element float32 sum-reduce."""
