@@ -227,7 +227,9 @@ int shm_launch_wg_get_all(shm_ctx *ctx, int pe_shift, uint64_t dst_off, uint64_t
  * latency of the work-group put as issued from a running kernel): one kernel of n_wg groups on
  * me's stream performs the same put `reps` times, each followed by the group's quiet, and reads
  * the device wall clock before and after.  dev_ticks (device pointer to two uint64, initialised by
- * the caller to UINT64_MAX and 0) receives the earliest start and the latest end over all groups,
+ * the caller to UINT64_MAX and 0) receives the earliest start and the latest end over the groups that
+ * have a share of the message (a group without one returns from every put at once; when it is started is
+ * launch overhead),
  * combined with atomic min/max so that several launches can share one pair.  shm_wall_clock_khz
  * gives the tick rate. */
 int shm_launch_wg_put_timed(shm_ctx *ctx, int me, int pe, uint64_t dst_off, uint64_t src_off, size_t n, int n_wg, int reps,

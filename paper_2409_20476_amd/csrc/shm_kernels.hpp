@@ -112,7 +112,8 @@ __global__ __launch_bounds__(SHMK_WG) void shmk_stream_probe(shm_dev_ctx c, uint
 
 // The same put repeated `reps` times inside one kernel, each followed by the group's quiet, with the
 // device clock read before the first and after the last: the cost of a put issued from a running
-// kernel, free of any launch overhead.  ticks[0] = earliest start, ticks[1] = latest end over groups.
+// kernel, free of any launch overhead.  ticks[0] = earliest start, ticks[1] = latest end over the groups
+// that have a share of the message.
 // tiles != 0: long message on group-owned tiles (the launcher's choice, as for an untimed put).
 __global__ __launch_bounds__(SHMK_WG) void shmk_wg_put_timed(shm_dev_ctx c, uint64_t dst_off, uint64_t src_off, size_t n, int me, int pe,
                                                              int reps, unsigned long long *ticks, int tiles)
@@ -128,7 +129,9 @@ __global__ __launch_bounds__(SHMK_WG) void shmk_wg_put_timed(shm_dev_ctx c, uint
         if (mine) shmx_quiet_wg(c);
     }
     const unsigned long long t1 = wall_clock64();
-    if (threadIdx.x == 0) {
+    // Only the groups that moved bytes report: a group without a share returns from every put at
+    // once, and when the dispatcher gets round to starting it is launch overhead, not part of the put.
+    if (threadIdx.x == 0 && mine) {
         atomicMin(&ticks[0], t0);
         atomicMax(&ticks[1], t1);
     }
