@@ -9,9 +9,7 @@
 typedef float shm_f32x4 __attribute__((ext_vector_type(4)));
 
 // Split reductions walk a PE's slice on group-owned 64 KiB tiles from this many tiles per PE.
-#ifndef SHMK_OWNED_MIN_TILES
 #define SHMK_OWNED_MIN_TILES 64
-#endif
 
 // ---- work-group put / get, one PE or a team of PEs in one grid ----------------------------
 // PE me = me0 + blockIdx.y targets PE (me + shift) mod npes; group blockIdx.x of gridDim.x takes
