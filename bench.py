@@ -279,23 +279,28 @@ def crossover_at_other_queue_count(queues):
 
 
 def placement_spread(torch, S, g, args):
-    """The headline put at nine placements of the destination relative to the source (HBM channel
-    hashing makes the copy rate depend on it): percent of the HBM copy roofline, HIP events."""
-    npes, n = 8, 256 * MiB
-    region = g.malloc(2 * n + 64 * MiB)
+    """The team put at nine placements of the destination relative to the source (HBM channel
+    hashing can make a copy's rate depend on it), at the headline size and at 64 MiB per PE (the
+    front form): percent of the HBM copy roofline, HIP events."""
+    npes = 8
     shifts = (0, 4096, 8192, 65536, MiB, MiB + 4096, 2 * MiB, 16 * MiB + 8192, 64 * MiB - 4096)
+    out = {"note": "8 PEs x 1024 groups, destination = source + message size + shift"}
     g.set_team_sync(False)
-    pcts = {}
-    for sh in shifts:
-        dst = region + n + sh
-        ms = min(time_on_stream(torch, g.streams[0], lambda: g.launch_wg_put_all(1, dst, region, n, 1024, S.SHM_PATH_LDST), 5)
-                 for _ in range(4))
-        pcts[str(sh)] = 100.0 * 2 * npes * n / ms / 1e6 / HBM_PEAK_GBS
+    for n in (256 * MiB, 64 * MiB):
+        region = g.malloc(2 * n + 64 * MiB)
+        pcts = {}
+        for sh in shifts:
+            dst = region + n + sh
+            ms = min(time_on_stream(torch, g.streams[0], lambda: g.launch_wg_put_all(1, dst, region, n, 1024, S.SHM_PATH_LDST), 5)
+                     for _ in range(4))
+            pcts[str(sh)] = 100.0 * 2 * npes * n / ms / 1e6 / HBM_PEAK_GBS
+        g.free(region)
+        v = sorted(pcts.values())
+        suffix = "" if n == 256 * MiB else f"_{n // MiB}mib"
+        out["pct_by_destination_shift_bytes" + suffix] = pcts
+        out["pct_min_med_max" + suffix] = [v[0], v[len(v) // 2], v[-1]]
     g.set_team_sync(True)
-    g.free(region)
-    v = sorted(pcts.values())
-    return {"pct_by_destination_shift_bytes": pcts, "pct_min_med_max": [v[0], v[len(v) // 2], v[-1]],
-            "note": "8 PEs x 256 MiB x 1024 groups, destination = source + 256 MiB + shift"}
+    return out
 
 
 def hbm_ceilings(torch, S, g, args):
@@ -882,6 +887,7 @@ def summarise(extras, cpu_legs):
         }
         if "placement" in r:
             out["c2"]["placement_pct_min_med_max"] = r["placement"]["pct_min_med_max"]
+            out["c2"]["placement_pct_min_med_max_64mib"] = r["placement"].get("pct_min_med_max_64mib")
     if "hbm_ceilings" in extras:
         hc = extras["hbm_ceilings"]
         out["hbm_ceilings_pct"] = {**{k: v["frac_hbm"] * 100 for k, v in hc["kernels"].items()},

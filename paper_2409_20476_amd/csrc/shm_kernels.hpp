@@ -31,8 +31,9 @@ __global__ __launch_bounds__(SHMK_WG) void shmk_wg_rma(shm_dev_ctx c, uint64_t d
 // its first load counts: the kernel takes the heap as base address and partition stride (the
 // library's partitions are equally spaced) instead of the whole device view -- one scalar load of
 // the arguments, no table look-up.
+// front != 0: the groups sweep the message together instead (shm_copy_front).
 __global__ __launch_bounds__(SHMK_WG) void shmk_wg_rma_tiles(char *base, uint64_t stride, uint64_t dst_off, uint64_t src_off, size_t n,
-                                                             int npes, int me0, int shift, int is_get)
+                                                             int npes, int me0, int shift, int is_get, int front)
 {
     const int me = me0 + blockIdx.y;
     int pe = me + shift;
@@ -40,7 +41,7 @@ __global__ __launch_bounds__(SHMK_WG) void shmk_wg_rma_tiles(char *base, uint64_
     // one copy of the tile walk for both directions: only the two addresses differ
     char *d = base + static_cast<uint64_t>(is_get ? me : pe) * stride + dst_off;
     const char *s = base + static_cast<uint64_t>(is_get ? pe : me) * stride + src_off;
-    shmx_copy_tiles_wg<SHMK_WG / 64>(d, s, n, blockIdx.x, gridDim.x);
+    shmx_copy_tiles_wg<SHMK_WG / 64>(d, s, n, blockIdx.x, gridDim.x, front != 0);
 }
 
 // One-direction ceilings of the memory system with the access forms of the long-message put: the

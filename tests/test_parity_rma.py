@@ -205,11 +205,12 @@ def test_long_messages_by_64_groups_or_more_take_group_owned_tiles(n_wg):
             assert_heaps_equal(g, o, upto=160 * MiB, what=f"n_wg {n_wg} size {n}")
 
 
-@pytest.mark.parametrize("n_wg", [8, 15, 16, 33, 100, 128, 160])
-def test_long_messages_team_forms_on_both_long_message_paths(n_wg):
+@pytest.mark.parametrize("n_wg", [8, 15, 16, 33, 100, 128, 160, 512, 600])
+def test_long_messages_team_forms_on_all_long_message_paths(n_wg):
     """Team grids of 4 PEs, 33 MiB: below 64 groups in the grid (8, 15 per PE) the virtual blocks, from
     16 per PE group-owned tiles -- up to 128 groups take more than four tiles each, 160 are cut to one
-    group per four tiles; put_all and get_all, ragged last tile and byte tail."""
+    group per four tiles --, from 512 per PE the front swept by 512 groups per PE; put_all and get_all,
+    a rest after the whole steps of the front, ragged last tile and byte tail."""
     g, o = make_pair(4, 80 * MiB)
     with g:
         fill_random(g, o, 8, upto=76 * MiB)
