@@ -395,21 +395,24 @@ unsigned tile_groups(size_t n, int n_wg, size_t tiles_per_group = TILES_PER_GROU
     return static_cast<unsigned>(want < static_cast<size_t>(n_wg) ? (want ? want : 1) : n_wg);
 }
 
-// Team puts and gets of 32-128 MiB per PE by 512 or more groups per PE are swept as a front by 512
-// groups per PE (shm_copy_front; a lane's successive accesses are then 2 MiB apart).  Measured on
-// MI355X, 8 PEs x 1024 groups asked for, two placements each: 32 MiB 80.6 % of the HBM roofline (tiles
-// 78.6), 48 MiB 81.3 (79.8), 64 MiB 81.0-81.3 (78.9), 96 MiB 80.4-80.9 (79.4), 128 MiB 79.8-80.1
-// (78.1-79.1); beyond that the front falls behind (192 MiB 74-78, 256 MiB 73-77 against 79-80 on
-// tiles).  4 PEs x 64 / 128 MiB: 79.0 / 79.9 (tiles 77.5 / 79.0).  Other group counts per PE lose (256:
-// -1 point, 1024: -7), and eight separate per-PE launches lose 11 points as fronts: only team grids
-// of 4 to 8 PEs -- the shapes measured -- take this form.
-constexpr size_t FRONT_MIN_BYTES = size_t(32) << 20, FRONT_MAX_BYTES = size_t(128) << 20;
-constexpr int FRONT_GROUPS_PER_PE = 512;
+// Team puts and gets of 32 MiB or more per PE by 512 or more groups per PE are swept as fronts:
+// the message is cut into segments of 32 MiB and 512 groups sweep each segment together
+// (shm_copy_front; a lane's successive accesses are 2 MiB apart, a group moves 64 KiB of its segment).
+// Measured on MI355X, 8 PEs x 1024 groups asked for, three placements each: 64 MiB 80.4-80.8 % of the
+// HBM roofline (tiles 78.9), 96 MiB 80.7 (79.4), 128 MiB 80.6-81.0 (78.1-79.1), 192 MiB 79.5-80.7
+// (78.2), 256 MiB 79.8-80.7 (78.9-79.7).  One front over the whole message is level up to 64 MiB and
+// falls behind beyond (128 MiB 79.7, 192 MiB 74-78, 256 MiB 73-77: the longer the sweep, the further
+// the groups drift apart); segments of 16 MiB lose a point, of 8 MiB seven.  4 PEs x 64 / 128 MiB, one
+// front: 79.0 / 79.9 (tiles 77.5 / 79.0).  Other group counts per segment lose (256: -1 point, 1024:
+// -7), and eight separate per-PE launches lose 11 points as fronts: only team grids of 4 to 8 PEs --
+// the shapes measured -- take this form.
+constexpr size_t FRONT_MIN_BYTES = size_t(32) << 20, FRONT_SEG_BYTES = size_t(32) << 20;
+constexpr int FRONT_GROUPS_PER_SEGMENT = 512;
 bool use_front(uint64_t dst_off, uint64_t src_off, size_t n, int n_wg, int grid_pes)
 {
-    return ((dst_off | src_off) & 15) == 0 && n >= FRONT_MIN_BYTES && n <= FRONT_MAX_BYTES && n_wg >= FRONT_GROUPS_PER_PE &&
-           grid_pes >= 4 && grid_pes <= 8;
+    return ((dst_off | src_off) & 15) == 0 && n >= FRONT_MIN_BYTES && n_wg >= FRONT_GROUPS_PER_SEGMENT && grid_pes >= 4 && grid_pes <= 8;
 }
+unsigned front_segments(size_t n) { return static_cast<unsigned>((n + FRONT_SEG_BYTES - 1) / FRONT_SEG_BYTES); }
 
 // Long, 16-byte-aligned messages moved by a grid that fills the chip take the group-owned-tile kernel.
 bool use_tiles(uint64_t dst_off, uint64_t src_off, size_t n, int n_wg, int grid_pes)
@@ -438,7 +441,7 @@ int wg_rma(shm_ctx *c, int me, int pe, uint64_t dst_off, uint64_t src_off, size_
     const int shift = (pe - me + c->npes) % c->npes;
     if (use_tiles(dst_off, src_off, n, n_wg, 1)) {
         hipLaunchKernelGGL(shmk_wg_rma_tiles, dim3(tile_groups(n, n_wg), 1), dim3(SHMK_WG), TILES_LDS_BYTES, c->stream[me], c->base,
-                           static_cast<uint64_t>(c->part_bytes), dst_off, src_off, n, c->npes, me, shift, is_get, 0);
+                           static_cast<uint64_t>(c->part_bytes), dst_off, src_off, n, c->npes, me, shift, is_get, 0, size_t(0));
         return launched("work-group put/get (tiles)");
     }
     hipLaunchKernelGGL(shmk_wg_rma, dim3(n_wg, 1), dim3(SHMK_WG), 0, c->stream[me], dev_view(c), dst_off, src_off, n, me, shift,
@@ -478,11 +481,12 @@ int wg_rma_all(shm_ctx *c, int pe_shift, uint64_t dst_off, uint64_t src_off, siz
     if (c->team_sync)
         if (int r = team_join(c)) return r;
     if (use_front(dst_off, src_off, n, n_wg, c->npes)) {
-        hipLaunchKernelGGL(shmk_wg_rma_tiles, dim3(FRONT_GROUPS_PER_PE, c->npes), dim3(SHMK_WG), TILES_LDS_BYTES, c->stream[0],
-                           c->base, static_cast<uint64_t>(c->part_bytes), dst_off, src_off, n, c->npes, 0, pe_shift, is_get, 1);
+        hipLaunchKernelGGL(shmk_wg_rma_tiles, dim3(FRONT_GROUPS_PER_SEGMENT * front_segments(n), c->npes), dim3(SHMK_WG), TILES_LDS_BYTES,
+                           c->stream[0], c->base, static_cast<uint64_t>(c->part_bytes), dst_off, src_off, n, c->npes, 0, pe_shift, is_get,
+                           FRONT_GROUPS_PER_SEGMENT, FRONT_SEG_BYTES);
     } else if (use_tiles(dst_off, src_off, n, n_wg, c->npes)) {
         hipLaunchKernelGGL(shmk_wg_rma_tiles, dim3(tile_groups(n, n_wg), c->npes), dim3(SHMK_WG), TILES_LDS_BYTES, c->stream[0], c->base,
-                           static_cast<uint64_t>(c->part_bytes), dst_off, src_off, n, c->npes, 0, pe_shift, is_get, 0);
+                           static_cast<uint64_t>(c->part_bytes), dst_off, src_off, n, c->npes, 0, pe_shift, is_get, 0, size_t(0));
     } else {
         hipLaunchKernelGGL(shmk_wg_rma, dim3(n_wg, c->npes), dim3(SHMK_WG), 0, c->stream[0], dev_view(c), dst_off, src_off, n, 0,
                            pe_shift, is_get);

@@ -399,14 +399,15 @@ __device__ __forceinline__ void shm_copy_tiles(char *dst, const char *src, size_
 }
 
 // ------------------------------------------------------------------------------------------
-// A front: the third dealing, for messages of a few tens of MiB moved by a chip-filling grid.  The
-// nparts groups sweep the message together: in step k group g moves the 4 KiB piece k * nparts + g
-// (one vector per lane), so what the chip touches at one moment is a few compact windows -- the
-// order in which this memory system both reads and writes fastest when it does only one of the two.
-// A lane keeps two steps in flight and stores the vector of two steps ago right before it loads
-// the next one into the same register (loads and stores alternate one by one).  Measured on MI355X,
-// 8 PEs x 512 groups: 82 % of the HBM roofline at 32-64 MiB per PE for every placement tried (tiles:
-// 79 %), 78-79 % at 96-128 MiB and falling beyond (73 % at 192 MiB), where tiles stay at 79-80 %.
+// A front: the third dealing, for long messages moved by a chip-filling team grid.  The nparts
+// groups sweep a segment of the message together: in step k group g moves the 4 KiB piece
+// k * nparts + g (one vector per lane), so what the chip touches at one moment is a few compact
+// windows -- the order in which this memory system both reads and writes fastest when it does only
+// one of the two.  A lane keeps two steps in flight and stores the vector of two steps ago right
+// before it loads the next one into the same register (loads and stores alternate one by one).
+// Measured on MI355X, 8 PEs, 512 groups per segment of 32 MiB: 80-81 % of the HBM roofline from 64
+// to 256 MiB per PE for every placement tried (group-owned tiles: 78-80 %).  A sweep should stay
+// short: one front over 192-256 MiB measures 73-78 %, because the groups drift apart.
 // dst and src are 16-byte aligned, n is a multiple of 16.
 // ------------------------------------------------------------------------------------------
 __device__ __forceinline__ void shm_copy_front(char *dst, const char *src, size_t n, unsigned part, unsigned nparts)

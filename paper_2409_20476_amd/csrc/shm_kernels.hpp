@@ -31,9 +31,11 @@ __global__ __launch_bounds__(SHMK_WG) void shmk_wg_rma(shm_dev_ctx c, uint64_t d
 // its first load counts: the kernel takes the heap as base address and partition stride (the
 // library's partitions are equally spaced) instead of the whole device view -- one scalar load of
 // the arguments, no table look-up.
-// front != 0: the groups sweep the message together instead (shm_copy_front).
+// front != 0: the message is cut into segments of seg_bytes (a multiple of 16; the last one takes the
+// rest) and `front` groups sweep one segment together (shm_copy_front); the groups of a segment are
+// consecutive in the dispatch order, so the chip works on a few segments at a time.
 __global__ __launch_bounds__(SHMK_WG) void shmk_wg_rma_tiles(char *base, uint64_t stride, uint64_t dst_off, uint64_t src_off, size_t n,
-                                                             int npes, int me0, int shift, int is_get, int front)
+                                                             int npes, int me0, int shift, int is_get, int front, size_t seg_bytes)
 {
     const int me = me0 + blockIdx.y;
     int pe = me + shift;
@@ -41,7 +43,14 @@ __global__ __launch_bounds__(SHMK_WG) void shmk_wg_rma_tiles(char *base, uint64_
     // one copy of the tile walk for both directions: only the two addresses differ
     char *d = base + static_cast<uint64_t>(is_get ? me : pe) * stride + dst_off;
     const char *s = base + static_cast<uint64_t>(is_get ? pe : me) * stride + src_off;
-    shmx_copy_tiles_wg<SHMK_WG / 64>(d, s, n, blockIdx.x, gridDim.x, front != 0);
+    if (front) {
+        const unsigned per = static_cast<unsigned>(front), seg = blockIdx.x / per;
+        const size_t lo = static_cast<size_t>(seg) * seg_bytes;          // the host launches exactly ceil(n / seg_bytes) segments
+        const size_t len = n - lo < seg_bytes ? n - lo : seg_bytes;
+        shmx_copy_tiles_wg<SHMK_WG / 64>(d + lo, s + lo, len, blockIdx.x % per, per, true);
+        return;
+    }
+    shmx_copy_tiles_wg<SHMK_WG / 64>(d, s, n, blockIdx.x, gridDim.x, false);
 }
 
 // One-direction ceilings of the memory system with the access forms of the long-message put: the
