@@ -927,9 +927,13 @@ int shm_launch_wg_put_timed(shm_ctx *c, int me, int pe, uint64_t dst_off, uint64
     if (c->no_device) return no_device("shm_launch_wg_put_timed");
     if (int r = begin_pe_launch(c, me)) return r;
     const bool tiles = use_tiles(dst_off, src_off, n, n_wg, 1);
-    // a put that its own quiet follows drains the group's stores before the group can go on: eight
-    // tiles per group and put instead of four halve what that costs (measured 69 -> 7x % of the roofline)
-    hipLaunchKernelGGL(shmk_wg_put_timed, dim3(tiles ? tile_groups(n, n_wg, 2 * TILES_PER_GROUP) : n_wg), dim3(SHMK_WG), tiles ? TILES_LDS_BYTES : 0,
+    // A put that its own quiet follows drains the group's stores before the group can go on, so the
+    // groups should be few and long-lived: eight tiles per group and put, and from 128 groups per PE
+    // on rather longer runs than more groups (measured with 8 PEs at once, 8 / 16 / 32 tiles per group:
+    // 64 MiB 70.6 / 57.8 / 38.0 % of the roofline, 128 MiB 72.6 / 74.5 / 60.4, 256 MiB 73.1 / 75.8 / 76.0).
+    const size_t n_tiles = (n + TILE_BYTES - 1) / TILE_BYTES;
+    const size_t per_group = n_tiles / 128 > 2 * TILES_PER_GROUP ? n_tiles / 128 : 2 * TILES_PER_GROUP;
+    hipLaunchKernelGGL(shmk_wg_put_timed, dim3(tiles ? tile_groups(n, n_wg, per_group) : n_wg), dim3(SHMK_WG), tiles ? TILES_LDS_BYTES : 0,
                        c->stream[me], dev_view(c), dst_off, src_off, n, me, pe, reps, reinterpret_cast<unsigned long long *>(dev_ticks),
                        tiles ? 1 : 0);
     return launched("timed work-group put");
