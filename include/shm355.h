@@ -211,7 +211,9 @@ int    shm_stream_used(shm_ctx *ctx, int pe);
 /* Work-group put/get (paper section "Proposed Device APIs", the work_group extensions; section
  * "Remote Memory Access": multi-threaded vectorised copy).  n_wg work-groups of SHM_WG_SIZE
  * threads share the message; which bytes a group moves is not observable and is chosen for the
- * memory system (see shm_device.hpp).  path: LDST = kernel on me's stream, SDMA = copy engine,
+ * memory system (see shm_device.hpp) -- including how many of the n_wg groups take part: a launch may
+ * run fewer groups than it was asked for (long messages, short messages dealt to very many groups,
+ * long collectives), never more.  path: LDST = kernel on me's stream, SDMA = copy engine,
  * MEMCPY = runtime copy on me's stream, AUTO = LDST or SDMA by cutover.  Any byte alignment; n may
  * be 0. */
 int shm_launch_wg_put(shm_ctx *ctx, int me, int pe, uint64_t dst_off, uint64_t src_off, size_t n, int n_wg, int path);
