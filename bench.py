@@ -874,7 +874,7 @@ def summarise(extras, cpu_legs):
         rows = {q["bytes"] >> 20: q for q in r["rows"] if q["bytes"] >= 64 * MiB}
         out["c2"] = {
             "pct_of_hbm_roofline_by_mib": {
-                "team_grid_wg1024": {str(m): pct(q["team_wg1024_event_gbs"]) for m, q in rows.items()},
+                "team_grid_wg1024": {str(q["bytes"] >> 20): pct(q["team_wg1024_event_gbs"]) for q in r["rows"] if q["bytes"] >= 8 * MiB},
                 "per_pe_streams_wg1024": {str(m): pct(8 * q["bytes"] / q["ldst_wg1024_host_us"] / 1e3) for m, q in rows.items()},
                 "per_pe_streams_wg64": {str(m): pct(8 * q["bytes"] / q["ldst_wg64_host_us"] / 1e3) for m, q in rows.items()},
                 "put_plus_quiet_inside_kernel_wg1024": {str(m): pct(q["ldst_wg1024_gbs"]) for m, q in rows.items()},

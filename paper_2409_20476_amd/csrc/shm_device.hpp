@@ -199,18 +199,22 @@ struct shm_deal {
     size_t rem_step;  // lanes in all groups together
 };
 
-// How many of the `nparts` groups take part in a message of nvec 16-byte vectors.  A group's share
-// has a fixed price -- its barriers, the drain of its stores and its part in the quiet that follows
-// a put -- so beyond SHM_DEAL_ALWAYS_GROUPS groups a message is dealt to further groups only while
-// each still gets SHM_MIN_SHARE_BYTES; the others return at once, with nothing to complete.
-// Measured on MI355X (8 PEs, put + quiet from inside a kernel of 1024 groups per PE): 16 MiB per PE
-// 1.0 -> 1.6 TB/s, 32 MiB 1.0 -> 2.0 TB/s; up to 64 groups the dealing is what it was.
+// How many of the `nparts` groups take part in a message of nvec 16-byte vectors when every group is
+// to get at least min_share bytes (0: all of them, the default).  A group's share has a fixed price
+// when the group completes it by itself -- the drain of its stores and its part in the quiet that
+// follows its put -- so a kernel that puts and then quiets in every group (shmx_putmem_parts followed
+// by shmx_quiet_wg) passes SHM_MIN_SHARE_BYTES: beyond SHM_DEAL_ALWAYS_GROUPS groups the message is
+// then dealt to further groups only while each still gets that much, and the others return at once,
+// with nothing to complete.  Measured on MI355X (8 PEs, put + quiet inside a kernel of 1024 groups
+// per PE): 16 MiB per PE 1.0 -> 1.9 TB/s, 32 MiB 1.0 -> 2.1 TB/s.  A put that the END of its kernel
+// completes wants the opposite, every group at work (8 PEs x 8 MiB by 1024 groups each: 75 % of the
+// HBM roofline against 54 % on 64 groups), hence the default.
 constexpr size_t SHM_MIN_SHARE_BYTES = size_t(128) << 10;
 constexpr unsigned SHM_DEAL_ALWAYS_GROUPS = 64;
-__device__ __forceinline__ unsigned shm_deal_groups(size_t nvec, unsigned nparts)
+__device__ __forceinline__ unsigned shm_deal_groups(size_t nvec, unsigned nparts, size_t min_share)
 {
-    if (nparts <= SHM_DEAL_ALWAYS_GROUPS) return nparts;
-    size_t want = nvec / (SHM_MIN_SHARE_BYTES / 16);
+    if (min_share < 16 || nparts <= SHM_DEAL_ALWAYS_GROUPS) return nparts;
+    size_t want = nvec / (min_share / 16);
     if (want < SHM_DEAL_ALWAYS_GROUPS) want = SHM_DEAL_ALWAYS_GROUPS;
     return want >= nparts ? nparts : static_cast<unsigned>(want & ~static_cast<size_t>(7));      // whole virtual blocks of 8
 }
@@ -236,10 +240,10 @@ __device__ __forceinline__ shm_deal shm_deal_make(size_t nvec, unsigned part, un
 // Whether group `part` moves any byte of an n-byte message dealt to `nparts` groups of `nthr`
 // threads (a conservative test: true whenever one of its lanes could own a vector).
 template <int U>
-__device__ __forceinline__ bool shm_deal_has_share(size_t n, unsigned part, unsigned nparts, unsigned nthr)
+__device__ __forceinline__ bool shm_deal_has_share(size_t n, unsigned part, unsigned nparts, unsigned nthr, size_t min_share = 0)
 {
     if (part == 0) return n != 0;
-    nparts = shm_deal_groups(n >> 4, nparts);
+    nparts = shm_deal_groups(n >> 4, nparts, min_share);
     if (part >= nparts) return false;
     const shm_deal k = shm_deal_make<U>(n >> 4, part, nparts, 0, nthr);
     return k.vb < k.ntiles || k.rem_lane < ((n + 15) >> 4) + 1;
@@ -272,7 +276,7 @@ __device__ __forceinline__ void shm_copy_body_dealt(shm_u32x4 *d, const shm_u32x
 // Group `part` of `nparts` does its share of copying n bytes, any alignment.  All threads of all
 // groups call this with the same dst/src/n.
 template <int U = 8, int POLICY = SHM_ST_STREAM>
-__device__ __forceinline__ void shm_copy_parts(char *dst, const char *src, size_t n, unsigned part, unsigned nparts)
+__device__ __forceinline__ void shm_copy_parts(char *dst, const char *src, size_t n, unsigned part, unsigned nparts, size_t min_share = 0)
 {
     if (n == 0) return;
     const unsigned tid = threadIdx.x, nthr = blockDim.x;
@@ -289,7 +293,7 @@ __device__ __forceinline__ void shm_copy_parts(char *dst, const char *src, size_
     const char *bs = src + head;
     const uint32_t mis = static_cast<uint32_t>(reinterpret_cast<uintptr_t>(bs) & 15);
     const size_t nvec = body >> 4;
-    nparts = shm_deal_groups(nvec, nparts);
+    nparts = shm_deal_groups(nvec, nparts, min_share);
     if (part >= nparts) return;
     if (mis == 0) {
         shm_copy_body_dealt<U, POLICY>(d, reinterpret_cast<const shm_u32x4 *>(bs), nvec, part, nparts, tid, nthr);
@@ -458,12 +462,12 @@ __device__ __forceinline__ void shm_put_coop(char *dst, const char *src, size_t 
         shm_copy_coop<U, SHM_ST_STREAM>(dst, src, n, tid, nthr);
 }
 template <int U>
-__device__ __forceinline__ void shm_put_parts(char *dst, const char *src, size_t n, unsigned part, unsigned nparts)
+__device__ __forceinline__ void shm_put_parts(char *dst, const char *src, size_t n, unsigned part, unsigned nparts, size_t min_share = 0)
 {
-    if (n <= SHM_PUT_THROUGH_BYTES_PER_THREAD * blockDim.x * shm_deal_groups(n >> 4, nparts))
-        shm_copy_parts<U, SHM_ST_THROUGH>(dst, src, n, part, nparts);
+    if (n <= SHM_PUT_THROUGH_BYTES_PER_THREAD * blockDim.x * shm_deal_groups(n >> 4, nparts, min_share))
+        shm_copy_parts<U, SHM_ST_THROUGH>(dst, src, n, part, nparts, min_share);
     else
-        shm_copy_parts<U, SHM_ST_STREAM>(dst, src, n, part, nparts);
+        shm_copy_parts<U, SHM_ST_STREAM>(dst, src, n, part, nparts, min_share);
 }
 
 // Scalar put and get (paper section "Remote Memory Access": the ishmem_long_p example -- translate
@@ -549,11 +553,14 @@ __device__ __forceinline__ void shmx_getmem_wg(const shm_dev_ctx &c, int me, uin
 // The same for `nparts` work-groups of one PE sharing one message; this group is number `part`.
 // Every thread of every group passes the same offsets and n.  On return this group's share is
 // done; the message is complete when all groups have returned (and delivered after their quiet).
+// min_share: see shm_deal_groups (a kernel whose groups each quiet after the put passes
+// SHM_MIN_SHARE_BYTES and asks shm_deal_has_share, with the same value, which groups have anything to
+// complete).
 __device__ __forceinline__ void shmx_putmem_parts(const shm_dev_ctx &c, int me, uint64_t dst_off, uint64_t src_off, size_t n,
-                                                  int pe, unsigned part, unsigned nparts)
+                                                  int pe, unsigned part, unsigned nparts, size_t min_share = 0)
 {
     __syncthreads();
-    shm_put_parts<8>(shm_ptr(c, dst_off, pe), shm_ptr(c, src_off, me), n, part, nparts);
+    shm_put_parts<8>(shm_ptr(c, dst_off, pe), shm_ptr(c, src_off, me), n, part, nparts, min_share);
     __syncthreads();
 }
 __device__ __forceinline__ void shmx_getmem_parts(const shm_dev_ctx &c, int me, uint64_t dst_off, uint64_t src_off, size_t n,

@@ -127,13 +127,13 @@ __global__ __launch_bounds__(SHMK_WG) void shmk_wg_put_timed(shm_dev_ctx c, uint
                                                              int reps, unsigned long long *ticks, int tiles)
 {
     // groups without a share have nothing to complete
-    const bool mine = tiles ? blockIdx.x < (n + 65535) / 65536 : shm_deal_has_share<8>(n, blockIdx.x, gridDim.x, SHMK_WG);
+    const bool mine = tiles ? blockIdx.x < (n + 65535) / 65536 : shm_deal_has_share<8>(n, blockIdx.x, gridDim.x, SHMK_WG, SHM_MIN_SHARE_BYTES);
     const unsigned long long t0 = wall_clock64();
     for (int r = 0; r < reps; ++r) {
         if (tiles)
             shmx_putmem_tiles<SHMK_WG / 64>(c, me, dst_off, src_off, n, pe, blockIdx.x, gridDim.x);
         else
-            shmx_putmem_parts(c, me, dst_off, src_off, n, pe, blockIdx.x, gridDim.x);
+            shmx_putmem_parts(c, me, dst_off, src_off, n, pe, blockIdx.x, gridDim.x, SHM_MIN_SHARE_BYTES);
         if (mine) shmx_quiet_wg(c);
     }
     const unsigned long long t1 = wall_clock64();

@@ -133,10 +133,11 @@ def test_timed_put_moves_the_same_bytes_and_reports_device_time():
 
 
 @pytest.mark.parametrize("n_wg", [65, 200, 1024])
-def test_more_groups_than_take_part(n_wg):
-    """Beyond 64 groups a message is dealt only to as many groups as get 128 KiB each; the others have
-    no share.  Sizes around the steps of that rule, shifted and aligned sources, put, get, put_signal
-    by all groups, and the timed put whose groups without a share skip their quiet."""
+def test_more_groups_than_vectors_and_the_minimum_share_of_put_then_quiet(n_wg):
+    """Messages asked of 65, 200 and 1024 groups: plain puts and gets deal them to every group that can
+    get a vector; the timed put, whose every group quiets after its share, deals only to as many groups
+    as get 128 KiB each beyond 64 groups, and the others skip their quiet.  Sizes around the steps of
+    that rule, shifted and aligned sources, and a put_signal by all groups."""
     import torch
     g, o = make_pair(2, 64 * MiB)
     with g:
@@ -155,9 +156,11 @@ def test_more_groups_than_take_part(n_wg):
             assert_heaps_equal(g, o, upto=48 * MiB, what=f"n={n} by {n_wg} groups")
         ticks = torch.zeros(2, dtype=torch.int64, device="cuda")
         ticks[0] = -1
-        g.launch_wg_put_timed(1, 0, 20 * MiB + 16, 1 * MiB, 9 * MiB + 48 + 3, n_wg, 3, ticks)
-        g.quiet(1)
-        o.wg_put(1, 20 * MiB + 16, 1 * MiB, 9 * MiB + 48 + 3, 0, n_wg)
+        for m in (9 * MiB + 48 + 3, 8 * MiB + 128 * 1024 * 3 + 16 + 5, 300001):
+            g.launch_wg_put_timed(1, 0, 20 * MiB + 16, 1 * MiB, m, n_wg, 3, ticks)
+            g.quiet(1)
+            o.wg_put(1, 20 * MiB + 16, 1 * MiB, m, 0, n_wg)
+            assert_heaps_equal(g, o, upto=48 * MiB, what=f"timed put of {m} bytes by {n_wg} groups")
         z = np.zeros(8, np.uint8)
         for p in range(2):
             write_both(g, o, p, sig, z)
