@@ -134,7 +134,7 @@ __global__ __launch_bounds__(SHMK_WG) void shmk_wg_put_timed(shm_dev_ctx c, uint
             shmx_putmem_tiles<SHMK_WG / 64>(c, me, dst_off, src_off, n, pe, blockIdx.x, gridDim.x);
         else
             shmx_putmem_parts(c, me, dst_off, src_off, n, pe, blockIdx.x, gridDim.x, SHM_MIN_SHARE_BYTES);
-        if (mine) shmx_quiet_wg(c);
+        if (mine) shmx_quiet_wg(c, tiles || !shm_put_stores_through(n, gridDim.x, SHM_MIN_SHARE_BYTES));
     }
     const unsigned long long t1 = wall_clock64();
     // Only the groups that moved bytes report: a group without a share returns from every put at
@@ -173,7 +173,7 @@ __global__ __launch_bounds__(1024) void shmk_rma_device_initiated(shm_dev_ctx c,
                 shmx_getmem_wg(c, me, d, s, len, pe);
             } else {
                 shmx_putmem_wg(c, me, d, s, len, pe);
-                if (len) shmx_quiet_wg(c);
+                if (len) shmx_quiet_wg(c, !shm_put_stores_through(len));
             }
         } else if (mode == 1) {
             if (is_get)
@@ -186,7 +186,7 @@ __global__ __launch_bounds__(1024) void shmk_rma_device_initiated(shm_dev_ctx c,
                 shmx_getmem_auto_wg(c, me, d, s, len, pe, cutover);
             } else {
                 shmx_putmem_auto_wg(c, me, d, s, len, pe, cutover);
-                if (!engine && len) shmx_quiet_wg(c);
+                if (!engine && len) shmx_quiet_wg(c, !shm_put_stores_through(len));
             }
         } else if (mode == 3) {
             if (is_get)
