@@ -827,7 +827,7 @@ def kernel_source_sha256():
     sources says nothing about the kernels measured now."""
     import hashlib
     h = hashlib.sha256()
-    for name in ("shm_device.hpp", "shm_kernels.hpp"):
+    for name in ("shm_device.hpp", "shm_kernels.hpp", "shm_release_algo.hpp"):
         with open(os.path.join(ROOT, "paper_2409_20476_amd", "csrc", name), "rb") as f:
             h.update(f.read())
     return h.hexdigest()

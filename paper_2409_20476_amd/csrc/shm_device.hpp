@@ -9,6 +9,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include "shm_release_algo.hpp"
+
 #define SHM_MAX_PES 32
 
 // Per-launch view of the context, passed to kernels by value (it lives in the kernel-argument
@@ -634,19 +636,9 @@ __device__ __forceinline__ void shmx_quiet_wg()
 // hundreds of groups.  But ONE write-back covers every store that had reached that L2 when it
 // began, whoever issued it.  So the groups of an XCD share their releases through one 64-bit word
 // per XCD (in the library's tail of PE 0's partition; the XCD number is the hardware's XCC_ID
-// register):
-//   bit 0       set while one group is writing back (the lock)
-//   bits 63..1  number of shared write-backs that have FINISHED on this XCD
-// Every wave first waits for the acknowledgement of its own stores (s_waitcnt vmcnt(0): they are in
-// the L2 or beyond).  The leader then sets bit 0 with one fetch-or.  If the bit was clear the
-// leader is the one who writes back: agent-scope release, then ONE store that publishes count + 1
-// and clears the lock -- two memory round trips in all when nobody else is releasing.  If the bit
-// was set, with count c, write-back c + 1 is under way and may have begun before this group's
-// stores arrived; the group is covered by write-back c + 2, which can only begin after c + 1 has
-// ended, i.e. after this moment.  The leader polls the word: count >= c + 2 ends the wait; a clear
-// lock lets it try to become the one who writes back.  The holder of the lock never waits for
-// anybody, so every wait ends; waits are bounded all the same, and a leader that has polled for
-// too long releases for itself.  Small grids (fewer than SHMD_QUIET_SHARED_MIN_GROUPS groups)
+// register) by the protocol of shm_release_algo.hpp.  Every wave first waits for the
+// acknowledgement of its own stores (s_waitcnt vmcnt(0): they are in the L2 or beyond); then the
+// group's leader runs the protocol.  Small grids (fewer than SHMD_QUIET_SHARED_MIN_GROUPS groups)
 // release directly: an atomic costs more than a write-back nobody queues for.
 #define SHMD_INTERNAL_QUIET 33280u            // 8 words, 128 bytes apart
 #define SHMD_QUIET_SHARED_MIN_GROUPS 64u
@@ -659,41 +651,20 @@ __device__ __forceinline__ unsigned shm_xcc_id()
     return v & 7u;
 }
 
+struct shm_release_device_ops {
+    unsigned long long *word;
+    __device__ __forceinline__ unsigned long long fetch_or_lock() { return __hip_atomic_fetch_or(word, 1ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
+    __device__ __forceinline__ unsigned long long load() { return __hip_atomic_load(word, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
+    __device__ __forceinline__ void store(unsigned long long v) { __hip_atomic_store(word, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
+    __device__ __forceinline__ void write_back() { __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent"); }      // the write-back, waited for
+    __device__ __forceinline__ void pause() { __builtin_amdgcn_s_sleep(2); }
+};
+
 // One thread; the stores it speaks for are acknowledged.
 __device__ __forceinline__ void shm_release_shared(const shm_dev_ctx &c)
 {
-    unsigned long long *word =
-        reinterpret_cast<unsigned long long *>(c.base[0] + c.internal_off + SHMD_INTERNAL_QUIET + 128u * shm_xcc_id());
-    unsigned long long need = 0;                 // 0: no write-back was under way when this group arrived
-    // With the lock held (v = the word before our fetch-or): write back unless a write-back that
-    // covers this group has finished meanwhile, then publish the count and clear the lock.
-    auto as_holder = [&](unsigned long long v) {
-        if (need == 0 || (v >> 1) < need) {
-            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");          // the write-back, waited for
-            v += 2ull;
-        }
-        __hip_atomic_store(word, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    };
-    unsigned long long v = __hip_atomic_fetch_or(word, 1ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    if (!(v & 1ull)) {
-        as_holder(v);
-        return;
-    }
-    need = (v >> 1) + 2ull;
-    for (int spin = 0; spin < SHMD_QUIET_SPIN_LIMIT; ++spin) {
-        __builtin_amdgcn_s_sleep(2);
-        v = __hip_atomic_load(word, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        if ((v >> 1) >= need) return;
-        if (!(v & 1ull)) {
-            v = __hip_atomic_fetch_or(word, 1ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            if (!(v & 1ull)) {
-                as_holder(v);
-                return;
-            }
-            if ((v >> 1) >= need) return;
-        }
-    }
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
+    shm_release_device_ops ops{reinterpret_cast<unsigned long long *>(c.base[0] + c.internal_off + SHMD_INTERNAL_QUIET + 128u * shm_xcc_id())};
+    shm_release_shared_algo(ops, SHMD_QUIET_SPIN_LIMIT);
 }
 
 // bulk == false says that the group's puts since its last quiet all stored write-through
