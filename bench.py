@@ -299,6 +299,26 @@ def placement_spread(torch, S, g, args):
         suffix = "" if n == 256 * MiB else f"_{n // MiB}mib"
         out["pct_by_destination_shift_bytes" + suffix] = pcts
         out["pct_min_med_max" + suffix] = [v[0], v[len(v) // 2], v[-1]]
+    # ... and at sixteen random placements (seeded; offsets in steps of 2 MiB, the last four of 64 KiB) anywhere in a
+    # 1000 MiB region, for the form the launcher takes for 1024 groups per PE (fronts) and the one it takes for 511 (tiles)
+    import random
+    rnd = random.Random(20476)
+    span = 1000 * MiB
+    region = g.malloc(span)
+    for n in (256 * MiB, 64 * MiB):
+        rows = {"fronts_wg1024": [], "tiles_wg511": []}
+        for k in range(16):
+            gran = 2 * MiB if k < 12 else 64 * 1024
+            while True:
+                so, do = (rnd.randrange(0, (span - n) // gran) * gran for _ in range(2))
+                if so + n <= do or do + n <= so:
+                    break
+            for key, n_wg in (("fronts_wg1024", 1024), ("tiles_wg511", 511)):
+                ms = min(time_on_stream(torch, g.streams[0],
+                                        lambda: g.launch_wg_put_all(1, region + do, region + so, n, n_wg, S.SHM_PATH_LDST), 4) for _ in range(3))
+                rows[key].append(100.0 * 2 * npes * n / ms / 1e6 / HBM_PEAK_GBS)
+        out[f"random_placements_pct_min_mean_max_{n // MiB}mib"] = {k: [min(v), sum(v) / len(v), max(v)] for k, v in rows.items()}
+    g.free(region)
     g.set_team_sync(True)
     return out
 
@@ -888,6 +908,8 @@ def summarise(extras, cpu_legs):
         if "placement" in r:
             out["c2"]["placement_pct_min_med_max"] = r["placement"]["pct_min_med_max"]
             out["c2"]["placement_pct_min_med_max_64mib"] = r["placement"].get("pct_min_med_max_64mib")
+            out["c2"]["random_placements_pct_min_mean_max"] = {k.rsplit("_", 1)[1]: v for k, v in r["placement"].items()
+                                                               if k.startswith("random_placements")}
     if "hbm_ceilings" in extras:
         hc = extras["hbm_ceilings"]
         out["hbm_ceilings_pct"] = {**{k: v["frac_hbm"] * 100 for k, v in hc["kernels"].items()},
