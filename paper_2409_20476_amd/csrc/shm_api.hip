@@ -4,6 +4,7 @@
 
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
 #include <cstdarg>
 #include <cstdio>
 #include <cstdlib>
@@ -42,9 +43,11 @@ constexpr size_t TILE_BYTES = 64u << 10, TILES_PER_GROUP = 4;
 constexpr long long TILES_MIN_GRID_GROUPS = 64;               // groups asked for, all PEs of the grid together
 constexpr long long TILES_MIN_LAUNCHED_GROUPS = 64;           // groups launched, all PEs of the grid together
 constexpr unsigned TILES_LDS_BYTES = 54000;                   // unused LDS that caps a CU at 3 resident groups
+constexpr size_t TIMED_TICKET_GROUPS = 96;                    // groups per PE of a timed put whose tiles are dealt by ticket
 constexpr uint64_t OFFLOAD_COUNTERS = 32768;                  // offset of the ring's three index words in PE 0's internal tail
 static_assert(ARRIVE_SLOTS * 8 <= OFFLOAD_COUNTERS && OFFLOAD_COUNTERS + 24 <= SHMD_INTERNAL_SYNC_COUNT &&
-                  SHMD_INTERNAL_SYNC_EPOCH + 8 <= SHMD_INTERNAL_QUIET && SHMD_INTERNAL_QUIET + 8 * 128 <= SHM_INTERNAL_BYTES,
+                  SHMD_INTERNAL_SYNC_EPOCH + 8 <= SHMD_INTERNAL_QUIET && SHMD_INTERNAL_QUIET + 8 * 128 <= SHMD_INTERNAL_TICKETS &&
+                  SHMD_INTERNAL_TICKETS + 8 * SHMD_TICKET_WORDS <= SHM_INTERNAL_BYTES,
               "internal tail layout");
 static_assert(SHM_OFFLOAD_SLOTS == SHMD_OFFLOAD_SLOTS && SHM_OFFLOAD_COMPLETIONS == SHMD_OFFLOAD_COMPLETIONS &&
                   SHM_OFFLOAD_NO_COMPLETION == SHMD_OFFLOAD_NONE, "host and device agree on the ring");
@@ -928,15 +931,30 @@ int shm_launch_wg_put_timed(shm_ctx *c, int me, int pe, uint64_t dst_off, uint64
     if (c->no_device) return no_device("shm_launch_wg_put_timed");
     if (int r = begin_pe_launch(c, me)) return r;
     const bool tiles = use_tiles(dst_off, src_off, n, n_wg, 1);
-    // A put that its own quiet follows drains the group's stores before the group can go on, so the
-    // groups should be few and long-lived: eight tiles per group and put, and from 128 groups per PE
-    // on rather longer runs than more groups (measured with 8 PEs at once, 8 / 16 / 32 tiles per group:
-    // 64 MiB 70.6 / 57.8 / 38.0 % of the roofline, 128 MiB 72.6 / 74.5 / 60.4, 256 MiB 73.1 / 75.8 / 76.0).
+    // A put that its own quiet follows keeps its groups in the kernel, so the groups should be few and
+    // long-lived, and they draw their tiles by ticket (shm_copy_tiles_ticketed; one counter per
+    // repetition in the PE's own tail, cleared here -- this entry point is not for graph capture):
+    // measured with 8 PEs at once on 4 hardware queues, 64 / 128 / 256 MiB per PE, by groups per PE:
+    // 64 groups 68.1 / 71.4 / 73.9 % of the roofline, 80: 72.2 / 75.6 / 77.5, 96: 73.0 / 77.0 / 78.4,
+    // 128: 72.3 / 76.0 / 77.8, 192: 68.2 / 74.0 / 77.3; fixed shares, 128 groups: 70.4 / 74.6 / 75.1.
+    // More repetitions than there are counters take fixed shares, eight tiles or more per group.
     const size_t n_tiles = (n + TILE_BYTES - 1) / TILE_BYTES;
-    const size_t per_group = n_tiles / 128 > 2 * TILES_PER_GROUP ? n_tiles / 128 : 2 * TILES_PER_GROUP;
-    hipLaunchKernelGGL(shmk_wg_put_timed, dim3(tiles ? tile_groups(n, n_wg, per_group) : n_wg), dim3(SHMK_WG), tiles ? TILES_LDS_BYTES : 0,
-                       c->stream[me], dev_view(c), dst_off, src_off, n, me, pe, reps, reinterpret_cast<unsigned long long *>(dev_ticks),
-                       tiles ? 1 : 0);
+    const bool tickets = tiles && reps <= static_cast<int>(SHMD_TICKET_WORDS);
+    const size_t per_group = tickets ? std::max(TILES_PER_GROUP, n_tiles / TIMED_TICKET_GROUPS) : std::max(2 * TILES_PER_GROUP, n_tiles / 128);
+    if (tickets)
+        HIP_TRY(hipMemsetAsync(c->base + static_cast<size_t>(me) * c->part_bytes + c->user_bytes + SHMD_INTERNAL_TICKETS, 0, 8u * reps,
+                               c->stream[me]));
+    unsigned long long *ticks = reinterpret_cast<unsigned long long *>(dev_ticks);
+    const dim3 tile_grid(tile_groups(n, n_wg, per_group));
+    if (tickets)
+        hipLaunchKernelGGL(shmk_wg_put_timed<2>, tile_grid, dim3(SHMK_WG), TILES_LDS_BYTES, c->stream[me], dev_view(c), dst_off, src_off, n, me,
+                           pe, reps, ticks);
+    else if (tiles)
+        hipLaunchKernelGGL(shmk_wg_put_timed<1>, tile_grid, dim3(SHMK_WG), TILES_LDS_BYTES, c->stream[me], dev_view(c), dst_off, src_off, n, me,
+                           pe, reps, ticks);
+    else
+        hipLaunchKernelGGL(shmk_wg_put_timed<0>, dim3(n_wg), dim3(SHMK_WG), 0, c->stream[me], dev_view(c), dst_off, src_off, n, me, pe, reps,
+                           ticks);
     return launched("timed work-group put");
 }
 
@@ -1031,8 +1049,26 @@ int shm_launch_rma_device_initiated(shm_ctx *c, int me, int pe, uint64_t dst_off
     if (c->no_device) return no_device("shm_launch_rma_device_initiated");
     if (mode != 0 && !c->proxy.running()) return fail(SHM_EINVAL, "the host proxy is not running (shm_proxy_start)");
     if (int r = begin_pe_launch(c, me)) return r;
-    hipLaunchKernelGGL(shmk_rma_device_initiated, dim3(n_wg), dim3(wg_size), 0, c->stream[me], dev_view(c), dst_off, src_off, n, me, pe,
-                       is_get ? 1 : 0, mode, cutover, cover, consume_off, reps, reinterpret_cast<unsigned long long *>(dev_ticks));
+    unsigned long long *ticks = reinterpret_cast<unsigned long long *>(dev_ticks);
+    auto launch = [&](auto kernel) {
+        hipLaunchKernelGGL(kernel, dim3(n_wg), dim3(wg_size), 0, c->stream[me], dev_view(c), dst_off, src_off, n, me, pe, cutover, cover,
+                           consume_off, reps, ticks);
+    };
+    switch (mode * 2 + (is_get ? 1 : 0)) {
+    case 0: launch(shmk_rma_device_initiated<0, false>); break;
+    case 1: launch(shmk_rma_device_initiated<0, true>); break;
+    case 2: launch(shmk_rma_device_initiated<1, false>); break;
+    case 3: launch(shmk_rma_device_initiated<1, true>); break;
+    case 4: launch(shmk_rma_device_initiated<2, false>); break;
+    case 5: launch(shmk_rma_device_initiated<2, true>); break;
+    case 6: launch(shmk_rma_device_initiated<3, false>); break;
+    case 7: launch(shmk_rma_device_initiated<3, true>); break;
+    case 8: launch(shmk_rma_device_initiated<4, false>); break;
+    case 9: launch(shmk_rma_device_initiated<4, true>); break;
+    case 10: launch(shmk_rma_device_initiated<5, false>); break;
+    case 11: launch(shmk_rma_device_initiated<5, true>); break;
+    default: return fail(SHM_EINVAL, "mode outside 0..5");
+    }
     return launched("device-initiated transfer");
 }
 

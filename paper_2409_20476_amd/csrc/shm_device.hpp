@@ -152,6 +152,42 @@ __device__ __forceinline__ void shm_st1(char *p, char v)
         *p = v;
 }
 
+template <int POLICY = SHM_ST_STREAM>
+__device__ __forceinline__ void shm_st8(char *p, uint64_t v)
+{
+    if (POLICY == SHM_ST_THROUGH)
+        asm volatile("global_store_dwordx2 %0, %1, off sc1" ::"v"(p), "v"(v) : "memory");
+    else
+        *reinterpret_cast<uint64_t *>(p) = v;
+}
+template <int POLICY = SHM_ST_STREAM>
+__device__ __forceinline__ void shm_st4(char *p, uint32_t v)
+{
+    if (POLICY == SHM_ST_THROUGH)
+        asm volatile("global_store_dword %0, %1, off sc1" ::"v"(p), "v"(v) : "memory");
+    else
+        *reinterpret_cast<uint32_t *>(p) = v;
+}
+
+// Fewer than 16 bytes by ONE thread: an 8- and a 4-byte piece where both addresses allow, bytes for
+// the rest (a thread's byte stores follow one another at a memory round trip each: 8 bytes as bytes
+// measure 2.3 us, as one piece what a 16-byte put takes).
+template <int POLICY = SHM_ST_STREAM>
+__device__ __forceinline__ void shm_copy_below16(char *dst, const char *src, size_t len)
+{
+    const uintptr_t both = reinterpret_cast<uintptr_t>(dst) | reinterpret_cast<uintptr_t>(src);
+    size_t i = 0;
+    if (len >= 8 && (both & 7) == 0) {
+        shm_st8<POLICY>(dst, *reinterpret_cast<const uint64_t *>(src));
+        i = 8;
+    }
+    if (len - i >= 4 && (both & 3) == 0) {
+        shm_st4<POLICY>(dst + i, *reinterpret_cast<const uint32_t *>(src + i));
+        i += 4;
+    }
+    for (; i < len; ++i) shm_st1<POLICY>(dst + i, src[i]);
+}
+
 template <int U = 8, int POLICY = SHM_ST_STREAM>
 __device__ __forceinline__ void shm_copy_coop(char *dst, const char *src, size_t n, unsigned tid, unsigned nthr)
 {
@@ -160,8 +196,13 @@ __device__ __forceinline__ void shm_copy_coop(char *dst, const char *src, size_t
     if (head > n) head = n;
     const size_t body = (n - head) & ~static_cast<size_t>(15);
     const size_t tail = n - head - body;
-    for (size_t i = tid; i < head; i += nthr) shm_st1<POLICY>(dst + i, src[i]);
-    for (size_t i = tid; i < tail; i += nthr) shm_st1<POLICY>(dst + head + body + i, src[head + body + i]);
+    if (nthr == 1) {              // a lone thread: pieces instead of bytes
+        shm_copy_below16<POLICY>(dst, src, head);
+        shm_copy_below16<POLICY>(dst + head + body, src + head + body, tail);
+    } else {
+        for (size_t i = tid; i < head; i += nthr) shm_st1<POLICY>(dst + i, src[i]);
+        for (size_t i = tid; i < tail; i += nthr) shm_st1<POLICY>(dst + head + body + i, src[head + body + i]);
+    }
     if (body == 0) return;
     shm_u32x4 *d = reinterpret_cast<shm_u32x4 *>(dst + head);
     const char *bs = src + head;
@@ -333,14 +374,62 @@ __device__ __forceinline__ void shm_copy_parts(char *dst, const char *src, size_
 // (77-79 % otherwise); the per-column form it replaces measured 82 % at its best placement and 72-77 %
 // at the others.  dst and src are 16-byte aligned, n is a multiple of 16.
 // ------------------------------------------------------------------------------------------
+// One whole tile of the walk: the stores of the columns loaded LAG steps ago (the first LAG of them
+// belong to the previous tile, at `prev`, if there was one), each followed by the load of the next column.
+template <int U, unsigned CPW, unsigned LAG>
+__device__ __forceinline__ void shm_tile_walk(shm_u32x4 *d, const shm_u32x4 *s, size_t base, size_t prev, bool have, unsigned rot,
+                                              shm_u32x4 (&r)[LAG][U])
+{
+    constexpr size_t rowv = 2048;                        // 32 KiB
+    auto col = [&](unsigned c) { return static_cast<size_t>((c + rot) & (CPW - 1)) * 64; };
+#pragma unroll
+    for (unsigned c = 0; c < CPW; ++c) {
+        const unsigned slot = c % LAG;                   // holds the column loaded LAG steps ago
+        if (c >= LAG) {
+#pragma unroll
+            for (int u = 0; u < U; ++u) shm_st16(d + base + col(c - LAG) + u * rowv, r[slot][u]);
+        } else if (have) {
+#pragma unroll
+            for (int u = 0; u < U; ++u) shm_st16(d + prev + col(c + CPW - LAG) + u * rowv, r[slot][u]);
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) r[slot][u] = shm_ld16(s + base + col(c) + u * rowv);
+    }
+}
+// The stores still owed to the last whole tile of a walk.
+template <int U, unsigned CPW, unsigned LAG>
+__device__ __forceinline__ void shm_tile_walk_end(shm_u32x4 *d, size_t prev, unsigned rot, shm_u32x4 (&r)[LAG][U])
+{
+    constexpr size_t rowv = 2048;
+#pragma unroll
+    for (unsigned c = CPW - LAG; c < CPW; ++c)
+#pragma unroll
+        for (int u = 0; u < U; ++u) shm_st16(d + prev + static_cast<size_t>((c + rot) & (CPW - 1)) * 64 + u * rowv, r[c % LAG][u]);
+}
+// The last, partial tile of a message of nvec vectors: column by column, no lag.
+template <int U, unsigned CPW>
+__device__ __forceinline__ void shm_tile_partial(shm_u32x4 *d, const shm_u32x4 *s, size_t base, size_t nvec)
+{
+    constexpr size_t rowv = 2048;
+    for (unsigned c = 0; c < CPW; ++c) {
+        const size_t i = base + static_cast<size_t>(c) * 64;
+        shm_u32x4 q[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+            if (i + u * rowv < nvec) q[u] = shm_ld16(s + i + u * rowv);
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+            if (i + u * rowv < nvec) shm_st16(d + i + u * rowv, q[u]);
+    }
+}
+
 template <int U, int NWAVES>
 __device__ __forceinline__ void shm_copy_tiles_impl(char *dst, const char *src, size_t n, unsigned part, unsigned nparts)
 {
     const shm_u32x4 *s = reinterpret_cast<const shm_u32x4 *>(src);
     shm_u32x4 *d = reinterpret_cast<shm_u32x4 *>(dst);
     const size_t nvec = n >> 4;
-    constexpr size_t rowv = 2048;                        // 32 KiB
-    constexpr size_t tilev = rowv * U;
+    constexpr size_t tilev = 2048 * U;                   // U rows of 32 KiB
     const size_t nwhole = nvec / tilev;                  // whole tiles; one more, partial, if nvec % tilev
     const unsigned wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     constexpr unsigned CPW = 32 / NWAVES;                // columns per wave; compile-time trip counts throughout
@@ -348,47 +437,68 @@ __device__ __forceinline__ void shm_copy_tiles_impl(char *dst, const char *src, 
     static_assert(CPW % LAG == 0, "a register slot is refilled by the column LAG steps later, also across tiles");
     const unsigned rot = part & (CPW - 1);
     const size_t lane_off = static_cast<size_t>(wave * CPW) * 64 + lane;
-    auto col = [&](unsigned c) { return static_cast<size_t>((c + rot) & (CPW - 1)) * 64; };
     shm_u32x4 r[LAG][U];
     size_t prev = 0;
     bool have = false;
     for (size_t t = part; t < nwhole; t += nparts) {
         const size_t base = t * tilev + lane_off;
-#pragma unroll
-        for (unsigned c = 0; c < CPW; ++c) {
-            const unsigned slot = c % LAG;               // holds the column loaded LAG steps ago
-            if (c >= LAG) {
-#pragma unroll
-                for (int u = 0; u < U; ++u) shm_st16(d + base + col(c - LAG) + u * rowv, r[slot][u]);
-            } else if (have) {
-#pragma unroll
-                for (int u = 0; u < U; ++u) shm_st16(d + prev + col(c + CPW - LAG) + u * rowv, r[slot][u]);
-            }
-#pragma unroll
-            for (int u = 0; u < U; ++u) r[slot][u] = shm_ld16(s + base + col(c) + u * rowv);
-        }
+        shm_tile_walk<U, CPW, LAG>(d, s, base, prev, have, rot, r);
         prev = base;
         have = true;
     }
-    if (have) {
-#pragma unroll
-        for (unsigned c = CPW - LAG; c < CPW; ++c)
-#pragma unroll
-            for (int u = 0; u < U; ++u) shm_st16(d + prev + col(c) + u * rowv, r[c % LAG][u]);
-    }
-    if (nwhole * tilev < nvec && nwhole % nparts == part) {      // the last, partial tile
-        const size_t base = nwhole * tilev + lane_off;
-        for (unsigned c = 0; c < CPW; ++c) {
-            const size_t i = base + static_cast<size_t>(c) * 64;
-            shm_u32x4 q[U];
-#pragma unroll
-            for (int u = 0; u < U; ++u)
-                if (i + u * rowv < nvec) q[u] = shm_ld16(s + i + u * rowv);
-#pragma unroll
-            for (int u = 0; u < U; ++u)
-                if (i + u * rowv < nvec) shm_st16(d + i + u * rowv, q[u]);
+    if (have) shm_tile_walk_end<U, CPW, LAG>(d, prev, rot, r);
+    if (nwhole * tilev < nvec && nwhole % nparts == part) shm_tile_partial<U, CPW>(d, s, nwhole * tilev + lane_off, nvec);
+}
+
+// The same tiles dealt by tickets instead of by group number: every group draws the number of its
+// next tile from a counter (one atomic per 64 KiB, drawn a tile ahead so that its latency is hidden),
+// until it draws a number past the last tile.  For groups that stay resident through a whole put --
+// a put issued from a running kernel and followed by the group's quiet -- this evens out what fixed
+// shares cannot: the groups of a kernel do not get equal parts of the memory bandwidth (measured
+// with 8 PEs x 128 groups x 64 MiB: half of a kernel's groups finish their fixed share in 200 us,
+// the other half in 370-390 us, and while those finish most of the chip has nothing left to do).
+// *counter must read first_ticket when the first group arrives and is left at first_ticket + tiles
+// + groups (every group draws exactly one ticket too many).  `part` only rotates the column walk.
+// dst and src 16-byte aligned, n a multiple of 16; every thread of the group calls.
+template <int U, int NWAVES>
+__device__ __forceinline__ void shm_copy_tiles_ticketed(char *dst, const char *src, size_t n, unsigned part, unsigned long long *counter,
+                                                        unsigned long long first_ticket)
+{
+    __shared__ unsigned long long drawn[2];
+    const shm_u32x4 *s = reinterpret_cast<const shm_u32x4 *>(src);
+    shm_u32x4 *d = reinterpret_cast<shm_u32x4 *>(dst);
+    const size_t nvec = n >> 4;
+    constexpr size_t tilev = 2048 * U;
+    const size_t nwhole = nvec / tilev, ntiles = nwhole + (nwhole * tilev < nvec ? 1 : 0);
+    const unsigned wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    constexpr unsigned CPW = 32 / NWAVES;
+    constexpr unsigned LAG = CPW < 4 ? CPW : 4;
+    static_assert(CPW % LAG == 0, "a register slot is refilled by the column LAG steps later, also across tiles");
+    const unsigned rot = part & (CPW - 1);
+    const size_t lane_off = static_cast<size_t>(wave * CPW) * 64 + lane;
+    auto draw = [&]() { return __hip_atomic_fetch_add(counter, 1ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) - first_ticket; };
+    shm_u32x4 r[LAG][U];
+    size_t prev = 0;
+    bool have = false;
+    unsigned long long pending = 0;
+    if (threadIdx.x == 0) drawn[0] = draw();
+    __syncthreads();
+    size_t t = drawn[0];
+    for (unsigned it = 0; t < ntiles; ++it) {
+        if (threadIdx.x == 0) pending = draw();              // the next tile's number, on its way while this tile moves
+        const size_t base = t * tilev + lane_off;
+        if (t < nwhole) {
+            shm_tile_walk<U, CPW, LAG>(d, s, base, prev, have, rot, r);
+            prev = base;
+            have = true;
+        } else {
+            shm_tile_partial<U, CPW>(d, s, base, nvec);
         }
+        if (threadIdx.x == 0) drawn[(it + 1) & 1] = pending;  // two slots: the other one may still be being read
+        __syncthreads();
+        t = drawn[(it + 1) & 1];
     }
+    if (have) shm_tile_walk_end<U, CPW, LAG>(d, prev, rot, r);
 }
 
 template <int U = 2>
@@ -451,9 +561,14 @@ __device__ __forceinline__ void shm_copy_front(char *dst, const char *src, size_
 // time (measured: 8 bytes by one group, put + quiet 0.69 -> 0.56 us).  Longer puts stream with
 // nontemporal stores: a write-through store is acknowledged by memory rather than by the L2, and a
 // few waves with a bounded number of stores in flight then move less than half the bytes per
-// microsecond (1 MiB by one group: 17 us streaming, 38 us write-through).
+// microsecond (1 MiB by one group: 17 us streaming, 38 us write-through).  Eight groups or more
+// have the waves to cover that latency and store write-through up to 256 bytes per thread (put + quiet
+// inside the kernel, 8 PEs x 64 groups: 2 MiB per PE 8.0 -> 4.4 us, 4 MiB 11.3 -> 8.0 us; at 1 KiB per
+// thread 8 MiB 17.8 -> 19.6 us and 16 MiB 31 -> 39-44 us, and messages of 48 MiB and more move at 75 %
+// of the HBM roofline written through against 81 % streamed).
 // ------------------------------------------------------------------------------------------
 constexpr size_t SHM_PUT_THROUGH_BYTES_PER_THREAD = 64;
+constexpr size_t SHM_PUT_THROUGH_BYTES_PER_THREAD_MANY = 256;     // eight groups or more share the message
 
 // Whether a put of n bytes by nparts groups of the calling group's size stores write-through (the
 // rule of shm_put_parts / shm_put_coop): then nothing of it is dirty in the L2 afterwards and the
@@ -470,7 +585,8 @@ __device__ __forceinline__ void shm_put_coop(char *dst, const char *src, size_t 
 }
 __device__ __forceinline__ bool shm_put_stores_through(size_t n, unsigned nparts, size_t min_share)
 {
-    return n <= SHM_PUT_THROUGH_BYTES_PER_THREAD * blockDim.x * shm_deal_groups(n >> 4, nparts, min_share);
+    const unsigned groups = shm_deal_groups(n >> 4, nparts, min_share);
+    return n <= (groups >= 8 ? SHM_PUT_THROUGH_BYTES_PER_THREAD_MANY : SHM_PUT_THROUGH_BYTES_PER_THREAD) * blockDim.x * groups;
 }
 template <int U>
 __device__ __forceinline__ void shm_put_parts(char *dst, const char *src, size_t n, unsigned part, unsigned nparts, size_t min_share = 0)
@@ -613,6 +729,24 @@ __device__ __forceinline__ void shmx_getmem_tiles(const shm_dev_ctx &c, int me, 
     shmx_copy_tiles_wg<NWAVES>(shm_ptr(c, dst_off, me), shm_ptr(c, src_off, pe), n, part, nparts);
 }
 
+// A long put shared by groups that draw their tiles from a ticket counter (shm_copy_tiles_ticketed):
+// for groups that stay in the kernel after the put.  `counter` is a 64-bit word in device memory
+// that reads first_ticket before the first group arrives; NWAVES states the group size
+// (64 * NWAVES work-items).  Offsets 16-byte aligned; the last n mod 16 bytes are copied by group 0.
+template <int NWAVES>
+__device__ __forceinline__ void shmx_putmem_tickets(const shm_dev_ctx &c, int me, uint64_t dst_off, uint64_t src_off, size_t n, int pe,
+                                                    unsigned part, unsigned long long *counter, unsigned long long first_ticket)
+{
+    char *d = shm_ptr(c, dst_off, pe);
+    const char *s = shm_ptr(c, src_off, me);
+    __syncthreads();
+    const size_t body = n & ~static_cast<size_t>(15);
+    shm_copy_tiles_ticketed<2, NWAVES>(d, s, body, part, counter, first_ticket);
+    if (part == 0)
+        for (size_t i = body + threadIdx.x; i < n; i += blockDim.x) d[i] = s[i];
+    __syncthreads();
+}
+
 // ------------------------------------------------------------------------------------------
 // Ordering.  All logical PEs live on one GPU, so agent scope is the widest scope ever needed
 // between PEs.  quiet = the calling thread's puts and atomics are complete and visible to every
@@ -641,6 +775,8 @@ __device__ __forceinline__ void shmx_quiet_wg()
 // group's leader runs the protocol.  Small grids (fewer than SHMD_QUIET_SHARED_MIN_GROUPS groups)
 // release directly: an atomic costs more than a write-back nobody queues for.
 #define SHMD_INTERNAL_QUIET 33280u            // 8 words, 128 bytes apart
+#define SHMD_INTERNAL_TICKETS 36864u          // SHMD_TICKET_WORDS uint64: tile tickets of the timed put, one word per repetition
+#define SHMD_TICKET_WORDS 512u
 #define SHMD_QUIET_SHARED_MIN_GROUPS 64u
 #define SHMD_QUIET_SPIN_LIMIT 4096
 

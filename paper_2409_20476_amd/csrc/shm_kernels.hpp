@@ -122,19 +122,27 @@ __global__ __launch_bounds__(SHMK_WG) void shmk_stream_probe(shm_dev_ctx c, uint
 // device clock read before the first and after the last: the cost of a put issued from a running
 // kernel, free of any launch overhead.  ticks[0] = earliest start, ticks[1] = latest end over the groups
 // that have a share of the message.
-// tiles != 0: long message on group-owned tiles (the launcher's choice, as for an untimed put).
+// FORM 0: the general dealing; 1: long message on group-owned tiles (the launcher's choice, as for an
+// untimed put); 2: the same tiles drawn by ticket, repetition r from the r-th ticket word of this PE's
+// tail, which reads 0.  One kernel per form: the loop of a short put stays a few hundred instructions.
+template <int FORM>
 __global__ __launch_bounds__(SHMK_WG) void shmk_wg_put_timed(shm_dev_ctx c, uint64_t dst_off, uint64_t src_off, size_t n, int me, int pe,
-                                                             int reps, unsigned long long *ticks, int tiles)
+                                                             int reps, unsigned long long *ticks)
 {
     // groups without a share have nothing to complete
-    const bool mine = tiles ? blockIdx.x < (n + 65535) / 65536 : shm_deal_has_share<8>(n, blockIdx.x, gridDim.x, SHMK_WG, SHM_MIN_SHARE_BYTES);
+    const bool mine = FORM ? blockIdx.x < (n + 65535) / 65536 : shm_deal_has_share<8>(n, blockIdx.x, gridDim.x, SHMK_WG, SHM_MIN_SHARE_BYTES);
+    const bool bulk = FORM || !shm_put_stores_through(n, gridDim.x, SHM_MIN_SHARE_BYTES);
+    [[maybe_unused]] unsigned long long *tickets =
+        reinterpret_cast<unsigned long long *>(shm_ptr(c, c.internal_off + SHMD_INTERNAL_TICKETS, me));
     const unsigned long long t0 = wall_clock64();
     for (int r = 0; r < reps; ++r) {
-        if (tiles)
+        if constexpr (FORM == 2)
+            shmx_putmem_tickets<SHMK_WG / 64>(c, me, dst_off, src_off, n, pe, blockIdx.x, tickets + r, 0);
+        else if constexpr (FORM == 1)
             shmx_putmem_tiles<SHMK_WG / 64>(c, me, dst_off, src_off, n, pe, blockIdx.x, gridDim.x);
         else
             shmx_putmem_parts(c, me, dst_off, src_off, n, pe, blockIdx.x, gridDim.x, SHM_MIN_SHARE_BYTES);
-        if (mine) shmx_quiet_wg(c, tiles || !shm_put_stores_through(n, gridDim.x, SHM_MIN_SHARE_BYTES));
+        if (mine) shmx_quiet_wg(c, bulk);
     }
     const unsigned long long t1 = wall_clock64();
     // Only the groups that moved bytes report: a group without a share returns from every put at
@@ -156,10 +164,15 @@ __global__ __launch_bounds__(SHMK_WG) void shmk_wg_put_timed(shm_dev_ctx c, uint
 // after every get it copies the share again, so the copy shows what a thread of the group reads.
 constexpr uint64_t SHMK_NO_CONSUME = ~0ull;
 
+// One kernel per mode and direction (compile-time): what a repetition runs through stays short, which
+// is worth a quarter of a small put's time against one kernel that branches on the mode.
+template <int MODE, bool IS_GET>
 __global__ __launch_bounds__(1024) void shmk_rma_device_initiated(shm_dev_ctx c, uint64_t dst_off, uint64_t src_off, size_t n, int me,
-                                                                     int pe, int is_get, int mode, size_t cutover, size_t cover,
-                                                                     uint64_t consume_off, int reps, unsigned long long *ticks)
+                                                                     int pe, size_t cutover, size_t cover, uint64_t consume_off, int reps,
+                                                                     unsigned long long *ticks)
 {
+    constexpr int mode = MODE;
+    constexpr bool is_get = IS_GET;
     size_t per = (n + gridDim.x - 1) / gridDim.x;
     per = (per + 255) & ~static_cast<size_t>(255);
     const size_t lo = min(n, blockIdx.x * per), len = min(n, lo + per) - lo;
@@ -168,19 +181,19 @@ __global__ __launch_bounds__(1024) void shmk_rma_device_initiated(shm_dev_ctx c,
     if (consume) shmx_putmem_wg(c, me, consume_off + lo, d, len, me);
     const unsigned long long t0 = wall_clock64();
     for (int r = 0; r < reps; ++r) {
-        if (mode == 0) {
+        if constexpr (mode == 0) {
             if (is_get) {
                 shmx_getmem_wg(c, me, d, s, len, pe);
             } else {
                 shmx_putmem_wg(c, me, d, s, len, pe);
                 if (len) shmx_quiet_wg(c, !shm_put_stores_through(len));
             }
-        } else if (mode == 1) {
+        } else if constexpr (mode == 1) {
             if (is_get)
                 shmx_getmem_offload_wg(c, me, d, s, len, pe, true);
             else
                 shmx_putmem_offload_wg(c, me, d, s, len, pe, true);
-        } else if (mode == 2) {
+        } else if constexpr (mode == 2) {
             const bool engine = c.off.ring != nullptr && len >= shm_resolve_cutover(cutover);
             if (is_get) {
                 shmx_getmem_auto_wg(c, me, d, s, len, pe, cutover);
@@ -188,19 +201,19 @@ __global__ __launch_bounds__(1024) void shmk_rma_device_initiated(shm_dev_ctx c,
                 shmx_putmem_auto_wg(c, me, d, s, len, pe, cutover);
                 if (!engine && len) shmx_quiet_wg(c, !shm_put_stores_through(len));
             }
-        } else if (mode == 3) {
+        } else if constexpr (mode == 3) {
             if (is_get)
                 shmx_getmem_offload_wg(c, me, d, s, len, pe, false);
             else
                 shmx_putmem_offload_wg(c, me, d, s, len, pe, false);
             shmx_quiet_offload_wg(c, me);
-        } else if (mode == 5) {
+        } else if constexpr (mode == 5) {
             if (is_get)
                 shmx_getmem_offload_wg(c, me, d, s, len, pe, false);
             else
                 shmx_putmem_offload_wg(c, me, d, s, len, pe, false);
         } else {
-            shmx_rma_covered_wg(c, me, d, s, len, pe, cover, is_get != 0);
+            shmx_rma_covered_wg(c, me, d, s, len, pe, cover, is_get);
             if (!is_get && len) shmx_quiet_wg(c);
             shmx_quiet_offload_wg(c, me);
         }

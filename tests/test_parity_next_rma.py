@@ -13,8 +13,11 @@ MiB = 1 << 20
 
 
 @pytest.mark.parametrize("is_get", [False, True])
-@pytest.mark.parametrize("n,sa,da", [(0, 0, 0), (1, 3, 5), (15, 1, 0), (4096, 0, 0), (100003, 7, 9), (65536 + 48, 16, 32), (513, 0, 8)])
+@pytest.mark.parametrize("n,sa,da", [(0, 0, 0), (1, 3, 5), (15, 1, 0), (4096, 0, 0), (100003, 7, 9), (65536 + 48, 16, 32), (513, 0, 8),
+                                     (8, 0, 0), (12, 8, 8), (15, 4, 4), (7, 8, 16), (31, 8, 24), (24, 8, 0), (14, 2, 6)])
 def test_single_thread_put_get(is_get, n, sa, da):
+    """Also the ends of a message that a lone thread moves in 8- and 4-byte pieces where source and
+    destination are both aligned for them (8 bytes at 0/0, 8 + 4 at 8/8, 4 + bytes at 4/4 ...)."""
     g, o = make_pair(3, 4 * MiB)
     with g:
         fill_random(g, o, 61, upto=3 * MiB)

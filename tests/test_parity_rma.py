@@ -172,19 +172,24 @@ def test_more_groups_than_vectors_and_the_minimum_share_of_put_then_quiet(n_wg):
 
 def test_timed_put_of_long_messages_moves_the_same_bytes_on_both_long_message_paths():
     """9 MiB by 64 groups and 40 MiB by 48 groups stay on the virtual blocks (short message; fewer than 64
-    groups), 65 MiB by 512 groups and 33 MiB by 64 groups take group-owned tiles."""
+    groups); 65 MiB by 512 groups and 33 MiB by 64 groups take 64 KiB tiles, which the groups draw by
+    ticket -- up to 512 repetitions, one ticket counter each; beyond, every group owns fixed tiles.  The
+    launches follow one another at once: each finds the counters its predecessor used cleared."""
     import torch
     g, o = make_pair(2, 160 * MiB)
     with g:
         fill_random(g, o, 7, upto=144 * MiB)
-        for n, n_wg in [(9 * MiB + 16 * 3 + 5, 64), (65 * MiB + 16 * 3 + 5, 512), (40 * MiB + 16 * 7 + 1, 48),
-                        (33 * MiB + 65536 + 16 + 3, 64)]:      # ragged last tile and a byte tail
+        for n, n_wg, reps in [(9 * MiB + 16 * 3 + 5, 64, 3), (65 * MiB + 16 * 3 + 5, 512, 3), (40 * MiB + 16 * 7 + 1, 48, 3),
+                              (33 * MiB + 65536 + 16 + 3, 64, 3),      # ragged last tile and a byte tail
+                              (32 * MiB + 48, 1024, 1), (33 * MiB + 65536 + 16 + 3, 200, 513)]:
             ticks = torch.zeros(2, dtype=torch.int64, device="cuda")
             ticks[0] = -1
-            g.launch_wg_put_timed(0, 1, 70 * MiB + 16, 32, n, n_wg, 3, ticks)
+            g.launch_wg_put_timed(0, 1, 70 * MiB + 16, 32, n, n_wg, reps, ticks)
             g.quiet(0)
             o.wg_put(0, 70 * MiB + 16, 32, n, 1, n_wg)
-            assert_heaps_equal(g, o, upto=144 * MiB, what=f"n {n} by {n_wg} groups")
+            assert_heaps_equal(g, o, upto=144 * MiB, what=f"n {n} by {n_wg} groups, {reps} repetitions")
+            t = ticks.cpu().numpy()
+            assert 0 < t[0] < t[1], "device clock: first start before last end"
 
 
 @pytest.mark.parametrize("n_wg", [64, 100, 512, 515, 600])
