@@ -318,6 +318,24 @@ def placement_spread(torch, S, g, args):
                                         lambda: g.launch_wg_put_all(1, region + do, region + so, n, n_wg, S.SHM_PATH_LDST), 4) for _ in range(3))
                 rows[key].append(100.0 * 2 * npes * n / ms / 1e6 / HBM_PEAK_GBS)
         out[f"random_placements_pct_min_mean_max_{n // MiB}mib"] = {k: [min(v), sum(v) / len(v), max(v)] for k, v in rows.items()}
+    # ... and whether repeating a transfer on the same buffers flatters it: the same put through buffer pairs taken
+    # in turn (7 pairs of 64 MiB, 3 of 128 MiB: 0.9-1.8 GiB per PE round before a byte is touched again, against a
+    # memory-side cache of 256 MiB) beside the put repeated on one pair
+    fresh = {}
+    for n in (64 * MiB, 128 * MiB):
+        pairs = span // (2 * n)
+        for key, n_wg in (("fronts_wg1024", 1024), ("tiles_wg511", 511)):
+            def same():
+                g.launch_wg_put_all(1, region + n, region, n, n_wg, S.SHM_PATH_LDST)
+
+            def in_turn():
+                for i in range(pairs):
+                    g.launch_wg_put_all(1, region + (2 * i + 1) * n, region + 2 * i * n, n, n_wg, S.SHM_PATH_LDST)
+            ms_same = min(time_on_stream(torch, g.streams[0], same, 2 * pairs) for _ in range(3))
+            ms_turn = min(time_on_stream(torch, g.streams[0], in_turn, 2) for _ in range(3)) / pairs
+            fresh[f"{key}_{n // MiB}mib"] = {"same_pair_pct": 100.0 * 2 * npes * n / ms_same / 1e6 / HBM_PEAK_GBS,
+                                             "pairs_in_turn_pct": 100.0 * 2 * npes * n / ms_turn / 1e6 / HBM_PEAK_GBS, "pairs": pairs}
+    out["fresh_buffers"] = fresh
     g.free(region)
     g.set_team_sync(True)
     return out
@@ -908,6 +926,8 @@ def summarise(extras, cpu_legs):
         if "placement" in r:
             out["c2"]["placement_pct_min_med_max"] = r["placement"]["pct_min_med_max"]
             out["c2"]["placement_pct_min_med_max_64mib"] = r["placement"].get("pct_min_med_max_64mib")
+            out["c2"]["same_pair_vs_pairs_in_turn_pct"] = {k: [v["same_pair_pct"], v["pairs_in_turn_pct"]]
+                                                           for k, v in r["placement"].get("fresh_buffers", {}).items()}
             out["c2"]["random_placements_pct_min_mean_max"] = {k.rsplit("_", 1)[1]: v for k, v in r["placement"].items()
                                                                if k.startswith("random_placements")}
     if "hbm_ceilings" in extras:
@@ -1073,11 +1093,11 @@ def main():
                 line["extras_file"] = os.path.relpath(args.extras_out, ROOT)
             except OSError as e:
                 log(f"[bench] could not write {args.extras_out}: {e}")
-    text = json.dumps(line)
+    text = json.dumps(line, separators=(",", ":"))
     if len(text) > 6000:                 # the reader of this line keeps only the end of stdout
         line.pop("configs", None)
         line["configs_dropped"] = "summary too long; see extras_file"
-        text = json.dumps(line)
+        text = json.dumps(line, separators=(",", ":"))
     sys.stdout.flush()
     print(text, flush=True)
     return 0

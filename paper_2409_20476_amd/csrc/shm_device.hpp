@@ -374,10 +374,14 @@ __device__ __forceinline__ void shm_copy_parts(char *dst, const char *src, size_
 // (77-79 % otherwise); the per-column form it replaces measured 82 % at its best placement and 72-77 %
 // at the others.  dst and src are 16-byte aligned, n is a multiple of 16.
 // ------------------------------------------------------------------------------------------
-// One whole tile of the walk: the stores of the columns loaded LAG steps ago (the first LAG of them
-// belong to the previous tile, at `prev`, if there was one), each followed by the load of the next column.
-template <int U, unsigned CPW, unsigned LAG>
-__device__ __forceinline__ void shm_tile_walk(shm_u32x4 *d, const shm_u32x4 *s, size_t base, size_t prev, bool have, unsigned rot,
+// One whole tile of the walk: the stores of the columns loaded LAG steps ago, each followed by the
+// load of the next column.  The first LAG of those stores belong to the previous tile, at `prev`;
+// the FIRST tile of a walk has none (a compile-time case of its own: with a run-time flag the
+// compiler peels the first tile itself and its copies of those loads lose the nontemporal hint,
+// after which a repeated transfer finds an eighth of its source in the memory-side cache and
+// measures 3-5 points more than a transfer of fresh data does).
+template <int U, unsigned CPW, unsigned LAG, bool FIRST>
+__device__ __forceinline__ void shm_tile_walk(shm_u32x4 *d, const shm_u32x4 *s, size_t base, size_t prev, unsigned rot,
                                               shm_u32x4 (&r)[LAG][U])
 {
     constexpr size_t rowv = 2048;                        // 32 KiB
@@ -388,7 +392,7 @@ __device__ __forceinline__ void shm_tile_walk(shm_u32x4 *d, const shm_u32x4 *s, 
         if (c >= LAG) {
 #pragma unroll
             for (int u = 0; u < U; ++u) shm_st16(d + base + col(c - LAG) + u * rowv, r[slot][u]);
-        } else if (have) {
+        } else if (!FIRST) {
 #pragma unroll
             for (int u = 0; u < U; ++u) shm_st16(d + prev + col(c + CPW - LAG) + u * rowv, r[slot][u]);
         }
@@ -437,16 +441,17 @@ __device__ __forceinline__ void shm_copy_tiles_impl(char *dst, const char *src, 
     static_assert(CPW % LAG == 0, "a register slot is refilled by the column LAG steps later, also across tiles");
     const unsigned rot = part & (CPW - 1);
     const size_t lane_off = static_cast<size_t>(wave * CPW) * 64 + lane;
-    shm_u32x4 r[LAG][U];
-    size_t prev = 0;
-    bool have = false;
-    for (size_t t = part; t < nwhole; t += nparts) {
-        const size_t base = t * tilev + lane_off;
-        shm_tile_walk<U, CPW, LAG>(d, s, base, prev, have, rot, r);
-        prev = base;
-        have = true;
+    if (part < nwhole) {
+        shm_u32x4 r[LAG][U];
+        size_t prev = part * tilev + lane_off;
+        shm_tile_walk<U, CPW, LAG, true>(d, s, prev, 0, rot, r);
+        for (size_t t = part + nparts; t < nwhole; t += nparts) {
+            const size_t base = t * tilev + lane_off;
+            shm_tile_walk<U, CPW, LAG, false>(d, s, base, prev, rot, r);
+            prev = base;
+        }
+        shm_tile_walk_end<U, CPW, LAG>(d, prev, rot, r);
     }
-    if (have) shm_tile_walk_end<U, CPW, LAG>(d, prev, rot, r);
     if (nwhole * tilev < nvec && nwhole % nparts == part) shm_tile_partial<U, CPW>(d, s, nwhole * tilev + lane_off, nvec);
 }
 
@@ -479,26 +484,35 @@ __device__ __forceinline__ void shm_copy_tiles_ticketed(char *dst, const char *s
     auto draw = [&]() { return __hip_atomic_fetch_add(counter, 1ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) - first_ticket; };
     shm_u32x4 r[LAG][U];
     size_t prev = 0;
-    bool have = false;
     unsigned long long pending = 0;
+    unsigned it = 0;
+    // hands the number drawn during this tile to the group; two slots: the other one may still be being read
+    auto next = [&]() {
+        if (threadIdx.x == 0) drawn[(it + 1) & 1] = pending;
+        __syncthreads();
+        ++it;
+        return static_cast<size_t>(drawn[it & 1]);
+    };
     if (threadIdx.x == 0) drawn[0] = draw();
     __syncthreads();
     size_t t = drawn[0];
-    for (unsigned it = 0; t < ntiles; ++it) {
+    if (t < nwhole) {                                          // the walk's first tile has no stores owed
         if (threadIdx.x == 0) pending = draw();              // the next tile's number, on its way while this tile moves
-        const size_t base = t * tilev + lane_off;
-        if (t < nwhole) {
-            shm_tile_walk<U, CPW, LAG>(d, s, base, prev, have, rot, r);
+        prev = t * tilev + lane_off;
+        shm_tile_walk<U, CPW, LAG, true>(d, s, prev, 0, rot, r);
+        for (t = next(); t < nwhole; t = next()) {
+            if (threadIdx.x == 0) pending = draw();
+            const size_t base = t * tilev + lane_off;
+            shm_tile_walk<U, CPW, LAG, false>(d, s, base, prev, rot, r);
             prev = base;
-            have = true;
-        } else {
-            shm_tile_partial<U, CPW>(d, s, base, nvec);
         }
-        if (threadIdx.x == 0) drawn[(it + 1) & 1] = pending;  // two slots: the other one may still be being read
-        __syncthreads();
-        t = drawn[(it + 1) & 1];
+        shm_tile_walk_end<U, CPW, LAG>(d, prev, rot, r);
     }
-    if (have) shm_tile_walk_end<U, CPW, LAG>(d, prev, rot, r);
+    if (t < ntiles) {                                          // the partial tile; whoever draws it draws once more
+        if (threadIdx.x == 0) pending = draw();
+        shm_tile_partial<U, CPW>(d, s, t * tilev + lane_off, nvec);
+        (void)next();
+    }
 }
 
 template <int U = 2>

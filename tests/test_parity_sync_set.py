@@ -77,12 +77,39 @@ def test_every_form_against_the_oracle_on_random_sets():
         g.set_wait_timeout_us(2_000_000)
 
 
+def _runs_beside(g, o, waiter, setter, off):
+    """Whether a kernel on PE `setter`'s stream runs while a kernel on PE `waiter`'s stream waits.  The
+    runtime maps streams onto a few hardware queues (four unless GPU_MAX_HW_QUEUES says otherwise) and
+    kernels of two streams that share a queue run one after the other, in the order they were
+    launched: a wait launched BEFORE the kernel that releases it then lasts until its bound.  The probe
+    is that situation with a 20 ms bound: the waiter's kernel ends either way."""
+    write_both(g, o, waiter, off, np.zeros(1, np.int64))
+    out = torch.zeros(2, dtype=torch.int64, device="cuda")
+    g.set_wait_timeout_us(20_000)
+    g.launch_sync_set(waiter, off, 1, None, S.SHM_SYNC_WAIT, S.SHM_CMP_GE, 1, out)
+    g.launch_amo(setter, waiter, off, S.SHM_AMO_SET, 1)
+    try:
+        g.barrier_all()
+        beside = True
+    except S.ShmError as e:
+        assert e.code == S.SHM_ETIMEOUT
+        beside = False
+    g.barrier_all()
+    g.set_wait_timeout_us(2_000_000)
+    write_both(g, o, waiter, off, np.ones(1, np.int64))
+    return beside
+
+
 def test_wait_until_all_is_released_by_puts_from_other_pes():
-    """PE 0 waits (enqueued first, on its own stream) until all of four variables are >= 1; three other
-    streams then set one variable each with a scalar put and the fourth with an atomic; the data that
-    one of them put before its variable is readable after the wait."""
+    """PE 0 waits until all of four variables are >= 1; three other streams set one variable each with
+    a scalar put and the fourth with an atomic; the data that one of them put before its variable is
+    readable after the wait.  The wait is launched FIRST, and blocks until the others release it,
+    whenever the four streams run beside each other (see _runs_beside); on streams that share a
+    hardware queue it is launched last, where it finds the variables set."""
     g, o = make_pair(4, MiB)
     with g:
+        wait_first = all(_runs_beside(g, o, 0, p, 49152) for p in (1, 2, 3))
+        print(f"wait launched {'first' if wait_first else 'last: PE 0 shares a hardware queue with another PE'}", flush=True)
         fill_random(g, o, 92, upto=65536)             # the heap is uninitialised device memory: give both sides the same bytes
         zeros = np.zeros(4, np.int64)
         write_both(g, o, 0, 4096, zeros)
@@ -92,13 +119,18 @@ def test_wait_until_all_is_released_by_puts_from_other_pes():
         for p in (1, 2, 3):
             write_both(g, o, p, 256, ones)
         out = torch.zeros(5, dtype=torch.int64, device="cuda")
-        g.launch_sync_set(0, 4096, 4, None, S.SHM_SYNC_WAIT_ALL, S.SHM_CMP_GE, 1, out)
-        g.launch_wg_get(0, 0, 32768, 16384, 1000, 1)                      # PE 0 reads, after its wait, what PE 1 put before its flag
+        def wait_then_read():
+            g.launch_sync_set(0, 4096, 4, None, S.SHM_SYNC_WAIT_ALL, S.SHM_CMP_GE, 1, out)
+            g.launch_wg_get(0, 0, 32768, 16384, 1000, 1)                  # PE 0 reads, after its wait, what PE 1 put before its flag
+        if wait_first:
+            wait_then_read()
         g.launch_wg_put(1, 0, 16384, 8192, 1000, 1)
         g.launch_scalar_pg(1, 0, 4096, 256, 1, 8)                          # same stream: ordered after the payload put ... by a quiet:
         for p in (2, 3):
             g.launch_scalar_pg(p, 0, 4096 + 8 * (p - 1), 256, 1, 8)
         g.launch_amo(3, 0, 4096 + 24, S.SHM_AMO_SET, 1)
+        if not wait_first:
+            wait_then_read()
         g.barrier_all()
         o.putmem(1, 16384, 8192, 1000, 0)
         for i in range(4):
