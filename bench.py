@@ -280,8 +280,8 @@ def crossover_at_other_queue_count(queues):
 
 def placement_spread(torch, S, g, args):
     """The team put at nine placements of the destination relative to the source (HBM channel
-    hashing can make a copy's rate depend on it), at the headline size and at 64 MiB per PE (the
-    front form): percent of the HBM copy roofline, HIP events."""
+    hashing can make a copy's rate depend on it), at the headline size and at 64 MiB per PE:
+    percent of the HBM copy roofline, HIP events."""
     npes = 8
     shifts = (0, 4096, 8192, 65536, MiB, MiB + 4096, 2 * MiB, 16 * MiB + 8192, 64 * MiB - 4096)
     out = {"note": "8 PEs x 1024 groups, destination = source + message size + shift"}
@@ -300,20 +300,20 @@ def placement_spread(torch, S, g, args):
         out["pct_by_destination_shift_bytes" + suffix] = pcts
         out["pct_min_med_max" + suffix] = [v[0], v[len(v) // 2], v[-1]]
     # ... and at sixteen random placements (seeded; offsets in steps of 2 MiB, the last four of 64 KiB) anywhere in a
-    # 1000 MiB region, for the form the launcher takes for 1024 groups per PE (fronts) and the one it takes for 511 (tiles)
+    # 1000 MiB region, for the form the launcher takes for 128 groups per PE or more (pieces by ticket) and the one it takes for fewer (127: group-owned tiles)
     import random
     rnd = random.Random(20476)
     span = 1000 * MiB
     region = g.malloc(span)
     for n in (256 * MiB, 64 * MiB):
-        rows = {"fronts_wg1024": [], "tiles_wg511": []}
+        rows = {"tickets_wg1024": [], "tiles_wg127": []}
         for k in range(16):
             gran = 2 * MiB if k < 12 else 64 * 1024
             while True:
                 so, do = (rnd.randrange(0, (span - n) // gran) * gran for _ in range(2))
                 if so + n <= do or do + n <= so:
                     break
-            for key, n_wg in (("fronts_wg1024", 1024), ("tiles_wg511", 511)):
+            for key, n_wg in (("tickets_wg1024", 1024), ("tiles_wg127", 127)):
                 ms = min(time_on_stream(torch, g.streams[0],
                                         lambda: g.launch_wg_put_all(1, region + do, region + so, n, n_wg, S.SHM_PATH_LDST), 4) for _ in range(3))
                 rows[key].append(100.0 * 2 * npes * n / ms / 1e6 / HBM_PEAK_GBS)
@@ -324,7 +324,7 @@ def placement_spread(torch, S, g, args):
     fresh = {}
     for n in (64 * MiB, 128 * MiB):
         pairs = span // (2 * n)
-        for key, n_wg in (("fronts_wg1024", 1024), ("tiles_wg511", 511)):
+        for key, n_wg in (("tickets_wg1024", 1024), ("tiles_wg127", 127)):
             def same():
                 g.launch_wg_put_all(1, region + n, region, n, n_wg, S.SHM_PATH_LDST)
 
@@ -343,8 +343,8 @@ def placement_spread(torch, S, g, args):
 
 def hbm_ceilings(torch, S, g, args):
     """One-direction and copy ceilings of this chip measured with the library's own access forms
-    (group-owned 64 KiB tiles, 16-byte nontemporal loads and stores, the launch shape of the headline
-    put): what a kernel that only reads, only writes, or copies can reach."""
+    (16-byte nontemporal loads and stores in the launch shape of the headline put): what a kernel
+    that only reads, only writes, or copies can reach."""
     npes, n = 8, 256 * MiB
     a, b = g.malloc(n), g.malloc(n)
     g.set_team_sync(False)
@@ -353,10 +353,12 @@ def hbm_ceilings(torch, S, g, args):
     def probe(kind, n_wg):
         return min(time_on_stream(torch, g.streams[0], lambda: g.launch_stream_probe(kind, b, a, n, n_wg), 5) for _ in range(5))
 
-    # each direction in two access orders: the tiles of the put, and a front that sweeps the block;
-    # the better one is that direction's ceiling
-    for name, kinds in (("read_only", (("tiles", S.SHM_PROBE_READ, (1024,)), ("front", S.SHM_PROBE_READ_FRONT, (64, 256, 1024)))),
-                        ("write_only", (("tiles", S.SHM_PROBE_WRITE, (1024,)), ("front", S.SHM_PROBE_WRITE_FRONT, (64, 256, 1024))))):
+    # each direction in three access orders: group-owned tiles, a front that sweeps the block, and the put's own walk
+    # (32 KiB pieces by ticket); the best one is that direction's ceiling
+    for name, kinds in (("read_only", (("tiles", S.SHM_PROBE_READ, (1024,)), ("front", S.SHM_PROBE_READ_FRONT, (64, 256, 1024)),
+                                       ("tickets", S.SHM_PROBE_READ_TICKETS, (128,)))),
+                        ("write_only", (("tiles", S.SHM_PROBE_WRITE, (1024,)), ("front", S.SHM_PROBE_WRITE_FRONT, (64, 256, 1024)),
+                                        ("tickets", S.SHM_PROBE_WRITE_TICKETS, (128,))))):
         forms = {f"{form}_wg{w}": probe(kind, w) for form, kind, wgs in kinds for w in wgs}
         best = min(forms, key=forms.get)
         ms = forms[best]
@@ -368,8 +370,8 @@ def hbm_ceilings(torch, S, g, args):
     g.free(a), g.free(b)
     r, w = out["read_only"]["gbs"], out["write_only"]["gbs"]
     return {"kernels": out, "copy_bus_time_limit_frac_hbm": 2.0 / (1.0 / r + 1.0 / w) / HBM_PEAK_GBS,
-            "note": "8 PEs x 256 MiB; read_only / write_only: the better of two access orders (group-owned 64 KiB tiles as in the put; "
-                    "a front of n_wg x 4 KiB per PE sweeping the block); copy = the put itself; copy_bus_time_limit = "
+            "note": "8 PEs x 256 MiB; read_only / write_only: the best of three access orders (group-owned 64 KiB tiles; a front of "
+                    "n_wg x 4 KiB per PE sweeping the block; the put's own walk, 32 KiB pieces by ticket); copy = the put itself; copy_bus_time_limit = "
                     "2 / (1/read + 1/write): a copy whose reads and writes share the bus without overlapping or disturbing each other"}
 
 

@@ -248,9 +248,13 @@ int shm_wall_clock_khz(const shm_ctx *ctx);
  *   SHM_PROBE_COPY   the team put itself (shm_launch_wg_put_all with shift 1, loads/stores);
  *   SHM_PROBE_READ_FRONT, SHM_PROBE_WRITE_FRONT   as READ / WRITE, but the n_wg groups of a PE sweep
  *                    its block together, 4 KiB per group and step (no tiles): the order in which this
- *                    chip writes fastest, so the better of the two forms is the direction's ceiling.
+ *                    chip writes fastest with fixed shares;
+ *   SHM_PROBE_READ_TICKETS, SHM_PROBE_WRITE_TICKETS   as READ / WRITE with the walk of the long put
+ *                    itself: the n_wg groups of a PE (128 is what the put runs) draw 32 KiB pieces of
+ *                    its block by ticket.  The best form of a direction is that direction's ceiling.
  * READ leaves memory unchanged; WRITE overwrites the destination with a pattern of no meaning. */
-enum { SHM_PROBE_READ = 0, SHM_PROBE_WRITE = 1, SHM_PROBE_COPY = 2, SHM_PROBE_READ_FRONT = 3, SHM_PROBE_WRITE_FRONT = 4 };
+enum { SHM_PROBE_READ = 0, SHM_PROBE_WRITE = 1, SHM_PROBE_COPY = 2, SHM_PROBE_READ_FRONT = 3, SHM_PROBE_WRITE_FRONT = 4,
+       SHM_PROBE_READ_TICKETS = 5, SHM_PROBE_WRITE_TICKETS = 6 };
 int shm_launch_stream_probe(shm_ctx *ctx, int kind, uint64_t dst_off, uint64_t src_off, size_t n, int n_wg);
 
 /* ---- device-initiated copy-engine transfers (paper section "Synchronization with Host": the

@@ -398,25 +398,26 @@ unsigned tile_groups(size_t n, int n_wg, size_t tiles_per_group = TILES_PER_GROU
     return static_cast<unsigned>(want < static_cast<size_t>(n_wg) ? (want ? want : 1) : n_wg);
 }
 
-// Team puts and gets of 32 MiB or more per PE by 512 or more groups per PE are swept as fronts:
-// the message is cut into segments of 32 MiB and 512 groups sweep each segment together
-// (shm_copy_front; a lane's successive accesses are 2 MiB apart, a group moves 64 KiB of its segment).
-// Measured on MI355X, 8 PEs x 1024 groups asked for, three placements each: 64 MiB 80.4-80.8 % of the
-// HBM roofline (tiles 78.9), 96 MiB 80.7 (79.4), 128 MiB 80.6-81.0 (78.1-79.1), 192 MiB 79.5-80.7
-// (78.2), 256 MiB 79.8-80.7 (78.9-79.7).  One front over the whole message is level up to 64 MiB and
-// falls behind beyond (128 MiB 79.7, 192 MiB 74-78, 256 MiB 73-77: the longer the sweep, the further
-// the groups drift apart); segments of 16 MiB lose a point, of 8 MiB seven.  4 PEs x 64 / 128 MiB, one
-// front: 79.0 / 79.9 (tiles 77.5 / 79.0).  Other group counts per segment lose (256: -1 point, 1024:
-// -7), and eight separate per-PE launches lose 11 points as fronts: only team grids of 4 to 8 PEs --
-// the shapes measured -- take this form.  Below 32 MiB per PE the virtual blocks are faster (8-16 MiB
-// per PE x 8 PEs stay in the memory-side cache: 89-99 % against 70-78 % as fronts).
-constexpr size_t FRONT_MIN_BYTES = size_t(32) << 20, FRONT_SEG_BYTES = size_t(32) << 20;
-constexpr int FRONT_GROUPS_PER_SEGMENT = 512;
-bool use_front(uint64_t dst_off, uint64_t src_off, size_t n, int n_wg, int grid_pes)
+// Team puts and gets of 32 MiB or more per PE asked of 128 or more groups per PE, in grids of four
+// PEs or more, run 128 groups per PE that stay in the kernel and draw half-tile pieces (32 KiB) by
+// ticket, in address order, from a counter pair in their PE's tail (shm_copy_tiles_ticketed; the
+// pair sets itself back, so a recorded launch replays).  Measured on MI355X over twelve random
+// placements of the buffers, min / mean / max percent of the HBM roofline: 8 PEs x 256 MiB 83.9 /
+// 84.1 / 84.4, 128 MiB 83.4 / 83.7 / 83.9, 64 MiB 82.2 / 82.6 / 83.0, 48 MiB 81.1 / 81.9 / 82.2, 32 MiB
+// 79.5 / 80.4 / 80.9; 6 PEs x 256 / 64 MiB 84.2 / 82.0 mean; 4 PEs 83.7 / 80.6.  The forms it replaces:
+// fronts (512 groups sweeping each 32 MiB segment together, 4 KiB per group and step) 77.4 / 79.2 / 80.1
+// at 8 x 256 MiB and 74.8 / 79.9 / 81.7 at 64 MiB -- their rate follows the distance between destination
+// and source modulo 128 MiB --, group-owned tiles 77-79 %.  The number of groups is the window: 128 x
+// 32 KiB = 4 MiB per PE is what this memory system likes (112 or 144 groups: 81.6 % at 8 x 256 MiB, 96 or
+// 192: 81.5, 256: 82.0; the same at 4 and 6 PEs).  Below 32 MiB per PE the virtual blocks are faster (8-16
+// MiB per PE x 8 PEs stay in the memory-side cache).
+constexpr size_t TICKETS_MIN_BYTES = size_t(32) << 20;
+constexpr int TICKET_GROUPS = 128;
+bool use_tickets(uint64_t dst_off, uint64_t src_off, size_t n, int n_wg, int grid_pes)
 {
-    return ((dst_off | src_off) & 15) == 0 && n >= FRONT_MIN_BYTES && n_wg >= FRONT_GROUPS_PER_SEGMENT && grid_pes >= 4 && grid_pes <= 8;
+    return ((dst_off | src_off) & 15) == 0 && n >= TICKETS_MIN_BYTES && n_wg >= TICKET_GROUPS && grid_pes >= 4;
 }
-unsigned front_segments(size_t n) { return static_cast<unsigned>((n + FRONT_SEG_BYTES - 1) / FRONT_SEG_BYTES); }
+uint64_t ticket_pair_off(const shm_ctx *c, unsigned pair) { return c->user_bytes + SHMD_INTERNAL_TICKETS + 8ull * pair; }
 
 // Long, 16-byte-aligned messages moved by a grid that fills the chip take the group-owned-tile kernel.
 bool use_tiles(uint64_t dst_off, uint64_t src_off, size_t n, int n_wg, int grid_pes)
@@ -445,7 +446,7 @@ int wg_rma(shm_ctx *c, int me, int pe, uint64_t dst_off, uint64_t src_off, size_
     const int shift = (pe - me + c->npes) % c->npes;
     if (use_tiles(dst_off, src_off, n, n_wg, 1)) {
         hipLaunchKernelGGL(shmk_wg_rma_tiles, dim3(tile_groups(n, n_wg), 1), dim3(SHMK_WG), TILES_LDS_BYTES, c->stream[me], c->base,
-                           static_cast<uint64_t>(c->part_bytes), dst_off, src_off, n, c->npes, me, shift, is_get, 0, size_t(0));
+                           static_cast<uint64_t>(c->part_bytes), dst_off, src_off, n, c->npes, me, shift, is_get, uint64_t(0));
         return launched("work-group put/get (tiles)");
     }
     hipLaunchKernelGGL(shmk_wg_rma, dim3(n_wg, 1), dim3(SHMK_WG), 0, c->stream[me], dev_view(c), dst_off, src_off, n, me, shift,
@@ -484,13 +485,13 @@ int wg_rma_all(shm_ctx *c, int pe_shift, uint64_t dst_off, uint64_t src_off, siz
     }
     if (c->team_sync)
         if (int r = team_join(c)) return r;
-    if (use_front(dst_off, src_off, n, n_wg, c->npes)) {
-        hipLaunchKernelGGL(shmk_wg_rma_tiles, dim3(FRONT_GROUPS_PER_SEGMENT * front_segments(n), c->npes), dim3(SHMK_WG), TILES_LDS_BYTES,
-                           c->stream[0], c->base, static_cast<uint64_t>(c->part_bytes), dst_off, src_off, n, c->npes, 0, pe_shift, is_get,
-                           FRONT_GROUPS_PER_SEGMENT, FRONT_SEG_BYTES);
+    if (use_tickets(dst_off, src_off, n, n_wg, c->npes)) {
+        hipLaunchKernelGGL(shmk_wg_rma_tiles, dim3(TICKET_GROUPS, c->npes), dim3(SHMK_WG), TILES_LDS_BYTES, c->stream[0], c->base,
+                           static_cast<uint64_t>(c->part_bytes), dst_off, src_off, n, c->npes, 0, pe_shift, is_get,
+                           ticket_pair_off(c, SHMD_TICKET_TEAM));
     } else if (use_tiles(dst_off, src_off, n, n_wg, c->npes)) {
         hipLaunchKernelGGL(shmk_wg_rma_tiles, dim3(tile_groups(n, n_wg), c->npes), dim3(SHMK_WG), TILES_LDS_BYTES, c->stream[0], c->base,
-                           static_cast<uint64_t>(c->part_bytes), dst_off, src_off, n, c->npes, 0, pe_shift, is_get, 0, size_t(0));
+                           static_cast<uint64_t>(c->part_bytes), dst_off, src_off, n, c->npes, 0, pe_shift, is_get, uint64_t(0));
     } else {
         hipLaunchKernelGGL(shmk_wg_rma, dim3(n_wg, c->npes), dim3(SHMK_WG), 0, c->stream[0], dev_view(c), dst_off, src_off, n, 0,
                            pe_shift, is_get);
@@ -931,15 +932,12 @@ int shm_launch_wg_put_timed(shm_ctx *c, int me, int pe, uint64_t dst_off, uint64
     if (c->no_device) return no_device("shm_launch_wg_put_timed");
     if (int r = begin_pe_launch(c, me)) return r;
     const bool tiles = use_tiles(dst_off, src_off, n, n_wg, 1);
-    // A put that its own quiet follows keeps its groups in the kernel, so the groups should be few and
-    // long-lived, and they draw their tiles by ticket (shm_copy_tiles_ticketed; one counter per
-    // repetition in the PE's own tail, cleared here -- this entry point is not for graph capture):
-    // measured with 8 PEs at once on 4 hardware queues, 64 / 128 / 256 MiB per PE, by groups per PE:
-    // 64 groups 68.1 / 71.4 / 73.9 % of the roofline, 80: 72.2 / 75.6 / 77.5, 96: 73.0 / 77.0 / 78.4,
-    // 128: 72.3 / 76.0 / 77.8, 192: 68.2 / 74.0 / 77.3; fixed shares, 128 groups: 70.4 / 74.6 / 75.1.
-    // More repetitions than there are counters take fixed shares, eight tiles or more per group.
+    // A put that its own quiet follows keeps its groups in the kernel anyway; from 32 MiB they draw
+    // half-tile pieces by ticket (shm_copy_tiles_ticketed), one counter per repetition in the PE's own tail,
+    // cleared here -- this entry point is not for graph capture.  More repetitions than there are
+    // counters take fixed shares, eight tiles or more per group.
     const size_t n_tiles = (n + TILE_BYTES - 1) / TILE_BYTES;
-    const bool tickets = tiles && reps <= static_cast<int>(SHMD_TICKET_WORDS);
+    const bool tickets = tiles && reps <= static_cast<int>(SHMD_TICKET_TIMED_WORDS);
     const size_t per_group = tickets ? std::max(TILES_PER_GROUP, n_tiles / TIMED_TICKET_GROUPS) : std::max(2 * TILES_PER_GROUP, n_tiles / 128);
     if (tickets)
         HIP_TRY(hipMemsetAsync(c->base + static_cast<size_t>(me) * c->part_bytes + c->user_bytes + SHMD_INTERNAL_TICKETS, 0, 8u * reps,
@@ -961,7 +959,7 @@ int shm_launch_wg_put_timed(shm_ctx *c, int me, int pe, uint64_t dst_off, uint64
 int shm_launch_stream_probe(shm_ctx *c, int kind, uint64_t dst_off, uint64_t src_off, size_t n, int n_wg)
 {
     if (int r = check_ctx(c)) return r;
-    if (kind < SHM_PROBE_READ || kind > SHM_PROBE_WRITE_FRONT) return fail(SHM_EINVAL, "unknown probe kind %d", kind);
+    if (kind < SHM_PROBE_READ || kind > SHM_PROBE_WRITE_TICKETS) return fail(SHM_EINVAL, "unknown probe kind %d", kind);
     if (int r = rma_args(c, 0, c->npes > 1 ? 1 : 0, dst_off, src_off, n)) return r;
     if (n == 0 || n % 65536 || ((dst_off | src_off) & 15)) return fail(SHM_EINVAL, "the probe moves whole 64 KiB tiles at 16-byte aligned offsets");
     if (int r = check_team_grid(c, n_wg)) return r;
@@ -971,16 +969,20 @@ int shm_launch_stream_probe(shm_ctx *c, int kind, uint64_t dst_off, uint64_t src
     if (c->team_sync)
         if (int r = team_join(c)) return r;
     const int shift = c->npes > 1 ? 1 : 0;
-    const bool front = kind == SHM_PROBE_READ_FRONT || kind == SHM_PROBE_WRITE_FRONT;
-    const dim3 grid(front ? n_wg : tile_groups(n, n_wg), c->npes), block(SHMK_WG);
-    if (kind == SHM_PROBE_READ)
-        hipLaunchKernelGGL((shmk_stream_probe<0, 0>), grid, block, TILES_LDS_BYTES, c->stream[0], dev_view(c), dst_off, src_off, n, shift, 0x5eedf00du);
-    else if (kind == SHM_PROBE_WRITE)
-        hipLaunchKernelGGL((shmk_stream_probe<1, 0>), grid, block, TILES_LDS_BYTES, c->stream[0], dev_view(c), dst_off, src_off, n, shift, 0x5eedf00du);
-    else if (kind == SHM_PROBE_READ_FRONT)
-        hipLaunchKernelGGL((shmk_stream_probe<0, 1>), grid, block, TILES_LDS_BYTES, c->stream[0], dev_view(c), dst_off, src_off, n, shift, 0x5eedf00du);
-    else
-        hipLaunchKernelGGL((shmk_stream_probe<1, 1>), grid, block, TILES_LDS_BYTES, c->stream[0], dev_view(c), dst_off, src_off, n, shift, 0x5eedf00du);
+    const bool tiles = kind == SHM_PROBE_READ || kind == SHM_PROBE_WRITE;
+    const dim3 grid(tiles ? tile_groups(n, n_wg) : n_wg, c->npes), block(SHMK_WG);
+    const uint64_t pair = ticket_pair_off(c, SHMD_TICKET_PROBE);
+    auto launch = [&](auto kernel) {
+        hipLaunchKernelGGL(kernel, grid, block, TILES_LDS_BYTES, c->stream[0], dev_view(c), dst_off, src_off, n, shift, 0x5eedf00du, pair);
+    };
+    switch (kind) {
+    case SHM_PROBE_READ: launch(shmk_stream_probe<0, 0>); break;
+    case SHM_PROBE_WRITE: launch(shmk_stream_probe<1, 0>); break;
+    case SHM_PROBE_READ_FRONT: launch(shmk_stream_probe<0, 1>); break;
+    case SHM_PROBE_WRITE_FRONT: launch(shmk_stream_probe<1, 1>); break;
+    case SHM_PROBE_READ_TICKETS: launch(shmk_stream_probe<0, 2>); break;
+    default: launch(shmk_stream_probe<1, 2>); break;
+    }
     if (int r = launched("stream probe")) return r;
     if (c->team_sync)
         if (int r = team_fork(c)) return r;

@@ -374,14 +374,31 @@ __device__ __forceinline__ void shm_copy_parts(char *dst, const char *src, size_
 // (77-79 % otherwise); the per-column form it replaces measured 82 % at its best placement and 72-77 %
 // at the others.  dst and src are 16-byte aligned, n is a multiple of 16.
 // ------------------------------------------------------------------------------------------
-// One whole tile of the walk: the stores of the columns loaded LAG steps ago, each followed by the
-// load of the next column.  The first LAG of those stores belong to the previous tile, at `prev`;
-// the FIRST tile of a walk has none (a compile-time case of its own: with a run-time flag the
-// compiler peels the first tile itself and its copies of those loads lose the nontemporal hint,
-// after which a repeated transfer finds an eighth of its source in the memory-side cache and
-// measures 3-5 points more than a transfer of fresh data does).
-template <int U, unsigned CPW, unsigned LAG, bool FIRST>
-__device__ __forceinline__ void shm_tile_walk(shm_u32x4 *d, const shm_u32x4 *s, size_t base, size_t prev, unsigned rot,
+// What a walk does with a column: copy it (the library's puts and gets), only read it, or only write
+// it (the one-direction probes of the memory system, which must walk exactly as the copy does).
+struct shm_walk_copy {
+    __device__ __forceinline__ shm_u32x4 load(const shm_u32x4 *p) const { return shm_ld16(p); }
+    __device__ __forceinline__ void store(shm_u32x4 *p, shm_u32x4 v) { shm_st16(p, v); }
+};
+struct shm_walk_read {                 // the loads are folded into a word that the caller keeps alive
+    uint32_t fold = 0;
+    __device__ __forceinline__ shm_u32x4 load(const shm_u32x4 *p) const { return shm_ld16(p); }
+    __device__ __forceinline__ void store(shm_u32x4 *, shm_u32x4 v) { fold ^= v.x ^ v.y ^ v.z ^ v.w; }
+};
+struct shm_walk_write {                // nothing is loaded: every store writes the pattern
+    shm_u32x4 pattern;
+    __device__ __forceinline__ shm_u32x4 load(const shm_u32x4 *) const { return pattern; }
+    __device__ __forceinline__ void store(shm_u32x4 *p, shm_u32x4 v) { shm_st16(p, v); }
+};
+
+// One whole tile (or piece of a tile) of the walk: the stores of the columns loaded LAG steps ago,
+// each followed by the load of the next column.  The first LAG of those stores belong to the
+// previous tile, at `prev`; the FIRST tile of a walk has none (a compile-time case of its own: with
+// a run-time flag the compiler peels the first tile itself and its copies of those loads lose the
+// nontemporal hint, after which a repeated transfer finds an eighth of its source in the memory-side
+// cache and measures 3-5 points more than a transfer of fresh data does).
+template <int U, unsigned CPW, unsigned LAG, bool FIRST, typename OPS>
+__device__ __forceinline__ void shm_tile_walk(OPS &ops, shm_u32x4 *d, const shm_u32x4 *s, size_t base, size_t prev, unsigned rot,
                                               shm_u32x4 (&r)[LAG][U])
 {
     constexpr size_t rowv = 2048;                        // 32 KiB
@@ -391,28 +408,28 @@ __device__ __forceinline__ void shm_tile_walk(shm_u32x4 *d, const shm_u32x4 *s, 
         const unsigned slot = c % LAG;                   // holds the column loaded LAG steps ago
         if (c >= LAG) {
 #pragma unroll
-            for (int u = 0; u < U; ++u) shm_st16(d + base + col(c - LAG) + u * rowv, r[slot][u]);
+            for (int u = 0; u < U; ++u) ops.store(d + base + col(c - LAG) + u * rowv, r[slot][u]);
         } else if (!FIRST) {
 #pragma unroll
-            for (int u = 0; u < U; ++u) shm_st16(d + prev + col(c + CPW - LAG) + u * rowv, r[slot][u]);
+            for (int u = 0; u < U; ++u) ops.store(d + prev + col(c + CPW - LAG) + u * rowv, r[slot][u]);
         }
 #pragma unroll
-        for (int u = 0; u < U; ++u) r[slot][u] = shm_ld16(s + base + col(c) + u * rowv);
+        for (int u = 0; u < U; ++u) r[slot][u] = ops.load(s + base + col(c) + u * rowv);
     }
 }
 // The stores still owed to the last whole tile of a walk.
-template <int U, unsigned CPW, unsigned LAG>
-__device__ __forceinline__ void shm_tile_walk_end(shm_u32x4 *d, size_t prev, unsigned rot, shm_u32x4 (&r)[LAG][U])
+template <int U, unsigned CPW, unsigned LAG, typename OPS>
+__device__ __forceinline__ void shm_tile_walk_end(OPS &ops, shm_u32x4 *d, size_t prev, unsigned rot, shm_u32x4 (&r)[LAG][U])
 {
     constexpr size_t rowv = 2048;
 #pragma unroll
     for (unsigned c = CPW - LAG; c < CPW; ++c)
 #pragma unroll
-        for (int u = 0; u < U; ++u) shm_st16(d + prev + static_cast<size_t>((c + rot) & (CPW - 1)) * 64 + u * rowv, r[c % LAG][u]);
+        for (int u = 0; u < U; ++u) ops.store(d + prev + static_cast<size_t>((c + rot) & (CPW - 1)) * 64 + u * rowv, r[c % LAG][u]);
 }
 // The last, partial tile of a message of nvec vectors: column by column, no lag.
-template <int U, unsigned CPW>
-__device__ __forceinline__ void shm_tile_partial(shm_u32x4 *d, const shm_u32x4 *s, size_t base, size_t nvec)
+template <int U, unsigned CPW, typename OPS>
+__device__ __forceinline__ void shm_tile_partial(OPS &ops, shm_u32x4 *d, const shm_u32x4 *s, size_t base, size_t nvec)
 {
     constexpr size_t rowv = 2048;
     for (unsigned c = 0; c < CPW; ++c) {
@@ -420,10 +437,10 @@ __device__ __forceinline__ void shm_tile_partial(shm_u32x4 *d, const shm_u32x4 *
         shm_u32x4 q[U];
 #pragma unroll
         for (int u = 0; u < U; ++u)
-            if (i + u * rowv < nvec) q[u] = shm_ld16(s + i + u * rowv);
+            if (i + u * rowv < nvec) q[u] = ops.load(s + i + u * rowv);
 #pragma unroll
         for (int u = 0; u < U; ++u)
-            if (i + u * rowv < nvec) shm_st16(d + i + u * rowv, q[u]);
+            if (i + u * rowv < nvec) ops.store(d + i + u * rowv, q[u]);
     }
 }
 
@@ -441,77 +458,124 @@ __device__ __forceinline__ void shm_copy_tiles_impl(char *dst, const char *src, 
     static_assert(CPW % LAG == 0, "a register slot is refilled by the column LAG steps later, also across tiles");
     const unsigned rot = part & (CPW - 1);
     const size_t lane_off = static_cast<size_t>(wave * CPW) * 64 + lane;
+    shm_walk_copy ops;
     if (part < nwhole) {
         shm_u32x4 r[LAG][U];
         size_t prev = part * tilev + lane_off;
-        shm_tile_walk<U, CPW, LAG, true>(d, s, prev, 0, rot, r);
+        shm_tile_walk<U, CPW, LAG, true>(ops, d, s, prev, 0, rot, r);
         for (size_t t = part + nparts; t < nwhole; t += nparts) {
             const size_t base = t * tilev + lane_off;
-            shm_tile_walk<U, CPW, LAG, false>(d, s, base, prev, rot, r);
+            shm_tile_walk<U, CPW, LAG, false>(ops, d, s, base, prev, rot, r);
             prev = base;
         }
-        shm_tile_walk_end<U, CPW, LAG>(d, prev, rot, r);
+        shm_tile_walk_end<U, CPW, LAG>(ops, d, prev, rot, r);
     }
-    if (nwhole * tilev < nvec && nwhole % nparts == part) shm_tile_partial<U, CPW>(d, s, nwhole * tilev + lane_off, nvec);
+    if (nwhole * tilev < nvec && nwhole % nparts == part) shm_tile_partial<U, CPW>(ops, d, s, nwhole * tilev + lane_off, nvec);
 }
 
-// The same tiles dealt by tickets instead of by group number: every group draws the number of its
-// next tile from a counter (one atomic per 64 KiB, drawn a tile ahead so that its latency is hidden),
-// until it draws a number past the last tile.  For groups that stay resident through a whole put --
-// a put issued from a running kernel and followed by the group's quiet -- this evens out what fixed
-// shares cannot: the groups of a kernel do not get equal parts of the memory bandwidth (measured
-// with 8 PEs x 128 groups x 64 MiB: half of a kernel's groups finish their fixed share in 200 us,
-// the other half in 370-390 us, and while those finish most of the chip has nothing left to do).
-// *counter must read first_ticket when the first group arrives and is left at first_ticket + tiles
-// + groups (every group draws exactly one ticket too many).  `part` only rotates the column walk.
-// dst and src 16-byte aligned, n a multiple of 16; every thread of the group calls.
-template <int U, int NWAVES>
-__device__ __forceinline__ void shm_copy_tiles_ticketed(char *dst, const char *src, size_t n, unsigned part, unsigned long long *counter,
-                                                        unsigned long long first_ticket)
+// ------------------------------------------------------------------------------------------
+// Tiles by ticket: the form of the long put.  The groups of a PE stay in the kernel and draw what
+// they move next from a counter, in address order: a ticket is one of the PIECES equal parts of a
+// 64 KiB tile (each wave's columns cut into PIECES runs; with 4 waves and PIECES = 2 a piece is 32 KiB:
+// four columns of 1 KiB per wave in each of the tile's two rows), the partial tile at the end of the
+// message is one ticket.  Thread 0 draws the next number one piece ahead, so the atomic's latency is
+// hidden behind the piece being moved, and hands it to the group through one of two LDS slots and one
+// barrier per piece; the stores still trail the loads by LAG columns across pieces.  A group stops at
+// the first number past the last piece.  With own_groups != 0 the first piece of group `part` is piece
+// `part`, without a ticket (own_groups = number of groups drawing from this counter; tickets then
+// start at that piece), which saves the one round trip nothing could hide.
+// What it buys (measured on MI355X, puts of 32-256 MiB per PE, 4-8 PEs):
+//   * what the chip touches at one moment is a compact window per PE that sweeps through the message
+//     -- with 128 groups per PE and 32 KiB pieces, 4 MiB -- however unevenly the memory system serves
+//     the groups; fixed shares drift apart and scatter the accesses;
+//   * no group waits for work while another still has some: groups of one kernel are not served
+//     equally (the ones started first are served first; with fixed shares half of a kernel's groups
+//     finish in 200 us and the other half in 370-390 us), and the end of the transfer costs one
+//     piece's time instead of one share's.
+// 8 PEs x 128 groups, half-tile pieces: 84.1 % of the HBM roofline at 256 MiB per PE, 83.7 % at 128 MiB,
+// 82.6 % at 64 MiB, within +-0.4 points over twelve random placements of the buffers (fixed tiles
+// 77-79 %, fronts of 512 groups over 32 MiB segments 74-81 % depending on the placement); whole-tile
+// pieces 81.1 / 80.7 / 79.7, quarter-tile pieces as half-tile ones; 112 or 144 groups per PE 81.6 %, 96
+// or 192 81.5 %, 256 82.0 %: the window of 128 x 32 KiB = 4 MiB is the one this memory system likes.
+// *counter must read first_ticket when the first group arrives and is left somewhere beyond the
+// last ticket (every group that moved anything draws one ticket too many): whoever launches clears
+// it, or the groups do (shm_tickets_done).  `part` also rotates the column walk.  dst and src 16-byte aligned, n a multiple of 16; every thread of the
+// group calls.
+// ------------------------------------------------------------------------------------------
+template <int U, int NWAVES, int PIECES, typename OPS>
+__device__ __forceinline__ void shm_walk_tiles_ticketed(OPS &ops, char *dst, const char *src, size_t n, unsigned part,
+                                                        unsigned long long *counter, unsigned long long first_ticket, unsigned own_groups)
 {
     __shared__ unsigned long long drawn[2];
     const shm_u32x4 *s = reinterpret_cast<const shm_u32x4 *>(src);
     shm_u32x4 *d = reinterpret_cast<shm_u32x4 *>(dst);
     const size_t nvec = n >> 4;
     constexpr size_t tilev = 2048 * U;
-    const size_t nwhole = nvec / tilev, ntiles = nwhole + (nwhole * tilev < nvec ? 1 : 0);
+    const size_t nwhole = nvec / tilev;
+    const size_t npieces = nwhole * PIECES, ntickets = npieces + (nwhole * tilev < nvec ? 1 : 0);
     const unsigned wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-    constexpr unsigned CPW = 32 / NWAVES;
-    constexpr unsigned LAG = CPW < 4 ? CPW : 4;
-    static_assert(CPW % LAG == 0, "a register slot is refilled by the column LAG steps later, also across tiles");
-    const unsigned rot = part & (CPW - 1);
+    constexpr unsigned CPW = 32 / NWAVES;                // a wave's columns in a whole tile
+    constexpr unsigned CPP = CPW / PIECES;               // ... and in one piece
+    static_assert(CPP >= 1 && CPP * PIECES == CPW, "whole columns per piece");
+    constexpr unsigned LAG = CPP < 4 ? CPP : 4;
+    static_assert(CPP % LAG == 0, "a register slot is refilled by the column LAG steps later, also across pieces");
+    const unsigned rot = part & (CPP - 1);
     const size_t lane_off = static_cast<size_t>(wave * CPW) * 64 + lane;
-    auto draw = [&]() { return __hip_atomic_fetch_add(counter, 1ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) - first_ticket; };
+    auto at = [&](size_t t) { return (t / PIECES) * tilev + (t % PIECES) * (CPP * 64) + lane_off; };
+    auto draw = [&]() {
+        return own_groups + __hip_atomic_fetch_add(counter, 1ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) - first_ticket;
+    };
     shm_u32x4 r[LAG][U];
     size_t prev = 0;
     unsigned long long pending = 0;
     unsigned it = 0;
-    // hands the number drawn during this tile to the group; two slots: the other one may still be being read
+    // hands the number drawn during this piece to the group; two slots: the other one may still be being read
     auto next = [&]() {
         if (threadIdx.x == 0) drawn[(it + 1) & 1] = pending;
         __syncthreads();
         ++it;
         return static_cast<size_t>(drawn[it & 1]);
     };
-    if (threadIdx.x == 0) drawn[0] = draw();
-    __syncthreads();
-    size_t t = drawn[0];
-    if (t < nwhole) {                                          // the walk's first tile has no stores owed
-        if (threadIdx.x == 0) pending = draw();              // the next tile's number, on its way while this tile moves
-        prev = t * tilev + lane_off;
-        shm_tile_walk<U, CPW, LAG, true>(d, s, prev, 0, rot, r);
-        for (t = next(); t < nwhole; t = next()) {
+    size_t t = part;
+    if (own_groups == 0) {
+        if (threadIdx.x == 0) drawn[0] = draw();
+        __syncthreads();
+        t = drawn[0];
+    }
+    if (t < npieces) {                                         // the walk's first piece has no stores owed
+        if (threadIdx.x == 0) pending = draw();              // the next piece's number, on its way while this piece moves
+        prev = at(t);
+        shm_tile_walk<U, CPP, LAG, true>(ops, d, s, prev, 0, rot, r);
+        for (t = next(); t < npieces; t = next()) {
             if (threadIdx.x == 0) pending = draw();
-            const size_t base = t * tilev + lane_off;
-            shm_tile_walk<U, CPW, LAG, false>(d, s, base, prev, rot, r);
+            const size_t base = at(t);
+            shm_tile_walk<U, CPP, LAG, false>(ops, d, s, base, prev, rot, r);
             prev = base;
         }
-        shm_tile_walk_end<U, CPW, LAG>(d, prev, rot, r);
+        shm_tile_walk_end<U, CPP, LAG>(ops, d, prev, rot, r);
     }
-    if (t < ntiles) {                                          // the partial tile; whoever draws it draws once more
+    if (t < ntickets) {                                        // the partial tile (drawn, or a group's own); one more draw ends the walk
         if (threadIdx.x == 0) pending = draw();
-        shm_tile_partial<U, CPW>(d, s, t * tilev + lane_off, nvec);
+        shm_tile_partial<U, CPW>(ops, d, s, nwhole * tilev + lane_off, nvec);
         (void)next();
+    }
+}
+template <int U, int NWAVES, int PIECES = 2>
+__device__ __forceinline__ void shm_copy_tiles_ticketed(char *dst, const char *src, size_t n, unsigned part, unsigned long long *counter,
+                                                        unsigned long long first_ticket, unsigned own_groups = 0)
+{
+    shm_walk_copy ops;
+    shm_walk_tiles_ticketed<U, NWAVES, PIECES>(ops, dst, src, n, part, counter, first_ticket, own_groups);
+}
+
+// A counter pair (ticket word, then a word that counts the groups that are through) that the last
+// of `groups` groups to finish sets back to zero, so that the next launch -- or the next replay of
+// a recorded one -- finds it as this one did.  Thread 0 of every group calls once, after its walk.
+__device__ __forceinline__ void shm_tickets_done(unsigned long long *pair, unsigned groups)
+{
+    if (__hip_atomic_fetch_add(pair + 1, 1ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == groups - 1) {
+        __hip_atomic_store(pair + 1, 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __hip_atomic_store(pair, 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
 }
 
@@ -526,43 +590,6 @@ __device__ __forceinline__ void shm_copy_tiles(char *dst, const char *src, size_
     case 1024: shm_copy_tiles_impl<U, 16>(dst, src, n, part, nparts); break;
     default: shm_copy_parts<8, SHM_ST_STREAM>(dst, src, n, part, nparts); break;      // any other group size: the general dealing
     }
-}
-
-// ------------------------------------------------------------------------------------------
-// A front: the third dealing, for long messages moved by a chip-filling team grid.  The nparts
-// groups sweep a segment of the message together: in step k group g moves the 4 KiB piece
-// k * nparts + g (one vector per lane), so what the chip touches at one moment is a few compact
-// windows -- the order in which this memory system both reads and writes fastest when it does only
-// one of the two.  A lane keeps two steps in flight and stores the vector of two steps ago right
-// before it loads the next one into the same register (loads and stores alternate one by one).
-// Measured on MI355X, 8 PEs, 512 groups per segment of 32 MiB: 80-81 % of the HBM roofline from 64
-// to 256 MiB per PE for every placement tried (group-owned tiles: 78-80 %).  A sweep should stay
-// short: one front over 192-256 MiB measures 73-78 %, because the groups drift apart.
-// dst and src are 16-byte aligned, n is a multiple of 16.
-// ------------------------------------------------------------------------------------------
-__device__ __forceinline__ void shm_copy_front(char *dst, const char *src, size_t n, unsigned part, unsigned nparts)
-{
-    const shm_u32x4 *s = reinterpret_cast<const shm_u32x4 *>(src);
-    shm_u32x4 *d = reinterpret_cast<shm_u32x4 *>(dst);
-    const size_t nvec = n >> 4, step = static_cast<size_t>(nparts) * blockDim.x;
-    const size_t whole = nvec - nvec % (2 * step);           // vectors in whole pairs of steps
-    size_t i = static_cast<size_t>(part) * blockDim.x + threadIdx.x;
-    shm_u32x4 r0, r1;
-    if (i < whole) {
-        r0 = shm_ld16(s + i);
-        r1 = shm_ld16(s + i + step);
-        size_t prev = i;
-        for (i += 2 * step; i < whole; i += 2 * step) {
-            shm_st16(d + prev, r0);
-            r0 = shm_ld16(s + i);
-            shm_st16(d + prev + step, r1);
-            r1 = shm_ld16(s + i + step);
-            prev = i;
-        }
-        shm_st16(d + prev, r0);
-        shm_st16(d + prev + step, r1);
-    }
-    for (i = whole + static_cast<size_t>(part) * blockDim.x + threadIdx.x; i < nvec; i += step) shm_st16(d + i, shm_ld16(s + i));
 }
 
 // ------------------------------------------------------------------------------------------
@@ -716,13 +743,11 @@ __device__ __forceinline__ void shmx_getmem_parts(const shm_dev_ctx &c, int me, 
 // the last n mod 16 bytes are copied by group 0.  NWAVES != 0 states the group size at compile time
 // (64 * NWAVES work-items; the library's own kernels do), 0 takes it from blockDim.
 template <int NWAVES = 0>
-__device__ __forceinline__ void shmx_copy_tiles_wg(char *d, const char *s, size_t n, unsigned part, unsigned nparts, bool front = false)
+__device__ __forceinline__ void shmx_copy_tiles_wg(char *d, const char *s, size_t n, unsigned part, unsigned nparts)
 {
     __syncthreads();
     const size_t body = n & ~static_cast<size_t>(15);
-    if (front)
-        shm_copy_front(d, s, body, part, nparts);
-    else if (NWAVES)
+    if (NWAVES)
         shm_copy_tiles_impl<2, NWAVES ? NWAVES : 1>(d, s, body, part, nparts);
     else
         shm_copy_tiles<2>(d, s, body, part, nparts);
@@ -743,19 +768,21 @@ __device__ __forceinline__ void shmx_getmem_tiles(const shm_dev_ctx &c, int me, 
     shmx_copy_tiles_wg<NWAVES>(shm_ptr(c, dst_off, me), shm_ptr(c, src_off, pe), n, part, nparts);
 }
 
-// A long put shared by groups that draw their tiles from a ticket counter (shm_copy_tiles_ticketed):
-// for groups that stay in the kernel after the put.  `counter` is a 64-bit word in device memory
-// that reads first_ticket before the first group arrives; NWAVES states the group size
+// A long put shared by groups that draw what they move from a ticket counter (shm_copy_tiles_ticketed):
+// for groups that stay in the kernel.  `counter` is a 64-bit word in device memory that reads
+// first_ticket before the first group arrives; own_groups: 0, or the number of groups that draw from
+// it, group `part` of them then starting on piece `part` without a ticket.  NWAVES states the group size
 // (64 * NWAVES work-items).  Offsets 16-byte aligned; the last n mod 16 bytes are copied by group 0.
 template <int NWAVES>
 __device__ __forceinline__ void shmx_putmem_tickets(const shm_dev_ctx &c, int me, uint64_t dst_off, uint64_t src_off, size_t n, int pe,
-                                                    unsigned part, unsigned long long *counter, unsigned long long first_ticket)
+                                                    unsigned part, unsigned long long *counter, unsigned long long first_ticket,
+                                                    unsigned own_groups = 0)
 {
     char *d = shm_ptr(c, dst_off, pe);
     const char *s = shm_ptr(c, src_off, me);
     __syncthreads();
     const size_t body = n & ~static_cast<size_t>(15);
-    shm_copy_tiles_ticketed<2, NWAVES>(d, s, body, part, counter, first_ticket);
+    shm_copy_tiles_ticketed<2, NWAVES>(d, s, body, part, counter, first_ticket, own_groups);
     if (part == 0)
         for (size_t i = body + threadIdx.x; i < n; i += blockDim.x) d[i] = s[i];
     __syncthreads();
@@ -789,8 +816,12 @@ __device__ __forceinline__ void shmx_quiet_wg()
 // group's leader runs the protocol.  Small grids (fewer than SHMD_QUIET_SHARED_MIN_GROUPS groups)
 // release directly: an atomic costs more than a write-back nobody queues for.
 #define SHMD_INTERNAL_QUIET 33280u            // 8 words, 128 bytes apart
-#define SHMD_INTERNAL_TICKETS 36864u          // SHMD_TICKET_WORDS uint64: tile tickets of the timed put, one word per repetition
+#define SHMD_INTERNAL_TICKETS 36864u          // SHMD_TICKET_WORDS uint64 in every partition's tail: ticket counters of the long puts
 #define SHMD_TICKET_WORDS 512u
+#define SHMD_TICKET_TIMED_WORDS 504u          // words 0..503: the timed put, one per repetition (cleared by its launcher)
+#define SHMD_TICKET_TEAM 504u                 // a counter pair (ticket, groups through) for team launches ...
+#define SHMD_TICKET_PE 506u                   // ... for a PE's own launches ...
+#define SHMD_TICKET_PROBE 508u                // ... and for the stream probes; the pairs reset themselves (shm_tickets_done)
 #define SHMD_QUIET_SHARED_MIN_GROUPS 64u
 #define SHMD_QUIET_SPIN_LIMIT 4096
 

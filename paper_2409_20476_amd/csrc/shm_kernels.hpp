@@ -26,44 +26,46 @@ __global__ __launch_bounds__(SHMK_WG) void shmk_wg_rma(shm_dev_ctx c, uint64_t d
         shmx_putmem_parts(c, me, dst_off, src_off, n, pe, blockIdx.x, gridDim.x);
 }
 
-// Long messages: group-owned tiles.  The dynamic LDS the host asks for is never touched: it only
-// caps how many groups a CU holds at once.  A group lives for four tiles, so what it does before
-// its first load counts: the kernel takes the heap as base address and partition stride (the
-// library's partitions are equally spaced) instead of the whole device view -- one scalar load of
-// the arguments, no table look-up.
-// front != 0: the message is cut into segments of seg_bytes (a multiple of 16; the last one takes the
-// rest) and `front` groups sweep one segment together (shm_copy_front); the groups of a segment are
-// consecutive in the dispatch order, so the chip works on a few segments at a time.
+// Long messages.  The dynamic LDS the host asks for is never touched: it only caps how many groups a
+// CU holds at once.  What a group does before its first load counts: the kernel takes the heap as
+// base address and partition stride (the library's partitions are equally spaced) instead of the
+// whole device view -- one scalar load of the arguments, no table look-up.
+// ticket_pair_off == 0: group-owned tiles, group g of gridDim.x taking tiles g, g + gridDim.x, ...
+// ticket_pair_off != 0: the offset, in every partition, of a counter pair that reads zero: the
+// gridDim.x groups of a PE draw half-tile pieces by ticket from their own PE's pair (shm_copy_tiles_ticketed;
+// every group starts on the piece of its own number) and the last one through sets the pair back.
 __global__ __launch_bounds__(SHMK_WG) void shmk_wg_rma_tiles(char *base, uint64_t stride, uint64_t dst_off, uint64_t src_off, size_t n,
-                                                             int npes, int me0, int shift, int is_get, int front, size_t seg_bytes)
+                                                             int npes, int me0, int shift, int is_get, uint64_t ticket_pair_off)
 {
     const int me = me0 + blockIdx.y;
     int pe = me + shift;
     if (pe >= npes) pe -= npes;
-    // one copy of the tile walk for both directions: only the two addresses differ
+    // one copy of the walk for both directions: only the two addresses differ
     char *d = base + static_cast<uint64_t>(is_get ? me : pe) * stride + dst_off;
     const char *s = base + static_cast<uint64_t>(is_get ? pe : me) * stride + src_off;
-    if (front) {
-        const unsigned per = static_cast<unsigned>(front), seg = blockIdx.x / per;
-        const size_t lo = static_cast<size_t>(seg) * seg_bytes;          // the host launches exactly ceil(n / seg_bytes) segments
-        const size_t len = n - lo < seg_bytes ? n - lo : seg_bytes;
-        shmx_copy_tiles_wg<SHMK_WG / 64>(d + lo, s + lo, len, blockIdx.x % per, per, true);
+    if (ticket_pair_off == 0) {
+        shmx_copy_tiles_wg<SHMK_WG / 64>(d, s, n, blockIdx.x, gridDim.x);
         return;
     }
-    shmx_copy_tiles_wg<SHMK_WG / 64>(d, s, n, blockIdx.x, gridDim.x, false);
+    unsigned long long *pair = reinterpret_cast<unsigned long long *>(base + static_cast<uint64_t>(me) * stride + ticket_pair_off);
+    const size_t body = n & ~static_cast<size_t>(15);
+    shm_copy_tiles_ticketed<2, SHMK_WG / 64>(d, s, body, blockIdx.x, pair, 0, gridDim.x);
+    if (blockIdx.x == 0)
+        for (size_t i = body + threadIdx.x; i < n; i += SHMK_WG) d[i] = s[i];
+    if (threadIdx.x == 0) shm_tickets_done(pair, gridDim.x);
 }
 
 // One-direction ceilings of the memory system with the access forms of the long-message put: the
-// team grid and the group-owned 64 KiB tiles of shmk_wg_rma_tiles, but every tile is only read
-// (KIND 0: 16-byte nontemporal loads of the source on the calling PE, folded into a word that is
-// stored only if it equals `magic`, which keeps the loads alive) or only written (KIND 1: 16-byte
-// nontemporal stores of a lane-dependent pattern to the destination on the target PE).
-// FRONT != 0: no tiles; the PE's groups sweep the block together, every group one 4 KiB piece of a
-// front of gridDim.x pieces that moves through the block (the pattern that writes fastest on this
-// chip: what runs at one moment touches a few compact windows instead of hundreds of scattered tiles).
-template <int KIND, int FRONT>
+// team grid, but every byte is only read (KIND 0: 16-byte nontemporal loads of the source on the
+// calling PE, folded into a word that is stored only if it equals `magic`, which keeps the loads
+// alive) or only written (KIND 1: 16-byte nontemporal stores of a lane-dependent pattern to the
+// destination on the target PE).
+// FORM 0: group-owned 64 KiB tiles.  FORM 1: a front -- the PE's groups sweep the block together,
+// every group one 4 KiB piece of a front of gridDim.x pieces that moves through the block.  FORM 2:
+// half-tile pieces by ticket, exactly the walk of the long put (ticket_pair_off as there).
+template <int KIND, int FORM>
 __global__ __launch_bounds__(SHMK_WG) void shmk_stream_probe(shm_dev_ctx c, uint64_t dst_off, uint64_t src_off, size_t n, int shift,
-                                                             uint32_t magic)
+                                                             uint32_t magic, uint64_t ticket_pair_off)
 {
     const int me = blockIdx.y;
     int pe = me + shift;
@@ -76,7 +78,23 @@ __global__ __launch_bounds__(SHMK_WG) void shmk_stream_probe(shm_dev_ctx c, uint
     uint32_t fold = 0;
     shm_u32x4 pattern;
     pattern.x = threadIdx.x, pattern.y = blockIdx.x, pattern.z = magic, pattern.w = static_cast<uint32_t>(me);
-    if (FRONT) {
+    if (FORM == 2) {
+        unsigned long long *pair = reinterpret_cast<unsigned long long *>(shm_ptr(c, ticket_pair_off, me));
+        char *db = reinterpret_cast<char *>(d);
+        const char *sb = reinterpret_cast<const char *>(s);
+        if (KIND == 0) {
+            shm_walk_read ops;
+            shm_walk_tiles_ticketed<2, SHMK_WG / 64, 2>(ops, db, sb, n, blockIdx.x, pair, 0, gridDim.x);
+            fold = ops.fold;
+        } else {
+            shm_walk_write ops{pattern};
+            shm_walk_tiles_ticketed<2, SHMK_WG / 64, 2>(ops, db, sb, n, blockIdx.x, pair, 0, gridDim.x);
+        }
+        if (threadIdx.x == 0) shm_tickets_done(pair, gridDim.x);
+        if (KIND == 0 && fold == magic && n == 1) d[0].x = fold;
+        return;
+    }
+    if (FORM == 1) {
         const size_t nvec = n >> 4, step = static_cast<size_t>(gridDim.x) * SHMK_WG;
         size_t i = static_cast<size_t>(blockIdx.x) * SHMK_WG + threadIdx.x;
         for (; i + 3 * step < nvec; i += 4 * step) {           // four steps of the front in flight per lane
@@ -137,7 +155,7 @@ __global__ __launch_bounds__(SHMK_WG) void shmk_wg_put_timed(shm_dev_ctx c, uint
     const unsigned long long t0 = wall_clock64();
     for (int r = 0; r < reps; ++r) {
         if constexpr (FORM == 2)
-            shmx_putmem_tickets<SHMK_WG / 64>(c, me, dst_off, src_off, n, pe, blockIdx.x, tickets + r, 0);
+            shmx_putmem_tickets<SHMK_WG / 64>(c, me, dst_off, src_off, n, pe, blockIdx.x, tickets + r, 0, gridDim.x);
         else if constexpr (FORM == 1)
             shmx_putmem_tiles<SHMK_WG / 64>(c, me, dst_off, src_off, n, pe, blockIdx.x, gridDim.x);
         else

@@ -28,6 +28,7 @@ SHM_INIT_DEFAULT, SHM_INIT_NO_DEVICE = 0, 1
 SHM_STORM_FETCH_ADD, SHM_STORM_ADD, SHM_STORM_CSWAP_LOOP, SHM_STORM_PLAIN_STORE, SHM_STORM_FETCH_ADD_WG = range(5)
 SHM_REDUCE_DUPLICATE, SHM_REDUCE_SPLIT = 0, 1
 SHM_PROBE_READ, SHM_PROBE_WRITE, SHM_PROBE_COPY, SHM_PROBE_READ_FRONT, SHM_PROBE_WRITE_FRONT = 0, 1, 2, 3, 4
+SHM_PROBE_READ_TICKETS, SHM_PROBE_WRITE_TICKETS = 5, 6
 SHM_STATIC_RING_MAX_CHUNKS = 1024
 SHM_COLL_FCOLLECT, SHM_COLL_BROADCAST = 0, 1
 SHM_TEAM_SYNC_OFF, SHM_TEAM_SYNC_FULL, SHM_TEAM_SYNC_TRACKED = 0, 1, 2

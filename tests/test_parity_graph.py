@@ -78,3 +78,34 @@ def test_recorded_team_collectives_replay_correctly():
             for p in range(4):
                 o.heap[(p + 1) % 4][4 * MiB:4 * MiB + 120000] = before[p][3 * MiB + 16:3 * MiB + 16 + 120000]
             assert_heaps_equal(g, o, upto=7 * MiB, what=f"replay {replay}")
+
+
+def test_recorded_long_team_put_and_get_replay_correctly():
+    """The long team put draws its pieces from counters in the heap's tail that the last group through
+    sets back: two such launches recorded back to back (a put and a get, 33 MiB x 4 PEs, ragged last
+    tile, byte tail) and replayed four times with fresh source bytes in between."""
+    g, o = make_pair(4, 112 * MiB)
+    with g:
+        fill_random(g, o, 65, upto=108 * MiB)
+        g.set_team_sync(False)
+        n = 33 * MiB + 65536 + 16 * 5 + 3
+        stream = g.streams[0]
+        graph = torch.cuda.CUDAGraph()
+        torch.cuda.synchronize()
+        with torch.cuda.graph(graph, stream=stream):
+            g.launch_wg_put_all(1, 36 * MiB, 32, n, 1024, S.SHM_PATH_LDST)
+            g.launch_wg_get_all(3, 72 * MiB + 16, 36 * MiB, n, 128, S.SHM_PATH_LDST)
+        rng = np.random.default_rng(66)
+        for replay in range(4):
+            for p in range(4):
+                write_both(g, o, p, 4096 * (replay + 1), rng.integers(0, 256, 200000, dtype=np.uint8))
+            torch.cuda.synchronize()
+            graph.replay()
+            g.barrier_all()
+            before = [h.copy() for h in o.heap]
+            for p in range(4):
+                o.heap[(p + 1) % 4][36 * MiB:36 * MiB + n] = before[p][32:32 + n]
+            before = [h.copy() for h in o.heap]
+            for p in range(4):
+                o.heap[p][72 * MiB + 16:72 * MiB + 16 + n] = before[(p + 3) % 4][36 * MiB:36 * MiB + n]
+            assert_heaps_equal(g, o, upto=108 * MiB, what=f"replay {replay}")

@@ -216,9 +216,9 @@ def test_long_messages_by_64_groups_or_more_take_group_owned_tiles(n_wg):
 @pytest.mark.parametrize("n_wg", [8, 15, 16, 33, 100, 128, 160, 512, 600])
 def test_long_messages_team_forms_on_all_long_message_paths(n_wg):
     """Team grids of 4 PEs, 33 MiB: below 64 groups in the grid (8, 15 per PE) the virtual blocks, from
-    16 per PE group-owned tiles -- up to 128 groups take more than four tiles each, 160 are cut to one
-    group per four tiles --, from 512 per PE the front swept by 512 groups per PE; put_all and get_all,
-    a rest after the whole steps of the front, ragged last tile and byte tail."""
+    16 per PE group-owned tiles (each group more than four tiles), from 128 per PE half-tile pieces
+    drawn by ticket by 128 groups per PE; put_all and get_all back to back (the second launch finds
+    the counters as the first one did), ragged last tile and byte tail."""
     g, o = make_pair(4, 80 * MiB)
     with g:
         fill_random(g, o, 8, upto=76 * MiB)
@@ -233,3 +233,30 @@ def test_long_messages_team_forms_on_all_long_message_paths(n_wg):
             o.heap[p][64:64 + n] = before[(p + 1) % 4][38 * MiB + 4096:38 * MiB + 4096 + n]
         g.barrier_all()
         assert_heaps_equal(g, o, upto=76 * MiB, what="team forms")
+
+
+@pytest.mark.parametrize("npes", [4, 7])
+def test_team_puts_by_ticket_at_the_edges_of_the_piece_count(npes):
+    """Half-tile pieces by ticket (team grids of four PEs or more, 32 MiB or more, 128 groups or more
+    asked): exactly 32 MiB (1024 pieces), one vector more (a partial tile of 16 bytes), one byte more,
+    one tile less than a whole number plus a byte tail, and the same sizes again at once, put and get
+    in turn, so that every launch but the first depends on its predecessor having set the counters back."""
+    g, o = make_pair(npes, 72 * MiB)
+    with g:
+        fill_random(g, o, 9, upto=70 * MiB)
+        sizes = [32 * MiB, 32 * MiB + 16, 32 * MiB + 1, 33 * MiB - 65536 + 17, 32 * MiB + 32768 + 48]
+        for rep, n in enumerate(sizes + sizes[:2]):
+            src, dst = 16 * (rep % 3), 35 * MiB + 16 * (rep % 5)
+            shift = 1 + rep % (npes - 1)
+            if rep % 2 == 0:
+                g.launch_wg_put_all(shift, dst, src, n, 128 + 100 * rep)
+                before = [h.copy() for h in o.heap]
+                for p in range(npes):
+                    o.heap[(p + shift) % npes][dst:dst + n] = before[p][src:src + n]
+            else:
+                g.launch_wg_get_all(shift, src, dst, n, 1024)
+                before = [h.copy() for h in o.heap]
+                for p in range(npes):
+                    o.heap[p][src:src + n] = before[(p + shift) % npes][dst:dst + n]
+            g.barrier_all()
+            assert_heaps_equal(g, o, upto=70 * MiB, what=f"launch {rep}, {n} bytes")
