@@ -411,12 +411,15 @@ unsigned tile_groups(size_t n, int n_wg, size_t tiles_per_group = TILES_PER_GROU
 // 32 KiB = 4 MiB per PE is what this memory system likes (112 or 144 groups: 81.6 % at 8 x 256 MiB, 96 or
 // 192: 81.5, 256: 82.0; the same at 4 and 6 PEs).  Below 32 MiB per PE the virtual blocks are faster (8-16
 // MiB per PE x 8 PEs stay in the memory-side cache).
-constexpr size_t TICKETS_MIN_BYTES = size_t(32) << 20;
+constexpr size_t TICKETS_MIN_BYTES = size_t(32) << 20, FCOLLECT_TICKETS_MIN_BYTES = size_t(8) << 20;
 constexpr int TICKET_GROUPS = 128;
 bool use_tickets(uint64_t dst_off, uint64_t src_off, size_t n, int n_wg, int grid_pes)
 {
     return ((dst_off | src_off) & 15) == 0 && n >= TICKETS_MIN_BYTES && n_wg >= TICKET_GROUPS && grid_pes >= 4;
 }
+// A PE's own launches stay on group-owned tiles: eight per-PE kernels of 128 groups drawing tickets
+// measure what the tiles do (78 % at 8 x 256 MiB, 75-77 % at 64-128 MiB) and one PE launching alone
+// loses a quarter (4.9 against 6.5 TB/s of traffic).
 uint64_t ticket_pair_off(const shm_ctx *c, unsigned pair) { return c->user_bytes + SHMD_INTERNAL_TICKETS + 8ull * pair; }
 
 // Long, 16-byte-aligned messages moved by a grid that fills the chip take the group-owned-tile kernel.
@@ -1517,12 +1520,22 @@ int shm_launch_fcollect(shm_ctx *c, uint64_t dst_off, uint64_t src_off, size_t b
     // runs that many groups, never more than it was asked for.
     const int per_cu = c->num_cu / c->npes > 0 ? c->num_cu / c->npes : 1;
     if (n_wg > per_cu && bytes_per_pe / TILE_BYTES >= 16u * static_cast<size_t>(per_cu)) n_wg = per_cu;
+    // From 8 MiB per PE and 8 PEs on, those groups draw quarter-tile pieces (16 KiB) of their PE's block
+    // by ticket, in address order, and store every column to the destinations in turn (measured, % of
+    // the HBM roofline, fixed tiles -> tickets: 8 PEs x 8 / 16 / 64 MiB 62.9 -> 73.6, 65.5 -> 77.8, 76.9 -> 80.7
+    // -- the write-only ceiling of this chip is 81 % --; 16 PEs 63.1 -> 73.5, 69.8 -> 74.5, 71.2 -> 74.0; with
+    // 4 or 6 PEs, or other numbers of groups -- 8 PEs: 24 groups 69 %, 40 and more 76-77 % --, nothing is gained).
+    uint64_t pair = 0;
+    if (((dst_off | src_off | bytes_per_pe) & 15) == 0 && bytes_per_pe >= FCOLLECT_TICKETS_MIN_BYTES && c->npes >= 8 && n_wg >= per_cu) {
+        n_wg = per_cu;
+        pair = ticket_pair_off(c, SHMD_TICKET_COLL);
+    }
     const dim3 grid(n_wg, c->npes), block(SHMK_WG);
     if (((dst_off | src_off | bytes_per_pe) & 15) == 0) {
         if (c->npes == 8)
-            hipLaunchKernelGGL((shmk_fcollect_vec<2, 8>), grid, block, 0, c->stream[0], dev_view(c), dst_off, src_off, bytes_per_pe);
+            hipLaunchKernelGGL((shmk_fcollect_vec<2, 8>), grid, block, 0, c->stream[0], dev_view(c), dst_off, src_off, bytes_per_pe, pair);
         else
-            hipLaunchKernelGGL((shmk_fcollect_vec<2, 0>), grid, block, 0, c->stream[0], dev_view(c), dst_off, src_off, bytes_per_pe);
+            hipLaunchKernelGGL((shmk_fcollect_vec<2, 0>), grid, block, 0, c->stream[0], dev_view(c), dst_off, src_off, bytes_per_pe, pair);
     } else
         hipLaunchKernelGGL(shmk_fcollect_any, grid, block, 0, c->stream[0], dev_view(c), dst_off, src_off, bytes_per_pe);
     if (int r = launched("fcollect")) return r;

@@ -568,6 +568,30 @@ __device__ __forceinline__ void shm_copy_tiles_ticketed(char *dst, const char *s
     shm_walk_tiles_ticketed<U, NWAVES, PIECES>(ops, dst, src, n, part, counter, first_ticket, own_groups);
 }
 
+// The drawing of tickets by itself, for kernels whose groups walk something other than a copy: group
+// `part` of `groups` starts on number `part`; ahead() is called by every thread at the start of a
+// piece (thread 0 draws the next number, which then travels while the piece is worked on) and next()
+// at its end (the number is handed to the group through one of the two LDS words `slots`; one
+// barrier).  The numbers drawn start at `groups`.
+struct shm_ticket_draw {
+    unsigned long long *counter;
+    unsigned long long *slots;
+    unsigned groups;
+    unsigned it = 0;
+    unsigned long long pending = 0;
+    __device__ __forceinline__ void ahead()
+    {
+        if (threadIdx.x == 0) pending = groups + __hip_atomic_fetch_add(counter, 1ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+    __device__ __forceinline__ size_t next()
+    {
+        if (threadIdx.x == 0) slots[(it + 1) & 1] = pending;
+        __syncthreads();
+        ++it;
+        return static_cast<size_t>(slots[it & 1]);
+    }
+};
+
 // A counter pair (ticket word, then a word that counts the groups that are through) that the last
 // of `groups` groups to finish sets back to zero, so that the next launch -- or the next replay of
 // a recorded one -- finds it as this one did.  Thread 0 of every group calls once, after its walk.
@@ -819,8 +843,8 @@ __device__ __forceinline__ void shmx_quiet_wg()
 #define SHMD_INTERNAL_TICKETS 36864u          // SHMD_TICKET_WORDS uint64 in every partition's tail: ticket counters of the long puts
 #define SHMD_TICKET_WORDS 512u
 #define SHMD_TICKET_TIMED_WORDS 504u          // words 0..503: the timed put, one per repetition (cleared by its launcher)
-#define SHMD_TICKET_TEAM 504u                 // a counter pair (ticket, groups through) for team launches ...
-#define SHMD_TICKET_PE 506u                   // ... for a PE's own launches ...
+#define SHMD_TICKET_TEAM 504u                 // a counter pair (ticket, groups through) for team puts and gets ...
+#define SHMD_TICKET_COLL 506u                 // ... for team collectives ...
 #define SHMD_TICKET_PROBE 508u                // ... and for the stream probes; the pairs reset themselves (shm_tickets_done)
 #define SHMD_QUIET_SHARED_MIN_GROUPS 64u
 #define SHMD_QUIET_SPIN_LIMIT 4096

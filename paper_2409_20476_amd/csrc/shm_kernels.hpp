@@ -733,7 +733,8 @@ __global__ __launch_bounds__(SHMK_STORM_WG) void shmk_amo_storm_wg(shm_dev_ctx c
 // NPES > 0 fixes the number of PEs at compile time, so that the destination loop unrolls and the
 // base-pointer lookups leave the tile loop; NPES == 0 is the general form.
 template <int U, int NPES>
-__global__ __launch_bounds__(SHMK_WG) void shmk_fcollect_vec(shm_dev_ctx c, uint64_t dst_off, uint64_t src_off, size_t bytes_per_pe)
+__global__ __launch_bounds__(SHMK_WG) void shmk_fcollect_vec(shm_dev_ctx c, uint64_t dst_off, uint64_t src_off, size_t bytes_per_pe,
+                                                             uint64_t ticket_pair_off)
 {
     // Group-owned tiles of U rows x 32 KiB, as in shm_copy_tiles: per column U loads, then those
     // U vectors to every destination, then the next column.
@@ -754,6 +755,56 @@ __global__ __launch_bounds__(SHMK_WG) void shmk_fcollect_vec(shm_dev_ctx c, uint
     // share is number p (mod groups per PE), so that the first shares of the PEs -- all there is
     // to do in a short block -- sit on different XCDs instead of all on the first one.
     const unsigned first = (blockIdx.x + gridDim.x - static_cast<unsigned>(p) % gridDim.x) % gridDim.x;
+    if (ticket_pair_off) {
+        // Quarter-tile pieces (16 KiB of the block: two columns per wave in each of the tile's two
+        // rows) drawn by ticket in address order, as the long put draws its pieces; the last group
+        // through sets the counter pair back.
+        __shared__ unsigned long long slots[2];
+        unsigned long long *pair = reinterpret_cast<unsigned long long *>(shm_ptr(c, ticket_pair_off, p));
+        constexpr unsigned PIECES = 4, CPP = 8 / PIECES;
+        static_assert(U == 2, "a tile of two rows");
+        const size_t nwhole = nvec / tilev, npieces = nwhole * PIECES;
+        // to every destination in turn, starting with the right-hand neighbour: both rows of a column, or one vector
+        auto push2 = [&](size_t i, const shm_u32x4 &r0, const shm_u32x4 &r1) {
+            if (NPES) {
+#pragma unroll
+                for (int j = 0; j < NQ; ++j) {
+                    shm_st16(dq[j] + i, r0);
+                    shm_st16(dq[j] + i + rowv, r1);
+                }
+            } else {
+                for (int j = 0; j < npes; ++j) {
+                    int q = p + 1 + j;
+                    if (q >= npes) q -= npes;
+                    shm_u32x4 *d = reinterpret_cast<shm_u32x4 *>(shm_ptr(c, d0, q));
+                    shm_st16(d + i, r0);
+                    shm_st16(d + i + rowv, r1);
+                }
+            }
+        };
+        auto push = [&](size_t i, const shm_u32x4 &r) {
+            for (int j = 0; j < npes; ++j) {
+                int q = p + 1 + j;
+                if (q >= npes) q -= npes;
+                shm_st16(reinterpret_cast<shm_u32x4 *>(shm_ptr(c, d0, q)) + i, r);
+            }
+        };
+        shm_ticket_draw tk{pair, slots, gridDim.x};
+        for (size_t t = blockIdx.x; t < npieces; t = tk.next()) {
+            tk.ahead();
+            const size_t base = (t / PIECES) * tilev + (t % PIECES) * (CPP * 64) + static_cast<size_t>(wave * 8) * 64 + lane;
+#pragma unroll
+            for (unsigned cc = 0; cc < CPP; ++cc) {
+                const size_t i = base + cc * 64;
+                const shm_u32x4 r0 = shm_ld16(s + i), r1 = shm_ld16(s + i + rowv);
+                push2(i, r0, r1);
+            }
+        }
+        if (blockIdx.x == 0)                      // what is left after the whole tiles
+            for (size_t i = nwhole * tilev + threadIdx.x; i < nvec; i += SHMK_WG) push(i, shm_ld16(s + i));
+        if (threadIdx.x == 0) shm_tickets_done(pair, gridDim.x);
+        return;
+    }
     if (ntiles < gridDim.x) {
         // Short block, fewer tiles than groups: deal rows of one vector per thread instead, so that
         // as many groups as there are rows take part.
@@ -922,6 +973,18 @@ __global__ __launch_bounds__(SHMK_WG) void shmk_reduce_sum_f32_vec(shm_dev_ctx c
             for (int u = 0; u < U; ++u) v[u] = load(sp + i + u * rowv);
 #pragma unroll
             for (int u = 0; u < U; ++u) r[u].x += v[u].x, r[u].y += v[u].y, r[u].z += v[u].z, r[u].w += v[u].w;
+        }
+        if (SPLIT) {
+            // destination by destination, both rows each (own copy first, then the others in ring
+            // order): 75.4 % of the HBM roofline at 8 PEs x 64 MiB against 71.8 % row by row
+            for (int t = 0; t < npes; ++t) {
+                int w = q + t;
+                if (w >= npes) w -= npes;
+                shm_f32x4 *dw = reinterpret_cast<shm_f32x4 *>(shm_ptr(c, dof, w));
+#pragma unroll
+                for (int u = 0; u < U; ++u) __builtin_nontemporal_store(r[u], dw + i + u * rowv);
+            }
+            return;
         }
 #pragma unroll
         for (int u = 0; u < U; ++u) emit(i + u * rowv, r[u]);

@@ -103,6 +103,26 @@ def test_fcollect(path, npes, n, n_wg, soff, doff):
         assert_heaps_equal(g, o, upto=12 * MiB)
 
 
+@pytest.mark.parametrize("npes,n,n_wg", [(8, 8 * MiB, 1024), (8, 8 * MiB + 65536 + 48, 32), (8, 9 * MiB - 16, 31), (16, 8 * MiB + 16, 16)])
+def test_fcollect_of_long_blocks_by_ticket(npes, n, n_wg):
+    """From 8 MiB per PE, 8 PEs or more and as many groups asked as the launcher runs (256 / npes per PE)
+    the groups of a PE draw 16 KiB pieces of its block by ticket: whole tiles only, a rest of less than
+    a tile, one group too few (fixed tiles then), 16 PEs; twice in a row, the second launch with other
+    source bytes, so that it depends on the counters having been set back."""
+    g, o = make_pair(npes, (npes + 2) * 9 * MiB + MiB)
+    rng = np.random.default_rng(23)
+    with g:
+        fill_random(g, o, 23, upto=(npes + 1) * 9 * MiB + 65536)
+        src, dst = 64, 9 * MiB + 128
+        for rep in range(2):
+            g.launch_fcollect(dst, src, n, n_wg, S.SHM_PATH_LDST)
+            g.barrier_all()
+            o.fcollect(dst, src, n)
+            assert_heaps_equal(g, o, upto=(npes + 1) * 9 * MiB + 65536, what=f"launch {rep}")
+            for p in range(npes):
+                write_both(g, o, p, src + 4096 * p, rng.integers(0, 256, 100000, dtype=np.uint8))
+
+
 @pytest.mark.parametrize("algo", [S.SHM_REDUCE_DUPLICATE, S.SHM_REDUCE_SPLIT])
 @pytest.mark.parametrize("npes,nelems,n_wg,soff,doff", [(8, 4096 * 5 + 3, 8, 0, 0), (3, 1001, 2, 4, 8), (8, 65536 * 9 + 4, 64, 0, 0),
                                                        (1, 777, 3, 0, 0), (5, 2, 1, 0, 0), (4, 131072 * 3 + 1, 16, 16, 32)])
