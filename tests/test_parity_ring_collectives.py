@@ -208,23 +208,23 @@ def test_config2_full_size_team_put():
         g.barrier_all()
         for p in range(npes):
             assert np.array_equal(g.read((p + 1) % npes, dst, n), data[p]), f"put of PE {p}"
-        # the 64 MiB and 128 MiB points of the same curve (swept as a front by 512 groups per PE), the
+        # the 64 MiB and 128 MiB points of the same curve (half-tile pieces drawn by ticket by 128 groups per PE), the
         # second with a rest after the whole steps and a byte tail; put and get, other shifts
         for m, shift in ((64 * MiB, 2), (128 * MiB - 4096 * 3 + 16 + 7, 5)):
             g.launch_wg_put_all(shift, dst, src, m, 1024, S.SHM_PATH_LDST)
             g.barrier_all()
             for p in range(npes):
                 got = g.read((p + shift) % npes, dst, n)
-                assert np.array_equal(got[:m], data[p][:m]), f"front put of PE {p}, {m} bytes"
-                assert np.array_equal(got[m:], data[(p + shift - 1) % npes][m:]), f"bytes behind the front put of PE {p}"
+                assert np.array_equal(got[:m], data[p][:m]), f"long put of PE {p}, {m} bytes"
+                assert np.array_equal(got[m:], data[(p + shift - 1) % npes][m:]), f"bytes behind the long put of PE {p}"
             g.launch_wg_put_all(1, dst, src, n, 1024, S.SHM_PATH_LDST)            # every PE holds its left neighbour's data again
             g.barrier_all()
             g.launch_wg_get_all(shift, dst, src, m, 1024, S.SHM_PATH_LDST)
             g.barrier_all()
             for p in range(npes):
                 got = g.read(p, dst, n)
-                assert np.array_equal(got[:m], data[(p + shift) % npes][:m]), f"front get of PE {p}, {m} bytes"
-                assert np.array_equal(got[m:], data[(p - 1) % npes][m:]), f"bytes behind the front get of PE {p}"
+                assert np.array_equal(got[:m], data[(p + shift) % npes][:m]), f"long get of PE {p}, {m} bytes"
+                assert np.array_equal(got[m:], data[(p - 1) % npes][m:]), f"bytes behind the long get of PE {p}"
             g.launch_wg_put_all(1, dst, src, n, 1024, S.SHM_PATH_LDST)
             g.barrier_all()
         # per-PE streams, copy-engine path, smaller message with a ragged tail
