@@ -1369,9 +1369,16 @@ int ring_pipeline(shm_ctx *c, uint64_t src_off, uint64_t slot_off, uint64_t sig_
     if (int r = drain_all_engines(c)) return r;
     int per_cu = 0;
     const bool lanes = n_sig > 1 || (n_wg_prod == 1 && n_wg_cons == 1);
-    const auto kernel = lanes ? shmk_ring<1> : shmk_ring<0>;
+    // producer shares of 32-128 KiB per chunk take the form that keeps two 64 KiB blocks in registers
+    const size_t pper = (nvec + n_wg_prod - 1) / n_wg_prod;
+    const bool deep = !lanes && pper > static_cast<size_t>(SHMK_WG) * SHMK_RING_VPT && pper <= 2u * SHMK_WG * SHMK_RING_DEEP_VPT;
+    auto kernel = lanes ? shmk_ring<1, 0> : deep ? shmk_ring<0, 1> : shmk_ring<0, 0>;
     HIP_TRY(hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kernel, SHMK_WG, 0));
     const long long groups = static_cast<long long>(c->npes) * (n_wg_prod + n_wg_cons);
+    if (deep && groups > static_cast<long long>(per_cu) * c->num_cu) {       // too many groups for its registers: the plain form
+        kernel = shmk_ring<0, 0>;
+        HIP_TRY(hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kernel, SHMK_WG, 0));
+    }
     if (groups > static_cast<long long>(per_cu) * c->num_cu)
         return fail(SHM_EINVAL, "%lld groups cannot all be resident (%d CUs x %d); consumers would wait on groups that never start",
                     groups, c->num_cu, per_cu);

@@ -432,8 +432,18 @@ __global__ __launch_bounds__(SHMK_WG) void shmk_wave_exchange(shm_dev_ctx c, uin
 
 // LANES: one signal word per producer/consumer group pair (compile-time, so that each form carries
 // only its own code and registers: both fit 128 VGPRs, four groups per compute unit).
-template <int LANES>
-__global__ __launch_bounds__(SHMK_WG, 4) void shmk_ring(shm_dev_ctx c, uint64_t src_off, uint64_t slot_off, uint64_t sig_off,
+// DEEP: for producer shares of more than 32 KiB and up to 128 KiB per chunk (fewer than 32 producer
+// groups per PE at 1 MiB chunks), which do not fit the two-half form's registers: the whole group
+// walks its share in blocks of 64 KiB -- 16 vectors per thread -- and keeps TWO blocks in registers,
+// loading block s+1 while the stores of block s are on their way, 128 KiB in flight per group; the
+// chunk is signalled after the acknowledgements of its last block.  That needs 137 registers, so
+// this form is a kernel of its own (three groups per compute unit instead of four).  Measured, 8 PEs x
+// 64 chunks of 1 MiB: 8 producer groups per PE 0.60 -> 0.55 ms, 16 groups 0.415 -> 0.366 ms (32 groups,
+// two-half form: 0.26 ms): a step still lasts as long as its slower half, the loads or the stores'
+// acknowledgements, and few groups mean few steps in flight.
+#define SHMK_RING_DEEP_VPT 16
+template <int LANES, int DEEP = 0>
+__global__ __launch_bounds__(SHMK_WG, DEEP ? 2 : 4) void shmk_ring(shm_dev_ctx c, uint64_t src_off, uint64_t slot_off, uint64_t sig_off,
                                                         uint64_t acc_off, size_t chunk_bytes, int n_chunks, int n_prod, int n_cons,
                                                         uint64_t *arrive_pe0, uint64_t arrive_pe_stride)
 {
@@ -448,6 +458,54 @@ __global__ __launch_bounds__(SHMK_WG, 4) void shmk_ring(shm_dev_ctx c, uint64_t 
         int pe = me + 1;
         if (pe >= npes) pe = 0;
         const size_t pper = lanes ? per : (nvec + n_prod - 1) / n_prod;     // this producer's share of a chunk, in vectors
+        if constexpr (DEEP != 0) {
+            constexpr int J = SHMK_RING_DEEP_VPT;
+            constexpr uint32_t BLOCK = SHMK_WG * J;                        // vectors per block
+            const size_t lo = min(nvec, part * pper), hi = min(nvec, lo + pper);
+            const bool any = hi > lo;
+            const uint32_t last = any ? static_cast<uint32_t>(hi - 1 - lo) : 0;
+            const int nsub = static_cast<int>((pper + BLOCK - 1) / BLOCK);  // blocks per chunk; the host allows up to 2
+            const shm_u32x4 *s = reinterpret_cast<const shm_u32x4 *>(shm_ptr(c, src_off, me)) + lo;
+            shm_u32x4 *d = reinterpret_cast<shm_u32x4 *>(shm_ptr(c, slot_off, pe)) + lo;
+            uint64_t *sig = reinterpret_cast<uint64_t *>(shm_ptr(c, sig_off, pe));
+            uint64_t *arrive = arrive_pe0 + static_cast<uint64_t>(me) * arrive_pe_stride;
+            // vector of the share that thread t touches in block `sub`, access j; past the share: its last vector again
+            auto v = [&](int sub, int j) { return min(last, static_cast<uint32_t>(sub) * BLOCK + threadIdx.x + static_cast<uint32_t>(j) * SHMK_WG); };
+            const int steps = n_chunks * nsub;
+            shm_u32x4 a[J], b[J];
+            auto load = [&](shm_u32x4 (&r)[J], int step) {
+                const size_t at = static_cast<size_t>(step / nsub) * nvec;
+                const int sub = step % nsub;
+#pragma unroll
+                for (int j = 0; j < J; ++j) r[j] = shm_ld16(s + at + v(sub, j));
+            };
+            auto store_and_signal = [&](shm_u32x4 (&r)[J], int step) {
+                const int k = step / nsub, sub = step % nsub;
+                if (any) {
+#pragma unroll
+                    for (int j = 0; j < J; ++j) shm_st16<SHM_ST_THROUGH>(d + static_cast<size_t>(k) * nvec + v(sub, j), r[j]);
+                }
+                asm volatile("s_waitcnt vmcnt(0)" ::: "memory");           // this wave's stores are performed at agent scope
+                __syncthreads();
+                if (sub == nsub - 1 && threadIdx.x == 0) {
+                    const uint64_t old = __hip_atomic_fetch_add(arrive + k, 1ull, SHMD_ARRIVE_ORDER, __HIP_MEMORY_SCOPE_AGENT);
+                    if (old == static_cast<uint64_t>(n_prod) - 1) {
+                        __hip_atomic_store(arrive + k, 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                        __hip_atomic_fetch_add(sig, 1ull, SHMD_SIGNAL_ORDER, __HIP_MEMORY_SCOPE_AGENT);
+                    }
+                }
+            };
+            if (any) load(a, 0);
+            for (int step = 0; step < steps; step += 2) {
+                if (any && step + 1 < steps) load(b, step + 1);
+                store_and_signal(a, step);
+                if (step + 1 < steps) {
+                    if (any && step + 2 < steps) load(a, step + 2);
+                    store_and_signal(b, step + 1);
+                }
+            }
+            return;
+        } else
         if (pper <= static_cast<size_t>(SHMK_WG) * SHMK_RING_VPT) {
             // The share fits the group's registers.  A put_signal per chunk is a chain of two
             // memory latencies (loads, then the stores' acknowledgements), so the group works as two
@@ -501,10 +559,8 @@ __global__ __launch_bounds__(SHMK_WG, 4) void shmk_ring(shm_dev_ctx c, uint64_t 
             }
             return;
         }
-        // Larger shares: one put_signal per chunk by all producer groups together.  (Walking such a
-        // share block by block through the same two-half pipeline was measured and is slower: with
-        // 8 or 16 producer groups per PE -- 64 or 128 on the whole chip -- the rate is bound by the
-        // bytes those few groups keep in flight, 32 KiB each either way, not by the chain of latencies.)
+        // Larger shares (more than 128 KiB per chunk, or a grid too large for the DEEP form's
+        // registers): one put_signal per chunk by all producer groups together.
         uint64_t *arrive = arrive_pe0 + static_cast<uint64_t>(me) * arrive_pe_stride;
         for (int k = 0; k < n_chunks; ++k)
             shmx_putmem_signal_parts(c, me, slot_off + k * chunk_bytes, src_off + k * chunk_bytes, chunk_bytes, sig_off, 1,

@@ -64,6 +64,15 @@ def test_config3_full_size_one_counter_pipelined():
 
 
 @pytest.mark.timeout(600)
+@pytest.mark.parametrize("n_prod,n_cons", [(16, 32), (9, 32), (11, 40)])
+def test_ring_producer_shares_of_32_to_128_kib_keep_two_blocks_in_registers(n_prod, n_cons):
+    """1 MiB chunks by 16, 9 and 11 producer groups per PE: shares of 64, 114 and 93 KiB per chunk (one
+    block, and two blocks with a ragged second one), the last group's share shorter than the others';
+    three rounds through the same slots."""
+    _ring_case(8, 24, 524288, n_prod, n_cons, 128 * MiB, reps=3)
+
+
+@pytest.mark.timeout(600)
 def test_config3_full_size_lanes():
     """The same with one signal counter per producer/consumer group pair."""
     _ring_case(8, 64, 524288, 32, 32, 256 * MiB, reps=2, n_sig=32)
