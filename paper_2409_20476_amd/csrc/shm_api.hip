@@ -43,7 +43,8 @@ constexpr size_t TILE_BYTES = 64u << 10, TILES_PER_GROUP = 4;
 constexpr long long TILES_MIN_GRID_GROUPS = 64;               // groups asked for, all PEs of the grid together
 constexpr long long TILES_MIN_LAUNCHED_GROUPS = 64;           // groups launched, all PEs of the grid together
 constexpr unsigned TILES_LDS_BYTES = 54000;                   // unused LDS that caps a CU at 3 resident groups
-constexpr size_t TIMED_TICKET_GROUPS = 96;                    // groups per PE of a timed put whose tiles are dealt by ticket
+constexpr size_t TIMED_TICKET_GROUPS = 96;
+constexpr size_t TIMED_TILES_MIN_BYTES = size_t(16) << 20;                    // groups per PE of a timed put whose tiles are dealt by ticket
 constexpr uint64_t OFFLOAD_COUNTERS = 32768;                  // offset of the ring's three index words in PE 0's internal tail
 static_assert(ARRIVE_SLOTS * 8 <= OFFLOAD_COUNTERS && OFFLOAD_COUNTERS + 24 <= SHMD_INTERNAL_SYNC_COUNT &&
                   SHMD_INTERNAL_SYNC_EPOCH + 8 <= SHMD_INTERNAL_QUIET && SHMD_INTERNAL_QUIET + 8 * 128 <= SHMD_INTERNAL_TICKETS &&
@@ -934,8 +935,9 @@ int shm_launch_wg_put_timed(shm_ctx *c, int me, int pe, uint64_t dst_off, uint64
     if (!dev_ticks) return fail(SHM_EINVAL, "null tick buffer");
     if (c->no_device) return no_device("shm_launch_wg_put_timed");
     if (int r = begin_pe_launch(c, me)) return r;
-    const bool tiles = use_tiles(dst_off, src_off, n, n_wg, 1);
-    // A put that its own quiet follows keeps its groups in the kernel anyway; from 32 MiB they draw
+    // pieces by ticket pay from 16 MiB here (put + quiet, 8 PEs: 16 MiB 50 -> 54 % of the roofline, 24 MiB 50 -> 62 %; 8 MiB 41 -> 35 %)
+    const bool tiles = ((dst_off | src_off) & 15) == 0 && n >= TIMED_TILES_MIN_BYTES && n_wg >= TILES_MIN_GRID_GROUPS;
+    // A put that its own quiet follows keeps its groups in the kernel anyway; from 16 MiB they draw
     // half-tile pieces by ticket (shm_copy_tiles_ticketed), one counter per repetition in the PE's own tail,
     // cleared here -- this entry point is not for graph capture.  More repetitions than there are
     // counters take fixed shares, eight tiles or more per group.

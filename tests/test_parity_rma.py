@@ -172,8 +172,8 @@ def test_more_groups_than_vectors_and_the_minimum_share_of_put_then_quiet(n_wg):
 
 def test_timed_put_of_long_messages_moves_the_same_bytes_on_both_long_message_paths():
     """9 MiB by 64 groups and 40 MiB by 48 groups stay on the virtual blocks (short message; fewer than 64
-    groups); 65 MiB by 512 groups and 33 MiB by 64 groups take 64 KiB tiles, which the groups draw by
-    ticket -- up to 512 repetitions, one ticket counter each; beyond, every group owns fixed tiles.  The
+    groups); from 16 MiB and 64 groups on -- 65 MiB by 512 groups, 33 MiB by 64, 16 MiB and a bit by 100 -- the groups
+    draw half-tile pieces by ticket, up to 504 repetitions, one ticket counter each; beyond, every group owns fixed tiles.  The
     launches follow one another at once: each finds the counters its predecessor used cleared."""
     import torch
     g, o = make_pair(2, 160 * MiB)
@@ -181,7 +181,7 @@ def test_timed_put_of_long_messages_moves_the_same_bytes_on_both_long_message_pa
         fill_random(g, o, 7, upto=144 * MiB)
         for n, n_wg, reps in [(9 * MiB + 16 * 3 + 5, 64, 3), (65 * MiB + 16 * 3 + 5, 512, 3), (40 * MiB + 16 * 7 + 1, 48, 3),
                               (33 * MiB + 65536 + 16 + 3, 64, 3),      # ragged last tile and a byte tail
-                              (32 * MiB + 48, 1024, 1), (33 * MiB + 65536 + 16 + 3, 200, 513)]:
+                              (32 * MiB + 48, 1024, 1), (33 * MiB + 65536 + 16 + 3, 200, 513), (16 * MiB + 32768 + 16 + 7, 100, 2)]:
             ticks = torch.zeros(2, dtype=torch.int64, device="cuda")
             ticks[0] = -1
             g.launch_wg_put_timed(0, 1, 70 * MiB + 16, 32, n, n_wg, reps, ticks)
