@@ -235,6 +235,37 @@ def test_long_messages_team_forms_on_all_long_message_paths(n_wg):
         assert_heaps_equal(g, o, upto=76 * MiB, what="team forms")
 
 
+def test_team_puts_by_ticket_random_sizes_and_places():
+    """Ten seeded random team puts and gets of 32-36 MiB at random 16-byte-aligned offsets (and two that
+    are not: those take the general dealing), random shifts and group counts from 128 up, 5 PEs, one after
+    the other without anything in between but the barrier the comparison needs."""
+    npes = 5
+    g, o = make_pair(npes, 80 * MiB)
+    rng = np.random.default_rng(20476)
+    with g:
+        fill_random(g, o, 10, upto=78 * MiB)
+        for rep in range(10):
+            n = int(rng.integers(32 * MiB, 36 * MiB))
+            if rep % 3 == 0:
+                n &= ~15
+            align = 1 if rep in (4, 7) else 16
+            a = int(rng.integers(0, (38 * MiB - n) // align)) * align
+            b = 39 * MiB + int(rng.integers(0, (38 * MiB - n) // align)) * align
+            src, dst = (a, b) if rep % 2 else (b, a)
+            shift, n_wg = int(rng.integers(1, npes)), int(rng.integers(128, 1025))
+            before = [h.copy() for h in o.heap]
+            if rng.integers(2):
+                g.launch_wg_put_all(shift, dst, src, n, n_wg)
+                for p in range(npes):
+                    o.heap[(p + shift) % npes][dst:dst + n] = before[p][src:src + n]
+            else:
+                g.launch_wg_get_all(shift, dst, src, n, n_wg)
+                for p in range(npes):
+                    o.heap[p][dst:dst + n] = before[(p + shift) % npes][src:src + n]
+            g.barrier_all()
+            assert_heaps_equal(g, o, upto=78 * MiB, what=f"launch {rep}: {n} bytes {src} -> {dst}, shift {shift}, {n_wg} groups")
+
+
 @pytest.mark.parametrize("npes", [4, 7])
 def test_team_puts_by_ticket_at_the_edges_of_the_piece_count(npes):
     """Half-tile pieces by ticket (team grids of four PEs or more, 32 MiB or more, 128 groups or more
