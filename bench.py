@@ -12,7 +12,7 @@ kernel against the HBM copy roofline, timed with HIP events on the stream it run
 `configs`, a short summary per configuration with the oracle's time beside each GPU figure.  The
 full measurements (the put sweep over message sizes, work-group counts and transfer paths, the
 ping/flag latency, the pipelined ring, the atomic storm, the collectives, the sweeps of the paper's
-other experiments) go to a JSON file (`--extras-out`, default gpurun_out/bench_extras.json) and, in
+other experiments) go to a JSON file (`--extras-out`; see its default) and, in
 short form, to stderr.
 """
 from __future__ import annotations
