@@ -410,8 +410,10 @@ unsigned tile_groups(size_t n, int n_wg, size_t tiles_per_group = TILES_PER_GROU
 // at 8 x 256 MiB and 74.8 / 79.9 / 81.7 at 64 MiB -- their rate follows the distance between destination
 // and source modulo 128 MiB --, group-owned tiles 77-79 %.  The number of groups is the window: 128 x
 // 32 KiB = 4 MiB per PE is what this memory system likes (112 or 144 groups: 81.6 % at 8 x 256 MiB, 96 or
-// 192: 81.5, 256: 82.0; the same at 4 and 6 PEs).  Below 32 MiB per PE the virtual blocks are faster (8-16
-// MiB per PE x 8 PEs stay in the memory-side cache).
+// 192: 81.5, 256: 82.0; the same at 4 and 6 PEs).  Below 32 MiB per PE the virtual blocks stay: on buffers that
+// nothing has touched for a while the two forms are level (8 PEs x 8 / 16 / 24 MiB: 25.4 / 45.6 / 66.6 us against 24.8 /
+// 44.2 / 63.1 us by ticket), on buffers that sit in the 256 MiB memory-side cache the virtual blocks, which store such
+// sizes write-through, are a quarter faster (18.8 / 33.8 / 48.4 us against 23.6 / 43.5 / 62.4 us).
 constexpr size_t TICKETS_MIN_BYTES = size_t(32) << 20, FCOLLECT_TICKETS_MIN_BYTES = size_t(8) << 20;
 constexpr int TICKET_GROUPS = 128;
 bool use_tickets(uint64_t dst_off, uint64_t src_off, size_t n, int n_wg, int grid_pes)
