@@ -414,7 +414,7 @@ unsigned tile_groups(size_t n, int n_wg, size_t tiles_per_group = TILES_PER_GROU
 // nothing has touched for a while the two forms are level (8 PEs x 8 / 16 / 24 MiB: 25.4 / 45.6 / 66.6 us against 24.8 /
 // 44.2 / 63.1 us by ticket), on buffers that sit in the 256 MiB memory-side cache the virtual blocks, which store such
 // sizes write-through, are a quarter faster (18.8 / 33.8 / 48.4 us against 23.6 / 43.5 / 62.4 us).
-constexpr size_t TICKETS_MIN_BYTES = size_t(32) << 20, FCOLLECT_TICKETS_MIN_BYTES = size_t(8) << 20;
+constexpr size_t TICKETS_MIN_BYTES = size_t(32) << 20, FCOLLECT_TICKETS_MIN_BYTES = size_t(8) << 20, BROADCAST_TICKETS_MIN_BYTES = size_t(32) << 20;
 constexpr int TICKET_GROUPS = 128;
 bool use_tickets(uint64_t dst_off, uint64_t src_off, size_t n, int n_wg, int grid_pes)
 {
@@ -1687,7 +1687,15 @@ int shm_launch_broadcast(shm_ctx *c, uint64_t dst_off, uint64_t src_off, size_t 
         }
         return SHM_OK;
     }
-    hipLaunchKernelGGL(shmk_broadcast, dim3(n_wg), dim3(SHMK_WG), 0, c->stream[0], dev_view(c), dst_off, src_off, n, root);
+    // A long block asked of a group per compute unit or more is pushed by exactly that many groups, which draw 16 KiB
+    // pieces of it by ticket like fcollect's (measured, 8 PEs, root's block of 64 / 256 MiB, % of the HBM roofline:
+    // 60.5 -> 78.6 and 62.5 -> 84.3; 16 MiB level at 28-29 us; 128 / 192 / 384 / 512 groups: 63 / 76 / 78 / 77 % at 256 MiB).
+    uint64_t pair = 0;
+    if (((dst_off | src_off) & 15) == 0 && n >= BROADCAST_TICKETS_MIN_BYTES && n_wg >= c->num_cu) {
+        n_wg = c->num_cu;
+        pair = ticket_pair_off(c, SHMD_TICKET_COLL);
+    }
+    hipLaunchKernelGGL(shmk_broadcast, dim3(n_wg), dim3(SHMK_WG), 0, c->stream[0], dev_view(c), dst_off, src_off, n, root, pair);
     if (int r = launched("broadcast")) return r;
     if (c->team_sync)
         if (int r = team_fork(c)) return r;

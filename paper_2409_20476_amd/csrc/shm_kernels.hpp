@@ -782,6 +782,68 @@ __global__ __launch_bounds__(SHMK_STORM_WG) void shmk_amo_storm_wg(shm_dev_ctx c
         [&](auto fetch) { walk(fetch, std::true_type{}); });
 }
 
+// The push of a long 16-byte-aligned block by ticket (fcollect: every PE's block; broadcast: the root's): the
+// gridDim.x groups draw quarter-tile pieces (16 KiB: two columns per wave in each of the tile's two 32 KiB rows) of
+// the block in address order, as the long put draws its pieces, and store every column to the PEs in turn, both rows
+// per destination, starting with the right-hand neighbour of `p`; group 0 moves what is left after the whole tiles,
+// and the last group through sets the counter pair back.  s = the block, d0 = its offset in every destination,
+// nvec = its length in vectors.  NPES > 0 fixes the number of PEs at compile time.
+template <int NPES>
+__device__ __forceinline__ void shmk_push_pieces_ticketed(const shm_dev_ctx &c, const shm_u32x4 *s, uint64_t d0, int p, size_t nvec,
+                                                          unsigned long long *pair)
+{
+    __shared__ unsigned long long slots[2];
+    const int npes = NPES ? NPES : c.npes;
+    constexpr int NQ = NPES ? NPES : 1;
+    shm_u32x4 *dq[NQ];
+    if (NPES) {
+#pragma unroll
+        for (int j = 0; j < NQ; ++j) dq[j] = reinterpret_cast<shm_u32x4 *>(shm_ptr(c, d0, (p + 1 + j) % NQ));
+    }
+    constexpr size_t rowv = 2048, tilev = 2 * rowv;
+    constexpr unsigned PIECES = 4, CPP = 8 / PIECES;
+    const unsigned wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const size_t nwhole = nvec / tilev, npieces = nwhole * PIECES;
+    auto push2 = [&](size_t i, const shm_u32x4 &r0, const shm_u32x4 &r1) {
+        if (NPES) {
+#pragma unroll
+            for (int j = 0; j < NQ; ++j) {
+                shm_st16(dq[j] + i, r0);
+                shm_st16(dq[j] + i + rowv, r1);
+            }
+        } else {
+            for (int j = 0; j < npes; ++j) {
+                int q = p + 1 + j;
+                if (q >= npes) q -= npes;
+                shm_u32x4 *d = reinterpret_cast<shm_u32x4 *>(shm_ptr(c, d0, q));
+                shm_st16(d + i, r0);
+                shm_st16(d + i + rowv, r1);
+            }
+        }
+    };
+    auto push = [&](size_t i, const shm_u32x4 &r) {
+        for (int j = 0; j < npes; ++j) {
+            int q = p + 1 + j;
+            if (q >= npes) q -= npes;
+            shm_st16(reinterpret_cast<shm_u32x4 *>(shm_ptr(c, d0, q)) + i, r);
+        }
+    };
+    shm_ticket_draw tk{pair, slots, gridDim.x};
+    for (size_t t = blockIdx.x; t < npieces; t = tk.next()) {
+        tk.ahead();
+        const size_t base = (t / PIECES) * tilev + (t % PIECES) * (CPP * 64) + static_cast<size_t>(wave * 8) * 64 + lane;
+#pragma unroll
+        for (unsigned cc = 0; cc < CPP; ++cc) {
+            const size_t i = base + cc * 64;
+            const shm_u32x4 r0 = shm_ld16(s + i), r1 = shm_ld16(s + i + rowv);
+            push2(i, r0, r1);
+        }
+    }
+    if (blockIdx.x == 0)                      // what is left after the whole tiles
+        for (size_t i = nwhole * tilev + threadIdx.x; i < nvec; i += SHMK_WG) push(i, shm_ld16(s + i));
+    if (threadIdx.x == 0) shm_tickets_done(pair, gridDim.x);
+}
+
 // ---- configuration 5a: fcollect, push --------------------------------------------------------
 // PE p = blockIdx.y reads its block once and stores every vector to all PEs (inner loop over
 // destinations, outer loop over addresses), starting with its right-hand neighbour.  The block is
@@ -812,53 +874,7 @@ __global__ __launch_bounds__(SHMK_WG) void shmk_fcollect_vec(shm_dev_ctx c, uint
     // to do in a short block -- sit on different XCDs instead of all on the first one.
     const unsigned first = (blockIdx.x + gridDim.x - static_cast<unsigned>(p) % gridDim.x) % gridDim.x;
     if (ticket_pair_off) {
-        // Quarter-tile pieces (16 KiB of the block: two columns per wave in each of the tile's two
-        // rows) drawn by ticket in address order, as the long put draws its pieces; the last group
-        // through sets the counter pair back.
-        __shared__ unsigned long long slots[2];
-        unsigned long long *pair = reinterpret_cast<unsigned long long *>(shm_ptr(c, ticket_pair_off, p));
-        constexpr unsigned PIECES = 4, CPP = 8 / PIECES;
-        static_assert(U == 2, "a tile of two rows");
-        const size_t nwhole = nvec / tilev, npieces = nwhole * PIECES;
-        // to every destination in turn, starting with the right-hand neighbour: both rows of a column, or one vector
-        auto push2 = [&](size_t i, const shm_u32x4 &r0, const shm_u32x4 &r1) {
-            if (NPES) {
-#pragma unroll
-                for (int j = 0; j < NQ; ++j) {
-                    shm_st16(dq[j] + i, r0);
-                    shm_st16(dq[j] + i + rowv, r1);
-                }
-            } else {
-                for (int j = 0; j < npes; ++j) {
-                    int q = p + 1 + j;
-                    if (q >= npes) q -= npes;
-                    shm_u32x4 *d = reinterpret_cast<shm_u32x4 *>(shm_ptr(c, d0, q));
-                    shm_st16(d + i, r0);
-                    shm_st16(d + i + rowv, r1);
-                }
-            }
-        };
-        auto push = [&](size_t i, const shm_u32x4 &r) {
-            for (int j = 0; j < npes; ++j) {
-                int q = p + 1 + j;
-                if (q >= npes) q -= npes;
-                shm_st16(reinterpret_cast<shm_u32x4 *>(shm_ptr(c, d0, q)) + i, r);
-            }
-        };
-        shm_ticket_draw tk{pair, slots, gridDim.x};
-        for (size_t t = blockIdx.x; t < npieces; t = tk.next()) {
-            tk.ahead();
-            const size_t base = (t / PIECES) * tilev + (t % PIECES) * (CPP * 64) + static_cast<size_t>(wave * 8) * 64 + lane;
-#pragma unroll
-            for (unsigned cc = 0; cc < CPP; ++cc) {
-                const size_t i = base + cc * 64;
-                const shm_u32x4 r0 = shm_ld16(s + i), r1 = shm_ld16(s + i + rowv);
-                push2(i, r0, r1);
-            }
-        }
-        if (blockIdx.x == 0)                      // what is left after the whole tiles
-            for (size_t i = nwhole * tilev + threadIdx.x; i < nvec; i += SHMK_WG) push(i, shm_ld16(s + i));
-        if (threadIdx.x == 0) shm_tickets_done(pair, gridDim.x);
+        shmk_push_pieces_ticketed<NPES>(c, s, d0, p, nvec, reinterpret_cast<unsigned long long *>(shm_ptr(c, ticket_pair_off, p)));
         return;
     }
     if (ntiles < gridDim.x) {
@@ -1124,9 +1140,22 @@ __global__ __launch_bounds__(SHMK_WG) void shmk_sync_all(shm_dev_ctx c, int roun
     }
 }
 
-__global__ __launch_bounds__(SHMK_WG) void shmk_broadcast(shm_dev_ctx c, uint64_t dst_off, uint64_t src_off, size_t n, int root)
+// ticket_pair_off != 0 (long blocks; offsets 16-byte aligned): the groups draw pieces by ticket from the root's pair.
+__global__ __launch_bounds__(SHMK_WG) void shmk_broadcast(shm_dev_ctx c, uint64_t dst_off, uint64_t src_off, size_t n, int root,
+                                                          uint64_t ticket_pair_off)
 {
-    shmx_broadcast_push(c, root, dst_off, src_off, n, blockIdx.x, gridDim.x);
+    if (ticket_pair_off == 0) {
+        shmx_broadcast_push(c, root, dst_off, src_off, n, blockIdx.x, gridDim.x);
+        return;
+    }
+    const char *src = shm_ptr(c, src_off, root);
+    shmk_push_pieces_ticketed<0>(c, reinterpret_cast<const shm_u32x4 *>(src), dst_off, root, n >> 4,
+                                 reinterpret_cast<unsigned long long *>(shm_ptr(c, ticket_pair_off, root)));
+    if (blockIdx.x == 0)
+        for (size_t b = (n & ~static_cast<size_t>(15)) + threadIdx.x; b < n; b += SHMK_WG) {       // the last n mod 16 bytes
+            const char v = src[b];
+            for (int q = 0; q < c.npes; ++q) shm_ptr(c, dst_off, q)[b] = v;
+        }
 }
 
 // ---- the reduction matrix (paper section "Collective Operations", reduction paragraph) ------------

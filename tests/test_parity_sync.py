@@ -4,7 +4,7 @@ import pytest
 import torch
 
 from paper_2409_20476_amd import shm as S
-from parity_util import assert_heaps_equal, fill_random, make_pair
+from parity_util import assert_heaps_equal, fill_random, make_pair, write_both
 
 pytestmark = pytest.mark.gpu
 
@@ -51,6 +51,24 @@ def test_broadcast(path, npes, n, root, n_wg, soff, doff):
         g.barrier_all()
         o.broadcast(dst, src, n, root)
         assert_heaps_equal(g, o, upto=12 * MiB)
+
+
+@pytest.mark.parametrize("npes,n,root,n_wg", [(8, 32 * MiB, 2, 1024), (3, 32 * MiB + 65536 + 16 * 3 + 5, 0, 256), (5, 33 * MiB - 16, 4, 255)])
+def test_long_broadcast_by_ticket(npes, n, root, n_wg):
+    """From 32 MiB, 16-byte-aligned offsets and a group per compute unit asked (256), that many groups draw 16 KiB
+    pieces of the root's block by ticket: whole tiles only; a rest after the whole tiles and a byte tail; one group too
+    few (the grid-strided push then).  Twice in a row with other source bytes: the counters were set back."""
+    g, o = make_pair(npes, 72 * MiB)
+    rng = np.random.default_rng(44)
+    with g:
+        fill_random(g, o, 44, upto=70 * MiB)
+        src, dst = 48, 35 * MiB + 16
+        for rep in range(2):
+            g.launch_broadcast(dst, src, n, root, n_wg, S.SHM_PATH_LDST)
+            g.barrier_all()
+            o.broadcast(dst, src, n, root)
+            assert_heaps_equal(g, o, upto=70 * MiB, what=f"launch {rep}")
+            write_both(g, o, root, src + 8192, rng.integers(0, 256, 300000, dtype=np.uint8))
 
 
 @pytest.mark.parametrize("npes,sizes,n_wg,soff,doff", [
