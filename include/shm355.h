@@ -222,7 +222,8 @@ int shm_launch_wg_get(shm_ctx *ctx, int me, int pe, uint64_t dst_off, uint64_t s
 /* Team form: every PE p does the same put/get towards PE (p + pe_shift) mod npes, each with n_wg
  * work-groups, as ONE grid of npes*n_wg groups on the team stream (LDST) or as npes copies, one
  * per PE, on the engines (SDMA) or the PEs' own streams (MEMCPY).  Long LDST messages (32 MiB or
- * more per PE asked of 128 groups or more, four PEs or more) are moved by 128 groups per PE that
+ * more per PE asked of 128 groups or more, two PEs or more) are moved by about 128 groups per PE
+ * (a whole number of groups per compute unit in all) that stay in the kernel and
  * draw 32 KiB pieces from counters in the library's tail of the heap; the counters set themselves
  * back, so such a launch can be recorded into a HIP graph and replayed like any other. */
 int shm_launch_wg_put_all(shm_ctx *ctx, int pe_shift, uint64_t dst_off, uint64_t src_off, size_t n, int n_wg, int path);

@@ -399,8 +399,8 @@ unsigned tile_groups(size_t n, int n_wg, size_t tiles_per_group = TILES_PER_GROU
     return static_cast<unsigned>(want < static_cast<size_t>(n_wg) ? (want ? want : 1) : n_wg);
 }
 
-// Team puts and gets of 32 MiB or more per PE asked of 128 or more groups per PE, in grids of four
-// PEs or more, run 128 groups per PE that stay in the kernel and draw half-tile pieces (32 KiB) by
+// Team puts and gets of 32 MiB or more per PE asked of 128 or more groups per PE, in grids of two
+// PEs or more, run about 128 groups per PE (ticket_groups) that stay in the kernel and draw half-tile pieces (32 KiB) by
 // ticket, in address order, from a counter pair in their PE's tail (shm_copy_tiles_ticketed; the
 // pair sets itself back, so a recorded launch replays).  Measured on MI355X over twelve random
 // placements of the buffers, min / mean / max percent of the HBM roofline: 8 PEs x 256 MiB 83.9 /
@@ -418,7 +418,20 @@ constexpr size_t TICKETS_MIN_BYTES = size_t(32) << 20, FCOLLECT_TICKETS_MIN_BYTE
 constexpr int TICKET_GROUPS = 128;
 bool use_tickets(uint64_t dst_off, uint64_t src_off, size_t n, int n_wg, int grid_pes)
 {
-    return ((dst_off | src_off) & 15) == 0 && n >= TICKETS_MIN_BYTES && n_wg >= TICKET_GROUPS && grid_pes >= 4;
+    return ((dst_off | src_off) & 15) == 0 && n >= TICKETS_MIN_BYTES && n_wg >= TICKET_GROUPS && grid_pes >= 2;
+}
+// Groups per PE of a team launch by ticket: the whole grid is a multiple of the number of compute
+// units (half a group per unit and PE, rounded down to whole groups per unit), 128 per PE on 256 units
+// when the number of PEs is even.  With 128 per PE at an odd number of PEs some units hold one group
+// more than others and the rate falls below the tiles' (3 PEs x 128 MiB 77.0 % against 78.9 %); 85
+// groups per PE give 82.9 %, 170 give 79.4 %; 5 PEs: 102 groups 81.0 %, 128 78.5 %, 153 79.8 %, tiles 78.7 %;
+// 7 PEs: 109 groups 81.2 %, 128 80.5 %, 73 79.8 %, tiles 78.5 %.  Even grids at 128 per PE: 2 PEs x 256 MiB
+// 84.4 % (tiles 81.0 %), 10 / 12 / 16 PEs x 128 MiB 83.2 / 83.3 / 83.6 % (tiles 78.4-78.6 %); odd grids by this
+// rule: 3 PEs x 256 MiB 84.9 %, 9 / 11 / 13 / 15 PEs x 128 MiB 81.1 / 81.4 / 81.6 / 81.9 % (tiles 78.4-78.7 %).
+unsigned ticket_groups(const shm_ctx *c, int grid_pes)
+{
+    const int cus = c->num_cu > 0 ? c->num_cu : 2 * TICKET_GROUPS, rounds = std::max(1, grid_pes / 2);
+    return static_cast<unsigned>(std::max(1, cus * rounds / grid_pes));
 }
 // A PE's own launches stay on group-owned tiles: eight per-PE kernels of 128 groups drawing tickets
 // measure what the tiles do (78 % at 8 x 256 MiB, 75-77 % at 64-128 MiB) and one PE launching alone
@@ -492,7 +505,7 @@ int wg_rma_all(shm_ctx *c, int pe_shift, uint64_t dst_off, uint64_t src_off, siz
     if (c->team_sync)
         if (int r = team_join(c)) return r;
     if (use_tickets(dst_off, src_off, n, n_wg, c->npes)) {
-        hipLaunchKernelGGL(shmk_wg_rma_tiles, dim3(TICKET_GROUPS, c->npes), dim3(SHMK_WG), TILES_LDS_BYTES, c->stream[0], c->base,
+        hipLaunchKernelGGL(shmk_wg_rma_tiles, dim3(ticket_groups(c, c->npes), c->npes), dim3(SHMK_WG), TILES_LDS_BYTES, c->stream[0], c->base,
                            static_cast<uint64_t>(c->part_bytes), dst_off, src_off, n, c->npes, 0, pe_shift, is_get,
                            ticket_pair_off(c, SHMD_TICKET_TEAM));
     } else if (use_tiles(dst_off, src_off, n, n_wg, c->npes)) {

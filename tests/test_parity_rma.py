@@ -266,10 +266,10 @@ def test_team_puts_by_ticket_random_sizes_and_places():
             assert_heaps_equal(g, o, upto=78 * MiB, what=f"launch {rep}: {n} bytes {src} -> {dst}, shift {shift}, {n_wg} groups")
 
 
-@pytest.mark.parametrize("npes", [4, 7])
+@pytest.mark.parametrize("npes", [2, 3, 4, 7])
 def test_team_puts_by_ticket_at_the_edges_of_the_piece_count(npes):
-    """Half-tile pieces by ticket (team grids of four PEs or more, 32 MiB or more, 128 groups or more
-    asked): exactly 32 MiB (1024 pieces), one vector more (a partial tile of 16 bytes), one byte more,
+    """Half-tile pieces by ticket (team grids of two PEs or more, 32 MiB or more, 128 groups or more
+    asked; 128 groups per PE run at even PE counts, 85 at three PEs, 109 at seven): exactly 32 MiB (1024 pieces), one vector more (a partial tile of 16 bytes), one byte more,
     one tile less than a whole number plus a byte tail, and the same sizes again at once, put and get
     in turn, so that every launch but the first depends on its predecessor having set the counters back."""
     g, o = make_pair(npes, 72 * MiB)
