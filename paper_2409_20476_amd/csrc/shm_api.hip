@@ -525,7 +525,7 @@ int wg_rma_all(shm_ctx *c, int pe_shift, uint64_t dst_off, uint64_t src_off, siz
 
 namespace {
 
-typedef void (*reduce_kernel)(shm_dev_ctx, uint64_t, uint64_t, size_t, int);
+typedef void (*reduce_kernel)(shm_dev_ctx, uint64_t, uint64_t, size_t);
 
 // Groups per PE a split reduction over nvec 16-byte vectors is launched with.  When a PE's slice is
 // walked on group-owned tiles (the kernels' rule: SHMK_OWNED_MIN_TILES or more tiles of 64 KiB per
@@ -541,36 +541,42 @@ int split_reduce_groups(const shm_ctx *c, size_t nvec, int n_wg)
     return want < static_cast<size_t>(n_wg) ? static_cast<int>(want) : n_wg;
 }
 
+template <typename T, int OP>
+reduce_kernel reduce_kernel_of(bool split)
+{
+    return split ? shmk_reduce<T, OP, true> : shmk_reduce<T, OP, false>;
+}
+
 template <typename T>
-reduce_kernel reduce_kernel_for(int op, bool bitwise_ok)
+reduce_kernel reduce_kernel_for(int op, bool bitwise_ok, bool split)
 {
     switch (op) {
-    case SHM_OP_MIN: return shmk_reduce<T, SHMD_OP_MIN>;
-    case SHM_OP_MAX: return shmk_reduce<T, SHMD_OP_MAX>;
-    case SHM_OP_SUM: return shmk_reduce<T, SHMD_OP_SUM>;
-    case SHM_OP_PROD: return shmk_reduce<T, SHMD_OP_PROD>;
-    case SHM_OP_AND: return bitwise_ok ? shmk_reduce<T, SHMD_OP_AND> : nullptr;
-    case SHM_OP_OR: return bitwise_ok ? shmk_reduce<T, SHMD_OP_OR> : nullptr;
-    case SHM_OP_XOR: return bitwise_ok ? shmk_reduce<T, SHMD_OP_XOR> : nullptr;
+    case SHM_OP_MIN: return reduce_kernel_of<T, SHMD_OP_MIN>(split);
+    case SHM_OP_MAX: return reduce_kernel_of<T, SHMD_OP_MAX>(split);
+    case SHM_OP_SUM: return reduce_kernel_of<T, SHMD_OP_SUM>(split);
+    case SHM_OP_PROD: return reduce_kernel_of<T, SHMD_OP_PROD>(split);
+    case SHM_OP_AND: return bitwise_ok ? reduce_kernel_of<T, SHMD_OP_AND>(split) : nullptr;
+    case SHM_OP_OR: return bitwise_ok ? reduce_kernel_of<T, SHMD_OP_OR>(split) : nullptr;
+    case SHM_OP_XOR: return bitwise_ok ? reduce_kernel_of<T, SHMD_OP_XOR>(split) : nullptr;
     default: return nullptr;
     }
 }
 
 // Signed and unsigned integers of one width share every kernel except min and max.
-reduce_kernel pick_reduce(int dtype, int op, size_t *elem)
+reduce_kernel pick_reduce(int dtype, int op, bool split, size_t *elem)
 {
     const bool order = op == SHM_OP_MIN || op == SHM_OP_MAX;
     switch (dtype) {
-    case SHM_INT8: *elem = 1; return order ? reduce_kernel_for<int8_t>(op, true) : reduce_kernel_for<uint8_t>(op, true);
-    case SHM_UINT8: *elem = 1; return reduce_kernel_for<uint8_t>(op, true);
-    case SHM_INT16: *elem = 2; return order ? reduce_kernel_for<int16_t>(op, true) : reduce_kernel_for<uint16_t>(op, true);
-    case SHM_UINT16: *elem = 2; return reduce_kernel_for<uint16_t>(op, true);
-    case SHM_INT32: *elem = 4; return order ? reduce_kernel_for<int32_t>(op, true) : reduce_kernel_for<uint32_t>(op, true);
-    case SHM_UINT32: *elem = 4; return reduce_kernel_for<uint32_t>(op, true);
-    case SHM_INT64: *elem = 8; return order ? reduce_kernel_for<int64_t>(op, true) : reduce_kernel_for<uint64_t>(op, true);
-    case SHM_UINT64: *elem = 8; return reduce_kernel_for<uint64_t>(op, true);
-    case SHM_FLOAT32: *elem = 4; return reduce_kernel_for<float>(op, false);
-    case SHM_FLOAT64: *elem = 8; return reduce_kernel_for<double>(op, false);
+    case SHM_INT8: *elem = 1; return order ? reduce_kernel_for<int8_t>(op, true, split) : reduce_kernel_for<uint8_t>(op, true, split);
+    case SHM_UINT8: *elem = 1; return reduce_kernel_for<uint8_t>(op, true, split);
+    case SHM_INT16: *elem = 2; return order ? reduce_kernel_for<int16_t>(op, true, split) : reduce_kernel_for<uint16_t>(op, true, split);
+    case SHM_UINT16: *elem = 2; return reduce_kernel_for<uint16_t>(op, true, split);
+    case SHM_INT32: *elem = 4; return order ? reduce_kernel_for<int32_t>(op, true, split) : reduce_kernel_for<uint32_t>(op, true, split);
+    case SHM_UINT32: *elem = 4; return reduce_kernel_for<uint32_t>(op, true, split);
+    case SHM_INT64: *elem = 8; return order ? reduce_kernel_for<int64_t>(op, true, split) : reduce_kernel_for<uint64_t>(op, true, split);
+    case SHM_UINT64: *elem = 8; return reduce_kernel_for<uint64_t>(op, true, split);
+    case SHM_FLOAT32: *elem = 4; return reduce_kernel_for<float>(op, false, split);
+    case SHM_FLOAT64: *elem = 8; return reduce_kernel_for<double>(op, false, split);
     default: *elem = 0; return nullptr;
     }
 }
@@ -1603,7 +1609,7 @@ int shm_launch_reduce(shm_ctx *c, uint64_t dst_off, uint64_t src_off, size_t nel
 {
     if (int r = check_ctx(c)) return r;
     size_t elem = 0;
-    const reduce_kernel k = pick_reduce(dtype, op, &elem);
+    const reduce_kernel k = pick_reduce(dtype, op, algo == SHM_REDUCE_SPLIT, &elem);
     if (elem == 0) return fail(SHM_EINVAL, "unknown element type %d", dtype);
     if (op < SHM_OP_MIN || op > SHM_OP_XOR) return fail(SHM_EINVAL, "unknown reduction %d", op);
     if (!k) return fail(SHM_EINVAL, "and/or/xor are defined for integer types only");
@@ -1620,8 +1626,7 @@ int shm_launch_reduce(shm_ctx *c, uint64_t dst_off, uint64_t src_off, size_t nel
     if (c->team_sync)
         if (int r = team_join(c)) return r;
     if (algo == SHM_REDUCE_SPLIT) n_wg = split_reduce_groups(c, nelems / (16 / elem), n_wg);
-    hipLaunchKernelGGL(k, dim3(n_wg, c->npes), dim3(SHMK_WG), 0, c->stream[0], dev_view(c), dst_off, src_off, nelems,
-                       algo == SHM_REDUCE_SPLIT ? 1 : 0);
+    hipLaunchKernelGGL(k, dim3(n_wg, c->npes), dim3(SHMK_WG), 0, c->stream[0], dev_view(c), dst_off, src_off, nelems);
     if (int r = launched("reduce")) return r;
     if (c->team_sync)
         if (int r = team_fork(c)) return r;
