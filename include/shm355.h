@@ -456,7 +456,10 @@ int shm_launch_collect(shm_ctx *ctx, uint64_t dst_off, uint64_t src_off, const s
  * remote vector loads (algo SHM_REDUCE_DUPLICATE), or -- the method the same section names for very
  * large reductions, algo SHM_REDUCE_SPLIT -- the vector is divided by address across PEs, each PE
  * folds its slice and pushes the result to every PE.  Both give the same bits.  Integer sums and
- * products wrap; min/max keep the earlier operand on ties.  Offsets 16-byte aligned. */
+ * products wrap; min/max keep the earlier operand on ties.  Offsets 16-byte aligned.  n_wg is the
+ * most groups per PE the launch may use: a long SPLIT reduction (slices of 6 MiB or more) asked of a
+ * group per compute unit or more runs exactly that many in all, drawing pieces of the slices from
+ * the counters long fcollects and broadcasts use (same rule for recorded launches). */
 int shm_launch_reduce(shm_ctx *ctx, uint64_t dst_off, uint64_t src_off, size_t nelems, int dtype, int op, int n_wg, int algo);
 
 /* Broadcast (paper section "Collective Operations": push, inner loop over destinations): every
@@ -479,7 +482,8 @@ int shm_launch_barrier_exchange(shm_ctx *ctx, uint64_t dst_off, uint64_t src_off
  * element, so all PEs get bit-identical results.  DUPLICATE: every PE computes every element from
  * one local and npes-1 remote loads (paper section "Collective Operations", reduction paragraph).
  * SPLIT: PE q reduces the q-th share of the addresses and pushes it to all PEs (same section, the
- * remark on very large reductions).  Offsets 4-byte aligned (16 for the vector path). */
+ * remark on very large reductions; launch shape as for shm_launch_reduce).  Offsets 4-byte aligned
+ * (16 for the vector path). */
 int shm_launch_reduce_sum_f32(shm_ctx *ctx, uint64_t dst_off, uint64_t src_off, size_t nelems, int n_wg, int algo);
 
 #ifdef __cplusplus

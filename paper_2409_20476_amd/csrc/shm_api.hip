@@ -525,18 +525,33 @@ int wg_rma_all(shm_ctx *c, int pe_shift, uint64_t dst_off, uint64_t src_off, siz
 
 namespace {
 
-typedef void (*reduce_kernel)(shm_dev_ctx, uint64_t, uint64_t, size_t);
+typedef void (*reduce_kernel)(shm_dev_ctx, uint64_t, uint64_t, size_t, uint64_t);
 
-// Groups per PE a split reduction over nvec 16-byte vectors is launched with.  When a PE's slice is
-// walked on group-owned tiles (the kernels' rule: SHMK_OWNED_MIN_TILES or more tiles of 64 KiB per
-// PE) a group beyond the number of tiles has nothing to do, and launching it only delays the groups
-// of the later PEs in the dispatch order (measured: 8 x 64 MiB, 1024 groups asked for, 128 tiles per
-// PE: 0.22 ms with the idle groups, 0.185 ms without).  Which group folds which vectors cannot be
-// observed, so the launcher runs one group per two tiles, never more groups than it was asked for.
-int split_reduce_groups(const shm_ctx *c, size_t nvec, int n_wg)
+// Groups per PE a split reduction over nvec 16-byte vectors is launched with, and the counter pair its
+// groups draw from (0: none).  When a PE's slice is walked on group-owned tiles (the kernels' rule:
+// SHMK_OWNED_MIN_TILES or more tiles of 64 KiB per PE) a group beyond the number of tiles has nothing
+// to do, and launching it only delays the groups of the later PEs in the dispatch order (measured: 8 x
+// 64 MiB, 1024 groups asked for, 128 tiles per PE: 0.22 ms with the idle groups, 0.185 ms without).
+// Which group folds which vectors cannot be observed, so the launcher runs one group per two tiles,
+// never more groups than it was asked for.  From 96 tiles per PE, asked of a group per compute unit
+// or more, it runs exactly one group per compute unit in all, and they draw quarter tiles of their
+// PE's slice by ticket (measured over twelve random placements of the buffers, mean % of the HBM
+// roofline, fixed tiles -> tickets: 8 PEs x 48 / 64 / 96 / 128 MiB 70.4 -> 75.9, 74.2 -> 77.1, 73.6 -> 78.4,
+// 73.0 -> 79.4, and the spread over placements falls from 70.4-76.8 to 76.4-77.4 at 64 MiB; 6 PEs x 64 /
+// 128 MiB 65.8 -> 75.2, 69.2 -> 78.3; 12 PEs x 128 MiB 68.0 -> 77.4; 16 PEs x 128 MiB 70.6 -> 78.3; 4 PEs level;
+// 8 PEs x 32 MiB, 64 tiles per PE, 74.3 -> 72.7, hence the 96; other numbers of groups at 8 x 64 MiB:
+// 16 per PE 54 %, 24: 69.5, 40: 68.1, 48: 72.9, 64: 74.7, 96: 72.9; half tiles 76.4, eighths 76.7).
+constexpr size_t SPLIT_REDUCE_TICKETS_MIN_TILES = 96;
+int split_reduce_groups(const shm_ctx *c, size_t nvec, int n_wg, uint64_t *ticket_pair)
 {
-    const size_t per_pe = (nvec + c->npes - 1) / c->npes, tiles = per_pe / 4096;
+    const size_t tiles = shmk_split_share(nvec, c->npes) / 4096;
+    *ticket_pair = 0;
     if (tiles < SHMK_OWNED_MIN_TILES) return n_wg;
+    const int per_cu = c->num_cu / c->npes > 0 ? c->num_cu / c->npes : 1;
+    if (tiles >= SPLIT_REDUCE_TICKETS_MIN_TILES && n_wg >= per_cu) {
+        *ticket_pair = ticket_pair_off(c, SHMD_TICKET_COLL);
+        return per_cu;
+    }
     const size_t want = tiles / 2 < SHMK_OWNED_MIN_TILES ? SHMK_OWNED_MIN_TILES : tiles / 2;      // two tiles per group measure 1-3 points above one
     return want < static_cast<size_t>(n_wg) ? static_cast<int>(want) : n_wg;
 }
@@ -1625,8 +1640,9 @@ int shm_launch_reduce(shm_ctx *c, uint64_t dst_off, uint64_t src_off, size_t nel
     if (nelems == 0) return team_order_only(c);
     if (c->team_sync)
         if (int r = team_join(c)) return r;
-    if (algo == SHM_REDUCE_SPLIT) n_wg = split_reduce_groups(c, nelems / (16 / elem), n_wg);
-    hipLaunchKernelGGL(k, dim3(n_wg, c->npes), dim3(SHMK_WG), 0, c->stream[0], dev_view(c), dst_off, src_off, nelems);
+    uint64_t pair = 0;
+    if (algo == SHM_REDUCE_SPLIT) n_wg = split_reduce_groups(c, nelems / (16 / elem), n_wg, &pair);
+    hipLaunchKernelGGL(k, dim3(n_wg, c->npes), dim3(SHMK_WG), 0, c->stream[0], dev_view(c), dst_off, src_off, nelems, pair);
     if (int r = launched("reduce")) return r;
     if (c->team_sync)
         if (int r = team_fork(c)) return r;
@@ -1740,11 +1756,12 @@ int shm_launch_reduce_sum_f32(shm_ctx *c, uint64_t dst_off, uint64_t src_off, si
     size_t done = 0;
     if (((src_off | dst_off) & 15) == 0 && nelems >= 4) {
         const size_t nvec = nelems / 4;
-        if (algo == SHM_REDUCE_SPLIT)
-            hipLaunchKernelGGL(shmk_reduce_sum_f32_vec<true>, dim3(split_reduce_groups(c, nvec, n_wg), c->npes), block, 0, c->stream[0], d,
-                               dst_off, src_off, nvec);
-        else
-            hipLaunchKernelGGL(shmk_reduce_sum_f32_vec<false>, grid, block, 0, c->stream[0], d, dst_off, src_off, nvec);
+        if (algo == SHM_REDUCE_SPLIT) {
+            uint64_t pair = 0;
+            const int groups = split_reduce_groups(c, nvec, n_wg, &pair);
+            hipLaunchKernelGGL(shmk_reduce_sum_f32_vec<true>, dim3(groups, c->npes), block, 0, c->stream[0], d, dst_off, src_off, nvec, pair);
+        } else
+            hipLaunchKernelGGL(shmk_reduce_sum_f32_vec<false>, grid, block, 0, c->stream[0], d, dst_off, src_off, nvec, uint64_t(0));
         if (int r = launched("sum-reduce")) return r;
         done = nvec * 4;
     }

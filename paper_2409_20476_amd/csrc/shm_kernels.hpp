@@ -10,6 +10,7 @@ typedef float shm_f32x4 __attribute__((ext_vector_type(4)));
 
 // Split reductions walk a PE's slice on group-owned 64 KiB tiles from this many tiles per PE.
 #define SHMK_OWNED_MIN_TILES 64
+#define SHMK_REDUCE_PIECES 4        // pieces per 64 KiB tile that a long split reduction draws by ticket
 
 // ---- work-group put / get, one PE or a team of PEs in one grid ----------------------------
 // PE me = me0 + blockIdx.y targets PE (me + shift) mod npes; group blockIdx.x of gridDim.x takes
@@ -974,12 +975,23 @@ __device__ __forceinline__ void shmk_duplicate_coords(int npes, unsigned &part, 
     }
 }
 
+// Vectors per PE of a split reduction over nvec 16-byte vectors: an equal share, and from
+// SHMK_OWNED_MIN_TILES tiles on a whole number of 64 KiB tiles, so that every PE's slice starts on
+// a tile boundary whatever the number of PEs (the last PEs then take what is left; with slices that
+// began at any 16 bytes 6 PEs x 128 MiB measured 57 % of the HBM roofline).
+__host__ __device__ inline size_t shmk_split_share(size_t nvec, int npes)
+{
+    const size_t share = (nvec + npes - 1) / npes;
+    return share < size_t(4096) * SHMK_OWNED_MIN_TILES ? share : (share + 4095) / 4096 * 4096;
+}
+
 // ---- configuration 5b: float32 sum-reduce ---------------------------------------------------
 // Element i of the result is ((x0[i] + x1[i]) + x2[i]) + ... in PE order, on every PE.
 // SPLIT = false: PE q = blockIdx.y computes all elements and stores to its own destination.
 // SPLIT = true : PE q computes the q-th share of the vectors and stores it to every PE.
 template <bool SPLIT>
-__global__ __launch_bounds__(SHMK_WG) void shmk_reduce_sum_f32_vec(shm_dev_ctx c, uint64_t dst_off, uint64_t src_off, size_t nvec)
+__global__ __launch_bounds__(SHMK_WG) void shmk_reduce_sum_f32_vec(shm_dev_ctx c, uint64_t dst_off, uint64_t src_off, size_t nvec,
+                                                                   uint64_t ticket_pair_off)
 {
     constexpr int U = 2;
     const int npes = c.npes;
@@ -988,7 +1000,7 @@ __global__ __launch_bounds__(SHMK_WG) void shmk_reduce_sum_f32_vec(shm_dev_ctx c
     if (!SPLIT) shmk_duplicate_coords(npes, part, q);
     size_t first = 0, count = nvec;
     if (SPLIT) {
-        const size_t share = (nvec + npes - 1) / npes;
+        const size_t share = shmk_split_share(nvec, npes);
         first = min(nvec, q * share);
         count = min(nvec, first + share) - first;
     }
@@ -1068,7 +1080,24 @@ __global__ __launch_bounds__(SHMK_WG) void shmk_reduce_sum_f32_vec(shm_dev_ctx c
     constexpr size_t own_rowv = 2048, own_tilev = U * own_rowv;
     const bool owned = SPLIT && count / own_tilev >= SHMK_OWNED_MIN_TILES;
     size_t rem_lane = k.rem_lane;
-    if (owned) {
+    if (owned && ticket_pair_off) {
+        // by ticket: the PE's groups (the launcher runs one per compute unit in all) draw quarter
+        // tiles of the slice in address order from the pair in PE q's tail
+        __shared__ unsigned long long slots[2];
+        constexpr unsigned PIECES = SHMK_REDUCE_PIECES, CPP = 8 / PIECES;
+        const size_t ntiles = count / own_tilev, npieces = ntiles * PIECES;
+        const unsigned wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+        unsigned long long *pair = reinterpret_cast<unsigned long long *>(shm_ptr(c, ticket_pair_off, q));
+        shm_ticket_draw tk{pair, slots, gridDim.x};
+        for (size_t t = part; t < npieces; t = tk.next()) {
+            tk.ahead();
+            const size_t base = (t / PIECES) * own_tilev + (t % PIECES) * (CPP * 64) + static_cast<size_t>(wave * 8) * 64 + lane;
+#pragma unroll
+            for (unsigned cc = 0; cc < CPP; ++cc) tile_part(base + cc * 64, own_rowv);
+        }
+        if (threadIdx.x == 0) shm_tickets_done(pair, gridDim.x);
+        rem_lane = ntiles * own_tilev + static_cast<size_t>(part) * SHMK_WG + threadIdx.x;
+    } else if (owned) {
         const size_t ntiles = count / own_tilev;
         const unsigned wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
         for (size_t t = part; t < ntiles; t += gridDim.x) {
@@ -1166,7 +1195,8 @@ __global__ __launch_bounds__(SHMK_WG) void shmk_broadcast(shm_dev_ctx c, uint64_
 // Integer sums and products wrap (computed in the unsigned type); min/max keep the earlier operand
 // on ties, which also fixes the sign of a zero.
 template <typename T, int OP, bool SPLIT>
-__global__ __launch_bounds__(SHMK_WG) void shmk_reduce(shm_dev_ctx c, uint64_t dst_off, uint64_t src_off, size_t nelems)
+__global__ __launch_bounds__(SHMK_WG) void shmk_reduce(shm_dev_ctx c, uint64_t dst_off, uint64_t src_off, size_t nelems,
+                                                       uint64_t ticket_pair_off)
 {
     // SPLIT false: every PE folds the whole vector into its own destination (the paper's method: no
     // PE waits for another).  SPLIT true: the method the paper names for very large reductions --
@@ -1188,7 +1218,7 @@ __global__ __launch_bounds__(SHMK_WG) void shmk_reduce(shm_dev_ctx c, uint64_t d
     const size_t nvec = nelems / EPV;
     size_t vlo = 0, vhi = nvec;
     if (split) {
-        const size_t per_pe = (nvec + npes - 1) / npes;
+        const size_t per_pe = shmk_split_share(nvec, npes);
         vlo = min(nvec, q * per_pe);
         vhi = min(nvec, vlo + per_pe);
     }
@@ -1244,7 +1274,8 @@ __global__ __launch_bounds__(SHMK_WG) void shmk_reduce(shm_dev_ctx c, uint64_t d
 #pragma unroll
             for (int k = 0; k < EPV; ++k) r1.e[k] = shm_combine<T, OP>(r1.e[k], x1.e[k]);
         }
-        for (int d = d0; d < d1; ++d) {
+        for (int t = d0; t < d1; ++t) {           // split: own copy first, then the others in ring order
+            const int d = !split ? t : q + t < npes ? q + t : q + t - npes;
             shm_st16(reinterpret_cast<shm_u32x4 *>(shm_ptr(c, dst_off, d)) + i, r0.v);
             shm_st16(reinterpret_cast<shm_u32x4 *>(shm_ptr(c, dst_off, d)) + i2, r1.v);
         }
@@ -1268,6 +1299,20 @@ __global__ __launch_bounds__(SHMK_WG) void shmk_reduce(shm_dev_ctx c, uint64_t d
     const size_t ntiles = (vhi - vlo) / tilev;
     if (split && ntiles >= SHMK_OWNED_MIN_TILES) {
         const unsigned wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+        if (ticket_pair_off) {
+            // by ticket, as in shmk_reduce_sum_f32_vec: quarter tiles of the slice in address order
+            __shared__ unsigned long long slots[2];
+            constexpr unsigned PIECES = SHMK_REDUCE_PIECES, CPP = 8 / PIECES;
+            unsigned long long *pair = reinterpret_cast<unsigned long long *>(shm_ptr(c, ticket_pair_off, q));
+            shm_ticket_draw tk{pair, slots, gridDim.x};
+            for (size_t t = part; t < ntiles * PIECES; t = tk.next()) {
+                tk.ahead();
+                const size_t base = vlo + (t / PIECES) * tilev + (t % PIECES) * (CPP * 64) + static_cast<size_t>(wave * 8) * 64 + lane;
+#pragma unroll
+                for (unsigned cc = 0; cc < CPP; ++cc) fold2(base + cc * 64, base + cc * 64 + rowv);
+            }
+            if (threadIdx.x == 0) shm_tickets_done(pair, gridDim.x);
+        } else
         for (size_t t = part; t < ntiles; t += gridDim.x) {
 #pragma unroll 2
             for (unsigned cc = 0; cc < 8; ++cc) {

@@ -109,3 +109,35 @@ def test_recorded_long_team_put_and_get_replay_correctly():
             for p in range(4):
                 o.heap[p][72 * MiB + 16:72 * MiB + 16 + n] = before[(p + 3) % 4][36 * MiB:36 * MiB + n]
             assert_heaps_equal(g, o, upto=108 * MiB, what=f"replay {replay}")
+
+
+def test_recorded_long_collectives_replay_correctly():
+    """A long split reduction and a long broadcast draw their pieces from one counter pair per PE that
+    the last group through sets back: recorded back to back (2 PEs; slices of 96 tiles and a ragged
+    rest; a block of 33 MiB and a few vectors) and replayed three times with fresh bytes in between."""
+    g, o = make_pair(2, 112 * MiB)
+    with g:
+        fill_random(g, o, 67, upto=108 * MiB)
+        g.set_team_sync(False)
+        nel = 4 * (2 * (96 * 4096 + 500) - 1) + 3                     # int32 elements, 12 MiB per PE
+        n = 33 * MiB + 16 * 7
+        rsrc, rdst, bsrc, bdst = 64, 14 * MiB + 16, 30 * MiB, 70 * MiB + 32
+        stream = g.streams[0]
+        graph = torch.cuda.CUDAGraph()
+        torch.cuda.synchronize()
+        with torch.cuda.graph(graph, stream=stream):
+            g.launch_reduce(rdst, rsrc, nel, S.SHM_INT32, S.SHM_OP_SUM, 128, S.SHM_REDUCE_SPLIT)
+            g.launch_broadcast(bdst, bsrc, n, 1, 1024, S.SHM_PATH_LDST)
+            g.launch_reduce(rdst + 14 * MiB, rdst, nel, S.SHM_INT32, S.SHM_OP_MAX, 1024, S.SHM_REDUCE_SPLIT)
+        rng = np.random.default_rng(68)
+        for replay in range(3):
+            for p in range(2):
+                write_both(g, o, p, rsrc + 4096 * replay, rng.integers(0, 256, 300000, dtype=np.uint8))
+                write_both(g, o, p, bsrc + 8192 * replay, rng.integers(0, 256, 300000, dtype=np.uint8))
+            torch.cuda.synchronize()
+            graph.replay()
+            g.barrier_all()
+            o.reduce(rdst, rsrc, nel, np.int32, "sum")
+            o.broadcast(bdst, bsrc, n, 1)
+            o.reduce(rdst + 14 * MiB, rdst, nel, np.int32, "max")
+            assert_heaps_equal(g, o, upto=108 * MiB, what=f"replay {replay}")

@@ -89,6 +89,26 @@ def test_split_on_group_owned_tiles(npes, n_wg):
                 write_both(g, o, p, 18 * MiB + 16, np.full(n * width, 0x5A, np.uint8))
 
 
+@pytest.mark.parametrize("npes,n_wg", [(2, 128), (3, 300)])
+def test_split_by_ticket(npes, n_wg):
+    """Slices of 96 tiles plus a ragged rest per PE, asked of a group per compute unit or more: the
+    split form draws quarter tiles by ticket.  1-byte, 4-byte and 8-byte elements, an element tail,
+    launches in a row on the same counters."""
+    nvec = npes * (96 * 4096 + 1000) - 3
+    g, o = make_pair(npes, 48 * MiB)
+    with g:
+        fill_random(g, o, 79, upto=44 * MiB)
+        for dtype, op, tail in [(S.SHM_UINT8, S.SHM_OP_XOR, 9), (S.SHM_INT32, S.SHM_OP_MIN, 2), (S.SHM_INT64, S.SHM_OP_PROD, 1)]:
+            width = np.dtype(DTYPES[dtype]).itemsize
+            n = nvec * (16 // width) + tail
+            o.reduce(22 * MiB + 16, 4096, n, DTYPES[dtype], OPS[op])
+            g.launch_reduce(22 * MiB + 16, 4096, n, dtype, op, n_wg, S.SHM_REDUCE_SPLIT)
+            g.barrier_all()
+            assert_heaps_equal(g, o, upto=44 * MiB, what=f"{dtype} {op}")
+            for p in range(npes):
+                write_both(g, o, p, 22 * MiB + 16, np.full(n * width, 0x5A, np.uint8))
+
+
 def test_full_size_sum_matches_the_f32_entry_point_and_the_oracle():
     # configuration 5's vector length (16 Mi elements, 8 PEs): int32 sum against the oracle, and the
     # float32 sum of the matrix against the dedicated float32 entry point

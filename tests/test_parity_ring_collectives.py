@@ -172,6 +172,48 @@ def test_reduce_sum_f32_split_on_group_owned_tiles(npes, n_wg):
                 g.write(p, dst, np.full(4 * nelems, 0x5A, np.uint8))
 
 
+@pytest.mark.parametrize("npes,n_wg", [(2, 128), (2, 1024), (3, 85), (3, 200)])
+def test_reduce_sum_f32_split_by_ticket(npes, n_wg):
+    """A split reduction with 96 or more tiles per PE, asked of a group per compute unit or more, draws
+    quarter tiles by ticket: slices of 96 tiles plus a ragged rest (the last PE's slice is shorter, the
+    slices start on tile boundaries), a scalar tail; three launches in a row, so that every launch but
+    the first depends on its predecessor having set the counters back."""
+    nvec = npes * (96 * 4096 + 1000) - 3
+    nelems = 4 * nvec + 3
+    g, o = make_pair(npes, 48 * MiB)
+    with g:
+        fill_random(g, o, 24, upto=44 * MiB)
+        src, dst = 4096, 22 * MiB + 16
+        for rep in range(3):
+            for p in range(npes):
+                write_both(g, o, p, src, synth.c5_reduce_source(p + 10 * rep, nelems))
+            o.reduce_sum_f32(dst, src, nelems)
+            g.launch_reduce_sum_f32(dst, src, nelems, n_wg, S.SHM_REDUCE_SPLIT)
+            g.barrier_all()
+            assert_heaps_equal(g, o, upto=44 * MiB, what=f"launch {rep}")
+
+
+def test_reduce_sum_f32_split_when_the_last_slice_is_short():
+    """Six PEs, slices rounded up to whole tiles: five PEs walk 65 group-owned tiles each and the last
+    one is left with 59 tiles and some vectors, which it deals to its groups the plain way."""
+    npes = 6
+    nvec = npes * 64 * 4096 + 6
+    nelems = 4 * nvec + 1
+    g, o = make_pair(npes, 56 * MiB)
+    with g:
+        fill_random(g, o, 25, upto=52 * MiB)
+        src, dst = 4096, 26 * MiB + 16
+        for p in range(npes):
+            write_both(g, o, p, src, synth.c5_reduce_source(p, nelems))
+        o.reduce_sum_f32(dst, src, nelems)
+        for n_wg in (16, 300):
+            g.launch_reduce_sum_f32(dst, src, nelems, n_wg, S.SHM_REDUCE_SPLIT)
+            g.barrier_all()
+            assert_heaps_equal(g, o, upto=52 * MiB, what=f"{n_wg} groups")
+            for p in range(npes):
+                g.write(p, dst, np.full(4 * nelems, 0x5A, np.uint8))
+
+
 @pytest.mark.timeout(900)
 def test_config5_full_size():
     """8 PEs: fcollect of 64 MiB int32 per PE into 512 MiB, and a 16M-element float32 sum-reduce."""
