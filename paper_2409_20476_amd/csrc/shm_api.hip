@@ -418,7 +418,8 @@ constexpr size_t TICKETS_MIN_BYTES = size_t(32) << 20, FCOLLECT_TICKETS_MIN_BYTE
 constexpr int TICKET_GROUPS = 128;
 bool use_tickets(uint64_t dst_off, uint64_t src_off, size_t n, int n_wg, int grid_pes)
 {
-    return ((dst_off | src_off) & 15) == 0 && n >= TICKETS_MIN_BYTES && n_wg >= TICKET_GROUPS && grid_pes >= 2;
+    (void)dst_off, (void)src_off;           // any byte addresses: the kernel walks from the destination's next 1 KiB boundary
+    return n >= TICKETS_MIN_BYTES && n_wg >= TICKET_GROUPS && grid_pes >= 2;
 }
 // Groups per PE of a team launch by ticket: the whole grid is a multiple of the number of compute
 // units (half a group per unit and PE, rounded down to whole groups per unit), 128 per PE on 256 units
@@ -1613,7 +1614,26 @@ int shm_launch_collect(shm_ctx *c, uint64_t dst_off, uint64_t src_off, const siz
     if (total == 0) return team_order_only(c);
     if (c->team_sync)
         if (int r = team_join(c)) return r;
-    hipLaunchKernelGGL(shmk_collect, dim3(n_wg, c->npes), dim3(SHMK_WG), 0, c->stream[0], dev_view(c), dst_off, src_off, t);
+    // Blocks that all lie and end on multiples of 16 bytes are pushed like fcollect's: about a group per
+    // compute unit for long blocks, and from 8 MiB (the largest block) and 8 PEs on pieces by ticket
+    // (measured, 8 PEs, % of the HBM roofline, 32 / 256 / 1024 groups per PE asked -> now: blocks of 64 MiB
+    // 60.5 / 61.0 / 47.2 -> 80.6, of 48 MiB and up to 109 KiB more 59.0 / 61.5 / 50.4 -> 71.2, of 8 MiB and up to
+    // 28 KiB more 62.9 / 64.5 / 68.8 -> 72.9).  Otherwise the kernel pushes the blocks that do the same way
+    // and the others the general way, with the groups it was asked for (blocks of 40-61 MiB that begin
+    // at odd bytes: 19 / 35 / 39 %).
+    bool aligned = ((dst_off | src_off) & 15) == 0;
+    for (int p = 0; p < c->npes; ++p) aligned = aligned && ((t.at[p] | t.nbytes[p]) & 15) == 0;
+    const int per_cu = c->num_cu / c->npes > 0 ? c->num_cu / c->npes : 1;
+    if (aligned && n_wg > per_cu && largest / TILE_BYTES >= 16u * static_cast<size_t>(per_cu)) n_wg = per_cu;
+    uint64_t pair = 0;
+    if (aligned && largest >= FCOLLECT_TICKETS_MIN_BYTES && c->npes >= 8 && n_wg >= per_cu) {
+        n_wg = per_cu;
+        pair = ticket_pair_off(c, SHMD_TICKET_COLL);
+    }
+    if (c->npes == 8)
+        hipLaunchKernelGGL(shmk_collect<8>, dim3(n_wg, c->npes), dim3(SHMK_WG), 0, c->stream[0], dev_view(c), dst_off, src_off, t, pair);
+    else
+        hipLaunchKernelGGL(shmk_collect<0>, dim3(n_wg, c->npes), dim3(SHMK_WG), 0, c->stream[0], dev_view(c), dst_off, src_off, t, pair);
     if (int r = launched("collect")) return r;
     if (c->team_sync)
         if (int r = team_fork(c)) return r;

@@ -10,6 +10,9 @@ typedef float shm_f32x4 __attribute__((ext_vector_type(4)));
 
 // Split reductions walk a PE's slice on group-owned 64 KiB tiles from this many tiles per PE.
 #define SHMK_OWNED_MIN_TILES 64
+#ifndef SHMK_STORE_LINE
+#define SHMK_STORE_LINE 1024u       // long walks by ticket start on a destination address that is a multiple of this
+#endif
 #define SHMK_REDUCE_PIECES 4        // pieces per 64 KiB tile that a long split reduction draws by ticket
 
 // ---- work-group put / get, one PE or a team of PEs in one grid ----------------------------
@@ -32,6 +35,7 @@ __global__ __launch_bounds__(SHMK_WG) void shmk_wg_rma(shm_dev_ctx c, uint64_t d
 // base address and partition stride (the library's partitions are equally spaced) instead of the
 // whole device view -- one scalar load of the arguments, no table look-up.
 // ticket_pair_off == 0: group-owned tiles, group g of gridDim.x taking tiles g, g + gridDim.x, ...
+// (offsets 16-byte aligned).
 // ticket_pair_off != 0: the offset, in every partition, of a counter pair that reads zero: the
 // gridDim.x groups of a PE draw half-tile pieces by ticket from their own PE's pair (shm_copy_tiles_ticketed;
 // every group starts on the piece of its own number) and the last one through sets the pair back.
@@ -48,9 +52,20 @@ __global__ __launch_bounds__(SHMK_WG) void shmk_wg_rma_tiles(char *base, uint64_
         shmx_copy_tiles_wg<SHMK_WG / 64>(d, s, n, blockIdx.x, gridDim.x);
         return;
     }
+    // By ticket, at any byte addresses.  The walk starts where the destination reaches a multiple of
+    // SHMK_STORE_LINE bytes -- the bytes before it are moved by the last group, the bytes after the last
+    // whole vector by the first -- and reads a source that is then not on a 16-byte boundary as the
+    // aligned words around each vector.  Stores that straddle lines cost far more than loads that do
+    // (8 PEs x 128 MiB; destination alone 16 bytes past a boundary: 75.4 % of the HBM roofline walking from
+    // there, 81.4 % from the next boundary; both 16 bytes past: 73.1 -> 83.7 %; neither: 83.9 %).
+    size_t head = (SHMK_STORE_LINE - (reinterpret_cast<uintptr_t>(d) & (SHMK_STORE_LINE - 1))) & (SHMK_STORE_LINE - 1);
+    if (head > n) head = n;
+    if (blockIdx.x == gridDim.x - 1)
+        for (size_t i = threadIdx.x; i < head; i += SHMK_WG) d[i] = s[i];
+    d += head, s += head, n -= head;
     unsigned long long *pair = reinterpret_cast<unsigned long long *>(base + static_cast<uint64_t>(me) * stride + ticket_pair_off);
     const size_t body = n & ~static_cast<size_t>(15);
-    shm_copy_tiles_ticketed<2, SHMK_WG / 64>(d, s, body, blockIdx.x, pair, 0, gridDim.x);
+    shm_copy_tiles_ticketed_any<2, SHMK_WG / 64>(d, s, body, blockIdx.x, pair, 0, gridDim.x);
     if (blockIdx.x == 0)
         for (size_t i = body + threadIdx.x; i < n; i += SHMK_WG) d[i] = s[i];
     if (threadIdx.x == 0) shm_tickets_done(pair, gridDim.x);
@@ -786,7 +801,7 @@ __global__ __launch_bounds__(SHMK_STORM_WG) void shmk_amo_storm_wg(shm_dev_ctx c
 // The push of a long 16-byte-aligned block by ticket (fcollect: every PE's block; broadcast: the root's): the
 // gridDim.x groups draw quarter-tile pieces (16 KiB: two columns per wave in each of the tile's two 32 KiB rows) of
 // the block in address order, as the long put draws its pieces, and store every column to the PEs in turn, both rows
-// per destination, starting with the right-hand neighbour of `p`; group 0 moves what is left after the whole tiles,
+// per destination, starting with the right-hand neighbour of `p`; group 0 first moves what is left after the whole tiles,
 // and the last group through sets the counter pair back.  s = the block, d0 = its offset in every destination,
 // nvec = its length in vectors.  NPES > 0 fixes the number of PEs at compile time.
 template <int NPES>
@@ -795,6 +810,19 @@ __device__ __forceinline__ void shmk_push_pieces_ticketed(const shm_dev_ctx &c, 
 {
     __shared__ unsigned long long slots[2];
     const int npes = NPES ? NPES : c.npes;
+    // The walk starts where the destinations (the same offset in equally spaced partitions) reach a
+    // multiple of SHMK_STORE_LINE bytes; the vectors before it are pushed by the last group's first lanes
+    // (8 PEs x 48 MiB, destination 16 / 64 / 256 bytes past a boundary: 53 / 76 / 75 % of the HBM roofline
+    // walking from there, 80 % from a boundary).
+    {
+        size_t headv = ((SHMK_STORE_LINE - (reinterpret_cast<uintptr_t>(shm_ptr(c, d0, 0)) & (SHMK_STORE_LINE - 1))) & (SHMK_STORE_LINE - 1)) >> 4;
+        if (headv > nvec) headv = nvec;
+        if (blockIdx.x == gridDim.x - 1 && threadIdx.x < headv) {
+            const shm_u32x4 r = shm_ld16(s + threadIdx.x);
+            for (int q = 0; q < npes; ++q) shm_st16(reinterpret_cast<shm_u32x4 *>(shm_ptr(c, d0, q)) + threadIdx.x, r);
+        }
+        s += headv, d0 += 16 * headv, nvec -= headv;
+    }
     constexpr int NQ = NPES ? NPES : 1;
     shm_u32x4 *dq[NQ];
     if (NPES) {
@@ -829,6 +857,8 @@ __device__ __forceinline__ void shmk_push_pieces_ticketed(const shm_dev_ctx &c, 
             shm_st16(reinterpret_cast<shm_u32x4 *>(shm_ptr(c, d0, q)) + i, r);
         }
     };
+    if (blockIdx.x == 0)                      // what is left after the whole tiles: first, while the others have all their pieces before them
+        for (size_t i = nwhole * tilev + threadIdx.x; i < nvec; i += SHMK_WG) push(i, shm_ld16(s + i));
     shm_ticket_draw tk{pair, slots, gridDim.x};
     for (size_t t = blockIdx.x; t < npieces; t = tk.next()) {
         tk.ahead();
@@ -840,8 +870,6 @@ __device__ __forceinline__ void shmk_push_pieces_ticketed(const shm_dev_ctx &c, 
             push2(i, r0, r1);
         }
     }
-    if (blockIdx.x == 0)                      // what is left after the whole tiles
-        for (size_t i = nwhole * tilev + threadIdx.x; i < nvec; i += SHMK_WG) push(i, shm_ld16(s + i));
     if (threadIdx.x == 0) shm_tickets_done(pair, gridDim.x);
 }
 
@@ -851,15 +879,16 @@ __device__ __forceinline__ void shmk_push_pieces_ticketed(const shm_dev_ctx &c, 
 // dealt to the PE's groups like a put.
 // NPES > 0 fixes the number of PEs at compile time, so that the destination loop unrolls and the
 // base-pointer lookups leave the tile loop; NPES == 0 is the general form.
+// The push of one PE's block: bytes_per_pe bytes at src_off of PE p go to d0 of every PE; src_off, d0
+// and bytes_per_pe are multiples of 16; the calling groups are those of blockIdx.y = p.
 template <int U, int NPES>
-__global__ __launch_bounds__(SHMK_WG) void shmk_fcollect_vec(shm_dev_ctx c, uint64_t dst_off, uint64_t src_off, size_t bytes_per_pe,
-                                                             uint64_t ticket_pair_off)
+__device__ __forceinline__ void shmk_push_block(const shm_dev_ctx &c, uint64_t d0, uint64_t src_off, size_t bytes_per_pe, int p,
+                                                uint64_t ticket_pair_off)
 {
     // Group-owned tiles of U rows x 32 KiB, as in shm_copy_tiles: per column U loads, then those
     // U vectors to every destination, then the next column.
-    const int p = blockIdx.y, npes = NPES ? NPES : c.npes;
+    const int npes = NPES ? NPES : c.npes;
     const shm_u32x4 *s = reinterpret_cast<const shm_u32x4 *>(shm_ptr(c, src_off, p));
-    const uint64_t d0 = dst_off + static_cast<uint64_t>(p) * bytes_per_pe;
     constexpr int NQ = NPES ? NPES : 1;
     shm_u32x4 *dq[NQ];
     if (NPES) {
@@ -936,6 +965,14 @@ __global__ __launch_bounds__(SHMK_WG) void shmk_fcollect_vec(shm_dev_ctx c, uint
     }
 }
 
+template <int U, int NPES>
+__global__ __launch_bounds__(SHMK_WG) void shmk_fcollect_vec(shm_dev_ctx c, uint64_t dst_off, uint64_t src_off, size_t bytes_per_pe,
+                                                             uint64_t ticket_pair_off)
+{
+    const int p = blockIdx.y;
+    shmk_push_block<U, NPES>(c, dst_off + static_cast<uint64_t>(p) * bytes_per_pe, src_off, bytes_per_pe, p, ticket_pair_off);
+}
+
 // Any alignment or length: PE p's block is pushed to every PE like a broadcast rooted at p -- each
 // vector loaded once and stored to all PEs where source and destination are 16-byte aligned, one
 // multi-group put per destination otherwise.
@@ -952,10 +989,19 @@ struct shmk_collect_table {
     uint64_t nbytes[SHM_MAX_PES];
 };
 
-__global__ __launch_bounds__(SHMK_WG) void shmk_collect(shm_dev_ctx c, uint64_t dst_off, uint64_t src_off, shmk_collect_table t)
+// A block whose place in the destination and whose length are multiples of 16 bytes is pushed like
+// fcollect's (tiles, or pieces by ticket when the launcher passes the counters); any other block the
+// general way.
+template <int NPES>
+__global__ __launch_bounds__(SHMK_WG) void shmk_collect(shm_dev_ctx c, uint64_t dst_off, uint64_t src_off, shmk_collect_table t,
+                                                        uint64_t ticket_pair_off)
 {
     const int p = blockIdx.y;
-    shmx_broadcast_push(c, p, dst_off + t.at[p], src_off, t.nbytes[p], blockIdx.x, gridDim.x);
+    const uint64_t d0 = dst_off + t.at[p];
+    if (((d0 | src_off | t.nbytes[p]) & 15) == 0)
+        shmk_push_block<2, NPES>(c, d0, src_off, t.nbytes[p], p, ticket_pair_off);
+    else
+        shmx_broadcast_push(c, p, d0, src_off, t.nbytes[p], blockIdx.x, gridDim.x);
 }
 
 // Team grids (n_wg, npes) whose npes groups with the same blockIdx.x read the SAME source bytes
@@ -979,6 +1025,16 @@ __device__ __forceinline__ void shmk_duplicate_coords(int npes, unsigned &part, 
 // SHMK_OWNED_MIN_TILES tiles on a whole number of 64 KiB tiles, so that every PE's slice starts on
 // a tile boundary whatever the number of PEs (the last PEs then take what is left; with slices that
 // began at any 16 bytes 6 PEs x 128 MiB measured 57 % of the HBM roofline).
+// Vectors before the first slice of a split reduction: the slices start where the destinations (the
+// same offset in equally spaced partitions) reach a multiple of SHMK_STORE_LINE bytes, and PE 0's last
+// group folds the vectors before that place (8 PEs x 64 MiB, destination 16 bytes past a boundary:
+// 56.8 % of the HBM roofline with slices from the destination's first byte).
+__device__ __forceinline__ size_t shmk_split_head(const shm_dev_ctx &c, uint64_t dst_off, size_t nvec)
+{
+    const size_t headv = ((SHMK_STORE_LINE - (reinterpret_cast<uintptr_t>(shm_ptr(c, dst_off, 0)) & (SHMK_STORE_LINE - 1))) & (SHMK_STORE_LINE - 1)) >> 4;
+    return headv < nvec ? headv : nvec;
+}
+
 __host__ __device__ inline size_t shmk_split_share(size_t nvec, int npes)
 {
     const size_t share = (nvec + npes - 1) / npes;
@@ -998,10 +1054,11 @@ __global__ __launch_bounds__(SHMK_WG) void shmk_reduce_sum_f32_vec(shm_dev_ctx c
     int q = blockIdx.y;
     unsigned part = blockIdx.x;
     if (!SPLIT) shmk_duplicate_coords(npes, part, q);
-    size_t first = 0, count = nvec;
+    size_t first = 0, count = nvec, headv = 0;
     if (SPLIT) {
-        const size_t share = shmk_split_share(nvec, npes);
-        first = min(nvec, q * share);
+        headv = shmk_split_head(c, dst_off, nvec);
+        const size_t share = shmk_split_share(nvec - headv, npes);
+        first = min(nvec, headv + q * share);
         count = min(nvec, first + share) - first;
     }
     const uint64_t so = src_off + 16 * first, dof = dst_off + 16 * first;
@@ -1116,6 +1173,14 @@ __global__ __launch_bounds__(SHMK_WG) void shmk_reduce_sum_f32_vec(shm_dev_ctx c
         }
         emit(i, r);
     }
+    if (SPLIT && q == 0 && part == gridDim.x - 1 && threadIdx.x < headv) {       // the vectors before the first slice
+        shm_f32x4 r = load(reinterpret_cast<const shm_f32x4 *>(shm_ptr(c, src_off, 0)) + threadIdx.x);
+        for (int p = 1; p < npes; ++p) {
+            const shm_f32x4 v = load(reinterpret_cast<const shm_f32x4 *>(shm_ptr(c, src_off, p)) + threadIdx.x);
+            r.x += v.x, r.y += v.y, r.z += v.z, r.w += v.w;
+        }
+        for (int w = 0; w < npes; ++w) __builtin_nontemporal_store(r, reinterpret_cast<shm_f32x4 *>(shm_ptr(c, dst_off, w)) + threadIdx.x);
+    }
 }
 
 // Scalar form for the last nelems % 4 elements and for offsets that are not 16-byte aligned:
@@ -1216,10 +1281,11 @@ __global__ __launch_bounds__(SHMK_WG) void shmk_reduce(shm_dev_ctx c, uint64_t d
     if (!split) shmk_duplicate_coords(npes, part, q);
     const int d0 = split ? 0 : q, d1 = split ? npes : q + 1;
     const size_t nvec = nelems / EPV;
-    size_t vlo = 0, vhi = nvec;
+    size_t vlo = 0, vhi = nvec, headv = 0;
     if (split) {
-        const size_t per_pe = shmk_split_share(nvec, npes);
-        vlo = min(nvec, q * per_pe);
+        headv = shmk_split_head(c, dst_off, nvec);
+        const size_t per_pe = shmk_split_share(nvec - headv, npes);
+        vlo = min(nvec, headv + q * per_pe);
         vhi = min(nvec, vlo + per_pe);
     }
     const size_t per = (vhi - vlo + gridDim.x - 1) / gridDim.x;
@@ -1328,6 +1394,7 @@ __global__ __launch_bounds__(SHMK_WG) void shmk_reduce(shm_dev_ctx c, uint64_t d
         for (; i + SHMK_WG < hi; i += 2 * SHMK_WG) fold2(i, i + SHMK_WG);
         for (; i < hi; i += SHMK_WG) fold1(i);
     }
+    if (split && q == 0 && part == gridDim.x - 1 && threadIdx.x < headv) fold1(threadIdx.x);       // the vectors before the first slice
     // the last nelems mod EPV elements, one thread each
     const size_t t = nvec * EPV + threadIdx.x;
     if (part == 0 && (!split || q == 0) && t < nelems) {

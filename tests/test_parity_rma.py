@@ -266,6 +266,34 @@ def test_team_puts_by_ticket_random_sizes_and_places():
             assert_heaps_equal(g, o, upto=78 * MiB, what=f"launch {rep}: {n} bytes {src} -> {dst}, shift {shift}, {n_wg} groups")
 
 
+def test_team_puts_by_ticket_at_any_byte_address():
+    """The long team put walks from the destination's next 1 KiB boundary and reads a source that is
+    then off a 16-byte boundary as the aligned words around each vector: every combination class of
+    destination and source address modulo 16 (equal, words apart, bytes apart, either one aligned),
+    lengths that leave a byte tail, a partial tile, or neither; put and get in turn on the same counters."""
+    npes = 4
+    g, o = make_pair(npes, 72 * MiB)
+    with g:
+        fill_random(g, o, 10, upto=70 * MiB)
+        cases = [(3, 3, 32 * MiB + 5), (0, 5, 32 * MiB), (9, 0, 32 * MiB + 65536 - 9), (8, 4, 33 * MiB + 1), (1, 15, 32 * MiB + 1024 - 1),
+                 (13, 6, 32 * MiB + 16), (1008, 0, 32 * MiB + 16), (1023, 1, 32 * MiB), (16, 12, 32 * MiB + 32768 + 7)]
+        for rep, (da, sa, n) in enumerate(cases):
+            src, dst = 2048 + sa, 35 * MiB + da
+            shift = 1 + rep % (npes - 1)
+            if rep % 2 == 0:
+                g.launch_wg_put_all(shift, dst, src, n, 128 + 50 * rep, S.SHM_PATH_LDST)
+                before = [h.copy() for h in o.heap]
+                for p in range(npes):
+                    o.heap[(p + shift) % npes][dst:dst + n] = before[p][src:src + n]
+            else:
+                g.launch_wg_get_all(shift, src, dst, n, 1024, S.SHM_PATH_LDST)
+                before = [h.copy() for h in o.heap]
+                for p in range(npes):
+                    o.heap[p][src:src + n] = before[(p + shift) % npes][dst:dst + n]
+            g.barrier_all()
+            assert_heaps_equal(g, o, upto=70 * MiB, what=f"case {rep}: dst+{da}, src+{sa}, {n} bytes")
+
+
 @pytest.mark.parametrize("npes", [2, 3, 4, 7])
 def test_team_puts_by_ticket_at_the_edges_of_the_piece_count(npes):
     """Half-tile pieces by ticket (team grids of two PEs or more, 32 MiB or more, 128 groups or more

@@ -87,6 +87,30 @@ def test_collect(npes, sizes, n_wg, soff, doff):
             g.launch_collect(dst, src, [16 * MiB] + [0] * (npes - 1), n_wg)
 
 
+@pytest.mark.parametrize("sizes,n_wg", [
+    ([9 * MiB + 16 * 37, 0, 8 * MiB, 16, 65536 * 3 + 48, 2 * MiB + 16, 8 * MiB + 65536 - 16, 32], 32),      # all on 16 bytes: pieces by ticket
+    ([9 * MiB + 16 * 37, 0, 8 * MiB, 16, 65536 * 3 + 48, 2 * MiB + 16, 8 * MiB + 65536 - 16, 32], 1024),
+    ([8 * MiB + 5, 4 * MiB, 3, 0, MiB + 16, 65536, 9 * MiB, 77], 64)])                                     # some blocks begin at odd bytes
+def test_collect_of_long_blocks(sizes, n_wg):
+    """Eight PEs, blocks of 0 bytes to 9 MiB: with every block on multiples of 16 bytes and a group per
+    compute unit or more asked for, the groups draw 16 KiB pieces by ticket (twice in a row, so that the
+    second launch depends on the first having set the counters back); with blocks at odd bytes the
+    kernel pushes those the general way and the others on tiles."""
+    npes = 8
+    g, o = make_pair(npes, 56 * MiB)
+    with g:
+        fill_random(g, o, 44, upto=52 * MiB)
+        src, dst = 4096, 12 * MiB + 32
+        rng = np.random.default_rng(45)
+        for rep in range(2):
+            g.launch_collect(dst, src, sizes, n_wg)
+            g.barrier_all()
+            o.collect(dst, src, sizes)
+            assert_heaps_equal(g, o, upto=52 * MiB, what=f"launch {rep}")
+            for p in range(npes):
+                write_both(g, o, p, src + 8192 * p, rng.integers(0, 256, 200000, dtype=np.uint8))
+
+
 def test_collectives_on_auto_follow_their_own_cutover():
     """AUTO below and above the collective's threshold (moved down so that small cases cross it):
     the same bytes either way, and the answer of shm_choose_collective_path changes at the threshold."""
