@@ -318,6 +318,7 @@ __device__ __forceinline__ void shm_copy_body_dealt(shm_u32x4 *d, const shm_u32x
 
 // Group `part` of `nparts` does its share of copying n bytes, any alignment.  All threads of all
 // groups call this with the same dst/src/n.
+constexpr size_t SHM_STORE_LINE = 1024, SHM_LINE_HEAD_MIN_BYTES = size_t(4) << 20;
 template <int U = 8, int POLICY = SHM_ST_STREAM>
 __device__ __forceinline__ void shm_copy_parts(char *dst, const char *src, size_t n, unsigned part, unsigned nparts, size_t min_share = 0)
 {
@@ -335,9 +336,22 @@ __device__ __forceinline__ void shm_copy_parts(char *dst, const char *src, size_
     shm_u32x4 *d = reinterpret_cast<shm_u32x4 *>(dst + head);
     const char *bs = src + head;
     const uint32_t mis = static_cast<uint32_t>(reinterpret_cast<uintptr_t>(bs) & 15);
-    const size_t nvec = body >> 4;
+    size_t nvec = body >> 4;
     nparts = shm_deal_groups(nvec, nparts, min_share);
     if (part >= nparts) return;
+    // A message of SHM_LINE_HEAD_MIN_BYTES or more is dealt from where the destination reaches a multiple
+    // of SHM_STORE_LINE bytes; the (fewer than 64) vectors before it are moved by the last group's first
+    // lanes.  Stores that straddle lines are what costs (8 PEs x 24 MiB by 1024 groups each, % of the HBM
+    // roofline: 74.6 on a boundary; destination 16 bytes past one 63.6 -> 72.9, both addresses 8 bytes past
+    // 62.4 -> 74.2, 8 bytes apart 58.6 -> 67.9; 8 MiB: 58.1 -> 63.6, 56.1 -> 64.8, 59.4 -> 66.3; 4 MiB: both 8 bytes
+    // past 52.6 -> 57.2; at 2 MiB and below the extra step of the last group costs what the boundary gains).
+    if (nvec >= SHM_LINE_HEAD_MIN_BYTES / 16) {
+        const size_t hv = ((SHM_STORE_LINE - (reinterpret_cast<uintptr_t>(d) & (SHM_STORE_LINE - 1))) & (SHM_STORE_LINE - 1)) >> 4;
+        if (hv) {
+            if (part == nparts - 1) shm_copy_coop<1, POLICY>(reinterpret_cast<char *>(d), bs, hv * 16, tid, nthr);
+            d += hv, bs += hv * 16, nvec -= hv;
+        }
+    }
     if (mis == 0) {
         shm_copy_body_dealt<U, POLICY>(d, reinterpret_cast<const shm_u32x4 *>(bs), nvec, part, nparts, tid, nthr);
         return;

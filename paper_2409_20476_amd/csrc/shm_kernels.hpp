@@ -10,9 +10,7 @@ typedef float shm_f32x4 __attribute__((ext_vector_type(4)));
 
 // Split reductions walk a PE's slice on group-owned 64 KiB tiles from this many tiles per PE.
 #define SHMK_OWNED_MIN_TILES 64
-#ifndef SHMK_STORE_LINE
-#define SHMK_STORE_LINE 1024u       // long walks by ticket start on a destination address that is a multiple of this
-#endif
+#define SHMK_STORE_LINE static_cast<unsigned>(SHM_STORE_LINE)       // long walks by ticket start on a destination address that is a multiple of this
 #define SHMK_REDUCE_PIECES 4        // pieces per 64 KiB tile that a long split reduction draws by ticket
 
 // ---- work-group put / get, one PE or a team of PEs in one grid ----------------------------

@@ -266,6 +266,35 @@ def test_team_puts_by_ticket_random_sizes_and_places():
             assert_heaps_equal(g, o, upto=78 * MiB, what=f"launch {rep}: {n} bytes {src} -> {dst}, shift {shift}, {n_wg} groups")
 
 
+@pytest.mark.parametrize("n_wg", [3, 64, 1024])
+def test_messages_of_4_mib_and_more_are_dealt_from_a_destination_boundary(n_wg):
+    """Below the long forms a message of 4 MiB or more is dealt from where the destination reaches a
+    multiple of 1 KiB, the vectors before it moved by the last group: destinations and sources at odd
+    bytes, 16 bytes and whole boundaries past one, equal and different modulo 16; one message just
+    below 4 MiB (dealt from its first vector); team form and one PE's own launch."""
+    npes = 3
+    g, o = make_pair(npes, 24 * MiB)
+    with g:
+        fill_random(g, o, 11, upto=22 * MiB)
+        cases = [(16, 0, 4 * MiB + 1024), (5, 5, 5 * MiB + 3), (1008, 1, 4 * MiB + 16), (8, 4, 6 * MiB - 7), (0, 9, 4 * MiB + 15),
+                 (1023, 1023, 4 * MiB + 2048), (48, 0, 4 * MiB - 64), (1, 2, 9 * MiB + 1)]
+        for rep, (da, sa, n) in enumerate(cases):
+            src, dst = 1024 + sa, 11 * MiB + da
+            if rep % 2 == 0:
+                shift = 1 + rep % (npes - 1)
+                g.launch_wg_put_all(shift, dst, src, n, n_wg, S.SHM_PATH_LDST)
+                before = [h.copy() for h in o.heap]
+                for p in range(npes):
+                    o.heap[(p + shift) % npes][dst:dst + n] = before[p][src:src + n]
+                g.barrier_all()
+            else:
+                me, pe = rep % npes, (rep + 1) % npes
+                g.launch_wg_put(me, pe, dst, src, n, n_wg)
+                o.wg_put(me, dst, src, n, pe, n_wg)
+                g.quiet(me)
+            assert_heaps_equal(g, o, upto=22 * MiB, what=f"case {rep}: dst+{da}, src+{sa}, {n} bytes, {n_wg} groups")
+
+
 def test_team_puts_by_ticket_at_any_byte_address():
     """The long team put walks from the destination's next 1 KiB boundary and reads a source that is
     then off a 16-byte boundary as the aligned words around each vector: every combination class of
