@@ -46,21 +46,28 @@ __global__ __launch_bounds__(SHMK_WG) void shmk_wg_rma_tiles(char *base, uint64_
     // one copy of the walk for both directions: only the two addresses differ
     char *d = base + static_cast<uint64_t>(is_get ? me : pe) * stride + dst_off;
     const char *s = base + static_cast<uint64_t>(is_get ? pe : me) * stride + src_off;
+    // Either walk starts where the destination reaches a multiple of SHMK_STORE_LINE bytes; the bytes
+    // before it are moved by the last group (on tiles: whole vectors, the addresses being 16-byte aligned).
+    // Stores that straddle lines cost far more than loads that do (8 PEs x 128 MiB by ticket; destination
+    // alone 16 bytes past a boundary: 75.4 % of the HBM roofline walking from there, 81.4 % from the next
+    // boundary; both 16 bytes past: 73.1 -> 83.7 %; neither: 83.9 %).
+    size_t head = (SHMK_STORE_LINE - (reinterpret_cast<uintptr_t>(d) & (SHMK_STORE_LINE - 1))) & (SHMK_STORE_LINE - 1);
+    if (head > n) head = n;
+    if (blockIdx.x == gridDim.x - 1) {
+        if (ticket_pair_off == 0) {
+            if (threadIdx.x < head / 16)
+                shm_st16(reinterpret_cast<shm_u32x4 *>(d) + threadIdx.x, shm_ld16(reinterpret_cast<const shm_u32x4 *>(s) + threadIdx.x));
+        } else {
+            for (size_t i = threadIdx.x; i < head; i += SHMK_WG) d[i] = s[i];
+        }
+    }
+    d += head, s += head, n -= head;
     if (ticket_pair_off == 0) {
         shmx_copy_tiles_wg<SHMK_WG / 64>(d, s, n, blockIdx.x, gridDim.x);
         return;
     }
-    // By ticket, at any byte addresses.  The walk starts where the destination reaches a multiple of
-    // SHMK_STORE_LINE bytes -- the bytes before it are moved by the last group, the bytes after the last
-    // whole vector by the first -- and reads a source that is then not on a 16-byte boundary as the
-    // aligned words around each vector.  Stores that straddle lines cost far more than loads that do
-    // (8 PEs x 128 MiB; destination alone 16 bytes past a boundary: 75.4 % of the HBM roofline walking from
-    // there, 81.4 % from the next boundary; both 16 bytes past: 73.1 -> 83.7 %; neither: 83.9 %).
-    size_t head = (SHMK_STORE_LINE - (reinterpret_cast<uintptr_t>(d) & (SHMK_STORE_LINE - 1))) & (SHMK_STORE_LINE - 1);
-    if (head > n) head = n;
-    if (blockIdx.x == gridDim.x - 1)
-        for (size_t i = threadIdx.x; i < head; i += SHMK_WG) d[i] = s[i];
-    d += head, s += head, n -= head;
+    // By ticket, at any byte addresses: a source that is now not on a 16-byte boundary is read as the
+    // aligned words around each vector; the bytes after the last whole vector are moved by the first group.
     unsigned long long *pair = reinterpret_cast<unsigned long long *>(base + static_cast<uint64_t>(me) * stride + ticket_pair_off);
     const size_t body = n & ~static_cast<size_t>(15);
     shm_copy_tiles_ticketed_any<2, SHMK_WG / 64>(d, s, body, blockIdx.x, pair, 0, gridDim.x);
