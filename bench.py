@@ -318,6 +318,16 @@ def placement_spread(torch, S, g, args):
                                         lambda: g.launch_wg_put_all(1, region + do, region + so, n, n_wg, S.SHM_PATH_LDST), 4) for _ in range(3))
                 rows[key].append(100.0 * 2 * npes * n / ms / 1e6 / HBM_PEAK_GBS)
         out[f"random_placements_pct_min_mean_max_{n // MiB}mib"] = {k: [min(v), sum(v) / len(v), max(v)] for k, v in rows.items()}
+    # ... and at byte addresses off the 1 KiB boundaries the buffers above lie on (128 MiB per PE): destination and
+    # source the same number of bytes past a boundary, the destination alone, and the two 8 bytes apart
+    odd = {}
+    n = 128 * MiB
+    for key, da, sa in (("on_boundaries", 0, 0), ("both_8_bytes_past", 8, 8), ("both_16_bytes_past", 16, 16), ("dst_16_bytes_past", 16, 0),
+                        ("dst_256_bytes_past", 256, 0), ("src_16_bytes_past", 0, 16), ("8_bytes_apart", 8, 0)):
+        ms = min(time_on_stream(torch, g.streams[0],
+                                lambda: g.launch_wg_put_all(1, region + 512 * MiB + da, region + sa, n, 1024, S.SHM_PATH_LDST), 4) for _ in range(3))
+        odd[key] = 100.0 * 2 * npes * n / ms / 1e6 / HBM_PEAK_GBS
+    out["odd_addresses_pct_128mib"] = odd
     # ... and whether repeating a transfer on the same buffers flatters it: the same put through buffer pairs taken
     # in turn (7 pairs of 64 MiB, 3 of 128 MiB: 0.9-1.8 GiB per PE round before a byte is touched again, against a
     # memory-side cache of 256 MiB) beside the put repeated on one pair
@@ -930,6 +940,7 @@ def summarise(extras, cpu_legs):
             out["c2"]["placement_pct_min_med_max_64mib"] = r["placement"].get("pct_min_med_max_64mib")
             out["c2"]["same_pair_vs_pairs_in_turn_pct"] = {k: [v["same_pair_pct"], v["pairs_in_turn_pct"]]
                                                            for k, v in r["placement"].get("fresh_buffers", {}).items()}
+            out["c2"]["odd_addresses_pct_128mib"] = r["placement"].get("odd_addresses_pct_128mib")
             out["c2"]["random_placements_pct_min_mean_max"] = {k.rsplit("_", 1)[1]: v for k, v in r["placement"].items()
                                                                if k.startswith("random_placements")}
     if "hbm_ceilings" in extras:
