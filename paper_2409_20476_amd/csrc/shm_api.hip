@@ -416,9 +416,8 @@ unsigned tile_groups(size_t n, int n_wg, size_t tiles_per_group = TILES_PER_GROU
 // sizes write-through, are a quarter faster (18.8 / 33.8 / 48.4 us against 23.6 / 43.5 / 62.4 us).
 constexpr size_t TICKETS_MIN_BYTES = size_t(32) << 20, FCOLLECT_TICKETS_MIN_BYTES = size_t(8) << 20, BROADCAST_TICKETS_MIN_BYTES = size_t(32) << 20;
 constexpr int TICKET_GROUPS = 128;
-bool use_tickets(uint64_t dst_off, uint64_t src_off, size_t n, int n_wg, int grid_pes)
+bool use_tickets(size_t n, int n_wg, int grid_pes)      // any byte addresses: the kernel walks from the destination's next 1 KiB boundary
 {
-    (void)dst_off, (void)src_off;           // any byte addresses: the kernel walks from the destination's next 1 KiB boundary
     return n >= TICKETS_MIN_BYTES && n_wg >= TICKET_GROUPS && grid_pes >= 2;
 }
 // Groups per PE of a team launch by ticket: the whole grid is a multiple of the number of compute
@@ -505,7 +504,7 @@ int wg_rma_all(shm_ctx *c, int pe_shift, uint64_t dst_off, uint64_t src_off, siz
     }
     if (c->team_sync)
         if (int r = team_join(c)) return r;
-    if (use_tickets(dst_off, src_off, n, n_wg, c->npes)) {
+    if (use_tickets(n, n_wg, c->npes)) {
         hipLaunchKernelGGL(shmk_wg_rma_tiles, dim3(ticket_groups(c, c->npes), c->npes), dim3(SHMK_WG), TILES_LDS_BYTES, c->stream[0], c->base,
                            static_cast<uint64_t>(c->part_bytes), dst_off, src_off, n, c->npes, 0, pe_shift, is_get,
                            ticket_pair_off(c, SHMD_TICKET_TEAM));
