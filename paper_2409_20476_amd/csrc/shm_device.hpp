@@ -1686,11 +1686,64 @@ __device__ __forceinline__ void shmx_broadcast_push(const shm_dev_ctx &c, int ro
         __syncthreads();
         return;
     }
-    for (int j = 0; j < c.npes; ++j) {
-        int q = root + 1 + j;           // the right-hand neighbour first, the root's own copy last
-        if (q >= c.npes) q -= c.npes;
-        shmx_putmem_parts(c, root, dst_off, src_off, n, q, part, nparts);
+    if (c.stride == 0 || (c.stride & 15) != 0) {         // partitions that do not share their alignment: a put per destination
+        for (int j = 0; j < c.npes; ++j) {
+            int q = root + 1 + j;           // the right-hand neighbour first, the root's own copy last
+            if (q >= c.npes) q -= c.npes;
+            shmx_putmem_parts(c, root, dst_off, src_off, n, q, part, nparts);
+        }
+        return;
     }
+    // Any other addresses: the destinations -- the same offset in equally spaced partitions, so one
+    // alignment -- are brought to a 16-byte boundary by a head of single bytes, the source is read ONCE,
+    // as aligned words, and every vector is put together and stored to all PEs (a put per destination
+    // read the block npes times: 8 PEs, blocks of 40-61 MiB at odd bytes, 19-39 % of the HBM roofline).
+    __syncthreads();
+    const char *src = shm_ptr(c, src_off, root);
+    const unsigned tid = threadIdx.x, nthr = blockDim.x;
+    const size_t line = n >= SHM_LINE_HEAD_MIN_BYTES ? SHM_STORE_LINE : 16;      // long blocks: from a boundary of whole lines
+    size_t head = (line - (reinterpret_cast<uintptr_t>(shm_ptr(c, dst_off, 0)) & (line - 1))) & (line - 1);
+    if (head > n) head = n;
+    const size_t body = (n - head) & ~static_cast<size_t>(15), tail = n - head - body;
+    auto bytes_to_all = [&](size_t first, size_t count) {
+        for (size_t b = first + tid; b < first + count; b += nthr) {
+            const char v = src[b];
+            for (int q = 0; q < c.npes; ++q) shm_ptr(c, dst_off, q)[b] = v;
+        }
+    };
+    if (part == 0) {
+        bytes_to_all(0, head);
+        bytes_to_all(head + body, tail);
+    }
+    if (body) {
+        const char *bs = src + head;
+        const uint32_t mis = static_cast<uint32_t>(reinterpret_cast<uintptr_t>(bs) & 15), sh = mis & 3;
+        const shm_u32x4 *sa = reinterpret_cast<const shm_u32x4 *>(bs - mis);
+        const size_t nvec = body >> 4, gthr = static_cast<size_t>(nparts) * nthr;
+        auto to_all = [&](size_t i, const shm_u32x4 &r) {
+            for (int j = 0; j < c.npes; ++j) {
+                int q = root + 1 + j;       // the right-hand neighbour first, the root's own copy last
+                if (q >= c.npes) q -= c.npes;
+                shm_st16(reinterpret_cast<shm_u32x4 *>(shm_ptr(c, dst_off + head, q)) + i, r);
+            }
+        };
+        // word i + 1 holds at least one byte of the block whenever mis != 0, so it is mapped
+        for (size_t i = static_cast<size_t>(part) * nthr + tid; i < nvec; i += gthr) {
+            const shm_u32x4 lo = shm_ld16(sa + i);
+            if (mis == 0) {
+                to_all(i, lo);
+                continue;
+            }
+            const shm_u32x4 hi = shm_ld16(sa + i + 1);
+            switch (mis >> 2) {       // uniform over the grid
+            case 0: to_all(i, shm_realign<0>(lo, hi, sh)); break;
+            case 1: to_all(i, shm_realign<1>(lo, hi, sh)); break;
+            case 2: to_all(i, shm_realign<2>(lo, hi, sh)); break;
+            default: to_all(i, shm_realign<3>(lo, hi, sh)); break;
+            }
+        }
+    }
+    __syncthreads();
 }
 
 // ------------------------------------------------------------------------------------------
