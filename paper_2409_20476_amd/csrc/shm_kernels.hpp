@@ -893,6 +893,16 @@ __device__ __forceinline__ void shmk_push_block(const shm_dev_ctx &c, uint64_t d
     // Group-owned tiles of U rows x 32 KiB, as in shm_copy_tiles: per column U loads, then those
     // U vectors to every destination, then the next column.
     const int npes = NPES ? NPES : c.npes;
+    // long blocks: the tiles start where the destinations reach a multiple of SHMK_STORE_LINE bytes, as the
+    // pieces by ticket do; the vectors before it are pushed by the last group's first lanes
+    if (bytes_per_pe >= SHM_LINE_HEAD_MIN_BYTES) {
+        const size_t headv = ((SHMK_STORE_LINE - (reinterpret_cast<uintptr_t>(shm_ptr(c, d0, 0)) & (SHMK_STORE_LINE - 1))) & (SHMK_STORE_LINE - 1)) >> 4;
+        if (blockIdx.x == gridDim.x - 1 && threadIdx.x < headv) {
+            const shm_u32x4 r = shm_ld16(reinterpret_cast<const shm_u32x4 *>(shm_ptr(c, src_off, p)) + threadIdx.x);
+            for (int q = 0; q < npes; ++q) shm_st16(reinterpret_cast<shm_u32x4 *>(shm_ptr(c, d0, q)) + threadIdx.x, r);
+        }
+        d0 += 16 * headv, src_off += 16 * headv, bytes_per_pe -= 16 * headv;
+    }
     const shm_u32x4 *s = reinterpret_cast<const shm_u32x4 *>(shm_ptr(c, src_off, p));
     constexpr int NQ = NPES ? NPES : 1;
     shm_u32x4 *dq[NQ];
