@@ -435,7 +435,8 @@ unsigned ticket_groups(const shm_ctx *c, int grid_pes)
 }
 // A PE's own launches stay on group-owned tiles: eight per-PE kernels of 128 groups drawing tickets
 // measure what the tiles do (78 % at 8 x 256 MiB, 75-77 % at 64-128 MiB) and one PE launching alone
-// loses a quarter (4.9 against 6.5 TB/s of traffic).
+// loses a quarter (4.9 against 6.5 TB/s of traffic); with 256 groups per kernel eight kernels gain 2.6 points
+// at 256 MiB (80.9 %) and one alone falls from 81 to 60-64 %.  The launcher cannot know who else is running.
 uint64_t ticket_pair_off(const shm_ctx *c, unsigned pair) { return c->user_bytes + SHMD_INTERNAL_TICKETS + 8ull * pair; }
 
 // Long, 16-byte-aligned messages moved by a grid that fills the chip take the group-owned-tile kernel.
