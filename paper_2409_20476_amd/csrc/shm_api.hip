@@ -433,6 +433,19 @@ unsigned ticket_groups(const shm_ctx *c, int grid_pes)
     const int cus = c->num_cu > 0 ? c->num_cu : 2 * TICKET_GROUPS, rounds = std::max(1, grid_pes / 2);
     return static_cast<unsigned>(std::max(1, cus * rounds / grid_pes));
 }
+// The largest number of groups per PE, not above `groups`, that makes a team grid a whole number of
+// groups per compute unit (`groups` itself when the grid has fewer groups than the chip has units).
+// A grid that leaves some units with one group more than others runs at the pace of those units: team
+// puts of 128 MiB per PE on group-owned tiles, % of the HBM roofline as asked -> rounded down: 8 PEs x 40 / 48 /
+// 70 / 100 groups 65.5 / 73.7 / 70.0 / 72.3 -> 79.9 / 79.9 / 79.2 / 78.5; 4 PEs x 70 / 100 / 127: 60.9 / 76.4 / 78.1 ->
+// 80.5 / 80.7 / 80.6; 6 PEs x 48 / 64 / 100: 61.4 / 75.0 / 73.2 -> 78.8 / 78.9 / 78.4; 3 PEs x 100 / 120 / 127: 62.9 / 70.7 /
+// 72.8 -> 78.2 / 78.3 / 78.3; never slower in any case measured.
+unsigned balanced_groups(const shm_ctx *c, unsigned groups, int grid_pes)
+{
+    const unsigned cus = c->num_cu > 0 ? static_cast<unsigned>(c->num_cu) : 256u;
+    const unsigned per_cu = groups * static_cast<unsigned>(grid_pes) / cus;
+    return per_cu == 0 ? groups : per_cu * cus / static_cast<unsigned>(grid_pes);
+}
 // A PE's own launches stay on group-owned tiles: eight per-PE kernels of 128 groups drawing tickets
 // measure what the tiles do (78 % at 8 x 256 MiB, 75-77 % at 64-128 MiB) and one PE launching alone
 // loses a quarter (4.9 against 6.5 TB/s of traffic); with 256 groups per kernel eight kernels gain 2.6 points
@@ -510,9 +523,12 @@ int wg_rma_all(shm_ctx *c, int pe_shift, uint64_t dst_off, uint64_t src_off, siz
                            static_cast<uint64_t>(c->part_bytes), dst_off, src_off, n, c->npes, 0, pe_shift, is_get,
                            ticket_pair_off(c, SHMD_TICKET_TEAM));
     } else if (use_tiles(dst_off, src_off, n, n_wg, c->npes)) {
-        hipLaunchKernelGGL(shmk_wg_rma_tiles, dim3(tile_groups(n, n_wg), c->npes), dim3(SHMK_WG), TILES_LDS_BYTES, c->stream[0], c->base,
+        hipLaunchKernelGGL(shmk_wg_rma_tiles, dim3(balanced_groups(c, tile_groups(n, n_wg), c->npes), c->npes), dim3(SHMK_WG), TILES_LDS_BYTES, c->stream[0], c->base,
                            static_cast<uint64_t>(c->part_bytes), dst_off, src_off, n, c->npes, 0, pe_shift, is_get, uint64_t(0));
     } else {
+        // from 4 MiB per PE the grid is a whole number of groups per compute unit here too (8 PEs x 24 MiB asked of
+        // 70 / 100 groups: 65 / 69 -> 76 / 73 % of the HBM roofline, 8 MiB of 40 / 70: 62 / 62 -> 68 / 70 %; at 2 MiB mixed)
+        if (n >= (size_t(4) << 20)) n_wg = static_cast<int>(balanced_groups(c, static_cast<unsigned>(n_wg), c->npes));
         hipLaunchKernelGGL(shmk_wg_rma, dim3(n_wg, c->npes), dim3(SHMK_WG), 0, c->stream[0], dev_view(c), dst_off, src_off, n, 0,
                            pe_shift, is_get);
     }
@@ -554,7 +570,7 @@ int split_reduce_groups(const shm_ctx *c, size_t nvec, int n_wg, uint64_t *ticke
         return per_cu;
     }
     const size_t want = tiles / 2 < SHMK_OWNED_MIN_TILES ? SHMK_OWNED_MIN_TILES : tiles / 2;      // two tiles per group measure 1-3 points above one
-    return want < static_cast<size_t>(n_wg) ? static_cast<int>(want) : n_wg;
+    return static_cast<int>(balanced_groups(c, want < static_cast<size_t>(n_wg) ? static_cast<unsigned>(want) : static_cast<unsigned>(n_wg), c->npes));
 }
 
 template <typename T, int OP>
