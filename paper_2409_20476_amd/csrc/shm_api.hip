@@ -573,6 +573,17 @@ int split_reduce_groups(const shm_ctx *c, size_t nvec, int n_wg, uint64_t *ticke
     return static_cast<int>(balanced_groups(c, want < static_cast<size_t>(n_wg) ? static_cast<unsigned>(want) : static_cast<unsigned>(n_wg), c->npes));
 }
 
+// Groups per PE of a duplicate reduction over `bytes` per PE: from 4 MiB a whole number of groups per
+// compute unit in all, and a multiple of 8 per PE, which the kernels' XCD-aware numbering needs (with
+// another count the npes readers of a share are spread over the XCDs and every one of them fetches it
+// from HBM).
+int duplicate_reduce_groups(const shm_ctx *c, size_t bytes, int n_wg)
+{
+    if (bytes < (size_t(4) << 20) || n_wg < 8) return n_wg;
+    const unsigned g = balanced_groups(c, static_cast<unsigned>(n_wg), c->npes) & ~7u;
+    return g ? static_cast<int>(g) : (n_wg & ~7);
+}
+
 template <typename T, int OP>
 reduce_kernel reduce_kernel_of(bool split)
 {
@@ -1679,6 +1690,7 @@ int shm_launch_reduce(shm_ctx *c, uint64_t dst_off, uint64_t src_off, size_t nel
         if (int r = team_join(c)) return r;
     uint64_t pair = 0;
     if (algo == SHM_REDUCE_SPLIT) n_wg = split_reduce_groups(c, nelems / (16 / elem), n_wg, &pair);
+    else n_wg = duplicate_reduce_groups(c, nelems * elem, n_wg);
     hipLaunchKernelGGL(k, dim3(n_wg, c->npes), dim3(SHMK_WG), 0, c->stream[0], dev_view(c), dst_off, src_off, nelems, pair);
     if (int r = launched("reduce")) return r;
     if (c->team_sync)
@@ -1798,7 +1810,8 @@ int shm_launch_reduce_sum_f32(shm_ctx *c, uint64_t dst_off, uint64_t src_off, si
             const int groups = split_reduce_groups(c, nvec, n_wg, &pair);
             hipLaunchKernelGGL(shmk_reduce_sum_f32_vec<true>, dim3(groups, c->npes), block, 0, c->stream[0], d, dst_off, src_off, nvec, pair);
         } else
-            hipLaunchKernelGGL(shmk_reduce_sum_f32_vec<false>, grid, block, 0, c->stream[0], d, dst_off, src_off, nvec, uint64_t(0));
+            hipLaunchKernelGGL(shmk_reduce_sum_f32_vec<false>, dim3(duplicate_reduce_groups(c, nelems * 4, n_wg), c->npes), block, 0, c->stream[0], d,
+                               dst_off, src_off, nvec, uint64_t(0));
         if (int r = launched("sum-reduce")) return r;
         done = nvec * 4;
     }
