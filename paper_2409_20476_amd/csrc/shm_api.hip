@@ -1661,6 +1661,8 @@ int shm_launch_collect(shm_ctx *c, uint64_t dst_off, uint64_t src_off, const siz
         n_wg = per_cu;
         pair = ticket_pair_off(c, SHMD_TICKET_COLL);
     }
+    if (aligned && !pair && largest >= FCOLLECT_TICKETS_MIN_BYTES)      // as fcollect on tiles: a whole number of groups per compute unit
+        n_wg = static_cast<int>(balanced_groups(c, static_cast<unsigned>(n_wg), c->npes));
     if (c->npes == 8)
         hipLaunchKernelGGL(shmk_collect<8>, dim3(n_wg, c->npes), dim3(SHMK_WG), 0, c->stream[0], dev_view(c), dst_off, src_off, t, pair);
     else
