@@ -222,8 +222,9 @@ int shm_launch_wg_get(shm_ctx *ctx, int me, int pe, uint64_t dst_off, uint64_t s
 /* Team form: every PE p does the same put/get towards PE (p + pe_shift) mod npes, each with n_wg
  * work-groups, as ONE grid of npes*n_wg groups on the team stream (LDST) or as npes copies, one
  * per PE, on the engines (SDMA) or the PEs' own streams (MEMCPY).  Long LDST messages (32 MiB or
- * more per PE asked of 128 groups or more, two PEs or more, at any byte addresses) are moved by
- * about 128 groups per PE (a whole number of groups per compute unit in all) that stay in the kernel
+ * more per PE asked of about 128 groups or more, from 128 MiB also of fewer; two PEs or more; any
+ * byte addresses) are moved by at most about 128 groups per PE (a whole number of groups per compute
+ * unit in all, never more than asked for) that stay in the kernel
  * and draw 32 KiB pieces, counted from the destination's next 1 KiB boundary, from counters in the library's tail of the heap; the counters set themselves
  * back, so such a launch can be recorded into a HIP graph and replayed like any other.  The library's
  * own launches follow one another on the team stream; a caller who replays recorded team launches of

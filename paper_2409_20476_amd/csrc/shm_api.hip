@@ -399,8 +399,8 @@ unsigned tile_groups(size_t n, int n_wg, size_t tiles_per_group = TILES_PER_GROU
     return static_cast<unsigned>(want < static_cast<size_t>(n_wg) ? (want ? want : 1) : n_wg);
 }
 
-// Team puts and gets of 32 MiB or more per PE asked of 128 or more groups per PE, in grids of two
-// PEs or more, run about 128 groups per PE (ticket_groups) that stay in the kernel and draw half-tile pieces (32 KiB) by
+// Team puts and gets of 32 MiB or more per PE asked of about 128 or more groups per PE (ticket_groups; from
+// 128 MiB also of fewer: team_ticket_groups), in grids of two PEs or more, run that many groups per PE that stay in the kernel and draw half-tile pieces (32 KiB) by
 // ticket, in address order, from a counter pair in their PE's tail (shm_copy_tiles_ticketed; the
 // pair sets itself back, so a recorded launch replays).  Measured on MI355X over twelve random
 // placements of the buffers, min / mean / max percent of the HBM roofline: 8 PEs x 256 MiB 83.9 /
@@ -416,10 +416,6 @@ unsigned tile_groups(size_t n, int n_wg, size_t tiles_per_group = TILES_PER_GROU
 // sizes write-through, are a quarter faster (18.8 / 33.8 / 48.4 us against 23.6 / 43.5 / 62.4 us).
 constexpr size_t TICKETS_MIN_BYTES = size_t(32) << 20, FCOLLECT_TICKETS_MIN_BYTES = size_t(8) << 20, BROADCAST_TICKETS_MIN_BYTES = size_t(32) << 20;
 constexpr int TICKET_GROUPS = 128;
-bool use_tickets(size_t n, int n_wg, int grid_pes)      // any byte addresses: the kernel walks from the destination's next 1 KiB boundary
-{
-    return n >= TICKETS_MIN_BYTES && n_wg >= TICKET_GROUPS && grid_pes >= 2;
-}
 // Groups per PE of a team launch by ticket: the whole grid is a multiple of the number of compute
 // units (half a group per unit and PE, rounded down to whole groups per unit), 128 per PE on 256 units
 // when the number of PEs is even.  With 128 per PE at an odd number of PEs some units hold one group
@@ -445,6 +441,23 @@ unsigned balanced_groups(const shm_ctx *c, unsigned groups, int grid_pes)
     const unsigned cus = c->num_cu > 0 ? static_cast<unsigned>(c->num_cu) : 256u;
     const unsigned per_cu = groups * static_cast<unsigned>(grid_pes) / cus;
     return per_cu == 0 ? groups : per_cu * cus / static_cast<unsigned>(grid_pes);
+}
+// Groups per PE with which a team put or get of n bytes per PE asked of n_wg groups per PE runs by ticket,
+// or 0 if it does not (any byte addresses: the kernel walks from the destination's next 1 KiB boundary).
+// From 32 MiB and ticket_groups() asked for: that many.  From 128 MiB also with fewer, as long as there is a
+// group per compute unit in all: the largest whole number of groups per unit not above what was asked (%
+// of the HBM roofline on balanced tiles -> by ticket, 256 / 128 MiB per PE: 8 PEs x 40-127 groups 77-79 -> 81.2,
+// 78-80 -> 80.3-81.4; 4 PEs x 64-127 groups 79.5 -> 84.0, 79.3 -> 82.5; 6 PEs x 64-127 groups 78 -> 82-83, 78.5 -> 81-82.6;
+// at 64 MiB the two are level or the tiles ahead).
+constexpr size_t TICKETS_FEW_GROUPS_MIN_BYTES = size_t(128) << 20;
+unsigned team_ticket_groups(const shm_ctx *c, size_t n, int n_wg)
+{
+    if (n < TICKETS_MIN_BYTES || c->npes < 2) return 0;
+    const unsigned full = ticket_groups(c, c->npes);
+    if (static_cast<unsigned>(n_wg) >= full) return full;
+    if (n >= TICKETS_FEW_GROUPS_MIN_BYTES && static_cast<long long>(n_wg) * c->npes >= std::max(1, c->num_cu))
+        return balanced_groups(c, static_cast<unsigned>(n_wg), c->npes);
+    return 0;
 }
 // A PE's own launches stay on group-owned tiles: eight per-PE kernels of 128 groups drawing tickets
 // measure what the tiles do (78 % at 8 x 256 MiB, 75-77 % at 64-128 MiB) and one PE launching alone
@@ -518,8 +531,8 @@ int wg_rma_all(shm_ctx *c, int pe_shift, uint64_t dst_off, uint64_t src_off, siz
     }
     if (c->team_sync)
         if (int r = team_join(c)) return r;
-    if (use_tickets(n, n_wg, c->npes)) {
-        hipLaunchKernelGGL(shmk_wg_rma_tiles, dim3(ticket_groups(c, c->npes), c->npes), dim3(SHMK_WG), TILES_LDS_BYTES, c->stream[0], c->base,
+    if (const unsigned tkg = team_ticket_groups(c, n, n_wg)) {
+        hipLaunchKernelGGL(shmk_wg_rma_tiles, dim3(tkg, c->npes), dim3(SHMK_WG), TILES_LDS_BYTES, c->stream[0], c->base,
                            static_cast<uint64_t>(c->part_bytes), dst_off, src_off, n, c->npes, 0, pe_shift, is_get,
                            ticket_pair_off(c, SHMD_TICKET_TEAM));
     } else if (use_tiles(dst_off, src_off, n, n_wg, c->npes)) {

@@ -295,6 +295,30 @@ def test_messages_of_4_mib_and_more_are_dealt_from_a_destination_boundary(n_wg):
             assert_heaps_equal(g, o, upto=22 * MiB, what=f"case {rep}: dst+{da}, src+{sa}, {n} bytes, {n_wg} groups")
 
 
+@pytest.mark.timeout(600)
+def test_team_puts_of_128_mib_asked_of_fewer_groups_run_by_ticket():
+    """From 128 MiB per PE a team put asked of fewer groups than the ticket form's own count, but of a
+    group per compute unit in all or more, runs by ticket with a whole number of groups per unit (4 PEs:
+    70 asked, 64 run; 127 asked, 64 run): ragged length at an odd destination, put then get."""
+    npes = 4
+    g, o = make_pair(npes, 264 * MiB)
+    with g:
+        fill_random(g, o, 12, upto=262 * MiB)
+        n = 128 * MiB + 65536 + 16 * 3 + 5
+        src, dst = 64, 130 * MiB + 9
+        g.launch_wg_put_all(1, dst, src, n, 70, S.SHM_PATH_LDST)
+        before = [h[src:src + n].copy() for h in o.heap]
+        for p in range(npes):
+            o.heap[(p + 1) % npes][dst:dst + n] = before[p]
+        g.barrier_all()
+        g.launch_wg_get_all(3, src + 16, dst, n, 127, S.SHM_PATH_LDST)
+        before = [h[dst:dst + n].copy() for h in o.heap]
+        for p in range(npes):
+            o.heap[p][src + 16:src + 16 + n] = before[(p + 3) % npes]
+        g.barrier_all()
+        assert_heaps_equal(g, o, upto=262 * MiB, what="128 MiB by ticket with fewer groups")
+
+
 def test_team_puts_by_ticket_at_any_byte_address():
     """The long team put walks from the destination's next 1 KiB boundary and reads a source that is
     then off a 16-byte boundary as the aligned words around each vector: every combination class of
