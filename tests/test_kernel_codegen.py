@@ -39,7 +39,7 @@ def _find(kernels, fragment):
     return names
 
 
-@pytest.mark.parametrize("fragment", ["shmk_wg_rma_tiles", "shmk_wg_put_timedILi1E", "shmk_wg_put_timedILi2E", "shmk_fcollect_vec", "shmk_broadcast", "shmk_reduce_sum_f32_vecILb1E"])
+@pytest.mark.parametrize("fragment", ["shmk_wg_rma_tiles", "shmk_wg_put_timedILi1E", "shmk_wg_put_timedILi2E", "shmk_fcollect_vec", "shmk_broadcast", "shmk_reduce_sum_f32_vecILb1E", "shmk_collect", "shmk_reduceIfLi2ELb1E"])
 def test_long_copies_keep_the_nontemporal_hint(kernels, fragment):
     for name in _find(kernels, fragment):
         body = kernels[name]
