@@ -415,7 +415,7 @@ unsigned tile_groups(size_t n, int n_wg, size_t tiles_per_group = TILES_PER_GROU
 // 44.2 / 63.1 us by ticket), on buffers that sit in the 256 MiB memory-side cache the virtual blocks, which store such
 // sizes write-through, are a quarter faster (18.8 / 33.8 / 48.4 us against 23.6 / 43.5 / 62.4 us).
 constexpr size_t TICKETS_MIN_BYTES = size_t(32) << 20, FCOLLECT_TICKETS_MIN_BYTES = size_t(8) << 20, BROADCAST_TICKETS_MIN_BYTES = size_t(32) << 20;
-constexpr int TICKET_GROUPS = 128;
+constexpr int TICKET_GROUPS = 128, PER_PE_TICKET_MIN_GROUPS = 32, PER_PE_TICKET_MAX_GROUPS = 100;
 // Groups per PE of a team launch by ticket: the whole grid is a multiple of the number of compute
 // units (half a group per unit and PE, rounded down to whole groups per unit), 128 per PE on 256 units
 // when the number of PEs is even.  With 128 per PE at an odd number of PEs some units hold one group
@@ -459,7 +459,7 @@ unsigned team_ticket_groups(const shm_ctx *c, size_t n, int n_wg)
         return balanced_groups(c, static_cast<unsigned>(n_wg), c->npes);
     return 0;
 }
-// A PE's own launches stay on group-owned tiles: eight per-PE kernels of 128 groups drawing tickets
+// A PE's own launches asked of more than 100 groups stay on group-owned tiles: eight per-PE kernels of 128 groups drawing tickets
 // measure what the tiles do (78 % at 8 x 256 MiB, 75-77 % at 64-128 MiB) and one PE launching alone
 // loses a quarter (4.9 against 6.5 TB/s of traffic); with 256 groups per kernel eight kernels gain 2.6 points
 // at 256 MiB (80.9 %) and one alone falls from 81 to 60-64 %.  The launcher cannot know who else is running.
@@ -490,6 +490,18 @@ int wg_rma(shm_ctx *c, int me, int pe, uint64_t dst_off, uint64_t src_off, size_
         return is_get ? transfer_copy(c, use, me, me, dst_off, pe, src_off, n) : transfer_copy(c, use, me, pe, dst_off, me, src_off, n);
     if (int r = begin_pe_launch(c, me)) return r;
     const int shift = (pe - me + c->npes) % c->npes;
+    // A PE's own long put or get asked of 32-100 groups runs exactly those groups by ticket (any byte addresses;
+    // the PE's own counter pair): measured with 64 groups, 256 / 64 MiB, % of the HBM roofline, tiles -> tickets:
+    // eight PEs launching at once 67.9 -> 78.2 and 62.9 -> 70.4, one PE alone 38.5 -> 42.3 and 37.3 -> 39.6; 32 groups:
+    // eight 41.8 -> 57.7, alone 24.4 -> 23.7; 100 groups: eight 75.2 -> 81.1, alone 54.9 -> 58.2.  With 128 groups one PE
+    // alone loses 4-5 points by ticket and with 192 or more 16 (one counter's window is too small for the whole
+    // chip), so those stay on tiles: the launcher cannot know who else is running.
+    if (n >= TICKETS_MIN_BYTES && n_wg >= PER_PE_TICKET_MIN_GROUPS && n_wg <= PER_PE_TICKET_MAX_GROUPS) {
+        hipLaunchKernelGGL(shmk_wg_rma_tiles, dim3(n_wg, 1), dim3(SHMK_WG), TILES_LDS_BYTES, c->stream[me], c->base,
+                           static_cast<uint64_t>(c->part_bytes), dst_off, src_off, n, c->npes, me, shift, is_get,
+                           ticket_pair_off(c, SHMD_TICKET_PE));
+        return launched("work-group put/get (by ticket)");
+    }
     if (use_tiles(dst_off, src_off, n, n_wg, 1)) {
         hipLaunchKernelGGL(shmk_wg_rma_tiles, dim3(tile_groups(n, n_wg), 1), dim3(SHMK_WG), TILES_LDS_BYTES, c->stream[me], c->base,
                            static_cast<uint64_t>(c->part_bytes), dst_off, src_off, n, c->npes, me, shift, is_get, uint64_t(0));

@@ -937,7 +937,8 @@ __device__ __forceinline__ void shmx_quiet_wg()
 #define SHMD_TICKET_TIMED_WORDS 504u          // words 0..503: the timed put, one per repetition (cleared by its launcher)
 #define SHMD_TICKET_TEAM 504u                 // a counter pair (ticket, groups through) for team puts and gets ...
 #define SHMD_TICKET_COLL 506u                 // ... for team collectives ...
-#define SHMD_TICKET_PROBE 508u                // ... and for the stream probes; the pairs reset themselves (shm_tickets_done)
+#define SHMD_TICKET_PROBE 508u                // ... for the stream probes ...
+#define SHMD_TICKET_PE 510u                   // ... and for a PE's own long puts and gets; the pairs reset themselves (shm_tickets_done)
 #define SHMD_QUIET_SHARED_MIN_GROUPS 64u
 #define SHMD_QUIET_SPIN_LIMIT 4096
 

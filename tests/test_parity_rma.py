@@ -295,6 +295,30 @@ def test_messages_of_4_mib_and_more_are_dealt_from_a_destination_boundary(n_wg):
             assert_heaps_equal(g, o, upto=22 * MiB, what=f"case {rep}: dst+{da}, src+{sa}, {n} bytes, {n_wg} groups")
 
 
+@pytest.mark.parametrize("n_wg", [32, 77, 100])
+def test_a_pes_own_long_puts_asked_of_32_to_100_groups_run_by_ticket(n_wg):
+    """One PE's own put or get of 32 MiB or more asked of 32-100 groups draws its pieces from that PE's
+    counter pair: both PEs launching at once (each on its own pair), odd byte addresses, ragged lengths,
+    launches in a row on the same pair."""
+    g, o = make_pair(2, 112 * MiB)
+    with g:
+        fill_random(g, o, 13, upto=108 * MiB)
+        cases = [(0, 0, 32 * MiB), (7, 7, 32 * MiB + 65536 + 3), (16, 5, 33 * MiB - 11)]
+        for rep, (da, sa, n) in enumerate(cases):
+            src, dst = 1024 + sa, 36 * MiB + da
+            for me in (0, 1):
+                g.launch_wg_put(me, 1 - me, dst, src, n, n_wg)
+            before = [h[src:src + n].copy() for h in o.heap]
+            for me in (0, 1):
+                o.heap[1 - me][dst:dst + n] = before[me]
+            g.quiet(0)
+            g.quiet(1)
+            g.launch_wg_get(rep % 2, 1 - rep % 2, 72 * MiB + sa, dst, n, n_wg)
+            o.wg_get(rep % 2, 72 * MiB + sa, dst, n, 1 - rep % 2, n_wg)
+            g.quiet(rep % 2)
+            assert_heaps_equal(g, o, upto=108 * MiB, what=f"case {rep}: dst+{da}, src+{sa}, {n} bytes, {n_wg} groups")
+
+
 @pytest.mark.timeout(600)
 def test_team_puts_of_128_mib_asked_of_fewer_groups_run_by_ticket():
     """From 128 MiB per PE a team put asked of fewer groups than the ticket form's own count, but of a
