@@ -215,8 +215,9 @@ int    shm_stream_used(shm_ctx *ctx, int pe);
  * run fewer groups than it was asked for (long messages, short messages dealt to very many groups,
  * long collectives), never more.  path: LDST = kernel on me's stream, SDMA = copy engine,
  * MEMCPY = runtime copy on me's stream, AUTO = LDST or SDMA by cutover.  Any byte alignment; n may
- * be 0.  A message of 32 MiB or more asked of 32-100 groups is moved in pieces drawn from a counter
- * pair in PE me's part of the library's tail of the heap (it sets itself back): me's launches follow
+ * be 0.  A message of 32 MiB or more asked of 32-100 groups, and one of 128 MiB or more asked of a
+ * group per compute unit or more, is moved in pieces drawn from counter
+ * pairs in PE me's part of the library's tail of the heap (it sets itself back): me's launches follow
  * one another on its stream; a caller who replays recorded ones elsewhere keeps them from overlapping. */
 int shm_launch_wg_put(shm_ctx *ctx, int me, int pe, uint64_t dst_off, uint64_t src_off, size_t n, int n_wg, int path);
 int shm_launch_wg_get(shm_ctx *ctx, int me, int pe, uint64_t dst_off, uint64_t src_off, size_t n, int n_wg, int path);

@@ -416,6 +416,10 @@ unsigned tile_groups(size_t n, int n_wg, size_t tiles_per_group = TILES_PER_GROU
 // sizes write-through, are a quarter faster (18.8 / 33.8 / 48.4 us against 23.6 / 43.5 / 62.4 us).
 constexpr size_t TICKETS_MIN_BYTES = size_t(32) << 20, FCOLLECT_TICKETS_MIN_BYTES = size_t(8) << 20, BROADCAST_TICKETS_MIN_BYTES = size_t(32) << 20;
 constexpr int TICKET_GROUPS = 128, PER_PE_TICKET_MIN_GROUPS = 32, PER_PE_TICKET_MAX_GROUPS = 100;
+constexpr size_t PER_PE_WAYS_MIN_BYTES = size_t(128) << 20;
+static_assert(SHMD_INTERNAL_WAY_TICKETS >= SHMD_INTERNAL_TICKETS + 8 * SHMD_TICKET_WORDS &&
+                  SHMD_INTERNAL_WAY_TICKETS + SHMD_TICKET_MAX_WAYS * SHMD_TICKET_WAY_BYTES <= SHM_INTERNAL_BYTES,
+              "the pairs of walks in ways lie behind the ticket words, inside the internal tail");
 // Groups per PE of a team launch by ticket: the whole grid is a multiple of the number of compute
 // units (half a group per unit and PE, rounded down to whole groups per unit), 128 per PE on 256 units
 // when the number of PEs is even.  With 128 per PE at an odd number of PEs some units hold one group
@@ -459,7 +463,7 @@ unsigned team_ticket_groups(const shm_ctx *c, size_t n, int n_wg)
         return balanced_groups(c, static_cast<unsigned>(n_wg), c->npes);
     return 0;
 }
-// A PE's own launches asked of more than 100 groups stay on group-owned tiles: eight per-PE kernels of 128 groups drawing tickets
+// A PE's own launches asked of more than 100 groups stay on group-owned tiles below 128 MiB: eight per-PE kernels of 128 groups drawing tickets
 // measure what the tiles do (78 % at 8 x 256 MiB, 75-77 % at 64-128 MiB) and one PE launching alone
 // loses a quarter (4.9 against 6.5 TB/s of traffic); with 256 groups per kernel eight kernels gain 2.6 points
 // at 256 MiB (80.9 %) and one alone falls from 81 to 60-64 %.  The launcher cannot know who else is running.
@@ -499,12 +503,24 @@ int wg_rma(shm_ctx *c, int me, int pe, uint64_t dst_off, uint64_t src_off, size_
     if (n >= TICKETS_MIN_BYTES && n_wg >= PER_PE_TICKET_MIN_GROUPS && n_wg <= PER_PE_TICKET_MAX_GROUPS) {
         hipLaunchKernelGGL(shmk_wg_rma_tiles, dim3(n_wg, 1), dim3(SHMK_WG), TILES_LDS_BYTES, c->stream[me], c->base,
                            static_cast<uint64_t>(c->part_bytes), dst_off, src_off, n, c->npes, me, shift, is_get,
-                           ticket_pair_off(c, SHMD_TICKET_PE));
+                           ticket_pair_off(c, SHMD_TICKET_PE), 1u);
         return launched("work-group put/get (by ticket)");
+    }
+    // From 128 MiB, asked of a group per compute unit or more, it runs a group per unit by ticket in TWO ways: the
+    // message in two halves, half of the groups and a counter pair each, the pairs 4 KiB apart.  One counter cannot
+    // serve a whole chip's draws (the memory side performs the atomics on one line, and on neighbouring lines, one after
+    // another: one PE alone with 256 groups on one pair 61 % of the HBM roofline, on two pairs in neighbouring lines 80.5 %,
+    // 4 KiB apart 81.3-82.3 %, in four ways 78 %).  Measured, tiles -> two ways: 256 MiB one PE alone 79.4-81.2 -> 81.3, eight PEs
+    // at once 76.6-77.9 -> 80.6; 128 MiB 78 -> 76.5 and 76.0 -> 78.6; at 64 MiB one PE alone loses 5 points, so tiles below 128 MiB.
+    if (n >= PER_PE_WAYS_MIN_BYTES && n_wg >= c->num_cu && c->num_cu >= 2) {
+        hipLaunchKernelGGL(shmk_wg_rma_tiles, dim3(c->num_cu & ~1, 1), dim3(SHMK_WG), TILES_LDS_BYTES, c->stream[me], c->base,
+                           static_cast<uint64_t>(c->part_bytes), dst_off, src_off, n, c->npes, me, shift, is_get,
+                           c->user_bytes + SHMD_INTERNAL_WAY_TICKETS, 2u);
+        return launched("work-group put/get (by ticket, two ways)");
     }
     if (use_tiles(dst_off, src_off, n, n_wg, 1)) {
         hipLaunchKernelGGL(shmk_wg_rma_tiles, dim3(tile_groups(n, n_wg), 1), dim3(SHMK_WG), TILES_LDS_BYTES, c->stream[me], c->base,
-                           static_cast<uint64_t>(c->part_bytes), dst_off, src_off, n, c->npes, me, shift, is_get, uint64_t(0));
+                           static_cast<uint64_t>(c->part_bytes), dst_off, src_off, n, c->npes, me, shift, is_get, uint64_t(0), 1u);
         return launched("work-group put/get (tiles)");
     }
     hipLaunchKernelGGL(shmk_wg_rma, dim3(n_wg, 1), dim3(SHMK_WG), 0, c->stream[me], dev_view(c), dst_off, src_off, n, me, shift,
@@ -546,10 +562,10 @@ int wg_rma_all(shm_ctx *c, int pe_shift, uint64_t dst_off, uint64_t src_off, siz
     if (const unsigned tkg = team_ticket_groups(c, n, n_wg)) {
         hipLaunchKernelGGL(shmk_wg_rma_tiles, dim3(tkg, c->npes), dim3(SHMK_WG), TILES_LDS_BYTES, c->stream[0], c->base,
                            static_cast<uint64_t>(c->part_bytes), dst_off, src_off, n, c->npes, 0, pe_shift, is_get,
-                           ticket_pair_off(c, SHMD_TICKET_TEAM));
+                           ticket_pair_off(c, SHMD_TICKET_TEAM), 1u);
     } else if (use_tiles(dst_off, src_off, n, n_wg, c->npes)) {
         hipLaunchKernelGGL(shmk_wg_rma_tiles, dim3(balanced_groups(c, tile_groups(n, n_wg), c->npes), c->npes), dim3(SHMK_WG), TILES_LDS_BYTES, c->stream[0], c->base,
-                           static_cast<uint64_t>(c->part_bytes), dst_off, src_off, n, c->npes, 0, pe_shift, is_get, uint64_t(0));
+                           static_cast<uint64_t>(c->part_bytes), dst_off, src_off, n, c->npes, 0, pe_shift, is_get, uint64_t(0), 1u);
     } else {
         // from 4 MiB per PE the grid is a whole number of groups per compute unit here too (8 PEs x 24 MiB asked of
         // 70 / 100 groups: 65 / 69 -> 76 / 73 % of the HBM roofline, 8 MiB of 40 / 70: 62 / 62 -> 68 / 70 %; at 2 MiB mixed)

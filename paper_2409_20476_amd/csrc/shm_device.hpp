@@ -939,6 +939,14 @@ __device__ __forceinline__ void shmx_quiet_wg()
 #define SHMD_TICKET_COLL 506u                 // ... for team collectives ...
 #define SHMD_TICKET_PROBE 508u                // ... for the stream probes ...
 #define SHMD_TICKET_PE 510u                   // ... and for a PE's own long puts and gets; the pairs reset themselves (shm_tickets_done)
+// A walk in several ways (the message cut into that many runs of whole tiles, each with its own groups
+// and its own counter pair) keeps its pairs SHMD_TICKET_WAY_BYTES apart: tickets are drawn with an
+// atomic on one word, the memory side performs the atomics on one line -- and on neighbouring lines --
+// one after another (some 60 million a second), and one walk that moves 3 TB/s in 32 KiB pieces draws
+// 100 million.
+#define SHMD_INTERNAL_WAY_TICKETS 40960u      // SHMD_TICKET_MAX_WAYS pairs, SHMD_TICKET_WAY_BYTES apart: a PE's own long puts and gets in ways
+#define SHMD_TICKET_WAY_BYTES 4096u
+#define SHMD_TICKET_MAX_WAYS 4u
 #define SHMD_QUIET_SHARED_MIN_GROUPS 64u
 #define SHMD_QUIET_SPIN_LIMIT 4096
 

@@ -36,9 +36,10 @@ __global__ __launch_bounds__(SHMK_WG) void shmk_wg_rma(shm_dev_ctx c, uint64_t d
 // (offsets 16-byte aligned).
 // ticket_pair_off != 0: the offset, in every partition, of a counter pair that reads zero: the
 // gridDim.x groups of a PE draw half-tile pieces by ticket from their own PE's pair (shm_copy_tiles_ticketed;
-// every group starts on the piece of its own number) and the last one through sets the pair back.
+// every group starts on the piece of its own number) and the last one through sets the pair back; ways: see below.
 __global__ __launch_bounds__(SHMK_WG) void shmk_wg_rma_tiles(char *base, uint64_t stride, uint64_t dst_off, uint64_t src_off, size_t n,
-                                                             int npes, int me0, int shift, int is_get, uint64_t ticket_pair_off)
+                                                             int npes, int me0, int shift, int is_get, uint64_t ticket_pair_off,
+                                                             unsigned ways)
 {
     const int me = me0 + blockIdx.y;
     int pe = me + shift;
@@ -68,12 +69,17 @@ __global__ __launch_bounds__(SHMK_WG) void shmk_wg_rma_tiles(char *base, uint64_
     }
     // By ticket, at any byte addresses: a source that is now not on a 16-byte boundary is read as the
     // aligned words around each vector; the bytes after the last whole vector are moved by the first group.
-    unsigned long long *pair = reinterpret_cast<unsigned long long *>(base + static_cast<uint64_t>(me) * stride + ticket_pair_off);
     const size_t body = n & ~static_cast<size_t>(15);
-    shm_copy_tiles_ticketed_any<2, SHMK_WG / 64>(d, s, body, blockIdx.x, pair, 0, gridDim.x);
     if (blockIdx.x == 0)
         for (size_t i = body + threadIdx.x; i < n; i += SHMK_WG) d[i] = s[i];
-    if (threadIdx.x == 0) shm_tickets_done(pair, gridDim.x);
+    // ways > 1 (a divisor of gridDim.x): the message is walked as that many runs of whole tiles, each by
+    // its share of the groups on a counter pair of its own, SHMD_TICKET_WAY_BYTES further on
+    const unsigned groups = gridDim.x / ways, way = blockIdx.x / groups, part = blockIdx.x - way * groups;
+    const size_t tiles = body >> 16, lo = (tiles * way / ways) << 16, hi = way + 1 == ways ? body : (tiles * (way + 1) / ways) << 16;
+    unsigned long long *pair = reinterpret_cast<unsigned long long *>(base + static_cast<uint64_t>(me) * stride + ticket_pair_off +
+                                                                      static_cast<uint64_t>(way) * SHMD_TICKET_WAY_BYTES);
+    shm_copy_tiles_ticketed_any<2, SHMK_WG / 64>(d + lo, s + lo, hi - lo, part, pair, 0, groups);
+    if (threadIdx.x == 0) shm_tickets_done(pair, groups);
 }
 
 // One-direction ceilings of the memory system with the access forms of the long-message put: the

@@ -320,6 +320,30 @@ def test_a_pes_own_long_puts_asked_of_32_to_100_groups_run_by_ticket(n_wg):
 
 
 @pytest.mark.timeout(600)
+def test_a_pes_own_puts_of_128_mib_run_by_ticket_in_two_ways():
+    """From 128 MiB a PE's own put or get asked of a group per compute unit or more is walked as two halves
+    of whole tiles, each by half of the groups on its own counter pair: odd addresses, a ragged length, an
+    odd number of tiles, put and get back, twice in a row on the same pairs, both PEs launching at once."""
+    g, o = make_pair(2, 392 * MiB)
+    with g:
+        fill_random(g, o, 14, upto=390 * MiB)
+        n = 128 * MiB + 65536 * 3 + 16 * 7 + 3
+        src, dst, back = 1024 + 5, 130 * MiB + 11, 260 * MiB + 2
+        for rep in range(2):
+            for me in (0, 1):
+                g.launch_wg_put(me, 1 - me, dst, src + rep, n, 256 + 768 * rep)
+            before = [h[src + rep:src + rep + n].copy() for h in o.heap]
+            for me in (0, 1):
+                o.heap[1 - me][dst:dst + n] = before[me]
+            g.quiet(0)
+            g.quiet(1)
+            g.launch_wg_get(rep, 1 - rep, back, dst, n, 1024)
+            o.wg_get(rep, back, dst, n, 1 - rep, 1024)
+            g.quiet(rep)
+            assert_heaps_equal(g, o, upto=390 * MiB, what=f"launch {rep}")
+
+
+@pytest.mark.timeout(600)
 def test_team_puts_of_128_mib_asked_of_fewer_groups_run_by_ticket():
     """From 128 MiB per PE a team put asked of fewer groups than the ticket form's own count, but of a
     group per compute unit in all or more, runs by ticket with a whole number of groups per unit (4 PEs:
