@@ -625,6 +625,16 @@ int duplicate_reduce_groups(const shm_ctx *c, size_t bytes, int n_wg)
     return g ? static_cast<int>(g) : (n_wg & ~7);
 }
 
+// Whether the groups of an fcollect (or collect) of blocks of `bytes` draw their pieces by ticket: from 8 MiB
+// with six PEs or more, from 64 MiB with four or five (measured, 1024 groups asked, % of the HBM roofline, tiles ->
+// tickets, blocks of 8 / 16 / 64 / 96 MiB: 7 PEs 69.1 / 67.2 / 76.5 / 76.7 -> 70.6 / 74.3 / 84.0 / 84.2; 6 PEs 67.9 / 67.7 / 71.9 /
+// 75.3 -> 68.6 / 71.4 / 80.2 / 81.3; 4 PEs 66.4 / 68.7 / 74.8 / 70.0 -> 62.3 / 65.9 / 75.7 / 75.8; 3 PEs 62.3 / 66.0 / 73.3 / 71.0 ->
+// 56.8 / 62.6 / 69.6 / 70.6; 2 PEs 60.6 / 66.7 / 67.5 / 68.2 -> 45.4 / 54.2 / 63.6 / 65.6).
+bool fcollect_by_ticket(const shm_ctx *c, size_t bytes)
+{
+    return (c->npes >= 6 && bytes >= FCOLLECT_TICKETS_MIN_BYTES) || (c->npes >= 4 && bytes >= (size_t(64) << 20));
+}
+
 template <typename T, int OP>
 reduce_kernel reduce_kernel_of(bool split)
 {
@@ -1634,13 +1644,13 @@ int shm_launch_fcollect(shm_ctx *c, uint64_t dst_off, uint64_t src_off, size_t b
     // runs that many groups, never more than it was asked for.
     const int per_cu = c->num_cu / c->npes > 0 ? c->num_cu / c->npes : 1;
     if (n_wg > per_cu && bytes_per_pe / TILE_BYTES >= 16u * static_cast<size_t>(per_cu)) n_wg = per_cu;
-    // From 8 MiB per PE and 8 PEs on, those groups draw quarter-tile pieces (16 KiB) of their PE's block
+    // From 8 MiB per PE and 6 PEs on (fcollect_by_ticket), those groups draw quarter-tile pieces (16 KiB) of their PE's block
     // by ticket, in address order, and store every column to the destinations in turn (measured, % of
     // the HBM roofline, fixed tiles -> tickets: 8 PEs x 8 / 16 / 64 MiB 62.9 -> 73.6, 65.5 -> 77.8, 76.9 -> 80.7
     // -- the write-only ceiling of this chip is 81 % --; 16 PEs 63.1 -> 73.5, 69.8 -> 74.5, 71.2 -> 74.0; with
-    // 4 or 6 PEs, or other numbers of groups -- 8 PEs: 24 groups 69 %, 40 and more 76-77 % --, nothing is gained).
+    // other numbers of groups -- 8 PEs: 24 groups 69 %, 40 and more 76-77 % -- nothing is gained; fewer PEs: fcollect_by_ticket).
     uint64_t pair = 0;
-    if (((dst_off | src_off | bytes_per_pe) & 15) == 0 && bytes_per_pe >= FCOLLECT_TICKETS_MIN_BYTES && c->npes >= 8 && n_wg >= per_cu) {
+    if (((dst_off | src_off | bytes_per_pe) & 15) == 0 && fcollect_by_ticket(c, bytes_per_pe) && n_wg >= per_cu) {
         n_wg = per_cu;
         pair = ticket_pair_off(c, SHMD_TICKET_COLL);
     }
@@ -1698,7 +1708,7 @@ int shm_launch_collect(shm_ctx *c, uint64_t dst_off, uint64_t src_off, const siz
     const int per_cu = c->num_cu / c->npes > 0 ? c->num_cu / c->npes : 1;
     if (aligned && n_wg > per_cu && largest / TILE_BYTES >= 16u * static_cast<size_t>(per_cu)) n_wg = per_cu;
     uint64_t pair = 0;
-    if (aligned && largest >= FCOLLECT_TICKETS_MIN_BYTES && c->npes >= 8 && n_wg >= per_cu) {
+    if (aligned && fcollect_by_ticket(c, largest) && n_wg >= per_cu) {
         n_wg = per_cu;
         pair = ticket_pair_off(c, SHMD_TICKET_COLL);
     }

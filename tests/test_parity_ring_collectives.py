@@ -112,9 +112,10 @@ def test_fcollect(path, npes, n, n_wg, soff, doff):
         assert_heaps_equal(g, o, upto=12 * MiB)
 
 
-@pytest.mark.parametrize("npes,n,n_wg", [(8, 8 * MiB, 1024), (8, 8 * MiB + 65536 + 48, 32), (8, 9 * MiB - 16, 31), (16, 8 * MiB + 16, 16)])
+@pytest.mark.parametrize("npes,n,n_wg", [(8, 8 * MiB, 1024), (8, 8 * MiB + 65536 + 48, 32), (8, 9 * MiB - 16, 31), (16, 8 * MiB + 16, 16),
+                                         (6, 8 * MiB + 32, 42), (7, 9 * MiB - 48, 500)])
 def test_fcollect_of_long_blocks_by_ticket(npes, n, n_wg):
-    """From 8 MiB per PE, 8 PEs or more and as many groups asked as the launcher runs (256 / npes per PE)
+    """From 8 MiB per PE, 6 PEs or more and as many groups asked as the launcher runs (256 / npes per PE)
     the groups of a PE draw 16 KiB pieces of its block by ticket: whole tiles only, a rest of less than
     a tile, one group too few (fixed tiles then), 16 PEs; twice in a row, the second launch with other
     source bytes, so that it depends on the counters having been set back."""
